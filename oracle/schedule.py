@@ -1,0 +1,137 @@
+"""The layer-pack-major iteration of the paper, driven over the oracle's layers.
+
+TEST INFRASTRUCTURE.  The same per-layer functions as `model.py`, executed in
+the order the paper's Runtime executes them on one GPU (Section 3, "Key
+Optimizations"; Section 4.3.2 and Algorithm 3 for the task order):
+
+  * input-batch grouping: a forward task runs its layer pack over ALL
+    microbatches before the next pack starts;
+  * the forward pass keeps only the INPUT of each backward pack (the
+    checkpoint, Section 4.3.1 first bullet); a backward task first recomputes
+    the pack's forward from that input, then runs its backward;
+  * jit-compute: the last backward pack is shared with the forward pass and
+    runs forward+backward per microbatch, with no recompute;
+  * jit-update: the optimizer step of a pack directly follows its backward task.
+
+Because the result must equal ordinary synchronous training exactly, this
+driver is also a pin on the oracle: its gradients must be bit-identical to
+`iteration_microbatch_major` (each tensor still receives its microbatch
+contributions in ascending order; only the interleaving across layers differs).
+
+Packs are lists of (first_layer, end_layer) half-open ranges over the R layers.
+P_B covers 0..R; P_F covers exactly the layers before P_B's last pack
+(Algorithm 2, first two lines).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+from . import model as om
+
+
+def check_packs(spec: om.Spec, P_F, P_B) -> None:
+    R = spec.n_layers
+    if not P_B:
+        raise ValueError("P_B is empty")
+    pos = 0
+    for (a, e) in P_B:
+        if a != pos or e <= a:
+            raise ValueError(f"P_B not contiguous/non-empty at {(a, e)}")
+        pos = e
+    if pos != R:
+        raise ValueError("P_B does not cover all layers")
+    last_start = P_B[-1][0]
+    pos = 0
+    for (a, e) in P_F:
+        if a != pos or e <= a:
+            raise ValueError(f"P_F not contiguous/non-empty at {(a, e)}")
+        pos = e
+    if pos != last_start:
+        raise ValueError("P_F must cover exactly the layers before P_B's last pack")
+
+
+@dataclass
+class Task:
+    """One entry of the ordered task list (Algorithm 3 at N = 1).
+    kind: 'F' forward, 'B' backward (recompute + backward, or forward +
+    backward for the last pack), 'A' update."""
+    index: int
+    kind: str
+    pack: tuple
+    is_last_pack: bool = False
+    stash_out_layers: list = field(default_factory=list)  # F: inputs checkpointed
+    stash_in_layer: int | None = None                      # B: checkpoint consumed
+
+
+def task_list(spec: om.Spec, P_F, P_B):
+    """Forward tasks in pack order, then (backward, update) pairs in reverse
+    pack order (Algorithm 3, the two creation loops)."""
+    check_packs(spec, P_F, P_B)
+    ckpt_layers = {a for (a, _) in P_B[1:-1]}   # inputs that must be stashed
+    tasks = []
+    for pack in P_F:
+        t = Task(len(tasks), "F", pack)
+        t.stash_out_layers = [l for l in range(pack[0], pack[1]) if l in ckpt_layers]
+        tasks.append(t)
+    for k in reversed(range(len(P_B))):
+        pack = P_B[k]
+        last = (k == len(P_B) - 1)
+        t = Task(len(tasks), "B", pack, is_last_pack=last)
+        if not last and pack[0] != 0:
+            t.stash_in_layer = pack[0]
+        tasks.append(t)
+        tasks.append(Task(len(tasks), "A", pack, is_last_pack=last))
+    return tasks
+
+
+def iteration_layer_pack_major(spec: om.Spec, params, ids, targets, P_F, P_B,
+                               m, v, hp: om.AdamHP):
+    """One iteration in task-list order.  Returns dict(loss, grads, weights, m, v)."""
+    M = ids.shape[0]
+    n_tgt = om.count_targets(targets)
+    tasks = task_list(spec, P_F, P_B)
+    X = [None] * M                    # boundary activation of each microbatch
+    stash = {}                        # (layer, mb) -> checkpointed input
+    grads: dict = {}
+    loss = 0.0
+    new_w, new_m, new_v = {}, {}, {}
+
+    for t in tasks:
+        a, e = t.pack
+        if t.kind == "F":
+            for mb in range(M):
+                x = X[mb]
+                for layer in range(a, e):
+                    if layer in t.stash_out_layers:
+                        stash[(layer, mb)] = x.copy()
+                    x, _ = om.layer_fwd(layer, x, params, spec, ids[mb], targets[mb], n_tgt)
+                X[mb] = x
+        elif t.kind == "B":
+            for mb in range(M):
+                b = ids[mb].shape[0]
+                if a == 0:
+                    x = None                  # the embedding restarts from the ids
+                elif t.is_last_pack:
+                    x = X[mb]                 # still resident from the forward pass
+                else:
+                    x = stash.pop((t.stash_in_layer, mb))
+                caches = {}
+                for layer in range(a, e):
+                    x, caches[layer] = om.layer_fwd(layer, x, params, spec,
+                                                    ids[mb], targets[mb], n_tgt)
+                if t.is_last_pack:
+                    loss += x
+                    dy = None
+                else:
+                    dy = X[mb]
+                for layer in reversed(range(a, e)):
+                    dy, g = om.layer_bwd(layer, dy, caches[layer], params, spec, b)
+                    om.accumulate(grads, g)
+                X[mb] = dy               # gradient w.r.t. the pack's input
+        else:  # 'A': jit-update of this pack's tensors
+            for layer in range(a, e):
+                for name in om.layer_param_shapes(spec, layer):
+                    new_w[name], new_m[name], new_v[name] = om.adam_update(
+                        params[name], grads[name], m[name], v[name], hp)
+    assert not stash, "every checkpoint must be consumed exactly once"
+    return {"loss": float(loss), "grads": grads, "weights": new_w, "m": new_m, "v": new_v}

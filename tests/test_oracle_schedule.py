@@ -1,0 +1,221 @@
+"""Pins for the layer-pack-major driver, the swap-volume counts and the
+balanced-time packing of the oracle."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import model as om
+from oracle import packing as opk
+from oracle import schedule as osch
+from oracle import swapcount as osw
+from paper_2202_01306_amd import synth
+from tests.helpers import f64, oracle_spec, tiny_cfg
+
+
+def all_packings(R):
+    """Every way to cut 0..R into contiguous non-empty packs."""
+    for mask in range(1 << (R - 1)):
+        cuts = [i + 1 for i in range(R - 1) if mask >> i & 1]
+        b = [0] + cuts + [R]
+        yield list(zip(b[:-1], b[1:]))
+
+
+# ---------------------------------------------------------------- schedule ---
+
+@pytest.mark.parametrize("causal", [1, 0])
+def test_layer_pack_major_is_bit_identical_to_microbatch_major(causal):
+    """The paper's correctness claim (Section 5.2): the swapped, regrouped
+    schedule gives exactly what ordinary training gives."""
+    cfg = tiny_cfg(n_blocks=3, causal=causal, M=3, b=2)
+    spec = oracle_spec(cfg)
+    params = f64(synth.gen_params(cfg, 1, bench_init=False))
+    m0, v0 = (f64(x) for x in synth.gen_adam_state(cfg, 1, zero=False))
+    ids = synth.gen_tokens(cfg, 1)
+    tg = synth.gen_targets(cfg, ids, 1)
+    hp = om.AdamHP(step=10)
+    ref = om.training_iteration(spec, params, ids, tg, m0, v0, hp)
+    R = spec.n_layers   # 5
+    tried = 0
+    for P_B in all_packings(R):
+        last_start = P_B[-1][0]
+        fwd_opts = list(all_packings(last_start)) if last_start > 0 else [[]]
+        for P_F in fwd_opts[::3] + fwd_opts[-1:]:
+            out = osch.iteration_layer_pack_major(spec, params, ids, tg, P_F, P_B, m0, v0, hp)
+            assert out["loss"] == ref["loss"] or abs(out["loss"] - ref["loss"]) < 1e-15
+            for k in ("grads", "weights", "m", "v"):
+                for name in params:
+                    np.testing.assert_array_equal(out[k][name], ref[k][name], err_msg=f"{k}:{name}")
+            tried += 1
+    assert tried > 16
+
+
+def test_task_list_order_follows_algorithm_3():
+    spec = om.Spec(4, 8, 2, 16, 4, 16)
+    P_B = [(0, 2), (2, 4), (4, 6)]
+    P_F = [(0, 3), (3, 4)]
+    tl = osch.task_list(spec, P_F, P_B)
+    assert [(t.kind, t.pack) for t in tl] == [
+        ("F", (0, 3)), ("F", (3, 4)),
+        ("B", (4, 6)), ("A", (4, 6)), ("B", (2, 4)), ("A", (2, 4)), ("B", (0, 2)), ("A", (0, 2))]
+    assert [t.index for t in tl] == list(range(8))
+    assert tl[0].stash_out_layers == [2] and tl[1].stash_out_layers == []
+    assert tl[4].stash_in_layer == 2 and tl[6].stash_in_layer is None and tl[2].stash_in_layer is None
+
+
+def test_bad_packs_are_rejected():
+    spec = om.Spec(2, 8, 2, 16, 4, 16)
+    with pytest.raises(ValueError):
+        osch.check_packs(spec, [], [(0, 2), (3, 4)])
+    with pytest.raises(ValueError):
+        osch.check_packs(spec, [(0, 1)], [(0, 2), (2, 4)])
+    with pytest.raises(ValueError):
+        osch.check_packs(spec, [], [(0, 3)])
+    osch.check_packs(spec, [(0, 1), (1, 2)], [(0, 2), (2, 4)])
+
+
+# -------------------------------------------------------------- swap bytes ---
+
+def test_residency_machine_reproduces_the_papers_weight_volumes():
+    """Section 3, 'Intuitive Example': one layer fits; equal layers.
+    Per-GPU swap: (4m+2)|W|.  Harmony: 3|W|."""
+    for R, m in itertools.product((1, 2, 6, 13), (1, 2, 5)):
+        pack_bytes = [1000] * R
+        W = sum(pack_bytes)
+        i, o = osw.residency_machine(osw.steps_microbatch_major(R, m, True), pack_bytes, True)
+        assert i + o == osw.paper_W_volume_per_gpu_swap_dp(m, 1, W) == (4 * m + 2) * W
+        i, o = osw.residency_machine(osw.steps_layer_pack_major(R, m, False), pack_bytes, False)
+        assert (i, o) == (2 * W, W)
+        assert i + o == osw.paper_W_volume_harmony_dp(1, W) == 3 * W
+        # jit-compute shares the last pack between the passes
+        i, o = osw.residency_machine(osw.steps_layer_pack_major(R, m, True), pack_bytes, False)
+        assert (i, o) == (2 * W - pack_bytes[-1], W)
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_closed_form_equals_ledger_equals_machine_on_every_packing(precision):
+    spec = om.Spec(4, 8, 2, 24, 4, 16)      # R = 6, unequal layers
+    R = spec.n_layers
+    w_c, k_B, g_B = osw.bytes_per_param(precision)
+    pc = [om.layer_param_count(spec, l) for l in range(R)]
+    for M, b in ((1, 1), (3, 2)):
+        for P_B in all_packings(R):
+            last_start = P_B[-1][0]
+            for P_F in (list(all_packings(last_start)) if last_start else [[]]):
+                cf = osw.closed_form(spec, P_F, P_B, M, b, precision)
+                lg = osw.ledger(spec, P_F, P_B, M, b, precision)
+                assert cf == lg
+                # weights, from first principles: forward packs then backward packs
+                packs = list(P_F) + list(P_B)
+                steps = [(i, False) for i in range(len(P_F)) for _ in range(M)]
+                for j in reversed(range(len(P_B))):
+                    steps += [(len(P_F) + j, False)] * M + [(len(P_F) + j, True)]
+                pb = [w_c * sum(pc[a:e]) for (a, e) in packs]
+                i, o = osw.residency_machine(steps, pb, False)
+                assert (i, o) == (cf["h2d"]["W"], cf["d2h"]["W"])
+                # microbatch-major brings the weights in exactly M times as often
+                mm = osw.closed_form_microbatch_major(spec, P_F, P_B, M, b, precision)
+                assert mm["h2d"]["W"] == M * cf["h2d"]["W"]
+                # optimizer state: in and out once (appendix), gradients never come in
+                K = k_B * sum(pc)
+                assert cf["h2d"]["K"] + cf["d2h"]["K"] == osw.paper_K_volume(1, K)
+                assert cf["h2d"]["dW"] == 0 and cf["d2h"]["dW"] == g_B * sum(pc)
+                assert cf["h2d"]["sX"] == cf["d2h"]["sX"] == \
+                    M * b * spec.seq_len * spec.d_model * w_c * max(len(P_B) - 2, 0)
+
+
+def test_weight_volume_reduces_to_3W_when_last_pack_is_counted_twice():
+    spec = om.Spec(3, 8, 2, 16, 4, 16)
+    P_B = [(0, 2), (2, 4), (4, 5)]
+    P_F = [(0, 4)]
+    cf = osw.closed_form(spec, P_F, P_B, 4, 2, "fp32")
+    W = 4 * sum(om.layer_param_count(spec, l) for l in range(5))
+    W_last = 4 * om.layer_param_count(spec, 4)
+    assert cf["h2d"]["W"] + cf["d2h"]["W"] + W_last == osw.paper_W_volume_harmony_dp(1, W)
+
+
+def test_parameter_counts_match_the_workload_table():
+    """p_blk = 4d^2 + 2df + 9d + f; GPT-2-medium ~ 355 M parameters."""
+    cfg = synth.CONFIGS["gpt2m"]
+    spec = oracle_spec(cfg)
+    d, f = 1024, 4096
+    assert om.layer_param_count(spec, 1) == 4 * d * d + 2 * d * f + 9 * d + f == 12_596_224
+    total = sum(om.layer_param_count(spec, l) for l in range(spec.n_layers))
+    assert total - 50257 * d == 354_823_168        # tied-head count of GPT-2 medium
+    assert list(om.param_shapes(spec).items()) == list(synth.shape_table(cfg).items())
+
+
+# ----------------------------------------------------------------- packing ---
+
+def test_equal_layers_split_evenly():
+    assert opk.balanced_time_packing([5] * 4, [10] * 4, 20) == [(0, 2), (2, 4)]
+    # ties are exact: 6 equal layers into 4 packs
+    packs = opk.balanced_time_packing([7] * 6, [10] * 6, 19)      # one layer per pack would be 6
+    assert packs == [(0, 1), (1, 2), (2, 3), (3, 4), (4, 5), (5, 6)]
+    packs = opk.balanced_time_packing([7] * 6, [10] * 6, 20)
+    assert packs == [(0, 2), (2, 4), (4, 6)]
+
+
+def test_packing_properties_on_random_profiles():
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        R = int(rng.integers(1, 14))
+        t = [int(x) for x in rng.integers(1, 100, R)]
+        m = [int(x) for x in rng.integers(1, 50, R)]
+        alpha = int(rng.integers(max(m), 4 * max(m) + 1))
+        packs = opk.balanced_time_packing(t, m, alpha)
+        assert packs is not None
+        assert packs[0][0] == 0 and packs[-1][1] == R
+        assert all(a < e for a, e in packs)
+        assert all(p[1] == q[0] for p, q in zip(packs, packs[1:]))
+        assert all(sum(m[a:e]) <= alpha for a, e in packs)
+        S_min = max(1, -(-sum(m) // alpha))
+        assert len(packs) >= S_min or len(packs) >= 1
+        # first feasible S is returned: every smaller S (from S_min) has an over-full pack
+        for S in range(S_min, R + 1):
+            cand = opk.packs_from_cuts(opk.split_points(t, S), R)
+            if all(sum(m[a:e]) <= alpha for a, e in cand):
+                assert cand == packs
+                break
+        else:   # no balanced split fits: one layer per pack
+            assert packs == [(j, j + 1) for j in range(R)]
+
+
+def test_infeasible_when_one_layer_exceeds_capacity():
+    assert opk.balanced_time_packing([1, 1, 1], [5, 50, 5], 49) is None
+    assert opk.balanced_time_packing([], [], 10) == []
+
+
+def test_uniform_transformer_layers_give_pack_sizes_differing_by_at_most_one():
+    """Shape of the paper's Table 'detailed scheduling result': BERT96's forward
+    packs are 21 packs of 4 layers and 3 packs of 3 over 93 layers; GPT2's
+    backward packs over blocks are 16 packs of 3 over 48 layers.
+    (Exact positions depend on the paper's measured profiles: unpinned.)"""
+    # 93 equal layers, capacity of 4 layers
+    packs = opk.balanced_time_packing([10] * 93, [1] * 93, 4)
+    sizes = [e - a for a, e in packs]
+    assert len(packs) == 24 and sorted(set(sizes)) == [3, 4]
+    assert sizes.count(4) == 21 and sizes.count(3) == 3
+    packs = opk.balanced_time_packing([10] * 48, [1] * 48, 3)
+    assert [e - a for a, e in packs] == [3] * 16
+    packs = opk.balanced_time_packing([10] * 48, [1] * 48, 5)
+    sizes = [e - a for a, e in packs]
+    assert len(packs) == 10 and sizes.count(5) == 8 and sizes.count(4) == 2
+
+
+def test_a_long_layer_gets_its_own_pack_and_empty_packs_are_dropped():
+    t = [1, 1, 100, 1, 1]
+    packs = opk.balanced_time_packing(t, [10] * 5, 25)
+    assert packs is not None and all(10 * (e - a) <= 25 for a, e in packs)
+    assert all(e > a for a, e in packs)
+    assert packs[0][0] == 0 and packs[-1][1] == 5
+
+
+def test_forward_packing_covers_layers_before_last_backward_pack():
+    P_B = [(0, 3), (3, 6), (6, 8)]
+    n = opk.forward_layers_given_backward(P_B)
+    assert n == 6
+    P_F = opk.balanced_time_packing([4] * n, [2] * n, 12)
+    assert P_F == [(0, 6)]
+    # forward footprints are smaller, so forward packs are at least as large
+    assert max(e - a for a, e in P_F) >= max(e - a for a, e in P_B[:-1])
