@@ -1,0 +1,271 @@
+/*
+ * hmy.h -- C ABI of the swap-aware training iteration for one MI355X (gfx950).
+ *
+ * The library runs ONE training iteration of a transformer stack whose model
+ * state exceeds an imposed HBM budget, in the layer-pack-major order of the
+ * Harmony paper (arxiv 2202.01306): weights, optimizer state, gradients and
+ * checkpoints live in caller-owned pinned host memory; each layer pack is
+ * swapped in once and run over all microbatches ("input-batch grouping",
+ * Section 3, optimisation 1), backward packs run in reverse with recompute from
+ * the stashed pack input (Section 4.3.1), the last pack runs forward+backward
+ * per microbatch ("jit-compute") and every pack is updated right after its
+ * backward ("jit-update", Section 3, optimisation 2).
+ *
+ * Conventions
+ *   - every struct is plain data with fixed-width integers; no C++ types;
+ *   - every function returns HMY_OK (0) or a negative hmy_error; nothing
+ *     aborts or throws; hmy_last_error() gives a thread-local detail string;
+ *   - "host" pointers are CPU addresses, "device" pointers are HBM addresses
+ *     on the handle's GPU; "pinned" host memory was allocated page-locked
+ *     (hmy_host_alloc or any hipHostMalloc-backed allocator);
+ *   - a handle is used by one thread at a time;
+ *   - layers: 0 = embedding, 1..n_blocks = transformer blocks,
+ *     n_blocks+1 = final LayerNorm + LM head + loss; R = n_blocks + 2;
+ *   - linear maps store W as [out, in] row-major, y = x W^T + bias;
+ *   - GB means 1e9 bytes wherever a budget is quoted.
+ */
+#ifndef HMY_H
+#define HMY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HMY_MAX_LAYERS 512
+#define HMY_NAME_LEN 32
+
+typedef enum hmy_error {
+  HMY_OK = 0,
+  HMY_E_INVALID = -1,          /* null pointer, bad shape, unsupported size          */
+  HMY_E_BUDGET_TOO_SMALL = -2, /* no packing fits: even one layer per pack overflows */
+  HMY_E_BAD_SCHEDULE = -3,     /* packs not contiguous / not covering / over budget  */
+  HMY_E_HIP = -4,              /* a HIP runtime call failed (detail in last_error)   */
+  HMY_E_NOT_BOUND = -5,        /* hmy_iteration before hmy_bind_state                */
+  HMY_E_NO_DEVICE = -6         /* the call needs a GPU and none is usable            */
+} hmy_error;
+
+/* Tensor kinds of the paper's swap analysis (Figure "Tensors that need to be
+ * swapped", appendix "Additional Swap Analysis") + the token ids/targets. */
+typedef enum hmy_kind {
+  HMY_KIND_W = 0,   /* weights in compute precision              */
+  HMY_KIND_DW = 1,  /* weight gradients (exported once, fp32)    */
+  HMY_KIND_K = 2,   /* optimizer state: (master,) m, v           */
+  HMY_KIND_SX = 3,  /* stashed input of a backward pack          */
+  HMY_KIND_XY = 4,  /* activations between packs (stay in HBM)   */
+  HMY_KIND_DXDY = 5,/* their gradients (stay in HBM)             */
+  HMY_KIND_IDS = 6, /* token ids and targets                     */
+  HMY_NKINDS = 7
+} hmy_kind;
+
+#define HMY_PREC_FP32 0 /* fp32 weights, activations, math; K = (m, v)                  */
+#define HMY_PREC_BF16 1 /* bf16 weights/activations, fp32 accumulate; K = (master, m, v) */
+
+/* The model: what the paper's Decomposer would hand over as R sequential layers. */
+typedef struct hmy_model_spec {
+  int32_t n_blocks, d_model, n_heads, d_ffn, seq_len, vocab;
+  int32_t causal;    /* 1 decoder (keys j<=i), 0 bidirectional encoder */
+  int32_t precision; /* HMY_PREC_* */
+  float ln_eps;
+} hmy_model_spec;
+
+/* The machine model of Algorithm 1: memory capacity alpha. */
+typedef struct hmy_budget {
+  uint64_t hbm_budget_bytes; /* everything the library keeps in HBM must fit */
+} hmy_budget;
+
+/* Configuration (Section 4.3.1): forward and backward layer packs as exclusive
+ * end indices over the R layers.  Backward packs cover 0..R; forward packs cover
+ * exactly the layers before the last backward pack (Algorithm 2, lines 1-2).
+ * Microbatch sizes U_F = U_B = micro_batch are given by the caller. */
+typedef struct hmy_schedule {
+  int32_t n_fwd_packs, n_bwd_packs;
+  int32_t fwd_pack_end[HMY_MAX_LAYERS];
+  int32_t bwd_pack_end[HMY_MAX_LAYERS];
+} hmy_schedule;
+
+/* One minibatch as a list of n_micro microbatches of micro_batch sequences. */
+typedef struct hmy_minibatch {
+  int32_t n_micro, micro_batch;
+  const int32_t *token_ids; /* host, pinned or pageable; [n_micro*micro_batch*seq_len] */
+  const int32_t *targets;   /* host, same shape; -1 = position is not a target       */
+} hmy_minibatch;
+
+typedef struct hmy_adam {
+  float lr, beta1, beta2, eps;
+  int64_t step; /* 1-based */
+} hmy_adam;
+
+/* Caller-owned PINNED host arrays of n_params elements each, tensors in layout
+ * order (hmy_layout), no padding.  weights: bf16 (HMY_PREC_BF16) or fp32.
+ * master: fp32, only for HMY_PREC_BF16 (NULL otherwise: the fp32 weights are the
+ * master).  adam_m, adam_v, grads: fp32.  After hmy_iteration they hold the
+ * updated weights/state and this iteration's accumulated gradients. */
+typedef struct hmy_host_state {
+  void *weights;
+  float *master;
+  float *adam_m, *adam_v;
+  float *grads;
+  uint64_t n_params;
+} hmy_host_state;
+
+typedef struct hmy_stats {
+  uint64_t h2d[HMY_NKINDS]; /* bytes enqueued host->device, per kind */
+  uint64_t d2h[HMY_NKINDS]; /* bytes enqueued device->host, per kind */
+  double loss;              /* sum over target positions / number of targets */
+  double t_iter_s;          /* wall time of the iteration (host clock)      */
+  double t_compute_s;       /* compute stream: first kernel to last (events) */
+  double t_h2d_busy_s;      /* sum of H2D copy durations (events)           */
+  double t_d2h_busy_s;      /* sum of D2H copy durations (events)           */
+  double t_stall_s;         /* time the compute stream spent waiting on swaps */
+  uint64_t n_targets;
+} hmy_stats;
+
+typedef struct hmy_tensor_desc {
+  char name[HMY_NAME_LEN]; /* "wte", "h3.wqkv", "lnf_g", ... */
+  int32_t layer;
+  int32_t rows, cols;      /* cols = 1 for vectors */
+  uint64_t offset;         /* element offset inside every host array */
+  uint64_t count;          /* rows*cols */
+} hmy_tensor_desc;
+
+/* Analytic per-layer profile phi(type, U, layer) for one microbatch of
+ * micro_batch sequences (the paper measures it, Section 4.2; here it is
+ * computed): integer "times" (flops) and byte footprints. */
+typedef struct hmy_layer_profile {
+  int64_t t_fwd, t_bwd;   /* forward; recompute + backward                       */
+  uint64_t params;
+  uint64_t mem_fwd;       /* 2 * weight bytes (double-buffered)                    */
+  uint64_t mem_bwd;       /* 2 * (weight + fp32 gradient) bytes + activations      */
+  uint64_t act_bwd;       /* activations one microbatch keeps for backward         */
+} hmy_layer_profile;
+
+typedef struct hmy_arena_plan {
+  uint64_t total;         /* bytes of HBM the iteration needs (<= budget)          */
+  uint64_t reserved;      /* everything that does not depend on the packs          */
+  uint64_t slot_bytes;    /* one weight slot (there are two)                       */
+  uint64_t act_bytes;     /* activation workspace of the largest backward pack     */
+  uint64_t k_chunk_params;/* optimizer state streams through a ring of such chunks */
+} hmy_arena_plan;
+
+typedef struct hmy_handle hmy_handle;
+
+/* ---- host-only calls (no GPU needed) ----------------------------------- */
+
+const char *hmy_strerror(int err);
+const char *hmy_last_error(void);
+
+/* Number of layers R and of parameters; fails on shapes the kernels do not
+ * support (d_model % n_heads, d_model % 8, d_ffn % 8, d_head not in {32,64,128}
+ * ...). */
+int hmy_model_size(const hmy_model_spec *spec, int32_t *n_layers, uint64_t *n_params);
+
+/* Tensor table in storage order.  out may be NULL to query *n only; cap is the
+ * capacity of out in entries. */
+int hmy_layout(const hmy_model_spec *spec, hmy_tensor_desc *out, int32_t cap, int32_t *n);
+
+/* Per-layer profile (out has R entries) and the pack-independent reserve. */
+int hmy_profile(const hmy_model_spec *spec, int32_t n_micro, int32_t micro_batch,
+                hmy_layer_profile *out, uint64_t *reserved_bytes);
+
+/* Balanced-time packing (Algorithm 2) under the budget: backward packs first,
+ * forward packs over the layers before the last backward pack. */
+int hmy_plan(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_micro,
+             int32_t micro_batch, hmy_schedule *out);
+
+/* Validate a schedule and size the HBM arena it needs. */
+int hmy_arena(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro,
+              int32_t micro_batch, hmy_arena_plan *out);
+
+/* Walk the iteration's task list exactly as hmy_iteration does, touching no
+ * device: fills only the byte counters of *out. */
+int hmy_count_swaps(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro,
+                    int32_t micro_batch, hmy_stats *out);
+
+/* ---- device calls ------------------------------------------------------- */
+
+/* Page-locked host memory for hmy_host_state (hipHostMalloc / hipHostFree). */
+int hmy_host_alloc(uint64_t bytes, void **out);
+int hmy_host_free(void *p);
+
+/* Create the engine on `hip_device`.  sched == NULL plans with hmy_plan.
+ * arena: device pointer to at least hmy_arena().total bytes, 256-byte aligned,
+ * owned by the caller for the handle's lifetime; NULL lets the library
+ * allocate it.  Fails with HMY_E_BUDGET_TOO_SMALL if the arena exceeds the
+ * budget. */
+int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_micro,
+               int32_t micro_batch, const hmy_schedule *sched, int32_t hip_device,
+               void *arena, uint64_t arena_bytes, hmy_handle **out);
+int hmy_get_schedule(const hmy_handle *h, hmy_schedule *out);
+int hmy_bind_state(hmy_handle *h, const hmy_host_state *state);
+
+/* One iteration: gradients of the minibatch, Adam on every tensor, swap-byte
+ * counters.  Returns with all streams idle. */
+int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out);
+int hmy_destroy(hmy_handle *h);
+
+/* 0 = reference kernels (plain tiled loops), 1 = MFMA kernels where they exist
+ * (default).  Process-wide; for tests and A/B timing. */
+int hmy_set_kernel_path(int32_t use_mfma);
+
+/* ---- single kernels (all pointers DEVICE, stream = hipStream_t or NULL) ---
+ * prec selects the element type E of activations/weights (HMY_PREC_*).  These
+ * are the per-layer operations of one microbatch, T = rows. */
+
+/* x[T,d] = wte[id] + wpe[t % s] */
+int hmy_k_embed_fwd(int32_t prec, const int32_t *ids, const void *wte, const void *wpe, void *x,
+                    int32_t T, int32_t d, int32_t s, int32_t vocab, void *stream);
+/* dwte[id] += dx, dwpe[t % s] += dx  (fp32 accumulators) */
+int hmy_k_embed_bwd(int32_t prec, const int32_t *ids, const void *dx, float *dwte, float *dwpe,
+                    int32_t T, int32_t d, int32_t s, int32_t vocab, void *stream);
+/* y = gamma * (x-mean)*rstd + beta; mean,rstd [T] fp32 saved */
+int hmy_k_layernorm_fwd(int32_t prec, const void *x, const void *gamma, const void *beta, void *y,
+                        float *mean, float *rstd, int32_t T, int32_t d, float eps, void *stream);
+/* dx = (res ? res : 0) + LN'(dy); dgamma,dbeta += (fp32).  dx may alias res. */
+int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float *mean,
+                        const float *rstd, const void *gamma, const void *res, void *dx,
+                        float *dgamma, float *dbeta, int32_t T, int32_t d, void *stream);
+/* g = gelu_tanh(u); du = dg * gelu'(u) (du may alias dg) */
+int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream);
+int hmy_k_gelu_bwd(int32_t prec, const void *dg, const void *u, void *du, uint64_t n, void *stream);
+/* out[N] += column sums of a[T,N]  (fp32 accumulators; bias gradients) */
+int hmy_k_colsum(int32_t prec, const void *a, float *out, int32_t T, int32_t N, void *stream);
+
+/* C[M,N] = op(A) op(B) (+bias[N]) (+res[M,N]); optional second output
+ * gelu_out = gelu(C).  A is [M,K] (ta=0) or stored [K,M] (ta=1); B is stored
+ * [N,K] (tb=0: y = x W^T) or [K,N] (tb=1).  A, B, bias, res, gelu_out have
+ * element type E(prec); C has type E, or fp32 if c_fp32.  accumulate: C += (only
+ * with c_fp32).  Leading dimensions in elements. */
+typedef struct hmy_gemm_desc {
+  int32_t prec, M, N, K;
+  int32_t ta, tb, c_fp32, accumulate;
+  const void *A; int64_t lda;
+  const void *B; int64_t ldb;
+  void *C; int64_t ldc;
+  const void *bias;
+  const void *res; int64_t ldr;
+  void *gelu_out;
+} hmy_gemm_desc;
+int hmy_k_gemm(const hmy_gemm_desc *g, void *stream);
+
+/* qkv[T,3d] (q|k|v thirds, head h = columns h*dh..) -> o[T,d], lse[b,H,s] fp32 */
+int hmy_k_attn_fwd(int32_t prec, const void *qkv, void *o, float *lse, int32_t b, int32_t s,
+                   int32_t H, int32_t dh, int32_t causal, void *stream);
+/* dqkv[T,3d] from do[T,d]; delta[b,H,s] fp32 is scratch */
+int hmy_k_attn_bwd(int32_t prec, const void *qkv, const void *o, const void *d_o, const float *lse,
+                   float *delta, void *dqkv, int32_t b, int32_t s, int32_t H, int32_t dh,
+                   int32_t causal, void *stream);
+/* rows with target>=0: loss_acc[0] += (lse - logit[target]) * inv_ntgt (fp64 atomics); dlogits = (softmax - onehot) * inv_ntgt; other rows: dlogits = 0.
+ * logits fp32 [T,V] row stride ldl; dlogits type E, same stride. */
+int hmy_k_xent(int32_t prec, const float *logits, const int32_t *targets, double *loss_acc,
+               void *dlogits, int32_t T, int32_t V, int64_t ldl, float inv_ntgt, void *stream);
+/* Adam with bias correction.  bf16: master/m/v fp32 updated, w_out = RNE bf16(master).
+ * fp32: w (fp32, in w_out) is the master; master must be NULL. */
+int hmy_k_adam(int32_t prec, const float *grad, float *master, float *m, float *v, void *w_out,
+               uint64_t n, const hmy_adam *hp, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HMY_H */

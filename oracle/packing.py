@@ -77,3 +77,124 @@ def balanced_time_packing(t, m, alpha: int, also_fits=None, first: int = 0):
 def forward_layers_given_backward(P_B):
     """Number of layers the forward packing covers: all before P_B's last pack."""
     return P_B[-1][0]
+
+
+# --------------------------------------------------------------------------
+# analytic layer profile and device-memory model of the runtime under test
+# --------------------------------------------------------------------------
+# The paper's Profiler measures per-layer time, memory and activation size
+# (Section 4.2).  Here they are computed: "time" is the flop count of one
+# microbatch; memory follows the runtime's arena, written out below from its
+# description (two weight slots, one activation workspace, a pack-independent
+# reserve), every buffer rounded up to 256 bytes.
+
+def _a256(x: int) -> int:
+    return (x + 255) // 256 * 256
+
+
+OUT_RING, IN_RING, K_RING = 4, 2, 3
+K_CHUNK_MAX = 4 * 2 ** 20
+LOGIT_ROWS = 512
+
+
+def elem_bytes(precision: str) -> int:
+    return {"fp32": 4, "bf16": 2}[precision]
+
+
+def block_act_bytes(spec, b: int, precision: str) -> int:
+    """What one microbatch keeps per block for backward: x_in, LN1 out, qkv,
+    attention out, x_mid, LN2 out, MLP pre- and post-activation, two LayerNorm
+    (mean, rstd) pairs and the attention logsumexp."""
+    E = elem_bytes(precision)
+    T, d, f, H = b * spec.seq_len, spec.d_model, spec.d_ffn, spec.n_heads
+    sizes = [T * d * E, T * d * E, 3 * T * d * E, T * d * E, T * d * E, T * d * E, T * f * E, T * f * E,
+             T * 4, T * 4, T * 4, T * 4, T * H * 4]
+    return sum(_a256(x) for x in sizes)
+
+
+def head_act_bytes(spec, b: int, precision: str) -> int:
+    """Head input, final-LN output, its (mean, rstd), and one chunk of logits
+    (fp32) and their gradient (element type), rows padded to a multiple of 8."""
+    E = elem_bytes(precision)
+    T, d = b * spec.seq_len, spec.d_model
+    rows = min(T, LOGIT_ROWS)
+    ldl = (spec.vocab + 7) // 8 * 8
+    sizes = [T * d * E, T * d * E, T * 4, T * 4, rows * ldl * 4, rows * ldl * E]
+    return sum(_a256(x) for x in sizes)
+
+
+def layer_profile(spec, M: int, b: int, precision: str):
+    """Per layer: dict(t_fwd, t_bwd, params, mem_fwd, mem_bwd, act_bwd)."""
+    from . import model as om
+    E = elem_bytes(precision)
+    T, d, f, V, s = b * spec.seq_len, spec.d_model, spec.d_ffn, spec.vocab, spec.seq_len
+    out = []
+    for layer in range(spec.n_layers):
+        p = om.layer_param_count(spec, layer)
+        if layer == 0:
+            t_f, act = T * d, 0
+        elif layer <= spec.n_blocks:
+            t_f = T * (8 * d * d + 4 * d * f + (2 if spec.causal else 4) * s * d)
+            act = block_act_bytes(spec, b, precision)
+        else:
+            t_f, act = 2 * T * d * V, head_act_bytes(spec, b, precision)
+        out.append(dict(t_fwd=t_f, t_bwd=3 * t_f, params=p, mem_fwd=2 * E * p,
+                        mem_bwd=2 * (E + 4) * p + act, act_bwd=act))
+    return out
+
+
+def reserved_bytes(spec, M: int, b: int, precision: str) -> int:
+    """Pack-independent device memory: resident boundary activations (one per
+    microbatch), pack-input ring, checkpoint staging ring, gradient scratch,
+    ids and targets, a 4 KiB scalar page, and the optimizer-state ring."""
+    from . import model as om
+    E = elem_bytes(precision)
+    T, d, f, H = b * spec.seq_len, spec.d_model, spec.d_ffn, spec.n_heads
+    x = _a256(T * d * E)
+    total = _a256(M * x) + _a256(IN_RING * x) + _a256(OUT_RING * x)
+    total += _a256(T * max(f, 3 * d) * E) + _a256(T * d * E) + _a256(T * H * 4)
+    total += 2 * _a256(M * T * 4) + 4096
+    chunk = min(K_CHUNK_MAX, max(om.layer_param_count(spec, l) for l in range(spec.n_layers)))
+    n_k = 3 if precision == "bf16" else 2
+    total += _a256(K_RING * n_k * _a256(chunk * 4))
+    return total
+
+
+def arena_bytes(spec, P_F, P_B, M: int, b: int, precision: str):
+    """(total, slot_bytes, act_bytes): reserve + two weight slots + the largest
+    backward pack's activation workspace."""
+    from . import model as om
+    E = elem_bytes(precision)
+    prof = layer_profile(spec, M, b, precision)
+
+    def npar(a, e):
+        return sum(om.layer_param_count(spec, l) for l in range(a, e))
+    slot = 0
+    for (a, e) in P_F:
+        slot = max(slot, _a256(E * npar(a, e)))
+    act = 0
+    for (a, e) in P_B:
+        slot = max(slot, _a256(E * npar(a, e)) + _a256(4 * npar(a, e)))
+        act = max(act, sum(prof[l]["act_bwd"] for l in range(a, e)))
+    return reserved_bytes(spec, M, b, precision) + 2 * slot + act, slot, act
+
+
+def plan(spec, budget: int, M: int, b: int, precision: str):
+    """Backward packs by Algorithm 2 on (t_bwd, mem_bwd) with capacity budget -
+    reserve and the whole-arena test; then forward packs on (t_fwd, mem_fwd)
+    over the layers before the last backward pack with capacity 2 * slot.
+    Returns (P_F, P_B) or None."""
+    prof = layer_profile(spec, M, b, precision)
+    res = reserved_bytes(spec, M, b, precision)
+    if budget <= res:
+        return None
+    P_B = balanced_time_packing([p["t_bwd"] for p in prof], [p["mem_bwd"] for p in prof], budget - res,
+                                also_fits=lambda packs: arena_bytes(spec, [], packs, M, b, precision)[0] <= budget)
+    if P_B is None:
+        return None
+    slot = arena_bytes(spec, [], P_B, M, b, precision)[1]
+    RF = forward_layers_given_backward(P_B)
+    P_F = balanced_time_packing([p["t_fwd"] for p in prof[:RF]], [p["mem_fwd"] for p in prof[:RF]], 2 * slot)
+    if P_F is None:
+        return None
+    return P_F, P_B

@@ -1,0 +1,177 @@
+// C ABI: host-only entry points and the single-kernel entry points.  The engine's
+// own entry points (create / bind / iteration / destroy / count_swaps) live next
+// to the executor.
+#include <cstring>
+
+#include "hmy_internal.h"
+
+namespace hmy {
+const char *last_error();
+}
+using namespace hmy;
+
+extern "C" {
+
+const char *hmy_strerror(int err) {
+  switch (err) {
+    case HMY_OK: return "ok";
+    case HMY_E_INVALID: return "invalid argument";
+    case HMY_E_BUDGET_TOO_SMALL: return "HBM budget too small for any packing";
+    case HMY_E_BAD_SCHEDULE: return "bad schedule";
+    case HMY_E_HIP: return "HIP runtime error";
+    case HMY_E_NOT_BOUND: return "host state not bound";
+    case HMY_E_NO_DEVICE: return "no usable GPU";
+    default: return "unknown error";
+  }
+}
+
+const char *hmy_last_error(void) { return hmy::last_error(); }
+
+int hmy_model_size(const hmy_model_spec *spec, int32_t *n_layers, uint64_t *n_params) {
+  Model m;
+  int rc = build_model(spec, &m);
+  if (rc) return rc;
+  if (n_layers) *n_layers = m.R;
+  if (n_params) *n_params = m.n_params;
+  return HMY_OK;
+}
+
+int hmy_layout(const hmy_model_spec *spec, hmy_tensor_desc *out, int32_t cap, int32_t *n) {
+  if (!n) return fail(HMY_E_INVALID, "null n");
+  Model m;
+  int rc = build_model(spec, &m);
+  if (rc) return rc;
+  *n = int32_t(m.tensors.size());
+  if (!out) return HMY_OK;
+  if (cap < *n) return fail(HMY_E_INVALID, "layout: capacity %d < %d tensors", cap, *n);
+  for (size_t i = 0; i < m.tensors.size(); ++i) {
+    const Tensor &t = m.tensors[i];
+    std::memset(&out[i], 0, sizeof(out[i]));
+    std::strncpy(out[i].name, t.name.c_str(), HMY_NAME_LEN - 1);
+    out[i].layer = t.layer;
+    out[i].rows = t.rows;
+    out[i].cols = t.cols;
+    out[i].offset = t.offset;
+    out[i].count = t.count;
+  }
+  return HMY_OK;
+}
+
+int hmy_profile(const hmy_model_spec *spec, int32_t n_micro, int32_t micro_batch, hmy_layer_profile *out,
+                uint64_t *reserved_bytes) {
+  Model m;
+  int rc = build_model(spec, &m);
+  if (rc) return rc;
+  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
+  if (out) {
+    std::vector<hmy_layer_profile> prof;
+    layer_profile(m, n_micro, micro_batch, &prof);
+    for (int l = 0; l < m.R; ++l) out[l] = prof[l];
+  }
+  if (reserved_bytes) *reserved_bytes = reserved_layout(m, n_micro, micro_batch).size;
+  return HMY_OK;
+}
+
+int hmy_plan(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_micro, int32_t micro_batch,
+             hmy_schedule *out) {
+  if (!budget || !out) return fail(HMY_E_INVALID, "null argument");
+  Model m;
+  int rc = build_model(spec, &m);
+  if (rc) return rc;
+  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
+  Packs p;
+  rc = plan_packs(m, budget->hbm_budget_bytes, n_micro, micro_batch, &p);
+  if (rc) return rc;
+  packs_to_schedule(p, out);
+  return HMY_OK;
+}
+
+int hmy_arena(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro, int32_t micro_batch,
+              hmy_arena_plan *out) {
+  if (!out) return fail(HMY_E_INVALID, "null argument");
+  Model m;
+  int rc = build_model(spec, &m);
+  if (rc) return rc;
+  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
+  Packs p;
+  rc = schedule_to_packs(m, sched, &p);
+  if (rc) return rc;
+  const Arena a = arena_layout(m, p, n_micro, micro_batch);
+  for (const Pack &q : p.fwd)
+    if (pack_state_fwd(m, q) > a.slot_bytes) return fail(HMY_E_BAD_SCHEDULE, "forward pack over slot");
+  out->total = a.total;
+  out->reserved = a.res.size;
+  out->slot_bytes = a.slot_bytes;
+  out->act_bytes = a.act_bytes;
+  out->k_chunk_params = a.res.k_chunk_params;
+  return HMY_OK;
+}
+
+int hmy_set_kernel_path(int32_t use_mfma) {
+  g_use_mfma = use_mfma ? 1 : 0;
+  return HMY_OK;
+}
+
+// ---- single kernels ----------------------------------------------------------------
+#define NOTNULL(p) \
+  if (!(p)) return fail(HMY_E_INVALID, "%s: null pointer %s", __func__, #p)
+
+int hmy_k_embed_fwd(int32_t prec, const int32_t *ids, const void *wte, const void *wpe, void *x, int32_t T, int32_t d,
+                    int32_t s, int32_t vocab, void *stream) {
+  NOTNULL(ids); NOTNULL(wte); NOTNULL(wpe); NOTNULL(x);
+  return launch_embed_fwd(prec, ids, wte, wpe, x, T, d, s, vocab, stream);
+}
+int hmy_k_embed_bwd(int32_t prec, const int32_t *ids, const void *dx, float *dwte, float *dwpe, int32_t T, int32_t d,
+                    int32_t s, int32_t vocab, void *stream) {
+  NOTNULL(ids); NOTNULL(dx); NOTNULL(dwte); NOTNULL(dwpe);
+  return launch_embed_bwd(prec, ids, dx, dwte, dwpe, T, d, s, vocab, stream);
+}
+int hmy_k_layernorm_fwd(int32_t prec, const void *x, const void *gamma, const void *beta, void *y, float *mean,
+                        float *rstd, int32_t T, int32_t d, float eps, void *stream) {
+  NOTNULL(x); NOTNULL(gamma); NOTNULL(beta); NOTNULL(y); NOTNULL(mean); NOTNULL(rstd);
+  return launch_layernorm_fwd(prec, x, gamma, beta, y, mean, rstd, T, d, eps, stream);
+}
+int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float *mean, const float *rstd,
+                        const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int32_t T, int32_t d,
+                        void *stream) {
+  NOTNULL(dy); NOTNULL(x); NOTNULL(mean); NOTNULL(rstd); NOTNULL(gamma); NOTNULL(dx); NOTNULL(dgamma); NOTNULL(dbeta);
+  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream);
+}
+int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream) {
+  NOTNULL(u); NOTNULL(g);
+  return launch_gelu_fwd(prec, u, g, n, stream);
+}
+int hmy_k_gelu_bwd(int32_t prec, const void *dg, const void *u, void *du, uint64_t n, void *stream) {
+  NOTNULL(dg); NOTNULL(u); NOTNULL(du);
+  return launch_gelu_bwd(prec, dg, u, du, n, stream);
+}
+int hmy_k_colsum(int32_t prec, const void *a, float *out, int32_t T, int32_t N, void *stream) {
+  NOTNULL(a); NOTNULL(out);
+  return launch_colsum(prec, a, out, T, N, stream);
+}
+int hmy_k_gemm(const hmy_gemm_desc *g, void *stream) {
+  NOTNULL(g);
+  return launch_gemm(*g, stream);
+}
+int hmy_k_attn_fwd(int32_t prec, const void *qkv, void *o, float *lse, int32_t b, int32_t s, int32_t H, int32_t dh,
+                   int32_t causal, void *stream) {
+  NOTNULL(qkv); NOTNULL(o); NOTNULL(lse);
+  return launch_attn_fwd(prec, qkv, o, lse, b, s, H, dh, causal, stream);
+}
+int hmy_k_attn_bwd(int32_t prec, const void *qkv, const void *o, const void *d_o, const float *lse, float *delta,
+                   void *dqkv, int32_t b, int32_t s, int32_t H, int32_t dh, int32_t causal, void *stream) {
+  NOTNULL(qkv); NOTNULL(o); NOTNULL(d_o); NOTNULL(lse); NOTNULL(delta); NOTNULL(dqkv);
+  return launch_attn_bwd(prec, qkv, o, d_o, lse, delta, dqkv, b, s, H, dh, causal, stream);
+}
+int hmy_k_xent(int32_t prec, const float *logits, const int32_t *targets, double *loss_acc, void *dlogits, int32_t T,
+               int32_t V, int64_t ldl, float inv_ntgt, void *stream) {
+  NOTNULL(logits); NOTNULL(targets); NOTNULL(loss_acc); NOTNULL(dlogits);
+  return launch_xent(prec, logits, targets, loss_acc, dlogits, T, V, ldl, inv_ntgt, stream);
+}
+int hmy_k_adam(int32_t prec, const float *grad, float *master, float *m, float *v, void *w_out, uint64_t n,
+               const hmy_adam *hp, void *stream) {
+  NOTNULL(grad); NOTNULL(m); NOTNULL(v); NOTNULL(w_out); NOTNULL(hp);
+  return launch_adam(prec, grad, master, m, v, w_out, n, *hp, stream);
+}
+
+}  // extern "C"

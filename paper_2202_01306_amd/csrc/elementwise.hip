@@ -1,0 +1,443 @@
+// HBM-bound kernels: embedding, LayerNorm, GELU, bias-gradient column sums,
+// softmax cross-entropy, fused Adam, fill and copy.  One wavefront (64 lanes)
+// per row for the row reductions; 16-byte accesses along the contiguous axis.
+#include <algorithm>
+#include <cmath>
+
+#include "dev_common.h"
+#include "hmy_internal.h"
+
+namespace hmy {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+inline int grid_for(uint64_t work_items, int per_block, int cap = 1 << 16) {
+  uint64_t g = (work_items + per_block - 1) / per_block;
+  if (g < 1) g = 1;
+  if (g > uint64_t(cap)) g = cap;
+  return int(g);
+}
+
+inline int check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(HMY_E_HIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return HMY_OK;
+}
+
+// ---- fill / copy ---------------------------------------------------------------
+__global__ void k_fill_zero(uint32_t *p, uint64_t n_words) {
+  const uint64_t stride = uint64_t(gridDim.x) * blockDim.x;
+  const uint64_t n4 = n_words / 4;
+  uint4 *p4 = reinterpret_cast<uint4 *>(p);
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n4; i += stride) p4[i] = make_uint4(0, 0, 0, 0);
+  for (uint64_t i = n4 * 4 + uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n_words; i += stride) p[i] = 0;
+}
+__global__ void k_copy(uint32_t *dst, const uint32_t *src, uint64_t n_words) {
+  const uint64_t stride = uint64_t(gridDim.x) * blockDim.x;
+  const uint64_t n4 = n_words / 4;
+  uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+  const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n4; i += stride) d4[i] = s4[i];
+  for (uint64_t i = n4 * 4 + uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n_words; i += stride) dst[i] = src[i];
+}
+
+// ---- embedding ---------------------------------------------------------------
+template <typename E>
+__global__ void k_embed_fwd(const int32_t *ids, const E *wte, const E *wpe, E *x, int T, int d, int s) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  const int vec_per_row = d / VEC;
+  const uint64_t total = uint64_t(T) * vec_per_row;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += uint64_t(gridDim.x) * blockDim.x) {
+    const int t = int(i / vec_per_row), c = int(i % vec_per_row) * VEC;
+    const Vec16<E> a = load16(wte + uint64_t(ids[t]) * d + c);
+    const Vec16<E> p = load16(wpe + uint64_t(t % s) * d + c);
+    Vec16<E> o;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) o.v[k] = from_f32<E>(to_f32(a.v[k]) + to_f32(p.v[k]));
+    store16(x + uint64_t(t) * d + c, o);
+  }
+}
+// dwte[id[t]] += dx[t]  (rows may repeat: atomics)
+template <typename E>
+__global__ void k_embed_bwd_wte(const int32_t *ids, const E *dx, float *dwte, int T, int d) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  const int vec_per_row = d / VEC;
+  const uint64_t total = uint64_t(T) * vec_per_row;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += uint64_t(gridDim.x) * blockDim.x) {
+    const int t = int(i / vec_per_row), c = int(i % vec_per_row) * VEC;
+    const Vec16<E> g = load16(dx + uint64_t(t) * d + c);
+    float *dst = dwte + uint64_t(ids[t]) * d + c;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) atomicAdd(dst + k, to_f32(g.v[k]));
+  }
+}
+// dwpe[j] += sum over sequences of dx[i*s + j]  (one owner per element: no atomics)
+template <typename E>
+__global__ void k_embed_bwd_wpe(const E *dx, float *dwpe, int T, int d, int s) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  const int vec_per_row = d / VEC;
+  const int nseq = T / s;
+  const uint64_t total = uint64_t(s) * vec_per_row;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += uint64_t(gridDim.x) * blockDim.x) {
+    const int j = int(i / vec_per_row), c = int(i % vec_per_row) * VEC;
+    float acc[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = 0.f;
+    for (int q = 0; q < nseq; ++q) {
+      const Vec16<E> g = load16(dx + (uint64_t(q) * s + j) * d + c);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) acc[k] += to_f32(g.v[k]);
+    }
+    float *dst = dwpe + uint64_t(j) * d + c;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) dst[k] += acc[k];
+  }
+}
+
+// ---- LayerNorm -----------------------------------------------------------------
+// One wavefront per row.  Mean, then biased variance about the mean, then the
+// normalised output; the row is re-read from cache between passes.
+template <typename E>
+__global__ void k_layernorm_fwd(const E *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T, int d,
+                                float eps) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  for (int row = blockIdx.x * kWavesPerBlock + wave; row < T; row += gridDim.x * kWavesPerBlock) {
+    const E *xr = x + uint64_t(row) * d;
+    float s = 0.f;
+    for (int c = lane * VEC; c < d; c += kWave * VEC) {
+      const Vec16<E> v = load16(xr + c);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) s += to_f32(v.v[k]);
+    }
+    const float mu = wave_sum(s) / float(d);
+    float q = 0.f;
+    for (int c = lane * VEC; c < d; c += kWave * VEC) {
+      const Vec16<E> v = load16(xr + c);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        const float t = to_f32(v.v[k]) - mu;
+        q += t * t;
+      }
+    }
+    const float rs = rsqrtf(wave_sum(q) / float(d) + eps);
+    if (lane == 0) {
+      mean[row] = mu;
+      rstd[row] = rs;
+    }
+    E *yr = y + uint64_t(row) * d;
+    for (int c = lane * VEC; c < d; c += kWave * VEC) {
+      const Vec16<E> v = load16(xr + c), g = load16(gamma + c), b = load16(beta + c);
+      Vec16<E> o;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) o.v[k] = from_f32<E>(to_f32(g.v[k]) * ((to_f32(v.v[k]) - mu) * rs) + to_f32(b.v[k]));
+      store16(yr + c, o);
+    }
+  }
+}
+
+// dx = res + (dxhat - mean(dxhat) - xhat*mean(dxhat*xhat)) * rstd, dxhat = dy*gamma;
+// dgamma += sum_rows dy*xhat, dbeta += sum_rows dy.  Per-block partial column
+// sums live in LDS (2*d floats) and are flushed with one atomic per column.
+template <typename E>
+__global__ void k_layernorm_bwd(const E *dy, const E *x, const float *mean, const float *rstd, const E *gamma,
+                                const E *res, E *dx, float *dgamma, float *dbeta, int T, int d) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  extern __shared__ float lds[];
+  float *s_dg = lds, *s_db = lds + d;
+  for (int c = threadIdx.x; c < 2 * d; c += blockDim.x) lds[c] = 0.f;
+  __syncthreads();
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  for (int row = blockIdx.x * kWavesPerBlock + wave; row < T; row += gridDim.x * kWavesPerBlock) {
+    const E *xr = x + uint64_t(row) * d, *dyr = dy + uint64_t(row) * d;
+    const float mu = mean[row], rs = rstd[row];
+    float s1 = 0.f, s2 = 0.f;
+    for (int c = lane * VEC; c < d; c += kWave * VEC) {
+      const Vec16<E> xv = load16(xr + c), gv = load16(dyr + c), gm = load16(gamma + c);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        const float xh = (to_f32(xv.v[k]) - mu) * rs;
+        const float g = to_f32(gv.v[k]);
+        const float dxh = g * to_f32(gm.v[k]);
+        s1 += dxh;
+        s2 += dxh * xh;
+        atomicAdd(&s_dg[c + k], g * xh);
+        atomicAdd(&s_db[c + k], g);
+      }
+    }
+    s1 = wave_sum(s1) / float(d);
+    s2 = wave_sum(s2) / float(d);
+    E *dxr = dx + uint64_t(row) * d;
+    const E *rr = res ? res + uint64_t(row) * d : nullptr;
+    for (int c = lane * VEC; c < d; c += kWave * VEC) {
+      const Vec16<E> xv = load16(xr + c), gv = load16(dyr + c), gm = load16(gamma + c);
+      Vec16<E> rv;
+      if (rr) rv = load16(rr + c);
+      Vec16<E> o;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        const float xh = (to_f32(xv.v[k]) - mu) * rs;
+        const float dxh = to_f32(gv.v[k]) * to_f32(gm.v[k]);
+        float v = (dxh - s1 - xh * s2) * rs;
+        if (rr) v += to_f32(rv.v[k]);
+        o.v[k] = from_f32<E>(v);
+      }
+      store16(dxr + c, o);
+    }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    atomicAdd(&dgamma[c], s_dg[c]);
+    atomicAdd(&dbeta[c], s_db[c]);
+  }
+}
+
+// ---- GELU ------------------------------------------------------------------------
+template <typename E>
+__global__ void k_gelu_fwd(const E *u, E *g, uint64_t nvec) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec; i += uint64_t(gridDim.x) * blockDim.x) {
+    const Vec16<E> a = load16(u + i * VEC);
+    Vec16<E> o;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) o.v[k] = from_f32<E>(gelu_f(to_f32(a.v[k])));
+    store16(g + i * VEC, o);
+  }
+}
+template <typename E>
+__global__ void k_gelu_bwd(const E *dg, const E *u, E *du, uint64_t nvec) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec; i += uint64_t(gridDim.x) * blockDim.x) {
+    const Vec16<E> a = load16(u + i * VEC), b = load16(dg + i * VEC);
+    Vec16<E> o;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) o.v[k] = from_f32<E>(to_f32(b.v[k]) * gelu_grad_f(to_f32(a.v[k])));
+    store16(du + i * VEC, o);
+  }
+}
+
+// ---- column sums (bias gradients) ---------------------------------------------
+// grid = (column tiles of kBlock*VEC, row splits); each thread owns VEC columns.
+template <typename E>
+__global__ void k_colsum(const E *a, float *out, int T, int N, int rows_per_split) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  const int c = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+  if (c >= N) return;
+  const int r0 = blockIdx.y * rows_per_split, r1 = min(T, r0 + rows_per_split);
+  float acc[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) acc[k] = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    const Vec16<E> v = load16(a + uint64_t(r) * N + c);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] += to_f32(v.v[k]);
+  }
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) atomicAdd(out + c + k, acc[k]);
+}
+
+// ---- softmax cross-entropy ---------------------------------------------------
+__device__ __forceinline__ float block_reduce(float v, bool is_max, float *scratch) {
+  v = is_max ? wave_max(v) : wave_sum(v);
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  __syncthreads();
+  if (lane == 0) scratch[wave] = v;
+  __syncthreads();
+  float r = scratch[0];
+  for (int w = 1; w < kWavesPerBlock; ++w) r = is_max ? fmaxf(r, scratch[w]) : r + scratch[w];
+  return r;
+}
+
+template <typename E>
+__global__ void k_xent(const float *logits, const int32_t *targets, double *loss_acc, E *dlogits, int V, int64_t ldl,
+                       float inv_ntgt) {
+  __shared__ float scratch[kWavesPerBlock];
+  const int row = blockIdx.x;
+  const float *lr = logits + uint64_t(row) * ldl;
+  E *dr = dlogits + uint64_t(row) * ldl;
+  const int tgt = targets[row];
+  if (tgt < 0) {
+    for (int j = threadIdx.x; j < ldl; j += blockDim.x) dr[j] = from_f32<E>(0.f);
+    return;
+  }
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < V; j += blockDim.x) mx = fmaxf(mx, lr[j]);
+  mx = block_reduce(mx, true, scratch);
+  float se = 0.f;
+  for (int j = threadIdx.x; j < V; j += blockDim.x) se += expf(lr[j] - mx);
+  se = block_reduce(se, false, scratch);
+  const float lse = mx + logf(se);
+  if (threadIdx.x == 0) atomicAdd(loss_acc, double(lse - lr[tgt]) * double(inv_ntgt));
+  for (int j = threadIdx.x; j < ldl; j += blockDim.x) {
+    float g = 0.f;
+    if (j < V) g = (expf(lr[j] - lse) - (j == tgt ? 1.f : 0.f)) * inv_ntgt;
+    dr[j] = from_f32<E>(g);
+  }
+}
+
+// ---- fused Adam ---------------------------------------------------------------
+// mixed: fp32 master/m/v in, updated master/m/v + RNE-rounded compute weight out.
+// fp32:  the fp32 weight is the master (W == float, master == w_out).
+template <typename W>
+__global__ void k_adam(const float *grad, float *master, float *m, float *v, W *w_out, uint64_t n, float lr, float b1,
+                       float b2, float eps, float inv_bc1, float inv_bc2) {
+  const uint64_t stride = uint64_t(gridDim.x) * blockDim.x;
+  const uint64_t n4 = n / 4;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n4 + (n % 4 ? 1 : 0); i += stride) {
+    const uint64_t base = i * 4;
+    const int cnt = int(min<uint64_t>(4, n - base));
+    for (int k = 0; k < cnt; ++k) {
+      const uint64_t j = base + k;
+      const float g = grad[j];
+      const float mm = b1 * m[j] + (1.f - b1) * g;
+      const float vv = b2 * v[j] + (1.f - b2) * g * g;
+      const float w = master[j] - lr * (mm * inv_bc1) / (sqrtf(vv * inv_bc2) + eps);
+      m[j] = mm;
+      v[j] = vv;
+      master[j] = w;
+      if (sizeof(W) == 2) w_out[j] = from_f32<W>(w);
+    }
+  }
+}
+
+}  // namespace
+
+#define DISPATCH_PREC(prec, CALL)                                   \
+  do {                                                              \
+    if ((prec) == HMY_PREC_FP32) { typedef float E; CALL; }         \
+    else if ((prec) == HMY_PREC_BF16) { typedef bf16_t E; CALL; }   \
+    else return fail(HMY_E_INVALID, "unknown precision %d", prec);  \
+  } while (0)
+
+int launch_fill_zero(void *p, uint64_t bytes, stream_t st) {
+  if (!bytes) return HMY_OK;
+  if (bytes % 4 || (reinterpret_cast<uintptr_t>(p) & 15)) return fail(HMY_E_INVALID, "fill_zero: unaligned");
+  const uint64_t words = bytes / 4;
+  hipLaunchKernelGGL(k_fill_zero, dim3(grid_for(words / 4 + 1, kBlock, 2048)), dim3(kBlock), 0, (hipStream_t)st,
+                     (uint32_t *)p, words);
+  return check_launch("fill_zero");
+}
+int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st) {
+  if (!bytes) return HMY_OK;
+  if (bytes % 4 || (reinterpret_cast<uintptr_t>(dst) & 15) || (reinterpret_cast<uintptr_t>(src) & 15))
+    return fail(HMY_E_INVALID, "copy: unaligned");
+  const uint64_t words = bytes / 4;
+  hipLaunchKernelGGL(k_copy, dim3(grid_for(words / 4 + 1, kBlock, 2048)), dim3(kBlock), 0, (hipStream_t)st,
+                     (uint32_t *)dst, (const uint32_t *)src, words);
+  return check_launch("copy");
+}
+
+int launch_embed_fwd(int prec, const int32_t *ids, const void *wte, const void *wpe, void *x, int T, int d, int s,
+                     int vocab, stream_t st) {
+  (void)vocab;
+  if (T < 1 || d % 8 || s < 1) return fail(HMY_E_INVALID, "embed_fwd: bad shape");
+  DISPATCH_PREC(prec, {
+    const uint64_t work = uint64_t(T) * (d / ElemTraits<E>::VEC);
+    hipLaunchKernelGGL(k_embed_fwd<E>, dim3(grid_for(work, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st, ids,
+                       (const E *)wte, (const E *)wpe, (E *)x, T, d, s);
+  });
+  return check_launch("embed_fwd");
+}
+int launch_embed_bwd(int prec, const int32_t *ids, const void *dx, float *dwte, float *dwpe, int T, int d, int s,
+                     int vocab, stream_t st) {
+  (void)vocab;
+  if (T < 1 || d % 8 || s < 1 || T % s) return fail(HMY_E_INVALID, "embed_bwd: bad shape");
+  DISPATCH_PREC(prec, {
+    const uint64_t work = uint64_t(T) * (d / ElemTraits<E>::VEC);
+    hipLaunchKernelGGL(k_embed_bwd_wte<E>, dim3(grid_for(work, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st, ids,
+                       (const E *)dx, dwte, T, d);
+    const uint64_t work2 = uint64_t(s) * (d / ElemTraits<E>::VEC);
+    hipLaunchKernelGGL(k_embed_bwd_wpe<E>, dim3(grid_for(work2, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st,
+                       (const E *)dx, dwpe, T, d, s);
+  });
+  return check_launch("embed_bwd");
+}
+
+int launch_layernorm_fwd(int prec, const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd,
+                         int T, int d, float eps, stream_t st) {
+  if (T < 1 || d % 8) return fail(HMY_E_INVALID, "layernorm_fwd: bad shape");
+  DISPATCH_PREC(prec, {
+    hipLaunchKernelGGL(k_layernorm_fwd<E>, dim3(grid_for(T, kWavesPerBlock, 8192)), dim3(kBlock), 0, (hipStream_t)st,
+                       (const E *)x, (const E *)gamma, (const E *)beta, (E *)y, mean, rstd, T, d, eps);
+  });
+  return check_launch("layernorm_fwd");
+}
+int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
+                         const void *res, void *dx, float *dgamma, float *dbeta, int T, int d, stream_t st) {
+  if (T < 1 || d % 8 || d > 8192) return fail(HMY_E_INVALID, "layernorm_bwd: bad shape");
+  DISPATCH_PREC(prec, {
+    hipLaunchKernelGGL(k_layernorm_bwd<E>, dim3(grid_for(T, kWavesPerBlock, 512)), dim3(kBlock), size_t(2) * d * 4,
+                       (hipStream_t)st, (const E *)dy, (const E *)x, mean, rstd, (const E *)gamma, (const E *)res,
+                       (E *)dx, dgamma, dbeta, T, d);
+  });
+  return check_launch("layernorm_bwd");
+}
+
+int launch_gelu_fwd(int prec, const void *u, void *g, uint64_t n, stream_t st) {
+  if (n % 8) return fail(HMY_E_INVALID, "gelu: n must be a multiple of 8");
+  DISPATCH_PREC(prec, {
+    const uint64_t nvec = n / ElemTraits<E>::VEC;
+    hipLaunchKernelGGL(k_gelu_fwd<E>, dim3(grid_for(nvec, kBlock, 8192)), dim3(kBlock), 0, (hipStream_t)st,
+                       (const E *)u, (E *)g, nvec);
+  });
+  return check_launch("gelu_fwd");
+}
+int launch_gelu_bwd(int prec, const void *dg, const void *u, void *du, uint64_t n, stream_t st) {
+  if (n % 8) return fail(HMY_E_INVALID, "gelu: n must be a multiple of 8");
+  DISPATCH_PREC(prec, {
+    const uint64_t nvec = n / ElemTraits<E>::VEC;
+    hipLaunchKernelGGL(k_gelu_bwd<E>, dim3(grid_for(nvec, kBlock, 8192)), dim3(kBlock), 0, (hipStream_t)st,
+                       (const E *)dg, (const E *)u, (E *)du, nvec);
+  });
+  return check_launch("gelu_bwd");
+}
+
+int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st) {
+  if (T < 1 || N % 8) return fail(HMY_E_INVALID, "colsum: bad shape");
+  DISPATCH_PREC(prec, {
+    const int cols_per_block = kBlock * ElemTraits<E>::VEC;
+    const int gx = (N + cols_per_block - 1) / cols_per_block;
+    int splits = std::max(1, std::min(T / 32, 1024 / gx));
+    const int rows_per_split = (T + splits - 1) / splits;
+    splits = (T + rows_per_split - 1) / rows_per_split;
+    hipLaunchKernelGGL(k_colsum<E>, dim3(gx, splits), dim3(kBlock), 0, (hipStream_t)st, (const E *)a, out, T, N,
+                       rows_per_split);
+  });
+  return check_launch("colsum");
+}
+
+int launch_xent(int prec, const float *logits, const int32_t *targets, double *loss_acc, void *dlogits, int T, int V,
+                int64_t ldl, float inv_ntgt, stream_t st) {
+  if (T < 1 || V < 2 || ldl < V) return fail(HMY_E_INVALID, "xent: bad shape");
+  DISPATCH_PREC(prec, {
+    hipLaunchKernelGGL(k_xent<E>, dim3(T), dim3(kBlock), 0, (hipStream_t)st, logits, targets, loss_acc, (E *)dlogits, V,
+                       ldl, inv_ntgt);
+  });
+  return check_launch("xent");
+}
+
+int launch_adam(int prec, const float *grad, float *master, float *m, float *v, void *w_out, uint64_t n,
+                const hmy_adam &hp, stream_t st) {
+  if (!n) return HMY_OK;
+  if (hp.step < 1) return fail(HMY_E_INVALID, "adam: step is 1-based");
+  const float inv_bc1 = float(1.0 / (1.0 - std::pow(double(hp.beta1), double(hp.step))));
+  const float inv_bc2 = float(1.0 / (1.0 - std::pow(double(hp.beta2), double(hp.step))));
+  const int grid = grid_for(n / 4 + 1, kBlock, 4096);
+  if (prec == HMY_PREC_BF16) {
+    if (!master) return fail(HMY_E_INVALID, "adam(bf16): master required");
+    hipLaunchKernelGGL(k_adam<bf16_t>, dim3(grid), dim3(kBlock), 0, (hipStream_t)st, grad, master, m, v,
+                       (bf16_t *)w_out, n, hp.lr, hp.beta1, hp.beta2, hp.eps, inv_bc1, inv_bc2);
+  } else if (prec == HMY_PREC_FP32) {
+    if (master) return fail(HMY_E_INVALID, "adam(fp32): master must be NULL");
+    hipLaunchKernelGGL(k_adam<float>, dim3(grid), dim3(kBlock), 0, (hipStream_t)st, grad, (float *)w_out, m, v,
+                       (float *)w_out, n, hp.lr, hp.beta1, hp.beta2, hp.eps, inv_bc1, inv_bc2);
+  } else {
+    return fail(HMY_E_INVALID, "unknown precision %d", prec);
+  }
+  return check_launch("adam");
+}
+
+}  // namespace hmy

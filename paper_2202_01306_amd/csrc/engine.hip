@@ -1,0 +1,746 @@
+// Swap engine + iteration executor: the layer-pack-major training iteration of
+// the Harmony paper (Section 3; task order of Algorithm 3 at N = 1) on one GPU.
+//
+// Streams (the paper's Runtime uses compute / swap-in / swap-out streams plus
+// events, Section 4.4; p2p streams have no role on one GPU):
+//   s_comp  every layer kernel
+//   s_in    token ids, weight packs (prefetched one visit ahead, in n_micro pieces
+//           interleaved with the microbatch loop) and checkpoints coming back
+//   s_upd   optimizer state coming in, chunk by chunk, and the fused Adam kernel
+//   s_out   everything going to the host: checkpoints, updated state, gradients
+// All ordering is by events; the host thread only enqueues and finally waits.
+//
+// A "visit" is one task of the ordered list: forward packs in order, then
+// backward packs in reverse, each followed by its update (jit-update).  The
+// first backward visit is the last pack, run forward+backward per microbatch
+// (jit-compute).  Visit v uses weight slot v % 2.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+
+#include "hmy_internal.h"
+
+namespace hmy {
+const char *last_error();
+}
+using namespace hmy;
+
+struct Visit {
+  bool bwd;
+  bool last;    // the shared last pack (forward + backward, no recompute)
+  Pack pack;
+  int slot;
+  uint64_t poff;     // element offset of the pack's first parameter
+  uint64_t nparams;
+};
+
+struct hmy_handle {
+  Model model;
+  Packs packs;
+  Arena arena;
+  int M = 0, b = 0;
+  int device = -1;
+  bool dry = false;
+  char *base = nullptr;
+  bool own_arena = false;
+  hipStream_t s_comp = nullptr, s_in = nullptr, s_upd = nullptr, s_out = nullptr;
+  hmy_host_state host{};
+  bool bound = false;
+  char *stash_host = nullptr;   // pinned: checkpoints [n_ckpt][M][x_bytes]
+  std::vector<int> ckpt_layers; // first layers of backward packs 1..n_B-2
+  std::vector<Visit> visits;
+  BlockActs bacts;
+  HeadActs hacts;
+
+  // per-iteration bookkeeping
+  std::vector<hipEvent_t> sync_events;
+  size_t sync_used = 0;
+  std::vector<hipEvent_t> time_events;
+  size_t time_used = 0;
+  struct Span { size_t a, b; int what; };  // what: 0 h2d, 1 d2h, 2 stall, 3 compute
+  std::vector<Span> spans;
+  hmy_stats st{};
+  int err = HMY_OK;
+  bool timing = true;
+};
+
+#define HIPCHK(h, call)                                                                      \
+  do {                                                                                       \
+    if ((h)->err == HMY_OK) {                                                                \
+      hipError_t e_ = (call);                                                                \
+      if (e_ != hipSuccess)                                                                  \
+        (h)->err = fail(HMY_E_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+    }                                                                                        \
+  } while (0)
+
+namespace {
+
+// ---- events -----------------------------------------------------------------
+hipEvent_t rec(hmy_handle *h, hipStream_t s) {
+  if (h->dry || h->err) return nullptr;
+  if (h->sync_used == h->sync_events.size()) {
+    hipEvent_t e = nullptr;
+    HIPCHK(h, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    if (h->err) return nullptr;
+    h->sync_events.push_back(e);
+  }
+  hipEvent_t e = h->sync_events[h->sync_used++];
+  HIPCHK(h, hipEventRecord(e, s));
+  return e;
+}
+void wait(hmy_handle *h, hipStream_t s, hipEvent_t e) {
+  if (h->dry || h->err || !e) return;
+  HIPCHK(h, hipStreamWaitEvent(s, e, 0));
+}
+size_t trec(hmy_handle *h, hipStream_t s) {
+  if (h->dry || h->err || !h->timing) return size_t(-1);
+  if (h->time_used == h->time_events.size()) {
+    hipEvent_t e = nullptr;
+    HIPCHK(h, hipEventCreate(&e));
+    if (h->err) return size_t(-1);
+    h->time_events.push_back(e);
+  }
+  size_t i = h->time_used++;
+  HIPCHK(h, hipEventRecord(h->time_events[i], s));
+  return i;
+}
+void span(hmy_handle *h, size_t a, size_t b, int what) {
+  if (a != size_t(-1) && b != size_t(-1)) h->spans.push_back({a, b, what});
+}
+// wait on a swap event from the compute stream, measuring the stall
+void comp_wait(hmy_handle *h, hipEvent_t e) {
+  if (h->dry || h->err || !e) return;
+  size_t a = trec(h, h->s_comp);
+  wait(h, h->s_comp, e);
+  size_t b = trec(h, h->s_comp);
+  span(h, a, b, 2);
+}
+
+// ---- copies (bytes are counted when enqueued) ---------------------------------
+void h2d(hmy_handle *h, int kind, void *dst, const void *src, uint64_t bytes, hipStream_t s) {
+  if (!bytes) return;
+  h->st.h2d[kind] += bytes;
+  if (h->dry || h->err) return;
+  size_t a = trec(h, s);
+  HIPCHK(h, hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, s));
+  size_t b = trec(h, s);
+  span(h, a, b, 0);
+}
+void d2h(hmy_handle *h, int kind, void *dst, const void *src, uint64_t bytes, hipStream_t s) {
+  if (!bytes) return;
+  h->st.d2h[kind] += bytes;
+  if (h->dry || h->err) return;
+  size_t a = trec(h, s);
+  HIPCHK(h, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, s));
+  size_t b = trec(h, s);
+  span(h, a, b, 1);
+}
+
+#define KCHK(h, call)                          \
+  do {                                         \
+    if (!(h)->dry && (h)->err == HMY_OK) {     \
+      int rc_ = (call);                        \
+      if (rc_ != HMY_OK) (h)->err = rc_;       \
+    }                                          \
+  } while (0)
+
+// ---- addressing -----------------------------------------------------------------
+struct PackPtrs {
+  char *W;    // compute-precision weights of the pack
+  float *dW;  // fp32 gradient accumulators (backward visits)
+};
+PackPtrs pack_ptrs(const hmy_handle *h, const Visit &v) {
+  PackPtrs p;
+  p.W = h->base + h->arena.slot_off[v.slot];
+  p.dW = reinterpret_cast<float *>(p.W + a256(uint64_t(h->model.elem_bytes()) * v.nparams));
+  return p;
+}
+const char *wptr(const hmy_handle *h, const Visit &v, const PackPtrs &p, int tensor) {
+  return p.W + (h->model.tensors[tensor].offset - v.poff) * h->model.elem_bytes();
+}
+float *gptr(const hmy_handle *h, const Visit &v, const PackPtrs &p, int tensor) {
+  return p.dW + (h->model.tensors[tensor].offset - v.poff);
+}
+char *Xbuf(const hmy_handle *h, int mb) { return h->base + h->arena.res.X + uint64_t(mb) * h->arena.res.x_bytes; }
+char *inring(const hmy_handle *h, int r) { return h->base + h->arena.res.inring + uint64_t(r) * h->arena.res.x_bytes; }
+char *outring(const hmy_handle *h, int r) { return h->base + h->arena.res.outring + uint64_t(r) * h->arena.res.x_bytes; }
+const int32_t *ids_dev(const hmy_handle *h, int mb) {
+  return reinterpret_cast<const int32_t *>(h->base + h->arena.res.ids) + uint64_t(mb) * h->b * h->model.spec.seq_len;
+}
+const int32_t *tgt_dev(const hmy_handle *h, int mb) {
+  return reinterpret_cast<const int32_t *>(h->base + h->arena.res.targets) + uint64_t(mb) * h->b * h->model.spec.seq_len;
+}
+// activation region of `layer` inside the workspace of the pack being run
+char *act_region(const hmy_handle *h, const Pack &pk, int layer) {
+  uint64_t off = 0;
+  for (int l = pk.a; l < layer; ++l) {
+    if (l == 0) continue;
+    off += (l <= h->model.spec.n_blocks) ? h->bacts.size : h->hacts.size;
+  }
+  return h->base + h->arena.act_off + off;
+}
+
+hmy_gemm_desc gemm_desc(int prec, int M, int N, int K) {
+  hmy_gemm_desc g;
+  std::memset(&g, 0, sizeof(g));
+  g.prec = prec;
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  return g;
+}
+// C[M,N] = A[M,K] W[N,K]^T + bias (+ res)
+void linear_fwd(hmy_handle *h, const void *A, const void *W, const void *bias, const void *res, void *C,
+                void *gelu_out, int M, int N, int K) {
+  hmy_gemm_desc g = gemm_desc(h->model.spec.precision, M, N, K);
+  g.A = A; g.lda = K;
+  g.B = W; g.ldb = K; g.tb = 0;
+  g.C = C; g.ldc = N;
+  g.bias = bias;
+  g.res = res; g.ldr = N;
+  g.gelu_out = gelu_out;
+  KCHK(h, launch_gemm(g, h->s_comp));
+}
+// dX[M,K] = dY[M,N] W[N,K];  dW[N,K] += dY^T X;  db[N] += colsum(dY)
+void linear_bwd(hmy_handle *h, const void *dY, const void *X, const void *W, void *dX, float *dW, float *db,
+                int M, int N, int K) {
+  const int prec = h->model.spec.precision;
+  if (dX) {
+    hmy_gemm_desc g = gemm_desc(prec, M, K, N);
+    g.A = dY; g.lda = N;
+    g.B = W; g.ldb = K; g.tb = 1;
+    g.C = dX; g.ldc = K;
+    KCHK(h, launch_gemm(g, h->s_comp));
+  }
+  {
+    hmy_gemm_desc g = gemm_desc(prec, N, K, M);
+    g.A = dY; g.lda = N; g.ta = 1;
+    g.B = X; g.ldb = K; g.tb = 1;
+    g.C = dW; g.ldc = K; g.c_fp32 = 1; g.accumulate = 1;
+    KCHK(h, launch_gemm(g, h->s_comp));
+  }
+  if (db) KCHK(h, launch_colsum(prec, dY, db, M, N, h->s_comp));
+}
+
+struct BlockPtrs {
+  char *x_in, *a, *qkv, *o, *x_mid, *hh, *u, *g;
+  float *ln1_mean, *ln1_rstd, *ln2_mean, *ln2_rstd, *lse;
+};
+BlockPtrs block_ptrs(const hmy_handle *h, char *region) {
+  const BlockActs &b = h->bacts;
+  BlockPtrs p;
+  p.x_in = region + b.x_in; p.a = region + b.a; p.qkv = region + b.qkv; p.o = region + b.o;
+  p.x_mid = region + b.x_mid; p.hh = region + b.h; p.u = region + b.u; p.g = region + b.g;
+  p.ln1_mean = (float *)(region + b.ln1_mean); p.ln1_rstd = (float *)(region + b.ln1_rstd);
+  p.ln2_mean = (float *)(region + b.ln2_mean); p.ln2_rstd = (float *)(region + b.ln2_rstd);
+  p.lse = (float *)(region + b.lse);
+  return p;
+}
+
+// Forward of one block.  x_in -> x_mid -> y; in the forward pass all three are
+// the resident boundary buffer (in place); in a backward visit they are distinct
+// saved buffers and y == nullptr skips the second MLP GEMM (output not needed).
+void block_forward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, const BlockPtrs &A,
+                   const char *x_in, char *x_mid, char *y) {
+  const hmy_model_spec &s = h->model.spec;
+  const int prec = s.precision, T = h->b * s.seq_len, d = s.d_model, f = s.d_ffn;
+  const int t0 = h->model.first_tensor[layer];
+  auto W = [&](int i) { return wptr(h, v, pp, t0 + i); };
+  KCHK(h, launch_layernorm_fwd(prec, x_in, W(LN1_G), W(LN1_B), A.a, A.ln1_mean, A.ln1_rstd, T, d, s.ln_eps, h->s_comp));
+  linear_fwd(h, A.a, W(WQKV), W(BQKV), nullptr, A.qkv, nullptr, T, 3 * d, d);
+  KCHK(h, launch_attn_fwd(prec, A.qkv, A.o, A.lse, h->b, s.seq_len, s.n_heads, d / s.n_heads, s.causal, h->s_comp));
+  linear_fwd(h, A.o, W(WO), W(BO), x_in, x_mid, nullptr, T, d, d);
+  KCHK(h, launch_layernorm_fwd(prec, x_mid, W(LN2_G), W(LN2_B), A.hh, A.ln2_mean, A.ln2_rstd, T, d, s.ln_eps, h->s_comp));
+  linear_fwd(h, A.hh, W(W1), W(B1), nullptr, A.u, A.g, T, f, d);
+  if (y) linear_fwd(h, A.g, W(W2), W(B2), x_mid, y, nullptr, T, d, f);
+}
+
+// Backward of one block; D holds dL/dy on entry and dL/dx_in on exit (in place).
+void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, const BlockPtrs &A,
+                    const char *x_in, char *D) {
+  const hmy_model_spec &s = h->model.spec;
+  const int prec = s.precision, T = h->b * s.seq_len, d = s.d_model, f = s.d_ffn;
+  const int t0 = h->model.first_tensor[layer];
+  auto W = [&](int i) { return wptr(h, v, pp, t0 + i); };
+  auto G = [&](int i) { return gptr(h, v, pp, t0 + i); };
+  char *gbig = h->base + h->arena.res.gbig;
+  char *gsmall = h->base + h->arena.res.gsmall;
+  float *delta = (float *)(h->base + h->arena.res.delta);
+  // y = x_mid + W2 gelu(W1 LN2(x_mid) + b1) + b2
+  linear_bwd(h, D, A.g, W(W2), gbig, G(W2), G(B2), T, d, f);                     // dg
+  KCHK(h, launch_gelu_bwd(prec, gbig, A.u, gbig, uint64_t(T) * f, h->s_comp));   // du
+  linear_bwd(h, gbig, A.hh, W(W1), gsmall, G(W1), G(B1), T, f, d);               // dh
+  KCHK(h, launch_layernorm_bwd(prec, gsmall, A.x_mid, A.ln2_mean, A.ln2_rstd, W(LN2_G), D, D, G(LN2_G), G(LN2_B), T, d,
+                               h->s_comp));                                        // D = dx_mid
+  // x_mid = x_in + Wo attn(Wqkv LN1(x_in) + bqkv) + bo
+  linear_bwd(h, D, A.o, W(WO), gsmall, G(WO), G(BO), T, d, d);                   // do
+  KCHK(h, launch_attn_bwd(prec, A.qkv, A.o, gsmall, A.lse, delta, gbig, h->b, s.seq_len, s.n_heads, d / s.n_heads,
+                          s.causal, h->s_comp));                                   // dqkv
+  linear_bwd(h, gbig, A.a, W(WQKV), gsmall, G(WQKV), G(BQKV), T, 3 * d, d);      // da
+  KCHK(h, launch_layernorm_bwd(prec, gsmall, x_in, A.ln1_mean, A.ln1_rstd, W(LN1_G), D, D, G(LN1_G), G(LN1_B), T, d,
+                               h->s_comp));                                        // D = dx_in
+}
+
+// Final norm, vocabulary projection, loss and their backward, chunked over rows
+// so the [rows, vocab] logits never exceed one chunk.  Writes dL/dx into D.
+void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, char *region,
+                           const char *x_in, int mb, char *D, float inv_ntgt) {
+  const hmy_model_spec &s = h->model.spec;
+  const int prec = s.precision, T = h->b * s.seq_len, d = s.d_model, V = s.vocab, E = h->model.elem_bytes();
+  const HeadActs &ha = h->hacts;
+  const int t0 = h->model.first_tensor[layer];
+  const char *lnf_g = wptr(h, v, pp, t0 + 0), *lnf_b = wptr(h, v, pp, t0 + 1), *wh = wptr(h, v, pp, t0 + 2);
+  float *g_lnf_g = gptr(h, v, pp, t0 + 0), *g_lnf_b = gptr(h, v, pp, t0 + 1), *g_wh = gptr(h, v, pp, t0 + 2);
+  char *z = region + ha.z;
+  float *mean = (float *)(region + ha.mean), *rstd = (float *)(region + ha.rstd);
+  float *logits = (float *)(region + ha.logits);
+  char *dlogits = region + ha.dlogits;
+  char *dz = h->base + h->arena.res.gsmall;
+  double *loss_acc = (double *)(h->base + h->arena.res.misc);
+  KCHK(h, launch_layernorm_fwd(prec, x_in, lnf_g, lnf_b, z, mean, rstd, T, d, s.ln_eps, h->s_comp));
+  for (int r0 = 0; r0 < T; r0 += ha.chunk_rows) {
+    const int rows = std::min(ha.chunk_rows, T - r0);
+    const char *zc = z + uint64_t(r0) * d * E;
+    {  // logits = z Wh^T (fp32)
+      hmy_gemm_desc g = gemm_desc(prec, rows, V, d);
+      g.A = zc; g.lda = d;
+      g.B = wh; g.ldb = d;
+      g.C = logits; g.ldc = ha.ldl; g.c_fp32 = 1;
+      KCHK(h, launch_gemm(g, h->s_comp));
+    }
+    KCHK(h, launch_xent(prec, logits, tgt_dev(h, mb) + r0, loss_acc, dlogits, rows, V, ha.ldl, inv_ntgt, h->s_comp));
+    {  // dz = dlogits Wh
+      hmy_gemm_desc g = gemm_desc(prec, rows, d, V);
+      g.A = dlogits; g.lda = ha.ldl;
+      g.B = wh; g.ldb = d; g.tb = 1;
+      g.C = dz + uint64_t(r0) * d * E; g.ldc = d;
+      KCHK(h, launch_gemm(g, h->s_comp));
+    }
+    {  // dWh += dlogits^T z
+      hmy_gemm_desc g = gemm_desc(prec, V, d, rows);
+      g.A = dlogits; g.lda = ha.ldl; g.ta = 1;
+      g.B = zc; g.ldb = d; g.tb = 1;
+      g.C = g_wh; g.ldc = d; g.c_fp32 = 1; g.accumulate = 1;
+      KCHK(h, launch_gemm(g, h->s_comp));
+    }
+  }
+  KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, g_lnf_g, g_lnf_b, T, d, h->s_comp));
+}
+
+struct IterState {
+  hipEvent_t slot_free[2] = {nullptr, nullptr};
+  hipEvent_t in_free[kInRing] = {};
+  hipEvent_t in_ready[kInRing] = {};
+  hipEvent_t out_free[kOutRing] = {};
+  hipEvent_t k_free[kKRing] = {};
+  hipEvent_t stash_all_out = nullptr;
+  bool stash_waited = false;
+  int out_count = 0;
+  int k_count = 0;
+  float inv_ntgt = 0.f;
+};
+
+int ckpt_index(const hmy_handle *h, int layer) {
+  for (size_t i = 0; i < h->ckpt_layers.size(); ++i)
+    if (h->ckpt_layers[i] == layer) return int(i);
+  return -1;
+}
+char *stash_slot(const hmy_handle *h, int ck, int mb) {
+  return h->stash_host + (uint64_t(ck) * h->M + mb) * h->arena.res.x_bytes;
+}
+
+void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int mb) {
+  const hmy_model_spec &s = h->model.spec;
+  const int T = h->b * s.seq_len, d = s.d_model;
+  const uint64_t xb = uint64_t(T) * d * h->model.elem_bytes();
+  const PackPtrs pp = pack_ptrs(h, v);
+  char *X = Xbuf(h, mb);
+  const BlockPtrs scratch = block_ptrs(h, h->base + h->arena.act_off);
+  for (int layer = v.pack.a; layer < v.pack.e; ++layer) {
+    const int ck = ckpt_index(h, layer);
+    if (ck >= 0) {  // this layer's input is a backward pack's checkpoint: send it to the host
+      const int q = it.out_count++ % kOutRing;
+      comp_wait(h, it.out_free[q]);
+      KCHK(h, launch_copy(outring(h, q), X, xb, h->s_comp));
+      hipEvent_t e = rec(h, h->s_comp);
+      wait(h, h->s_out, e);
+      d2h(h, HMY_KIND_SX, stash_slot(h, ck, mb), outring(h, q), xb, h->s_out);
+      it.out_free[q] = rec(h, h->s_out);
+    }
+    if (layer == 0) {
+      const int t0 = h->model.first_tensor[0];
+      KCHK(h, launch_embed_fwd(s.precision, ids_dev(h, mb), wptr(h, v, pp, t0), wptr(h, v, pp, t0 + 1), X, T, d,
+                               s.seq_len, s.vocab, h->s_comp));
+    } else {
+      block_forward(h, v, pp, layer, scratch, X, X, X);
+    }
+  }
+}
+
+// enqueue whatever brings the input of backward visit v, microbatch mb, into inring[mb % 2]
+void issue_pack_input(hmy_handle *h, IterState &it, const Visit &v, int mb) {
+  const int r = mb % kInRing;
+  const uint64_t xb = uint64_t(h->b) * h->model.spec.seq_len * h->model.spec.d_model * h->model.elem_bytes();
+  it.in_ready[r] = nullptr;
+  if (v.pack.a == 0) return;  // starts at the embedding: restarts from the token ids
+  if (v.last) {               // still resident from the forward pass
+    KCHK(h, launch_copy(inring(h, r), Xbuf(h, mb), xb, h->s_comp));
+    return;
+  }
+  const int ck = ckpt_index(h, v.pack.a);
+  if (!it.stash_waited) {
+    wait(h, h->s_in, it.stash_all_out);
+    it.stash_waited = true;
+  }
+  wait(h, h->s_in, it.in_free[r]);
+  h2d(h, HMY_KIND_SX, inring(h, r), stash_slot(h, ck, mb), xb, h->s_in);
+  it.in_ready[r] = rec(h, h->s_in);
+}
+
+void backward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int mb) {
+  const hmy_model_spec &s = h->model.spec;
+  const int T = h->b * s.seq_len, d = s.d_model, L = s.n_blocks;
+  const PackPtrs pp = pack_ptrs(h, v);
+  const int r = mb % kInRing;
+  char *D = Xbuf(h, mb);
+  comp_wait(h, it.in_ready[r]);
+  // where each layer of the pack reads its input
+  auto input_of = [&](int layer) -> char * {
+    if (layer == v.pack.a) return inring(h, r);
+    char *reg = act_region(h, v.pack, layer);
+    return layer <= L ? reg + h->bacts.x_in : reg + h->hacts.x_in;
+  };
+  // (re)compute the pack's forward, keeping what backward needs
+  for (int layer = v.pack.a; layer < v.pack.e; ++layer) {
+    const bool has_next = layer + 1 < v.pack.e;
+    if (layer == 0) {
+      if (!has_next) continue;  // embedding alone: its backward needs only ids and dY
+      const int t0 = h->model.first_tensor[0];
+      KCHK(h, launch_embed_fwd(s.precision, ids_dev(h, mb), wptr(h, v, pp, t0), wptr(h, v, pp, t0 + 1), input_of(1), T,
+                               d, s.seq_len, s.vocab, h->s_comp));
+    } else if (layer <= L) {
+      const BlockPtrs A = block_ptrs(h, act_region(h, v.pack, layer));
+      block_forward(h, v, pp, layer, A, input_of(layer), A.x_mid, has_next ? input_of(layer + 1) : nullptr);
+    } else {
+      head_forward_backward(h, v, pp, layer, act_region(h, v.pack, layer), input_of(layer), mb, D, it.inv_ntgt);
+    }
+  }
+  // backward in reverse (the head's backward already ran, fused with its forward)
+  for (int layer = std::min(v.pack.e - 1, L); layer >= v.pack.a; --layer) {
+    if (layer == 0) {
+      const int t0 = h->model.first_tensor[0];
+      KCHK(h, launch_embed_bwd(s.precision, ids_dev(h, mb), D, gptr(h, v, pp, t0), gptr(h, v, pp, t0 + 1), T, d,
+                               s.seq_len, s.vocab, h->s_comp));
+    } else {
+      const BlockPtrs A = block_ptrs(h, act_region(h, v.pack, layer));
+      block_backward(h, v, pp, layer, A, input_of(layer), D);
+    }
+  }
+  it.in_free[r] = rec(h, h->s_comp);
+}
+
+// jit-update of the visit's pack: optimizer state streams through the ring
+// (in on s_upd, Adam on s_upd, out on s_out) while the next pack computes.
+void update_visit(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_done, const hmy_adam &hp) {
+  const Reserved &R = h->arena.res;
+  const int E = h->model.elem_bytes();
+  const bool mixed = h->model.spec.precision == HMY_PREC_BF16;
+  const PackPtrs pp = pack_ptrs(h, v);
+  for (uint64_t lo = 0, c = 0; lo < v.nparams; lo += R.k_chunk_params, ++c) {
+    const uint64_t n = std::min<uint64_t>(R.k_chunk_params, v.nparams - lo);
+    const int r = it.k_count++ % kKRing;
+    char *ring = h->base + R.kring + uint64_t(r) * h->model.k_arrays() * R.karr_bytes;
+    float *r_master = mixed ? (float *)ring : nullptr;
+    float *r_m = (float *)(ring + (mixed ? 1 : 0) * R.karr_bytes);
+    float *r_v = (float *)(ring + (mixed ? 2 : 1) * R.karr_bytes);
+    const uint64_t g0 = v.poff + lo;  // element offset in the host arrays
+    wait(h, h->s_upd, it.k_free[r]);
+    if (mixed) h2d(h, HMY_KIND_K, r_master, h->dry ? nullptr : h->host.master + g0, n * 4, h->s_upd);
+    h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_upd);
+    h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_upd);
+    if (c == 0) wait(h, h->s_upd, bwd_done);
+    KCHK(h, launch_adam(h->model.spec.precision, pp.dW + lo, r_master, r_m, r_v, pp.W + lo * E, n, hp, h->s_upd));
+    hipEvent_t e = rec(h, h->s_upd);
+    wait(h, h->s_out, e);
+    if (mixed) d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.master + g0, r_master, n * 4, h->s_out);
+    d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.adam_m + g0, r_m, n * 4, h->s_out);
+    d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.adam_v + g0, r_v, n * 4, h->s_out);
+    d2h(h, HMY_KIND_W, h->dry ? nullptr : (char *)h->host.weights + g0 * E, pp.W + lo * E, n * E, h->s_out);
+    d2h(h, HMY_KIND_DW, h->dry ? nullptr : h->host.grads + g0, pp.dW + lo, n * 4, h->s_out);
+    it.k_free[r] = rec(h, h->s_out);
+  }
+}
+
+void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
+  const hmy_model_spec &s = h->model.spec;
+  const int M = h->M, E = h->model.elem_bytes();
+  const uint64_t T = uint64_t(h->b) * s.seq_len;
+  IterState it;
+  std::memset(&h->st, 0, sizeof(h->st));
+  h->sync_used = h->time_used = 0;
+  h->spans.clear();
+
+  if (!h->dry) {
+    uint64_t nt = 0;
+    for (uint64_t i = 0; i < uint64_t(M) * T; ++i) nt += mb->targets[i] >= 0;
+    h->st.n_targets = nt;
+    it.inv_ntgt = nt ? float(1.0 / double(nt)) : 0.f;
+  }
+  h2d(h, HMY_KIND_IDS, h->base + h->arena.res.ids, h->dry ? nullptr : mb->token_ids, uint64_t(M) * T * 4, h->s_in);
+  h2d(h, HMY_KIND_IDS, h->base + h->arena.res.targets, h->dry ? nullptr : mb->targets, uint64_t(M) * T * 4, h->s_in);
+  hipEvent_t ev_ids = rec(h, h->s_in);
+  KCHK(h, launch_fill_zero(h->base + h->arena.res.misc, 4096, h->s_comp));
+  const size_t t_first = trec(h, h->s_comp);
+
+  // weight prefetch of a visit in M pieces
+  auto w_piece = [&](const Visit &v, int piece) {
+    const uint64_t total = uint64_t(E) * v.nparams;
+    const uint64_t chunk = a256((total + M - 1) / M);
+    const uint64_t lo = std::min(total, chunk * piece), hi = std::min(total, chunk * (piece + 1));
+    if (piece == 0) wait(h, h->s_in, it.slot_free[v.slot]);
+    if (hi > lo) {
+      char *dst = h->base + h->arena.slot_off[v.slot] + lo;
+      const char *src = h->dry ? nullptr : (const char *)h->host.weights + v.poff * E + lo;
+      h2d(h, HMY_KIND_W, dst, src, hi - lo, h->s_in);
+    }
+  };
+
+  const int nv = int(h->visits.size());
+  for (int p = 0; p < M; ++p) w_piece(h->visits[0], p);
+  hipEvent_t ev_w = rec(h, h->s_in);
+  for (int vi = 0; vi < nv; ++vi) {
+    const Visit &v = h->visits[vi];
+    const Visit *next = vi + 1 < nv ? &h->visits[vi + 1] : nullptr;
+    comp_wait(h, ev_w);
+    if (vi == 0) comp_wait(h, ev_ids);
+    if (v.bwd) {
+      if (!it.stash_all_out) it.stash_all_out = rec(h, h->s_out);  // every checkpoint has been queued out
+      const PackPtrs pp = pack_ptrs(h, v);
+      KCHK(h, launch_fill_zero(pp.dW, v.nparams * 4, h->s_comp));
+    }
+    for (int m = 0; m < M; ++m) {
+      if (v.bwd) {
+        if (m == 0) issue_pack_input(h, it, v, 0);
+        if (m + 1 < M && !v.last && v.pack.a != 0) issue_pack_input(h, it, v, m + 1);
+      }
+      if (next) w_piece(*next, m);
+      if (v.bwd) {
+        if (m > 0 && (v.last || v.pack.a == 0)) issue_pack_input(h, it, v, m);
+        backward_visit_microbatch(h, it, v, m);
+      } else {
+        forward_visit_microbatch(h, it, v, m);
+      }
+    }
+    if (next) ev_w = rec(h, h->s_in);
+    if (!v.bwd) {
+      it.slot_free[v.slot] = rec(h, h->s_comp);
+    } else {
+      hipEvent_t bwd_done = rec(h, h->s_comp);
+      update_visit(h, it, v, bwd_done, hp);
+      it.slot_free[v.slot] = rec(h, h->s_out);
+    }
+  }
+  const size_t t_last = trec(h, h->s_comp);
+  span(h, t_first, t_last, 3);
+}
+
+}  // namespace
+
+// ---- handle construction ---------------------------------------------------------
+static int init_handle(hmy_handle *h, const hmy_model_spec *spec, const hmy_schedule *sched, const hmy_budget *budget,
+                       int n_micro, int micro_batch) {
+  int rc = build_model(spec, &h->model);
+  if (rc) return rc;
+  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
+  h->M = n_micro;
+  h->b = micro_batch;
+  if (sched) {
+    rc = schedule_to_packs(h->model, sched, &h->packs);
+  } else {
+    if (!budget) return fail(HMY_E_INVALID, "neither schedule nor budget given");
+    rc = plan_packs(h->model, budget->hbm_budget_bytes, n_micro, micro_batch, &h->packs);
+  }
+  if (rc) return rc;
+  h->arena = arena_layout(h->model, h->packs, n_micro, micro_batch);
+  // forward packs must fit a weight slot
+  for (const Pack &q : h->packs.fwd)
+    if (pack_state_fwd(h->model, q) > h->arena.slot_bytes) return fail(HMY_E_BAD_SCHEDULE, "forward pack over slot");
+  if (budget && h->arena.total > budget->hbm_budget_bytes)
+    return fail(sched ? HMY_E_BAD_SCHEDULE : HMY_E_BUDGET_TOO_SMALL, "schedule needs %llu B of HBM, budget is %llu B",
+                (unsigned long long)h->arena.total, (unsigned long long)budget->hbm_budget_bytes);
+  h->bacts = block_acts(h->model.spec, micro_batch);
+  h->hacts = head_acts(h->model.spec, micro_batch);
+  h->ckpt_layers.clear();
+  for (size_t k = 1; k + 1 < h->packs.bwd.size(); ++k) h->ckpt_layers.push_back(h->packs.bwd[k].a);
+  h->visits.clear();
+  auto mk = [&](bool bwd, bool last, Pack p) {
+    Visit v;
+    v.bwd = bwd;
+    v.last = last;
+    v.pack = p;
+    v.slot = int(h->visits.size() % 2);
+    v.poff = h->model.layer_off[p.a];
+    v.nparams = h->model.params_in(p.a, p.e);
+    h->visits.push_back(v);
+  };
+  for (const Pack &q : h->packs.fwd) mk(false, false, q);
+  for (int k = int(h->packs.bwd.size()) - 1; k >= 0; --k) mk(true, k == int(h->packs.bwd.size()) - 1, h->packs.bwd[k]);
+  return HMY_OK;
+}
+
+extern "C" {
+
+int hmy_count_swaps(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro, int32_t micro_batch,
+                    hmy_stats *out) {
+  if (!spec || !sched || !out) return fail(HMY_E_INVALID, "null argument");
+  hmy_handle h;
+  h.dry = true;
+  int rc = init_handle(&h, spec, sched, nullptr, n_micro, micro_batch);
+  if (rc) return rc;
+  hmy_adam hp{};
+  run_iteration(&h, nullptr, hp);
+  *out = h.st;
+  return h.err;
+}
+
+int hmy_host_alloc(uint64_t bytes, void **out) {
+  if (!out) return fail(HMY_E_INVALID, "null out");
+  *out = nullptr;
+  hipError_t e = hipHostMalloc(out, bytes ? bytes : 1, hipHostMallocDefault);
+  if (e != hipSuccess) return fail(HMY_E_HIP, "hipHostMalloc(%llu): %s", (unsigned long long)bytes, hipGetErrorString(e));
+  return HMY_OK;
+}
+int hmy_host_free(void *p) {
+  if (!p) return HMY_OK;
+  hipError_t e = hipHostFree(p);
+  if (e != hipSuccess) return fail(HMY_E_HIP, "hipHostFree: %s", hipGetErrorString(e));
+  return HMY_OK;
+}
+
+int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_micro, int32_t micro_batch,
+               const hmy_schedule *sched, int32_t hip_device, void *arena, uint64_t arena_bytes, hmy_handle **out) {
+  if (!spec || !budget || !out) return fail(HMY_E_INVALID, "null argument");
+  *out = nullptr;
+  hmy_handle *h = new hmy_handle();
+  int rc = init_handle(h, spec, sched, budget, n_micro, micro_batch);
+  if (rc) { delete h; return rc; }
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1 || hip_device < 0 || hip_device >= ndev) {
+    delete h;
+    return fail(HMY_E_NO_DEVICE, "no usable HIP device %d (found %d)", hip_device, ndev);
+  }
+  h->device = hip_device;
+  HIPCHK(h, hipSetDevice(hip_device));
+  if (arena) {
+    if (arena_bytes < h->arena.total || (reinterpret_cast<uintptr_t>(arena) & 255)) {
+      delete h;
+      return fail(HMY_E_INVALID, "arena too small (%llu < %llu) or not 256-byte aligned", (unsigned long long)arena_bytes,
+                  (unsigned long long)h->arena.total);
+    }
+    h->base = static_cast<char *>(arena);
+  } else {
+    HIPCHK(h, hipMalloc(reinterpret_cast<void **>(&h->base), h->arena.total));
+    h->own_arena = true;
+  }
+  HIPCHK(h, hipStreamCreateWithFlags(&h->s_comp, hipStreamNonBlocking));
+  HIPCHK(h, hipStreamCreateWithFlags(&h->s_in, hipStreamNonBlocking));
+  HIPCHK(h, hipStreamCreateWithFlags(&h->s_upd, hipStreamNonBlocking));
+  HIPCHK(h, hipStreamCreateWithFlags(&h->s_out, hipStreamNonBlocking));
+  const uint64_t stash_bytes = uint64_t(h->ckpt_layers.size()) * h->M * h->arena.res.x_bytes;
+  if (stash_bytes) HIPCHK(h, hipHostMalloc(reinterpret_cast<void **>(&h->stash_host), stash_bytes, hipHostMallocDefault));
+  if (h->err) {
+    int e = h->err;
+    hmy_destroy(h);
+    return e;
+  }
+  *out = h;
+  return HMY_OK;
+}
+
+int hmy_get_schedule(const hmy_handle *h, hmy_schedule *out) {
+  if (!h || !out) return fail(HMY_E_INVALID, "null argument");
+  packs_to_schedule(h->packs, out);
+  return HMY_OK;
+}
+
+int hmy_bind_state(hmy_handle *h, const hmy_host_state *state) {
+  if (!h || !state) return fail(HMY_E_INVALID, "null argument");
+  const bool mixed = h->model.spec.precision == HMY_PREC_BF16;
+  if (!state->weights || !state->adam_m || !state->adam_v || !state->grads)
+    return fail(HMY_E_INVALID, "weights, adam_m, adam_v and grads must be given");
+  if (mixed && !state->master) return fail(HMY_E_INVALID, "bf16 precision needs an fp32 master array");
+  if (!mixed && state->master) return fail(HMY_E_INVALID, "fp32 precision: master must be NULL (weights are the master)");
+  if (state->n_params != h->model.n_params)
+    return fail(HMY_E_INVALID, "state has %llu parameters, model has %llu", (unsigned long long)state->n_params,
+                (unsigned long long)h->model.n_params);
+  h->host = *state;
+  h->bound = true;
+  return HMY_OK;
+}
+
+int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out) {
+  if (!h || !mb || !adam) return fail(HMY_E_INVALID, "null argument");
+  if (!h->bound) return fail(HMY_E_NOT_BOUND, "hmy_bind_state has not been called");
+  if (mb->n_micro != h->M || mb->micro_batch != h->b)
+    return fail(HMY_E_INVALID, "minibatch is %dx%d, handle was created for %dx%d", mb->n_micro, mb->micro_batch, h->M, h->b);
+  if (!mb->token_ids || !mb->targets) return fail(HMY_E_INVALID, "null token_ids/targets");
+  if (adam->step < 1) return fail(HMY_E_INVALID, "adam step is 1-based");
+  const hmy_model_spec &s = h->model.spec;
+  const uint64_t n = uint64_t(h->M) * h->b * s.seq_len;
+  for (uint64_t i = 0; i < n; ++i) {
+    if (mb->token_ids[i] < 0 || mb->token_ids[i] >= s.vocab) return fail(HMY_E_INVALID, "token id out of range at %llu", (unsigned long long)i);
+    if (mb->targets[i] < -1 || mb->targets[i] >= s.vocab) return fail(HMY_E_INVALID, "target out of range at %llu", (unsigned long long)i);
+  }
+  h->err = HMY_OK;
+  HIPCHK(h, hipSetDevice(h->device));
+  h->timing = out != nullptr;
+  auto t0 = std::chrono::steady_clock::now();
+  run_iteration(h, mb, *adam);
+  // always drain, even after an error, so no stream still touches caller memory
+  hipStreamSynchronize(h->s_comp);
+  hipStreamSynchronize(h->s_in);
+  hipStreamSynchronize(h->s_upd);
+  hipError_t e_last = hipStreamSynchronize(h->s_out);
+  if (h->err == HMY_OK && e_last != hipSuccess) h->err = fail(HMY_E_HIP, "stream sync: %s", hipGetErrorString(e_last));
+  auto t1 = std::chrono::steady_clock::now();
+  if (h->err) return h->err;
+  double loss = 0.0;
+  HIPCHK(h, hipMemcpy(&loss, h->base + h->arena.res.misc, sizeof(double), hipMemcpyDeviceToHost));
+  if (out) {
+    h->st.loss = loss;
+    h->st.t_iter_s = std::chrono::duration<double>(t1 - t0).count();
+    for (const auto &sp : h->spans) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, h->time_events[sp.a], h->time_events[sp.b]) != hipSuccess) continue;
+      const double sec = ms * 1e-3;
+      if (sp.what == 0) h->st.t_h2d_busy_s += sec;
+      else if (sp.what == 1) h->st.t_d2h_busy_s += sec;
+      else if (sp.what == 2) h->st.t_stall_s += sec;
+      else h->st.t_compute_s += sec;
+    }
+    *out = h->st;
+  }
+  return h->err;
+}
+
+int hmy_destroy(hmy_handle *h) {
+  if (!h) return HMY_OK;
+  if (!h->dry && h->device >= 0) {
+    hipSetDevice(h->device);
+    if (h->s_comp) { hipStreamSynchronize(h->s_comp); hipStreamDestroy(h->s_comp); }
+    if (h->s_in) { hipStreamSynchronize(h->s_in); hipStreamDestroy(h->s_in); }
+    if (h->s_upd) { hipStreamSynchronize(h->s_upd); hipStreamDestroy(h->s_upd); }
+    if (h->s_out) { hipStreamSynchronize(h->s_out); hipStreamDestroy(h->s_out); }
+    for (hipEvent_t e : h->sync_events) hipEventDestroy(e);
+    for (hipEvent_t e : h->time_events) hipEventDestroy(e);
+    if (h->stash_host) hipHostFree(h->stash_host);
+    if (h->own_arena && h->base) hipFree(h->base);
+  }
+  delete h;
+  return HMY_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,129 @@
+// Internal declarations shared by the host logic and the kernel launchers.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "hmy.h"
+
+namespace hmy {
+
+// ---- errors ---------------------------------------------------------------
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// ---- model layout -----------------------------------------------------------
+struct Tensor {
+  std::string name;
+  int layer;
+  int rows, cols;
+  uint64_t offset;  // element offset in every host array
+  uint64_t count;
+};
+
+// indices of a block's tensors relative to the block's first tensor
+enum BlockTensor { LN1_G, LN1_B, WQKV, BQKV, WO, BO, LN2_G, LN2_B, W1, B1, W2, B2, N_BLOCK_TENSORS };
+
+struct Model {
+  hmy_model_spec spec;
+  int R;                            // layers
+  std::vector<Tensor> tensors;      // storage order
+  std::vector<int> first_tensor;    // per layer, index into tensors (size R+1)
+  std::vector<uint64_t> layer_off;  // per layer, element offset (size R+1)
+  uint64_t n_params;
+  int elem_bytes() const { return spec.precision == HMY_PREC_BF16 ? 2 : 4; }
+  int k_arrays() const { return spec.precision == HMY_PREC_BF16 ? 3 : 2; }  // K = (master,) m, v
+  uint64_t params_in(int a, int e) const { return layer_off[e] - layer_off[a]; }
+};
+
+int build_model(const hmy_model_spec *spec, Model *out);
+
+// ---- analytic profile and arena ---------------------------------------------
+inline uint64_t a256(uint64_t x) { return (x + 255) & ~uint64_t(255); }
+
+constexpr int kOutRing = 4;            // staging buffers for checkpoints going out
+constexpr int kInRing = 2;             // pack-input buffers (checkpoint coming in)
+constexpr int kKRing = 3;              // optimizer-state ring slots
+constexpr uint64_t kKChunkMax = 4ull << 20;  // parameters per optimizer chunk
+constexpr int kLogitRows = 512;        // rows of the vocabulary projection per chunk
+
+struct BlockActs {  // byte offsets of one block's saved activations inside its region
+  uint64_t x_in, a, qkv, o, x_mid, h, u, g, ln1_mean, ln1_rstd, ln2_mean, ln2_rstd, lse, size;
+};
+struct HeadActs {
+  uint64_t x_in, z, mean, rstd, logits, dlogits, size;
+  int chunk_rows;
+  int64_t ldl;  // row stride of logits / dlogits in elements
+};
+BlockActs block_acts(const hmy_model_spec &s, int micro_batch);
+HeadActs head_acts(const hmy_model_spec &s, int micro_batch);
+
+struct Reserved {  // pack-independent arena regions, byte offsets from the arena base
+  uint64_t X;         // n_micro buffers of x_bytes
+  uint64_t x_bytes;   // a256(T*d*E)
+  uint64_t inring;    // kInRing buffers of x_bytes
+  uint64_t outring;   // kOutRing buffers of x_bytes
+  uint64_t gbig;      // T*max(f,3d)*E : dg/du and dqkv
+  uint64_t gsmall;    // T*d*E : dh, do, da, dz
+  uint64_t delta;     // T*H*4
+  uint64_t ids, targets;
+  uint64_t misc;      // loss accumulators
+  uint64_t kring;     // kKRing slots of k_arrays * karr_bytes
+  uint64_t karr_bytes;
+  uint64_t k_chunk_params;
+  uint64_t size;
+};
+Reserved reserved_layout(const Model &m, int n_micro, int micro_batch);
+
+void layer_profile(const Model &m, int n_micro, int micro_batch, std::vector<hmy_layer_profile> *out);
+
+struct Pack { int a, e; };
+struct Packs { std::vector<Pack> fwd, bwd; };
+
+int schedule_to_packs(const Model &m, const hmy_schedule *s, Packs *out);
+void packs_to_schedule(const Packs &p, hmy_schedule *out);
+
+struct Arena {
+  Reserved res;
+  uint64_t slot_bytes;
+  uint64_t slot_off[2];
+  uint64_t act_off, act_bytes;
+  uint64_t total;
+};
+Arena arena_layout(const Model &m, const Packs &p, int n_micro, int micro_batch);
+uint64_t pack_state_bwd(const Model &m, Pack p);   // a256(E*P) + a256(4*P)
+uint64_t pack_state_fwd(const Model &m, Pack p);   // a256(E*P)
+
+int plan_packs(const Model &m, uint64_t budget, int n_micro, int micro_batch, Packs *out);
+
+// ---- kernel launchers (all pointers device; stream is a hipStream_t) ---------
+typedef void *stream_t;
+
+int launch_embed_fwd(int prec, const int32_t *ids, const void *wte, const void *wpe, void *x,
+                     int T, int d, int s, int vocab, stream_t st);
+int launch_embed_bwd(int prec, const int32_t *ids, const void *dx, float *dwte, float *dwpe,
+                     int T, int d, int s, int vocab, stream_t st);
+int launch_layernorm_fwd(int prec, const void *x, const void *gamma, const void *beta, void *y,
+                         float *mean, float *rstd, int T, int d, float eps, stream_t st);
+int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *mean,
+                         const float *rstd, const void *gamma, const void *res, void *dx,
+                         float *dgamma, float *dbeta, int T, int d, stream_t st);
+int launch_gelu_fwd(int prec, const void *u, void *g, uint64_t n, stream_t st);
+int launch_gelu_bwd(int prec, const void *dg, const void *u, void *du, uint64_t n, stream_t st);
+int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st);
+int launch_gemm(const hmy_gemm_desc &g, stream_t st);
+int launch_attn_fwd(int prec, const void *qkv, void *o, float *lse, int b, int s, int H, int dh,
+                    int causal, stream_t st);
+int launch_attn_bwd(int prec, const void *qkv, const void *o, const void *d_o, const float *lse,
+                    float *delta, void *dqkv, int b, int s, int H, int dh, int causal,
+                    stream_t st);
+int launch_xent(int prec, const float *logits, const int32_t *targets, double *loss_acc,
+                void *dlogits, int T, int V, int64_t ldl, float inv_ntgt, stream_t st);
+int launch_adam(int prec, const float *grad, float *master, float *m, float *v, void *w_out,
+                uint64_t n, const hmy_adam &hp, stream_t st);
+int launch_fill_zero(void *p, uint64_t bytes, stream_t st);
+int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st);
+
+extern int g_use_mfma;
+
+}  // namespace hmy

@@ -1,0 +1,275 @@
+// Pack planner: analytic layer profile, HBM arena layout and balanced-time
+// packing (the paper's Algorithm 2, Section 4.3.1) under the HBM budget.
+//
+// Memory model.  The runtime keeps two weight slots (prefetch distance 1:
+// "prefetching ... double buffering", Section 4.4), one activation workspace
+// for the backward pack in flight, and a pack-independent reserve (resident
+// boundary activations, checkpoint rings, gradient scratch, the optimizer ring).
+// A layer's footprint for the packing is therefore
+//   forward : 2 * E * p                        (E bytes per weight, p parameters)
+//   backward: 2 * (E + 4) * p + act            (weights + fp32 gradients, twice; activations once)
+// and the capacity is the budget minus the reserve.  Times are flop counts of
+// one microbatch (integers, so the balanced split has exact ties).
+#include <algorithm>
+#include <cstring>
+
+#include "hmy_internal.h"
+
+namespace hmy {
+
+BlockActs block_acts(const hmy_model_spec &s, int micro_batch) {
+  const uint64_t E = s.precision == HMY_PREC_BF16 ? 2 : 4;
+  const uint64_t T = uint64_t(micro_batch) * s.seq_len, d = s.d_model, f = s.d_ffn, H = s.n_heads;
+  BlockActs b;
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) { uint64_t o = off; off += a256(bytes); return o; };
+  b.x_in = take(T * d * E);
+  b.a = take(T * d * E);
+  b.qkv = take(3 * T * d * E);
+  b.o = take(T * d * E);
+  b.x_mid = take(T * d * E);
+  b.h = take(T * d * E);
+  b.u = take(T * f * E);
+  b.g = take(T * f * E);
+  b.ln1_mean = take(T * 4);
+  b.ln1_rstd = take(T * 4);
+  b.ln2_mean = take(T * 4);
+  b.ln2_rstd = take(T * 4);
+  b.lse = take(T * H * 4);
+  b.size = off;
+  return b;
+}
+
+HeadActs head_acts(const hmy_model_spec &s, int micro_batch) {
+  const uint64_t E = s.precision == HMY_PREC_BF16 ? 2 : 4;
+  const uint64_t T = uint64_t(micro_batch) * s.seq_len, d = s.d_model;
+  HeadActs h;
+  h.chunk_rows = int(std::min<uint64_t>(T, kLogitRows));
+  h.ldl = (int64_t(s.vocab) + 7) / 8 * 8;
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) { uint64_t o = off; off += a256(bytes); return o; };
+  h.x_in = take(T * d * E);
+  h.z = take(T * d * E);
+  h.mean = take(T * 4);
+  h.rstd = take(T * 4);
+  h.logits = take(uint64_t(h.chunk_rows) * h.ldl * 4);
+  h.dlogits = take(uint64_t(h.chunk_rows) * h.ldl * E);
+  h.size = off;
+  return h;
+}
+
+Reserved reserved_layout(const Model &m, int n_micro, int micro_batch) {
+  const hmy_model_spec &s = m.spec;
+  const uint64_t E = m.elem_bytes();
+  const uint64_t T = uint64_t(micro_batch) * s.seq_len, d = s.d_model, f = s.d_ffn, H = s.n_heads;
+  Reserved r;
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) { uint64_t o = off; off += a256(bytes); return o; };
+  r.x_bytes = a256(T * d * E);
+  r.X = take(uint64_t(n_micro) * r.x_bytes);
+  r.inring = take(kInRing * r.x_bytes);
+  r.outring = take(kOutRing * r.x_bytes);
+  r.gbig = take(T * std::max<uint64_t>(f, 3 * d) * E);
+  r.gsmall = take(T * d * E);
+  r.delta = take(T * H * 4);
+  r.ids = take(uint64_t(n_micro) * T * 4);
+  r.targets = take(uint64_t(n_micro) * T * 4);
+  r.misc = take(4096);
+  uint64_t maxp = 0;
+  for (int l = 0; l < m.R; ++l) maxp = std::max(maxp, m.params_in(l, l + 1));
+  r.k_chunk_params = std::min<uint64_t>(kKChunkMax, maxp);
+  r.karr_bytes = a256(r.k_chunk_params * 4);
+  r.kring = take(uint64_t(kKRing) * m.k_arrays() * r.karr_bytes);
+  r.size = off;
+  return r;
+}
+
+void layer_profile(const Model &m, int n_micro, int micro_batch, std::vector<hmy_layer_profile> *out) {
+  (void)n_micro;
+  const hmy_model_spec &s = m.spec;
+  const int64_t T = int64_t(micro_batch) * s.seq_len, d = s.d_model, f = s.d_ffn, V = s.vocab;
+  const uint64_t E = m.elem_bytes();
+  out->assign(m.R, hmy_layer_profile{});
+  const uint64_t act_block = block_acts(s, micro_batch).size;
+  const uint64_t act_head = head_acts(s, micro_batch).size;
+  for (int l = 0; l < m.R; ++l) {
+    hmy_layer_profile &p = (*out)[l];
+    p.params = m.params_in(l, l + 1);
+    if (l == 0) {
+      p.t_fwd = T * d;
+      p.act_bwd = 0;
+    } else if (l <= s.n_blocks) {
+      p.t_fwd = T * (8 * d * d + 4 * d * f + (s.causal ? 2 : 4) * int64_t(s.seq_len) * d);
+      p.act_bwd = act_block;
+    } else {
+      p.t_fwd = 2 * T * d * V;
+      p.act_bwd = act_head;
+    }
+    p.t_bwd = 3 * p.t_fwd;
+    p.mem_fwd = 2 * E * p.params;
+    p.mem_bwd = 2 * (E + 4) * p.params + p.act_bwd;
+  }
+}
+
+uint64_t pack_state_fwd(const Model &m, Pack p) { return a256(m.elem_bytes() * m.params_in(p.a, p.e)); }
+uint64_t pack_state_bwd(const Model &m, Pack p) {
+  return a256(m.elem_bytes() * m.params_in(p.a, p.e)) + a256(4 * m.params_in(p.a, p.e));
+}
+
+Arena arena_layout(const Model &m, const Packs &p, int n_micro, int micro_batch) {
+  Arena a;
+  a.res = reserved_layout(m, n_micro, micro_batch);
+  std::vector<hmy_layer_profile> prof;
+  layer_profile(m, n_micro, micro_batch, &prof);
+  a.slot_bytes = 0;
+  a.act_bytes = 0;
+  for (const Pack &q : p.fwd) a.slot_bytes = std::max(a.slot_bytes, pack_state_fwd(m, q));
+  for (const Pack &q : p.bwd) {
+    a.slot_bytes = std::max(a.slot_bytes, pack_state_bwd(m, q));
+    uint64_t act = 0;
+    for (int l = q.a; l < q.e; ++l) act += prof[l].act_bwd;
+    a.act_bytes = std::max(a.act_bytes, act);
+  }
+  a.slot_off[0] = a.res.size;
+  a.slot_off[1] = a.slot_off[0] + a.slot_bytes;
+  a.act_off = a.slot_off[1] + a.slot_bytes;
+  a.total = a.act_off + a.act_bytes;
+  return a;
+}
+
+int schedule_to_packs(const Model &m, const hmy_schedule *s, Packs *out) {
+  if (!s) return fail(HMY_E_INVALID, "null schedule");
+  if (s->n_bwd_packs < 1 || s->n_bwd_packs > m.R || s->n_fwd_packs < 0 || s->n_fwd_packs > m.R)
+    return fail(HMY_E_BAD_SCHEDULE, "pack counts out of range");
+  Packs p;
+  int pos = 0;
+  for (int i = 0; i < s->n_bwd_packs; ++i) {
+    int e = s->bwd_pack_end[i];
+    if (e <= pos || e > m.R) return fail(HMY_E_BAD_SCHEDULE, "backward pack %d is empty or out of range", i);
+    p.bwd.push_back({pos, e});
+    pos = e;
+  }
+  if (pos != m.R) return fail(HMY_E_BAD_SCHEDULE, "backward packs cover %d of %d layers", pos, m.R);
+  const int last_start = p.bwd.back().a;
+  pos = 0;
+  for (int i = 0; i < s->n_fwd_packs; ++i) {
+    int e = s->fwd_pack_end[i];
+    if (e <= pos || e > last_start) return fail(HMY_E_BAD_SCHEDULE, "forward pack %d is empty or out of range", i);
+    p.fwd.push_back({pos, e});
+    pos = e;
+  }
+  if (pos != last_start)
+    return fail(HMY_E_BAD_SCHEDULE, "forward packs must cover exactly the %d layers before the last backward pack",
+                last_start);
+  *out = std::move(p);
+  return HMY_OK;
+}
+
+void packs_to_schedule(const Packs &p, hmy_schedule *out) {
+  std::memset(out, 0, sizeof(*out));
+  out->n_fwd_packs = int(p.fwd.size());
+  out->n_bwd_packs = int(p.bwd.size());
+  for (size_t i = 0; i < p.fwd.size(); ++i) out->fwd_pack_end[i] = p.fwd[i].e;
+  for (size_t i = 0; i < p.bwd.size(); ++i) out->bwd_pack_end[i] = p.bwd[i].e;
+}
+
+// Algorithm 2 on explicit lists over layers first..first+R.  `fits` is the
+// whole-packing test ANDed to the per-pack capacity test.  Returns false if not
+// even one layer per pack fits.
+template <class Fits>
+static bool balanced_time_packing(const std::vector<int64_t> &t, const std::vector<uint64_t> &mem,
+                                  uint64_t alpha, int first, Fits fits, std::vector<Pack> *out) {
+  const int R = int(t.size());
+  out->clear();
+  if (R == 0) return true;
+  if (alpha == 0) return false;
+  __int128 total = 0;
+  uint64_t msum = 0;
+  std::vector<__int128> prefix(R);
+  for (int j = 0; j < R; ++j) {
+    total += t[j];
+    prefix[j] = total;
+    msum += mem[j];
+  }
+  auto per_pack_ok = [&](const std::vector<Pack> &ps) {
+    for (const Pack &q : ps) {
+      uint64_t s = 0;
+      for (int l = q.a; l < q.e; ++l) s += mem[l - first];
+      if (s > alpha) return false;
+    }
+    return true;
+  };
+  int S_min = int(std::max<uint64_t>(1, (msum + alpha - 1) / alpha));
+  for (int S = S_min; S <= R; ++S) {
+    // cut k = number of layers whose prefix time is <= k * total / S
+    std::vector<Pack> ps;
+    int prev = 0;
+    for (int k = 1; k <= S; ++k) {
+      int cut;
+      if (k == S) {
+        cut = R;
+      } else {
+        cut = 0;
+        for (int j = 0; j < R; ++j)
+          if (prefix[j] * S <= __int128(k) * total) ++cut;
+      }
+      if (cut > prev) ps.push_back({first + prev, first + cut});
+      prev = std::max(prev, cut);
+    }
+    if (per_pack_ok(ps) && fits(ps)) {
+      *out = std::move(ps);
+      return true;
+    }
+  }
+  std::vector<Pack> ps;
+  for (int j = 0; j < R; ++j) ps.push_back({first + j, first + j + 1});
+  if (per_pack_ok(ps) && fits(ps)) {
+    *out = std::move(ps);
+    return true;
+  }
+  return false;
+}
+
+int plan_packs(const Model &m, uint64_t budget, int n_micro, int micro_batch, Packs *out) {
+  std::vector<hmy_layer_profile> prof;
+  layer_profile(m, n_micro, micro_batch, &prof);
+  const Reserved res = reserved_layout(m, n_micro, micro_batch);
+  if (budget <= res.size)
+    return fail(HMY_E_BUDGET_TOO_SMALL, "budget %llu B does not cover the pack-independent reserve %llu B",
+                (unsigned long long)budget, (unsigned long long)res.size);
+  // backward packs first (Algorithm 1, line "backward packing")
+  std::vector<int64_t> t(m.R);
+  std::vector<uint64_t> mem(m.R);
+  for (int l = 0; l < m.R; ++l) {
+    t[l] = prof[l].t_bwd;
+    mem[l] = prof[l].mem_bwd;
+  }
+  Packs p;
+  auto arena_fits = [&](const std::vector<Pack> &bwd) {
+    Packs q;
+    q.bwd = bwd;
+    return arena_layout(m, q, n_micro, micro_batch).total <= budget;
+  };
+  if (!balanced_time_packing(t, mem, budget - res.size, 0, arena_fits, &p.bwd))
+    return fail(HMY_E_BUDGET_TOO_SMALL, "budget %llu B: even one layer per backward pack does not fit",
+                (unsigned long long)budget);
+  // forward packs over the layers before the last backward pack; they share the
+  // weight slots sized by the backward packing
+  const int RF = p.bwd.back().a;
+  Packs only_b;
+  only_b.bwd = p.bwd;
+  const uint64_t slot = arena_layout(m, only_b, n_micro, micro_batch).slot_bytes;
+  t.assign(RF, 0);
+  mem.assign(RF, 0);
+  for (int l = 0; l < RF; ++l) {
+    t[l] = prof[l].t_fwd;
+    mem[l] = prof[l].mem_fwd;
+  }
+  auto always = [](const std::vector<Pack> &) { return true; };
+  if (!balanced_time_packing(t, mem, 2 * slot, 0, always, &p.fwd))
+    return fail(HMY_E_BUDGET_TOO_SMALL, "forward packing failed (internal)");
+  *out = std::move(p);
+  return HMY_OK;
+}
+
+}  // namespace hmy

@@ -1,0 +1,207 @@
+"""CPU tests of the C-ABI library's host logic against the oracle: exported
+symbols, tensor layout, analytic profile, Algorithm 2 planner, arena sizing and
+the swap-byte counters of a dry walk of the executor (bit-exact)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import model as om
+from oracle import packing as opk
+from oracle import swapcount as osw
+from paper_2202_01306_amd import binding as B
+from paper_2202_01306_amd import synth
+from tests.helpers import oracle_spec, tiny_cfg
+from tests.test_oracle_schedule import all_packings
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "hmy.h")).read()
+    declared = set(re.findall(r"^(?:int|const char \*)\s*(hmy_[a-z0-9_]+)\s*\(", hdr, flags=re.M))
+    assert len(declared) >= 28
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib, name), name
+        getattr(B.lib, name)
+
+
+def test_struct_sizes_match_what_a_c_compiler_gives_for_the_header(tmp_path):
+    """The header must be valid C, and the ctypes mirrors must agree with it."""
+    import subprocess
+    names = ["hmy_model_spec", "hmy_budget", "hmy_schedule", "hmy_minibatch", "hmy_adam", "hmy_host_state",
+             "hmy_stats", "hmy_tensor_desc", "hmy_layer_profile", "hmy_arena_plan", "hmy_gemm_desc"]
+    src = tmp_path / "sz.c"
+    src.write_text('#include <stdio.h>\n#include "hmy.h"\nint main(void){' +
+                   "".join(f'printf("%zu\\n", sizeof({n}));' for n in names) +
+                   'printf("%d %d\\n", HMY_MAX_LAYERS, HMY_NKINDS);return 0;}')
+    exe = tmp_path / "sz"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    for n, sz in zip(names, out):
+        assert ctypes.sizeof(getattr(B, n)) == int(sz), n
+    assert (int(out[-2]), int(out[-1])) == (B.HMY_MAX_LAYERS, B.HMY_NKINDS)
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_layout_matches_the_named_shapes(name):
+    cfg = synth.CONFIGS[name]
+    spec = B.make_spec(cfg)
+    lay = B.hmy_layout(spec)
+    shapes = synth.shape_table(cfg)
+    assert [t["name"] for t in lay] == list(shapes)
+    off = 0
+    ospec = oracle_spec(cfg)
+    for t, (nm, shp) in zip(lay, shapes.items()):
+        assert t["count"] == int(np.prod(shp)) and t["offset"] == off
+        assert (t["rows"], t["cols"]) == (shp[0], shp[1] if len(shp) == 2 else 1)
+        assert nm in om.layer_param_shapes(ospec, t["layer"])
+        off += t["count"]
+    R, n = B.hmy_model_size(spec)
+    assert R == ospec.n_layers and n == off == sum(om.layer_param_count(ospec, l) for l in range(R))
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_profile_and_reserve_match_the_oracle_model(name):
+    cfg = synth.CONFIGS[name]
+    spec, ospec = B.make_spec(cfg), oracle_spec(cfg)
+    prof, res = B.hmy_profile(spec, cfg["M"], cfg["b"])
+    assert prof == opk.layer_profile(ospec, cfg["M"], cfg["b"], cfg["precision"])
+    assert res == opk.reserved_bytes(ospec, cfg["M"], cfg["b"], cfg["precision"])
+
+
+def one_layer_budget(cfg):
+    """'HBM budget sized for one layer resident': reserve + the largest single
+    layer's backward footprint."""
+    ospec = oracle_spec(cfg)
+    prof = opk.layer_profile(ospec, cfg["M"], cfg["b"], cfg["precision"])
+    return opk.reserved_bytes(ospec, cfg["M"], cfg["b"], cfg["precision"]) + max(p["mem_bwd"] for p in prof) + 512
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_planner_returns_the_oracles_packs(name):
+    cfg = dict(synth.CONFIGS[name])
+    if cfg["budget"] is None:
+        cfg["budget"] = one_layer_budget(cfg)
+    spec, ospec = B.make_spec(cfg), oracle_spec(cfg)
+    s = B.hmy_plan(spec, cfg["budget"], cfg["M"], cfg["b"])
+    P_F, P_B = B.schedule_packs(s)
+    want = opk.plan(ospec, cfg["budget"], cfg["M"], cfg["b"], cfg["precision"])
+    assert want is not None and (P_F, P_B) == (want[0], want[1])
+    a = B.hmy_arena(spec, s, cfg["M"], cfg["b"])
+    total, slot, act = opk.arena_bytes(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
+    assert (a["total"], a["slot_bytes"], a["act_bytes"]) == (total, slot, act)
+    assert a["total"] <= cfg["budget"]
+    # structure the paper states: forward packs cover the layers before the last
+    # backward pack and are at least as large as backward packs
+    assert (P_F[-1][1] if P_F else 0) == P_B[-1][0]
+    if P_F and len(P_B) > 1:
+        assert max(e - a_ for a_, e in P_F) >= max(e - a_ for a_, e in P_B[:-1])
+
+
+def test_tiny_config_budget_gives_one_layer_per_pack():
+    cfg = dict(synth.CONFIGS["tiny"])
+    spec = B.make_spec(cfg)
+    s = B.hmy_plan(spec, one_layer_budget(cfg), cfg["M"], cfg["b"])
+    P_F, P_B = B.schedule_packs(s)
+    assert P_B == [(i, i + 1) for i in range(6)]
+    # a forward slot only holds weights (no fp32 gradients), so in fp32 up to two
+    # layers share it: forward packs are at least as large as backward packs
+    assert P_F[0][0] == 0 and P_F[-1][1] == 5 and all(1 <= e - a <= 2 for a, e in P_F)
+    # the explicit one-layer-per-pack schedule is valid under the same budget
+    a = B.hmy_arena(spec, B.make_schedule([1, 2, 3, 4, 5], [1, 2, 3, 4, 5, 6]), cfg["M"], cfg["b"])
+    assert a["total"] <= one_layer_budget(cfg)
+
+
+def test_planner_matches_oracle_on_random_small_models_and_budgets():
+    rng = np.random.default_rng(0)
+    n_checked = 0
+    for _ in range(60):
+        H = int(rng.choice([1, 2, 4]))
+        dh = int(rng.choice([32, 64]))
+        cfg = tiny_cfg(n_blocks=int(rng.integers(1, 9)), d_model=H * dh, n_heads=H,
+                       d_ffn=int(rng.choice([64, 128, 512])), seq_len=int(rng.choice([8, 16, 64])),
+                       vocab=int(rng.integers(17, 3000)), causal=int(rng.integers(0, 2)),
+                       precision=str(rng.choice(["fp32", "bf16"])), M=int(rng.integers(1, 5)), b=int(rng.integers(1, 4)))
+        spec, ospec = B.make_spec(cfg), oracle_spec(cfg)
+        lo = one_layer_budget(cfg)
+        prof = opk.layer_profile(ospec, cfg["M"], cfg["b"], cfg["precision"])
+        hi = lo + sum(p["mem_bwd"] for p in prof)
+        for budget in (lo // 2, lo, (lo + hi) // 2, int(lo + 0.3 * (hi - lo)), hi + 10 ** 6):
+            want = opk.plan(ospec, budget, cfg["M"], cfg["b"], cfg["precision"])
+            try:
+                got = B.schedule_packs(B.hmy_plan(spec, budget, cfg["M"], cfg["b"]))
+            except B.HmyError as e:
+                assert e.code == B.HMY_E_BUDGET_TOO_SMALL and want is None
+                continue
+            assert want is not None and got == (want[0], want[1]), (cfg, budget)
+            n_checked += 1
+    assert n_checked > 100
+
+
+# ---------------------------------------------------------------- counters ---
+
+def _cmp_counters(cfg, P_F, P_B):
+    spec, ospec = B.make_spec(cfg), oracle_spec(cfg)
+    sched = B.make_schedule([e for _, e in P_F], [e for _, e in P_B])
+    got = B.hmy_count_swaps(spec, sched, cfg["M"], cfg["b"])
+    want = osw.closed_form(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
+    assert got["h2d"] == want["h2d"] and got["d2h"] == want["d2h"]
+    assert want == osw.ledger(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
+    return got
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_swap_counters_equal_closed_form_on_planned_configs(name):
+    cfg = dict(synth.CONFIGS[name])
+    if cfg["budget"] is None:
+        cfg["budget"] = one_layer_budget(cfg)
+    P_F, P_B = B.schedule_packs(B.hmy_plan(B.make_spec(cfg), cfg["budget"], cfg["M"], cfg["b"]))
+    got = _cmp_counters(cfg, P_F, P_B)
+    # the headline of the method: weights come in once per pass, not once per microbatch
+    E = 2 if cfg["precision"] == "bf16" else 4
+    n = B.hmy_model_size(B.make_spec(cfg))[1]
+    assert got["h2d"]["W"] < 2 * E * n
+    assert got["d2h"]["W"] == E * n and got["h2d"]["dW"] == 0 and got["h2d"]["XY"] == got["d2h"]["XY"] == 0
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_swap_counters_equal_closed_form_on_every_packing_of_a_small_model(precision):
+    cfg = tiny_cfg(n_blocks=3, d_model=32, n_heads=1, d_ffn=64, seq_len=8, vocab=40, precision=precision, M=3, b=2)
+    R = 5
+    n = 0
+    for P_B in all_packings(R):
+        last_start = P_B[-1][0]
+        for P_F in (list(all_packings(last_start)) if last_start else [[]]):
+            _cmp_counters(cfg, P_F, P_B)
+            n += 1
+    assert n > 30
+
+
+# ------------------------------------------------------------------ errors ---
+
+def test_error_paths_return_codes_not_crashes():
+    cfg = tiny_cfg(d_model=64, n_heads=2)
+    spec = B.make_spec(cfg)
+    with pytest.raises(B.HmyError) as e:
+        B.hmy_plan(spec, 1000, 2, 2)
+    assert e.value.code == B.HMY_E_BUDGET_TOO_SMALL
+    bad = B.make_spec(dict(cfg, d_model=60))          # head dim 30
+    with pytest.raises(B.HmyError) as e:
+        B.hmy_model_size(bad)
+    assert e.value.code == B.HMY_E_INVALID
+    with pytest.raises(B.HmyError) as e:                # packs do not cover all layers
+        B.hmy_arena(spec, B.make_schedule([], [2, 3]), 2, 2)
+    assert e.value.code == B.HMY_E_BAD_SCHEDULE
+    with pytest.raises(B.HmyError) as e:                # forward packs must stop before the last backward pack
+        B.hmy_arena(spec, B.make_schedule([4], [2, 4]), 2, 2)
+    assert e.value.code == B.HMY_E_BAD_SCHEDULE
+    with pytest.raises(B.HmyError) as e:
+        B.hmy_count_swaps(spec, B.make_schedule([1], [2, 4]), 2, 2)
+    assert e.value.code == B.HMY_E_BAD_SCHEDULE
+    assert B.lib.hmy_strerror(B.HMY_E_HIP) == b"HIP runtime error"
+    assert B.lib.hmy_model_size(None, None, None) == B.HMY_E_INVALID
