@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark: one layer-pack-major training iteration under the HBM budget.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config gpt2m] [--no-cpu-baseline]
+
+A step is one whole iteration (every forward pack, the last pack's
+forward+backward, every backward pack with recompute, fused Adam and all swaps)
+on synthetic data with model state starting in pinned host memory, which is
+where the method keeps it.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+VARIANTS = ("gemm_mfma<A[M,K],B[N,K]> (forward, recompute)", "gemm_mfma<A[M,K],B[K,N]> (input gradient)",
+            "gemm_mfma<A[K,M],B[N,K]>", "gemm_mfma<A[K,M],B[K,N]> (weight gradient)")
+
+
+def attention_flops(cfg, packs) -> float:
+    """Algorithmic attention flops of one iteration: QK^T and PV forward (causal
+    counts the visible half), 2.5x that for backward, forward repeated once for
+    every block that is recomputed (all but the last backward pack)."""
+    P_F, P_B = packs
+    L, s, d = cfg["n_blocks"], cfg["seq_len"], cfg["d_model"]
+    tokens = cfg["M"] * cfg["b"] * s
+    fwd = tokens * (2 if cfg["causal"] else 4) * s * d
+    last_a = P_B[-1][0]
+    recomputed = sum(1 for l in range(1, L + 1) if l < last_a)
+    return fwd * (L + recomputed) + 2.5 * fwd * L
+
+
+def cpu_baseline(cfg):
+    """Time the fp64 oracle, as it stands, on a bounded sample of the workload:
+    embedding, ONE block and the head, forward and backward, on one microbatch at
+    full width; extrapolated linearly to all blocks and microbatches."""
+    import numpy as np
+    from oracle import model as om
+    from paper_2202_01306_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    c1 = dict(cfg, n_blocks=1, M=1)
+    spec = om.Spec(1, cfg["d_model"], cfg["n_heads"], cfg["d_ffn"], cfg["seq_len"], cfg["vocab"], bool(cfg["causal"]),
+                   synth.LN_EPS)
+    params = {k: np.asarray(v, np.float64) for k, v in synth.gen_params(c1, 0).items()}
+    ids = synth.gen_tokens(c1, 0)
+    tg = synth.gen_targets(c1, ids, 0)
+    n_tgt = om.count_targets(tg)
+    t = {}
+    x, caches = None, []
+    for layer in range(3):
+        t0 = time.perf_counter()
+        x, c = om.layer_fwd(layer, x, params, spec, ids[0], tg[0], n_tgt)
+        t[("f", layer)] = time.perf_counter() - t0
+        caches.append(c)
+    dy = None
+    for layer in (2, 1, 0):
+        t0 = time.perf_counter()
+        dy, _ = om.layer_bwd(layer, dy, caches[layer], params, spec, cfg["b"])
+        t[("b", layer)] = time.perf_counter() - t0
+    t_block = t[("f", 1)] + t[("b", 1)]
+    t_rest = t[("f", 0)] + t[("b", 0)] + t[("f", 2)] + t[("b", 2)]
+    est = cfg["M"] * (cfg["n_blocks"] * t_block + t_rest)
+    return {
+        "value": cfg["M"] * cfg["b"] / est, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+        "sample": (f"fp64 numpy oracle: embedding + 1 block + head, forward+backward, 1 microbatch of "
+                   f"{cfg['b']}x{cfg['seq_len']} tokens at full width ({sum(t.values()):.1f} s of CPU work; block "
+                   f"{t_block:.2f} s, embedding+head {t_rest:.2f} s), extrapolated linearly to "
+                   f"{cfg['n_blocks']} blocks x {cfg['M']} microbatches (no recompute, no swapping)"),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="gpt2m")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reference-kernels", action="store_true", help="time the plain (non-MFMA) kernels")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {a.gpus} is not supported",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2202_01306_amd import binding as B
+    from paper_2202_01306_amd import synth
+    from paper_2202_01306_amd.runner import Engine, TrainingState
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU fallback)", file=sys.stderr)
+        return 3
+    cfg = dict(synth.CONFIGS[a.config])
+    if cfg["budget"] is None:
+        cfg["budget"] = 1 << 30
+    if a.reference_kernels:
+        B.hmy_set_kernel_path(False)
+    st = TrainingState(cfg)
+    st.fill_random(0)
+    ids = synth.gen_tokens(cfg, 0)
+    tg = synth.gen_targets(cfg, ids, 0)
+    with Engine(st, cfg["budget"], cfg["M"], cfg["b"]) as eng:
+        eng.set_batch(ids, tg)
+        step = 1
+        for _ in range(a.warmup):
+            eng.step(step=step, want_stats=False)
+            step += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        stats = None
+        for _ in range(a.steps):
+            stats = eng.step(step=step, want_stats=True)   # returns with all streams idle
+            step += 1
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        # one more identical step with every GEMM launch bracketed by events on the compute stream
+        B.hmy_set_profiling(eng.handle, True)
+        prof = eng.step(step=step, want_stats=True)
+        B.hmy_set_profiling(eng.handle, False)
+        packs, arena = eng.packs, eng.arena
+
+    ms = dt / a.steps * 1e3
+    samples = cfg["M"] * cfg["b"]
+    gemm_flops = sum(prof["gemm_flops"])
+    gemm_s = sum(prof["gemm_s"])
+    dom = max(range(4), key=lambda i: prof["gemm_s"][i])
+    peak = PEAK_BF16_TFLOPS if cfg["precision"] == "bf16" else PEAK_FP32_TFLOPS
+    dom_tflops = prof["gemm_flops"][dom] / max(prof["gemm_s"][dom], 1e-12) / 1e12
+    h2d = sum(stats["h2d"].values())
+    d2h = sum(stats["d2h"].values())
+    copy_s = stats["t_h2d_busy_s"] + stats["t_d2h_busy_s"]
+    total_flops = gemm_flops + attention_flops(cfg, packs)
+    out = {
+        "metric": "samples/sec per iteration under HBM budget; swap GB/iter; MFMA util %",
+        "value": samples / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["precision"], "data": "synthetic",
+        "config": {"workload": f"{a.config}: {cfg['n_blocks']} blocks d={cfg['d_model']} heads={cfg['n_heads']} "
+                               f"ffn={cfg['d_ffn']} seq={cfg['seq_len']} vocab={cfg['vocab']}, "
+                               f"{cfg['M']} microbatches x {cfg['b']} sequences",
+                   "hbm_budget_bytes": cfg["budget"], "arena_bytes": arena["total"],
+                   "fwd_packs": packs[0], "bwd_packs": packs[1],
+                   "kernels": "reference" if a.reference_kernels else "mfma"},
+        "tflops": total_flops / (ms * 1e-3) / 1e12,
+        "swap": {"h2d_GB_per_iter": h2d / 1e9, "d2h_GB_per_iter": d2h / 1e9,
+                 "h2d_by_kind_GB": {k: v / 1e9 for k, v in stats["h2d"].items() if v},
+                 "d2h_by_kind_GB": {k: v / 1e9 for k, v in stats["d2h"].items() if v},
+                 "h2d_GBps_while_copying": h2d / 1e9 / max(stats["t_h2d_busy_s"], 1e-12),
+                 "d2h_GBps_while_copying": d2h / 1e9 / max(stats["t_d2h_busy_s"], 1e-12),
+                 "compute_stall_s": stats["t_stall_s"],
+                 "hidden_fraction": 1.0 - stats["t_stall_s"] / max(copy_s, 1e-12)},
+        "mfma_util_pct": 100.0 * gemm_flops / max(gemm_s, 1e-12) / 1e12 / peak,
+        "roofline": {"bound": "mfma", "kernel": VARIANTS[dom], "achieved": dom_tflops, "peak": peak,
+                     "unit": "TFLOP/s", "frac": dom_tflops / peak, "traffic": None,
+                     "launches": prof["gemm_calls"][dom],
+                     "avg_launch_us": prof["gemm_s"][dom] / max(prof["gemm_calls"][dom], 1) * 1e6,
+                     "all_variants_TFLOPs": [prof["gemm_flops"][i] / max(prof["gemm_s"][i], 1e-12) / 1e12
+                                             if prof["gemm_calls"][i] else None for i in range(4)]},
+        "loss": stats["loss"],
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -120,6 +120,11 @@ typedef struct hmy_stats {
   double t_d2h_busy_s;      /* sum of D2H copy durations (events)           */
   double t_stall_s;         /* time the compute stream spent waiting on swaps */
   uint64_t n_targets;
+  /* per GEMM kernel variant (index = 2*ta + tb): launches, algorithmic flops
+   * (2*M*N*K each) and, only while hmy_set_profiling is on, summed durations */
+  uint64_t gemm_calls[4];
+  double gemm_flops[4];
+  double gemm_s[4];
 } hmy_stats;
 
 typedef struct hmy_tensor_desc {
@@ -204,6 +209,9 @@ int hmy_bind_state(hmy_handle *h, const hmy_host_state *state);
  * counters.  Returns with all streams idle. */
 int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out);
 int hmy_destroy(hmy_handle *h);
+/* Bracket every GEMM launch of the next iterations with timing events (fills
+ * hmy_stats.gemm_s; costs two event records per launch).  Off by default. */
+int hmy_set_profiling(hmy_handle *h, int32_t on);
 
 /* 0 = reference kernels (plain tiled loops), 1 = MFMA kernels where they exist
  * (default).  Process-wide; for tests and A/B timing. */

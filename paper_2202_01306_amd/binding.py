@@ -66,7 +66,8 @@ class hmy_host_state(C.Structure):
 class hmy_stats(C.Structure):
     _fields_ = [("h2d", C.c_uint64 * HMY_NKINDS), ("d2h", C.c_uint64 * HMY_NKINDS), ("loss", C.c_double),
                 ("t_iter_s", C.c_double), ("t_compute_s", C.c_double), ("t_h2d_busy_s", C.c_double),
-                ("t_d2h_busy_s", C.c_double), ("t_stall_s", C.c_double), ("n_targets", C.c_uint64)]
+                ("t_d2h_busy_s", C.c_double), ("t_stall_s", C.c_double), ("n_targets", C.c_uint64),
+                ("gemm_calls", C.c_uint64 * 4), ("gemm_flops", C.c_double * 4), ("gemm_s", C.c_double * 4)]
 
 
 class hmy_tensor_desc(C.Structure):
@@ -95,7 +96,7 @@ class hmy_gemm_desc(C.Structure):
 EXPORTS = [
     "hmy_strerror", "hmy_last_error", "hmy_model_size", "hmy_layout", "hmy_profile", "hmy_plan", "hmy_arena",
     "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state",
-    "hmy_iteration", "hmy_destroy", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
+    "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
     "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
     "hmy_k_gemm", "hmy_k_attn_fwd", "hmy_k_attn_bwd", "hmy_k_xent", "hmy_k_adam",
 ]
@@ -183,7 +184,8 @@ def _stats_dict(st: hmy_stats):
     return dict(h2d={k: st.h2d[i] for i, k in enumerate(KIND_NAMES)},
                 d2h={k: st.d2h[i] for i, k in enumerate(KIND_NAMES)},
                 loss=st.loss, t_iter_s=st.t_iter_s, t_compute_s=st.t_compute_s, t_h2d_busy_s=st.t_h2d_busy_s,
-                t_d2h_busy_s=st.t_d2h_busy_s, t_stall_s=st.t_stall_s, n_targets=st.n_targets)
+                t_d2h_busy_s=st.t_d2h_busy_s, t_stall_s=st.t_stall_s, n_targets=st.n_targets,
+                gemm_calls=list(st.gemm_calls), gemm_flops=list(st.gemm_flops), gemm_s=list(st.gemm_s))
 
 
 def hmy_count_swaps(spec, sched, n_micro, micro_batch):
@@ -238,6 +240,10 @@ def hmy_iteration(h, n_micro, micro_batch, ids_ptr, targets_ptr, lr=1e-4, beta1=
 
 def hmy_destroy(h) -> None:
     _check(lib.hmy_destroy(h))
+
+
+def hmy_set_profiling(h, on: bool) -> None:
+    _check(lib.hmy_set_profiling(h, int(bool(on))))
 
 
 def _p(x):

@@ -65,6 +65,7 @@ struct hmy_handle {
   hmy_stats st{};
   int err = HMY_OK;
   bool timing = true;
+  bool profile_gemm = false;
 };
 
 #define HIPCHK(h, call)                                                                      \
@@ -192,6 +193,18 @@ hmy_gemm_desc gemm_desc(int prec, int M, int N, int K) {
   g.K = K;
   return g;
 }
+// every GEMM of the iteration goes through here: counts algorithmic flops per
+// kernel variant and, when profiling, brackets the launch with timing events
+void run_gemm(hmy_handle *h, const hmy_gemm_desc &g) {
+  const int variant = 2 * g.ta + g.tb;
+  h->st.gemm_calls[variant] += 1;
+  h->st.gemm_flops[variant] += 2.0 * g.M * g.N * g.K;
+  if (h->dry || h->err) return;
+  const size_t a = h->profile_gemm ? trec(h, h->s_comp) : size_t(-1);
+  KCHK(h, launch_gemm(g, h->s_comp));
+  const size_t b = h->profile_gemm ? trec(h, h->s_comp) : size_t(-1);
+  span(h, a, b, 10 + variant);
+}
 // C[M,N] = A[M,K] W[N,K]^T + bias (+ res)
 void linear_fwd(hmy_handle *h, const void *A, const void *W, const void *bias, const void *res, void *C,
                 void *gelu_out, int M, int N, int K) {
@@ -202,7 +215,7 @@ void linear_fwd(hmy_handle *h, const void *A, const void *W, const void *bias, c
   g.bias = bias;
   g.res = res; g.ldr = N;
   g.gelu_out = gelu_out;
-  KCHK(h, launch_gemm(g, h->s_comp));
+  run_gemm(h, g);
 }
 // dX[M,K] = dY[M,N] W[N,K];  dW[N,K] += dY^T X;  db[N] += colsum(dY)
 void linear_bwd(hmy_handle *h, const void *dY, const void *X, const void *W, void *dX, float *dW, float *db,
@@ -213,14 +226,14 @@ void linear_bwd(hmy_handle *h, const void *dY, const void *X, const void *W, voi
     g.A = dY; g.lda = N;
     g.B = W; g.ldb = K; g.tb = 1;
     g.C = dX; g.ldc = K;
-    KCHK(h, launch_gemm(g, h->s_comp));
+    run_gemm(h, g);
   }
   {
     hmy_gemm_desc g = gemm_desc(prec, N, K, M);
     g.A = dY; g.lda = N; g.ta = 1;
     g.B = X; g.ldb = K; g.tb = 1;
     g.C = dW; g.ldc = K; g.c_fp32 = 1; g.accumulate = 1;
-    KCHK(h, launch_gemm(g, h->s_comp));
+    run_gemm(h, g);
   }
   if (db) KCHK(h, launch_colsum(prec, dY, db, M, N, h->s_comp));
 }
@@ -309,7 +322,7 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
       g.A = zc; g.lda = d;
       g.B = wh; g.ldb = d;
       g.C = logits; g.ldc = ha.ldl; g.c_fp32 = 1;
-      KCHK(h, launch_gemm(g, h->s_comp));
+      run_gemm(h, g);
     }
     KCHK(h, launch_xent(prec, logits, tgt_dev(h, mb) + r0, loss_acc, dlogits, rows, V, ha.ldl, inv_ntgt, h->s_comp));
     {  // dz = dlogits Wh
@@ -317,14 +330,14 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
       g.A = dlogits; g.lda = ha.ldl;
       g.B = wh; g.ldb = d; g.tb = 1;
       g.C = dz + uint64_t(r0) * d * E; g.ldc = d;
-      KCHK(h, launch_gemm(g, h->s_comp));
+      run_gemm(h, g);
     }
     {  // dWh += dlogits^T z
       hmy_gemm_desc g = gemm_desc(prec, V, d, rows);
       g.A = dlogits; g.lda = ha.ldl; g.ta = 1;
       g.B = zc; g.ldb = d; g.tb = 1;
       g.C = g_wh; g.ldc = d; g.c_fp32 = 1; g.accumulate = 1;
-      KCHK(h, launch_gemm(g, h->s_comp));
+      run_gemm(h, g);
     }
   }
   KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, g_lnf_g, g_lnf_b, T, d, h->s_comp));
@@ -719,11 +732,18 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
       if (sp.what == 0) h->st.t_h2d_busy_s += sec;
       else if (sp.what == 1) h->st.t_d2h_busy_s += sec;
       else if (sp.what == 2) h->st.t_stall_s += sec;
-      else h->st.t_compute_s += sec;
+      else if (sp.what == 3) h->st.t_compute_s += sec;
+      else h->st.gemm_s[sp.what - 10] += sec;
     }
     *out = h->st;
   }
   return h->err;
+}
+
+int hmy_set_profiling(hmy_handle *h, int32_t on) {
+  if (!h) return fail(HMY_E_INVALID, "null handle");
+  h->profile_gemm = on != 0;
+  return HMY_OK;
 }
 
 int hmy_destroy(hmy_handle *h) {
