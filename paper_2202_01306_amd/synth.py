@@ -95,8 +95,9 @@ def gen_params(cfg, seed: int = 0, bench_init: bool = True) -> "OrderedDict[str,
     return out
 
 
-def gen_adam_state(cfg, seed: int, zero: bool = True):
-    """(m, v) per tensor: zeros (step 1) or a plausible mid-training state."""
+def gen_adam_state(cfg, seed: int, zero: bool = True, scale: float = 1e-2):
+    """(m, v) per tensor: zeros (step 1) or a mid-training state with first
+    moments N(0, scale^2) and second moments of matching size."""
     rng = np.random.default_rng(seed + 7919)
     m: "OrderedDict[str, np.ndarray]" = OrderedDict()
     v: "OrderedDict[str, np.ndarray]" = OrderedDict()
@@ -105,9 +106,9 @@ def gen_adam_state(cfg, seed: int, zero: bool = True):
             m[name] = np.zeros(shape, np.float32)
             v[name] = np.zeros(shape, np.float32)
         else:
-            m[name] = rng.standard_normal(shape, dtype=np.float32) * np.float32(1e-3)
-            v[name] = (rng.standard_normal(shape, dtype=np.float32) * np.float32(1e-3)) ** 2 \
-                + np.float32(1e-8)
+            m[name] = rng.standard_normal(shape, dtype=np.float32) * np.float32(scale)
+            v[name] = (rng.standard_normal(shape, dtype=np.float32) * np.float32(scale)) ** 2 \
+                + np.float32(scale * scale * 1e-2)
     return m, v
 
 

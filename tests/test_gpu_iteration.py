@@ -65,7 +65,8 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
         assert eng.arena["total"] <= budget
         eng.set_batch(ids, tg)
         for step in steps:
-            hp = om.AdamHP(lr=lr, beta1=0.9, beta2=0.999, eps=1e-8, step=step)
+            f32 = lambda x: float(np.float32(x))     # the C ABI carries fp32 hyper-parameters
+            hp = om.AdamHP(lr=f32(lr), beta1=f32(0.9), beta2=f32(0.999), eps=f32(1e-8), step=step)
             stats = eng.step(lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, step=step)
             loss, grads, w2, m2, v2 = oracle_step(cfg, master, m, v, ids, tg, hp)
             # counters: bit-exact against the closed form
@@ -80,8 +81,16 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
                 assert max_rel_err(g_gpu[k], grads[k]) < tol, ("grad", k)
             new_master = st.named("master" if st.mixed else "weights")
             for k in w2:
-                assert max_rel_err(new_master[k], w2[k]) < tol, ("weight", k)
-                if not zero_state:   # the update itself (zero state gives -lr*sign(g): not a parity quantity)
+                if zero_state:
+                    # step 1 from zero state moves every weight by lr*g/(|g|+eps): +-lr whatever |g| is, so
+                    # a gradient near zero may land on the other side; compare where the sign is decided
+                    d_gpu, d_ref = new_master[k] - master[k], w2[k] - master[k]
+                    assert np.abs(d_gpu).max() <= hp.lr * (1 + 1e-3)
+                    sure = np.abs(grads[k]) > 1e-2 * np.abs(grads[k]).max()
+                    assert np.abs(d_gpu - d_ref)[sure].max() < tol * hp.lr, ("update", k)
+                else:
+                    assert max_rel_err(new_master[k], w2[k]) < tol, ("weight", k)
+                    # the update itself: a much sharper check than the weights, which barely move
                     assert max_rel_err(new_master[k] - master[k], w2[k] - master[k]) < tol, ("update", k)
             if st.mixed:   # compute weights are exactly the rounded master
                 wq = st.named("weights")
@@ -142,7 +151,7 @@ def test_bf16_encoder_masked_targets_head_dim_32():
     say("bf16 encoder, 15% masked targets, head dim 32")
     cfg = tiny_cfg(n_blocks=2, d_model=64, n_heads=2, d_ffn=256, seq_len=96, vocab=777, causal=0, precision="bf16",
                    M=2, b=3)
-    run_and_compare(cfg, sched_ends=([1, 2], [1, 2, 3, 4]), zero_state=False, steps=(7,), weight_scale=3.0)
+    run_and_compare(cfg, sched_ends=([1, 3], [1, 2, 3, 4]), zero_state=False, steps=(7,), weight_scale=3.0)
 
 
 def test_bf16_reference_kernel_path_matches_too():
@@ -163,7 +172,7 @@ def test_gpt2_medium_width_reduced_depth():
     microbatches so the fp64 oracle finishes in about a minute."""
     say("gpt2-medium width, L=2, M=2")
     cfg = dict(synth.CONFIGS["gpt2m"], n_blocks=2, M=2)
-    run_and_compare(cfg, sched_ends=([1, 2], [1, 2, 3, 4]), zero_state=False, steps=(3,))
+    run_and_compare(cfg, sched_ends=([1, 2, 3], [1, 2, 3, 4]), zero_state=False, steps=(3,))
 
 
 def test_errors_from_the_engine():
@@ -198,7 +207,9 @@ def test_errors_from_the_engine():
 def test_full_size_gpt2_medium_properties():
     """The benchmark workload at full size, in the configuration bench.py times.
     The fp64 oracle cannot run it, so: counters equal the closed form exactly;
-    the loss at N(0, 0.02) init is ln(vocab) within 1%; the vocabulary-axis sum of
+    the loss at N(0, 0.02) init is ln(vocab) + d*0.02^2/2 within 1% (logits are
+    Gaussian with variance d*0.02^2 since the final LayerNorm output has unit
+    variance; E[logsumexp] of V such values is ln V + variance/2); the vocabulary-axis sum of
     the head gradient vanishes (softmax shift invariance); step-1 Adam from zero
     state moved every master weight by lr*g/(|g|+eps), recomputed from the
     returned gradients."""
@@ -218,7 +229,8 @@ def test_full_size_gpt2_medium_properties():
         assert eng.arena["total"] <= cfg["budget"]
     want = osw.closed_form(oracle_spec(cfg), P_F, P_B, cfg["M"], cfg["b"], "bf16")
     assert stats["h2d"] == want["h2d"] and stats["d2h"] == want["d2h"]
-    assert abs(stats["loss"] - math.log(cfg["vocab"])) < 0.01 * math.log(cfg["vocab"])
+    expect_loss = math.log(cfg["vocab"]) + 0.5 * cfg["d_model"] * 0.02 ** 2
+    assert abs(stats["loss"] - expect_loss) < 0.01 * expect_loss, (stats["loss"], expect_loss)
     g = st.grads
     assert torch.isfinite(g).all()
     lay = {t["name"]: t for t in st.layout}

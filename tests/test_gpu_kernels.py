@@ -294,7 +294,8 @@ def test_adam(prec, pc, dt, tol, step):
     g = rng.standard_normal(n).astype(np.float32) * 1e-3
     m0 = (rng.standard_normal(n).astype(np.float32) * 1e-3) if step > 1 else np.zeros(n, np.float32)
     v0 = ((rng.standard_normal(n).astype(np.float32) * 1e-3) ** 2) if step > 1 else np.zeros(n, np.float32)
-    hp = om.AdamHP(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, step=step)
+    f32 = lambda x: float(np.float32(x))     # the C ABI carries fp32 hyper-parameters
+    hp = om.AdamHP(lr=f32(1e-3), beta1=f32(0.9), beta2=f32(0.999), eps=f32(1e-8), step=step)
     wr, mr, vr = om.adam_update(w.astype(np.float64), g.astype(np.float64), m0.astype(np.float64),
                                 v0.astype(np.float64), hp)
     gd, md, vd = dev(g, torch.float32), dev(m0, torch.float32), dev(v0, torch.float32)
