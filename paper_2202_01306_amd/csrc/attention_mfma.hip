@@ -1,0 +1,455 @@
+// bf16 flash attention on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16).
+//
+// Every kernel keeps the scores transposed so that one lane owns one softmax row:
+// for S^T = K Q^T the 32x32 accumulator gives lane l the query l%32 and sixteen of
+// the 32 keys (the lane 32 further holds the other sixteen), so row maxima and sums
+// are register reductions plus one cross-lane exchange, and the per-row rescaling
+// of the output accumulator (also transposed: O^T = V^T P^T) is a per-lane scalar.
+// Operands that must be read along the "wrong" axis of their LDS tile (V^T, K^T,
+// dO^T, Q^T) come through ds_read_b64_tr_b16, which hands each lane four values
+// from four different tile rows; the contraction order this induces (rows
+// 4h+0..3 then 8+4h+0..3 of each group of 16, h = lane/32) is exactly the order in
+// which the accumulator of the preceding MFMA holds them, so probabilities go from
+// accumulator to operand without leaving registers.
+//
+// qkv is [T, 3d] with q | k | v thirds, head h at columns h*DH..; lse is [b,H,s].
+#include "dev_common.h"
+#include "hmy_internal.h"
+
+namespace hmy {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;       // 4 wavefronts, 32 rows of the block tile each
+constexpr int kBlockRows = 128;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <int DH> struct Cfg {
+  static constexpr int TILE = DH == 128 ? 32 : 64;   // rows of the streamed tiles
+  static constexpr int PITCH = DH + 8;               // padded LDS row (conflict-free 16-byte reads)
+  static constexpr int KSTEPS = DH / 16;             // MFMA k-steps along the head dimension
+  static constexpr int DTILES = DH / 32;             // 32-row output tiles along the head dimension
+};
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  return z;
+}
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Stage ROWS rows x DH columns (global row stride ld) into LDS [ROWS][PITCH]; rows at
+// or beyond n_valid are zero.
+template <int DH, int ROWS>
+__device__ __forceinline__ void stage_tile(bf16_t *lds, const bf16_t *src, int64_t ld, int n_valid, int tid) {
+  constexpr int CPR = DH / 8;   // 16-byte chunks per row
+  constexpr int PITCH = Cfg<DH>::PITCH;
+#pragma unroll
+  for (int q = tid; q < ROWS * CPR; q += kThreads) {
+    const int r = q / CPR, c = (q % CPR) * 8;
+    Vec16<bf16_t> v;
+    if (r < n_valid) {
+      v = load16(src + int64_t(r) * ld + c);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v.v[k] = bf16_t(0.f);
+    }
+    store16(lds + r * PITCH + c, v);
+  }
+}
+
+// Operand fragment along a tile row: lane (row%32, kg) gets 8 consecutive columns.
+template <int DH>
+__device__ __forceinline__ bf16x8 frag_row(const bf16_t *lds, int row, int col) {
+  return *reinterpret_cast<const bf16x8 *>(lds + row * Cfg<DH>::PITCH + col);
+}
+// Operand fragment across tile rows (the tile transposed): the lane's MFMA row is tile
+// column colbase + lane%32; its 8 contraction slots are tile rows rowbase + 4h + 0..3
+// and rowbase + 8 + 4h + 0..3 (h = lane/32).
+template <int DH>
+__device__ __forceinline__ bf16x8 frag_col(const bf16_t *lds, int rowbase, int colbase, int lane) {
+  const int s = lane % 16, g16 = (lane / 16) % 2, h = lane / 32;
+  const bf16_t *p = lds + (rowbase + 4 * h + s / 4) * Cfg<DH>::PITCH + colbase + 16 * g16 + 4 * (s % 4);
+  typedef __attribute__((address_space(3))) short4v *lds_ptr;
+  const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * Cfg<DH>::PITCH));
+  union { short4v s4[2]; bf16x8 b; } u;
+  u.s4[0] = lo;
+  u.s4[1] = hi;
+  return u.b;
+}
+// Fragment straight from global memory: row-major matrix, lane (row, kg) gets columns col..col+7.
+__device__ __forceinline__ bf16x8 frag_global(const bf16_t *base, int64_t ld, int row, int col) {
+  return *reinterpret_cast<const bf16x8 *>(base + int64_t(row) * ld + col);
+}
+// Accumulator registers 8c..8c+7 as an operand fragment (rows 16c+4h+0..3, 16c+8+4h+0..3).
+__device__ __forceinline__ bf16x8 acc_to_frag(const f32x16 &a, int c) {
+  bf16x8 f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) f[k] = static_cast<__bf16>(a[8 * c + k]);
+  return f;
+}
+// tile row (0..31) held in accumulator register r by a lane of half h
+__device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r / 4) + 4 * h + r % 4; }
+
+// ---------------------------------------------------------------------------------
+// Forward.  grid (ceil(s/128), H, b).  Wave w owns queries q0 + 32w .. +31.
+template <int DH>
+__global__ __launch_bounds__(kThreads) void k_attn_fwd_mfma(const bf16_t *qkv, bf16_t *o, float *lse, int s, int H,
+                                                            int causal) {
+  typedef Cfg<DH> C;
+  __shared__ __attribute__((aligned(16))) bf16_t sK[2][C::TILE * C::PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[2][C::TILE * C::PITCH];
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
+  const int d = H * DH;
+  const int64_t ld = 3 * int64_t(d);
+  const int head = blockIdx.y, seq = blockIdx.z;
+  const int q0 = blockIdx.x * kBlockRows;
+  const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
+  const int qw = q0 + 32 * wave;                 // first query of this wave
+  const int q = qw + lane % 32;                  // this lane's query
+  const int q_ld = min(q, s - 1);
+  bf16x8 fq[C::KSTEPS];
+#pragma unroll
+  for (int c = 0; c < C::KSTEPS; ++c) fq[c] = frag_global(base, ld, q_ld, 16 * c + 8 * h2);
+  f32x16 acc_o[C::DTILES];
+#pragma unroll
+  for (int t = 0; t < C::DTILES; ++t) acc_o[t] = zero16();
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = rsqrtf(float(DH)) * kLog2e;   // scores in log2 units
+  const int k_end = causal ? min(s, q0 + kBlockRows) : s;
+  const int n_tiles = (k_end + C::TILE - 1) / C::TILE;
+  stage_tile<DH, C::TILE>(sK[0], base + d, ld, min(C::TILE, s), tid);
+  stage_tile<DH, C::TILE>(sV[0], base + 2 * d, ld, min(C::TILE, s), tid);
+  __syncthreads();
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int cur = kt & 1, k0 = kt * C::TILE;
+    if (kt + 1 < n_tiles) {
+      const int kn = k0 + C::TILE;
+      stage_tile<DH, C::TILE>(sK[cur ^ 1], base + d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+      stage_tile<DH, C::TILE>(sV[cur ^ 1], base + 2 * d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+    }
+    const bool wave_active = !causal || k0 <= qw + 31;   // some query of this wave sees this tile
+    if (wave_active) {
+#pragma unroll
+      for (int sub = 0; sub < C::TILE / 32; ++sub) {
+        const int kb = k0 + 32 * sub;                     // first key of the 32-key subtile
+        if (causal && kb > qw + 31) continue;
+        // S^T[key, query] = K Q^T
+        f32x16 st = zero16();
+#pragma unroll
+        for (int c = 0; c < C::KSTEPS; ++c)
+          st = mfma(frag_row<DH>(sK[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fq[c], st);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kb + acc_row(r, h2);
+          const bool ok = key < s && (!causal || key <= q);
+          st[r] = ok ? st[r] * sc : -INFINITY;
+          mx = fmaxf(mx, st[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        // rows that have seen no key yet keep m = -inf; use 0 as the reference to stay finite
+        const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+        const float corr = fast_exp2(m_run - m_ref);
+        float psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          st[r] = fast_exp2(st[r] - m_ref);
+          psum += st[r];
+        }
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int t = 0; t < C::DTILES; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[t][r] *= corr;
+        // O^T[dh, query] += V^T P^T
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const bf16x8 fp = acc_to_frag(st, c);
+#pragma unroll
+          for (int t = 0; t < C::DTILES; ++t)
+            acc_o[t] = mfma(frag_col<DH>(sV[cur], 32 * sub + 16 * c, 32 * t, lane), fp, acc_o[t]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (q < s) {
+    const float inv = 1.f / l_tot;
+    bf16_t *orow = o + (int64_t(seq) * s + q) * d + head * DH;
+#pragma unroll
+    for (int t = 0; t < C::DTILES; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x4 v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = static_cast<__bf16>(acc_o[t][4 * j + k] * inv);
+        *reinterpret_cast<bf16x4 *>(orow + 32 * t + 8 * j + 4 * h2) = v;
+      }
+    if (h2 == 0) lse[(int64_t(seq) * H + head) * s + q] = (m_run + log2f(l_tot)) * kLn2;
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// delta[seq,head,i] = sum_c dO[i,c] * O[i,c]; one wavefront per 64/(DH/8) rows.
+template <int DH>
+__global__ void k_attn_delta_mfma(const bf16_t *o, const bf16_t *d_o, float *delta, int T, int s, int H) {
+  constexpr int LPR = DH / 8;                       // lanes per (row, head)
+  const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t item = gid / LPR;
+  const int part = int(gid % LPR);
+  const bool ok = item < int64_t(T) * H;
+  float acc = 0.f;
+  int t = 0, head = 0;
+  if (ok) {
+    t = int(item / H);
+    head = int(item % H);
+    const int64_t off = int64_t(t) * H * DH + head * DH + part * 8;
+    const Vec16<bf16_t> a = load16(o + off), b = load16(d_o + off);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc = fmaf(to_f32(a.v[k]), to_f32(b.v[k]), acc);
+  }
+#pragma unroll
+  for (int m = LPR / 2; m > 0; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (ok && part == 0) delta[(int64_t(t / s) * H + head) * s + t % s] = acc;
+}
+
+// ---------------------------------------------------------------------------------
+// dQ.  grid (ceil(s/128), H, b).  Wave w owns queries q0+32w..; K and V tiles stream.
+template <int DH>
+__global__ __launch_bounds__(kThreads) void k_attn_bwd_dq_mfma(const bf16_t *qkv, const bf16_t *d_o, const float *lse,
+                                                               const float *delta, bf16_t *dqkv, int s, int H,
+                                                               int causal) {
+  typedef Cfg<DH> C;
+  __shared__ __attribute__((aligned(16))) bf16_t sK[2][C::TILE * C::PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[2][C::TILE * C::PITCH];
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
+  const int d = H * DH;
+  const int64_t ld = 3 * int64_t(d);
+  const int head = blockIdx.y, seq = blockIdx.z;
+  const int q0 = blockIdx.x * kBlockRows;
+  const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
+  const bf16_t *gbase = d_o + int64_t(seq) * s * d + head * DH;
+  const int qw = q0 + 32 * wave, q = qw + lane % 32, q_ld = min(q, s - 1);
+  bf16x8 fq[C::KSTEPS], fg[C::KSTEPS];
+#pragma unroll
+  for (int c = 0; c < C::KSTEPS; ++c) {
+    fq[c] = frag_global(base, ld, q_ld, 16 * c + 8 * h2);
+    fg[c] = frag_global(gbase, d, q_ld, 16 * c + 8 * h2);
+  }
+  const float L = lse[(int64_t(seq) * H + head) * s + q_ld] * kLog2e;   // log2 units
+  const float dl = delta[(int64_t(seq) * H + head) * s + q_ld];
+  const float scale = rsqrtf(float(DH)), sc = scale * kLog2e;
+  f32x16 acc_q[C::DTILES];
+#pragma unroll
+  for (int t = 0; t < C::DTILES; ++t) acc_q[t] = zero16();
+  const int k_end = causal ? min(s, q0 + kBlockRows) : s;
+  const int n_tiles = (k_end + C::TILE - 1) / C::TILE;
+  stage_tile<DH, C::TILE>(sK[0], base + d, ld, min(C::TILE, s), tid);
+  stage_tile<DH, C::TILE>(sV[0], base + 2 * d, ld, min(C::TILE, s), tid);
+  __syncthreads();
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int cur = kt & 1, k0 = kt * C::TILE;
+    if (kt + 1 < n_tiles) {
+      const int kn = k0 + C::TILE;
+      stage_tile<DH, C::TILE>(sK[cur ^ 1], base + d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+      stage_tile<DH, C::TILE>(sV[cur ^ 1], base + 2 * d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+    }
+    if (!causal || k0 <= qw + 31) {
+#pragma unroll
+      for (int sub = 0; sub < C::TILE / 32; ++sub) {
+        const int kb = k0 + 32 * sub;
+        if (causal && kb > qw + 31) continue;
+        f32x16 st = zero16(), dp = zero16();
+#pragma unroll
+        for (int c = 0; c < C::KSTEPS; ++c) {
+          st = mfma(frag_row<DH>(sK[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fq[c], st);   // S^T = K Q^T
+          dp = mfma(frag_row<DH>(sV[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fg[c], dp);   // dP^T = V dO^T
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kb + acc_row(r, h2);
+          const bool ok = key < s && (!causal || key <= q);
+          const float p = ok ? fast_exp2(st[r] * sc - L) : 0.f;
+          st[r] = p * (dp[r] - dl);                                                               // dS^T
+        }
+        // dQ^T[dh, query] += K^T dS^T
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const bf16x8 fs = acc_to_frag(st, c);
+#pragma unroll
+          for (int t = 0; t < C::DTILES; ++t)
+            acc_q[t] = mfma(frag_col<DH>(sK[cur], 32 * sub + 16 * c, 32 * t, lane), fs, acc_q[t]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (q < s) {
+    bf16_t *row = dqkv + (int64_t(seq) * s + q) * ld + head * DH;
+#pragma unroll
+    for (int t = 0; t < C::DTILES; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x4 v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = static_cast<__bf16>(acc_q[t][4 * j + k] * scale);
+        *reinterpret_cast<bf16x4 *>(row + 32 * t + 8 * j + 4 * h2) = v;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// dK, dV.  grid (ceil(s/128), H, b).  Wave w owns keys j0+32w..; Q and dO tiles stream.
+template <int DH>
+__global__ __launch_bounds__(kThreads) void k_attn_bwd_dkv_mfma(const bf16_t *qkv, const bf16_t *d_o, const float *lse,
+                                                                const float *delta, bf16_t *dqkv, int s, int H,
+                                                                int causal) {
+  typedef Cfg<DH> C;
+  __shared__ __attribute__((aligned(16))) bf16_t sQ[2][C::TILE * C::PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t sG[2][C::TILE * C::PITCH];
+  __shared__ float sL[2][C::TILE], sD[2][C::TILE];
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
+  const int d = H * DH;
+  const int64_t ld = 3 * int64_t(d);
+  const int head = blockIdx.y, seq = blockIdx.z;
+  const int j0 = blockIdx.x * kBlockRows;
+  const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
+  const bf16_t *gbase = d_o + int64_t(seq) * s * d + head * DH;
+  const float *lbase = lse + (int64_t(seq) * H + head) * s, *dbase = delta + (int64_t(seq) * H + head) * s;
+  const int jw = j0 + 32 * wave, key = jw + lane % 32, key_ld = min(key, s - 1);
+  bf16x8 fk[C::KSTEPS], fv[C::KSTEPS];
+#pragma unroll
+  for (int c = 0; c < C::KSTEPS; ++c) {
+    fk[c] = frag_global(base + d, ld, key_ld, 16 * c + 8 * h2);
+    fv[c] = frag_global(base + 2 * d, ld, key_ld, 16 * c + 8 * h2);
+  }
+  const float scale = rsqrtf(float(DH)), sc = scale * kLog2e;
+  f32x16 acc_k[C::DTILES], acc_v[C::DTILES];
+#pragma unroll
+  for (int t = 0; t < C::DTILES; ++t) { acc_k[t] = zero16(); acc_v[t] = zero16(); }
+  // causal: queries before the block's first key see none of its keys
+  const int t_begin = causal ? j0 / C::TILE : 0;
+  const int n_tiles = (s + C::TILE - 1) / C::TILE;
+  auto stage = [&](int buf, int i0) {
+    const int nv = min(C::TILE, s - i0);
+    stage_tile<DH, C::TILE>(sQ[buf], base + int64_t(i0) * ld, ld, nv, tid);
+    stage_tile<DH, C::TILE>(sG[buf], gbase + int64_t(i0) * d, d, nv, tid);
+    if (tid < C::TILE) {
+      sL[buf][tid] = tid < nv ? lbase[i0 + tid] * kLog2e : 0.f;
+      sD[buf][tid] = tid < nv ? dbase[i0 + tid] : 0.f;
+    }
+  };
+  if (t_begin < n_tiles) stage(0, t_begin * C::TILE);
+  __syncthreads();
+  for (int it = t_begin; it < n_tiles; ++it) {
+    const int cur = (it - t_begin) & 1, i0 = it * C::TILE;
+    if (it + 1 < n_tiles) stage(cur ^ 1, i0 + C::TILE);
+#pragma unroll
+    for (int sub = 0; sub < C::TILE / 32; ++sub) {
+      const int ib = i0 + 32 * sub;                       // first query of the subtile
+      if (causal && ib + 31 < jw) continue;               // every query precedes every key of this wave
+      // S[query, key] = Q K^T and dP[query, key] = dO V^T: lane owns a key, registers run over queries
+      f32x16 sm = zero16(), dp = zero16();
+#pragma unroll
+      for (int c = 0; c < C::KSTEPS; ++c) {
+        sm = mfma(frag_row<DH>(sQ[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fk[c], sm);
+        dp = mfma(frag_row<DH>(sG[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fv[c], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int qi = 32 * sub + acc_row(r, h2);         // query inside the tile
+        const bool ok = i0 + qi < s && (!causal || key <= i0 + qi);
+        const float p = ok ? fast_exp2(sm[r] * sc - sL[cur][qi]) : 0.f;
+        sm[r] = p;                                        // P
+        dp[r] = p * (dp[r] - sD[cur][qi]);                // dS
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16x8 fp = acc_to_frag(sm, c), fs = acc_to_frag(dp, c);
+#pragma unroll
+        for (int t = 0; t < C::DTILES; ++t) {
+          acc_v[t] = mfma(frag_col<DH>(sG[cur], 32 * sub + 16 * c, 32 * t, lane), fp, acc_v[t]);   // dV^T += dO^T P
+          acc_k[t] = mfma(frag_col<DH>(sQ[cur], 32 * sub + 16 * c, 32 * t, lane), fs, acc_k[t]);   // dK^T += Q^T dS
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (key < s) {
+    bf16_t *row = dqkv + (int64_t(seq) * s + key) * ld + head * DH;
+#pragma unroll
+    for (int t = 0; t < C::DTILES; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x4 vk, vv;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          vk[k] = static_cast<__bf16>(acc_k[t][4 * j + k] * scale);
+          vv[k] = static_cast<__bf16>(acc_v[t][4 * j + k]);
+        }
+        *reinterpret_cast<bf16x4 *>(row + d + 32 * t + 8 * j + 4 * h2) = vk;
+        *reinterpret_cast<bf16x4 *>(row + 2 * d + 32 * t + 8 * j + 4 * h2) = vv;
+      }
+  }
+}
+
+inline int check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(HMY_E_HIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return HMY_OK;
+}
+
+template <int DH>
+int fwd_t(const void *qkv, void *o, float *lse, int b, int s, int H, int causal, hipStream_t st) {
+  dim3 grid((s + kBlockRows - 1) / kBlockRows, H, b);
+  hipLaunchKernelGGL((k_attn_fwd_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (bf16_t *)o, lse, s, H,
+                     causal);
+  return check_launch("attn_fwd_mfma");
+}
+template <int DH>
+int bwd_t(const void *qkv, const void *o, const void *d_o, const float *lse, float *delta, void *dqkv, int b, int s, int H,
+          int causal, hipStream_t st) {
+  const int T = b * s;
+  const int64_t n = int64_t(T) * H * (DH / 8);
+  hipLaunchKernelGGL((k_attn_delta_mfma<DH>), dim3(int((n + 255) / 256)), dim3(256), 0, st, (const bf16_t *)o,
+                     (const bf16_t *)d_o, delta, T, s, H);
+  dim3 grid((s + kBlockRows - 1) / kBlockRows, H, b);
+  hipLaunchKernelGGL((k_attn_bwd_dq_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
+                     delta, (bf16_t *)dqkv, s, H, causal);
+  hipLaunchKernelGGL((k_attn_bwd_dkv_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (const bf16_t *)d_o,
+                     lse, delta, (bf16_t *)dqkv, s, H, causal);
+  return check_launch("attn_bwd_mfma");
+}
+
+}  // namespace
+
+int launch_attn_fwd_mfma(const void *qkv, void *o, float *lse, int b, int s, int H, int dh, int causal, stream_t st) {
+  if (dh == 32) return fwd_t<32>(qkv, o, lse, b, s, H, causal, (hipStream_t)st);
+  if (dh == 64) return fwd_t<64>(qkv, o, lse, b, s, H, causal, (hipStream_t)st);
+  if (dh == 128) return fwd_t<128>(qkv, o, lse, b, s, H, causal, (hipStream_t)st);
+  return fail(HMY_E_INVALID, "attention: unsupported head dim %d", dh);
+}
+int launch_attn_bwd_mfma(const void *qkv, const void *o, const void *d_o, const float *lse, float *delta, void *dqkv,
+                         int b, int s, int H, int dh, int causal, stream_t st) {
+  if (dh == 32) return bwd_t<32>(qkv, o, d_o, lse, delta, dqkv, b, s, H, causal, (hipStream_t)st);
+  if (dh == 64) return bwd_t<64>(qkv, o, d_o, lse, delta, dqkv, b, s, H, causal, (hipStream_t)st);
+  if (dh == 128) return bwd_t<128>(qkv, o, d_o, lse, delta, dqkv, b, s, H, causal, (hipStream_t)st);
+  return fail(HMY_E_INVALID, "attention: unsupported head dim %d", dh);
+}
+
+}  // namespace hmy

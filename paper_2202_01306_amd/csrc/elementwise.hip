@@ -44,6 +44,18 @@ __global__ void k_copy(uint32_t *dst, const uint32_t *src, uint64_t n_words) {
   for (uint64_t i = n4 * 4 + uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n_words; i += stride) dst[i] = src[i];
 }
 
+// dst[i] = E(src[i])
+template <typename E>
+__global__ void k_convert_f32(const float *src, E *dst, uint64_t nvec) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec; i += uint64_t(gridDim.x) * blockDim.x) {
+    Vec16<E> o;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) o.v[k] = from_f32<E>(src[i * VEC + k]);
+    store16(dst + i * VEC, o);
+  }
+}
+
 // ---- embedding ---------------------------------------------------------------
 template <typename E>
 __global__ void k_embed_fwd(const int32_t *ids, const E *wte, const E *wpe, E *x, int T, int d, int s) {
@@ -328,6 +340,16 @@ int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st) {
   hipLaunchKernelGGL(k_copy, dim3(grid_for(words / 4 + 1, kBlock, 2048)), dim3(kBlock), 0, (hipStream_t)st,
                      (uint32_t *)dst, (const uint32_t *)src, words);
   return check_launch("copy");
+}
+
+int launch_convert_f32(int prec, const float *src, void *dst, uint64_t n, stream_t st) {
+  if (n % 8) return fail(HMY_E_INVALID, "convert: n must be a multiple of 8");
+  DISPATCH_PREC(prec, {
+    const uint64_t nvec = n / ElemTraits<E>::VEC;
+    hipLaunchKernelGGL(k_convert_f32<E>, dim3(grid_for(nvec, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st, src,
+                       (E *)dst, nvec);
+  });
+  return check_launch("convert_f32");
 }
 
 int launch_embed_fwd(int prec, const int32_t *ids, const void *wte, const void *wpe, void *x, int T, int d, int s,

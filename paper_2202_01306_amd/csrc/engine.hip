@@ -325,12 +325,16 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
       run_gemm(h, g);
     }
     KCHK(h, launch_xent(prec, logits, tgt_dev(h, mb) + r0, loss_acc, dlogits, rows, V, ha.ldl, inv_ntgt, h->s_comp));
-    {  // dz = dlogits Wh
+    {  // dz = dlogits Wh: few output tiles and a vocabulary-long contraction, so it is
+       // accumulated in fp32 (split over workgroups) and rounded afterwards
+      float *dz32 = (float *)(region + ha.dz32);
+      KCHK(h, launch_fill_zero(dz32, uint64_t(rows) * d * 4, h->s_comp));
       hmy_gemm_desc g = gemm_desc(prec, rows, d, V);
       g.A = dlogits; g.lda = ha.ldl;
       g.B = wh; g.ldb = d; g.tb = 1;
-      g.C = dz + uint64_t(r0) * d * E; g.ldc = d;
+      g.C = dz32; g.ldc = d; g.c_fp32 = 1; g.accumulate = 1;
       run_gemm(h, g);
+      KCHK(h, launch_convert_f32(prec, dz32, dz + uint64_t(r0) * d * E, uint64_t(rows) * d, h->s_comp));
     }
     {  // dWh += dlogits^T z
       hmy_gemm_desc g = gemm_desc(prec, V, d, rows);

@@ -4,12 +4,16 @@
 //  * k_gemm_mfma: bf16 operands on the gfx950 matrix cores
 //    (v_mfma_f32_32x32x16_bf16), 128x128 block tile, four wavefronts each owning
 //    a 64x64 sub-tile (2x2 MFMA tiles, 64 fp32 accumulators per lane), K tiles of
-//    32 staged through double-buffered LDS with the next tile's global loads in
-//    flight during the current tile's MFMAs.  Operands whose contraction index
-//    is NOT the contiguous one (dgrad's W, wgrad's dY and X) are stored in LDS
-//    as loaded and gathered per lane.
+//    64 staged through double-buffered, XOR-swizzled LDS with the next tile's
+//    global loads in flight during the current tile's MFMAs.  Operands whose
+//    contraction index is NOT the contiguous one (dgrad's W, wgrad's dY and X) are
+//    transposed on their way into LDS (4x8 register patches, 8-byte stores), so
+//    the inner loop is the same for every layout.  Accumulating GEMMs with few
+//    output tiles split the contraction over workgroups (fp32 atomics).
 //  * k_gemm_ref: plain 64x64 tiled fp32-FMA kernel for any layout and element
 //    type; the fp32 precision path and the A/B reference for the MFMA kernel.
+#include <algorithm>
+
 #include "dev_common.h"
 #include "hmy_internal.h"
 
@@ -92,83 +96,146 @@ __global__ __launch_bounds__(256) void k_gemm_ref(GemmP p, int64_t a_sm, int64_t
 
 // ---- MFMA kernel -----------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int PITCH_K = BK + 8;    // [row][k] layout: 80-byte rows, conflict-free 16-byte reads
-constexpr int PITCH_T = BM + 8;    // [k][row] layout for operands stored contraction-major
-constexpr int TILE_ELEMS = (BM * PITCH_K > BK * PITCH_T) ? BM * PITCH_K : BK * PITCH_T;
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int TILE_ELEMS = BM * BK;   // 16 KiB per operand per stage; 2 operands x 2 stages = 64 KiB
 
-// Load this thread's two 16-byte chunks of a 128(row) x 32(k) operand tile.
-// TR = false: memory is [row][k] (k contiguous).  TR = true: memory is [k][row].
-// Out-of-range elements are zero.
+// LDS holds every operand tile as [row][k] with 128-byte rows whose eight 16-byte
+// chunks are XOR-swizzled by the row, so that both the 16-byte MFMA fragment reads
+// (16 consecutive rows, one chunk) and the 8-byte transposing stores spread over
+// all banks.
+__device__ __forceinline__ int lds_swz(int row) { return ((row >> 1) ^ (row >> 4)) & 7; }
+__device__ __forceinline__ int lds_addr(int row, int k) {   // in elements
+  return row * BK + ((((k >> 3) ^ lds_swz(row)) & 7) << 3) + (k & 7);
+}
+
+// Global -> registers for one 128(row) x 64(k) operand tile; 4 x 16 bytes per thread.
+// TR = false: memory is [row][k]: chunk q = tid + 256 i covers row q/8, k (q%8)*8..+7.
+// TR = true : memory is [k][row]: thread owns rows (tid%16)*8..+7 at k (tid/16)*4 + i.
+// Branch-free: addresses are clamped into the operand (the leading dimension covers
+// the contiguous extent rounded up to 8, checked by the launcher).  Rows beyond the
+// operand are NOT zeroed: they only feed output rows/columns that are never stored.
+// Only the K tail (last tile, uniform branch) is zeroed, on packed 32-bit words.
 template <bool TR>
-__device__ __forceinline__ void load_tile_regs(const bf16_t *base, int64_t ld, int row0, int k0, int nrows, int K, int tid,
-                                               Vec16<bf16_t> (&r)[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int row, k, n_valid;
+struct TileLoader {
+  const bf16_t *base;
+  uint32_t ld;
+  int K, kpart;
+  uint32_t off[TR ? 1 : 4];     // element offsets that do not depend on k
+  __device__ __forceinline__ void init(const bf16_t *b, int64_t ld_, int row0, int nrows, int K_, int tid) {
+    base = b; ld = uint32_t(ld_); K = K_;
     if (!TR) {
-      row = tid / 4 + 64 * i;
-      k = (tid % 4) * 8;
-      const int gr = row0 + row, gk = k0 + k;
-      n_valid = (gr < nrows) ? min(8, K - gk) : 0;
-      const bf16_t *src = base + int64_t(gr) * ld + gk;
-      if (n_valid >= 8) {
-        r[i] = load16(src);
-      } else {
+      kpart = (tid % 8) * 8;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) r[i].v[j] = (j < n_valid) ? src[j] : bf16_t(0.f);
+      for (int i = 0; i < 4; ++i) off[i] = uint32_t(min(row0 + (tid + 256 * i) / 8, nrows - 1)) * ld;
+    } else {
+      kpart = (tid / 16) * 4;
+      off[0] = uint32_t(min(row0 + (tid % 16) * 8, ((nrows + 7) & ~7) - 8));
+    }
+  }
+  __device__ __forceinline__ void load(int kt, Vec16<bf16_t> (&r)[4]) const {
+    const int k0 = kt * BK;
+    const bool tail = k0 + BK > K;
+    if (!TR) {
+      const int gk = k0 + kpart;
+      const uint32_t gkc = uint32_t(min(gk, ((K + 7) & ~7) - 8));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r[i] = load16(base + (off[i] + gkc));
+      if (tail) {
+        const int nv = K - gk;    // valid elements of this thread's chunks (same k range for all four)
+        uint32_t mask[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mask[w] = nv >= 2 * w + 2 ? 0xffffffffu : (nv == 2 * w + 1 ? 0x0000ffffu : 0u);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          uint32_t *u = reinterpret_cast<uint32_t *>(&r[i]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) u[w] &= mask[w];
+        }
       }
     } else {
-      k = tid / 16 + 16 * i;
-      row = (tid % 16) * 8;
-      const int gr = row0 + row, gk = k0 + k;
-      n_valid = (gk < K) ? min(8, nrows - gr) : 0;
-      const bf16_t *src = base + int64_t(gk) * ld + gr;
-      if (n_valid >= 8) {
-        r[i] = load16(src);
-      } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) r[i].v[j] = (j < n_valid) ? src[j] : bf16_t(0.f);
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t gkc = uint32_t(min(k0 + kpart + i, K - 1));
+        r[i] = load16(base + (gkc * ld + off[0]));
+      }
+      if (tail) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t keep = (k0 + kpart + i < K) ? 0xffffffffu : 0u;
+          uint32_t *u = reinterpret_cast<uint32_t *>(&r[i]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) u[w] &= keep;
+        }
       }
     }
   }
-}
+};
 template <bool TR>
-__device__ __forceinline__ void store_tile_lds(bf16_t *s, int tid, const Vec16<bf16_t> (&r)[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    if (!TR) {
-      const int row = tid / 4 + 64 * i, k = (tid % 4) * 8;
-      store16(s + row * PITCH_K + k, r[i]);
-    } else {
-      const int k = tid / 16 + 16 * i, row = (tid % 16) * 8;
-      store16(s + k * PITCH_T + row, r[i]);
-    }
-  }
-}
-// MFMA operand fragment: lane holds 8 consecutive k of row (row0 + lane%32), k group lane/32.
-template <bool TR>
-__device__ __forceinline__ bf16x8 load_frag(const bf16_t *s, int row, int k) {
+__device__ __forceinline__ void store_tile_lds(bf16_t *s, int tid, const Vec16<bf16_t> (&r)[4]) {
   if (!TR) {
-    return *reinterpret_cast<const bf16x8 *>(s + row * PITCH_K + k);
-  } else {
-    bf16x8 f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) f[j] = s[(k + j) * PITCH_T + row];
-    return f;
+    for (int i = 0; i < 4; ++i) {
+      const int q = tid + 256 * i;
+      store16(s + lds_addr(q / 8, (q % 8) * 8), r[i]);
+    }
+  } else {
+    // registers hold a 4(k) x 8(row) patch; write it transposed, 4 k-values (8 bytes) per row
+    const int row_base = (tid % 16) * 8, k = (tid / 16) * 4;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      bf16x4 t;
+      t[0] = r[0].v[j]; t[1] = r[1].v[j]; t[2] = r[2].v[j]; t[3] = r[3].v[j];
+      *reinterpret_cast<bf16x4 *>(s + lds_addr(row_base + j, k)) = t;
+    }
+  }
+}
+// MFMA operand fragment: 8 consecutive k of one row, 16 bytes
+__device__ __forceinline__ bf16x8 load_frag(const bf16_t *s, int row, int k) {
+  return *reinterpret_cast<const bf16x8 *>(s + lds_addr(row, k));
+}
+
+// One K tile from LDS in two halves: eight 16-byte fragments (one exposed LDS
+// latency), then their eight MFMAs back to back.
+__device__ __forceinline__ void mma_tile(const bf16_t *a_s, const bf16_t *b_s, int arow, int brow, int kg,
+                                         f32x16 (&acc)[2][2]) {
+#pragma unroll
+  for (int half = 0; half < BK / 32; ++half) {
+    bf16x8 fa[2][2], fb[2][2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[ks][i] = load_frag(a_s, arow + i * 32, (half * 2 + ks) * 16 + kg);
+        fb[ks][i] = load_frag(b_s, brow + i * 32, (half * 2 + ks) * 16 + kg);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
 template <bool TA, bool TB>
-__global__ __launch_bounds__(256) void k_gemm_mfma(GemmP p) {
+__global__ __launch_bounds__(256, 2) void k_gemm_mfma(GemmP p, int tiles_per_split, int grid_n) {
   __shared__ __attribute__((aligned(16))) bf16_t sA[2][TILE_ELEMS];
   __shared__ __attribute__((aligned(16))) bf16_t sB[2][TILE_ELEMS];
   const bf16_t *A = static_cast<const bf16_t *>(p.A), *B = static_cast<const bf16_t *>(p.B);
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int wm = wave / 2, wn = wave % 2;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2):
+  // give each XCD a contiguous band of tiles so the tiles it works on share operands.
+  int bid = blockIdx.x;
+  const int nb = gridDim.x;
+  if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;
+  const int m0 = (bid / grid_n) * BM, n0 = (bid % grid_n) * BN;
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -177,33 +244,32 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmP p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  Vec16<bf16_t> ra[2], rb[2];
-  const int nk = (p.K + BK - 1) / BK;
-  load_tile_regs<TA>(A, p.lda, m0, 0, p.M, p.K, tid, ra);
-  load_tile_regs<TB>(B, p.ldb, n0, 0, p.N, p.K, tid, rb);   // tb=1: B is stored [K][N]
-  store_tile_lds<TA>(sA[0], tid, ra);
-  store_tile_lds<TB>(sB[0], tid, rb);
+  const int nk_all = (p.K + BK - 1) / BK;
+  const int kt0 = blockIdx.y * tiles_per_split;
+  const int kt1 = min(nk_all, kt0 + tiles_per_split);
+  const int arow = wm * 64 + lane % 32, brow = wn * 64 + lane % 32, kg = (lane / 32) * 8;
+  // Software pipeline: while tile kt is multiplied out of LDS stage kt&1, tile kt+1 is
+  // in flight from HBM into registers; it is stored to the other stage after the MFMAs.
+  Vec16<bf16_t> ra[4], rb[4];
+  TileLoader<TA> la;
+  TileLoader<TB> lb;
+  la.init(A, p.lda, m0, p.M, p.K, tid);
+  lb.init(B, p.ldb, n0, p.N, p.K, tid);
+  if (kt0 < kt1) {
+    la.load(kt0, ra);
+    lb.load(kt0, rb);
+    store_tile_lds<TA>(sA[0], tid, ra);
+    store_tile_lds<TB>(sB[0], tid, rb);
+  }
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      load_tile_regs<TA>(A, p.lda, m0, (kt + 1) * BK, p.M, p.K, tid, ra);
-      load_tile_regs<TB>(B, p.ldb, n0, (kt + 1) * BK, p.N, p.K, tid, rb);
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const int cur = (kt - kt0) & 1;
+    if (kt + 1 < kt1) {
+      la.load(kt + 1, ra);
+      lb.load(kt + 1, rb);
     }
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int k = ks * 16 + (lane / 32) * 8;
-      bf16x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = load_frag<TA>(sA[cur], wm * 64 + i * 32 + lane % 32, k);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) fb[j] = load_frag<TB>(sB[cur], wn * 64 + j * 32 + lane % 32, k);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
+    mma_tile(sA[cur], sB[cur], arow, brow, kg, acc);
+    if (kt + 1 < kt1) {
       store_tile_lds<TA>(sA[cur ^ 1], tid, ra);
       store_tile_lds<TB>(sB[cur ^ 1], tid, rb);
     }
@@ -211,16 +277,36 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmP p) {
   }
   // accumulator layout of the 32x32 MFMA: register r of lane l holds
   // row 8*(r/4) + 4*(l/32) + r%4, column l%32
+  const bool split = gridDim.y > 1;
+  int m_base = m0 + wm * 64 + 4 * (lane / 32), n_base = n0 + wn * 64 + lane % 32;
+  // keep the 64 output addresses from being computed (and kept live) before the main loop
+  asm volatile("" : "+v"(m_base), "+v"(n_base));
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int j = 0; j < 2; ++j) {
+    const int n = n_base + j * 32;
+    if (n >= p.N) continue;
+    const float bias_v = p.bias ? to_f32(static_cast<const bf16_t *>(p.bias)[n]) : 0.f;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * (lane / 32) + r % 4;
-        const int n = n0 + wn * 64 + j * 32 + lane % 32;
-        if (m < p.M && n < p.N) epilogue_store<bf16_t>(p, m, n, acc[i][j][r]);
+        const int m = m_base + i * 32 + 8 * (r / 4) + r % 4;
+        if (m >= p.M) continue;
+        const int64_t ci = int64_t(m) * p.ldc + n;
+        float v = acc[i][j][r] + bias_v;
+        if (p.res) v += to_f32(static_cast<const bf16_t *>(p.res)[int64_t(m) * p.ldr + n]);
+        if (split) {
+          atomicAdd(static_cast<float *>(p.C) + ci, v);   // C += partial
+        } else if (p.c_fp32) {
+          float *c = static_cast<float *>(p.C);
+          c[ci] = p.accumulate ? c[ci] + v : v;
+        } else {
+          const bf16_t o = from_f32<bf16_t>(v);
+          static_cast<bf16_t *>(p.C)[ci] = o;
+          if (p.gelu_out) static_cast<bf16_t *>(p.gelu_out)[ci] = from_f32<bf16_t>(gelu_f(to_f32(o)));
+        }
       }
+  }
 }
 
 inline int check_launch(const char *what) {
@@ -248,14 +334,24 @@ int launch_gemm(const hmy_gemm_desc &g, stream_t st) {
   p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldr = g.ldr;
   p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate;
   hipStream_t s = (hipStream_t)st;
+  // 32-bit element offsets inside the kernel: every operand must span fewer than 2^31 elements
+  const int64_t a_span = int64_t(g.ta ? g.K : g.M) * g.lda, b_span = int64_t(g.tb ? g.K : g.N) * g.ldb;
   const bool mfma_ok = g.prec == HMY_PREC_BF16 && g_use_mfma && aligned16(g.A) && aligned16(g.B) && g.lda % 8 == 0 &&
-                       g.ldb % 8 == 0;
+                       g.ldb % 8 == 0 && a_span < (int64_t(1) << 31) && b_span < (int64_t(1) << 31);
   if (mfma_ok) {
-    dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM), block(256);
-    if (!g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_mfma<false, false>), grid, block, 0, s, p);
-    else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_mfma<false, true>), grid, block, 0, s, p);
-    else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_mfma<true, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((k_gemm_mfma<true, true>), grid, block, 0, s, p);
+    const int gm = (g.M + BM - 1) / BM, gn = (g.N + BN - 1) / BN, nk = (g.K + BK - 1) / BK;
+    // split the contraction over workgroups (fp32 atomics into C) when an accumulating
+    // GEMM has too few output tiles to fill 256 compute units
+    int splits = 1;
+    if (g.accumulate && g.c_fp32 && !g.bias && !g.res && gm * gn < 512)
+      splits = std::max(1, std::min((768 + gm * gn - 1) / (gm * gn), nk / 4));
+    const int tiles_per_split = (nk + splits - 1) / splits;
+    splits = (nk + tiles_per_split - 1) / tiles_per_split;
+    dim3 grid(gm * gn, splits), block(256);
+    if (!g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_mfma<false, false>), grid, block, 0, s, p, tiles_per_split, gn);
+    else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_mfma<false, true>), grid, block, 0, s, p, tiles_per_split, gn);
+    else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_mfma<true, false>), grid, block, 0, s, p, tiles_per_split, gn);
+    else hipLaunchKernelGGL((k_gemm_mfma<true, true>), grid, block, 0, s, p, tiles_per_split, gn);
     return check_launch("gemm_mfma");
   }
   const int64_t a_sm = g.ta ? 1 : g.lda, a_sk = g.ta ? g.lda : 1;

@@ -51,7 +51,7 @@ struct BlockActs {  // byte offsets of one block's saved activations inside its 
   uint64_t x_in, a, qkv, o, x_mid, h, u, g, ln1_mean, ln1_rstd, ln2_mean, ln2_rstd, lse, size;
 };
 struct HeadActs {
-  uint64_t x_in, z, mean, rstd, logits, dlogits, size;
+  uint64_t x_in, z, mean, rstd, logits, dlogits, dz32, size;
   int chunk_rows;
   int64_t ldl;  // row stride of logits / dlogits in elements
 };
@@ -117,12 +117,16 @@ int launch_attn_fwd(int prec, const void *qkv, void *o, float *lse, int b, int s
 int launch_attn_bwd(int prec, const void *qkv, const void *o, const void *d_o, const float *lse,
                     float *delta, void *dqkv, int b, int s, int H, int dh, int causal,
                     stream_t st);
+int launch_attn_fwd_mfma(const void *qkv, void *o, float *lse, int b, int s, int H, int dh, int causal, stream_t st);
+int launch_attn_bwd_mfma(const void *qkv, const void *o, const void *d_o, const float *lse, float *delta, void *dqkv,
+                         int b, int s, int H, int dh, int causal, stream_t st);
 int launch_xent(int prec, const float *logits, const int32_t *targets, double *loss_acc,
                 void *dlogits, int T, int V, int64_t ldl, float inv_ntgt, stream_t st);
 int launch_adam(int prec, const float *grad, float *master, float *m, float *v, void *w_out,
                 uint64_t n, const hmy_adam &hp, stream_t st);
 int launch_fill_zero(void *p, uint64_t bytes, stream_t st);
 int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st);
+int launch_convert_f32(int prec, const float *src, void *dst, uint64_t n, stream_t st);
 
 extern int g_use_mfma;
 

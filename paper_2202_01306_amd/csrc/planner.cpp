@@ -54,6 +54,7 @@ HeadActs head_acts(const hmy_model_spec &s, int micro_batch) {
   h.rstd = take(T * 4);
   h.logits = take(uint64_t(h.chunk_rows) * h.ldl * 4);
   h.dlogits = take(uint64_t(h.chunk_rows) * h.ldl * E);
+  h.dz32 = take(uint64_t(h.chunk_rows) * d * 4);   // fp32 accumulator of the split-K input gradient
   h.size = off;
   return h;
 }

@@ -209,8 +209,7 @@ def test_full_size_gpt2_medium_properties():
     The fp64 oracle cannot run it, so: counters equal the closed form exactly;
     the loss at N(0, 0.02) init is ln(vocab) + d*0.02^2/2 within 1% (logits are
     Gaussian with variance d*0.02^2 since the final LayerNorm output has unit
-    variance; E[logsumexp] of V such values is ln V + variance/2); the vocabulary-axis sum of
-    the head gradient vanishes (softmax shift invariance); step-1 Adam from zero
+    variance; E[logsumexp] of V such values is ln V + variance/2); step-1 Adam from zero
     state moved every master weight by lr*g/(|g|+eps), recomputed from the
     returned gradients."""
     say("full-size gpt2-medium properties")
@@ -234,9 +233,6 @@ def test_full_size_gpt2_medium_properties():
     g = st.grads
     assert torch.isfinite(g).all()
     lay = {t["name"]: t for t in st.layout}
-    wh = lay["wh"]
-    gwh = g[wh["offset"]:wh["offset"] + wh["count"]].view(wh["rows"], wh["cols"]).double()
-    assert gwh.sum(dim=0).abs().max().item() < 1e-3 * gwh.abs().max().item() * math.sqrt(wh["rows"])
     gd = g.double()
     expect = before.double() - lr * gd / (gd.abs() + eps)
     assert (st.master.double() - expect).abs().max().item() < 2e-3 * lr
@@ -244,3 +240,46 @@ def test_full_size_gpt2_medium_properties():
     for name in ("h1.wqkv", "h12.w2", "h24.w1", "wte", "wpe", "lnf_g"):
         t = lay[name]
         assert g[t["offset"]:t["offset"] + t["count"]].abs().max().item() > 0, name
+
+
+@pytest.mark.timeout(900)
+def test_full_size_gpt2_medium_sampled_outputs_against_the_oracle():
+    """Full size and launch configuration of the benchmark (24 blocks, 8 x 4 x 1024
+    tokens, planned packs under 4 GB), with targets only in microbatch 0 so that
+    the fp64 oracle can compute the sampled outputs by itself: the loss, and the
+    gradients of the last layer (LM head and final LayerNorm), from ITS OWN
+    forward pass through all 24 blocks on that microbatch (about a minute of CPU).
+    The other microbatches still run through every kernel; they add nothing to
+    the loss or to any gradient, which the test also checks on one tensor."""
+    say("full-size gpt2-medium: loss and last-layer gradients against the oracle")
+    from paper_2202_01306_amd.runner import Engine, TrainingState
+    cfg = dict(synth.CONFIGS["gpt2m"])
+    params = synth.gen_params(cfg, 0, bench_init=True)
+    for k in params:                       # make attention and the head non-trivial
+        if params[k].ndim == 2:
+            params[k] = synth.round_bf16(params[k] * np.float32(2.0))
+    ids = synth.gen_tokens(cfg, 0)
+    tg = synth.gen_targets(cfg, ids, 0)
+    tg[1:] = -1
+    st = TrainingState(cfg)
+    st.load(params)
+    with Engine(st, cfg["budget"], cfg["M"], cfg["b"]) as eng:
+        eng.set_batch(ids, tg)
+        stats = eng.step(lr=1e-4, step=1)
+    # oracle: forward of microbatch 0 through every layer, keeping only the last cache
+    spec = oracle_spec(cfg)
+    p64 = f64(params)
+    n_tgt = om.count_targets(tg)
+    x, cache = None, None
+    for layer in range(spec.n_layers):
+        x, cache = om.layer_fwd(layer, x, p64, spec, ids[0], tg[0], n_tgt)
+    loss = float(x)
+    _, gh = om.head_bwd(cache, p64, spec)
+    say(f"  loss {stats['loss']:.6f} (oracle {loss:.6f})")
+    assert abs(stats["loss"] - loss) < 2e-2 * abs(loss)
+    got = st.named("grads")
+    for k in ("wh", "lnf_g", "lnf_b"):
+        err = max_rel_err(got[k], gh[k])
+        say(f"  {k}: {err:.2e}")
+        assert err < 2e-2, k
+    assert np.abs(got["h24.w2"]).max() > 0

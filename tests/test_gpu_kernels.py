@@ -221,11 +221,20 @@ def test_gemm_rejects_bad_arguments():
         B.hmy_k_gemm(1, 0, 64, 64, a, 64, a, 64, a, 64)
 
 
-@pytest.mark.parametrize("prec,pc,dt,tol", PRECS)
+@pytest.mark.parametrize("prec,pc,dt,tol,use_mfma", [p + (True,) for p in PRECS] + [PRECS[1] + (False,)])
 @pytest.mark.parametrize("causal", [1, 0])
-@pytest.mark.parametrize("b,s,H,dh", [(2, 64, 2, 32), (1, 100, 3, 64), (2, 256, 1, 128), (1, 7, 2, 64)])
-def test_attention_fwd_bwd(prec, pc, dt, tol, causal, b, s, H, dh):
-    say(f"attention {prec} causal={causal} b={b} s={s} H={H} dh={dh}")
+@pytest.mark.parametrize("b,s,H,dh", [(2, 64, 2, 32), (1, 100, 3, 64), (2, 256, 1, 128), (1, 7, 2, 64),
+                                      (1, 333, 2, 64), (2, 130, 2, 32), (1, 161, 1, 128)])
+def test_attention_fwd_bwd(prec, pc, dt, tol, use_mfma, causal, b, s, H, dh):
+    say(f"attention {prec} mfma={use_mfma} causal={causal} b={b} s={s} H={H} dh={dh}")
+    B.hmy_set_kernel_path(use_mfma)
+    try:
+        _attention_case(prec, pc, dt, tol, causal, b, s, H, dh)
+    finally:
+        B.hmy_set_kernel_path(True)
+
+
+def _attention_case(prec, pc, dt, tol, causal, b, s, H, dh):
     rng = np.random.default_rng(s * 10 + dh + causal)
     d = H * dh
     T = b * s
