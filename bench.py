@@ -163,6 +163,11 @@ def main() -> int:
                  "d2h_GBps_while_copying": d2h / 1e9 / max(stats["t_d2h_busy_s"], 1e-12),
                  "compute_stall_s": stats["t_stall_s"],
                  "hidden_fraction": 1.0 - stats["t_stall_s"] / max(copy_s, 1e-12)},
+        "timeline_ms": {"iteration_host_clock": stats["t_iter_s"] * 1e3,
+                        "compute_stream_first_to_last_kernel": stats["t_compute_s"] * 1e3,
+                        "compute_stream_waiting_on_swaps": stats["t_stall_s"] * 1e3,
+                        "outside_compute_span(prologue+epilogue)": (stats["t_iter_s"] - stats["t_compute_s"]) * 1e3,
+                        "h2d_copy_busy": stats["t_h2d_busy_s"] * 1e3, "d2h_copy_busy": stats["t_d2h_busy_s"] * 1e3},
         "mfma_util_pct": 100.0 * gemm_flops / max(gemm_s, 1e-12) / 1e12 / peak,
         "roofline": {"bound": "mfma", "kernel": VARIANTS[dom], "achieved": dom_tflops, "peak": peak,
                      "unit": "TFLOP/s", "frac": dom_tflops / peak, "traffic": None,

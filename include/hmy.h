@@ -214,7 +214,8 @@ int hmy_destroy(hmy_handle *h);
 int hmy_set_profiling(hmy_handle *h, int32_t on);
 
 /* 0 = reference kernels (plain tiled loops), 1 = MFMA kernels where they exist
- * (default).  Process-wide; for tests and A/B timing. */
+ * (default), 2 = MFMA kernels but never the 256x256-tile GEMM.  Process-wide; for
+ * tests and A/B timing. */
 int hmy_set_kernel_path(int32_t use_mfma);
 
 /* ---- single kernels (all pointers DEVICE, stream = hipStream_t or NULL) ---

@@ -194,8 +194,9 @@ def hmy_count_swaps(spec, sched, n_micro, micro_batch):
     return _stats_dict(st)
 
 
-def hmy_set_kernel_path(use_mfma: bool) -> None:
-    _check(lib.hmy_set_kernel_path(int(bool(use_mfma))))
+def hmy_set_kernel_path(use_mfma) -> None:
+    """False/0: reference kernels; True/1: MFMA kernels; 2: MFMA without the large-tile GEMM."""
+    _check(lib.hmy_set_kernel_path(int(use_mfma)))
 
 
 # ---- device ---------------------------------------------------------------------

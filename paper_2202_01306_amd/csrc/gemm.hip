@@ -230,12 +230,19 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(GemmP p, int tiles_per_spl
   const bf16_t *A = static_cast<const bf16_t *>(p.A), *B = static_cast<const bf16_t *>(p.B);
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int wm = wave / 2, wn = wave % 2;
-  // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2):
-  // give each XCD a contiguous band of tiles so the tiles it works on share operands.
+  // Tile order.  Consecutive workgroup ids go round-robin over the 8 XCDs (each with its
+  // own L2), so first give each XCD a contiguous range of tile ids; then walk the tile
+  // grid in bands of 8 tile rows, column by column, so that the ~64 workgroups resident
+  // on an XCD form an 8x8 patch that shares 8 row panels of A and 8 column panels of B
+  // in L2 instead of streaming one whole operand per tile row.
   int bid = blockIdx.x;
-  const int nb = gridDim.x;
+  const int nb = gridDim.x, grid_m = nb / grid_n;
   if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;
-  const int m0 = (bid / grid_n) * BM, n0 = (bid % grid_n) * BN;
+  constexpr int kBand = 8;
+  const int band = bid / (kBand * grid_n), first_m = band * kBand;
+  const int band_rows = min(grid_m - first_m, kBand);
+  const int in_band = bid - band * kBand * grid_n;
+  const int m0 = (first_m + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -338,6 +345,7 @@ int launch_gemm(const hmy_gemm_desc &g, stream_t st) {
   const int64_t a_span = int64_t(g.ta ? g.K : g.M) * g.lda, b_span = int64_t(g.tb ? g.K : g.N) * g.ldb;
   const bool mfma_ok = g.prec == HMY_PREC_BF16 && g_use_mfma && aligned16(g.A) && aligned16(g.B) && g.lda % 8 == 0 &&
                        g.ldb % 8 == 0 && a_span < (int64_t(1) << 31) && b_span < (int64_t(1) << 31);
+  if (mfma_ok && g_use_mfma == 1) return launch_gemm_mfma32(g, st);
   if (mfma_ok) {
     const int gm = (g.M + BM - 1) / BM, gn = (g.N + BN - 1) / BN, nk = (g.K + BK - 1) / BK;
     // split the contraction over workgroups (fp32 atomics into C) when an accumulating
