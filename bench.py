@@ -89,6 +89,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="gpt2m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pack-search", type=int, default=None,
+                    help="how many pack counts beyond the first feasible one the planner may try (0 = Algorithm 2 alone)")
     ap.add_argument("--reference-kernels", action="store_true", help="time the plain (non-MFMA) kernels")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -101,6 +103,9 @@ def main() -> int:
     from paper_2202_01306_amd import synth
     from paper_2202_01306_amd.runner import Engine, TrainingState
 
+    if a.pack_search is None:
+        from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH
+        a.pack_search = BENCH_PACK_SEARCH
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (there is no CPU fallback)", file=sys.stderr)
         return 3
@@ -113,7 +118,7 @@ def main() -> int:
     st.fill_random(0)
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
-    with Engine(st, cfg["budget"], cfg["M"], cfg["b"]) as eng:
+    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search) as eng:
         eng.set_batch(ids, tg)
         step = 1
         for _ in range(a.warmup):
@@ -153,7 +158,7 @@ def main() -> int:
                                f"ffn={cfg['d_ffn']} seq={cfg['seq_len']} vocab={cfg['vocab']}, "
                                f"{cfg['M']} microbatches x {cfg['b']} sequences",
                    "hbm_budget_bytes": cfg["budget"], "arena_bytes": arena["total"],
-                   "fwd_packs": packs[0], "bwd_packs": packs[1],
+                   "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
                    "kernels": "reference" if a.reference_kernels else "mfma"},
         "tflops": total_flops / (ms * 1e-3) / 1e12,
         "swap": {"h2d_GB_per_iter": h2d / 1e9, "d2h_GB_per_iter": d2h / 1e9,

@@ -70,9 +70,16 @@ typedef struct hmy_model_spec {
   float ln_eps;
 } hmy_model_spec;
 
-/* The machine model of Algorithm 1: memory capacity alpha. */
+/* The machine model of Algorithm 1: memory capacity alpha, host-link bandwidth beta,
+ * plus a sustained compute rate for the runtime estimate. */
 typedef struct hmy_budget {
-  uint64_t hbm_budget_bytes; /* everything the library keeps in HBM must fit */
+  uint64_t hbm_budget_bytes; /* everything the library keeps in HBM must fit                   */
+  uint32_t host_link_MBps;   /* per direction, for the runtime estimate; 0 = 40000             */
+  uint32_t compute_GFLOPs;   /* sustained model flops/s for the runtime estimate; 0 = 250000   */
+  uint32_t max_extra_packs;  /* 0: first feasible pack count (Algorithm 2 alone); n: also try the
+                                next n feasible pack counts and keep the smallest estimated
+                                iteration time (the search of Algorithm 1)                      */
+  uint32_t reserved_;
 } hmy_budget;
 
 /* Configuration (Section 4.3.1): forward and backward layer packs as exclusive
@@ -178,6 +185,13 @@ int hmy_profile(const hmy_model_spec *spec, int32_t n_micro, int32_t micro_batch
  * forward packs over the layers before the last backward pack. */
 int hmy_plan(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_micro,
              int32_t micro_batch, hmy_schedule *out);
+
+/* Runtime estimate (integer nanoseconds) of one iteration for a schedule: an
+ * event-driven walk of the task list over the compute stream and the two
+ * directions of the host link (Section 4.3.1, "Runtime Estimator"), with the
+ * rates given in *budget.  This is what hmy_plan minimises when it searches. */
+int hmy_estimate(const hmy_model_spec *spec, const hmy_schedule *sched, const hmy_budget *budget,
+                 int32_t n_micro, int32_t micro_batch, uint64_t *iteration_ns);
 
 /* Validate a schedule and size the HBM arena it needs. */
 int hmy_arena(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro,

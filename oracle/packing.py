@@ -51,27 +51,34 @@ def packs_from_cuts(cuts, R: int, first: int = 0):
     return packs
 
 
-def balanced_time_packing(t, m, alpha: int, also_fits=None, first: int = 0):
+def balanced_time_packing(t, m, alpha: int, also_fits=None, first: int = 0, S_start: int = 1, with_S: bool = False):
     """Algorithm 2 on explicit lists.  Returns a list of (start, end) packs over
-    layers first..first+len(t), or None if no S <= R fits."""
+    layers first..first+len(t), or None if no S <= R fits.  The loop starts at
+    max(S_min, S_start); with_S also returns the accepted pack count (R + 1 for the
+    one-layer-per-pack fallback), so a caller can enumerate further candidates."""
     R = len(t)
     assert len(m) == R
+
+    def ret(packs, S):
+        return (packs, S) if with_S else packs
     if R == 0:
-        return []
+        return ret([], 0)
     if alpha <= 0:
-        return None
+        return ret(None, 0)
     S_min = max(1, -(-sum(m) // alpha))
-    for S in range(S_min, R + 1):
+    for S in range(max(S_min, S_start), R + 1):
         packs = packs_from_cuts(split_points(t, S), R, first)
         ok = all(sum(m[a - first:e - first]) <= alpha for (a, e) in packs)
         if ok and also_fits is not None:
             ok = also_fits(packs)
         if ok:
-            return packs
+            return ret(packs, S)
+    if S_start > R + 1:
+        return ret(None, 0)
     packs = [(first + j, first + j + 1) for j in range(R)]
     if all(mj <= alpha for mj in m) and (also_fits is None or also_fits(packs)):
-        return packs
-    return None
+        return ret(packs, R + 1)
+    return ret(None, 0)
 
 
 def forward_layers_given_backward(P_B):
@@ -180,22 +187,89 @@ def arena_bytes(spec, P_F, P_B, M: int, b: int, precision: str):
     return reserved_bytes(spec, M, b, precision) + 2 * slot + act, slot, act
 
 
-def plan(spec, budget: int, M: int, b: int, precision: str):
+def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_MBps: int, compute_GFLOPs: int) -> int:
+    """Runtime estimate of one iteration (the role of the paper's Runtime Estimator,
+    reduced to one GPU): an event-driven walk of the task list over the compute
+    stream and the two directions of the host link, in integer nanoseconds.
+    A visit computes for n_micro * (sum of its layers' flops) / rate; its weights
+    are requested when the previous visit starts computing and its slot (visit
+    index mod 2) is free; a backward visit's update moves the optimizer state in and
+    (state + weights + fp32 gradients) out after its compute ends; the two links
+    are each one queue.  Checkpoint traffic is ignored."""
+    from . import model as om
+    E = elem_bytes(precision)
+    kB = 12 if precision == "bf16" else 8
+    prof = layer_profile(spec, M, b, precision)
+
+    def t_bytes(n):
+        return -(-n * 1000 // link_MBps)
+
+    def t_flops(n):
+        return -(-n // compute_GFLOPs)
+
+    def npar(a, e):
+        return sum(om.layer_param_count(spec, l) for l in range(a, e))
+    visits = []
+    for (a, e) in P_F:
+        visits.append((False, t_flops(M * sum(prof[l]["t_fwd"] for l in range(a, e))), t_bytes(E * npar(a, e)), 0, 0))
+    for (a, e) in reversed(P_B):
+        P = npar(a, e)
+        visits.append((True, t_flops(M * sum(prof[l]["t_bwd"] for l in range(a, e))), t_bytes(E * P),
+                       t_bytes(kB * P), t_bytes((kB + E + 4) * P)))
+    h2d_free = d2h_free = comp_free = 0
+    slot_free = [0, 0]
+    w_ready = [0] * (len(visits) + 1)
+    w_ready[0] = visits[0][2]
+    h2d_free = w_ready[0]
+    for v, (bwd, comp, w, kin, out) in enumerate(visits):
+        comp_start = max(comp_free, w_ready[v])
+        if v + 1 < len(visits):
+            s = max(comp_start, slot_free[(v + 1) % 2], h2d_free)
+            w_ready[v + 1] = s + visits[v + 1][2]
+            h2d_free = w_ready[v + 1]
+        comp_end = comp_start + comp
+        comp_free = comp_end
+        if not bwd:
+            slot_free[v % 2] = comp_end
+        else:
+            kin_end = max(comp_end, h2d_free) + kin
+            h2d_free = kin_end
+            out_end = max(max(comp_end, d2h_free) + out, kin_end)
+            d2h_free = out_end
+            slot_free[v % 2] = out_end
+    return max(comp_free, d2h_free)
+
+
+def plan(spec, budget: int, M: int, b: int, precision: str, search: int = 0, link_MBps: int = 40000,
+         compute_GFLOPs: int = 250000):
     """Backward packs by Algorithm 2 on (t_bwd, mem_bwd) with capacity budget -
     reserve and the whole-arena test; then forward packs on (t_fwd, mem_fwd)
     over the layers before the last backward pack with capacity 2 * slot.
-    Returns (P_F, P_B) or None."""
+    search = 0 keeps the first feasible pack count (Algorithm 2 alone); search = n
+    also tries the next n feasible pack counts and, as Algorithm 1 does over its
+    configurations, keeps the one with the smallest estimated iteration time
+    (ties: fewer packs).  Returns (P_F, P_B) or None."""
     prof = layer_profile(spec, M, b, precision)
     res = reserved_bytes(spec, M, b, precision)
     if budget <= res:
         return None
-    P_B = balanced_time_packing([p["t_bwd"] for p in prof], [p["mem_bwd"] for p in prof], budget - res,
-                                also_fits=lambda packs: arena_bytes(spec, [], packs, M, b, precision)[0] <= budget)
-    if P_B is None:
-        return None
-    slot = arena_bytes(spec, [], P_B, M, b, precision)[1]
-    RF = forward_layers_given_backward(P_B)
-    P_F = balanced_time_packing([p["t_fwd"] for p in prof[:RF]], [p["mem_fwd"] for p in prof[:RF]], 2 * slot)
-    if P_F is None:
-        return None
-    return P_F, P_B
+    best, best_ns, S_start = None, None, 1
+    for _ in range(search + 1):
+        P_B, S_used = balanced_time_packing(
+            [p["t_bwd"] for p in prof], [p["mem_bwd"] for p in prof], budget - res,
+            also_fits=lambda packs: arena_bytes(spec, [], packs, M, b, precision)[0] <= budget,
+            S_start=S_start, with_S=True)
+        if P_B is None:
+            break
+        slot = arena_bytes(spec, [], P_B, M, b, precision)[1]
+        RF = forward_layers_given_backward(P_B)
+        P_F = balanced_time_packing([p["t_fwd"] for p in prof[:RF]], [p["mem_fwd"] for p in prof[:RF]], 2 * slot)
+        if P_F is None:
+            return None
+        ns = estimate_iteration_ns(spec, P_F, P_B, M, b, precision, link_MBps, compute_GFLOPs)
+        if best is None or ns < best_ns:
+            best, best_ns = (P_F, P_B), ns
+        if S_used > spec.n_layers:
+            break
+        S_start = S_used + 1
+    return best

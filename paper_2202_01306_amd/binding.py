@@ -40,7 +40,12 @@ class hmy_model_spec(C.Structure):
 
 
 class hmy_budget(C.Structure):
-    _fields_ = [("hbm_budget_bytes", C.c_uint64)]
+    _fields_ = [("hbm_budget_bytes", C.c_uint64), ("host_link_MBps", C.c_uint32), ("compute_GFLOPs", C.c_uint32),
+                ("max_extra_packs", C.c_uint32), ("reserved_", C.c_uint32)]
+
+
+def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0) -> hmy_budget:
+    return hmy_budget(int(budget_bytes), int(link_MBps), int(compute_GFLOPs), int(search), 0)
 
 
 class hmy_schedule(C.Structure):
@@ -94,7 +99,7 @@ class hmy_gemm_desc(C.Structure):
 
 
 EXPORTS = [
-    "hmy_strerror", "hmy_last_error", "hmy_model_size", "hmy_layout", "hmy_profile", "hmy_plan", "hmy_arena",
+    "hmy_strerror", "hmy_last_error", "hmy_model_size", "hmy_layout", "hmy_profile", "hmy_plan", "hmy_estimate", "hmy_arena",
     "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state",
     "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
     "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
@@ -167,10 +172,18 @@ def hmy_profile(spec, n_micro, micro_batch):
     return prof, res.value
 
 
-def hmy_plan(spec, budget_bytes, n_micro, micro_batch) -> hmy_schedule:
+def hmy_plan(spec, budget_bytes, n_micro, micro_batch, search=0, link_MBps=0, compute_GFLOPs=0) -> hmy_schedule:
     s = hmy_schedule()
-    _check(lib.hmy_plan(C.byref(spec), C.byref(hmy_budget(budget_bytes)), n_micro, micro_batch, C.byref(s)))
+    b = make_budget(budget_bytes, search, link_MBps, compute_GFLOPs)
+    _check(lib.hmy_plan(C.byref(spec), C.byref(b), n_micro, micro_batch, C.byref(s)))
     return s
+
+
+def hmy_estimate(spec, sched, n_micro, micro_batch, link_MBps=0, compute_GFLOPs=0) -> int:
+    ns = C.c_uint64()
+    _check(lib.hmy_estimate(C.byref(spec), C.byref(sched), C.byref(make_budget(0, 0, link_MBps, compute_GFLOPs)),
+                            n_micro, micro_batch, C.byref(ns)))
+    return ns.value
 
 
 def hmy_arena(spec, sched, n_micro, micro_batch):
@@ -211,9 +224,11 @@ def hmy_host_free(ptr: int) -> None:
     _check(lib.hmy_host_free(C.c_void_p(ptr)))
 
 
-def hmy_create(spec, budget_bytes, n_micro, micro_batch, sched=None, device=0, arena_ptr=None, arena_bytes=0):
+def hmy_create(spec, budget_bytes, n_micro, micro_batch, sched=None, device=0, arena_ptr=None, arena_bytes=0,
+               search=0, link_MBps=0, compute_GFLOPs=0):
     h = C.c_void_p()
-    _check(lib.hmy_create(C.byref(spec), C.byref(hmy_budget(budget_bytes)), n_micro, micro_batch,
+    _check(lib.hmy_create(C.byref(spec), C.byref(make_budget(budget_bytes, search, link_MBps, compute_GFLOPs)),
+                          n_micro, micro_batch,
                           C.byref(sched) if sched is not None else None, device,
                           C.c_void_p(arena_ptr) if arena_ptr else None, C.c_uint64(arena_bytes), C.byref(h)))
     return h

@@ -80,9 +80,26 @@ int hmy_plan(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_mic
   if (rc) return rc;
   if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
   Packs p;
-  rc = plan_packs(m, budget->hbm_budget_bytes, n_micro, micro_batch, &p);
+  rc = plan_packs(m, *budget, n_micro, micro_batch, &p);
   if (rc) return rc;
   packs_to_schedule(p, out);
+  return HMY_OK;
+}
+
+int hmy_estimate(const hmy_model_spec *spec, const hmy_schedule *sched, const hmy_budget *budget, int32_t n_micro,
+                 int32_t micro_batch, uint64_t *iteration_ns) {
+  if (!budget || !iteration_ns) return fail(HMY_E_INVALID, "null argument");
+  Model m;
+  int rc = build_model(spec, &m);
+  if (rc) return rc;
+  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
+  Packs p;
+  rc = schedule_to_packs(m, sched, &p);
+  if (rc) return rc;
+  std::vector<hmy_layer_profile> prof;
+  layer_profile(m, n_micro, micro_batch, &prof);
+  *iteration_ns = estimate_iteration_ns(m, prof, p, n_micro, budget->host_link_MBps ? budget->host_link_MBps : 40000,
+                                        budget->compute_GFLOPs ? budget->compute_GFLOPs : 250000);
   return HMY_OK;
 }
 

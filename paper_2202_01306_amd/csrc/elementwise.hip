@@ -3,6 +3,7 @@
 // per row for the row reductions; 16-byte accesses along the contiguous axis.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 
 #include "dev_common.h"
 #include "hmy_internal.h"
@@ -315,9 +316,79 @@ __global__ void k_adam(const float *grad, float *master, float *m, float *v, W *
   }
 }
 
+// Fused Adam + swap-out: reads the gradient from HBM and the optimizer state from
+// wherever in_* point (the HBM ring), and writes the updated state, the compute-
+// precision weight and the gradient straight to the caller's pinned host arrays
+// (out_*: host pointers, written over the host link as full 16/32-byte vectors).
+// MIXED: master/m/v fp32 + bf16 weight.  !MIXED: the fp32 weight is the master
+// (in_master = the weight in HBM, out_w is fp32 and out_master is not used).
+// Eight elements per thread per step; n may have a tail.
+template <bool MIXED>
+__global__ void k_adam_out(const float *grad, const float *in_master, const float *in_m, const float *in_v,
+                           float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
+                           float lr, float b1, float b2, float eps, float inv_bc1, float inv_bc2) {
+  const uint64_t stride = uint64_t(gridDim.x) * blockDim.x * 8;
+  for (uint64_t base = (uint64_t(blockIdx.x) * blockDim.x + threadIdx.x) * 8; base < n; base += stride) {
+    float g[8], w[8], m[8], v[8];
+    const bool full = base + 8 <= n;
+    if (full) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        *reinterpret_cast<float4 *>(g + 4 * h) = *reinterpret_cast<const float4 *>(grad + base + 4 * h);
+        *reinterpret_cast<float4 *>(w + 4 * h) = *reinterpret_cast<const float4 *>(in_master + base + 4 * h);
+        *reinterpret_cast<float4 *>(m + 4 * h) = *reinterpret_cast<const float4 *>(in_m + base + 4 * h);
+        *reinterpret_cast<float4 *>(v + 4 * h) = *reinterpret_cast<const float4 *>(in_v + base + 4 * h);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const bool ok = base + k < n;
+        g[k] = ok ? grad[base + k] : 0.f;
+        w[k] = ok ? in_master[base + k] : 0.f;
+        m[k] = ok ? in_m[base + k] : 0.f;
+        v[k] = ok ? in_v[base + k] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      m[k] = b1 * m[k] + (1.f - b1) * g[k];
+      v[k] = b2 * v[k] + (1.f - b2) * g[k] * g[k];
+      w[k] = w[k] - lr * (m[k] * inv_bc1) / (sqrtf(v[k] * inv_bc2) + eps);
+    }
+    if (full) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        *reinterpret_cast<float4 *>(out_m + base + 4 * h) = *reinterpret_cast<const float4 *>(m + 4 * h);
+        *reinterpret_cast<float4 *>(out_v + base + 4 * h) = *reinterpret_cast<const float4 *>(v + 4 * h);
+        *reinterpret_cast<float4 *>(out_g + base + 4 * h) = *reinterpret_cast<const float4 *>(g + 4 * h);
+        if (MIXED) *reinterpret_cast<float4 *>(out_master + base + 4 * h) = *reinterpret_cast<const float4 *>(w + 4 * h);
+        else *reinterpret_cast<float4 *>(static_cast<float *>(out_w) + base + 4 * h) = *reinterpret_cast<const float4 *>(w + 4 * h);
+      }
+      if (MIXED) {
+        Vec16<bf16_t> o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) o.v[k] = from_f32<bf16_t>(w[k]);
+        store16(static_cast<bf16_t *>(out_w) + base, o);
+      }
+    } else {
+      for (int k = 0; k < 8 && base + k < n; ++k) {
+        out_m[base + k] = m[k];
+        out_v[base + k] = v[k];
+        out_g[base + k] = g[k];
+        if (MIXED) {
+          out_master[base + k] = w[k];
+          static_cast<bf16_t *>(out_w)[base + k] = from_f32<bf16_t>(w[k]);
+        } else {
+          static_cast<float *>(out_w)[base + k] = w[k];
+        }
+      }
+    }
+  }
+}
+
 }  // namespace
 
-#define DISPATCH_PREC(prec, CALL)                                   \
+#define DISPATCH_PREC(prec, CALL)                                 \
   do {                                                              \
     if ((prec) == HMY_PREC_FP32) { typedef float E; CALL; }         \
     else if ((prec) == HMY_PREC_BF16) { typedef bf16_t E; CALL; }   \
@@ -460,6 +531,27 @@ int launch_adam(int prec, const float *grad, float *master, float *m, float *v, 
     return fail(HMY_E_INVALID, "unknown precision %d", prec);
   }
   return check_launch("adam");
+}
+
+int launch_adam_out(int prec, const float *grad, const float *in_master, const float *in_m, const float *in_v,
+                    float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
+                    const hmy_adam &hp, stream_t st) {
+  if (!n) return HMY_OK;
+  if (hp.step < 1) return fail(HMY_E_INVALID, "adam: step is 1-based");
+  const float inv_bc1 = float(1.0 / (1.0 - std::pow(double(hp.beta1), double(hp.step))));
+  const float inv_bc2 = float(1.0 / (1.0 - std::pow(double(hp.beta2), double(hp.step))));
+  // a modest grid: the kernel runs at host-link speed, not HBM speed, beside the compute stream
+  static const int cap = std::getenv("HMY_ADAM_GRID") ? std::max(1, std::atoi(std::getenv("HMY_ADAM_GRID"))) : 32;
+  const int grid = grid_for(n / 8 + 1, kBlock, cap);
+  if (prec == HMY_PREC_BF16)
+    hipLaunchKernelGGL(k_adam_out<true>, dim3(grid), dim3(kBlock), 0, (hipStream_t)st, grad, in_master, in_m, in_v,
+                       out_master, out_m, out_v, out_w, out_g, n, hp.lr, hp.beta1, hp.beta2, hp.eps, inv_bc1, inv_bc2);
+  else if (prec == HMY_PREC_FP32)
+    hipLaunchKernelGGL(k_adam_out<false>, dim3(grid), dim3(kBlock), 0, (hipStream_t)st, grad, in_master, in_m, in_v,
+                       out_master, out_m, out_v, out_w, out_g, n, hp.lr, hp.beta1, hp.beta2, hp.eps, inv_bc1, inv_bc2);
+  else
+    return fail(HMY_E_INVALID, "unknown precision %d", prec);
+  return check_launch("adam_out");
 }
 
 }  // namespace hmy

@@ -19,6 +19,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "hmy_internal.h"
@@ -66,6 +67,9 @@ struct hmy_handle {
   int err = HMY_OK;
   bool timing = true;
   bool profile_gemm = false;
+  // true: the Adam kernel writes its results directly into the pinned host arrays;
+  // false: results go to the ring / slot and leave by hipMemcpyAsync on s_out
+  bool fused_swap_out = true;
 };
 
 #define HIPCHK(h, call)                                                                      \
@@ -479,6 +483,24 @@ void update_visit(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_d
     h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_upd);
     h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_upd);
     if (c == 0) wait(h, h->s_upd, bwd_done);
+    if (h->fused_swap_out) {
+      // the update kernel itself writes state, weights and gradients to the host arrays
+      // (device->host over the link at vector width); bytes are counted as for copies
+      h->st.d2h[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
+      h->st.d2h[HMY_KIND_W] += n * E;
+      h->st.d2h[HMY_KIND_DW] += n * 4;
+      if (!h->dry && !h->err) {
+        const size_t a = trec(h, h->s_upd);
+        KCHK(h, launch_adam_out(h->model.spec.precision, pp.dW + lo, mixed ? r_master : (const float *)(pp.W + lo * E),
+                                r_m, r_v, mixed ? h->host.master + g0 : nullptr, h->host.adam_m + g0,
+                                h->host.adam_v + g0, (char *)h->host.weights + g0 * E, h->host.grads + g0, n, hp,
+                                h->s_upd));
+        const size_t b2 = trec(h, h->s_upd);
+        span(h, a, b2, 1);
+      }
+      it.k_free[r] = rec(h, h->s_upd);
+      continue;
+    }
     KCHK(h, launch_adam(h->model.spec.precision, pp.dW + lo, r_master, r_m, r_v, pp.W + lo * E, n, hp, h->s_upd));
     hipEvent_t e = rec(h, h->s_upd);
     wait(h, h->s_out, e);
@@ -557,7 +579,7 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
     } else {
       hipEvent_t bwd_done = rec(h, h->s_comp);
       update_visit(h, it, v, bwd_done, hp);
-      it.slot_free[v.slot] = rec(h, h->s_out);
+      it.slot_free[v.slot] = rec(h, h->fused_swap_out ? h->s_upd : h->s_out);
     }
   }
   const size_t t_last = trec(h, h->s_comp);
@@ -578,7 +600,7 @@ static int init_handle(hmy_handle *h, const hmy_model_spec *spec, const hmy_sche
     rc = schedule_to_packs(h->model, sched, &h->packs);
   } else {
     if (!budget) return fail(HMY_E_INVALID, "neither schedule nor budget given");
-    rc = plan_packs(h->model, budget->hbm_budget_bytes, n_micro, micro_batch, &h->packs);
+    rc = plan_packs(h->model, *budget, n_micro, micro_batch, &h->packs);
   }
   if (rc) return rc;
   h->arena = arena_layout(h->model, h->packs, n_micro, micro_batch);
@@ -695,6 +717,8 @@ int hmy_bind_state(hmy_handle *h, const hmy_host_state *state) {
                 (unsigned long long)h->model.n_params);
   h->host = *state;
   h->bound = true;
+  const char *zc = std::getenv("HMY_FUSED_SWAP_OUT");
+  if (zc) h->fused_swap_out = std::atoi(zc) != 0;
   return HMY_OK;
 }
 

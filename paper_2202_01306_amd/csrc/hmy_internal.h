@@ -94,7 +94,9 @@ Arena arena_layout(const Model &m, const Packs &p, int n_micro, int micro_batch)
 uint64_t pack_state_bwd(const Model &m, Pack p);   // a256(E*P) + a256(4*P)
 uint64_t pack_state_fwd(const Model &m, Pack p);   // a256(E*P)
 
-int plan_packs(const Model &m, uint64_t budget, int n_micro, int micro_batch, Packs *out);
+int plan_packs(const Model &m, const hmy_budget &budget, int n_micro, int micro_batch, Packs *out);
+uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profile> &prof, const Packs &p, int n_micro,
+                               uint64_t link_MBps, uint64_t compute_GFLOPs);
 
 // ---- kernel launchers (all pointers device; stream is a hipStream_t) ---------
 typedef void *stream_t;
@@ -126,6 +128,9 @@ int launch_xent(int prec, const float *logits, const int32_t *targets, double *l
                 void *dlogits, int T, int V, int64_t ldl, float inv_ntgt, stream_t st);
 int launch_adam(int prec, const float *grad, float *master, float *m, float *v, void *w_out,
                 uint64_t n, const hmy_adam &hp, stream_t st);
+int launch_adam_out(int prec, const float *grad, const float *in_master, const float *in_m, const float *in_v,
+                    float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
+                    const hmy_adam &hp, stream_t st);
 int launch_fill_zero(void *p, uint64_t bytes, stream_t st);
 int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st);
 int launch_convert_f32(int prec, const float *src, void *dst, uint64_t n, stream_t st);

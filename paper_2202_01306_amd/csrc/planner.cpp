@@ -177,11 +177,16 @@ void packs_to_schedule(const Packs &p, hmy_schedule *out) {
 // Algorithm 2 on explicit lists over layers first..first+R.  `fits` is the
 // whole-packing test ANDed to the per-pack capacity test.  Returns false if not
 // even one layer per pack fits.
+// The search starts at max(S_min, S_start); *S_used receives the pack count that was
+// accepted (R + 1 for the one-layer-per-pack fallback), so that a caller can ask for
+// the next feasible candidate.
 template <class Fits>
 static bool balanced_time_packing(const std::vector<int64_t> &t, const std::vector<uint64_t> &mem,
-                                  uint64_t alpha, int first, Fits fits, std::vector<Pack> *out) {
+                                  uint64_t alpha, int first, Fits fits, std::vector<Pack> *out, int S_start = 1,
+                                  int *S_used = nullptr) {
   const int R = int(t.size());
   out->clear();
+  if (S_used) *S_used = 0;
   if (R == 0) return true;
   if (alpha == 0) return false;
   __int128 total = 0;
@@ -201,7 +206,7 @@ static bool balanced_time_packing(const std::vector<int64_t> &t, const std::vect
     return true;
   };
   int S_min = int(std::max<uint64_t>(1, (msum + alpha - 1) / alpha));
-  for (int S = S_min; S <= R; ++S) {
+  for (int S = std::max(S_min, S_start); S <= R; ++S) {
     // cut k = number of layers whose prefix time is <= k * total / S
     std::vector<Pack> ps;
     int prev = 0;
@@ -219,57 +224,134 @@ static bool balanced_time_packing(const std::vector<int64_t> &t, const std::vect
     }
     if (per_pack_ok(ps) && fits(ps)) {
       *out = std::move(ps);
+      if (S_used) *S_used = S;
       return true;
     }
   }
+  if (S_start > R + 1) return false;
   std::vector<Pack> ps;
   for (int j = 0; j < R; ++j) ps.push_back({first + j, first + j + 1});
   if (per_pack_ok(ps) && fits(ps)) {
     *out = std::move(ps);
+    if (S_used) *S_used = R + 1;
     return true;
   }
   return false;
 }
 
-int plan_packs(const Model &m, uint64_t budget, int n_micro, int micro_batch, Packs *out) {
+// Runtime estimate of one iteration for a packing (the role of the paper's Runtime
+// Estimator, Section 4.3.1, reduced to what decides the pack count on one GPU): an
+// event-driven walk of the task list over three resources -- the compute stream, the
+// host->device link and the device->host link -- in integer nanoseconds.  Compute
+// time of a visit = n_micro * sum of its layers' flops / rate; each visit's weights
+// are requested when the previous visit starts computing and its slot is free; a
+// backward visit's update moves its optimizer state in and (state, weights,
+// gradients) out after its compute ends.  Checkpoint traffic is ignored (small).
+uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profile> &prof, const Packs &p, int n_micro,
+                               uint64_t link_MBps, uint64_t compute_GFLOPs) {
+  const uint64_t E = m.elem_bytes(), kB = 4 * uint64_t(m.k_arrays());
+  auto t_bytes = [&](uint64_t bytes) { return (bytes * 1000 + link_MBps - 1) / link_MBps; };
+  auto t_flops = [&](uint64_t flops) { return (flops + compute_GFLOPs - 1) / compute_GFLOPs; };
+  struct V { bool bwd; uint64_t comp, w, kin, out; };
+  std::vector<V> vs;
+  for (const Pack &q : p.fwd) {
+    uint64_t fl = 0;
+    for (int l = q.a; l < q.e; ++l) fl += uint64_t(prof[l].t_fwd);
+    vs.push_back({false, t_flops(fl * n_micro), t_bytes(E * m.params_in(q.a, q.e)), 0, 0});
+  }
+  for (int k = int(p.bwd.size()) - 1; k >= 0; --k) {
+    const Pack &q = p.bwd[k];
+    uint64_t fl = 0;
+    for (int l = q.a; l < q.e; ++l) fl += uint64_t(prof[l].t_bwd);
+    const uint64_t P = m.params_in(q.a, q.e);
+    vs.push_back({true, t_flops(fl * n_micro), t_bytes(E * P), t_bytes(kB * P), t_bytes((kB + E + 4) * P)});
+  }
+  uint64_t h2d_free = 0, d2h_free = 0, comp_free = 0, slot_free[2] = {0, 0};
+  std::vector<uint64_t> w_ready(vs.size() + 1, 0);
+  w_ready[0] = vs[0].w;
+  h2d_free = w_ready[0];
+  for (size_t v = 0; v < vs.size(); ++v) {
+    const uint64_t comp_start = std::max(comp_free, w_ready[v]);
+    if (v + 1 < vs.size()) {
+      const uint64_t s = std::max(std::max(comp_start, slot_free[(v + 1) % 2]), h2d_free);
+      w_ready[v + 1] = s + vs[v + 1].w;
+      h2d_free = w_ready[v + 1];
+    }
+    const uint64_t comp_end = comp_start + vs[v].comp;
+    comp_free = comp_end;
+    if (!vs[v].bwd) {
+      slot_free[v % 2] = comp_end;
+    } else {
+      const uint64_t kin_end = std::max(comp_end, h2d_free) + vs[v].kin;
+      h2d_free = kin_end;
+      const uint64_t out_end = std::max(std::max(comp_end, d2h_free) + vs[v].out, kin_end);
+      d2h_free = out_end;
+      slot_free[v % 2] = out_end;
+    }
+  }
+  return std::max(comp_free, d2h_free);
+}
+
+int plan_packs(const Model &m, const hmy_budget &b, int n_micro, int micro_batch, Packs *out) {
+  const uint64_t budget = b.hbm_budget_bytes;
+  const uint64_t link = b.host_link_MBps ? b.host_link_MBps : 40000, rate = b.compute_GFLOPs ? b.compute_GFLOPs : 250000;
   std::vector<hmy_layer_profile> prof;
   layer_profile(m, n_micro, micro_batch, &prof);
   const Reserved res = reserved_layout(m, n_micro, micro_batch);
   if (budget <= res.size)
     return fail(HMY_E_BUDGET_TOO_SMALL, "budget %llu B does not cover the pack-independent reserve %llu B",
                 (unsigned long long)budget, (unsigned long long)res.size);
-  // backward packs first (Algorithm 1, line "backward packing")
-  std::vector<int64_t> t(m.R);
-  std::vector<uint64_t> mem(m.R);
+  std::vector<int64_t> tb(m.R);
+  std::vector<uint64_t> mb(m.R);
   for (int l = 0; l < m.R; ++l) {
-    t[l] = prof[l].t_bwd;
-    mem[l] = prof[l].mem_bwd;
+    tb[l] = prof[l].t_bwd;
+    mb[l] = prof[l].mem_bwd;
   }
-  Packs p;
   auto arena_fits = [&](const std::vector<Pack> &bwd) {
     Packs q;
     q.bwd = bwd;
     return arena_layout(m, q, n_micro, micro_batch).total <= budget;
   };
-  if (!balanced_time_packing(t, mem, budget - res.size, 0, arena_fits, &p.bwd))
+  auto always = [](const std::vector<Pack> &) { return true; };
+  // Candidates: the first feasible pack count of Algorithm 2 (largest packs), then up to
+  // max_extra_packs further feasible pack counts; as in Algorithm 1 the configuration with
+  // the smallest estimated iteration time wins (ties: fewer packs).
+  bool have = false;
+  uint64_t best_ns = 0;
+  Packs best;
+  int S_start = 1;
+  for (uint32_t tries = 0; tries <= b.max_extra_packs; ++tries) {
+    Packs p;
+    int S_used = 0;
+    // backward packs first (Algorithm 1, line "backward packing")
+    if (!balanced_time_packing(tb, mb, budget - res.size, 0, arena_fits, &p.bwd, S_start, &S_used)) break;
+    // forward packs over the layers before the last backward pack; they share the
+    // weight slots sized by the backward packing
+    const int RF = p.bwd.back().a;
+    Packs only_b;
+    only_b.bwd = p.bwd;
+    const uint64_t slot = arena_layout(m, only_b, n_micro, micro_batch).slot_bytes;
+    std::vector<int64_t> tf(RF);
+    std::vector<uint64_t> mf(RF);
+    for (int l = 0; l < RF; ++l) {
+      tf[l] = prof[l].t_fwd;
+      mf[l] = prof[l].mem_fwd;
+    }
+    if (!balanced_time_packing(tf, mf, 2 * slot, 0, always, &p.fwd))
+      return fail(HMY_E_BUDGET_TOO_SMALL, "forward packing failed (internal)");
+    const uint64_t ns = estimate_iteration_ns(m, prof, p, n_micro, link, rate);
+    if (!have || ns < best_ns) {
+      have = true;
+      best_ns = ns;
+      best = p;
+    }
+    if (S_used > m.R) break;   // that was the one-layer-per-pack fallback
+    S_start = S_used + 1;
+  }
+  if (!have)
     return fail(HMY_E_BUDGET_TOO_SMALL, "budget %llu B: even one layer per backward pack does not fit",
                 (unsigned long long)budget);
-  // forward packs over the layers before the last backward pack; they share the
-  // weight slots sized by the backward packing
-  const int RF = p.bwd.back().a;
-  Packs only_b;
-  only_b.bwd = p.bwd;
-  const uint64_t slot = arena_layout(m, only_b, n_micro, micro_batch).slot_bytes;
-  t.assign(RF, 0);
-  mem.assign(RF, 0);
-  for (int l = 0; l < RF; ++l) {
-    t[l] = prof[l].t_fwd;
-    mem[l] = prof[l].mem_fwd;
-  }
-  auto always = [](const std::vector<Pack> &) { return true; };
-  if (!balanced_time_packing(t, mem, 2 * slot, 0, always, &p.fwd))
-    return fail(HMY_E_BUDGET_TOO_SMALL, "forward packing failed (internal)");
-  *out = std::move(p);
+  *out = std::move(best);
   return HMY_OK;
 }
 

@@ -11,6 +11,11 @@ import torch
 
 from . import binding as B
 
+# Pack counts beyond the first feasible one that the benchmark lets the planner
+# try; the full-size parity tests use the same value so they check the launch
+# configuration that is timed.
+BENCH_PACK_SEARCH = 4
+
 
 class TrainingState:
     """Caller-owned pinned host state in the library's tensor layout."""
@@ -85,12 +90,12 @@ class Engine:
     """One hmy handle bound to a TrainingState."""
 
     def __init__(self, state: TrainingState, budget_bytes: int, n_micro: int, micro_batch: int, sched=None,
-                 device: int = 0):
+                 device: int = 0, search: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("the engine needs a GPU (there is no CPU fallback)")
         self.state = state
         self.M, self.b = n_micro, micro_batch
-        self.handle = B.hmy_create(state.spec, budget_bytes, n_micro, micro_batch, sched, device)
+        self.handle = B.hmy_create(state.spec, budget_bytes, n_micro, micro_batch, sched, device, search=search)
         self.sched = B.hmy_get_schedule(self.handle)
         self.packs = B.schedule_packs(self.sched)
         self.arena = B.hmy_arena(state.spec, self.sched, n_micro, micro_batch)

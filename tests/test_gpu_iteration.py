@@ -44,7 +44,7 @@ def oracle_step(cfg, master, m, v, ids, tg, hp):
 def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps=(1,), seed=0, weight_scale=1.0,
                     lr=1e-3):
     from paper_2202_01306_amd import binding as B
-    from paper_2202_01306_amd.runner import Engine, TrainingState
+    from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     tol = 1e-4 if cfg["precision"] == "fp32" else 2e-2
     params = synth.gen_params(cfg, seed, bench_init=False)
     for k in params:
@@ -213,7 +213,7 @@ def test_full_size_gpt2_medium_properties():
     state moved every master weight by lr*g/(|g|+eps), recomputed from the
     returned gradients."""
     say("full-size gpt2-medium properties")
-    from paper_2202_01306_amd.runner import Engine, TrainingState
+    from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     cfg = dict(synth.CONFIGS["gpt2m"])
     st = TrainingState(cfg)
     st.fill_random(0)
@@ -221,7 +221,7 @@ def test_full_size_gpt2_medium_properties():
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
     lr, eps = 1e-4, 1e-8
-    with Engine(st, cfg["budget"], cfg["M"], cfg["b"]) as eng:
+    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], search=BENCH_PACK_SEARCH) as eng:
         eng.set_batch(ids, tg)
         stats = eng.step(lr=lr, eps=eps, step=1)
         P_F, P_B = eng.packs
@@ -252,7 +252,7 @@ def test_full_size_gpt2_medium_sampled_outputs_against_the_oracle():
     The other microbatches still run through every kernel; they add nothing to
     the loss or to any gradient, which the test also checks on one tensor."""
     say("full-size gpt2-medium: loss and last-layer gradients against the oracle")
-    from paper_2202_01306_amd.runner import Engine, TrainingState
+    from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     cfg = dict(synth.CONFIGS["gpt2m"])
     params = synth.gen_params(cfg, 0, bench_init=True)
     for k in params:                       # make attention and the head non-trivial
@@ -263,7 +263,7 @@ def test_full_size_gpt2_medium_sampled_outputs_against_the_oracle():
     tg[1:] = -1
     st = TrainingState(cfg)
     st.load(params)
-    with Engine(st, cfg["budget"], cfg["M"], cfg["b"]) as eng:
+    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], search=BENCH_PACK_SEARCH) as eng:
         eng.set_batch(ids, tg)
         stats = eng.step(lr=1e-4, step=1)
     # oracle: forward of microbatch 0 through every layer, keeping only the last cache

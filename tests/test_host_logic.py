@@ -103,6 +103,49 @@ def test_planner_returns_the_oracles_packs(name):
         assert max(e - a_ for a_, e in P_F) >= max(e - a_ for a_, e in P_B[:-1])
 
 
+@pytest.mark.parametrize("name", ["gpt2m", "gpt2xl", "bertl", "gpt6b7"])
+def test_pack_count_search_matches_the_oracle_and_never_estimates_worse(name):
+    """Algorithm 1's selection rule over the candidates Algorithm 2 produces: the
+    searched plan equals the oracle's, its estimate equals the oracle's estimate,
+    and it is no worse than the first feasible packing's."""
+    cfg = synth.CONFIGS[name]
+    spec, ospec = B.make_spec(cfg), oracle_spec(cfg)
+    first = B.hmy_plan(spec, cfg["budget"], cfg["M"], cfg["b"])
+    for link, rate in ((0, 0), (25000, 600000)):
+        kw = dict(link_MBps=link or 40000, compute_GFLOPs=rate or 250000)
+        s = B.hmy_plan(spec, cfg["budget"], cfg["M"], cfg["b"], search=64, link_MBps=link, compute_GFLOPs=rate)
+        P_F, P_B = B.schedule_packs(s)
+        want = opk.plan(ospec, cfg["budget"], cfg["M"], cfg["b"], cfg["precision"], search=64, **kw)
+        assert (P_F, P_B) == want
+        ns = B.hmy_estimate(spec, s, cfg["M"], cfg["b"], link, rate)
+        assert ns == opk.estimate_iteration_ns(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"],
+                                               kw["link_MBps"], kw["compute_GFLOPs"])
+        assert ns <= B.hmy_estimate(spec, first, cfg["M"], cfg["b"], link, rate)
+        assert B.hmy_arena(spec, s, cfg["M"], cfg["b"])["total"] <= cfg["budget"]
+
+
+def test_runtime_estimate_closed_forms():
+    """Degenerate cases of the estimator that can be worked by hand: with an
+    infinitely fast link the estimate is the sum of the visits' compute times; with
+    infinitely fast compute it is the serial swap time of the dominant direction."""
+    cfg = tiny_cfg(n_blocks=3, d_model=64, n_heads=2, d_ffn=128, seq_len=16, vocab=50, precision="bf16", M=2, b=2)
+    spec, ospec = B.make_spec(cfg), oracle_spec(cfg)
+    sched = B.make_schedule([2, 4], [2, 4, 5])
+    prof = opk.layer_profile(ospec, 2, 2, "bf16")
+    rate = 1000                                      # GFLOP/s = flops per ns
+    flops = 2 * (sum(prof[l]["t_fwd"] for l in range(4)) + sum(prof[l]["t_bwd"] for l in range(5)))
+    per_visit = [2 * sum(prof[l]["t_fwd"] for l in r) for r in (range(0, 2), range(2, 4))] + \
+                [2 * sum(prof[l]["t_bwd"] for l in r) for r in (range(4, 5), range(2, 4), range(0, 2))]
+    assert sum(per_visit) == flops
+    fast_link = B.hmy_estimate(spec, sched, 2, 2, link_MBps=4_000_000_000, compute_GFLOPs=rate)
+    assert abs(fast_link - sum(-(-f // rate) for f in per_visit)) <= 10     # + a few ns of (rounded-up) transfers
+    n = sum(p["params"] for p in prof)
+    slow = B.hmy_estimate(spec, sched, 2, 2, link_MBps=1, compute_GFLOPs=4_000_000_000)
+    # device->host moves (12 + 2 + 4) B/param once; host->device moves 12 B/param of state + weights twice minus the last pack
+    d2h_ns = 18 * n * 1000
+    assert d2h_ns <= slow <= d2h_ns + 2 * 2 * n * 1000 + 12 * n * 1000 + 100
+
+
 def test_tiny_config_budget_gives_one_layer_per_pack():
     cfg = dict(synth.CONFIGS["tiny"])
     spec = B.make_spec(cfg)
