@@ -227,8 +227,11 @@ int hmy_destroy(hmy_handle *h);
  * hmy_stats.gemm_s; costs two event records per launch).  Off by default. */
 int hmy_set_profiling(hmy_handle *h, int32_t on);
 
-/* 0 = reference kernels (plain tiled loops), 1 = MFMA kernels where they exist
- * (default), 2 = MFMA kernels but never the 256x256-tile GEMM.  Process-wide; for
+/* 0 = reference kernels (plain tiled loops); 1 = MFMA kernels where they exist
+ * (default: the GEMM that streams tiles HBM -> LDS with the load-to-LDS instruction
+ * when the shape allows it, else the register-staged one); 2 = the first,
+ * 128x128x64 register-staged MFMA GEMM; 3 = the register-staged K-tile-32 MFMA GEMM
+ * for every shape.  Attention uses its MFMA kernels for 1..3.  Process-wide; for
  * tests and A/B timing. */
 int hmy_set_kernel_path(int32_t use_mfma);
 

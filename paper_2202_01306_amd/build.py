@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhmy.so")
 
-SOURCES = ["model.cpp", "planner.cpp", "api.cpp", "engine.hip", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "gemm_tr.hip"]
+SOURCES = ["model.cpp", "planner.cpp", "api.cpp", "engine.hip", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "gemm_tr.hip", "gemm_dma.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

@@ -125,7 +125,7 @@ int hmy_arena(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_m
 }
 
 int hmy_set_kernel_path(int32_t use_mfma) {
-  g_use_mfma = use_mfma < 0 ? 0 : (use_mfma > 2 ? 1 : use_mfma);
+  g_use_mfma = use_mfma < 0 ? 0 : (use_mfma > 3 ? 1 : use_mfma);
   return HMY_OK;
 }
 

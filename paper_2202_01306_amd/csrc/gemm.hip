@@ -345,7 +345,8 @@ int launch_gemm(const hmy_gemm_desc &g, stream_t st) {
   const int64_t a_span = int64_t(g.ta ? g.K : g.M) * g.lda, b_span = int64_t(g.tb ? g.K : g.N) * g.ldb;
   const bool mfma_ok = g.prec == HMY_PREC_BF16 && g_use_mfma && aligned16(g.A) && aligned16(g.B) && g.lda % 8 == 0 &&
                        g.ldb % 8 == 0 && a_span < (int64_t(1) << 31) && b_span < (int64_t(1) << 31);
-  if (mfma_ok && g_use_mfma == 1) return launch_gemm_mfma32(g, st);
+  if (mfma_ok && g_use_mfma == 1 && gemm_dma_eligible(g)) return launch_gemm_dma(g, st);
+  if (mfma_ok && g_use_mfma != 2) return launch_gemm_mfma32(g, st);
   if (mfma_ok) {
     const int gm = (g.M + BM - 1) / BM, gn = (g.N + BN - 1) / BN, nk = (g.K + BK - 1) / BK;
     // split the contraction over workgroups (fp32 atomics into C) when an accumulating

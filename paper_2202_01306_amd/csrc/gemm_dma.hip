@@ -1,0 +1,340 @@
+// bf16 GEMM on the matrix cores with operand tiles streamed HBM -> LDS by the
+// load-to-LDS instruction (global_load_lds_dwordx4): no staging registers, so a ring
+// of S LDS stages keeps up to S-1 K tiles in flight per workgroup while one is multiplied, which is what hides HBM
+// latency when an operand is not cache-resident (activations of another microbatch,
+// weights that have just arrived from the host).
+//
+// 128x128 block tile, four wavefronts of 64x64 (2x2 v_mfma_f32_32x32x16_bf16), K tile
+// BK in {32, 64}.  One s_waitcnt vmcnt + one barrier per K tile.
+//
+// A load-to-LDS instruction writes 64 lanes x 16 bytes to one contiguous KiB of LDS
+// (lane i at byte 16 i) from per-lane global addresses, so the bank swizzle is applied
+// on the global side: the lane that owns LDS slot p of a row fetches the chunk that
+// the swizzle maps to p.
+//
+// LDS layouts.  Operand with the contraction index contiguous in memory: [row][k],
+// 16-byte chunks XOR-swizzled by the row, read with ds_read_b128.  Operand stored
+// contraction-major: kept as loaded, [k][row], chunks swizzled by k, read through
+// ds_read_b64_tr_b16 with k rows 8h..8h+3 and 8h+4..8h+7 (h = lane/32), which is the
+// same contraction order as the 16-byte read of the other layout.
+#include <algorithm>
+#include <cstdlib>
+
+#include "dev_common.h"
+#include "hmy_internal.h"
+
+namespace hmy {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, NT = 256;  // square block tile, threads
+
+struct DmaP {
+  const bf16_t *A, *B;
+  void *C;
+  const bf16_t *bias, *res;
+  bf16_t *gelu_out;
+  int M, N, K;
+  uint32_t lda, ldb;
+  int64_t ldc, ldr;
+  int c_fp32, accumulate;
+};
+
+// element address inside a [row][k] tile of BK columns (BK/8 chunks per row)
+template <int BK>
+__device__ __forceinline__ int addr_rk(int row, int chunk) {
+  if (BK == 32) return row * 32 + ((chunk ^ ((row >> 2) & 3)) << 3);
+  return row * 64 + ((chunk ^ ((row >> 1) & 7)) << 3);
+}
+// element address inside a [k][row] tile (16 chunks per k-row, swizzled by k)
+__device__ __forceinline__ int addr_kr(int k, int col) {
+  return k * BM + ((((col >> 3) ^ ((k & 3) << 2)) & 15) << 3) + (col & 7);
+}
+
+// one wavefront-wide 16-byte-per-lane copy HBM -> LDS.  lds_addr is wave-uniform (the
+// hardware adds 16 * lane); the global address is base + byte offset per lane.
+__device__ __forceinline__ void dma16(const void *base, uint32_t byte_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(byte_off), "s"(base), "s"(lds_addr)
+               : "memory");
+}
+
+// Per-thread, loop-invariant byte offsets of this thread's lanes of every KiB it copies.
+// TR = false: memory [row][k]; KiB c holds rows c*R..c*R+R-1 (R = 512/BK), lane i owns slot i%(BK/8) of row i/(BK/8).
+// TR = true : memory [k][row]; KiB c holds k rows 4c..4c+3, lane i owns slot i%16 of k row i/16.
+// Wave w copies KiBs c = 4 j + w, j = 0..BK/16-1.  Rows outside the operand are
+// clamped into it: they only feed outputs that are never stored.
+template <bool TR, int BK>
+struct Dma {
+  static constexpr int NJ = BK / 16;
+  uint32_t off[TR ? 1 : NJ];
+  uint32_t step;  // TR: bytes between this thread's consecutive KiBs
+  __device__ __forceinline__ void init(uint32_t ld, int row0, int nrows, int lane, int wave) {
+    if (!TR) {
+      constexpr int CH = BK / 8, R = 64 / CH;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int row = (4 * j + wave) * R + lane / CH, slot = lane % CH;
+        const int chunk = BK == 32 ? (slot ^ ((row >> 2) & 3)) : (slot ^ ((row >> 1) & 7));
+        off[j] = (uint32_t(min(row0 + row, nrows - 1)) * ld + uint32_t(chunk * 8)) * 2u;
+      }
+      step = 0;
+    } else {
+      const int kq = lane / 16, slot = lane % 16;
+      const int chunk = slot ^ (kq << 2);   // k & 3 == lane / 16 for every KiB
+      const int col = min(row0 + chunk * 8, ((nrows + 7) & ~7) - 8);
+      off[0] = (uint32_t(4 * wave + kq) * ld + uint32_t(col)) * 2u;
+      step = 16u * ld * 2u;
+    }
+  }
+  // base: operand base advanced to the K tile; lds: byte address of the tile's stage
+  __device__ __forceinline__ void issue_one(const bf16_t *base, uint32_t lds, int wave, int j) const {
+    dma16(base, TR ? off[0] + uint32_t(j) * step : off[j], lds + uint32_t(4 * j + wave) * 1024u);
+  }
+  __device__ __forceinline__ void issue(const bf16_t *base, uint32_t lds, int wave) const {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) issue_one(base, lds, wave, j);
+  }
+};
+
+template <bool TR, int BK>
+__device__ __forceinline__ bf16x8 frag(const bf16_t *s, int row32, int ks, int lane) {
+  if (!TR) {
+    return *reinterpret_cast<const bf16x8 *>(s + addr_rk<BK>(row32 + lane % 32, 2 * ks + lane / 32));
+  } else {
+    const int q = lane % 16, g16 = (lane / 16) % 2, h = lane / 32;
+    const int k = 16 * ks + 8 * h + q / 4, col = row32 + 16 * g16 + 4 * (q % 4);
+    typedef __attribute__((address_space(3))) short4v *lds_ptr;
+    union { short4v s4[2]; bf16x8 b; } u;
+    u.s4[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(s + addr_kr(k, col)));
+    u.s4[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(s + addr_kr(k + 4, col)));
+    return u.b;
+  }
+}
+
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <bool TA, bool TB, int BK, int S>
+__global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, int grid_n) {
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  constexpr int TILE = BM * BK;            // elements per operand per stage
+  constexpr int L = 2 * (BK / 16);         // load-to-LDS instructions per thread per K tile
+  static_assert((S - 1) * L <= 63, "vmcnt is a 6-bit counter");
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int wm = wave / 2, wn = wave % 2;
+  // tile order: contiguous tile-id range per XCD, then bands of 8 tile rows walked column by column
+  int bid = blockIdx.x;
+  const int nb = gridDim.x, grid_m = nb / grid_n;
+  if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;
+  constexpr int kBand = 8;
+  const int band = bid / (kBand * grid_n), first_m = band * kBand;
+  const int band_rows = min(grid_m - first_m, kBand);
+  const int in_band = bid - band * kBand * grid_n;
+  const int m0 = (first_m + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BM;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk_all = p.K / BK;
+  const int kt0 = blockIdx.y * tiles_per_split;
+  const int n = min(nk_all, kt0 + tiles_per_split) - kt0;   // K tiles of this workgroup
+  Dma<TA, BK> da;
+  Dma<TB, BK> db;
+  da.init(p.lda, m0, p.M, lane, wave);
+  db.init(p.ldb, n0, p.N, lane, wave);
+  const uint32_t lds0 = uint32_t(reinterpret_cast<uintptr_t>(smem));
+  // element strides of one K tile in each operand
+  const uint64_t a_kstep = TA ? uint64_t(BK) * p.lda : uint64_t(BK);
+  const uint64_t b_kstep = TB ? uint64_t(BK) * p.ldb : uint64_t(BK);
+  const bf16_t *a_next = p.A + uint64_t(kt0) * a_kstep;
+  const bf16_t *b_next = p.B + uint64_t(kt0) * b_kstep;
+  auto issue = [&](int stage) {
+    da.issue(a_next, lds0 + uint32_t(stage) * uint32_t(4 * TILE), wave);
+    db.issue(b_next, lds0 + uint32_t(stage) * uint32_t(4 * TILE) + uint32_t(2 * TILE), wave);
+    a_next += a_kstep;
+    b_next += b_kstep;
+  };
+#pragma unroll
+  for (int s = 0; s < S; ++s)
+    if (s < n) issue(s);
+
+  const int arow = wm * 64, brow = wn * 64;
+  constexpr int KS = BK / 16;
+  bf16x8 fa[2][2], fb[2][2];   // operand fragments, double-buffered over the 16-deep steps
+  auto load_frags = [&](int buf, int stage, int ks) {
+    const bf16_t *a_s = smem + stage * (2 * TILE), *b_s = a_s + TILE;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      fa[buf][i] = frag<TA, BK>(a_s, arow + 32 * i, ks, lane);
+      fb[buf][i] = frag<TB, BK>(b_s, brow + 32 * i, ks, lane);
+    }
+  };
+  // tile 0 has landed once at most the S-1 tiles issued after it are outstanding
+  if (n > S - 1) wait_vm<(S - 1) * L>();
+  else wait_vm<0>();
+  __syncthreads();
+  if (n > 0) load_frags(0, 0, 0);
+  // the fences keep the scheduler from sinking a step's fragment reads below the
+  // previous step's multiplies (it would, to save registers, and expose the LDS latency)
+  auto mma_step = [&](int buf) {
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // one 16-deep step's share (one KiB of each operand per wave) of the next tile to fetch
+  auto issue_part = [&](int stage, int j) {
+    da.issue_one(a_next, lds0 + uint32_t(stage) * uint32_t(4 * TILE), wave, j);
+    db.issue_one(b_next, lds0 + uint32_t(stage) * uint32_t(4 * TILE) + uint32_t(2 * TILE), wave, j);
+  };
+  int stage = 0;      // stage holding tile t
+  int freed = S - 1;  // stage of tile t-1: free since the barrier that ended it
+  for (int t = 0; t + 1 < n; ++t) {
+    const int next = stage + 1 == S ? 0 : stage + 1;
+    // tile t+S-1 goes to the stage tile t-1 has left; its loads are spread over this
+    // tile's steps so that they queue behind multiplies, not in front of them
+    const bool fetch = t > 0 && t + S - 1 < n;
+#pragma unroll
+    for (int ks = 0; ks + 1 < KS; ++ks) {
+      load_frags((ks + 1) & 1, stage, ks + 1);
+      if (fetch) issue_part(freed, ks);
+      mma_step(ks & 1);
+    }
+    if (fetch) {
+      issue_part(freed, KS - 1);
+      a_next += a_kstep;
+      b_next += b_kstep;
+    }
+    // every read of tile t has been issued.  Tile t+1 has landed once at most the S-2
+    // tiles issued after it are outstanding.
+    if (t + S - 1 < n) wait_vm<(S - 2) * L>();
+    else wait_vm<0>();
+    __syncthreads();   // tile t+1 visible to every wave; every wave is done reading tile t
+    load_frags(0, next, 0);
+    mma_step((KS - 1) & 1);
+    freed = stage;
+    stage = next;
+  }
+  if (n > 0) {   // last tile: nothing left to wait for
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) load_frags((ks + 1) & 1, stage, ks + 1);
+      mma_step(ks & 1);
+    }
+  }
+
+  // accumulator register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32
+  const bool split = gridDim.y > 1;
+  int m_base = m0 + wm * 64 + 4 * (lane / 32), n_base = n0 + wn * 64 + lane % 32;
+  asm volatile("" : "+v"(m_base), "+v"(n_base));   // keep the output addressing out of the main loop
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int nn = n_base + j * 32;
+    if (nn >= p.N) continue;
+    const float bias_v = p.bias ? to_f32(p.bias[nn]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m_base + i * 32 + 8 * (r / 4) + r % 4;
+        if (m >= p.M) continue;
+        const int64_t ci = int64_t(m) * p.ldc + nn;
+        float v = acc[i][j][r] + bias_v;
+        if (p.res) v += to_f32(p.res[int64_t(m) * p.ldr + nn]);
+        if (split) {
+          atomicAdd(static_cast<float *>(p.C) + ci, v);
+        } else if (p.c_fp32) {
+          float *c = static_cast<float *>(p.C);
+          c[ci] = p.accumulate ? c[ci] + v : v;
+        } else {
+          const bf16_t o = from_f32<bf16_t>(v);
+          static_cast<bf16_t *>(p.C)[ci] = o;
+          if (p.gelu_out) p.gelu_out[ci] = from_f32<bf16_t>(gelu_f(to_f32(o)));
+        }
+      }
+  }
+}
+
+inline int check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(HMY_E_HIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return HMY_OK;
+}
+
+template <int BK, int S>
+int launch_cfg(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int tiles_per_split, int gn, hipStream_t s) {
+  const size_t lds = size_t(S) * 2 * BM * BK * sizeof(bf16_t);
+  dim3 block(NT);
+  if (!g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<false, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
+  else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_dma<false, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
+  else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<true, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
+  else hipLaunchKernelGGL((k_gemm_dma<true, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
+  return check_launch("gemm_dma");
+}
+
+int env_int(const char *name, int dflt) {
+  const char *v = std::getenv(name);
+  return v ? std::atoi(v) : dflt;
+}
+
+}  // namespace
+
+// Shapes this kernel takes: K a multiple of 32 (no K tail: the copy engine cannot
+// mask), 16-byte aligned operands with leading dimensions that are multiples of 8
+// elements, every operand spanning less than 4 GiB (32-bit byte offsets).
+bool gemm_dma_eligible(const hmy_gemm_desc &g) {
+  const int64_t a_span = int64_t(g.ta ? g.K : g.M) * g.lda, b_span = int64_t(g.tb ? g.K : g.N) * g.ldb;
+  return g.K % 32 == 0 && a_span < (int64_t(1) << 31) && b_span < (int64_t(1) << 31);
+}
+
+int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st) {
+  DmaP p;
+  p.A = static_cast<const bf16_t *>(g.A); p.B = static_cast<const bf16_t *>(g.B); p.C = g.C;
+  p.bias = static_cast<const bf16_t *>(g.bias); p.res = static_cast<const bf16_t *>(g.res);
+  p.gelu_out = static_cast<bf16_t *>(g.gelu_out);
+  p.M = g.M; p.N = g.N; p.K = g.K;
+  p.lda = uint32_t(g.lda); p.ldb = uint32_t(g.ldb); p.ldc = g.ldc; p.ldr = g.ldr;
+  p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate;
+  static const int force_bk = env_int("HMY_GEMM_BK", 0), force_s = env_int("HMY_GEMM_STAGES", 0);
+  const int gm = (g.M + BM - 1) / BM, gn = (g.N + BM - 1) / BM;
+  int bk = g.K % 64 == 0 ? 64 : 32;
+  if (force_bk == 32 || (force_bk == 64 && g.K % 64 == 0)) bk = force_bk;
+  const int nk = g.K / bk;
+  // split the contraction over workgroups (fp32 atomics into C) when an accumulating
+  // GEMM has too few output tiles to fill 256 compute units several times over
+  int splits = 1;
+  if (g.accumulate && g.c_fp32 && !g.bias && !g.res && gm * gn < 512)
+    splits = std::max(1, std::min((768 + gm * gn - 1) / (gm * gn), nk * bk / 256));
+  const int tiles_per_split = (nk + splits - 1) / splits;
+  splits = (nk + tiles_per_split - 1) / tiles_per_split;
+  dim3 grid(gm * gn, splits);
+  hipStream_t s = (hipStream_t)st;
+  // one workgroup per compute unit can use a deep ring; with several tiles per unit two
+  // resident workgroups with shorter rings overlap each other's prologue and epilogue
+  int stages = int(grid.x) * int(grid.y) <= 256 ? 4 : 2;
+  if (force_s >= 2 && force_s <= 4) stages = force_s;
+  if (bk == 64) {
+    if (stages == 2) return launch_cfg<64, 2>(g, p, grid, tiles_per_split, gn, s);
+    if (stages == 3) return launch_cfg<64, 3>(g, p, grid, tiles_per_split, gn, s);
+    return launch_cfg<64, 4>(g, p, grid, tiles_per_split, gn, s);
+  }
+  if (stages == 2) return launch_cfg<32, 2>(g, p, grid, tiles_per_split, gn, s);
+  if (stages == 3) return launch_cfg<32, 3>(g, p, grid, tiles_per_split, gn, s);
+  return launch_cfg<32, 4>(g, p, grid, tiles_per_split, gn, s);
+}
+
+}  // namespace hmy

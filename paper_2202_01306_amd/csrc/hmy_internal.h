@@ -116,6 +116,8 @@ int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st
 int launch_gemm(const hmy_gemm_desc &g, stream_t st);
 
 int launch_gemm_mfma32(const hmy_gemm_desc &g, stream_t st);
+bool gemm_dma_eligible(const hmy_gemm_desc &g);
+int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st);
 int launch_attn_fwd(int prec, const void *qkv, void *o, float *lse, int b, int s, int H, int dh,
                     int causal, stream_t st);
 int launch_attn_bwd(int prec, const void *qkv, const void *o, const void *d_o, const float *lse,
