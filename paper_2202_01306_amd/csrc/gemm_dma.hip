@@ -18,7 +18,9 @@
 // ds_read_b64_tr_b16 with k rows 8h..8h+3 and 8h+4..8h+7 (h = lane/32), which is the
 // same contraction order as the 16-byte read of the other layout.
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
+#include <vector>
 
 #include "dev_common.h"
 #include "hmy_internal.h"
@@ -42,6 +44,7 @@ struct DmaP {
   uint32_t lda, ldb;
   int64_t ldc, ldr;
   int c_fp32, accumulate;
+  long long *ts;  // DEV: per-block phase timestamps
 };
 
 // element address inside a [row][k] tile of BK columns (BK/8 chunks per row)
@@ -119,11 +122,100 @@ __device__ __forceinline__ bf16x8 frag(const bf16_t *s, int row32, int ks, int l
 
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
+// Output stage for 8 consecutive columns of one row.
+struct Epi {
+  bool split, vec_c, vec_res, vec_bias, vec_gelu;
+  __device__ __forceinline__ void init(const DmaP &p, bool split_) {
+    split = split_;
+    const int esz = p.c_fp32 ? 4 : 2;
+    vec_c = (reinterpret_cast<uintptr_t>(p.C) & 15) == 0 && (p.ldc * esz) % 16 == 0;
+    vec_res = p.res && (reinterpret_cast<uintptr_t>(p.res) & 15) == 0 && p.ldr % 8 == 0;
+    vec_bias = p.bias && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;
+    vec_gelu = p.gelu_out && (reinterpret_cast<uintptr_t>(p.gelu_out) & 15) == 0 && p.ldc % 8 == 0;
+  }
+  __device__ __forceinline__ void emit(const DmaP &p, int m, int nn, float (&v)[8]) const {
+    const int cnt = min(8, p.N - nn);   // columns in range
+    const bool full = cnt == 8;
+    if (p.bias) {
+      if (full && vec_bias) {
+        const Vec16<bf16_t> b = load16(p.bias + nn);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+          if (c < cnt) v[c] += to_f32(p.bias[nn + c]);
+      }
+    }
+    if (p.res) {
+      const bf16_t *r = p.res + int64_t(m) * p.ldr + nn;
+      if (full && vec_res) {
+        const Vec16<bf16_t> b = load16(r);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+          if (c < cnt) v[c] += to_f32(r[c]);
+      }
+    }
+    const int64_t ci = int64_t(m) * p.ldc + nn;
+    if (split) {
+      float *c = static_cast<float *>(p.C) + ci;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (k < cnt) atomicAdd(c + k, v[k]);
+    } else if (p.c_fp32) {
+      float *c = static_cast<float *>(p.C) + ci;
+      if (full && vec_c) {
+        float4 lo = *reinterpret_cast<float4 *>(v), hi = *reinterpret_cast<float4 *>(v + 4);
+        if (p.accumulate) {
+          const float4 a = *reinterpret_cast<const float4 *>(c), b = *reinterpret_cast<const float4 *>(c + 4);
+          lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+          hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
+        }
+        *reinterpret_cast<float4 *>(c) = lo;
+        *reinterpret_cast<float4 *>(c + 4) = hi;
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (k < cnt) c[k] = p.accumulate ? c[k] + v[k] : v[k];
+      }
+    } else {
+      bf16_t *c = static_cast<bf16_t *>(p.C) + ci;
+      Vec16<bf16_t> o, g;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        o.v[k] = from_f32<bf16_t>(v[k]);
+        if (p.gelu_out) g.v[k] = from_f32<bf16_t>(gelu_f(to_f32(o.v[k])));
+      }
+      if (full && vec_c) {
+        store16(c, o);
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (k < cnt) c[k] = o.v[k];
+      }
+      if (p.gelu_out) {
+        bf16_t *go = p.gelu_out + ci;
+        if (full && vec_gelu) {
+          store16(go, g);
+        } else {
+#pragma unroll
+          for (int k = 0; k < 8; ++k)
+            if (k < cnt) go[k] = g.v[k];
+        }
+      }
+    }
+  }
+};
+
 template <bool TA, bool TB, int BK, int S>
 __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, int grid_n) {
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   constexpr int TILE = BM * BK;            // elements per operand per stage
   constexpr int L = 2 * (BK / 16);         // load-to-LDS instructions per thread per K tile
+  static_assert(S >= 3, "the tile being fetched gets its last part after the barrier: two tiles must be ahead of it");
   static_assert((S - 1) * L <= 63, "vmcnt is a 6-bit counter");
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -138,6 +230,8 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   const int in_band = bid - band * kBand * grid_n;
   const int m0 = (first_m + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BM;
 
+  long long ts0 = 0, ts1 = 0, ts2 = 0, cy1 = 0, cy2 = 0;
+  if (p.ts) ts0 = wall_clock64();
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -185,87 +279,119 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   else wait_vm<0>();
   __syncthreads();
   if (n > 0) load_frags(0, 0, 0);
-  // the fences keep the scheduler from sinking a step's fragment reads below the
-  // previous step's multiplies (it would, to save registers, and expose the LDS latency)
-  auto mma_step = [&](int buf) {
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  // one 16-deep step's share (one KiB of each operand per wave) of the next tile to fetch
-  auto issue_part = [&](int stage, int j) {
-    da.issue_one(a_next, lds0 + uint32_t(stage) * uint32_t(4 * TILE), wave, j);
-    db.issue_one(b_next, lds0 + uint32_t(stage) * uint32_t(4 * TILE) + uint32_t(2 * TILE), wave, j);
+  if (p.ts) { ts1 = wall_clock64(); cy1 = clock64(); }
+  // One 16-deep step: the four multiplies on fragment buffer `cur`, each followed by one
+  // of the four fragment reads of the next step (into the other buffer) and, twice, by
+  // one load-to-LDS of the tile being fetched.  A wavefront issues in order and an LDS
+  // read occupies its issue slot for some 20 cycles, so reads grouped in front of the
+  // multiplies would delay them; placed behind a multiply each read issues while the
+  // matrix pipe works through that multiply's 32 cycles.  The fences pin this order.
+#define HMY_FENCE() __builtin_amdgcn_sched_barrier(0)
+  auto step = [&](int cur, bool reads, int nstage, int nks, bool fetch, int fstage, int part) {
+    const bf16_t *a_s = smem + nstage * (2 * TILE), *b_s = a_s + TILE;
+    const uint32_t fl = lds0 + uint32_t(fstage) * uint32_t(4 * TILE);
+    HMY_FENCE();
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][0], acc[0][0], 0, 0, 0);
+    HMY_FENCE();
+    if (reads) fa[cur ^ 1][0] = frag<TA, BK>(a_s, arow, nks, lane);
+    HMY_FENCE();
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][1], acc[0][1], 0, 0, 0);
+    HMY_FENCE();
+    if (reads) fb[cur ^ 1][0] = frag<TB, BK>(b_s, brow, nks, lane);
+    if (fetch) da.issue_one(a_next, fl, wave, part);
+    HMY_FENCE();
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur][0], acc[1][0], 0, 0, 0);
+    HMY_FENCE();
+    if (reads) fb[cur ^ 1][1] = frag<TB, BK>(b_s, brow + 32, nks, lane);
+    HMY_FENCE();
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur][1], acc[1][1], 0, 0, 0);
+    HMY_FENCE();
+    if (reads) fa[cur ^ 1][1] = frag<TA, BK>(a_s, arow + 32, nks, lane);
+    if (fetch) db.issue_one(b_next, fl + uint32_t(2 * TILE), wave, part);
+    HMY_FENCE();
   };
   int stage = 0;      // stage holding tile t
   int freed = S - 1;  // stage of tile t-1: free since the barrier that ended it
   for (int t = 0; t + 1 < n; ++t) {
     const int next = stage + 1 == S ? 0 : stage + 1;
     // tile t+S-1 goes to the stage tile t-1 has left; its loads are spread over this
-    // tile's steps so that they queue behind multiplies, not in front of them
+    // tile's steps
     const bool fetch = t > 0 && t + S - 1 < n;
 #pragma unroll
-    for (int ks = 0; ks + 1 < KS; ++ks) {
-      load_frags((ks + 1) & 1, stage, ks + 1);
-      if (fetch) issue_part(freed, ks);
-      mma_step(ks & 1);
-    }
+    for (int ks = 0; ks + 1 < KS; ++ks) step(ks & 1, true, stage, ks + 1, fetch, freed, ks);
+    // every read of tile t has been issued.  Tile t+1 has landed once at most the S-2
+    // tiles issued after it (the one being fetched lacks its last part) are outstanding.
+    if (t + S - 1 < n) wait_vm<(S - 2) * L - (S > 2 ? 2 : 0)>();
+    else wait_vm<0>();
+    __syncthreads();   // tile t+1 visible to every wave; every wave is done reading tile t
+    step((KS - 1) & 1, true, next, 0, fetch, freed, KS - 1);
     if (fetch) {
-      issue_part(freed, KS - 1);
       a_next += a_kstep;
       b_next += b_kstep;
     }
-    // every read of tile t has been issued.  Tile t+1 has landed once at most the S-2
-    // tiles issued after it are outstanding.
-    if (t + S - 1 < n) wait_vm<(S - 2) * L>();
-    else wait_vm<0>();
-    __syncthreads();   // tile t+1 visible to every wave; every wave is done reading tile t
-    load_frags(0, next, 0);
-    mma_step((KS - 1) & 1);
     freed = stage;
     stage = next;
   }
-  if (n > 0) {   // last tile: nothing left to wait for
+  if (n > 0) {   // last tile: nothing left to fetch or wait for
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) load_frags((ks + 1) & 1, stage, ks + 1);
-      mma_step(ks & 1);
-    }
+    for (int ks = 0; ks < KS; ++ks) step(ks & 1, ks + 1 < KS, stage, ks + 1, false, 0, 0);
   }
+#undef HMY_FENCE
 
-  // accumulator register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32
+  if (p.ts) { ts2 = wall_clock64(); cy2 = clock64(); }
+  // Epilogue.  Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4,
+  // column l%32 of a 32x32 block: stored from there, a wavefront would write 2-byte
+  // elements in 64-byte runs.  Each wave instead passes its 64x64 outputs, 32 rows at a
+  // time, through 8 KiB of LDS (the operand stages are free now) and leaves with 8
+  // consecutive columns per lane: 16-byte stores, 128 contiguous bytes per row.  Rows
+  // that differ in bit 2 are written by the two lane halves at once; flipping bit 5 of
+  // the column for them keeps the halves on different banks.
   const bool split = gridDim.y > 1;
-  int m_base = m0 + wm * 64 + 4 * (lane / 32), n_base = n0 + wn * 64 + lane % 32;
-  asm volatile("" : "+v"(m_base), "+v"(n_base));   // keep the output addressing out of the main loop
+  if (split) {   // fp32 atomics: one column per lane, straight from the accumulator layout
+    const int m_base = m0 + wm * 64 + 4 * (lane / 32), n_base = n0 + wn * 64 + lane % 32;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int nn = n_base + j * 32;
-    if (nn >= p.N) continue;
-    const float bias_v = p.bias ? to_f32(p.bias[nn]) : 0.f;
+    for (int j = 0; j < 2; ++j) {
+      const int nn = n_base + j * 32;
+      if (nn >= p.N) continue;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m_base + i * 32 + 8 * (r / 4) + r % 4;
+          if (m < p.M) atomicAdd(static_cast<float *>(p.C) + int64_t(m) * p.ldc + nn, acc[i][j][r]);
+        }
+    }
+    return;
+  }
+  __syncthreads();   // every wave has finished reading the operand stages
+  float *slab = reinterpret_cast<float *>(smem) + wave * 2048;
+  Epi e;
+  e.init(p, false);
+  const int m_tile = m0 + wm * 64, n_tile = n0 + wn * 64;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m_base + i * 32 + 8 * (r / 4) + r % 4;
-        if (m >= p.M) continue;
-        const int64_t ci = int64_t(m) * p.ldc + nn;
-        float v = acc[i][j][r] + bias_v;
-        if (p.res) v += to_f32(p.res[int64_t(m) * p.ldr + nn]);
-        if (split) {
-          atomicAdd(static_cast<float *>(p.C) + ci, v);
-        } else if (p.c_fp32) {
-          float *c = static_cast<float *>(p.C);
-          c[ci] = p.accumulate ? c[ci] + v : v;
-        } else {
-          const bf16_t o = from_f32<bf16_t>(v);
-          static_cast<bf16_t *>(p.C)[ci] = o;
-          if (p.gelu_out) p.gelu_out[ci] = from_f32<bf16_t>(gelu_f(to_f32(o)));
-        }
+        const int row = 8 * (r / 4) + 4 * (lane / 32) + r % 4, col = 32 * j + lane % 32;
+        slab[row * 64 + (col ^ (((row >> 2) & 1) << 5))] = acc[i][j][r];
       }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = 8 * q + lane / 8, c0 = 8 * (lane % 8);
+      const float *src = slab + row * 64 + (c0 ^ (((row >> 2) & 1) << 5));
+      float v[8];
+      *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
+      *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
+      const int m = m_tile + 32 * i + row, nn = n_tile + c0;
+      if (m < p.M && nn < p.N) e.emit(p, m, nn, v);
+    }
+  }
+  if (p.ts && tid == 0) {
+    long long *o = p.ts + 4 * (blockIdx.x + gridDim.x * blockIdx.y);
+    o[0] = ts0; o[1] = ts1; o[2] = ts2; o[3] = wall_clock64();
+    if (blockIdx.x == 0 && blockIdx.y == 0) p.ts[4 * gridDim.x * gridDim.y] = cy2 - cy1;
   }
 }
 
@@ -283,6 +409,17 @@ int launch_cfg(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int tiles_per_s
   else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_dma<false, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
   else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<true, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
   else hipLaunchKernelGGL((k_gemm_dma<true, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
+  if (p.ts) {
+    (void)hipStreamSynchronize(s);
+    const int nb = int(grid.x * grid.y);
+    std::vector<long long> h(4 * nb);
+    (void)hipMemcpy(h.data(), p.ts, h.size() * 8, hipMemcpyDeviceToHost);
+    long long t0 = h[0], tend = 0; double pro = 0, loop = 0, epi = 0;
+    for (int b = 0; b < nb; ++b) { t0 = std::min(t0, h[4 * b]); tend = std::max(tend, h[4 * b + 3]); pro += h[4 * b + 1] - h[4 * b]; loop += h[4 * b + 2] - h[4 * b + 1]; epi += h[4 * b + 3] - h[4 * b + 2]; }
+    std::printf("[ts] BK=%d S=%d blocks=%d span %.2f us; per block: prologue %.2f us, loop %.2f us, epilogue %.2f us\n", BK, S, nb, (tend - t0) * 0.01, pro / nb * 0.01, loop / nb * 0.01, epi / nb * 0.01);
+    { long long cyc = 0; (void)hipMemcpy(&cyc, p.ts + 4 * nb, 8, hipMemcpyDeviceToHost); std::printf("   block 0 loop: %lld shader cycles over %.2f us = %.0f MHz\n", cyc, (h[2] - h[1]) * 0.01, cyc / ((h[2] - h[1]) * 0.01)); }
+    for (int b : {0, 1, nb / 2, nb - 1}) std::printf("   block %d: start %.2f pro %.2f loop %.2f epi %.2f\n", b, (h[4 * b] - t0) * 0.01, (h[4 * b + 1] - h[4 * b]) * 0.01, (h[4 * b + 2] - h[4 * b + 1]) * 0.01, (h[4 * b + 3] - h[4 * b + 2]) * 0.01);
+  }
   return check_launch("gemm_dma");
 }
 
@@ -309,32 +446,34 @@ int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st) {
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.lda = uint32_t(g.lda); p.ldb = uint32_t(g.ldb); p.ldc = g.ldc; p.ldr = g.ldr;
   p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate;
+  static long long *ts_buf = nullptr;
+  static const int want_ts = env_int("HMY_GEMM_TS", 0);
+  if (want_ts && !ts_buf) (void)hipMalloc(&ts_buf, 4 * 8 * 65536);
+  p.ts = want_ts ? ts_buf : nullptr;
   static const int force_bk = env_int("HMY_GEMM_BK", 0), force_s = env_int("HMY_GEMM_STAGES", 0);
   const int gm = (g.M + BM - 1) / BM, gn = (g.N + BM - 1) / BM;
-  int bk = g.K % 64 == 0 ? 64 : 32;
-  if (force_bk == 32 || (force_bk == 64 && g.K % 64 == 0)) bk = force_bk;
-  const int nk = g.K / bk;
   // split the contraction over workgroups (fp32 atomics into C) when an accumulating
   // GEMM has too few output tiles to fill 256 compute units several times over
   int splits = 1;
   if (g.accumulate && g.c_fp32 && !g.bias && !g.res && gm * gn < 512)
-    splits = std::max(1, std::min((768 + gm * gn - 1) / (gm * gn), nk * bk / 256));
-  const int tiles_per_split = (nk + splits - 1) / splits;
-  splits = (nk + tiles_per_split - 1) / tiles_per_split;
+    splits = std::max(1, std::min((768 + gm * gn - 1) / (gm * gn), g.K / 256));
+  // few workgroups: one per compute unit, deep K tiles and a deep ring; many: smaller
+  // stages so that several are resident and overlap each other's prologue and epilogue
+  int bk = g.K % 64 == 0 && gm * gn * splits <= 256 ? 64 : 32;
+  if (force_bk == 32 || (force_bk == 64 && g.K % 64 == 0)) bk = force_bk;
+  int stages = 4;
+  if (force_s >= 3 && force_s <= 4) stages = force_s;
+  const int nk = g.K / bk;
+  const int tps = (nk + splits - 1) / splits;
+  splits = (nk + tps - 1) / tps;
   dim3 grid(gm * gn, splits);
   hipStream_t s = (hipStream_t)st;
-  // one workgroup per compute unit can use a deep ring; with several tiles per unit two
-  // resident workgroups with shorter rings overlap each other's prologue and epilogue
-  int stages = int(grid.x) * int(grid.y) <= 256 ? 4 : 2;
-  if (force_s >= 2 && force_s <= 4) stages = force_s;
   if (bk == 64) {
-    if (stages == 2) return launch_cfg<64, 2>(g, p, grid, tiles_per_split, gn, s);
-    if (stages == 3) return launch_cfg<64, 3>(g, p, grid, tiles_per_split, gn, s);
-    return launch_cfg<64, 4>(g, p, grid, tiles_per_split, gn, s);
+    if (stages == 3) return launch_cfg<64, 3>(g, p, grid, tps, gn, s);
+    return launch_cfg<64, 4>(g, p, grid, tps, gn, s);
   }
-  if (stages == 2) return launch_cfg<32, 2>(g, p, grid, tiles_per_split, gn, s);
-  if (stages == 3) return launch_cfg<32, 3>(g, p, grid, tiles_per_split, gn, s);
-  return launch_cfg<32, 4>(g, p, grid, tiles_per_split, gn, s);
+  if (stages == 3) return launch_cfg<32, 3>(g, p, grid, tps, gn, s);
+  return launch_cfg<32, 4>(g, p, grid, tps, gn, s);
 }
 
 }  // namespace hmy
