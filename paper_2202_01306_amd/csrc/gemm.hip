@@ -346,6 +346,19 @@ int launch_gemm(const hmy_gemm_desc &g, stream_t st) {
   const bool mfma_ok = g.prec == HMY_PREC_BF16 && g_use_mfma && aligned16(g.A) && aligned16(g.B) && g.lda % 8 == 0 &&
                        g.ldb % 8 == 0 && a_span < (int64_t(1) << 31) && b_span < (int64_t(1) << 31);
   if (mfma_ok && g_use_mfma == 1 && gemm_dma_eligible(g)) return launch_gemm_dma(g, st);
+  if (mfma_ok && g_use_mfma == 1 && g.K % 32 != 0 && g.K > 256 && g.accumulate && g.c_fp32 && !g.bias && !g.res) {
+    // accumulating GEMM with a ragged contraction: the multiple-of-32 part goes to the
+    // load-to-LDS kernel, the tail is added by the register-staged one (which masks)
+    hmy_gemm_desc body = g, tail = g;
+    body.K = g.K / 32 * 32;
+    tail.K = g.K - body.K;
+    tail.A = static_cast<const bf16_t *>(g.A) + (g.ta ? int64_t(body.K) * g.lda : int64_t(body.K));
+    tail.B = static_cast<const bf16_t *>(g.B) + (g.tb ? int64_t(body.K) * g.ldb : int64_t(body.K));
+    if (gemm_dma_eligible(body) && aligned16(tail.A) && aligned16(tail.B)) {
+      const int rc = launch_gemm_dma(body, st);
+      return rc ? rc : launch_gemm_mfma32(tail, st);
+    }
+  }
   if (mfma_ok && g_use_mfma != 2) return launch_gemm_mfma32(g, st);
   if (mfma_ok) {
     const int gm = (g.M + BM - 1) / BM, gn = (g.N + BN - 1) / BN, nk = (g.K + BK - 1) / BK;

@@ -122,90 +122,66 @@ __device__ __forceinline__ bf16x8 frag(const bf16_t *s, int row32, int ks, int l
 
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// Output stage for 8 consecutive columns of one row.
+// Output stage for 8 consecutive columns of one row.  `fast`: the workgroup's tile lies
+// inside C and every pointer and leading dimension allows 16-byte accesses; the other
+// path is element-wise and kept rolled, so that it costs no instruction-cache space.
 struct Epi {
-  bool split, vec_c, vec_res, vec_bias, vec_gelu;
-  __device__ __forceinline__ void init(const DmaP &p, bool split_) {
-    split = split_;
+  bool fast;
+  __device__ __forceinline__ void init(const DmaP &p, int m0, int n0) {
     const int esz = p.c_fp32 ? 4 : 2;
-    vec_c = (reinterpret_cast<uintptr_t>(p.C) & 15) == 0 && (p.ldc * esz) % 16 == 0;
-    vec_res = p.res && (reinterpret_cast<uintptr_t>(p.res) & 15) == 0 && p.ldr % 8 == 0;
-    vec_bias = p.bias && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;
-    vec_gelu = p.gelu_out && (reinterpret_cast<uintptr_t>(p.gelu_out) & 15) == 0 && p.ldc % 8 == 0;
+    bool ok = (reinterpret_cast<uintptr_t>(p.C) & 15) == 0 && (p.ldc * esz) % 16 == 0;
+    if (p.res) ok = ok && (reinterpret_cast<uintptr_t>(p.res) & 15) == 0 && p.ldr % 8 == 0;
+    if (p.bias) ok = ok && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;
+    if (p.gelu_out) ok = ok && (reinterpret_cast<uintptr_t>(p.gelu_out) & 15) == 0;
+    fast = ok && m0 + BM <= p.M && n0 + BM <= p.N;
   }
-  __device__ __forceinline__ void emit(const DmaP &p, int m, int nn, float (&v)[8]) const {
-    const int cnt = min(8, p.N - nn);   // columns in range
-    const bool full = cnt == 8;
+  __device__ __forceinline__ void emit_fast(const DmaP &p, int m, int nn, float (&v)[8]) const {
     if (p.bias) {
-      if (full && vec_bias) {
-        const Vec16<bf16_t> b = load16(p.bias + nn);
+      const Vec16<bf16_t> b = load16(p.bias + nn);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
-      } else {
-#pragma unroll
-        for (int c = 0; c < 8; ++c)
-          if (c < cnt) v[c] += to_f32(p.bias[nn + c]);
-      }
+      for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
     }
     if (p.res) {
-      const bf16_t *r = p.res + int64_t(m) * p.ldr + nn;
-      if (full && vec_res) {
-        const Vec16<bf16_t> b = load16(r);
+      const Vec16<bf16_t> b = load16(p.res + int64_t(m) * p.ldr + nn);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
-      } else {
-#pragma unroll
-        for (int c = 0; c < 8; ++c)
-          if (c < cnt) v[c] += to_f32(r[c]);
-      }
+      for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
     }
     const int64_t ci = int64_t(m) * p.ldc + nn;
-    if (split) {
+    if (p.c_fp32) {
       float *c = static_cast<float *>(p.C) + ci;
-#pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (k < cnt) atomicAdd(c + k, v[k]);
-    } else if (p.c_fp32) {
-      float *c = static_cast<float *>(p.C) + ci;
-      if (full && vec_c) {
-        float4 lo = *reinterpret_cast<float4 *>(v), hi = *reinterpret_cast<float4 *>(v + 4);
-        if (p.accumulate) {
-          const float4 a = *reinterpret_cast<const float4 *>(c), b = *reinterpret_cast<const float4 *>(c + 4);
-          lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
-          hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
-        }
-        *reinterpret_cast<float4 *>(c) = lo;
-        *reinterpret_cast<float4 *>(c + 4) = hi;
-      } else {
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-          if (k < cnt) c[k] = p.accumulate ? c[k] + v[k] : v[k];
+      float4 lo = *reinterpret_cast<float4 *>(v), hi = *reinterpret_cast<float4 *>(v + 4);
+      if (p.accumulate) {
+        const float4 a = *reinterpret_cast<const float4 *>(c), b = *reinterpret_cast<const float4 *>(c + 4);
+        lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+        hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
       }
+      *reinterpret_cast<float4 *>(c) = lo;
+      *reinterpret_cast<float4 *>(c + 4) = hi;
     } else {
-      bf16_t *c = static_cast<bf16_t *>(p.C) + ci;
-      Vec16<bf16_t> o, g;
+      Vec16<bf16_t> o;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        o.v[k] = from_f32<bf16_t>(v[k]);
-        if (p.gelu_out) g.v[k] = from_f32<bf16_t>(gelu_f(to_f32(o.v[k])));
-      }
-      if (full && vec_c) {
-        store16(c, o);
-      } else {
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-          if (k < cnt) c[k] = o.v[k];
-      }
+      for (int k = 0; k < 8; ++k) o.v[k] = from_f32<bf16_t>(v[k]);
+      store16(static_cast<bf16_t *>(p.C) + ci, o);
       if (p.gelu_out) {
-        bf16_t *go = p.gelu_out + ci;
-        if (full && vec_gelu) {
-          store16(go, g);
-        } else {
+        Vec16<bf16_t> g;
 #pragma unroll
-          for (int k = 0; k < 8; ++k)
-            if (k < cnt) go[k] = g.v[k];
-        }
+        for (int k = 0; k < 8; ++k) g.v[k] = from_f32<bf16_t>(gelu_f(to_f32(o.v[k])));
+        store16(p.gelu_out + ci, g);
       }
+    }
+  }
+  // one element; src points at its fp32 value in LDS
+  __device__ __forceinline__ void emit_one(const DmaP &p, int m, int nn, float v) const {
+    if (p.bias) v += to_f32(p.bias[nn]);
+    if (p.res) v += to_f32(p.res[int64_t(m) * p.ldr + nn]);
+    const int64_t ci = int64_t(m) * p.ldc + nn;
+    if (p.c_fp32) {
+      float *c = static_cast<float *>(p.C) + ci;
+      *c = p.accumulate ? *c + v : v;
+    } else {
+      const bf16_t o = from_f32<bf16_t>(v);
+      static_cast<bf16_t *>(p.C)[ci] = o;
+      if (p.gelu_out) p.gelu_out[ci] = from_f32<bf16_t>(gelu_f(to_f32(o)));
     }
   }
 };
@@ -366,7 +342,7 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   __syncthreads();   // every wave has finished reading the operand stages
   float *slab = reinterpret_cast<float *>(smem) + wave * 2048;
   Epi e;
-  e.init(p, false);
+  e.init(p, m0, n0);
   const int m_tile = m0 + wm * 64, n_tile = n0 + wn * 64;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
@@ -377,15 +353,23 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
         const int row = 8 * (r / 4) + 4 * (lane / 32) + r % 4, col = 32 * j + lane % 32;
         slab[row * 64 + (col ^ (((row >> 2) & 1) << 5))] = acc[i][j][r];
       }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int row = 8 * q + lane / 8, c0 = 8 * (lane % 8);
-      const float *src = slab + row * 64 + (c0 ^ (((row >> 2) & 1) << 5));
-      float v[8];
-      *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
-      *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
-      const int m = m_tile + 32 * i + row, nn = n_tile + c0;
-      if (m < p.M && nn < p.N) e.emit(p, m, nn, v);
+    if (e.fast) {
+#pragma unroll 1
+      for (int q = 0; q < 4; ++q) {
+        const int row = 8 * q + lane / 8, c0 = 8 * (lane % 8);
+        const float *src = slab + row * 64 + (c0 ^ (((row >> 2) & 1) << 5));
+        float v[8];
+        *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
+        *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
+        e.emit_fast(p, m_tile + 32 * i + row, n_tile + c0, v);
+      }
+    } else {
+#pragma unroll 1
+      for (int idx = lane; idx < 32 * 64; idx += 64) {   // one row of 64 columns per pass
+        const int row = idx / 64, col = idx % 64;
+        const int m = m_tile + 32 * i + row, nn = n_tile + col;
+        if (m < p.M && nn < p.N) e.emit_one(p, m, nn, slab[row * 64 + (col ^ (((row >> 2) & 1) << 5))]);
+      }
     }
   }
   if (p.ts && tid == 0) {
@@ -452,11 +436,12 @@ int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st) {
   p.ts = want_ts ? ts_buf : nullptr;
   static const int force_bk = env_int("HMY_GEMM_BK", 0), force_s = env_int("HMY_GEMM_STAGES", 0);
   const int gm = (g.M + BM - 1) / BM, gn = (g.N + BM - 1) / BM;
-  // split the contraction over workgroups (fp32 atomics into C) when an accumulating
-  // GEMM has too few output tiles to fill 256 compute units several times over
+  // split the contraction over workgroups (fp32 atomics into C) only while that fills
+  // idle compute units: with one workgroup per unit already, a deeper K loop beats more
+  // workgroups that each pay a prologue and an atomic epilogue
   int splits = 1;
-  if (g.accumulate && g.c_fp32 && !g.bias && !g.res && gm * gn < 512)
-    splits = std::max(1, std::min((768 + gm * gn - 1) / (gm * gn), g.K / 256));
+  if (g.accumulate && g.c_fp32 && !g.bias && !g.res && gm * gn <= 128)
+    splits = std::max(1, std::min(256 / (gm * gn), g.K / 256));
   // few workgroups: one per compute unit, deep K tiles and a deep ring; many: smaller
   // stages so that several are resident and overlap each other's prologue and epilogue
   int bk = g.K % 64 == 0 && gm * gn * splits <= 256 ? 64 : 32;
