@@ -70,6 +70,7 @@ struct hmy_handle {
   // true: the Adam kernel writes its results directly into the pinned host arrays;
   // false: results go to the ring / slot and leave by hipMemcpyAsync on s_out
   bool fused_swap_out = true;
+  bool k_zero_copy = true;   // the update kernel reads optimizer state straight from pinned host memory
 };
 
 #define HIPCHK(h, call)                                                                      \
@@ -478,10 +479,21 @@ void update_visit(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_d
     float *r_m = (float *)(ring + (mixed ? 1 : 0) * R.karr_bytes);
     float *r_v = (float *)(ring + (mixed ? 2 : 1) * R.karr_bytes);
     const uint64_t g0 = v.poff + lo;  // element offset in the host arrays
-    wait(h, h->s_upd, it.k_free[r]);
-    if (mixed) h2d(h, HMY_KIND_K, r_master, h->dry ? nullptr : h->host.master + g0, n * 4, h->s_upd);
-    h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_upd);
-    h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_upd);
+    const bool zc = h->fused_swap_out && h->k_zero_copy;
+    if (zc) {
+      // no staging copy: the state crosses the link inside the update kernel's own loads
+      h->st.h2d[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
+      if (!h->dry) {
+        r_master = mixed ? h->host.master + g0 : nullptr;
+        r_m = h->host.adam_m + g0;
+        r_v = h->host.adam_v + g0;
+      }
+    } else {
+      wait(h, h->s_upd, it.k_free[r]);
+      if (mixed) h2d(h, HMY_KIND_K, r_master, h->dry ? nullptr : h->host.master + g0, n * 4, h->s_upd);
+      h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_upd);
+      h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_upd);
+    }
     if (c == 0) wait(h, h->s_upd, bwd_done);
     if (h->fused_swap_out) {
       // the update kernel itself writes state, weights and gradients to the host arrays
@@ -497,6 +509,7 @@ void update_visit(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_d
                                 h->s_upd));
         const size_t b2 = trec(h, h->s_upd);
         span(h, a, b2, 1);
+        if (zc) span(h, a, b2, 0);   // the same kernel carries the host->device half
       }
       it.k_free[r] = rec(h, h->s_upd);
       continue;
@@ -719,6 +732,8 @@ int hmy_bind_state(hmy_handle *h, const hmy_host_state *state) {
   h->bound = true;
   const char *zc = std::getenv("HMY_FUSED_SWAP_OUT");
   if (zc) h->fused_swap_out = std::atoi(zc) != 0;
+  const char *kz = std::getenv("HMY_K_ZERO_COPY");
+  if (kz) h->k_zero_copy = std::atoi(kz) != 0;
   return HMY_OK;
 }
 
