@@ -92,13 +92,15 @@ def forward_layers_given_backward(P_B):
 # The paper's Profiler measures per-layer time, memory and activation size
 # (Section 4.2).  Here they are computed: "time" is the flop count of one
 # microbatch; memory follows the runtime's arena, written out below from its
-# description (two weight slots, one activation workspace, a pack-independent
-# reserve), every buffer rounded up to 256 bytes.
+# description (N_SLOTS weight slots -- the pack in use, the next one arriving, the
+# previous one draining through its update --, one activation workspace, a
+# pack-independent reserve), every buffer rounded up to 256 bytes.
 
 def _a256(x: int) -> int:
     return (x + 255) // 256 * 256
 
 
+N_SLOTS = 3
 OUT_RING, IN_RING, K_RING = 4, 2, 3
 K_CHUNK_MAX = 4 * 2 ** 20
 LOGIT_ROWS = 512
@@ -146,8 +148,8 @@ def layer_profile(spec, M: int, b: int, precision: str):
             act = block_act_bytes(spec, b, precision)
         else:
             t_f, act = 2 * T * d * V, head_act_bytes(spec, b, precision)
-        out.append(dict(t_fwd=t_f, t_bwd=3 * t_f, params=p, mem_fwd=2 * E * p,
-                        mem_bwd=2 * (E + 4) * p + act, act_bwd=act))
+        out.append(dict(t_fwd=t_f, t_bwd=3 * t_f, params=p, mem_fwd=N_SLOTS * E * p,
+                        mem_bwd=N_SLOTS * (E + 4) * p + act, act_bwd=act))
     return out
 
 
@@ -169,7 +171,7 @@ def reserved_bytes(spec, M: int, b: int, precision: str) -> int:
 
 
 def arena_bytes(spec, P_F, P_B, M: int, b: int, precision: str):
-    """(total, slot_bytes, act_bytes): reserve + two weight slots + the largest
+    """(total, slot_bytes, act_bytes): reserve + N_SLOTS weight slots + the largest
     backward pack's activation workspace."""
     from . import model as om
     E = elem_bytes(precision)
@@ -184,7 +186,7 @@ def arena_bytes(spec, P_F, P_B, M: int, b: int, precision: str):
     for (a, e) in P_B:
         slot = max(slot, _a256(E * npar(a, e)) + _a256(4 * npar(a, e)))
         act = max(act, sum(prof[l]["act_bwd"] for l in range(a, e)))
-    return reserved_bytes(spec, M, b, precision) + 2 * slot + act, slot, act
+    return reserved_bytes(spec, M, b, precision) + N_SLOTS * slot + act, slot, act
 
 
 def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_MBps: int, compute_GFLOPs: int) -> int:
@@ -217,26 +219,26 @@ def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_M
         visits.append((True, t_flops(M * sum(prof[l]["t_bwd"] for l in range(a, e))), t_bytes(E * P),
                        t_bytes(kB * P), t_bytes((kB + E + 4) * P)))
     h2d_free = d2h_free = comp_free = 0
-    slot_free = [0, 0]
+    slot_free = [0] * N_SLOTS
     w_ready = [0] * (len(visits) + 1)
     w_ready[0] = visits[0][2]
     h2d_free = w_ready[0]
     for v, (bwd, comp, w, kin, out) in enumerate(visits):
         comp_start = max(comp_free, w_ready[v])
         if v + 1 < len(visits):
-            s = max(comp_start, slot_free[(v + 1) % 2], h2d_free)
+            s = max(comp_start, slot_free[(v + 1) % N_SLOTS], h2d_free)
             w_ready[v + 1] = s + visits[v + 1][2]
             h2d_free = w_ready[v + 1]
         comp_end = comp_start + comp
         comp_free = comp_end
         if not bwd:
-            slot_free[v % 2] = comp_end
+            slot_free[v % N_SLOTS] = comp_end
         else:
             kin_end = max(comp_end, h2d_free) + kin
             h2d_free = kin_end
             out_end = max(max(comp_end, d2h_free) + out, kin_end)
             d2h_free = out_end
-            slot_free[v % 2] = out_end
+            slot_free[v % N_SLOTS] = out_end
     return max(comp_free, d2h_free)
 
 
@@ -244,7 +246,7 @@ def plan(spec, budget: int, M: int, b: int, precision: str, search: int = 0, lin
          compute_GFLOPs: int = 250000):
     """Backward packs by Algorithm 2 on (t_bwd, mem_bwd) with capacity budget -
     reserve and the whole-arena test; then forward packs on (t_fwd, mem_fwd)
-    over the layers before the last backward pack with capacity 2 * slot.
+    over the layers before the last backward pack with capacity N_SLOTS * slot.
     search = 0 keeps the first feasible pack count (Algorithm 2 alone); search = n
     also tries the next n feasible pack counts and, as Algorithm 1 does over its
     configurations, keeps the one with the smallest estimated iteration time
@@ -263,7 +265,7 @@ def plan(spec, budget: int, M: int, b: int, precision: str, search: int = 0, lin
             break
         slot = arena_bytes(spec, [], P_B, M, b, precision)[1]
         RF = forward_layers_given_backward(P_B)
-        P_F = balanced_time_packing([p["t_fwd"] for p in prof[:RF]], [p["mem_fwd"] for p in prof[:RF]], 2 * slot)
+        P_F = balanced_time_packing([p["t_fwd"] for p in prof[:RF]], [p["mem_fwd"] for p in prof[:RF]], N_SLOTS * slot)
         if P_F is None:
             return None
         ns = estimate_iteration_ns(spec, P_F, P_B, M, b, precision, link_MBps, compute_GFLOPs)

@@ -44,6 +44,18 @@ __global__ void k_copy(uint32_t *dst, const uint32_t *src, uint64_t n_words) {
   for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n4; i += stride) d4[i] = s4[i];
   for (uint64_t i = n4 * 4 + uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n_words; i += stride) dst[i] = src[i];
 }
+// HBM -> pinned host memory.  Stores to the host drain at link speed; more of them
+// outstanding than the link needs back up into the memory fabric and slow every other
+// kernel on the device (measured: a streaming kernel runs 7x slower beside an
+// unthrottled 32x256-thread copy, 1.1x beside this one).  So: few, narrow workgroups,
+// each waiting for its store before the next.
+__global__ void k_copy_out(uint4 *dst, const uint4 *src, uint64_t n4) {
+  const uint64_t stride = uint64_t(gridDim.x) * blockDim.x;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    dst[i] = src[i];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+}
 
 // dst[i] = E(src[i])
 template <typename E>
@@ -383,6 +395,8 @@ __global__ void k_adam_out(const float *grad, const float *in_master, const floa
         }
       }
     }
+    // bound the stores to the host that are outstanding (see k_copy_out)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 }
 
@@ -403,14 +417,22 @@ int launch_fill_zero(void *p, uint64_t bytes, stream_t st) {
                      (uint32_t *)p, words);
   return check_launch("fill_zero");
 }
-int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st) {
+int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st, int grid_cap) {
   if (!bytes) return HMY_OK;
   if (bytes % 4 || (reinterpret_cast<uintptr_t>(dst) & 15) || (reinterpret_cast<uintptr_t>(src) & 15))
     return fail(HMY_E_INVALID, "copy: unaligned");
   const uint64_t words = bytes / 4;
-  hipLaunchKernelGGL(k_copy, dim3(grid_for(words / 4 + 1, kBlock, 2048)), dim3(kBlock), 0, (hipStream_t)st,
+  hipLaunchKernelGGL(k_copy, dim3(grid_for(words / 4 + 1, kBlock, grid_cap)), dim3(kBlock), 0, (hipStream_t)st,
                      (uint32_t *)dst, (const uint32_t *)src, words);
   return check_launch("copy");
+}
+
+int launch_copy_out(void *dst_host, const void *src, uint64_t bytes, stream_t st) {
+  if (!bytes) return HMY_OK;
+  if (bytes % 16 || (reinterpret_cast<uintptr_t>(dst_host) & 15) || (reinterpret_cast<uintptr_t>(src) & 15))
+    return fail(HMY_E_INVALID, "copy_out: unaligned");
+  hipLaunchKernelGGL(k_copy_out, dim3(32), dim3(64), 0, (hipStream_t)st, (uint4 *)dst_host, (const uint4 *)src, bytes / 16);
+  return check_launch("copy_out");
 }
 
 int launch_convert_f32(int prec, const float *src, void *dst, uint64_t n, stream_t st) {
@@ -535,19 +557,22 @@ int launch_adam(int prec, const float *grad, float *master, float *m, float *v, 
 
 int launch_adam_out(int prec, const float *grad, const float *in_master, const float *in_m, const float *in_v,
                     float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
-                    const hmy_adam &hp, stream_t st) {
+                    const hmy_adam &hp, bool alone, stream_t st) {
   if (!n) return HMY_OK;
   if (hp.step < 1) return fail(HMY_E_INVALID, "adam: step is 1-based");
   const float inv_bc1 = float(1.0 / (1.0 - std::pow(double(hp.beta1), double(hp.step))));
   const float inv_bc2 = float(1.0 / (1.0 - std::pow(double(hp.beta2), double(hp.step))));
-  // a modest grid: the kernel runs at host-link speed, not HBM speed, beside the compute stream
-  static const int cap = std::getenv("HMY_ADAM_GRID") ? std::max(1, std::atoi(std::getenv("HMY_ADAM_GRID"))) : 32;
-  const int grid = grid_for(n / 8 + 1, kBlock, cap);
+  // beside the compute stream: narrow workgroups, few of them -- what keeps the link busy
+  // without flooding the fabric (see k_copy_out); with the device to itself: enough to
+  // run the link at full speed
+  static const int cap_env = std::getenv("HMY_ADAM_GRID") ? std::max(1, std::atoi(std::getenv("HMY_ADAM_GRID"))) : 12;
+  const int blk = alone ? 256 : 64;
+  const int grid = grid_for(n / 8 + 1, blk, alone ? 32 : cap_env);
   if (prec == HMY_PREC_BF16)
-    hipLaunchKernelGGL(k_adam_out<true>, dim3(grid), dim3(kBlock), 0, (hipStream_t)st, grad, in_master, in_m, in_v,
+    hipLaunchKernelGGL(k_adam_out<true>, dim3(grid), dim3(blk), 0, (hipStream_t)st, grad, in_master, in_m, in_v,
                        out_master, out_m, out_v, out_w, out_g, n, hp.lr, hp.beta1, hp.beta2, hp.eps, inv_bc1, inv_bc2);
   else if (prec == HMY_PREC_FP32)
-    hipLaunchKernelGGL(k_adam_out<false>, dim3(grid), dim3(kBlock), 0, (hipStream_t)st, grad, in_master, in_m, in_v,
+    hipLaunchKernelGGL(k_adam_out<false>, dim3(grid), dim3(blk), 0, (hipStream_t)st, grad, in_master, in_m, in_v,
                        out_master, out_m, out_v, out_w, out_g, n, hp.lr, hp.beta1, hp.beta2, hp.eps, inv_bc1, inv_bc2);
   else
     return fail(HMY_E_INVALID, "unknown precision %d", prec);

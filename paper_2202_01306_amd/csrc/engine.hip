@@ -13,7 +13,7 @@
 // A "visit" is one task of the ordered list: forward packs in order, then
 // backward packs in reverse, each followed by its update (jit-update).  The
 // first backward visit is the last pack, run forward+backward per microbatch
-// (jit-compute).  Visit v uses weight slot v % 2.
+// (jit-compute).  Visit v uses weight slot v % kSlots.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -70,7 +70,7 @@ struct hmy_handle {
   // true: the Adam kernel writes its results directly into the pinned host arrays;
   // false: results go to the ring / slot and leave by hipMemcpyAsync on s_out
   bool fused_swap_out = true;
-  bool k_zero_copy = true;   // the update kernel reads optimizer state straight from pinned host memory
+  bool k_zero_copy = false;   // the update kernel reads optimizer state straight from pinned host memory
 };
 
 #define HIPCHK(h, call)                                                                      \
@@ -141,6 +141,20 @@ void d2h(hmy_handle *h, int kind, void *dst, const void *src, uint64_t bytes, hi
   if (h->dry || h->err) return;
   size_t a = trec(h, s);
   HIPCHK(h, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, s));
+  size_t b = trec(h, s);
+  span(h, a, b, 1);
+}
+
+// device -> pinned host through a throttled copy kernel on stream s (the library's blit
+// for hipMemcpyAsync floods the fabric with stores to the link and stalls the kernels
+// running beside it)
+void d2h_kernel(hmy_handle *h, int kind, void *dst, const void *src, uint64_t bytes, hipStream_t s) {
+  if (!bytes) return;
+  h->st.d2h[kind] += bytes;
+  if (h->dry || h->err) return;
+  size_t a = trec(h, s);
+  int rc = launch_copy_out(dst, src, bytes, s);
+  if (rc) h->err = rc;
   size_t b = trec(h, s);
   span(h, a, b, 1);
 }
@@ -352,8 +366,16 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
   KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, g_lnf_g, g_lnf_b, T, d, h->s_comp));
 }
 
+struct PendingUpdate {
+  const Visit *v = nullptr;
+  hipEvent_t bwd_done = nullptr;
+  int next = 0, n_chunks = 0;
+};
+
 struct IterState {
-  hipEvent_t slot_free[2] = {nullptr, nullptr};
+  PendingUpdate upd;
+  bool compute_done = false;   // nothing is left to enqueue on the compute stream
+  hipEvent_t slot_free[kSlots] = {};
   hipEvent_t in_free[kInRing] = {};
   hipEvent_t in_ready[kInRing] = {};
   hipEvent_t out_free[kOutRing] = {};
@@ -389,7 +411,8 @@ void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int 
       KCHK(h, launch_copy(outring(h, q), X, xb, h->s_comp));
       hipEvent_t e = rec(h, h->s_comp);
       wait(h, h->s_out, e);
-      d2h(h, HMY_KIND_SX, stash_slot(h, ck, mb), outring(h, q), xb, h->s_out);
+      if (h->fused_swap_out) d2h_kernel(h, HMY_KIND_SX, stash_slot(h, ck, mb), outring(h, q), xb, h->s_out);
+      else d2h(h, HMY_KIND_SX, stash_slot(h, ck, mb), outring(h, q), xb, h->s_out);
       it.out_free[q] = rec(h, h->s_out);
     }
     if (layer == 0) {
@@ -464,56 +487,61 @@ void backward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int
   it.in_free[r] = rec(h, h->s_comp);
 }
 
-// jit-update of the visit's pack: optimizer state streams through the ring
-// (in on s_upd, Adam on s_upd, out on s_out) while the next pack computes.
-void update_visit(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_done, const hmy_adam &hp) {
+// jit-update of a visit's pack: optimizer state streams through the ring in chunks
+// (in on s_upd, Adam on s_upd, results out by the same kernel or on s_out) while the
+// next pack computes.  Chunks are enqueued a few at a time from the next visit's
+// microbatch loop: a host->device copy that has to wait for its ring slot holds up every
+// copy queued behind it on the copy engine, checkpoint reads of the running visit
+// included, so no more of them are queued ahead than one microbatch's worth.
+void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
+  PendingUpdate &u = it.upd;
+  const Visit &v = *u.v;
   const Reserved &R = h->arena.res;
   const int E = h->model.elem_bytes();
   const bool mixed = h->model.spec.precision == HMY_PREC_BF16;
   const PackPtrs pp = pack_ptrs(h, v);
-  for (uint64_t lo = 0, c = 0; lo < v.nparams; lo += R.k_chunk_params, ++c) {
-    const uint64_t n = std::min<uint64_t>(R.k_chunk_params, v.nparams - lo);
-    const int r = it.k_count++ % kKRing;
-    char *ring = h->base + R.kring + uint64_t(r) * h->model.k_arrays() * R.karr_bytes;
-    float *r_master = mixed ? (float *)ring : nullptr;
-    float *r_m = (float *)(ring + (mixed ? 1 : 0) * R.karr_bytes);
-    float *r_v = (float *)(ring + (mixed ? 2 : 1) * R.karr_bytes);
-    const uint64_t g0 = v.poff + lo;  // element offset in the host arrays
-    const bool zc = h->fused_swap_out && h->k_zero_copy;
-    if (zc) {
-      // no staging copy: the state crosses the link inside the update kernel's own loads
-      h->st.h2d[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
-      if (!h->dry) {
-        r_master = mixed ? h->host.master + g0 : nullptr;
-        r_m = h->host.adam_m + g0;
-        r_v = h->host.adam_v + g0;
-      }
-    } else {
-      wait(h, h->s_upd, it.k_free[r]);
-      if (mixed) h2d(h, HMY_KIND_K, r_master, h->dry ? nullptr : h->host.master + g0, n * 4, h->s_upd);
-      h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_upd);
-      h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_upd);
+  const uint64_t lo = uint64_t(u.next) * R.k_chunk_params;
+  const uint64_t n = std::min<uint64_t>(R.k_chunk_params, v.nparams - lo);
+  const int r = it.k_count++ % kKRing;
+  char *ring = h->base + R.kring + uint64_t(r) * h->model.k_arrays() * R.karr_bytes;
+  float *r_master = mixed ? (float *)ring : nullptr;
+  float *r_m = (float *)(ring + (mixed ? 1 : 0) * R.karr_bytes);
+  float *r_v = (float *)(ring + (mixed ? 2 : 1) * R.karr_bytes);
+  const uint64_t g0 = v.poff + lo;  // element offset in the host arrays
+  const bool zc = h->fused_swap_out && h->k_zero_copy;
+  if (zc) {
+    // no staging copy: the state crosses the link inside the update kernel's own loads
+    h->st.h2d[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
+    if (!h->dry) {
+      r_master = mixed ? h->host.master + g0 : nullptr;
+      r_m = h->host.adam_m + g0;
+      r_v = h->host.adam_v + g0;
     }
-    if (c == 0) wait(h, h->s_upd, bwd_done);
-    if (h->fused_swap_out) {
-      // the update kernel itself writes state, weights and gradients to the host arrays
-      // (device->host over the link at vector width); bytes are counted as for copies
-      h->st.d2h[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
-      h->st.d2h[HMY_KIND_W] += n * E;
-      h->st.d2h[HMY_KIND_DW] += n * 4;
-      if (!h->dry && !h->err) {
-        const size_t a = trec(h, h->s_upd);
-        KCHK(h, launch_adam_out(h->model.spec.precision, pp.dW + lo, mixed ? r_master : (const float *)(pp.W + lo * E),
-                                r_m, r_v, mixed ? h->host.master + g0 : nullptr, h->host.adam_m + g0,
-                                h->host.adam_v + g0, (char *)h->host.weights + g0 * E, h->host.grads + g0, n, hp,
-                                h->s_upd));
-        const size_t b2 = trec(h, h->s_upd);
-        span(h, a, b2, 1);
-        if (zc) span(h, a, b2, 0);   // the same kernel carries the host->device half
-      }
-      it.k_free[r] = rec(h, h->s_upd);
-      continue;
+  } else {
+    wait(h, h->s_upd, it.k_free[r]);
+    if (mixed) h2d(h, HMY_KIND_K, r_master, h->dry ? nullptr : h->host.master + g0, n * 4, h->s_upd);
+    h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_upd);
+    h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_upd);
+  }
+  if (u.next == 0) wait(h, h->s_upd, u.bwd_done);
+  if (h->fused_swap_out) {
+    // the update kernel itself writes state, weights and gradients to the host arrays
+    // (device->host over the link at vector width); bytes are counted as for copies
+    h->st.d2h[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
+    h->st.d2h[HMY_KIND_W] += n * E;
+    h->st.d2h[HMY_KIND_DW] += n * 4;
+    if (!h->dry && !h->err) {
+      const size_t a = trec(h, h->s_upd);
+      KCHK(h, launch_adam_out(h->model.spec.precision, pp.dW + lo, mixed ? r_master : (const float *)(pp.W + lo * E),
+                              r_m, r_v, mixed ? h->host.master + g0 : nullptr, h->host.adam_m + g0,
+                              h->host.adam_v + g0, (char *)h->host.weights + g0 * E, h->host.grads + g0, n, hp,
+                              it.compute_done, h->s_upd));
+      const size_t b2 = trec(h, h->s_upd);
+      span(h, a, b2, 1);
+      if (zc) span(h, a, b2, 0);   // the same kernel carries the host->device half
     }
+    it.k_free[r] = rec(h, h->s_upd);
+  } else {
     KCHK(h, launch_adam(h->model.spec.precision, pp.dW + lo, r_master, r_m, r_v, pp.W + lo * E, n, hp, h->s_upd));
     hipEvent_t e = rec(h, h->s_upd);
     wait(h, h->s_out, e);
@@ -524,6 +552,22 @@ void update_visit(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_d
     d2h(h, HMY_KIND_DW, h->dry ? nullptr : h->host.grads + g0, pp.dW + lo, n * 4, h->s_out);
     it.k_free[r] = rec(h, h->s_out);
   }
+  if (++u.next == u.n_chunks) {   // the pack has left: its slot may be refilled
+    it.slot_free[v.slot] = rec(h, h->fused_swap_out ? h->s_upd : h->s_out);
+    u.v = nullptr;
+  }
+}
+// enqueue chunks of the pending update until `upto` of them have been (all if negative)
+void update_progress(hmy_handle *h, IterState &it, const hmy_adam &hp, int upto) {
+  while (it.upd.v && (upto < 0 || it.upd.next < upto)) update_chunk(h, it, hp);
+}
+void update_begin(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_done, const hmy_adam &hp) {
+  update_progress(h, it, hp, -1);   // nothing of an older update may be left behind
+  const uint64_t c = h->arena.res.k_chunk_params;
+  it.upd.v = &v;
+  it.upd.bwd_done = bwd_done;
+  it.upd.next = 0;
+  it.upd.n_chunks = int((v.nparams + c - 1) / c);
 }
 
 void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
@@ -579,6 +623,8 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
         if (m + 1 < M && !v.last && v.pack.a != 0) issue_pack_input(h, it, v, m + 1);
       }
       if (next) w_piece(*next, m);
+      // this microbatch's share of the previous visit's update
+      if (it.upd.v) update_progress(h, it, hp, (it.upd.n_chunks * (m + 1) + M - 1) / M);
       if (v.bwd) {
         if (m > 0 && (v.last || v.pack.a == 0)) issue_pack_input(h, it, v, m);
         backward_visit_microbatch(h, it, v, m);
@@ -590,11 +636,11 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
     if (!v.bwd) {
       it.slot_free[v.slot] = rec(h, h->s_comp);
     } else {
-      hipEvent_t bwd_done = rec(h, h->s_comp);
-      update_visit(h, it, v, bwd_done, hp);
-      it.slot_free[v.slot] = rec(h, h->fused_swap_out ? h->s_upd : h->s_out);
+      update_begin(h, it, v, rec(h, h->s_comp), hp);
     }
   }
+  it.compute_done = true;
+  update_progress(h, it, hp, -1);   // the first pack's update has no visit to hide behind
   const size_t t_last = trec(h, h->s_comp);
   span(h, t_first, t_last, 3);
 }
@@ -633,7 +679,7 @@ static int init_handle(hmy_handle *h, const hmy_model_spec *spec, const hmy_sche
     v.bwd = bwd;
     v.last = last;
     v.pack = p;
-    v.slot = int(h->visits.size() % 2);
+    v.slot = int(h->visits.size() % kSlots);
     v.poff = h->model.layer_off[p.a];
     v.nparams = h->model.params_in(p.a, p.e);
     h->visits.push_back(v);

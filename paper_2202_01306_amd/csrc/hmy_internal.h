@@ -41,6 +41,7 @@ int build_model(const hmy_model_spec *spec, Model *out);
 // ---- analytic profile and arena ---------------------------------------------
 inline uint64_t a256(uint64_t x) { return (x + 255) & ~uint64_t(255); }
 
+constexpr int kSlots = 3;              // weight slots: in use, being prefetched, being updated and written back
 constexpr int kOutRing = 4;            // staging buffers for checkpoints going out
 constexpr int kInRing = 2;             // pack-input buffers (checkpoint coming in)
 constexpr int kKRing = 3;              // optimizer-state ring slots
@@ -86,7 +87,7 @@ void packs_to_schedule(const Packs &p, hmy_schedule *out);
 struct Arena {
   Reserved res;
   uint64_t slot_bytes;
-  uint64_t slot_off[2];
+  uint64_t slot_off[kSlots];
   uint64_t act_off, act_bytes;
   uint64_t total;
 };
@@ -132,9 +133,12 @@ int launch_adam(int prec, const float *grad, float *master, float *m, float *v, 
                 uint64_t n, const hmy_adam &hp, stream_t st);
 int launch_adam_out(int prec, const float *grad, const float *in_master, const float *in_m, const float *in_v,
                     float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
-                    const hmy_adam &hp, stream_t st);
+                    const hmy_adam &hp, bool alone, stream_t st);
 int launch_fill_zero(void *p, uint64_t bytes, stream_t st);
-int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st);
+// grid_cap bounds the workgroups: a copy to pinned host memory needs few of them to fill
+// the link and must not crowd the compute units
+int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st, int grid_cap = 2048);
+int launch_copy_out(void *dst_host, const void *src, uint64_t bytes, stream_t st);
 int launch_convert_f32(int prec, const float *src, void *dst, uint64_t n, stream_t st);
 
 extern int g_use_mfma;

@@ -1,13 +1,14 @@
 // Pack planner: analytic layer profile, HBM arena layout and balanced-time
 // packing (the paper's Algorithm 2, Section 4.3.1) under the HBM budget.
 //
-// Memory model.  The runtime keeps two weight slots (prefetch distance 1:
-// "prefetching ... double buffering", Section 4.4), one activation workspace
+// Memory model.  The runtime keeps kSlots = 3 weight slots (prefetch distance 1,
+// Section 4.4: the pack being computed, the next one arriving, and the previous
+// one still draining through its update and write-back), one activation workspace
 // for the backward pack in flight, and a pack-independent reserve (resident
 // boundary activations, checkpoint rings, gradient scratch, the optimizer ring).
 // A layer's footprint for the packing is therefore
-//   forward : 2 * E * p                        (E bytes per weight, p parameters)
-//   backward: 2 * (E + 4) * p + act            (weights + fp32 gradients, twice; activations once)
+//   forward : kSlots * E * p                   (E bytes per weight, p parameters)
+//   backward: kSlots * (E + 4) * p + act       (weights + fp32 gradients per slot; activations once)
 // and the capacity is the budget minus the reserve.  Times are flop counts of
 // one microbatch (integers, so the balanced split has exact ties).
 #include <algorithm>
@@ -107,8 +108,8 @@ void layer_profile(const Model &m, int n_micro, int micro_batch, std::vector<hmy
       p.act_bwd = act_head;
     }
     p.t_bwd = 3 * p.t_fwd;
-    p.mem_fwd = 2 * E * p.params;
-    p.mem_bwd = 2 * (E + 4) * p.params + p.act_bwd;
+    p.mem_fwd = kSlots * E * p.params;
+    p.mem_bwd = kSlots * (E + 4) * p.params + p.act_bwd;
   }
 }
 
@@ -131,9 +132,8 @@ Arena arena_layout(const Model &m, const Packs &p, int n_micro, int micro_batch)
     for (int l = q.a; l < q.e; ++l) act += prof[l].act_bwd;
     a.act_bytes = std::max(a.act_bytes, act);
   }
-  a.slot_off[0] = a.res.size;
-  a.slot_off[1] = a.slot_off[0] + a.slot_bytes;
-  a.act_off = a.slot_off[1] + a.slot_bytes;
+  for (int i = 0; i < kSlots; ++i) a.slot_off[i] = a.res.size + uint64_t(i) * a.slot_bytes;
+  a.act_off = a.res.size + uint64_t(kSlots) * a.slot_bytes;
   a.total = a.act_off + a.act_bytes;
   return a;
 }
@@ -266,27 +266,27 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
     const uint64_t P = m.params_in(q.a, q.e);
     vs.push_back({true, t_flops(fl * n_micro), t_bytes(E * P), t_bytes(kB * P), t_bytes((kB + E + 4) * P)});
   }
-  uint64_t h2d_free = 0, d2h_free = 0, comp_free = 0, slot_free[2] = {0, 0};
+  uint64_t h2d_free = 0, d2h_free = 0, comp_free = 0, slot_free[kSlots] = {};
   std::vector<uint64_t> w_ready(vs.size() + 1, 0);
   w_ready[0] = vs[0].w;
   h2d_free = w_ready[0];
   for (size_t v = 0; v < vs.size(); ++v) {
     const uint64_t comp_start = std::max(comp_free, w_ready[v]);
     if (v + 1 < vs.size()) {
-      const uint64_t s = std::max(std::max(comp_start, slot_free[(v + 1) % 2]), h2d_free);
+      const uint64_t s = std::max(std::max(comp_start, slot_free[(v + 1) % kSlots]), h2d_free);
       w_ready[v + 1] = s + vs[v + 1].w;
       h2d_free = w_ready[v + 1];
     }
     const uint64_t comp_end = comp_start + vs[v].comp;
     comp_free = comp_end;
     if (!vs[v].bwd) {
-      slot_free[v % 2] = comp_end;
+      slot_free[v % kSlots] = comp_end;
     } else {
       const uint64_t kin_end = std::max(comp_end, h2d_free) + vs[v].kin;
       h2d_free = kin_end;
       const uint64_t out_end = std::max(std::max(comp_end, d2h_free) + vs[v].out, kin_end);
       d2h_free = out_end;
-      slot_free[v % 2] = out_end;
+      slot_free[v % kSlots] = out_end;
     }
   }
   return std::max(comp_free, d2h_free);
@@ -337,7 +337,7 @@ int plan_packs(const Model &m, const hmy_budget &b, int n_micro, int micro_batch
       tf[l] = prof[l].t_fwd;
       mf[l] = prof[l].mem_fwd;
     }
-    if (!balanced_time_packing(tf, mf, 2 * slot, 0, always, &p.fwd))
+    if (!balanced_time_packing(tf, mf, uint64_t(kSlots) * slot, 0, always, &p.fwd))
       return fail(HMY_E_BUDGET_TOO_SMALL, "forward packing failed (internal)");
     const uint64_t ns = estimate_iteration_ns(m, prof, p, n_micro, link, rate);
     if (!have || ns < best_ns) {
