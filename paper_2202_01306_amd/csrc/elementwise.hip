@@ -244,24 +244,142 @@ __global__ void k_gelu_bwd(const E *dg, const E *u, E *du, uint64_t nvec) {
   }
 }
 
+// LayerNorm backward for rows of at most 64 * VEC * NJ elements: lane l owns columns
+// VEC * (l + 64 j) .. + VEC - 1, j < NJ, and keeps their dgamma / dbeta partial sums in
+// registers over all the rows its wave visits; one pass over x and dy (kept in
+// registers between the two phases), waves combine through LDS and each workgroup adds
+// its sums to global memory once.
+template <typename E, int NJ>
+__global__ __launch_bounds__(512) void k_layernorm_bwd_reg(const E *dy, const E *x, const float *mean, const float *rstd,
+                                                          const E *gamma, const E *res, E *dx, float *dgamma, float *dbeta,
+                                                          int T, int d) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  extern __shared__ float lds[];   // dgamma[d], dbeta[d]
+  for (int c = threadIdx.x; c < 2 * d; c += blockDim.x) lds[c] = 0.f;
+  __syncthreads();
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
+  float dg[NJ][VEC], db[NJ][VEC];
+  Vec16<E> gm[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = VEC * (lane + kWave * j);
+    if (c < d) gm[j] = load16(gamma + c);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) dg[j][k] = db[j][k] = 0.f;
+  }
+  for (int row = blockIdx.x * waves + wave; row < T; row += gridDim.x * waves) {
+    const E *xr = x + uint64_t(row) * d, *dyr = dy + uint64_t(row) * d;
+    const float mu = mean[row], rs = rstd[row];
+    Vec16<E> xv[NJ], gv[NJ];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c = VEC * (lane + kWave * j);
+      if (c < d) {
+        xv[j] = load16(xr + c);
+        gv[j] = load16(dyr + c);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c = VEC * (lane + kWave * j);
+      if (c < d) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+          const float xh = (to_f32(xv[j].v[k]) - mu) * rs;
+          const float g = to_f32(gv[j].v[k]);
+          const float dxh = g * to_f32(gm[j].v[k]);
+          s1 += dxh;
+          s2 += dxh * xh;
+          dg[j][k] += g * xh;
+          db[j][k] += g;
+        }
+      }
+    }
+    s1 = wave_sum(s1) / float(d);
+    s2 = wave_sum(s2) / float(d);
+    E *dxr = dx + uint64_t(row) * d;
+    const E *rr = res ? res + uint64_t(row) * d : nullptr;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c = VEC * (lane + kWave * j);
+      if (c < d) {
+        Vec16<E> rv;
+        if (rr) rv = load16(rr + c);
+        Vec16<E> o;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+          const float xh = (to_f32(xv[j].v[k]) - mu) * rs;
+          const float dxh = to_f32(gv[j].v[k]) * to_f32(gm[j].v[k]);
+          float v = (dxh - s1 - xh * s2) * rs;
+          if (rr) v += to_f32(rv.v[k]);
+          o.v[k] = from_f32<E>(v);
+        }
+        store16(dxr + c, o);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = VEC * (lane + kWave * j);
+    if (c < d) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        atomicAdd(&lds[c + k], dg[j][k]);
+        atomicAdd(&lds[d + c + k], db[j][k]);
+      }
+    }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    atomicAdd(&dgamma[c], lds[c]);
+    atomicAdd(&dbeta[c], lds[d + c]);
+  }
+}
+
 // ---- column sums (bias gradients) ---------------------------------------------
-// grid = (column tiles of kBlock*VEC, row splits); each thread owns VEC columns.
+// grid = (column groups of 64*VEC, row splits).  A wave reads whole 64*VEC-column row
+// segments (16 bytes per lane), four rows in flight; the workgroup's waves take
+// interleaved rows, combine through LDS, and one atomic per column leaves the workgroup.
 template <typename E>
 __global__ void k_colsum(const E *a, float *out, int T, int N, int rows_per_split) {
   constexpr int VEC = ElemTraits<E>::VEC;
-  const int c = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
-  if (c >= N) return;
+  __shared__ float part[kWavesPerBlock][kWave * VEC];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int c = (blockIdx.x * kWave + lane) * VEC;
   const int r0 = blockIdx.y * rows_per_split, r1 = min(T, r0 + rows_per_split);
   float acc[VEC];
 #pragma unroll
   for (int k = 0; k < VEC; ++k) acc[k] = 0.f;
-  for (int r = r0; r < r1; ++r) {
-    const Vec16<E> v = load16(a + uint64_t(r) * N + c);
+  if (c < N) {
+    int r = r0 + wave;
+    for (; r + 3 * kWavesPerBlock < r1; r += 4 * kWavesPerBlock) {
+      Vec16<E> v[4];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) acc[k] += to_f32(v.v[k]);
+      for (int q = 0; q < 4; ++q) v[q] = load16(a + uint64_t(r + q * kWavesPerBlock) * N + c);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k] += to_f32(v[q].v[k]);
+    }
+    for (; r < r1; r += kWavesPerBlock) {
+      const Vec16<E> v = load16(a + uint64_t(r) * N + c);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) acc[k] += to_f32(v.v[k]);
+    }
   }
 #pragma unroll
-  for (int k = 0; k < VEC; ++k) atomicAdd(out + c + k, acc[k]);
+  for (int k = 0; k < VEC; ++k) part[wave][lane * VEC + k] = acc[k];
+  __syncthreads();
+  for (int i = threadIdx.x; i < kWave * VEC; i += blockDim.x) {
+    const int col = blockIdx.x * kWave * VEC + i;
+    if (col < N) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) t += part[w][i];
+      atomicAdd(out + col, t);
+    }
+  }
 }
 
 // ---- softmax cross-entropy ---------------------------------------------------
@@ -276,6 +394,9 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float *scrat
   return r;
 }
 
+// One workgroup per row.  Pass 1 keeps a running (max, sum of exponentials) pair per
+// thread over 16-byte loads and merges the pairs across the workgroup; pass 2 re-reads
+// the row (it is still in L2) and writes the gradient, 8 columns per thread per step.
 template <typename E>
 __global__ void k_xent(const float *logits, const int32_t *targets, double *loss_acc, E *dlogits, int V, int64_t ldl,
                        float inv_ntgt) {
@@ -284,21 +405,56 @@ __global__ void k_xent(const float *logits, const int32_t *targets, double *loss
   const float *lr = logits + uint64_t(row) * ldl;
   E *dr = dlogits + uint64_t(row) * ldl;
   const int tgt = targets[row];
+  const bool vec = (ldl % 8 == 0) && ((reinterpret_cast<uintptr_t>(logits) & 15) == 0) &&
+                   ((reinterpret_cast<uintptr_t>(dlogits) & 15) == 0) && sizeof(E) == 2;
+  const int nv = vec ? int(ldl / 8) : 0;   // 8-column groups handled with vector accesses
   if (tgt < 0) {
-    for (int j = threadIdx.x; j < ldl; j += blockDim.x) dr[j] = from_f32<E>(0.f);
+    Vec16<E> z;
+#pragma unroll
+    for (int k = 0; k < ElemTraits<E>::VEC; ++k) z.v[k] = from_f32<E>(0.f);
+    for (int j = threadIdx.x; j < nv; j += blockDim.x) store16(dr + 8 * j, z);
+    for (int j = nv * 8 + threadIdx.x; j < ldl; j += blockDim.x) dr[j] = from_f32<E>(0.f);
     return;
   }
-  float mx = -INFINITY;
-  for (int j = threadIdx.x; j < V; j += blockDim.x) mx = fmaxf(mx, lr[j]);
-  mx = block_reduce(mx, true, scratch);
-  float se = 0.f;
-  for (int j = threadIdx.x; j < V; j += blockDim.x) se += expf(lr[j] - mx);
+  float mx = -INFINITY, se = 0.f;
+  auto take = [&](float v) {
+    if (v > mx) {
+      se = se * __expf(mx - v) + 1.f;
+      mx = v;
+    } else {
+      se += __expf(v - mx);
+    }
+  };
+  for (int j = threadIdx.x; j < nv; j += blockDim.x) {
+    float v[8];
+    *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(lr + 8 * j);
+    *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(lr + 8 * j + 4);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (8 * j + k < V) take(v[k]);
+  }
+  for (int j = nv * 8 + threadIdx.x; j < V; j += blockDim.x) take(lr[j]);
+  const float gmx = block_reduce(mx, true, scratch);
+  se = mx == -INFINITY ? 0.f : se * __expf(mx - gmx);
   se = block_reduce(se, false, scratch);
-  const float lse = mx + logf(se);
+  const float lse = gmx + logf(se);
   if (threadIdx.x == 0) atomicAdd(loss_acc, double(lse - lr[tgt]) * double(inv_ntgt));
-  for (int j = threadIdx.x; j < ldl; j += blockDim.x) {
+  for (int j = threadIdx.x; j < nv; j += blockDim.x) {
+    float v[8];
+    *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(lr + 8 * j);
+    *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(lr + 8 * j + 4);
+    Vec16<E> o;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int col = 8 * j + k;
+      const float g = col < V ? (__expf(v[k] - lse) - (col == tgt ? 1.f : 0.f)) * inv_ntgt : 0.f;
+      if (k < ElemTraits<E>::VEC) o.v[k] = from_f32<E>(g);
+    }
+    store16(dr + 8 * j, o);
+  }
+  for (int j = nv * 8 + threadIdx.x; j < ldl; j += blockDim.x) {
     float g = 0.f;
-    if (j < V) g = (expf(lr[j] - lse) - (j == tgt ? 1.f : 0.f)) * inv_ntgt;
+    if (j < V) g = (__expf(lr[j] - lse) - (j == tgt ? 1.f : 0.f)) * inv_ntgt;
     dr[j] = from_f32<E>(g);
   }
 }
@@ -480,13 +636,29 @@ int launch_layernorm_fwd(int prec, const void *x, const void *gamma, const void 
   });
   return check_launch("layernorm_fwd");
 }
+template <typename E>
+void launch_ln_bwd(const E *dy, const E *x, const float *mean, const float *rstd, const E *gamma, const E *res, E *dx,
+                   float *dgamma, float *dbeta, int T, int d, hipStream_t st) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  const int nj = (d + kWave * VEC - 1) / (kWave * VEC);
+  const int waves = 8, grid = grid_for(T, waves * 4, 256);   // at least 4 rows per wave
+  const size_t lds = size_t(2) * d * 4;
+  const dim3 g(grid), b(waves * kWave);
+  if (nj == 1) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 1>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d);
+  else if (nj == 2) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 2>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d);
+  else if (nj <= 4) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 4>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d);
+  else if (nj <= 8) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 8>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d);
+  else
+    hipLaunchKernelGGL(k_layernorm_bwd<E>, dim3(grid_for(T, kWavesPerBlock, 512)), dim3(kBlock), lds, st, dy, x, mean, rstd,
+                       gamma, res, dx, dgamma, dbeta, T, d);
+}
+
 int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
                          const void *res, void *dx, float *dgamma, float *dbeta, int T, int d, stream_t st) {
   if (T < 1 || d % 8 || d > 8192) return fail(HMY_E_INVALID, "layernorm_bwd: bad shape");
   DISPATCH_PREC(prec, {
-    hipLaunchKernelGGL(k_layernorm_bwd<E>, dim3(grid_for(T, kWavesPerBlock, 512)), dim3(kBlock), size_t(2) * d * 4,
-                       (hipStream_t)st, (const E *)dy, (const E *)x, mean, rstd, (const E *)gamma, (const E *)res,
-                       (E *)dx, dgamma, dbeta, T, d);
+    launch_ln_bwd<E>((const E *)dy, (const E *)x, mean, rstd, (const E *)gamma, (const E *)res, (E *)dx, dgamma, dbeta, T,
+                     d, (hipStream_t)st);
   });
   return check_launch("layernorm_bwd");
 }
@@ -513,9 +685,9 @@ int launch_gelu_bwd(int prec, const void *dg, const void *u, void *du, uint64_t 
 int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st) {
   if (T < 1 || N % 8) return fail(HMY_E_INVALID, "colsum: bad shape");
   DISPATCH_PREC(prec, {
-    const int cols_per_block = kBlock * ElemTraits<E>::VEC;
+    const int cols_per_block = kWave * ElemTraits<E>::VEC;
     const int gx = (N + cols_per_block - 1) / cols_per_block;
-    int splits = std::max(1, std::min(T / 32, 1024 / gx));
+    int splits = std::max(1, std::min(T / 64, 2048 / gx));
     const int rows_per_split = (T + splits - 1) / splits;
     splits = (T + rows_per_split - 1) / rows_per_split;
     hipLaunchKernelGGL(k_colsum<E>, dim3(gx, splits), dim3(kBlock), 0, (hipStream_t)st, (const E *)a, out, T, N,
