@@ -6,7 +6,8 @@
 //   s_comp  every layer kernel
 //   s_in    token ids, weight packs (prefetched one visit ahead, in n_micro pieces
 //           interleaved with the microbatch loop) and checkpoints coming back
-//   s_upd   optimizer state coming in, chunk by chunk, and the fused Adam kernel
+//   s_kin   optimizer state coming in, chunk by chunk, up to the ring's depth ahead
+//   s_upd   the fused Adam kernel (which also writes its results to the host)
 //   s_out   everything going to the host: checkpoints, updated state, gradients
 // All ordering is by events; the host thread only enqueues and finally waits.
 //
@@ -47,7 +48,7 @@ struct hmy_handle {
   bool dry = false;
   char *base = nullptr;
   bool own_arena = false;
-  hipStream_t s_comp = nullptr, s_in = nullptr, s_upd = nullptr, s_out = nullptr;
+  hipStream_t s_comp = nullptr, s_in = nullptr, s_kin = nullptr, s_upd = nullptr, s_out = nullptr;
   hmy_host_state host{};
   bool bound = false;
   char *stash_host = nullptr;   // pinned: checkpoints [n_ckpt][M][x_bytes]
@@ -518,10 +519,12 @@ void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
       r_v = h->host.adam_v + g0;
     }
   } else {
-    wait(h, h->s_upd, it.k_free[r]);
-    if (mixed) h2d(h, HMY_KIND_K, r_master, h->dry ? nullptr : h->host.master + g0, n * 4, h->s_upd);
-    h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_upd);
-    h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_upd);
+    // on a stream of their own, so that chunk c+1 arrives while chunk c is updated
+    wait(h, h->s_kin, it.k_free[r]);
+    if (mixed) h2d(h, HMY_KIND_K, r_master, h->dry ? nullptr : h->host.master + g0, n * 4, h->s_kin);
+    h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_kin);
+    h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_kin);
+    wait(h, h->s_upd, rec(h, h->s_kin));
   }
   if (u.next == 0) wait(h, h->s_upd, u.bwd_done);
   if (h->fused_swap_out) {
@@ -745,6 +748,7 @@ int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_m
   }
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_comp, hipStreamNonBlocking));
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_in, hipStreamNonBlocking));
+  HIPCHK(h, hipStreamCreateWithFlags(&h->s_kin, hipStreamNonBlocking));
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_upd, hipStreamNonBlocking));
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_out, hipStreamNonBlocking));
   const uint64_t stash_bytes = uint64_t(h->ckpt_layers.size()) * h->M * h->arena.res.x_bytes;
@@ -804,6 +808,7 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
   // always drain, even after an error, so no stream still touches caller memory
   hipStreamSynchronize(h->s_comp);
   hipStreamSynchronize(h->s_in);
+  hipStreamSynchronize(h->s_kin);
   hipStreamSynchronize(h->s_upd);
   hipError_t e_last = hipStreamSynchronize(h->s_out);
   if (h->err == HMY_OK && e_last != hipSuccess) h->err = fail(HMY_E_HIP, "stream sync: %s", hipGetErrorString(e_last));
@@ -841,6 +846,7 @@ int hmy_destroy(hmy_handle *h) {
     hipSetDevice(h->device);
     if (h->s_comp) { hipStreamSynchronize(h->s_comp); hipStreamDestroy(h->s_comp); }
     if (h->s_in) { hipStreamSynchronize(h->s_in); hipStreamDestroy(h->s_in); }
+    if (h->s_kin) { hipStreamSynchronize(h->s_kin); hipStreamDestroy(h->s_kin); }
     if (h->s_upd) { hipStreamSynchronize(h->s_upd); hipStreamDestroy(h->s_upd); }
     if (h->s_out) { hipStreamSynchronize(h->s_out); hipStreamDestroy(h->s_out); }
     for (hipEvent_t e : h->sync_events) hipEventDestroy(e);
