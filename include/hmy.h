@@ -248,10 +248,14 @@ int hmy_k_embed_bwd(int32_t prec, const int32_t *ids, const void *dx, float *dwt
 /* y = gamma * (x-mean)*rstd + beta; mean,rstd [T] fp32 saved */
 int hmy_k_layernorm_fwd(int32_t prec, const void *x, const void *gamma, const void *beta, void *y,
                         float *mean, float *rstd, int32_t T, int32_t d, float eps, void *stream);
-/* dx = (res ? res : 0) + LN'(dy); dgamma,dbeta += (fp32).  dx may alias res. */
+/* dx = (res ? res : 0) + LN'(dy); dgamma,dbeta += (fp32).  dx may alias res.
+ * workspace (device, may be NULL): with at least 256 * 2 * d floats the per-workgroup
+ * partial sums of dgamma / dbeta go there and a second kernel adds them up; without it
+ * they are added with atomics (same result up to summation order, slower). */
 int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float *mean,
                         const float *rstd, const void *gamma, const void *res, void *dx,
-                        float *dgamma, float *dbeta, int32_t T, int32_t d, void *stream);
+                        float *dgamma, float *dbeta, int32_t T, int32_t d, void *stream,
+                        float *workspace, uint64_t workspace_bytes);
 /* g = gelu_tanh(u); du = dg * gelu'(u) (du may alias dg) */
 int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream);
 int hmy_k_gelu_bwd(int32_t prec, const void *dg, const void *u, void *du, uint64_t n, void *stream);

@@ -104,6 +104,7 @@ N_SLOTS = 3
 OUT_RING, IN_RING, K_RING = 4, 2, 3
 K_CHUNK_MAX = 4 * 2 ** 20
 LOGIT_ROWS = 512
+LN_BLOCKS = 256
 
 
 def elem_bytes(precision: str) -> int:
@@ -156,14 +157,15 @@ def layer_profile(spec, M: int, b: int, precision: str):
 def reserved_bytes(spec, M: int, b: int, precision: str) -> int:
     """Pack-independent device memory: resident boundary activations (one per
     microbatch), pack-input ring, checkpoint staging ring, gradient scratch,
-    ids and targets, a 4 KiB scalar page, and the optimizer-state ring."""
+    ids and targets, a 4 KiB scalar page, the LayerNorm-backward partial sums
+    (LN_BLOCKS rows of 2 d floats) and the optimizer-state ring."""
     from . import model as om
     E = elem_bytes(precision)
     T, d, f, H = b * spec.seq_len, spec.d_model, spec.d_ffn, spec.n_heads
     x = _a256(T * d * E)
     total = _a256(M * x) + _a256(IN_RING * x) + _a256(OUT_RING * x)
     total += _a256(T * max(f, 3 * d) * E) + _a256(T * d * E) + _a256(T * H * 4)
-    total += 2 * _a256(M * T * 4) + 4096
+    total += 2 * _a256(M * T * 4) + 4096 + _a256(LN_BLOCKS * 2 * d * 4)
     chunk = min(K_CHUNK_MAX, max(om.layer_param_count(spec, l) for l in range(spec.n_layers)))
     n_k = 3 if precision == "bf16" else 2
     total += _a256(K_RING * n_k * _a256(chunk * 4))

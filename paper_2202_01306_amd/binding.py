@@ -284,9 +284,10 @@ def hmy_k_layernorm_fwd(prec, x, gamma, beta, y, mean, rstd, T, d, eps, stream=N
                                    C.c_float(eps), _p(stream)))
 
 
-def hmy_k_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None):
+def hmy_k_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None, workspace=None):
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib.hmy_k_layernorm_bwd(prec, _p(dy), _p(x), _p(mean), _p(rstd), _p(gamma), _p(res), _p(dx),
-                                   _p(dgamma), _p(dbeta), T, d, _p(stream)))
+                                   _p(dgamma), _p(dbeta), T, d, _p(stream), _p(workspace), C.c_uint64(ws_bytes)))
 
 
 def hmy_k_gelu_fwd(prec, u, g, n, stream=None):

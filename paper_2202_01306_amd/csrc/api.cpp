@@ -150,9 +150,10 @@ int hmy_k_layernorm_fwd(int32_t prec, const void *x, const void *gamma, const vo
 }
 int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float *mean, const float *rstd,
                         const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int32_t T, int32_t d,
-                        void *stream) {
+                        void *stream, float *workspace, uint64_t workspace_bytes) {
   NOTNULL(dy); NOTNULL(x); NOTNULL(mean); NOTNULL(rstd); NOTNULL(gamma); NOTNULL(dx); NOTNULL(dgamma); NOTNULL(dbeta);
-  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream);
+  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream, workspace,
+                              workspace_bytes);
 }
 int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream) {
   NOTNULL(u); NOTNULL(g);

@@ -247,16 +247,15 @@ __global__ void k_gelu_bwd(const E *dg, const E *u, E *du, uint64_t nvec) {
 // LayerNorm backward for rows of at most 64 * VEC * NJ elements: lane l owns columns
 // VEC * (l + 64 j) .. + VEC - 1, j < NJ, and keeps their dgamma / dbeta partial sums in
 // registers over all the rows its wave visits; one pass over x and dy (kept in
-// registers between the two phases), waves combine through LDS and each workgroup adds
-// its sums to global memory once.
+// registers between the two phases).  Each wave then writes its sums to its own row of
+// LDS, the workgroup adds the rows up, and one row per workgroup goes to the workspace
+// (or, without one, into dgamma / dbeta with atomics).
 template <typename E, int NJ>
-__global__ __launch_bounds__(512) void k_layernorm_bwd_reg(const E *dy, const E *x, const float *mean, const float *rstd,
+__global__ __launch_bounds__(NJ <= 2 ? 1024 : 512) void k_layernorm_bwd_reg(const E *dy, const E *x, const float *mean, const float *rstd,
                                                           const E *gamma, const E *res, E *dx, float *dgamma, float *dbeta,
-                                                          int T, int d) {
+                                                          int T, int d, float *partial) {
   constexpr int VEC = ElemTraits<E>::VEC;
-  extern __shared__ float lds[];   // dgamma[d], dbeta[d]
-  for (int c = threadIdx.x; c < 2 * d; c += blockDim.x) lds[c] = 0.f;
-  __syncthreads();
+  extern __shared__ float lds[];   // per wave: dgamma[d], dbeta[d]
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
   float dg[NJ][VEC], db[NJ][VEC];
   Vec16<E> gm[NJ];
@@ -319,21 +318,52 @@ __global__ __launch_bounds__(512) void k_layernorm_bwd_reg(const E *dy, const E 
       }
     }
   }
+  float *mine = lds + uint64_t(wave) * 2 * d;
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int c = VEC * (lane + kWave * j);
     if (c < d) {
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
-        atomicAdd(&lds[c + k], dg[j][k]);
-        atomicAdd(&lds[d + c + k], db[j][k]);
+        mine[c + k] = dg[j][k];
+        mine[d + c + k] = db[j][k];
       }
     }
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    atomicAdd(&dgamma[c], lds[c]);
-    atomicAdd(&dbeta[c], lds[d + c]);
+  float *row = partial ? partial + uint64_t(blockIdx.x) * 2 * d : nullptr;
+  for (int c = threadIdx.x; c < 2 * d; c += blockDim.x) {
+    float t = 0.f;
+    for (int w = 0; w < waves; ++w) t += lds[uint64_t(w) * 2 * d + c];
+    if (row) row[c] = t;   // one row of sums per workgroup; k_ln_bwd_reduce adds them up
+    else atomicAdd(c < d ? &dgamma[c] : &dbeta[c - d], t);
+  }
+}
+
+// dgamma += column sums of partial[:, 0:d], dbeta += those of partial[:, d:2d].  The
+// launches that accumulate into one tensor are ordered on their stream, so plain adds do.
+__global__ void k_ln_bwd_reduce(const float *partial, int rows, int d, float *dgamma, float *dbeta) {
+  __shared__ float part[4][64];
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;   // 64 columns x 4 interleaved row groups
+  const int c = blockIdx.x * 64 + tx;
+  float t = 0.f;
+  if (c < 2 * d) {
+    int r = ty;
+    for (; r + 28 < rows; r += 32) {
+      float v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = partial[uint64_t(r + 4 * q) * 2 * d + c];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) t += v[q];
+    }
+    for (; r < rows; r += 4) t += partial[uint64_t(r) * 2 * d + c];
+  }
+  part[ty][tx] = t;
+  __syncthreads();
+  if (ty == 0 && c < 2 * d) {
+    t = part[0][tx] + part[1][tx] + part[2][tx] + part[3][tx];
+    if (c < d) dgamma[c] += t;
+    else dbeta[c - d] += t;
   }
 }
 
@@ -638,27 +668,34 @@ int launch_layernorm_fwd(int prec, const void *x, const void *gamma, const void 
 }
 template <typename E>
 void launch_ln_bwd(const E *dy, const E *x, const float *mean, const float *rstd, const E *gamma, const E *res, E *dx,
-                   float *dgamma, float *dbeta, int T, int d, hipStream_t st) {
+                   float *dgamma, float *dbeta, int T, int d, hipStream_t st, float *ws, uint64_t ws_bytes) {
   constexpr int VEC = ElemTraits<E>::VEC;
   const int nj = (d + kWave * VEC - 1) / (kWave * VEC);
-  const int waves = 8, grid = grid_for(T, waves * 4, 256);   // at least 4 rows per wave
-  const size_t lds = size_t(2) * d * 4;
+  // as many waves per workgroup as 128 KiB of LDS holds rows of 2 d floats (16 at most):
+  // with one row per wave nearly every row of the microbatch is in flight at once
+  int waves = 16;
+  while (waves > 1 && (uint64_t(waves) * 2 * d * 4 > (128u << 10) || (nj > 2 && waves > 8))) waves /= 2;
+  const int grid = grid_for(T, waves, kLnBlocks);
+  float *partial = ws && ws_bytes >= uint64_t(grid) * 2 * d * 4 && nj <= 8 ? ws : nullptr;
+  const size_t lds = size_t(waves) * 2 * d * 4;
   const dim3 g(grid), b(waves * kWave);
-  if (nj == 1) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 1>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d);
-  else if (nj == 2) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 2>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d);
-  else if (nj <= 4) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 4>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d);
-  else if (nj <= 8) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 8>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d);
+  if (nj == 1) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 1>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, partial);
+  else if (nj == 2) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 2>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, partial);
+  else if (nj <= 4) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 4>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, partial);
+  else if (nj <= 8) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 8>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, partial);
   else
-    hipLaunchKernelGGL(k_layernorm_bwd<E>, dim3(grid_for(T, kWavesPerBlock, 512)), dim3(kBlock), lds, st, dy, x, mean, rstd,
-                       gamma, res, dx, dgamma, dbeta, T, d);
+    hipLaunchKernelGGL(k_layernorm_bwd<E>, dim3(grid_for(T, kWavesPerBlock, 512)), dim3(kBlock), size_t(2) * d * 4, st, dy, x, mean,
+                       rstd, gamma, res, dx, dgamma, dbeta, T, d);
+  if (partial) hipLaunchKernelGGL(k_ln_bwd_reduce, dim3((2 * d + 63) / 64), dim3(256), 0, st, partial, grid, d, dgamma, dbeta);
 }
 
 int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
-                         const void *res, void *dx, float *dgamma, float *dbeta, int T, int d, stream_t st) {
+                         const void *res, void *dx, float *dgamma, float *dbeta, int T, int d, stream_t st,
+                         float *workspace, uint64_t workspace_bytes) {
   if (T < 1 || d % 8 || d > 8192) return fail(HMY_E_INVALID, "layernorm_bwd: bad shape");
   DISPATCH_PREC(prec, {
     launch_ln_bwd<E>((const E *)dy, (const E *)x, mean, rstd, (const E *)gamma, (const E *)res, (E *)dx, dgamma, dbeta, T,
-                     d, (hipStream_t)st);
+                     d, (hipStream_t)st, workspace, workspace_bytes);
   });
   return check_launch("layernorm_bwd");
 }
@@ -737,7 +774,7 @@ int launch_adam_out(int prec, const float *grad, const float *in_master, const f
   // beside the compute stream: narrow workgroups, few of them -- what keeps the link busy
   // without flooding the fabric (see k_copy_out); with the device to itself: enough to
   // run the link at full speed
-  static const int cap_env = std::getenv("HMY_ADAM_GRID") ? std::max(1, std::atoi(std::getenv("HMY_ADAM_GRID"))) : 12;
+  static const int cap_env = std::getenv("HMY_ADAM_GRID") ? std::max(1, std::atoi(std::getenv("HMY_ADAM_GRID"))) : 10;
   const int blk = alone ? 256 : 64;
   const int grid = grid_for(n / 8 + 1, blk, alone ? 32 : cap_env);
   if (prec == HMY_PREC_BF16)

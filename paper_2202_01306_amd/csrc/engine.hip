@@ -302,19 +302,21 @@ void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer
   char *gbig = h->base + h->arena.res.gbig;
   char *gsmall = h->base + h->arena.res.gsmall;
   float *delta = (float *)(h->base + h->arena.res.delta);
+  float *ln_ws = (float *)(h->base + h->arena.res.ln_ws);
+  const uint64_t ln_ws_bytes = uint64_t(kLnBlocks) * 2 * d * 4;
   // y = x_mid + W2 gelu(W1 LN2(x_mid) + b1) + b2
   linear_bwd(h, D, A.g, W(W2), gbig, G(W2), G(B2), T, d, f);                     // dg
   KCHK(h, launch_gelu_bwd(prec, gbig, A.u, gbig, uint64_t(T) * f, h->s_comp));   // du
   linear_bwd(h, gbig, A.hh, W(W1), gsmall, G(W1), G(B1), T, f, d);               // dh
   KCHK(h, launch_layernorm_bwd(prec, gsmall, A.x_mid, A.ln2_mean, A.ln2_rstd, W(LN2_G), D, D, G(LN2_G), G(LN2_B), T, d,
-                               h->s_comp));                                        // D = dx_mid
+                               h->s_comp, ln_ws, ln_ws_bytes));                                        // D = dx_mid
   // x_mid = x_in + Wo attn(Wqkv LN1(x_in) + bqkv) + bo
   linear_bwd(h, D, A.o, W(WO), gsmall, G(WO), G(BO), T, d, d);                   // do
   KCHK(h, launch_attn_bwd(prec, A.qkv, A.o, gsmall, A.lse, delta, gbig, h->b, s.seq_len, s.n_heads, d / s.n_heads,
                           s.causal, h->s_comp));                                   // dqkv
   linear_bwd(h, gbig, A.a, W(WQKV), gsmall, G(WQKV), G(BQKV), T, 3 * d, d);      // da
   KCHK(h, launch_layernorm_bwd(prec, gsmall, x_in, A.ln1_mean, A.ln1_rstd, W(LN1_G), D, D, G(LN1_G), G(LN1_B), T, d,
-                               h->s_comp));                                        // D = dx_in
+                               h->s_comp, ln_ws, ln_ws_bytes));                                        // D = dx_in
 }
 
 // Final norm, vocabulary projection, loss and their backward, chunked over rows
@@ -364,7 +366,8 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
       run_gemm(h, g);
     }
   }
-  KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, g_lnf_g, g_lnf_b, T, d, h->s_comp));
+  KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, g_lnf_g, g_lnf_b, T, d, h->s_comp,
+                               (float *)(h->base + h->arena.res.ln_ws), uint64_t(kLnBlocks) * 2 * d * 4));
 }
 
 struct PendingUpdate {

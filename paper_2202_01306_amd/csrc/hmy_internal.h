@@ -46,7 +46,8 @@ constexpr int kOutRing = 4;            // staging buffers for checkpoints going 
 constexpr int kInRing = 2;             // pack-input buffers (checkpoint coming in)
 constexpr int kKRing = 3;              // optimizer-state ring slots
 constexpr uint64_t kKChunkMax = 4ull << 20;  // parameters per optimizer chunk
-constexpr int kLogitRows = 512;        // rows of the vocabulary projection per chunk
+constexpr int kLogitRows = 512;
+constexpr int kLnBlocks = 256;         // workgroups of a LayerNorm backward, each leaving one row of partial sums        // rows of the vocabulary projection per chunk
 
 struct BlockActs {  // byte offsets of one block's saved activations inside its region
   uint64_t x_in, a, qkv, o, x_mid, h, u, g, ln1_mean, ln1_rstd, ln2_mean, ln2_rstd, lse, size;
@@ -69,6 +70,7 @@ struct Reserved {  // pack-independent arena regions, byte offsets from the aren
   uint64_t delta;     // T*H*4
   uint64_t ids, targets;
   uint64_t misc;      // loss accumulators
+  uint64_t ln_ws;     // kLnBlocks x 2 d fp32 partial sums of dgamma, dbeta
   uint64_t kring;     // kKRing slots of k_arrays * karr_bytes
   uint64_t karr_bytes;
   uint64_t k_chunk_params;
@@ -110,7 +112,8 @@ int launch_layernorm_fwd(int prec, const void *x, const void *gamma, const void 
                          float *mean, float *rstd, int T, int d, float eps, stream_t st);
 int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *mean,
                          const float *rstd, const void *gamma, const void *res, void *dx,
-                         float *dgamma, float *dbeta, int T, int d, stream_t st);
+                         float *dgamma, float *dbeta, int T, int d, stream_t st, float *workspace = nullptr,
+                         uint64_t workspace_bytes = 0);
 int launch_gelu_fwd(int prec, const void *u, void *g, uint64_t n, stream_t st);
 int launch_gelu_bwd(int prec, const void *dg, const void *u, void *du, uint64_t n, stream_t st);
 int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st);

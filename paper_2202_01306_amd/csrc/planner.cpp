@@ -77,6 +77,7 @@ Reserved reserved_layout(const Model &m, int n_micro, int micro_batch) {
   r.ids = take(uint64_t(n_micro) * T * 4);
   r.targets = take(uint64_t(n_micro) * T * 4);
   r.misc = take(4096);
+  r.ln_ws = take(uint64_t(kLnBlocks) * 2 * d * 4);
   uint64_t maxp = 0;
   for (int l = 0; l < m.R; ++l) maxp = std::max(maxp, m.params_in(l, l + 1));
   r.k_chunk_params = std::min<uint64_t>(kKChunkMax, maxp);

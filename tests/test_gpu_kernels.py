@@ -80,6 +80,13 @@ def test_layernorm_fwd_bwd(prec, pc, dt, tol, T, d):
     dxd = torch.empty_like(xd)
     B.hmy_k_layernorm_bwd(pc, dev(dy, dt), xd, mean, rstd, gd, None, dxd, dgd, dbd, T, d)
     assert max_rel_err(host(dxd), dxr) < tol
+    # with a workspace: partial sums per workgroup, added up by a second kernel
+    dgd2, dbd2 = dev(dg0, torch.float32), dev(db0, torch.float32)
+    ws = torch.full((256 * 2 * d,), float("nan"), device="cuda")
+    B.hmy_k_layernorm_bwd(pc, dev(dy, dt), xd, mean, rstd, gd, None, dxd, dgd2, dbd2, T, d, workspace=ws)
+    assert max_rel_err(host(dxd), dxr) < tol
+    assert max_rel_err(host(dgd2) - dg0, dgr) < (tol if prec == "bf16" else 2e-5)
+    assert max_rel_err(host(dbd2) - db0, dbr) < (tol if prec == "bf16" else 2e-5)
 
 
 @pytest.mark.parametrize("prec,pc,dt,tol", PRECS)
