@@ -241,7 +241,10 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
 
   const int arow = wm * 64, brow = wn * 64;
   constexpr int KS = BK / 16;
-  bf16x8 fa[2][2], fb[2][2];   // operand fragments, double-buffered over the 16-deep steps
+  // operand fragments: read one step ahead of their multiplies (two buffers) with K tiles
+  // of 32, two steps ahead (four buffers, indexed by the step within the tile) with 64
+  constexpr int NBUF = KS == 4 ? 4 : 2;
+  bf16x8 fa[NBUF][2], fb[NBUF][2];
   auto load_frags = [&](int buf, int stage, int ks) {
     const bf16_t *a_s = smem + stage * (2 * TILE), *b_s = a_s + TILE;
 #pragma unroll
@@ -254,63 +257,93 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   if (n > S - 1) wait_vm<(S - 1) * L>();
   else wait_vm<0>();
   __syncthreads();
-  if (n > 0) load_frags(0, 0, 0);
+  if (n > 0) {
+    load_frags(0, 0, 0);
+    if (KS == 4) load_frags(1, 0, 1);
+  }
   if (p.ts) { ts1 = wall_clock64(); cy1 = clock64(); }
   // One 16-deep step: the four multiplies on fragment buffer `cur`, each followed by one
-  // of the four fragment reads of the next step (into the other buffer) and, twice, by
-  // one load-to-LDS of the tile being fetched.  A wavefront issues in order and an LDS
-  // read occupies its issue slot for some 20 cycles, so reads grouped in front of the
+  // of the four fragment reads of a later step (into buffer `nxt`) and, twice, by one
+  // load-to-LDS of the tile being fetched.  A wavefront issues in order and an LDS read
+  // occupies its issue slot for some 20 cycles, so reads grouped in front of the
   // multiplies would delay them; placed behind a multiply each read issues while the
   // matrix pipe works through that multiply's 32 cycles.  The fences pin this order.
 #define HMY_FENCE() __builtin_amdgcn_sched_barrier(0)
-  auto step = [&](int cur, bool reads, int nstage, int nks, bool fetch, int fstage, int part) {
+  auto step = [&](int cur, int nxt, bool reads, int nstage, int nks, bool fetch, int fstage, int part) {
     const bf16_t *a_s = smem + nstage * (2 * TILE), *b_s = a_s + TILE;
     const uint32_t fl = lds0 + uint32_t(fstage) * uint32_t(4 * TILE);
     HMY_FENCE();
     acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][0], acc[0][0], 0, 0, 0);
     HMY_FENCE();
-    if (reads) fa[cur ^ 1][0] = frag<TA, BK>(a_s, arow, nks, lane);
+    if (reads) fa[nxt][0] = frag<TA, BK>(a_s, arow, nks, lane);
     HMY_FENCE();
     acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][1], acc[0][1], 0, 0, 0);
     HMY_FENCE();
-    if (reads) fb[cur ^ 1][0] = frag<TB, BK>(b_s, brow, nks, lane);
+    if (reads) fb[nxt][0] = frag<TB, BK>(b_s, brow, nks, lane);
     if (fetch) da.issue_one(a_next, fl, wave, part);
     HMY_FENCE();
     acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur][0], acc[1][0], 0, 0, 0);
     HMY_FENCE();
-    if (reads) fb[cur ^ 1][1] = frag<TB, BK>(b_s, brow + 32, nks, lane);
+    if (reads) fb[nxt][1] = frag<TB, BK>(b_s, brow + 32, nks, lane);
     HMY_FENCE();
     acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur][1], acc[1][1], 0, 0, 0);
     HMY_FENCE();
-    if (reads) fa[cur ^ 1][1] = frag<TA, BK>(a_s, arow + 32, nks, lane);
+    if (reads) fa[nxt][1] = frag<TA, BK>(a_s, arow + 32, nks, lane);
     if (fetch) db.issue_one(b_next, fl + uint32_t(2 * TILE), wave, part);
     HMY_FENCE();
   };
   int stage = 0;      // stage holding tile t
-  int freed = S - 1;  // stage of tile t-1: free since the barrier that ended it
-  for (int t = 0; t + 1 < n; ++t) {
-    const int next = stage + 1 == S ? 0 : stage + 1;
-    // tile t+S-1 goes to the stage tile t-1 has left; its loads are spread over this
-    // tile's steps
-    const bool fetch = t > 0 && t + S - 1 < n;
-#pragma unroll
-    for (int ks = 0; ks + 1 < KS; ++ks) step(ks & 1, true, stage, ks + 1, fetch, freed, ks);
-    // every read of tile t has been issued.  Tile t+1 has landed once at most the S-2
-    // tiles issued after it (the one being fetched lacks its last part) are outstanding.
-    if (t + S - 1 < n) wait_vm<(S - 2) * L - (S > 2 ? 2 : 0)>();
-    else wait_vm<0>();
-    __syncthreads();   // tile t+1 visible to every wave; every wave is done reading tile t
-    step((KS - 1) & 1, true, next, 0, fetch, freed, KS - 1);
-    if (fetch) {
-      a_next += a_kstep;
-      b_next += b_kstep;
+  int freed = S - 1;  // stage of tile t-1: free since the barrier inside that tile
+  if constexpr (KS == 4) {
+    for (int t = 0; t + 1 < n; ++t) {
+      const int next = stage + 1 == S ? 0 : stage + 1;
+      // tile t+S-1 goes to the stage tile t-1 has left, a part per step
+      const bool fetch = t > 0 && t + S - 1 < n;
+      step(0, 2, true, stage, 2, fetch, freed, 0);
+      step(1, 3, true, stage, 3, fetch, freed, 1);
+      // every read of tile t has been issued.  Tile t+1 has landed once at most the S-3
+      // whole tiles issued after it and two parts of the tile being fetched are outstanding.
+      if (t + S - 1 < n) wait_vm<(S - 3) * L + 4>();
+      else wait_vm<0>();
+      __syncthreads();   // tile t+1 visible to every wave; every wave is done reading tile t
+      step(2, 0, true, next, 0, fetch, freed, 2);
+      step(3, 1, true, next, 1, fetch, freed, 3);
+      if (fetch) {
+        a_next += a_kstep;
+        b_next += b_kstep;
+      }
+      freed = stage;
+      stage = next;
     }
-    freed = stage;
-    stage = next;
-  }
-  if (n > 0) {   // last tile: nothing left to fetch or wait for
+    if (n > 0) {   // last tile: nothing left to fetch or wait for
+      step(0, 2, true, stage, 2, false, 0, 0);
+      step(1, 3, true, stage, 3, false, 0, 0);
+      step(2, 0, false, stage, 0, false, 0, 0);
+      step(3, 1, false, stage, 0, false, 0, 0);
+    }
+  } else {
+    for (int t = 0; t + 1 < n; ++t) {
+      const int next = stage + 1 == S ? 0 : stage + 1;
+      const bool fetch = t > 0 && t + S - 1 < n;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) step(ks & 1, ks + 1 < KS, stage, ks + 1, false, 0, 0);
+      for (int ks = 0; ks + 1 < KS; ++ks) step(ks & 1, (ks + 1) & 1, true, stage, ks + 1, fetch, freed, ks);
+      // every read of tile t has been issued.  Tile t+1 has landed once at most the S-2
+      // tiles issued after it (the one being fetched lacks its last part) are outstanding.
+      if (t + S - 1 < n) wait_vm<(S - 2) * L - 2>();
+      else wait_vm<0>();
+      __syncthreads();   // tile t+1 visible to every wave; every wave is done reading tile t
+      step((KS - 1) & 1, 0, true, next, 0, fetch, freed, KS - 1);
+      if (fetch) {
+        a_next += a_kstep;
+        b_next += b_kstep;
+      }
+      freed = stage;
+      stage = next;
+    }
+    if (n > 0) {   // last tile: nothing left to fetch or wait for
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) step(ks & 1, (ks + 1) & 1, ks + 1 < KS, stage, ks + 1, false, 0, 0);
+    }
   }
 #undef HMY_FENCE
 
