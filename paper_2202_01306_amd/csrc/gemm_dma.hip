@@ -135,14 +135,34 @@ struct Epi {
     if (p.gelu_out) ok = ok && (reinterpret_cast<uintptr_t>(p.gelu_out) & 15) == 0;
     fast = ok && m0 + BM <= p.M && n0 + BM <= p.N;
   }
-  __device__ __forceinline__ void emit_fast(const DmaP &p, int m, int nn, float (&v)[8]) const {
+  // tanh-form GELU with the hardware exponential: the argument is a bf16 value and so is
+  // the result, which the 2-ulp exponential does not disturb
+  static __device__ __forceinline__ float gelu_fast(float u) {
+    const float c = 0.7978845608028654f, a = 0.044715f;
+    const float t = 1.f - __fdividef(2.f, __expf(2.f * c * (u + a * u * u * u)) + 1.f);
+    return 0.5f * u * (1.f + t);
+  }
+  // what the output stage reads from global memory for 8 columns of one row: the residual
+  // (bf16) or, for an accumulating fp32 C, C itself.  Fetched before the last K tile so
+  // that its latency hides behind that tile's multiplies.
+  struct Pre { float4 lo, hi; };
+  __device__ __forceinline__ void prefetch(const DmaP &p, int m, int nn, Pre &r) const {
+    if (p.res) {
+      r.lo = *reinterpret_cast<const float4 *>(p.res + int64_t(m) * p.ldr + nn);
+    } else if (p.c_fp32 && p.accumulate) {
+      const float *c = static_cast<const float *>(p.C) + int64_t(m) * p.ldc + nn;
+      r.lo = *reinterpret_cast<const float4 *>(c);
+      r.hi = *reinterpret_cast<const float4 *>(c + 4);
+    }
+  }
+  __device__ __forceinline__ void emit_fast(const DmaP &p, int m, int nn, float (&v)[8], const Pre &r) const {
     if (p.bias) {
       const Vec16<bf16_t> b = load16(p.bias + nn);
 #pragma unroll
       for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
     }
     if (p.res) {
-      const Vec16<bf16_t> b = load16(p.res + int64_t(m) * p.ldr + nn);
+      const Vec16<bf16_t> b = *reinterpret_cast<const Vec16<bf16_t> *>(&r.lo);
 #pragma unroll
       for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
     }
@@ -151,9 +171,14 @@ struct Epi {
       float *c = static_cast<float *>(p.C) + ci;
       float4 lo = *reinterpret_cast<float4 *>(v), hi = *reinterpret_cast<float4 *>(v + 4);
       if (p.accumulate) {
-        const float4 a = *reinterpret_cast<const float4 *>(c), b = *reinterpret_cast<const float4 *>(c + 4);
-        lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
-        hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
+        if (p.res) {   // the prefetch slot held the residual: read C now
+          const float4 a = *reinterpret_cast<const float4 *>(c), b = *reinterpret_cast<const float4 *>(c + 4);
+          lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+          hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
+        } else {
+          lo.x += r.lo.x; lo.y += r.lo.y; lo.z += r.lo.z; lo.w += r.lo.w;
+          hi.x += r.hi.x; hi.y += r.hi.y; hi.z += r.hi.z; hi.w += r.hi.w;
+        }
       }
       *reinterpret_cast<float4 *>(c) = lo;
       *reinterpret_cast<float4 *>(c + 4) = hi;
@@ -165,7 +190,7 @@ struct Epi {
       if (p.gelu_out) {
         Vec16<bf16_t> g;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) g.v[k] = from_f32<bf16_t>(gelu_f(to_f32(o.v[k])));
+        for (int k = 0; k < 8; ++k) g.v[k] = from_f32<bf16_t>(gelu_fast(to_f32(o.v[k])));
         store16(p.gelu_out + ci, g);
       }
     }
@@ -294,6 +319,19 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   };
   int stage = 0;      // stage holding tile t
   int freed = S - 1;  // stage of tile t-1: free since the barrier inside that tile
+  const bool split = gridDim.y > 1;
+  Epi e;
+  e.init(p, m0, n0);
+  const int m_tile = m0 + wm * 64, n_tile = n0 + wn * 64;
+  Epi::Pre pre[2][4];
+  // lane's share of the output: slab i (32 rows), pass q -> row 8 q + lane/8, columns 8 (lane%8) .. +7
+  auto prefetch_outputs = [&]() {
+    if (split || !e.fast) return;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) e.prefetch(p, m_tile + 32 * i + 8 * q + lane / 8, n_tile + 8 * (lane % 8), pre[i][q]);
+  };
   if constexpr (KS == 4) {
     for (int t = 0; t + 1 < n; ++t) {
       const int next = stage + 1 == S ? 0 : stage + 1;
@@ -315,6 +353,7 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
       freed = stage;
       stage = next;
     }
+    prefetch_outputs();
     if (n > 0) {   // last tile: nothing left to fetch or wait for
       step(0, 2, true, stage, 2, false, 0, 0);
       step(1, 3, true, stage, 3, false, 0, 0);
@@ -340,6 +379,7 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
       freed = stage;
       stage = next;
     }
+    prefetch_outputs();
     if (n > 0) {   // last tile: nothing left to fetch or wait for
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) step(ks & 1, (ks + 1) & 1, ks + 1 < KS, stage, ks + 1, false, 0, 0);
@@ -355,7 +395,6 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   // consecutive columns per lane: 16-byte stores, 128 contiguous bytes per row.  Rows
   // that differ in bit 2 are written by the two lane halves at once; flipping bit 5 of
   // the column for them keeps the halves on different banks.
-  const bool split = gridDim.y > 1;
   if (split) {   // fp32 atomics: one column per lane, straight from the accumulator layout
     const int m_base = m0 + wm * 64 + 4 * (lane / 32), n_base = n0 + wn * 64 + lane % 32;
 #pragma unroll
@@ -374,9 +413,6 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   }
   __syncthreads();   // every wave has finished reading the operand stages
   float *slab = reinterpret_cast<float *>(smem) + wave * 2048;
-  Epi e;
-  e.init(p, m0, n0);
-  const int m_tile = m0 + wm * 64, n_tile = n0 + wn * 64;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -387,14 +423,14 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
         slab[row * 64 + (col ^ (((row >> 2) & 1) << 5))] = acc[i][j][r];
       }
     if (e.fast) {
-#pragma unroll 1
+#pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int row = 8 * q + lane / 8, c0 = 8 * (lane % 8);
         const float *src = slab + row * 64 + (c0 ^ (((row >> 2) & 1) << 5));
         float v[8];
         *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
         *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
-        e.emit_fast(p, m_tile + 32 * i + row, n_tile + c0, v);
+        e.emit_fast(p, m_tile + 32 * i + row, n_tile + c0, v, pre[i][q]);
       }
     } else {
 #pragma unroll 1
