@@ -101,7 +101,7 @@ def _a256(x: int) -> int:
 
 
 N_SLOTS = 3
-OUT_RING, IN_RING, K_RING = 4, 2, 3
+OUT_RING, IN_RING, K_RING = 4, 4, 3
 K_CHUNK_MAX = 4 * 2 ** 20
 LOGIT_ROWS = 512
 LN_BLOCKS = 256
@@ -244,36 +244,91 @@ def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_M
     return max(comp_free, d2h_free)
 
 
+def taper_first_pack(P_B):
+    """[0, e) -> [0,1), [1,2), [2,e): the pack visited last gets the smallest update."""
+    e = P_B[0][1]
+    if e < 2:
+        return list(P_B)
+    head = [(0, 1), (1, 2)] + ([(2, e)] if e > 2 else [])
+    return head + list(P_B[1:])
+
+
+def merge_last_packs(P_B):
+    """The last two backward packs become one (less recompute, shorter forward pass)."""
+    if len(P_B) < 2:
+        return list(P_B)
+    return list(P_B[:-2]) + [(P_B[-2][0], P_B[-1][1])]
+
+
 def plan(spec, budget: int, M: int, b: int, precision: str, search: int = 0, link_MBps: int = 40000,
          compute_GFLOPs: int = 250000):
     """Backward packs by Algorithm 2 on (t_bwd, mem_bwd) with capacity budget -
     reserve and the whole-arena test; then forward packs on (t_fwd, mem_fwd)
     over the layers before the last backward pack with capacity N_SLOTS * slot.
     search = 0 keeps the first feasible pack count (Algorithm 2 alone); search = n
-    also tries the next n feasible pack counts and, as Algorithm 1 does over its
-    configurations, keeps the one with the smallest estimated iteration time
-    (ties: fewer packs).  Returns (P_F, P_B) or None."""
+    also tries the next n feasible pack counts, each also with its first pack
+    tapered, its last two packs merged, and both (where the arena still fits), each with
+    balanced forward packs and with forward packs doubling in size from two layers, and,
+    as Algorithm 1 does over its configurations, keeps the candidate with the
+    smallest estimated iteration time (ties: the earlier one).  Returns (P_F, P_B)
+    or None."""
     prof = layer_profile(spec, M, b, precision)
     res = reserved_bytes(spec, M, b, precision)
     if budget <= res:
         return None
-    best, best_ns, S_start = None, None, 1
-    for _ in range(search + 1):
-        P_B, S_used = balanced_time_packing(
-            [p["t_bwd"] for p in prof], [p["mem_bwd"] for p in prof], budget - res,
-            also_fits=lambda packs: arena_bytes(spec, [], packs, M, b, precision)[0] <= budget,
-            S_start=S_start, with_S=True)
-        if P_B is None:
-            break
+    fits = lambda packs: arena_bytes(spec, [], packs, M, b, precision)[0] <= budget
+    state = dict(best=None, ns=None, failed=False)
+
+    def consider(P_B):
         slot = arena_bytes(spec, [], P_B, M, b, precision)[1]
         RF = forward_layers_given_backward(P_B)
         P_F = balanced_time_packing([p["t_fwd"] for p in prof[:RF]], [p["mem_fwd"] for p in prof[:RF]], N_SLOTS * slot)
         if P_F is None:
+            state["failed"] = True
+            return
+        def offer(P_F):
+            ns = estimate_iteration_ns(spec, P_F, P_B, M, b, precision, link_MBps, compute_GFLOPs)
+            if state["best"] is None or ns < state["ns"]:
+                state["best"], state["ns"] = (P_F, P_B), ns
+
+        offer(P_F)
+        if search > 0 and RF > 2:
+            # forward packs that double in size from two layers on: the first pack's
+            # load is the part of the forward pass nothing can hide
+            G, a, size, ok = [], 0, 2, True
+            while a < RF:
+                e = min(RF, a + size)
+                if RF - e < size:
+                    e = RF
+                if sum(p["mem_fwd"] for p in prof[a:e]) > N_SLOTS * slot:
+                    ok = False
+                G.append((a, e))
+                a, size = e, size * 2
+            if ok:
+                offer(G)
+
+    S_start = 1
+    for _ in range(search + 1):
+        P_B, S_used = balanced_time_packing(
+            [p["t_bwd"] for p in prof], [p["mem_bwd"] for p in prof], budget - res,
+            also_fits=fits, S_start=S_start, with_S=True)
+        if P_B is None:
+            break
+        consider(P_B)
+        if search > 0:
+            t = taper_first_pack(P_B)
+            if len(t) != len(P_B) and fits(t):
+                consider(t)
+            if len(P_B) >= 2:
+                g = merge_last_packs(P_B)
+                if fits(g):
+                    consider(g)
+                    tg = taper_first_pack(g)
+                    if len(tg) != len(g) and fits(tg):
+                        consider(tg)
+        if state["failed"]:
             return None
-        ns = estimate_iteration_ns(spec, P_F, P_B, M, b, precision, link_MBps, compute_GFLOPs)
-        if best is None or ns < best_ns:
-            best, best_ns = (P_F, P_B), ns
         if S_used > spec.n_layers:
             break
         S_start = S_used + 1
-    return best
+    return state["best"]

@@ -429,7 +429,7 @@ void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int 
   }
 }
 
-// enqueue whatever brings the input of backward visit v, microbatch mb, into inring[mb % 2]
+// enqueue whatever brings the input of backward visit v, microbatch mb, into inring[mb % kInRing]
 void issue_pack_input(hmy_handle *h, IterState &it, const Visit &v, int mb) {
   const int r = mb % kInRing;
   const uint64_t xb = uint64_t(h->b) * h->model.spec.seq_len * h->model.spec.d_model * h->model.elem_bytes();
@@ -625,12 +625,19 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
     }
     for (int m = 0; m < M; ++m) {
       if (v.bwd) {
-        if (m == 0) issue_pack_input(h, it, v, 0);
-        if (m + 1 < M && !v.last && v.pack.a != 0) issue_pack_input(h, it, v, m + 1);
+        // checkpoints are requested kInRing - 1 microbatches ahead: the copy engine's queue
+        // may hold optimizer chunks in front of them that wait for their ring slots
+        const bool from_host = !v.last && v.pack.a != 0;
+        if (m == 0)
+          for (int q = 0; q < (from_host ? std::min(M, kInRing - 1) : 1); ++q) issue_pack_input(h, it, v, q);
+        if (from_host && m + kInRing - 1 < M) issue_pack_input(h, it, v, m + kInRing - 1);
       }
       if (next) w_piece(*next, m);
       // this microbatch's share of the previous visit's update
-      if (it.upd.v) update_progress(h, it, hp, (it.upd.n_chunks * (m + 1) + M - 1) / M);
+      // (not behind a final visit that is the embedding alone: it is over in a moment, and
+      // what is left of the update then runs at the full link rate)
+      const bool tiny_last = !next && v.pack.a == 0 && v.pack.e == 1;
+      if (it.upd.v && !tiny_last) update_progress(h, it, hp, (it.upd.n_chunks * (m + 1) + M - 1) / M);
       if (v.bwd) {
         if (m > 0 && (v.last || v.pack.a == 0)) issue_pack_input(h, it, v, m);
         backward_visit_microbatch(h, it, v, m);
@@ -642,6 +649,7 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
     if (!v.bwd) {
       it.slot_free[v.slot] = rec(h, h->s_comp);
     } else {
+      if (!next) it.compute_done = true;   // nothing else will be enqueued on the compute stream
       update_begin(h, it, v, rec(h, h->s_comp), hp);
     }
   }

@@ -43,7 +43,7 @@ inline uint64_t a256(uint64_t x) { return (x + 255) & ~uint64_t(255); }
 
 constexpr int kSlots = 3;              // weight slots: in use, being prefetched, being updated and written back
 constexpr int kOutRing = 4;            // staging buffers for checkpoints going out
-constexpr int kInRing = 2;             // pack-input buffers (checkpoint coming in)
+constexpr int kInRing = 4;             // pack-input buffers (checkpoints coming in, up to three microbatches ahead)
 constexpr int kKRing = 3;              // optimizer-state ring slots
 constexpr uint64_t kKChunkMax = 4ull << 20;  // parameters per optimizer chunk
 constexpr int kLogitRows = 512;

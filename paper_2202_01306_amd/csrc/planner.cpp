@@ -316,16 +316,22 @@ int plan_packs(const Model &m, const hmy_budget &b, int n_micro, int micro_batch
   auto always = [](const std::vector<Pack> &) { return true; };
   // Candidates: the first feasible pack count of Algorithm 2 (largest packs), then up to
   // max_extra_packs further feasible pack counts; as in Algorithm 1 the configuration with
-  // the smallest estimated iteration time wins (ties: fewer packs).
+  // the smallest estimated iteration time wins (ties: the earlier candidate).  When the
+  // search is on, each balanced packing is also tried in three reshaped forms that the
+  // balanced split cannot produce and the estimate can tell apart:
+  //   taper : the first backward pack [0, e) becomes [0,1), [1,2), [2,e) -- the update of
+  //           the pack visited last cannot hide behind any compute, so it should be small,
+  //           and so should the one before it, which hides behind that short visit;
+  //   merge : the last two backward packs become one (if the arena still fits) -- the last
+  //           pack is not recomputed, and its layers drop out of the forward pass;
+  //   both.
   bool have = false;
   uint64_t best_ns = 0;
   Packs best;
-  int S_start = 1;
-  for (uint32_t tries = 0; tries <= b.max_extra_packs; ++tries) {
+  int rc_fwd = HMY_OK;
+  auto consider = [&](const std::vector<Pack> &bwd) {
     Packs p;
-    int S_used = 0;
-    // backward packs first (Algorithm 1, line "backward packing")
-    if (!balanced_time_packing(tb, mb, budget - res.size, 0, arena_fits, &p.bwd, S_start, &S_used)) break;
+    p.bwd = bwd;
     // forward packs over the layers before the last backward pack; they share the
     // weight slots sized by the backward packing
     const int RF = p.bwd.back().a;
@@ -338,14 +344,70 @@ int plan_packs(const Model &m, const hmy_budget &b, int n_micro, int micro_batch
       tf[l] = prof[l].t_fwd;
       mf[l] = prof[l].mem_fwd;
     }
-    if (!balanced_time_packing(tf, mf, uint64_t(kSlots) * slot, 0, always, &p.fwd))
-      return fail(HMY_E_BUDGET_TOO_SMALL, "forward packing failed (internal)");
-    const uint64_t ns = estimate_iteration_ns(m, prof, p, n_micro, link, rate);
-    if (!have || ns < best_ns) {
-      have = true;
-      best_ns = ns;
-      best = p;
+    if (!balanced_time_packing(tf, mf, uint64_t(kSlots) * slot, 0, always, &p.fwd)) {
+      rc_fwd = HMY_E_BUDGET_TOO_SMALL;
+      return;
     }
+    auto offer = [&](const Packs &q) {
+      const uint64_t ns = estimate_iteration_ns(m, prof, q, n_micro, link, rate);
+      if (!have || ns < best_ns) {
+        have = true;
+        best_ns = ns;
+        best = q;
+      }
+    };
+    offer(p);
+    if (b.max_extra_packs > 0 && RF > 2) {
+      // the same backward packs with forward packs that double in size from two layers
+      // on: the first pack's load is the part of the forward pass nothing can hide
+      Packs q = p;
+      q.fwd.clear();
+      bool ok = true;
+      for (int a = 0, size = 2; a < RF; size *= 2) {
+        int e = std::min(RF, a + size);
+        if (RF - e < size) e = RF;   // a short remainder joins this pack
+        uint64_t mem = 0;
+        for (int l = a; l < e; ++l) mem += mf[l];
+        if (mem > uint64_t(kSlots) * slot) ok = false;
+        q.fwd.push_back({a, e});
+        a = e;
+      }
+      if (ok) offer(q);
+    }
+  };
+  auto taper = [](std::vector<Pack> v) {
+    const int e = v.front().e;
+    if (e < 2) return v;
+    std::vector<Pack> head = {{0, 1}, {1, 2}};
+    if (e > 2) head.push_back({2, e});
+    else head.back().e = e;
+    v.erase(v.begin());
+    v.insert(v.begin(), head.begin(), head.end());
+    return v;
+  };
+  int S_start = 1;
+  for (uint32_t tries = 0; tries <= b.max_extra_packs; ++tries) {
+    std::vector<Pack> bwd;
+    int S_used = 0;
+    // backward packs first (Algorithm 1, line "backward packing")
+    if (!balanced_time_packing(tb, mb, budget - res.size, 0, arena_fits, &bwd, S_start, &S_used)) break;
+    consider(bwd);
+    if (b.max_extra_packs > 0) {
+      const std::vector<Pack> t = taper(bwd);
+      if (t.size() != bwd.size() && arena_fits(t)) consider(t);
+      if (bwd.size() >= 2) {
+        std::vector<Pack> g = bwd;
+        const Pack last = g.back();
+        g.pop_back();
+        g.back().e = last.e;
+        if (arena_fits(g)) {
+          consider(g);
+          const std::vector<Pack> tg = taper(g);
+          if (tg.size() != g.size() && arena_fits(tg)) consider(tg);
+        }
+      }
+    }
+    if (rc_fwd) return fail(HMY_E_BUDGET_TOO_SMALL, "forward packing failed (internal)");
     if (S_used > m.R) break;   // that was the one-layer-per-pack fallback
     S_start = S_used + 1;
   }
