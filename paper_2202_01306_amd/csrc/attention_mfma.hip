@@ -49,24 +49,35 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Stage ROWS rows x DH columns (global row stride ld) into LDS [ROWS][PITCH]; rows at
-// or beyond n_valid are zero.
+// or beyond n_valid are zero.  Two phases, so that the loads of the next tile are in
+// flight while the current one is multiplied: fetch into registers, put into LDS after
+// the compute.
 template <int DH, int ROWS>
-__device__ __forceinline__ void stage_tile(bf16_t *lds, const bf16_t *src, int64_t ld, int n_valid, int tid) {
-  constexpr int CPR = DH / 8;   // 16-byte chunks per row
-  constexpr int PITCH = Cfg<DH>::PITCH;
+struct TileRegs {
+  static constexpr int CPR = DH / 8;
+  static constexpr int N = ROWS * CPR / kThreads;
+  static_assert(N >= 1 && ROWS * CPR % kThreads == 0, "tile does not divide over the workgroup");
+  Vec16<bf16_t> v[N];
+  __device__ __forceinline__ void fetch(const bf16_t *src, int64_t ld, int n_valid, int tid) {
 #pragma unroll
-  for (int q = tid; q < ROWS * CPR; q += kThreads) {
-    const int r = q / CPR, c = (q % CPR) * 8;
-    Vec16<bf16_t> v;
-    if (r < n_valid) {
-      v = load16(src + int64_t(r) * ld + c);
-    } else {
+    for (int i = 0; i < N; ++i) {
+      const int q = tid + i * kThreads, r = q / CPR, c = (q % CPR) * 8;
+      if (r < n_valid) {
+        v[i] = load16(src + int64_t(r) * ld + c);
+      } else {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) v.v[k] = bf16_t(0.f);
+        for (int k = 0; k < 8; ++k) v[i].v[k] = bf16_t(0.f);
+      }
     }
-    store16(lds + r * PITCH + c, v);
   }
-}
+  __device__ __forceinline__ void put(bf16_t *lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int q = tid + i * kThreads, r = q / CPR, c = (q % CPR) * 8;
+      store16(lds + r * Cfg<DH>::PITCH + c, v[i]);
+    }
+  }
+};
 
 // Operand fragment along a tile row: lane (row%32, kg) gets 8 consecutive columns.
 template <int DH>
@@ -114,7 +125,8 @@ __global__ __launch_bounds__(kThreads) void k_attn_fwd_mfma(const bf16_t *qkv, b
   const int d = H * DH;
   const int64_t ld = 3 * int64_t(d);
   const int head = blockIdx.y, seq = blockIdx.z;
-  const int q0 = blockIdx.x * kBlockRows;
+  // causal: the last query blocks see the most keys; launch order = blockIdx order, so they go first
+  const int q0 = (causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kBlockRows;
   const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
   const int qw = q0 + 32 * wave;                 // first query of this wave
   const int q = qw + lane % 32;                  // this lane's query
@@ -129,15 +141,19 @@ __global__ __launch_bounds__(kThreads) void k_attn_fwd_mfma(const bf16_t *qkv, b
   const float sc = rsqrtf(float(DH)) * kLog2e;   // scores in log2 units
   const int k_end = causal ? min(s, q0 + kBlockRows) : s;
   const int n_tiles = (k_end + C::TILE - 1) / C::TILE;
-  stage_tile<DH, C::TILE>(sK[0], base + d, ld, min(C::TILE, s), tid);
-  stage_tile<DH, C::TILE>(sV[0], base + 2 * d, ld, min(C::TILE, s), tid);
+  TileRegs<DH, C::TILE> rk, rv;
+  rk.fetch(base + d, ld, min(C::TILE, s), tid);
+  rv.fetch(base + 2 * d, ld, min(C::TILE, s), tid);
+  rk.put(sK[0], tid);
+  rv.put(sV[0], tid);
   __syncthreads();
   for (int kt = 0; kt < n_tiles; ++kt) {
     const int cur = kt & 1, k0 = kt * C::TILE;
-    if (kt + 1 < n_tiles) {
+    const bool more = kt + 1 < n_tiles;
+    if (more) {   // next tile's loads fly during this tile's multiplies
       const int kn = k0 + C::TILE;
-      stage_tile<DH, C::TILE>(sK[cur ^ 1], base + d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
-      stage_tile<DH, C::TILE>(sV[cur ^ 1], base + 2 * d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+      rk.fetch(base + d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+      rv.fetch(base + 2 * d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
     }
     const bool wave_active = !causal || k0 <= qw + 31;   // some query of this wave sees this tile
     if (wave_active) {
@@ -150,31 +166,38 @@ __global__ __launch_bounds__(kThreads) void k_attn_fwd_mfma(const bf16_t *qkv, b
 #pragma unroll
         for (int c = 0; c < C::KSTEPS; ++c)
           st = mfma(frag_row<DH>(sK[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fq[c], st);
-        float mx = -INFINITY;
+        // keys past the sequence end or (causal) past the query: only the diagonal and
+        // the last subtile need the per-element test
+        if (kb + 32 > s || (causal && kb + 31 > qw)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kb + acc_row(r, h2);
-          const bool ok = key < s && (!causal || key <= q);
-          st[r] = ok ? st[r] * sc : -INFINITY;
-          mx = fmaxf(mx, st[r]);
+          for (int r = 0; r < 16; ++r) {
+            const int key = kb + acc_row(r, h2);
+            if (!(key < s && (!causal || key <= q))) st[r] = -INFINITY;
+          }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        float mx = st[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, st[r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;     // log2 units (sc > 0)
         const float m_new = fmaxf(m_run, mx);
         // rows that have seen no key yet keep m = -inf; use 0 as the reference to stay finite
         const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-        const float corr = fast_exp2(m_run - m_ref);
         float psum = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          st[r] = fast_exp2(st[r] - m_ref);
+          st[r] = fast_exp2(fmaf(st[r], sc, -m_ref));
           psum += st[r];
         }
-        l_run = l_run * corr + psum;
+        if (__any(m_new != m_run)) {   // some row's maximum moved: rescale what was accumulated
+          const float corr = fast_exp2(m_run - m_ref);
+          l_run *= corr;
+#pragma unroll
+          for (int t = 0; t < C::DTILES; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[t][r] *= corr;
+        }
+        l_run += psum;
         m_run = m_new;
-#pragma unroll
-        for (int t = 0; t < C::DTILES; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[t][r] *= corr;
         // O^T[dh, query] += V^T P^T
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
@@ -184,6 +207,10 @@ __global__ __launch_bounds__(kThreads) void k_attn_fwd_mfma(const bf16_t *qkv, b
             acc_o[t] = mfma(frag_col<DH>(sV[cur], 32 * sub + 16 * c, 32 * t, lane), fp, acc_o[t]);
         }
       }
+    }
+    if (more) {
+      rk.put(sK[cur ^ 1], tid);
+      rv.put(sV[cur ^ 1], tid);
     }
     __syncthreads();
   }
@@ -241,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dq_mfma(const bf16_t *qkv
   const int d = H * DH;
   const int64_t ld = 3 * int64_t(d);
   const int head = blockIdx.y, seq = blockIdx.z;
-  const int q0 = blockIdx.x * kBlockRows;
+  const int q0 = (causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kBlockRows;   // most keys first
   const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
   const bf16_t *gbase = d_o + int64_t(seq) * s * d + head * DH;
   const int qw = q0 + 32 * wave, q = qw + lane % 32, q_ld = min(q, s - 1);
@@ -259,15 +286,19 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dq_mfma(const bf16_t *qkv
   for (int t = 0; t < C::DTILES; ++t) acc_q[t] = zero16();
   const int k_end = causal ? min(s, q0 + kBlockRows) : s;
   const int n_tiles = (k_end + C::TILE - 1) / C::TILE;
-  stage_tile<DH, C::TILE>(sK[0], base + d, ld, min(C::TILE, s), tid);
-  stage_tile<DH, C::TILE>(sV[0], base + 2 * d, ld, min(C::TILE, s), tid);
+  TileRegs<DH, C::TILE> rk, rv;
+  rk.fetch(base + d, ld, min(C::TILE, s), tid);
+  rv.fetch(base + 2 * d, ld, min(C::TILE, s), tid);
+  rk.put(sK[0], tid);
+  rv.put(sV[0], tid);
   __syncthreads();
   for (int kt = 0; kt < n_tiles; ++kt) {
     const int cur = kt & 1, k0 = kt * C::TILE;
-    if (kt + 1 < n_tiles) {
+    const bool more = kt + 1 < n_tiles;
+    if (more) {   // next tile's loads fly during this tile's multiplies
       const int kn = k0 + C::TILE;
-      stage_tile<DH, C::TILE>(sK[cur ^ 1], base + d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
-      stage_tile<DH, C::TILE>(sV[cur ^ 1], base + 2 * d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+      rk.fetch(base + d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+      rv.fetch(base + 2 * d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
     }
     if (!causal || k0 <= qw + 31) {
 #pragma unroll
@@ -280,12 +311,17 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dq_mfma(const bf16_t *qkv
           st = mfma(frag_row<DH>(sK[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fq[c], st);   // S^T = K Q^T
           dp = mfma(frag_row<DH>(sV[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fg[c], dp);   // dP^T = V dO^T
         }
+        if (kb + 32 > s || (causal && kb + 31 > qw)) {   // diagonal or ragged subtile: per-element test
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kb + acc_row(r, h2);
-          const bool ok = key < s && (!causal || key <= q);
-          const float p = ok ? fast_exp2(st[r] * sc - L) : 0.f;
-          st[r] = p * (dp[r] - dl);                                                               // dS^T
+          for (int r = 0; r < 16; ++r) {
+            const int key = kb + acc_row(r, h2);
+            const bool ok = key < s && (!causal || key <= q);
+            const float p = ok ? fast_exp2(fmaf(st[r], sc, -L)) : 0.f;
+            st[r] = p * (dp[r] - dl);                                                             // dS^T
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) st[r] = fast_exp2(fmaf(st[r], sc, -L)) * (dp[r] - dl);
         }
         // dQ^T[dh, query] += K^T dS^T
 #pragma unroll
@@ -296,6 +332,10 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dq_mfma(const bf16_t *qkv
             acc_q[t] = mfma(frag_col<DH>(sK[cur], 32 * sub + 16 * c, 32 * t, lane), fs, acc_q[t]);
         }
       }
+    }
+    if (more) {
+      rk.put(sK[cur ^ 1], tid);
+      rv.put(sV[cur ^ 1], tid);
     }
     __syncthreads();
   }
@@ -322,7 +362,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dkv_mfma(const bf16_t *qk
   typedef Cfg<DH> C;
   __shared__ __attribute__((aligned(16))) bf16_t sQ[2][C::TILE * C::PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t sG[2][C::TILE * C::PITCH];
-  __shared__ float sL[2][C::TILE], sD[2][C::TILE];
+  __shared__ __attribute__((aligned(16))) float sL[2][C::TILE], sD[2][C::TILE];
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
   const int d = H * DH;
   const int64_t ld = 3 * int64_t(d);
@@ -345,20 +385,39 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dkv_mfma(const bf16_t *qk
   // causal: queries before the block's first key see none of its keys
   const int t_begin = causal ? j0 / C::TILE : 0;
   const int n_tiles = (s + C::TILE - 1) / C::TILE;
-  auto stage = [&](int buf, int i0) {
+  TileRegs<DH, C::TILE> rq, rg;
+  float rl = 0.f, rd = 0.f;
+  auto fetch = [&](int i0) {
     const int nv = min(C::TILE, s - i0);
-    stage_tile<DH, C::TILE>(sQ[buf], base + int64_t(i0) * ld, ld, nv, tid);
-    stage_tile<DH, C::TILE>(sG[buf], gbase + int64_t(i0) * d, d, nv, tid);
+    rq.fetch(base + int64_t(i0) * ld, ld, nv, tid);
+    rg.fetch(gbase + int64_t(i0) * d, d, nv, tid);
     if (tid < C::TILE) {
-      sL[buf][tid] = tid < nv ? lbase[i0 + tid] * kLog2e : 0.f;
-      sD[buf][tid] = tid < nv ? dbase[i0 + tid] : 0.f;
+      rl = tid < nv ? lbase[i0 + tid] * kLog2e : 0.f;
+      rd = tid < nv ? dbase[i0 + tid] : 0.f;
     }
   };
-  if (t_begin < n_tiles) stage(0, t_begin * C::TILE);
+  auto put = [&](int buf) {
+    rq.put(sQ[buf], tid);
+    rg.put(sG[buf], tid);
+    if (tid < C::TILE) {
+      sL[buf][tid] = rl;
+      sD[buf][tid] = rd;
+    }
+  };
+  if (t_begin < n_tiles) {
+    fetch(t_begin * C::TILE);
+    put(0);
+  }
   __syncthreads();
   for (int it = t_begin; it < n_tiles; ++it) {
     const int cur = (it - t_begin) & 1, i0 = it * C::TILE;
-    if (it + 1 < n_tiles) stage(cur ^ 1, i0 + C::TILE);
+    const bool more = it + 1 < n_tiles;
+    // (no register prefetch across the compute here: with both accumulator sets it would
+    // cost the second resident wave per SIMD)
+    if (more) {
+      fetch(i0 + C::TILE);
+      put(cur ^ 1);
+    }
 #pragma unroll
     for (int sub = 0; sub < C::TILE / 32; ++sub) {
       const int ib = i0 + 32 * sub;                       // first query of the subtile
@@ -370,13 +429,23 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dkv_mfma(const bf16_t *qk
         sm = mfma(frag_row<DH>(sQ[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fk[c], sm);
         dp = mfma(frag_row<DH>(sG[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fv[c], dp);
       }
+      // queries past the sequence end or (causal) before the key: only the diagonal and
+      // the last subtile need the per-element test
+      const bool edge = ib + 32 > s || (causal && ib < jw + 31);
+      // the lane's sixteen queries are four runs of four consecutive rows: 16-byte reads
+      float ql[16], qd[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        *reinterpret_cast<float4 *>(ql + 4 * g) = *reinterpret_cast<const float4 *>(&sL[cur][32 * sub + 8 * g + 4 * h2]);
+        *reinterpret_cast<float4 *>(qd + 4 * g) = *reinterpret_cast<const float4 *>(&sD[cur][32 * sub + 8 * g + 4 * h2]);
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int qi = 32 * sub + acc_row(r, h2);         // query inside the tile
-        const bool ok = i0 + qi < s && (!causal || key <= i0 + qi);
-        const float p = ok ? fast_exp2(sm[r] * sc - sL[cur][qi]) : 0.f;
+        const bool ok = !edge || (i0 + qi < s && (!causal || key <= i0 + qi));
+        const float p = ok ? fast_exp2(fmaf(sm[r], sc, -ql[r])) : 0.f;
         sm[r] = p;                                        // P
-        dp[r] = p * (dp[r] - sD[cur][qi]);                // dS
+        dp[r] = p * (dp[r] - qd[r]);                      // dS
       }
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
