@@ -62,8 +62,10 @@ struct hmy_handle {
   size_t sync_used = 0;
   std::vector<hipEvent_t> time_events;
   size_t time_used = 0;
-  struct Span { size_t a, b; int what; };  // what: 0 h2d, 1 d2h, 2 stall, 3 compute
+  struct Span { size_t a, b; int what;   int tag = 0;
+};  // what: 0 h2d, 1 d2h, 2 stall, 3 compute
   std::vector<Span> spans;
+  int tag = 0;   // what the spans recorded now belong to: 1000 * visit + microbatch (timeline dump)
   hmy_stats st{};
   int err = HMY_OK;
   bool timing = true;
@@ -115,7 +117,7 @@ size_t trec(hmy_handle *h, hipStream_t s) {
   return i;
 }
 void span(hmy_handle *h, size_t a, size_t b, int what) {
-  if (a != size_t(-1) && b != size_t(-1)) h->spans.push_back({a, b, what});
+  if (a != size_t(-1) && b != size_t(-1)) h->spans.push_back({a, b, what, h->tag});
 }
 // wait on a swap event from the compute stream, measuring the stall
 void comp_wait(hmy_handle *h, hipEvent_t e) {
@@ -624,6 +626,7 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
       KCHK(h, launch_fill_zero(pp.dW, v.nparams * 4, h->s_comp));
     }
     for (int m = 0; m < M; ++m) {
+      h->tag = 1000 * vi + m;
       if (v.bwd) {
         // checkpoints are requested kInRing - 1 microbatches ahead: the copy engine's queue
         // may hold optimizer chunks in front of them that wait for their ring slots
@@ -841,6 +844,20 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
       else h->st.gemm_s[sp.what - 10] += sec;
     }
     *out = h->st;
+    if (const char *path = std::getenv("HMY_TIMELINE")) {
+      // one line per timed span: what (0 h2d, 1 d2h/update kernel, 2 compute-stream wait, 3 compute span,
+      // 10.. GEMM variants), tag (1000 * visit + microbatch at enqueue), start and end in ms
+      // since the first span's start
+      if (FILE *f = std::fopen(path, "w")) {
+        for (const auto &sp : h->spans) {
+          float a = 0.f, b = 0.f;
+          if (hipEventElapsedTime(&a, h->time_events[h->spans[0].a], h->time_events[sp.a]) != hipSuccess) continue;
+          if (hipEventElapsedTime(&b, h->time_events[h->spans[0].a], h->time_events[sp.b]) != hipSuccess) continue;
+          std::fprintf(f, "%d %d %.3f %.3f\n", sp.what, sp.tag, a, b);
+        }
+        std::fclose(f);
+      }
+    }
   }
   return h->err;
 }

@@ -1,11 +1,14 @@
 // bf16 GEMM on the matrix cores with operand tiles streamed HBM -> LDS by the
 // load-to-LDS instruction (global_load_lds_dwordx4): no staging registers, so a ring
-// of S LDS stages keeps up to S-1 K tiles in flight per workgroup while one is multiplied, which is what hides HBM
-// latency when an operand is not cache-resident (activations of another microbatch,
-// weights that have just arrived from the host).
+// of S LDS stages keeps up to S-1 K tiles in flight per workgroup while one is
+// multiplied, which is what hides HBM latency when an operand is not cache-resident
+// (activations of another microbatch, weights that have just arrived from the host).
 //
 // 128x128 block tile, four wavefronts of 64x64 (2x2 v_mfma_f32_32x32x16_bf16), K tile
-// BK in {32, 64}.  One s_waitcnt vmcnt + one barrier per K tile.
+// BK in {32, 64}.  One s_waitcnt vmcnt + one barrier per K tile, placed inside the tile
+// so that the first fragments of the next tile are requested before this tile's last
+// multiplies.  Fragments are read one (BK 32) or two (BK 64) 16-deep steps ahead of
+// their multiplies; every LDS read and load-to-LDS is issued right behind a multiply.
 //
 // A load-to-LDS instruction writes 64 lanes x 16 bytes to one contiguous KiB of LDS
 // (lane i at byte 16 i) from per-lane global addresses, so the bank swizzle is applied
@@ -17,10 +20,11 @@
 // contraction-major: kept as loaded, [k][row], chunks swizzled by k, read through
 // ds_read_b64_tr_b16 with k rows 8h..8h+3 and 8h+4..8h+7 (h = lane/32), which is the
 // same contraction order as the 16-byte read of the other layout.
+//
+// Tuning switches (read once per process): HMY_GEMM_BK = 32 | 64 and
+// HMY_GEMM_STAGES = 3 | 4 override the K tile and the ring depth.
 #include <algorithm>
-#include <cstdio>
 #include <cstdlib>
-#include <vector>
 
 #include "dev_common.h"
 #include "hmy_internal.h"
@@ -44,7 +48,6 @@ struct DmaP {
   uint32_t lda, ldb;
   int64_t ldc, ldr;
   int c_fp32, accumulate;
-  long long *ts;  // DEV: per-block phase timestamps
 };
 
 // element address inside a [row][k] tile of BK columns (BK/8 chunks per row)
@@ -231,8 +234,6 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   const int in_band = bid - band * kBand * grid_n;
   const int m0 = (first_m + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BM;
 
-  long long ts0 = 0, ts1 = 0, ts2 = 0, cy1 = 0, cy2 = 0;
-  if (p.ts) ts0 = wall_clock64();
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -286,7 +287,6 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
     load_frags(0, 0, 0);
     if (KS == 4) load_frags(1, 0, 1);
   }
-  if (p.ts) { ts1 = wall_clock64(); cy1 = clock64(); }
   // One 16-deep step: the four multiplies on fragment buffer `cur`, each followed by one
   // of the four fragment reads of a later step (into buffer `nxt`) and, twice, by one
   // load-to-LDS of the tile being fetched.  A wavefront issues in order and an LDS read
@@ -387,7 +387,6 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   }
 #undef HMY_FENCE
 
-  if (p.ts) { ts2 = wall_clock64(); cy2 = clock64(); }
   // Epilogue.  Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4,
   // column l%32 of a 32x32 block: stored from there, a wavefront would write 2-byte
   // elements in 64-byte runs.  Each wave instead passes its 64x64 outputs, 32 rows at a
@@ -441,11 +440,6 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
       }
     }
   }
-  if (p.ts && tid == 0) {
-    long long *o = p.ts + 4 * (blockIdx.x + gridDim.x * blockIdx.y);
-    o[0] = ts0; o[1] = ts1; o[2] = ts2; o[3] = wall_clock64();
-    if (blockIdx.x == 0 && blockIdx.y == 0) p.ts[4 * gridDim.x * gridDim.y] = cy2 - cy1;
-  }
 }
 
 inline int check_launch(const char *what) {
@@ -462,17 +456,6 @@ int launch_cfg(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int tiles_per_s
   else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_dma<false, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
   else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<true, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
   else hipLaunchKernelGGL((k_gemm_dma<true, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
-  if (p.ts) {
-    (void)hipStreamSynchronize(s);
-    const int nb = int(grid.x * grid.y);
-    std::vector<long long> h(4 * nb);
-    (void)hipMemcpy(h.data(), p.ts, h.size() * 8, hipMemcpyDeviceToHost);
-    long long t0 = h[0], tend = 0; double pro = 0, loop = 0, epi = 0;
-    for (int b = 0; b < nb; ++b) { t0 = std::min(t0, h[4 * b]); tend = std::max(tend, h[4 * b + 3]); pro += h[4 * b + 1] - h[4 * b]; loop += h[4 * b + 2] - h[4 * b + 1]; epi += h[4 * b + 3] - h[4 * b + 2]; }
-    std::printf("[ts] BK=%d S=%d blocks=%d span %.2f us; per block: prologue %.2f us, loop %.2f us, epilogue %.2f us\n", BK, S, nb, (tend - t0) * 0.01, pro / nb * 0.01, loop / nb * 0.01, epi / nb * 0.01);
-    { long long cyc = 0; (void)hipMemcpy(&cyc, p.ts + 4 * nb, 8, hipMemcpyDeviceToHost); std::printf("   block 0 loop: %lld shader cycles over %.2f us = %.0f MHz\n", cyc, (h[2] - h[1]) * 0.01, cyc / ((h[2] - h[1]) * 0.01)); }
-    for (int b : {0, 1, nb / 2, nb - 1}) std::printf("   block %d: start %.2f pro %.2f loop %.2f epi %.2f\n", b, (h[4 * b] - t0) * 0.01, (h[4 * b + 1] - h[4 * b]) * 0.01, (h[4 * b + 2] - h[4 * b + 1]) * 0.01, (h[4 * b + 3] - h[4 * b + 2]) * 0.01);
-  }
   return check_launch("gemm_dma");
 }
 
@@ -499,10 +482,6 @@ int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st) {
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.lda = uint32_t(g.lda); p.ldb = uint32_t(g.ldb); p.ldc = g.ldc; p.ldr = g.ldr;
   p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate;
-  static long long *ts_buf = nullptr;
-  static const int want_ts = env_int("HMY_GEMM_TS", 0);
-  if (want_ts && !ts_buf) (void)hipMalloc(&ts_buf, 4 * 8 * 65536);
-  p.ts = want_ts ? ts_buf : nullptr;
   static const int force_bk = env_int("HMY_GEMM_BK", 0), force_s = env_int("HMY_GEMM_STAGES", 0);
   const int gm = (g.M + BM - 1) / BM, gn = (g.N + BM - 1) / BM;
   // split the contraction over workgroups (fp32 atomics into C) only while that fills

@@ -219,3 +219,25 @@ def test_forward_packing_covers_layers_before_last_backward_pack():
     assert P_F == [(0, 6)]
     # forward footprints are smaller, so forward packs are at least as large
     assert max(e - a for a, e in P_F) >= max(e - a for a, e in P_B[:-1])
+
+
+def test_reshaped_packings_stay_valid_coverings():
+    """The planner's reshaping moves (tapered first pack, merged last packs) keep a
+    packing contiguous, ordered and covering, whatever it starts from."""
+    for R in (2, 3, 5, 9):
+        for cuts in ([], [1], [2], [1, 3], [2, 4, 7]):
+            ends = sorted(set(c for c in cuts if 0 < c < R)) + [R]
+            P_B, a = [], 0
+            for e in ends:
+                P_B.append((a, e))
+                a = e
+            for Q in (opk.taper_first_pack(P_B), opk.merge_last_packs(P_B),
+                      opk.taper_first_pack(opk.merge_last_packs(P_B))):
+                assert Q[0][0] == 0 and Q[-1][1] == R
+                assert all(x[0] < x[1] for x in Q)
+                assert all(Q[i][1] == Q[i + 1][0] for i in range(len(Q) - 1))
+            t = opk.taper_first_pack(P_B)
+            if P_B[0][1] >= 2:
+                assert t[0] == (0, 1) and t[1] == (1, 2)
+            g = opk.merge_last_packs(P_B)
+            assert len(g) == max(1, len(P_B) - 1) and g[-1][1] == R
