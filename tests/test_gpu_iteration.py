@@ -175,6 +175,34 @@ def test_gpt2_medium_width_reduced_depth():
     run_and_compare(cfg, sched_ends=([1, 2, 3], [1, 2, 3, 4]), zero_state=False, steps=(3,))
 
 
+@pytest.mark.timeout(600)
+def test_gpt2_xl_width_reduced_depth():
+    """Width of the 1.5 B decoder (d=1600: output tiles ragged against 128, 25 heads of
+    64, FFN 6400, vocab 50257), one block, two microbatches of 2 x 256 tokens."""
+    say("gpt2-xl width, L=1, M=2, seq 256")
+    cfg = dict(synth.CONFIGS["gpt2xl"], n_blocks=1, M=2, b=2, seq_len=256)
+    run_and_compare(cfg, sched_ends=([1, 2], [1, 2, 3]), zero_state=False, steps=(2,))
+
+
+@pytest.mark.timeout(600)
+def test_bert_large_width_reduced_depth():
+    """Width of the encoder workload (bidirectional attention over 512 positions, 15 %
+    of them targets, vocab 30522), one block, two microbatches of 2 sequences."""
+    say("bert-large width, L=1, M=2")
+    cfg = dict(synth.CONFIGS["bertl"], n_blocks=1, M=2, b=2)
+    run_and_compare(cfg, sched_ends=([2], [1, 2, 3]), zero_state=False, steps=(2,))
+
+
+@pytest.mark.timeout(900)
+def test_6b7_width_reduced_depth():
+    """Width of the 6.7 B decoder (d=4096, 32 heads of 128, FFN 16384), one block, two
+    microbatches of 256 tokens; vocabulary cut to 8193 rows (ragged) to keep the fp64
+    reference small."""
+    say("6.7B width, L=1, M=2, seq 256, vocab 8193")
+    cfg = dict(synth.CONFIGS["gpt6b7"], n_blocks=1, M=2, b=1, seq_len=256, vocab=8193)
+    run_and_compare(cfg, sched_ends=([1, 2], [1, 2, 3]), zero_state=False, steps=(2,))
+
+
 def test_errors_from_the_engine():
     from paper_2202_01306_amd import binding as B
     from paper_2202_01306_amd.runner import TrainingState
