@@ -1,13 +1,16 @@
 """Host-side plumbing around the C-ABI engine: pinned host arrays, packing named
 tensors into the flat layout, and one call per training iteration.
 
-Nothing of the method is computed here: PyTorch only owns pinned host memory
-(and optionally the device arena); every step runs inside libhmy.so.
+Nothing of the method is computed here.  The host arrays are pinned memory from the
+library's own allocator (`hmy_host_alloc`), seen from Python as numpy arrays, so this
+module needs no PyTorch: a process that imports only it and the binding runs on the
+HIP runtime the library was linked against.
 """
 from __future__ import annotations
 
+import ctypes as C
+
 import numpy as np
-import torch
 
 from . import binding as B
 
@@ -15,6 +18,35 @@ from . import binding as B
 # try; the full-size parity tests use the same value so they check the launch
 # configuration that is timed.
 BENCH_PACK_SEARCH = 4
+
+
+class Pinned:
+    """A pinned host buffer from the library, viewed as a 1-D numpy array."""
+
+    def __init__(self, count: int, dtype):
+        self.dtype = np.dtype(dtype)
+        self.count = int(count)
+        self.nbytes = max(self.count * self.dtype.itemsize, 16)
+        self.ptr = B.hmy_host_alloc(self.nbytes)
+        buf = (C.c_char * self.nbytes).from_address(self.ptr)
+        self.a = np.frombuffer(buf, dtype=self.dtype, count=self.count)
+
+    def free(self) -> None:
+        if self.ptr:
+            self.a = None
+            B.hmy_host_free(self.ptr)
+            self.ptr = 0
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even bf16 of fp32 values, as uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << 16).view(np.float32)
 
 
 class TrainingState:
@@ -26,33 +58,58 @@ class TrainingState:
         self.layout = B.hmy_layout(self.spec)
         self.n_params = B.hmy_model_size(self.spec)[1]
         self.mixed = cfg["precision"] == "bf16"
-        wdtype = torch.bfloat16 if self.mixed else torch.float32
         n = self.n_params
-        self.weights = torch.empty(n, dtype=wdtype, pin_memory=True)
-        self.master = torch.empty(n, dtype=torch.float32, pin_memory=True) if self.mixed else None
-        self.adam_m = torch.zeros(n, dtype=torch.float32, pin_memory=True)
-        self.adam_v = torch.zeros(n, dtype=torch.float32, pin_memory=True)
-        self.grads = torch.zeros(n, dtype=torch.float32, pin_memory=True)
+        self._bufs = []
+
+        def pinned(dtype):
+            p = Pinned(n, dtype)
+            self._bufs.append(p)
+            return p
+
+        self.weights = pinned(np.uint16 if self.mixed else np.float32)   # bf16 bit patterns in mixed mode
+        self.master = pinned(np.float32) if self.mixed else None
+        self.adam_m = pinned(np.float32)
+        self.adam_v = pinned(np.float32)
+        self.grads = pinned(np.float32)
+        for p in (self.adam_m, self.adam_v, self.grads):
+            p.a[:] = 0
+
+    def close(self) -> None:
+        for p in self._bufs:
+            p.free()
+        self._bufs = []
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
     # -- named <-> flat -----------------------------------------------------------
-    def _flat_set(self, flat: torch.Tensor, named) -> None:
+    def _flat_set(self, flat: Pinned, named) -> None:
         for t in self.layout:
-            src = torch.from_numpy(np.ascontiguousarray(named[t["name"]], dtype=np.float32)).reshape(-1)
-            flat[t["offset"]:t["offset"] + t["count"]].copy_(src.to(flat.dtype))
+            src = np.ascontiguousarray(named[t["name"]], dtype=np.float32).reshape(-1)
+            flat.a[t["offset"]:t["offset"] + t["count"]] = src
 
-    def _flat_get(self, flat: torch.Tensor):
+    def _flat_get(self, flat: Pinned, bf16: bool = False):
         out = {}
         for t in self.layout:
-            a = flat[t["offset"]:t["offset"] + t["count"]].to(torch.float32).numpy().copy()
-            out[t["name"]] = a.reshape(t["rows"], t["cols"]) if t["cols"] > 1 else a
+            a = flat.a[t["offset"]:t["offset"] + t["count"]]
+            a = bf16_bits_to_f32(a) if bf16 else a.astype(np.float32)
+            out[t["name"]] = a.reshape(t["rows"], t["cols"]).copy() if t["cols"] > 1 else a.copy()
         return out
+
+    def _round_weights(self) -> None:
+        step = 1 << 24
+        for lo in range(0, self.n_params, step):
+            self.weights.a[lo:lo + step] = f32_to_bf16_bits(self.master.a[lo:lo + step])
 
     def load(self, params, m=None, v=None) -> None:
         """params: name -> fp32 array.  In bf16 mode they become the fp32 master and
         the compute weights are their round-to-nearest-even bf16 copy."""
         if self.mixed:
             self._flat_set(self.master, params)
-            self.weights.copy_(self.master.to(torch.bfloat16))
+            self._round_weights()
         else:
             self._flat_set(self.weights, params)
         if m is not None:
@@ -63,27 +120,27 @@ class TrainingState:
     def fill_random(self, seed: int = 0, std: float = 0.02) -> None:
         """Benchmark init without the named round trip: matrices N(0, std^2),
         LayerNorm gains 1, everything else 0."""
-        g = torch.Generator().manual_seed(seed)
-        tgt = self.master if self.mixed else self.weights
+        rng = np.random.default_rng(seed)
+        tgt = (self.master if self.mixed else self.weights).a
         for t in self.layout:
             sl = tgt[t["offset"]:t["offset"] + t["count"]]
             base = t["name"].split(".")[-1]
             if t["cols"] > 1:
-                sl.normal_(0.0, std, generator=g)
+                sl[:] = rng.standard_normal(t["count"], dtype=np.float32) * np.float32(std)
             elif base.endswith("_g"):
-                sl.fill_(1.0)
+                sl[:] = 1.0
             else:
-                sl.zero_()
+                sl[:] = 0.0
         if self.mixed:
-            self.weights.copy_(self.master.to(torch.bfloat16))
-        self.adam_m.zero_()
-        self.adam_v.zero_()
+            self._round_weights()
+        self.adam_m.a[:] = 0
+        self.adam_v.a[:] = 0
 
     def named(self, what: str):
         """what in weights | master | m | v | grads -> name -> fp32 array."""
         flat = {"weights": self.weights, "master": self.master, "m": self.adam_m, "v": self.adam_v,
                 "grads": self.grads}[what]
-        return self._flat_get(flat)
+        return self._flat_get(flat, bf16=(what == "weights" and self.mixed))
 
 
 class Engine:
@@ -91,34 +148,40 @@ class Engine:
 
     def __init__(self, state: TrainingState, budget_bytes: int, n_micro: int, micro_batch: int, sched=None,
                  device: int = 0, search: int = 0):
-        if not torch.cuda.is_available():
-            raise RuntimeError("the engine needs a GPU (there is no CPU fallback)")
         self.state = state
         self.M, self.b = n_micro, micro_batch
+        # fails with HMY_E_NO_DEVICE when there is no GPU: there is no CPU fallback
         self.handle = B.hmy_create(state.spec, budget_bytes, n_micro, micro_batch, sched, device, search=search)
         self.sched = B.hmy_get_schedule(self.handle)
         self.packs = B.schedule_packs(self.sched)
         self.arena = B.hmy_arena(state.spec, self.sched, n_micro, micro_batch)
-        B.hmy_bind_state(self.handle, state.weights.data_ptr(),
-                         state.master.data_ptr() if state.mixed else None, state.adam_m.data_ptr(),
-                         state.adam_v.data_ptr(), state.grads.data_ptr(), state.n_params)
+        B.hmy_bind_state(self.handle, state.weights.ptr, state.master.ptr if state.mixed else None, state.adam_m.ptr,
+                         state.adam_v.ptr, state.grads.ptr, state.n_params)
         self._ids = None
         self._tgt = None
 
     def set_batch(self, ids: np.ndarray, targets: np.ndarray) -> None:
         s = self.state.cfg["seq_len"]
         assert ids.shape == (self.M, self.b, s) and targets.shape == ids.shape
-        self._ids = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).pin_memory()
-        self._tgt = torch.from_numpy(np.ascontiguousarray(targets, dtype=np.int32)).pin_memory()
+        for old in (self._ids, self._tgt):
+            if old is not None:
+                old.free()
+        self._ids, self._tgt = Pinned(ids.size, np.int32), Pinned(ids.size, np.int32)
+        self._ids.a[:] = np.ascontiguousarray(ids, dtype=np.int32).reshape(-1)
+        self._tgt.a[:] = np.ascontiguousarray(targets, dtype=np.int32).reshape(-1)
 
     def step(self, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, step=1, want_stats=True):
-        return B.hmy_iteration(self.handle, self.M, self.b, self._ids.data_ptr(), self._tgt.data_ptr(), lr, beta1,
-                               beta2, eps, step, want_stats)
+        return B.hmy_iteration(self.handle, self.M, self.b, self._ids.ptr, self._tgt.ptr, lr, beta1, beta2, eps, step,
+                               want_stats)
 
     def close(self) -> None:
         if self.handle is not None:
             B.hmy_destroy(self.handle)
             self.handle = None
+        for old in (self._ids, self._tgt):
+            if old is not None:
+                old.free()
+        self._ids = self._tgt = None
 
     def __enter__(self):
         return self
