@@ -61,6 +61,7 @@ class Task:
     is_last_pack: bool = False
     stash_out_layers: list = field(default_factory=list)  # F: inputs checkpointed
     stash_in_layer: int | None = None                      # B: checkpoint consumed
+    mb: int | None = None    # None: the task runs every microbatch (input-batch grouping); else this one
 
 
 def task_list(spec: om.Spec, P_F, P_B):
@@ -84,12 +85,35 @@ def task_list(spec: om.Spec, P_F, P_B):
     return tasks
 
 
+def task_list_microbatch_major(spec: om.Spec, P_F, P_B, M: int):
+    """The order the paper compares against (Section 3, "Intuitive Example": memory
+    virtualisation per GPU, every microbatch on its own), over the SAME packs: for each
+    microbatch all forward packs, then all backward packs in reverse.  Nothing is grouped,
+    so every task names its microbatch.  The update of a pack still follows the backward
+    task that completes its gradient (the one of the last microbatch)."""
+    tasks = []
+    for mb in range(M):
+        for t in task_list(spec, P_F, P_B):
+            if t.kind == "A" and mb != M - 1:
+                continue
+            t.index = len(tasks)
+            t.mb = mb
+            tasks.append(t)
+    return tasks
+
+
 def iteration_layer_pack_major(spec: om.Spec, params, ids, targets, P_F, P_B,
-                               m, v, hp: om.AdamHP):
-    """One iteration in task-list order.  Returns dict(loss, grads, weights, m, v)."""
+                               m, v, hp: om.AdamHP, order: str = "layer_pack_major"):
+    """One iteration in task-list order.  Returns dict(loss, grads, weights, m, v).
+    order = "microbatch_major" executes task_list_microbatch_major instead."""
     M = ids.shape[0]
     n_tgt = om.count_targets(targets)
-    tasks = task_list(spec, P_F, P_B)
+    if order == "layer_pack_major":
+        tasks = task_list(spec, P_F, P_B)
+    elif order == "microbatch_major":
+        tasks = task_list_microbatch_major(spec, P_F, P_B, M)
+    else:
+        raise ValueError(order)
     X = [None] * M                    # boundary activation of each microbatch
     stash = {}                        # (layer, mb) -> checkpointed input
     grads: dict = {}
@@ -98,8 +122,9 @@ def iteration_layer_pack_major(spec: om.Spec, params, ids, targets, P_F, P_B,
 
     for t in tasks:
         a, e = t.pack
+        mbs = range(M) if t.mb is None else (t.mb,)
         if t.kind == "F":
-            for mb in range(M):
+            for mb in mbs:
                 x = X[mb]
                 for layer in range(a, e):
                     if layer in t.stash_out_layers:
@@ -107,7 +132,7 @@ def iteration_layer_pack_major(spec: om.Spec, params, ids, targets, P_F, P_B,
                     x, _ = om.layer_fwd(layer, x, params, spec, ids[mb], targets[mb], n_tgt)
                 X[mb] = x
         elif t.kind == "B":
-            for mb in range(M):
+            for mb in mbs:
                 b = ids[mb].shape[0]
                 if a == 0:
                     x = None                  # the embedding restarts from the ids

@@ -77,9 +77,22 @@ def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
 
 def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
     """Same packs, same one-pack-at-a-time residency, but every microbatch runs
-    through all packs before the next one starts: weights come in M times."""
+    through all packs before the next one starts (the per-GPU-swap order of
+    Section 3, "Intuitive Example").  Weights come in M times.  A pack's gradient
+    buffer cannot stay on the device between microbatches either (appendix
+    "Additional Swap Analysis": dW swaps like W, in the backward pass only): it
+    goes out after every backward task and comes back in before the next
+    microbatch's.  Readings: the first microbatch starts from a zero-filled buffer
+    (nothing to bring in); the last microbatch's gradient is consumed on the device
+    by the update that follows it and leaves once, as the exported gradient -- so
+    M - 1 times in and M times out, against the paper's 2m + 2 for a system that
+    also swaps around a separate update phase."""
     out = closed_form(spec, P_F, P_B, M, b, precision)
+    w_c, k_B, g_B = bytes_per_param(precision)
+    P_all = _pcount(spec, 0, spec.n_layers)
     out["h2d"]["W"] *= M
+    out["h2d"]["dW"] = (M - 1) * g_B * P_all
+    out["d2h"]["dW"] = M * g_B * P_all
     return out
 
 
@@ -104,6 +117,38 @@ def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
             if t.stash_in_layer is not None:
                 for _mb in range(M):
                     h2d["sX"] += act
+        else:
+            h2d["K"] += k_B * npar
+            d2h["K"] += k_B * npar
+            d2h["W"] += w_c * npar
+            d2h["dW"] += g_B * npar
+    return {"h2d": h2d, "d2h": d2h}
+
+
+def ledger_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
+    """Add up what every task of the microbatch-major list swaps."""
+    w_c, k_B, g_B = bytes_per_param(precision)
+    T = b * spec.seq_len
+    act = T * spec.d_model * w_c
+    h2d = dict.fromkeys(KINDS, 0)
+    d2h = dict.fromkeys(KINDS, 0)
+    h2d["ids"] += M * T * 4       # token ids
+    h2d["ids"] += M * T * 4       # targets
+    has_gradient = set()          # packs whose buffer holds earlier microbatches' sums
+    for t in osch.task_list_microbatch_major(spec, P_F, P_B, M):
+        npar = _pcount(spec, *t.pack)
+        if t.kind == "F":
+            h2d["W"] += w_c * npar
+            d2h["sX"] += act * len(t.stash_out_layers)
+        elif t.kind == "B":
+            h2d["W"] += w_c * npar
+            if t.stash_in_layer is not None:
+                h2d["sX"] += act
+            if t.pack in has_gradient:
+                h2d["dW"] += g_B * npar
+            has_gradient.add(t.pack)
+            if t.mb != M - 1:                 # else the update that follows takes it from the device
+                d2h["dW"] += g_B * npar
         else:
             h2d["K"] += k_B * npar
             d2h["K"] += k_B * npar

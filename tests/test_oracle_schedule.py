@@ -50,6 +50,34 @@ def test_layer_pack_major_is_bit_identical_to_microbatch_major(causal):
     assert tried > 16
 
 
+def test_microbatch_major_over_packs_is_bit_identical_too():
+    """The comparison order of Section 3 (every microbatch on its own through all packs,
+    gradients summed across microbatches, update after the last one) is ordinary
+    training as well: same loss, gradients and updated state, bit for bit."""
+    cfg = tiny_cfg(n_blocks=3, M=3, b=2)
+    spec = oracle_spec(cfg)
+    params = f64(synth.gen_params(cfg, 2, bench_init=False))
+    m0, v0 = (f64(x) for x in synth.gen_adam_state(cfg, 2, zero=False))
+    ids = synth.gen_tokens(cfg, 2)
+    tg = synth.gen_targets(cfg, ids, 2)
+    hp = om.AdamHP(step=3)
+    ref = om.training_iteration(spec, params, ids, tg, m0, v0, hp)
+    for P_F, P_B in (([(0, 1), (1, 2), (2, 3), (3, 4)], [(0, 1), (1, 2), (2, 3), (3, 4), (4, 5)]),
+                     ([(0, 3)], [(0, 2), (2, 3), (3, 5)]), ([], [(0, 5)])):
+        tasks = osch.task_list_microbatch_major(spec, P_F, P_B, 3)
+        assert [t.index for t in tasks] == list(range(len(tasks)))
+        assert sum(t.kind == "A" for t in tasks) == len(P_B) and all(t.mb == 2 for t in tasks if t.kind == "A")
+        # per microbatch: every forward pack, then every backward pack in reverse
+        for mb in range(3):
+            mine = [t for t in tasks if t.mb == mb and t.kind != "A"]
+            assert [t.pack for t in mine] == list(P_F) + list(reversed(P_B))
+        out = osch.iteration_layer_pack_major(spec, params, ids, tg, P_F, P_B, m0, v0, hp, order="microbatch_major")
+        assert abs(out["loss"] - ref["loss"]) < 1e-15
+        for k in ("grads", "weights", "m", "v"):
+            for name in params:
+                np.testing.assert_array_equal(out[k][name], ref[k][name], err_msg=f"{k}:{name}")
+
+
 def test_task_list_order_follows_algorithm_3():
     spec = om.Spec(4, 8, 2, 16, 4, 16)
     P_B = [(0, 2), (2, 4), (4, 6)]
@@ -122,6 +150,51 @@ def test_closed_form_equals_ledger_equals_machine_on_every_packing(precision):
                 assert cf["h2d"]["dW"] == 0 and cf["d2h"]["dW"] == g_B * sum(pc)
                 assert cf["h2d"]["sX"] == cf["d2h"]["sX"] == \
                     M * b * spec.seq_len * spec.d_model * w_c * max(len(P_B) - 2, 0)
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_microbatch_major_volumes_closed_form_ledger_machine(precision):
+    """Closed form = walk over the microbatch-major task list = residency machine, on
+    every packing; and the distance to the paper's own dW count is exactly the three
+    transfers the readings remove (no first swap-in, no swap-in and no second swap-out
+    around a separate update phase)."""
+    spec = om.Spec(4, 8, 2, 24, 4, 16)      # R = 6, unequal layers
+    R = spec.n_layers
+    w_c, k_B, g_B = osw.bytes_per_param(precision)
+    pc = [om.layer_param_count(spec, l) for l in range(R)]
+    for M, b in ((1, 1), (2, 1), (4, 2)):
+        for P_B in all_packings(R):
+            last_start = P_B[-1][0]
+            fwd_opts = list(all_packings(last_start)) if last_start else [[]]
+            for P_F in fwd_opts[::2] + fwd_opts[-1:]:
+                cf = osw.closed_form_microbatch_major(spec, P_F, P_B, M, b, precision)
+                assert cf == osw.ledger_microbatch_major(spec, P_F, P_B, M, b, precision)
+                lpm = osw.closed_form(spec, P_F, P_B, M, b, precision)
+                for kind in ("K", "sX", "ids"):
+                    assert cf["h2d"][kind] == lpm["h2d"][kind] and cf["d2h"][kind] == lpm["d2h"][kind]
+                assert cf["d2h"]["W"] == lpm["d2h"]["W"]
+                # weights from first principles: one pack resident at a time, clean ones dropped
+                packs = list(P_F) + list(P_B)
+                one_mb = [(i, False) for i in range(len(P_F))] + \
+                         [(len(P_F) + j, False) for j in reversed(range(len(P_B)))]
+                steps = []
+                for mb in range(M):
+                    steps += one_mb if mb < M - 1 else one_mb[:len(P_F)]
+                    if mb < M - 1:
+                        steps.append(osw.FLUSH)     # the first forward pack of the next microbatch comes in anew
+                for j in reversed(range(len(P_B))):
+                    steps += [(len(P_F) + j, False), (len(P_F) + j, True)]
+                i, o = osw.residency_machine(steps, [w_c * sum(pc[a:e]) for (a, e) in packs], False)
+                assert (i, o) == (cf["h2d"]["W"], cf["d2h"]["W"])
+                # gradient buffers: written by every backward task, one resident at a time
+                gsteps = []
+                for mb in range(M):
+                    gsteps += [(j, True) for j in reversed(range(len(P_B)))] + [osw.FLUSH]
+                gi, go = osw.residency_machine(gsteps, [g_B * sum(pc[a:e]) for (a, e) in P_B], False)
+                dW = g_B * sum(pc)
+                assert go == cf["d2h"]["dW"] == M * dW
+                assert gi - dW == cf["h2d"]["dW"]          # the machine also "reads" the first, all-zero buffer
+                assert cf["h2d"]["dW"] + cf["d2h"]["dW"] == osw.paper_dW_volume_per_gpu_swap_dp(M, 1, dW) - 3 * dW
 
 
 def test_weight_volume_reduces_to_3W_when_last_pack_is_counted_twice():
