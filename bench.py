@@ -92,6 +92,8 @@ def main() -> int:
     ap.add_argument("--pack-search", type=int, default=None,
                     help="how many pack counts beyond the first feasible one the planner may try (0 = Algorithm 2 alone)")
     ap.add_argument("--reference-kernels", action="store_true", help="time the plain (non-MFMA) kernels")
+    ap.add_argument("--order", choices=("layer-pack-major", "microbatch-major"), default="layer-pack-major",
+                    help="microbatch-major: the order the paper compares against, over the same packs (ablation)")
     a = ap.parse_args()
     if a.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {a.gpus} is not supported",
@@ -120,7 +122,11 @@ def main() -> int:
     st.fill_random(0)
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
-    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search) as eng:
+    sched = None
+    if a.order == "microbatch-major":
+        sched = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search)
+        sched.order = B.HMY_ORDER_MICROBATCH_MAJOR
+    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], sched, search=a.pack_search) as eng:
         eng.set_batch(ids, tg)
         step = 1
         for _ in range(a.warmup):
@@ -158,7 +164,7 @@ def main() -> int:
                                f"ffn={cfg['d_ffn']} seq={cfg['seq_len']} vocab={cfg['vocab']}, "
                                f"{cfg['M']} microbatches x {cfg['b']} sequences",
                    "hbm_budget_bytes": cfg["budget"], "arena_bytes": arena["total"],
-                   "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
+                   "order": a.order, "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
                    "kernels": "reference" if a.reference_kernels else "mfma"},
         "tflops": total_flops / (ms * 1e-3) / 1e12,
         "swap": {"h2d_GB_per_iter": h2d / 1e9, "d2h_GB_per_iter": d2h / 1e9,

@@ -82,14 +82,30 @@ typedef struct hmy_budget {
   uint32_t reserved_;
 } hmy_budget;
 
+/* Order in which the tasks of one iteration run over the packs.
+ * LAYER_PACK_MAJOR is the method (Section 3, "Key Optimizations": input-batch
+ * grouping, jit-compute, jit-update): every pack is visited once per pass and run
+ * over all microbatches.  MICROBATCH_MAJOR is the order the paper compares against
+ * (Section 3, "Intuitive Example": per-GPU memory virtualisation): every microbatch
+ * runs through all packs on its own, so weights cross the link once per pass AND
+ * microbatch, and a pack's gradient sums go to the host array after each backward
+ * task and come back before the next microbatch's (appendix "Additional Swap
+ * Analysis"); the update of a pack follows its last microbatch's backward task.
+ * Same packs, same arena, same kernels, same results up to summation order. */
+#define HMY_ORDER_LAYER_PACK_MAJOR 0
+#define HMY_ORDER_MICROBATCH_MAJOR 1
+
 /* Configuration (Section 4.3.1): forward and backward layer packs as exclusive
  * end indices over the R layers.  Backward packs cover 0..R; forward packs cover
  * exactly the layers before the last backward pack (Algorithm 2, lines 1-2).
- * Microbatch sizes U_F = U_B = micro_batch are given by the caller. */
+ * Microbatch sizes U_F = U_B = micro_batch are given by the caller.
+ * order: HMY_ORDER_*; hmy_plan returns LAYER_PACK_MAJOR, any other value than the
+ * two above is HMY_E_BAD_SCHEDULE. */
 typedef struct hmy_schedule {
   int32_t n_fwd_packs, n_bwd_packs;
   int32_t fwd_pack_end[HMY_MAX_LAYERS];
   int32_t bwd_pack_end[HMY_MAX_LAYERS];
+  int32_t order;
 } hmy_schedule;
 
 /* One minibatch as a list of n_micro microbatches of micro_batch sequences. */
@@ -189,7 +205,8 @@ int hmy_plan(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_mic
 /* Runtime estimate (integer nanoseconds) of one iteration for a schedule: an
  * event-driven walk of the task list over the compute stream and the two
  * directions of the host link (Section 4.3.1, "Runtime Estimator"), with the
- * rates given in *budget.  This is what hmy_plan minimises when it searches. */
+ * rates given in *budget.  This is what hmy_plan minimises when it searches.
+ * It models the layer-pack-major order only (sched->order is not looked at). */
 int hmy_estimate(const hmy_model_spec *spec, const hmy_schedule *sched, const hmy_budget *budget,
                  int32_t n_micro, int32_t micro_batch, uint64_t *iteration_ns);
 
@@ -197,8 +214,8 @@ int hmy_estimate(const hmy_model_spec *spec, const hmy_schedule *sched, const hm
 int hmy_arena(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro,
               int32_t micro_batch, hmy_arena_plan *out);
 
-/* Walk the iteration's task list exactly as hmy_iteration does, touching no
- * device: fills only the byte counters of *out. */
+/* Walk the iteration's task list (in sched->order) exactly as hmy_iteration does,
+ * touching no device: fills only the byte counters of *out. */
 int hmy_count_swaps(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro,
                     int32_t micro_batch, hmy_stats *out);
 

@@ -18,6 +18,7 @@ HMY_NAME_LEN = 32
 HMY_NKINDS = 7
 KIND_NAMES = ("W", "dW", "K", "sX", "XY", "dXdY", "ids")
 HMY_PREC_FP32, HMY_PREC_BF16 = 0, 1
+HMY_ORDER_LAYER_PACK_MAJOR, HMY_ORDER_MICROBATCH_MAJOR = 0, 1
 (HMY_OK, HMY_E_INVALID, HMY_E_BUDGET_TOO_SMALL, HMY_E_BAD_SCHEDULE, HMY_E_HIP,
  HMY_E_NOT_BOUND, HMY_E_NO_DEVICE) = (0, -1, -2, -3, -4, -5, -6)
 
@@ -50,7 +51,8 @@ def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0) -> hmy_bu
 
 class hmy_schedule(C.Structure):
     _fields_ = [("n_fwd_packs", C.c_int32), ("n_bwd_packs", C.c_int32),
-                ("fwd_pack_end", C.c_int32 * HMY_MAX_LAYERS), ("bwd_pack_end", C.c_int32 * HMY_MAX_LAYERS)]
+                ("fwd_pack_end", C.c_int32 * HMY_MAX_LAYERS), ("bwd_pack_end", C.c_int32 * HMY_MAX_LAYERS),
+                ("order", C.c_int32)]
 
 
 class hmy_minibatch(C.Structure):
@@ -124,8 +126,9 @@ def make_spec(cfg) -> hmy_model_spec:
                           cfg["vocab"], int(cfg["causal"]), prec, float(cfg.get("ln_eps", 1e-5)))
 
 
-def make_schedule(fwd_ends, bwd_ends) -> hmy_schedule:
+def make_schedule(fwd_ends, bwd_ends, order=0) -> hmy_schedule:
     s = hmy_schedule()
+    s.order = order
     s.n_fwd_packs, s.n_bwd_packs = len(fwd_ends), len(bwd_ends)
     for i, e in enumerate(fwd_ends):
         s.fwd_pack_end[i] = e

@@ -662,6 +662,107 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
   span(h, t_first, t_last, 3);
 }
 
+// The order the paper compares against (Section 3, "Intuitive Example"; appendix
+// "Additional Swap Analysis" for the gradients): the same visits, but every microbatch
+// walks through all of them before the next one starts.  Weights come in for every
+// (visit, microbatch); a backward pack's gradient sums go home to the host gradient array
+// after each of its tasks and come back before the next microbatch's; the update follows
+// the last microbatch's task while the pack is still resident.  The next visit's weights are
+// prefetched into another slot while the current one computes, as in the method's own order.
+void run_iteration_microbatch_major(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
+  const hmy_model_spec &s = h->model.spec;
+  const int M = h->M, E = h->model.elem_bytes();
+  const uint64_t T = uint64_t(h->b) * s.seq_len;
+  IterState it;
+  std::memset(&h->st, 0, sizeof(h->st));
+  h->sync_used = h->time_used = 0;
+  h->spans.clear();
+
+  if (!h->dry) {
+    uint64_t nt = 0;
+    for (uint64_t i = 0; i < uint64_t(M) * T; ++i) nt += mb->targets[i] >= 0;
+    h->st.n_targets = nt;
+    it.inv_ntgt = nt ? float(1.0 / double(nt)) : 0.f;
+  }
+  h2d(h, HMY_KIND_IDS, h->base + h->arena.res.ids, h->dry ? nullptr : mb->token_ids, uint64_t(M) * T * 4, h->s_in);
+  h2d(h, HMY_KIND_IDS, h->base + h->arena.res.targets, h->dry ? nullptr : mb->targets, uint64_t(M) * T * 4, h->s_in);
+  hipEvent_t ev_ids = rec(h, h->s_in);
+  KCHK(h, launch_fill_zero(h->base + h->arena.res.misc, 4096, h->s_comp));
+  const size_t t_first = trec(h, h->s_comp);
+
+  // the visit sequence of the whole iteration; slots rotate over it
+  const int nv = int(h->visits.size());
+  std::vector<Visit> seq;
+  seq.reserve(size_t(M) * nv);
+  for (int m = 0; m < M; ++m)
+    for (int vi = 0; vi < nv; ++vi) {
+      Visit v = h->visits[vi];
+      v.slot = int(seq.size() % kSlots);
+      seq.push_back(v);
+    }
+  std::vector<hipEvent_t> grads_home(nv, nullptr);   // per visit of a microbatch: its gradient sums have reached the host
+
+  auto load_weights = [&](const Visit &v) {
+    wait(h, h->s_in, it.slot_free[v.slot]);
+    h2d(h, HMY_KIND_W, h->base + h->arena.slot_off[v.slot], h->dry ? nullptr : (const char *)h->host.weights + v.poff * E,
+        uint64_t(E) * v.nparams, h->s_in);
+    return rec(h, h->s_in);
+  };
+  // what earlier microbatches added to this pack's gradient; enqueued only after the task that
+  // sent those sums out has been enqueued (two consecutive visits can be the same pack)
+  auto load_gradient_sums = [&](const Visit &v, int vi) {
+    wait(h, h->s_in, grads_home[vi]);
+    h2d(h, HMY_KIND_DW, pack_ptrs(h, v).dW, h->dry ? nullptr : h->host.grads + v.poff, v.nparams * 4, h->s_in);
+    return rec(h, h->s_in);
+  };
+
+  hipEvent_t ev_w = load_weights(seq[0]);
+  const int total = M * nv;
+  for (int g = 0; g < total; ++g) {
+    const Visit &v = seq[g];
+    const int m = g / nv, vi = g % nv;
+    const Visit *next = g + 1 < total ? &seq[g + 1] : nullptr;
+    const int next_m = (g + 1) / nv, next_vi = (g + 1) % nv;
+    h->tag = 1000 * vi + m;
+    comp_wait(h, ev_w);
+    if (g == 0) comp_wait(h, ev_ids);
+    if (v.bwd) {
+      if (v.last) {   // first backward task of this microbatch: its checkpoints have all been queued out
+        it.stash_all_out = rec(h, h->s_out);
+        it.stash_waited = false;
+      }
+      if (m == 0) KCHK(h, launch_fill_zero(pack_ptrs(h, v).dW, v.nparams * 4, h->s_comp));
+      issue_pack_input(h, it, v, m);
+    }
+    if (next) ev_w = load_weights(*next);
+    update_progress(h, it, hp, -1);   // the update of the previous visit, if it had one
+    if (v.bwd) backward_visit_microbatch(h, it, v, m);
+    else forward_visit_microbatch(h, it, v, m);
+    if (!v.bwd) {
+      it.slot_free[v.slot] = rec(h, h->s_comp);
+    } else if (m == M - 1) {
+      if (!next) it.compute_done = true;
+      update_begin(h, it, v, rec(h, h->s_comp), hp);
+    } else {
+      wait(h, h->s_out, rec(h, h->s_comp));
+      float *dst = h->dry ? nullptr : h->host.grads + v.poff;
+      if (h->fused_swap_out) d2h_kernel(h, HMY_KIND_DW, dst, pack_ptrs(h, v).dW, v.nparams * 4, h->s_out);
+      else d2h(h, HMY_KIND_DW, dst, pack_ptrs(h, v).dW, v.nparams * 4, h->s_out);
+      grads_home[vi] = it.slot_free[v.slot] = rec(h, h->s_out);
+    }
+    if (next && next->bwd && next_m > 0) ev_w = load_gradient_sums(*next, next_vi);
+  }
+  it.compute_done = true;
+  update_progress(h, it, hp, -1);
+  const size_t t_last = trec(h, h->s_comp);
+  span(h, t_first, t_last, 3);
+}
+
+void run_in_order(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
+  if (h->packs.order == HMY_ORDER_MICROBATCH_MAJOR) run_iteration_microbatch_major(h, mb, hp);
+  else run_iteration(h, mb, hp);
+}
+
 }  // namespace
 
 // ---- handle construction ---------------------------------------------------------
@@ -716,7 +817,7 @@ int hmy_count_swaps(const hmy_model_spec *spec, const hmy_schedule *sched, int32
   int rc = init_handle(&h, spec, sched, nullptr, n_micro, micro_batch);
   if (rc) return rc;
   hmy_adam hp{};
-  run_iteration(&h, nullptr, hp);
+  run_in_order(&h, nullptr, hp);
   *out = h.st;
   return h.err;
 }
@@ -818,7 +919,7 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
   HIPCHK(h, hipSetDevice(h->device));
   h->timing = out != nullptr;
   auto t0 = std::chrono::steady_clock::now();
-  run_iteration(h, mb, *adam);
+  run_in_order(h, mb, *adam);
   // always drain, even after an error, so no stream still touches caller memory
   hipStreamSynchronize(h->s_comp);
   hipStreamSynchronize(h->s_in);

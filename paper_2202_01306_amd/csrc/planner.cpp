@@ -143,7 +143,10 @@ int schedule_to_packs(const Model &m, const hmy_schedule *s, Packs *out) {
   if (!s) return fail(HMY_E_INVALID, "null schedule");
   if (s->n_bwd_packs < 1 || s->n_bwd_packs > m.R || s->n_fwd_packs < 0 || s->n_fwd_packs > m.R)
     return fail(HMY_E_BAD_SCHEDULE, "pack counts out of range");
+  if (s->order != HMY_ORDER_LAYER_PACK_MAJOR && s->order != HMY_ORDER_MICROBATCH_MAJOR)
+    return fail(HMY_E_BAD_SCHEDULE, "unknown task order %d", s->order);
   Packs p;
+  p.order = s->order;
   int pos = 0;
   for (int i = 0; i < s->n_bwd_packs; ++i) {
     int e = s->bwd_pack_end[i];
@@ -171,6 +174,7 @@ void packs_to_schedule(const Packs &p, hmy_schedule *out) {
   std::memset(out, 0, sizeof(*out));
   out->n_fwd_packs = int(p.fwd.size());
   out->n_bwd_packs = int(p.bwd.size());
+  out->order = p.order;
   for (size_t i = 0; i < p.fwd.size(); ++i) out->fwd_pack_end[i] = p.fwd[i].e;
   for (size_t i = 0; i < p.bwd.size(); ++i) out->bwd_pack_end[i] = p.bwd[i].e;
 }

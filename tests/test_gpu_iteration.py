@@ -42,7 +42,7 @@ def oracle_step(cfg, master, m, v, ids, tg, hp):
 
 
 def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps=(1,), seed=0, weight_scale=1.0,
-                    lr=1e-3):
+                    lr=1e-3, order=0):
     from paper_2202_01306_amd import binding as B
     from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     tol = 1e-4 if cfg["precision"] == "fp32" else 2e-2
@@ -55,9 +55,13 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
     tg = synth.gen_targets(cfg, ids, seed)
     st = TrainingState(cfg)
     st.load(params, m0, v0)
-    sched = B.make_schedule(*sched_ends) if sched_ends is not None else None
     if budget is None:
         budget = 1 << 40
+    sched = B.make_schedule(*sched_ends, order=order) if sched_ends is not None else None
+    if sched is None and order:
+        sched = B.hmy_plan(st.spec, budget, cfg["M"], cfg["b"])
+        sched.order = order
+    closed_form = osw.closed_form_microbatch_major if order else osw.closed_form
     master, m, v = f64(params), f64(m0), f64(v0)
     with Engine(st, budget, cfg["M"], cfg["b"], sched) as eng:
         P_F, P_B = eng.packs
@@ -70,7 +74,7 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
             stats = eng.step(lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, step=step)
             loss, grads, w2, m2, v2 = oracle_step(cfg, master, m, v, ids, tg, hp)
             # counters: bit-exact against the closed form
-            want = osw.closed_form(oracle_spec(cfg), P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
+            want = closed_form(oracle_spec(cfg), P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
             assert stats["h2d"] == want["h2d"] and stats["d2h"] == want["d2h"]
             assert stats["n_targets"] == om.count_targets(tg)
             assert abs(stats["loss"] - loss) <= tol * abs(loss), (stats["loss"], loss)
@@ -129,6 +133,60 @@ def test_tiny_fp32_degenerate_and_uneven_schedules(ends):
     say(f"tiny fp32, schedule {ends}")
     cfg = dict(synth.CONFIGS["tiny"], M=3)
     run_and_compare(cfg, sched_ends=ends, zero_state=False, steps=(3,), weight_scale=4.0)
+
+
+# ---- the comparison order (every microbatch through all packs on its own) over the same packs ----
+
+@pytest.mark.parametrize("ends", [([], [6]), ([2], [2, 6]), ([5], [1, 5, 6]), ([3, 4], [2, 4, 6]),
+                                  ([1, 2, 3, 4, 5], [1, 2, 3, 4, 5, 6])])
+def test_microbatch_major_tiny_fp32(ends):
+    say(f"tiny fp32, microbatch-major, schedule {ends}")
+    cfg = dict(synth.CONFIGS["tiny"], M=3)
+    run_and_compare(cfg, sched_ends=ends, zero_state=False, steps=(3, 4), weight_scale=4.0, order=1)
+
+
+def test_microbatch_major_planned_under_one_layer_budget_and_single_microbatch():
+    say("tiny fp32, microbatch-major, planned schedule; then M=1")
+    cfg = dict(synth.CONFIGS["tiny"])
+    run_and_compare(cfg, budget=one_layer_budget(cfg), order=1)
+    cfg = tiny_cfg(n_blocks=2, d_model=64, n_heads=2, d_ffn=128, seq_len=16, vocab=50, M=1, b=1)
+    run_and_compare(cfg, sched_ends=([1, 3], [1, 3, 4]), zero_state=False, steps=(2,), weight_scale=4.0, order=1)
+
+
+def test_microbatch_major_bf16_ragged():
+    say("bf16, microbatch-major, ragged vocabulary, 2 blocks")
+    cfg = tiny_cfg(n_blocks=2, d_model=128, n_heads=2, d_ffn=384, seq_len=96, vocab=1001, precision="bf16", M=3, b=2)
+    run_and_compare(cfg, sched_ends=([1, 3], [1, 2, 3, 4]), zero_state=False, steps=(5,), weight_scale=3.0, order=1)
+
+
+def test_both_orders_give_the_same_gradients_on_the_gpu():
+    """Same packs, same kernels, per-tensor sums in the same microbatch order: the two task
+    orders must agree far more closely than either agrees with the fp64 definition."""
+    from paper_2202_01306_amd import binding as B
+    from paper_2202_01306_amd.runner import Engine, TrainingState
+    say("fp32: layer-pack-major against microbatch-major")
+    cfg = tiny_cfg(n_blocks=3, d_model=256, n_heads=4, d_ffn=1024, seq_len=128, vocab=2000, precision="fp32", M=4, b=2)
+    params = synth.gen_params(cfg, 3, bench_init=False)
+    m0, v0 = synth.gen_adam_state(cfg, 3, zero=False)
+    ids = synth.gen_tokens(cfg, 3)
+    tg = synth.gen_targets(cfg, ids, 3)
+    got = []
+    for order in (0, 1):
+        st = TrainingState(cfg)
+        st.load(params, m0, v0)
+        with Engine(st, 1 << 40, cfg["M"], cfg["b"], B.make_schedule([1, 4], [1, 3, 4, 5], order=order)) as eng:
+            eng.set_batch(ids, tg)
+            stats = eng.step(lr=1e-3, step=7)
+        got.append((stats, st.named("grads"), st.named("weights"), st.named("m"), st.named("v")))
+        st.close()
+    (s0, g0, w0, a0, b0), (s1, g1, w1, a1, b1) = got
+    assert abs(s0["loss"] - s1["loss"]) < 1e-6 * abs(s0["loss"])
+    assert s1["h2d"]["W"] == cfg["M"] * s0["h2d"]["W"]
+    for k in g0:
+        # partial sums added with atomics arrive in any order, so not bit-identical, but fp32-close
+        assert max_rel_err(g1[k], g0[k]) < 1e-5, k
+        assert max_rel_err(w1[k] - params[k], w0[k] - params[k]) < 1e-3, k
+        assert max_rel_err(a1[k], a0[k]) < 1e-5 and max_rel_err(b1[k], b0[k]) < 1e-5, k
 
 
 def test_single_microbatch_single_sequence():
@@ -231,15 +289,18 @@ def test_errors_from_the_engine():
 
 
 @pytest.mark.timeout(600)
-def test_full_size_gpt2_medium_properties():
-    """The benchmark workload at full size, in the configuration bench.py times.
+@pytest.mark.parametrize("order", [0, 1])
+def test_full_size_gpt2_medium_properties(order):
+    """The benchmark workload at full size, in the configuration bench.py times
+    (order 0), and in the comparison order over the same packs (order 1).
     The fp64 oracle cannot run it, so: counters equal the closed form exactly;
     the loss at N(0, 0.02) init is ln(vocab) + d*0.02^2/2 within 1% (logits are
     Gaussian with variance d*0.02^2 since the final LayerNorm output has unit
     variance; E[logsumexp] of V such values is ln V + variance/2); step-1 Adam from zero
     state moved every master weight by lr*g/(|g|+eps), recomputed from the
     returned gradients."""
-    say("full-size gpt2-medium properties")
+    say(f"full-size gpt2-medium properties, task order {order}")
+    from paper_2202_01306_amd import binding as B
     from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     cfg = dict(synth.CONFIGS["gpt2m"])
     st = TrainingState(cfg)
@@ -248,12 +309,17 @@ def test_full_size_gpt2_medium_properties():
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
     lr, eps = 1e-4, 1e-8
-    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], search=BENCH_PACK_SEARCH) as eng:
+    sched = None
+    if order:
+        sched = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=BENCH_PACK_SEARCH)
+        sched.order = order
+    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], sched, search=BENCH_PACK_SEARCH) as eng:
         eng.set_batch(ids, tg)
         stats = eng.step(lr=lr, eps=eps, step=1)
         P_F, P_B = eng.packs
         assert eng.arena["total"] <= cfg["budget"]
-    want = osw.closed_form(oracle_spec(cfg), P_F, P_B, cfg["M"], cfg["b"], "bf16")
+    closed_form = osw.closed_form_microbatch_major if order else osw.closed_form
+    want = closed_form(oracle_spec(cfg), P_F, P_B, cfg["M"], cfg["b"], "bf16")
     assert stats["h2d"] == want["h2d"] and stats["d2h"] == want["d2h"]
     expect_loss = math.log(cfg["vocab"]) + 0.5 * cfg["d_model"] * 0.02 ** 2
     assert abs(stats["loss"] - expect_loss) < 0.01 * expect_loss, (stats["loss"], expect_loss)

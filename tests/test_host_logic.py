@@ -195,6 +195,11 @@ def _cmp_counters(cfg, P_F, P_B):
     want = osw.closed_form(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
     assert got["h2d"] == want["h2d"] and got["d2h"] == want["d2h"]
     assert want == osw.ledger(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
+    # the comparison order over the same packs
+    sched.order = B.HMY_ORDER_MICROBATCH_MAJOR
+    got_mm = B.hmy_count_swaps(spec, sched, cfg["M"], cfg["b"])
+    want_mm = osw.closed_form_microbatch_major(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
+    assert got_mm["h2d"] == want_mm["h2d"] and got_mm["d2h"] == want_mm["d2h"]
     return got
 
 
@@ -210,6 +215,11 @@ def test_swap_counters_equal_closed_form_on_planned_configs(name):
     n = B.hmy_model_size(B.make_spec(cfg))[1]
     assert got["h2d"]["W"] < 2 * E * n
     assert got["d2h"]["W"] == E * n and got["h2d"]["dW"] == 0 and got["h2d"]["XY"] == got["d2h"]["XY"] == 0
+    # ... and what the comparison order pays instead (Section 3: M times the weights; appendix: gradients M-1 / M times)
+    sched = B.make_schedule([e for _, e in P_F], [e for _, e in P_B], order=B.HMY_ORDER_MICROBATCH_MAJOR)
+    mm = B.hmy_count_swaps(B.make_spec(cfg), sched, cfg["M"], cfg["b"])
+    assert mm["h2d"]["W"] == cfg["M"] * got["h2d"]["W"]
+    assert mm["h2d"]["dW"] == (cfg["M"] - 1) * 4 * n and mm["d2h"]["dW"] == cfg["M"] * 4 * n
 
 
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
@@ -245,6 +255,9 @@ def test_error_paths_return_codes_not_crashes():
     assert e.value.code == B.HMY_E_BAD_SCHEDULE
     with pytest.raises(B.HmyError) as e:
         B.hmy_count_swaps(spec, B.make_schedule([1], [2, 4]), 2, 2)
+    assert e.value.code == B.HMY_E_BAD_SCHEDULE
+    with pytest.raises(B.HmyError) as e:                # a task order that does not exist
+        B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4], order=2), 2, 2)
     assert e.value.code == B.HMY_E_BAD_SCHEDULE
     assert B.lib.hmy_strerror(B.HMY_E_HIP) == b"HIP runtime error"
     assert B.lib.hmy_model_size(None, None, None) == B.HMY_E_INVALID
