@@ -53,8 +53,13 @@ def _pcount(spec, a, e):
     return sum(om.layer_param_count(spec, l) for l in range(a, e))
 
 
-def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
-    """Layer-pack-major volumes.  Returns {'h2d': {kind: bytes}, 'd2h': {...}}."""
+def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False):
+    """Layer-pack-major volumes.  Returns {'h2d': {kind: bytes}, 'd2h': {...}}.
+
+    update_on_host: the Weight Update task runs on the CPU (Section 4.4, first
+    paragraph: the Runtime supports offloading it).  The optimizer state and the
+    updated weights then never cross the link: the host reads the gradient that the
+    backward task exported and writes W and K where they already live."""
     osch.check_packs(spec, P_F, P_B)
     w_c, k_B, g_B = bytes_per_param(precision)
     P_all = _pcount(spec, 0, spec.n_layers)
@@ -72,10 +77,13 @@ def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
     h2d["sX"] = M * a * n_ckpt
     d2h["sX"] = M * a * n_ckpt
     h2d["ids"] = 2 * M * T * 4
+    if update_on_host:
+        h2d["K"] = d2h["K"] = d2h["W"] = 0
     return {"h2d": h2d, "d2h": d2h}
 
 
-def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
+def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str,
+                                 update_on_host: bool = False):
     """Same packs, same one-pack-at-a-time residency, but every microbatch runs
     through all packs before the next one starts (the per-GPU-swap order of
     Section 3, "Intuitive Example").  Weights come in M times.  A pack's gradient
@@ -87,7 +95,7 @@ def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precis
     by the update that follows it and leaves once, as the exported gradient -- so
     M - 1 times in and M times out, against the paper's 2m + 2 for a system that
     also swaps around a separate update phase."""
-    out = closed_form(spec, P_F, P_B, M, b, precision)
+    out = closed_form(spec, P_F, P_B, M, b, precision, update_on_host)
     w_c, k_B, g_B = bytes_per_param(precision)
     P_all = _pcount(spec, 0, spec.n_layers)
     out["h2d"]["W"] *= M
@@ -96,7 +104,7 @@ def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precis
     return out
 
 
-def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
+def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False):
     """Add up what every task of the ordered list swaps."""
     w_c, k_B, g_B = bytes_per_param(precision)
     T = b * spec.seq_len
@@ -117,6 +125,8 @@ def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
             if t.stash_in_layer is not None:
                 for _mb in range(M):
                     h2d["sX"] += act
+        elif update_on_host:
+            d2h["dW"] += g_B * npar       # all the CPU needs from the device
         else:
             h2d["K"] += k_B * npar
             d2h["K"] += k_B * npar
@@ -125,7 +135,7 @@ def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
     return {"h2d": h2d, "d2h": d2h}
 
 
-def ledger_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str):
+def ledger_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False):
     """Add up what every task of the microbatch-major list swaps."""
     w_c, k_B, g_B = bytes_per_param(precision)
     T = b * spec.seq_len
@@ -149,6 +159,8 @@ def ledger_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: 
             has_gradient.add(t.pack)
             if t.mb != M - 1:                 # else the update that follows takes it from the device
                 d2h["dW"] += g_B * npar
+        elif update_on_host:
+            d2h["dW"] += g_B * npar
         else:
             h2d["K"] += k_B * npar
             d2h["K"] += k_B * npar

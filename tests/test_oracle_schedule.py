@@ -197,6 +197,31 @@ def test_microbatch_major_volumes_closed_form_ledger_machine(precision):
                 assert cf["h2d"]["dW"] + cf["d2h"]["dW"] == osw.paper_dW_volume_per_gpu_swap_dp(M, 1, dW) - 3 * dW
 
 
+def test_update_on_host_moves_only_the_gradient():
+    """Weight Update on the CPU (Section 4.4): K and the updated W stay where they live,
+    so the link carries W in (two passes), the checkpoints, and dW out once; everything
+    else equals the on-device count.  Closed form = ledger, both orders."""
+    spec = om.Spec(4, 8, 2, 24, 4, 16)
+    R = spec.n_layers
+    for precision in ("fp32", "bf16"):
+        w_c, k_B, g_B = osw.bytes_per_param(precision)
+        P = sum(om.layer_param_count(spec, l) for l in range(R))
+        for M, b in ((1, 1), (3, 2)):
+            for P_B in list(all_packings(R))[::3]:
+                last_start = P_B[-1][0]
+                P_F = [(0, last_start)] if last_start else []
+                dev = osw.closed_form(spec, P_F, P_B, M, b, precision)
+                host = osw.closed_form(spec, P_F, P_B, M, b, precision, update_on_host=True)
+                assert host == osw.ledger(spec, P_F, P_B, M, b, precision, update_on_host=True)
+                assert host["h2d"]["K"] == host["d2h"]["K"] == host["d2h"]["W"] == 0
+                assert host["d2h"]["dW"] == g_B * P
+                saved = sum(dev[d][k] - host[d][k] for d in ("h2d", "d2h") for k in osw.KINDS)
+                assert saved == (2 * k_B + w_c) * P       # K both ways and W out
+                mm = osw.closed_form_microbatch_major(spec, P_F, P_B, M, b, precision, update_on_host=True)
+                assert mm == osw.ledger_microbatch_major(spec, P_F, P_B, M, b, precision, update_on_host=True)
+                assert mm["h2d"]["K"] == mm["d2h"]["K"] == mm["d2h"]["W"] == 0 and mm["d2h"]["dW"] == M * g_B * P
+
+
 def test_weight_volume_reduces_to_3W_when_last_pack_is_counted_twice():
     spec = om.Spec(3, 8, 2, 16, 4, 16)
     P_B = [(0, 2), (2, 4), (4, 5)]
