@@ -94,6 +94,11 @@ def main() -> int:
     ap.add_argument("--reference-kernels", action="store_true", help="time the plain (non-MFMA) kernels")
     ap.add_argument("--order", choices=("layer-pack-major", "microbatch-major"), default="layer-pack-major",
                     help="microbatch-major: the order the paper compares against, over the same packs (ablation)")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the two extra short runs (update on the host; microbatch-major order) reported under 'variants'")
+    ap.add_argument("--update-site", choices=("device", "host"), default="device",
+                    help="host: the Weight Update task runs on CPU threads (the paper's optimizer offload); "
+                         "optimizer state then never crosses the link")
     a = ap.parse_args()
     if a.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {a.gpus} is not supported",
@@ -123,9 +128,10 @@ def main() -> int:
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
     sched = None
-    if a.order == "microbatch-major":
+    if a.order == "microbatch-major" or a.update_site == "host":
         sched = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search)
-        sched.order = B.HMY_ORDER_MICROBATCH_MAJOR
+        sched.order = B.HMY_ORDER_MICROBATCH_MAJOR if a.order == "microbatch-major" else B.HMY_ORDER_LAYER_PACK_MAJOR
+        sched.update_site = B.HMY_UPDATE_ON_HOST if a.update_site == "host" else B.HMY_UPDATE_ON_DEVICE
     with Engine(st, cfg["budget"], cfg["M"], cfg["b"], sched, search=a.pack_search) as eng:
         eng.set_batch(ids, tg)
         step = 1
@@ -143,6 +149,27 @@ def main() -> int:
         prof = eng.step(step=step, want_stats=True)
         B.hmy_set_profiling(eng.handle, False)
         packs, arena = eng.packs, eng.arena
+
+    # Two ablations over the SAME packs, outside the timed region of the headline number:
+    # the paper's optimizer offload (Weight Update on CPU threads) and the order it compares against.
+    variants = {}
+    if not a.no_variants and a.order == "layer-pack-major" and a.update_site == "device" and not a.reference_kernels:
+        for name, order, site, n in (("update_on_host", B.HMY_ORDER_LAYER_PACK_MAJOR, B.HMY_UPDATE_ON_HOST, max(2, a.steps)),
+                                     ("microbatch_major", B.HMY_ORDER_MICROBATCH_MAJOR, B.HMY_UPDATE_ON_DEVICE, 2)):
+            vs = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search)
+            vs.order, vs.update_site = order, site
+            with Engine(st, cfg["budget"], cfg["M"], cfg["b"], vs) as eng:
+                eng.set_batch(ids, tg)
+                eng.step(step=step, want_stats=False)
+                step += 1
+                t0 = time.perf_counter()
+                for _ in range(n):
+                    vstats = eng.step(step=step, want_stats=True)
+                    step += 1
+                vms = (time.perf_counter() - t0) / n * 1e3
+            variants[name] = {"value": cfg["M"] * cfg["b"] / (vms * 1e-3), "unit": "samples/s", "ms_per_step": vms, "steps": n,
+                              "h2d_GB_per_iter": sum(vstats["h2d"].values()) / 1e9,
+                              "d2h_GB_per_iter": sum(vstats["d2h"].values()) / 1e9}
 
     ms = dt / a.steps * 1e3
     samples = cfg["M"] * cfg["b"]
@@ -164,7 +191,7 @@ def main() -> int:
                                f"ffn={cfg['d_ffn']} seq={cfg['seq_len']} vocab={cfg['vocab']}, "
                                f"{cfg['M']} microbatches x {cfg['b']} sequences",
                    "hbm_budget_bytes": cfg["budget"], "arena_bytes": arena["total"],
-                   "order": a.order, "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
+                   "order": a.order, "update_site": a.update_site, "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
                    "kernels": "reference" if a.reference_kernels else "mfma"},
         "tflops": total_flops / (ms * 1e-3) / 1e12,
         "swap": {"h2d_GB_per_iter": h2d / 1e9, "d2h_GB_per_iter": d2h / 1e9,
@@ -188,6 +215,8 @@ def main() -> int:
                                              if prof["gemm_calls"][i] else None for i in range(4)]},
         "loss": stats["loss"],
     }
+    if variants:
+        out["variants"] = variants
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

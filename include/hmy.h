@@ -95,17 +95,28 @@ typedef struct hmy_budget {
 #define HMY_ORDER_LAYER_PACK_MAJOR 0
 #define HMY_ORDER_MICROBATCH_MAJOR 1
 
+/* Where the Weight Update task of a pack runs (Section 4.4: "all tasks run on GPUs,
+ * but ... the update task [can be] offloaded to the CPU").  ON_DEVICE: optimizer state
+ * comes in, the fused Adam kernel runs on the GPU, state, weights and gradient go out.
+ * ON_HOST: only the pack's gradient goes out; a pool of CPU threads inside the library
+ * applies the same Adam arithmetic to the caller's pinned arrays in place while the
+ * GPU goes on with the next pack, so optimizer state and updated weights never cross
+ * the link.  hmy_iteration returns once those threads are done too. */
+#define HMY_UPDATE_ON_DEVICE 0
+#define HMY_UPDATE_ON_HOST 1
+
 /* Configuration (Section 4.3.1): forward and backward layer packs as exclusive
  * end indices over the R layers.  Backward packs cover 0..R; forward packs cover
  * exactly the layers before the last backward pack (Algorithm 2, lines 1-2).
  * Microbatch sizes U_F = U_B = micro_batch are given by the caller.
- * order: HMY_ORDER_*; hmy_plan returns LAYER_PACK_MAJOR, any other value than the
- * two above is HMY_E_BAD_SCHEDULE. */
+ * order: HMY_ORDER_*, update_site: HMY_UPDATE_*; hmy_plan returns LAYER_PACK_MAJOR
+ * and ON_DEVICE, any value other than those defined above is HMY_E_BAD_SCHEDULE. */
 typedef struct hmy_schedule {
   int32_t n_fwd_packs, n_bwd_packs;
   int32_t fwd_pack_end[HMY_MAX_LAYERS];
   int32_t bwd_pack_end[HMY_MAX_LAYERS];
   int32_t order;
+  int32_t update_site;
 } hmy_schedule;
 
 /* One minibatch as a list of n_micro microbatches of micro_batch sequences. */
@@ -311,6 +322,13 @@ int hmy_k_xent(int32_t prec, const float *logits, const int32_t *targets, double
  * fp32: w (fp32, in w_out) is the master; master must be NULL. */
 int hmy_k_adam(int32_t prec, const float *grad, float *master, float *m, float *v, void *w_out,
                uint64_t n, const hmy_adam *hp, void *stream);
+
+/* ---- the host-side update on its own (all pointers HOST, no GPU needed) ----
+ * What HMY_UPDATE_ON_HOST applies to each chunk of a pack (Section 4.4, update task on
+ * the CPU): the arithmetic of hmy_k_adam, in place, over n elements, on `threads` CPU
+ * threads (0 = as many as the engine would use).  Argument rules as for hmy_k_adam. */
+int hmy_host_adam(int32_t prec, const float *grad, float *master, float *m, float *v, void *weights,
+                  uint64_t n, const hmy_adam *hp, int32_t threads);
 
 #ifdef __cplusplus
 }

@@ -19,6 +19,7 @@ HMY_NKINDS = 7
 KIND_NAMES = ("W", "dW", "K", "sX", "XY", "dXdY", "ids")
 HMY_PREC_FP32, HMY_PREC_BF16 = 0, 1
 HMY_ORDER_LAYER_PACK_MAJOR, HMY_ORDER_MICROBATCH_MAJOR = 0, 1
+HMY_UPDATE_ON_DEVICE, HMY_UPDATE_ON_HOST = 0, 1
 (HMY_OK, HMY_E_INVALID, HMY_E_BUDGET_TOO_SMALL, HMY_E_BAD_SCHEDULE, HMY_E_HIP,
  HMY_E_NOT_BOUND, HMY_E_NO_DEVICE) = (0, -1, -2, -3, -4, -5, -6)
 
@@ -52,7 +53,7 @@ def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0) -> hmy_bu
 class hmy_schedule(C.Structure):
     _fields_ = [("n_fwd_packs", C.c_int32), ("n_bwd_packs", C.c_int32),
                 ("fwd_pack_end", C.c_int32 * HMY_MAX_LAYERS), ("bwd_pack_end", C.c_int32 * HMY_MAX_LAYERS),
-                ("order", C.c_int32)]
+                ("order", C.c_int32), ("update_site", C.c_int32)]
 
 
 class hmy_minibatch(C.Structure):
@@ -105,7 +106,7 @@ EXPORTS = [
     "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state",
     "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
     "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
-    "hmy_k_gemm", "hmy_k_attn_fwd", "hmy_k_attn_bwd", "hmy_k_xent", "hmy_k_adam",
+    "hmy_k_gemm", "hmy_k_attn_fwd", "hmy_k_attn_bwd", "hmy_k_xent", "hmy_k_adam", "hmy_host_adam",
 ]
 
 lib.hmy_strerror.restype = C.c_char_p
@@ -126,9 +127,10 @@ def make_spec(cfg) -> hmy_model_spec:
                           cfg["vocab"], int(cfg["causal"]), prec, float(cfg.get("ln_eps", 1e-5)))
 
 
-def make_schedule(fwd_ends, bwd_ends, order=0) -> hmy_schedule:
+def make_schedule(fwd_ends, bwd_ends, order=0, update_site=0) -> hmy_schedule:
     s = hmy_schedule()
     s.order = order
+    s.update_site = update_site
     s.n_fwd_packs, s.n_bwd_packs = len(fwd_ends), len(bwd_ends)
     for i, e in enumerate(fwd_ends):
         s.fwd_pack_end[i] = e
@@ -324,6 +326,14 @@ def hmy_k_attn_bwd(prec, qkv, o, d_o, lse, delta, dqkv, b, s, H, dh, causal, str
 def hmy_k_xent(prec, logits, targets, loss_acc, dlogits, T, V, ldl, inv_ntgt, stream=None):
     _check(lib.hmy_k_xent(prec, _p(logits), _p(targets), _p(loss_acc), _p(dlogits), T, V, C.c_int64(ldl),
                           C.c_float(inv_ntgt), _p(stream)))
+
+
+def hmy_host_adam(prec, grad_ptr, master_ptr, m_ptr, v_ptr, weights_ptr, n, lr, beta1, beta2, eps, step, threads=0):
+    """Host pointers (ints); in place."""
+    hp = hmy_adam(lr, beta1, beta2, eps, step)
+    vp = lambda x: C.c_void_p(x) if x else None
+    _check(lib.hmy_host_adam(prec, vp(grad_ptr), vp(master_ptr), vp(m_ptr), vp(v_ptr), vp(weights_ptr), C.c_uint64(n),
+                             C.byref(hp), int(threads)))
 
 
 def hmy_k_adam(prec, grad, master, m, v, w_out, n, lr, beta1, beta2, eps, step, stream=None):

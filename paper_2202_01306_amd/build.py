@@ -12,14 +12,26 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhmy.so")
 
-SOURCES = ["model.cpp", "planner.cpp", "api.cpp", "engine.hip", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "gemm_tr.hip", "gemm_dma.hip"]
+SOURCES = ["model.cpp", "planner.cpp", "api.cpp", "engine.hip", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "gemm_tr.hip", "gemm_dma.hip", "host_update.cpp"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-munsafe-fp-atomics", "-Wall", "-Wno-unused-function", "-Wno-unused-value",
+    "-munsafe-fp-atomics", "-fno-math-errno", "-pthread", "-Wall", "-Wno-unused-function", "-Wno-unused-value",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
+
+
+# plain host C++ (no device pass): the CPU-side update uses x86 target attributes
+HOST_ONLY = {"host_update.cpp"}
+HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-fno-math-errno", "-pthread", "-Wall",
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
+def _hostcxx() -> str:
+    # hipcc would treat a .cpp as HIP and run a device pass over it
+    cand = os.environ.get("HOSTCXX", "/opt/rocm/lib/llvm/bin/clang++")
+    return cand if os.path.exists(cand) else "g++"
 
 
 def _hipcc() -> str:
@@ -28,7 +40,10 @@ def _hipcc() -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    if src in HOST_ONLY:
+        cmd = [_hostcxx(), *HOST_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    else:
+        cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                      if "packed-fp32-ops" not in l)      # the host pass does not know the feature: harmless
@@ -43,7 +58,7 @@ def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)

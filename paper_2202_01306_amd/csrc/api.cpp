@@ -192,4 +192,18 @@ int hmy_k_adam(int32_t prec, const float *grad, float *master, float *m, float *
   return launch_adam(prec, grad, master, m, v, w_out, n, *hp, stream);
 }
 
+int hmy_host_adam(int32_t prec, const float *grad, float *master, float *m, float *v, void *weights, uint64_t n,
+                  const hmy_adam *hp, int32_t threads) {
+  if (!grad || !m || !v || !weights || !hp) return fail(HMY_E_INVALID, "null argument");
+  if (prec != HMY_PREC_FP32 && prec != HMY_PREC_BF16) return fail(HMY_E_INVALID, "unknown precision %d", prec);
+  if (prec == HMY_PREC_BF16 && !master) return fail(HMY_E_INVALID, "adam(bf16): master required");
+  if (prec == HMY_PREC_FP32 && master) return fail(HMY_E_INVALID, "adam(fp32): master must be NULL");
+  if (hp->step < 1) return fail(HMY_E_INVALID, "adam: step is 1-based");
+  if (threads < 0 || threads > 256) return fail(HMY_E_INVALID, "threads out of range");
+  if (!n) return HMY_OK;
+  HostUpdater up(threads ? threads : default_host_threads(), nullptr, nullptr, nullptr);
+  up.submit(make_host_adam_job(nullptr, grad, master, m, v, weights, n, *hp));
+  return up.drain();
+}
+
 }  // extern "C"

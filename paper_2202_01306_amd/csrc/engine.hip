@@ -21,7 +21,9 @@
 #include <chrono>
 #include <cstdio>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
+#include <thread>
 
 #include "hmy_internal.h"
 
@@ -74,6 +76,7 @@ struct hmy_handle {
   // false: results go to the ring / slot and leave by hipMemcpyAsync on s_out
   bool fused_swap_out = true;
   bool k_zero_copy = false;   // the update kernel reads optimizer state straight from pinned host memory
+  HostUpdater *updater = nullptr;   // Weight Update on the CPU (packs.update_site == HMY_UPDATE_ON_HOST)
 };
 
 #define HIPCHK(h, call)                                                                      \
@@ -578,6 +581,40 @@ void update_begin(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_d
   it.upd.n_chunks = int((v.nparams + c - 1) / c);
 }
 
+// Weight Update on the host: the pack's gradient leaves for the pinned gradient array chunk by
+// chunk; each chunk's event is handed to the CPU threads, which apply Adam to the pinned state
+// in place as soon as it has arrived.  Nothing else of the pack crosses the link.
+void host_update_begin(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_done, const hmy_adam &hp) {
+  const uint64_t c = h->arena.res.k_chunk_params;
+  const int E = h->model.elem_bytes();
+  const bool mixed = h->model.spec.precision == HMY_PREC_BF16;
+  const PackPtrs pp = pack_ptrs(h, v);
+  wait(h, h->s_out, bwd_done);
+  for (uint64_t lo = 0; lo < v.nparams; lo += c) {
+    const uint64_t n = std::min<uint64_t>(c, v.nparams - lo), g0 = v.poff + lo;
+    float *dst = h->dry ? nullptr : h->host.grads + g0;
+    if (h->fused_swap_out) d2h_kernel(h, HMY_KIND_DW, dst, pp.dW + lo, n * 4, h->s_out);
+    else d2h(h, HMY_KIND_DW, dst, pp.dW + lo, n * 4, h->s_out);
+    hipEvent_t arrived = rec(h, h->s_out);
+    if (h->dry || h->err) continue;
+    h->updater->submit(make_host_adam_job(arrived, h->host.grads + g0, mixed ? h->host.master + g0 : nullptr,
+                                          h->host.adam_m + g0, h->host.adam_v + g0, (char *)h->host.weights + g0 * E, n,
+                                          hp));
+  }
+  it.slot_free[v.slot] = rec(h, h->s_out);
+}
+int updater_thread_init(void *arg, void *) {
+  return hipSetDevice(static_cast<hmy_handle *>(arg)->device) == hipSuccess ? HMY_OK : HMY_E_HIP;
+}
+int updater_wait(void *, void *ready) {
+  return hipEventSynchronize(static_cast<hipEvent_t>(ready)) == hipSuccess ? HMY_OK : HMY_E_HIP;
+}
+// the update that follows a pack's (last) backward task, wherever the schedule places it
+void pack_update_begin(hmy_handle *h, IterState &it, const Visit &v, hipEvent_t bwd_done, const hmy_adam &hp) {
+  if (h->packs.update_site == HMY_UPDATE_ON_HOST) host_update_begin(h, it, v, bwd_done, hp);
+  else update_begin(h, it, v, bwd_done, hp);
+}
+
 void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
   const hmy_model_spec &s = h->model.spec;
   const int M = h->M, E = h->model.elem_bytes();
@@ -653,7 +690,7 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
       it.slot_free[v.slot] = rec(h, h->s_comp);
     } else {
       if (!next) it.compute_done = true;   // nothing else will be enqueued on the compute stream
-      update_begin(h, it, v, rec(h, h->s_comp), hp);
+      pack_update_begin(h, it, v, rec(h, h->s_comp), hp);
     }
   }
   it.compute_done = true;
@@ -742,7 +779,7 @@ void run_iteration_microbatch_major(hmy_handle *h, const hmy_minibatch *mb, cons
       it.slot_free[v.slot] = rec(h, h->s_comp);
     } else if (m == M - 1) {
       if (!next) it.compute_done = true;
-      update_begin(h, it, v, rec(h, h->s_comp), hp);
+      pack_update_begin(h, it, v, rec(h, h->s_comp), hp);
     } else {
       wait(h, h->s_out, rec(h, h->s_comp));
       float *dst = h->dry ? nullptr : h->host.grads + v.poff;
@@ -866,6 +903,9 @@ int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_m
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_kin, hipStreamNonBlocking));
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_upd, hipStreamNonBlocking));
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_out, hipStreamNonBlocking));
+  if (h->packs.update_site == HMY_UPDATE_ON_HOST && !h->err) {
+    h->updater = new HostUpdater(default_host_threads(), updater_thread_init, updater_wait, h);
+  }
   const uint64_t stash_bytes = uint64_t(h->ckpt_layers.size()) * h->M * h->arena.res.x_bytes;
   if (stash_bytes) HIPCHK(h, hipHostMalloc(reinterpret_cast<void **>(&h->stash_host), stash_bytes, hipHostMallocDefault));
   if (h->err) {
@@ -927,6 +967,10 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
   hipStreamSynchronize(h->s_upd);
   hipError_t e_last = hipStreamSynchronize(h->s_out);
   if (h->err == HMY_OK && e_last != hipSuccess) h->err = fail(HMY_E_HIP, "stream sync: %s", hipGetErrorString(e_last));
+  if (h->updater) {   // the CPU threads may still be applying the last pack's update
+    const int rc = h->updater->drain();
+    if (h->err == HMY_OK && rc != HMY_OK) h->err = fail(rc, "the update on the host failed");
+  }
   auto t1 = std::chrono::steady_clock::now();
   if (h->err) return h->err;
   double loss = 0.0;
@@ -971,6 +1015,8 @@ int hmy_set_profiling(hmy_handle *h, int32_t on) {
 
 int hmy_destroy(hmy_handle *h) {
   if (!h) return HMY_OK;
+  delete h->updater;   // joins its threads
+  h->updater = nullptr;
   if (!h->dry && h->device >= 0) {
     hipSetDevice(h->device);
     if (h->s_comp) { hipStreamSynchronize(h->s_comp); hipStreamDestroy(h->s_comp); }

@@ -81,7 +81,7 @@ Reserved reserved_layout(const Model &m, int n_micro, int micro_batch);
 void layer_profile(const Model &m, int n_micro, int micro_batch, std::vector<hmy_layer_profile> *out);
 
 struct Pack { int a, e; };
-struct Packs { std::vector<Pack> fwd, bwd; int order = HMY_ORDER_LAYER_PACK_MAJOR; };
+struct Packs { std::vector<Pack> fwd, bwd; int order = HMY_ORDER_LAYER_PACK_MAJOR; int update_site = HMY_UPDATE_ON_DEVICE; };
 
 int schedule_to_packs(const Model &m, const hmy_schedule *s, Packs *out);
 void packs_to_schedule(const Packs &p, hmy_schedule *out);
@@ -138,6 +138,40 @@ int launch_adam_out(int prec, const float *grad, const float *in_master, const f
                     float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
                     const hmy_adam &hp, bool alone, stream_t st);
 int launch_fill_zero(void *p, uint64_t bytes, stream_t st);
+
+// ---- Weight Update on the host CPU (host_update.cpp) ----
+// One chunk of one pack: all pointers are host addresses of the same n elements.
+struct HostAdamJob {
+  void *ready;          // handed to the wait hook: the chunk's gradient has arrived in `grad` (NULL: it is there already)
+  const float *grad;
+  float *master;        // fp32 master (bf16 models) or NULL: then `weights` is the fp32 weight itself
+  float *m, *v;
+  void *weights;        // bf16 (with master) or fp32
+  uint64_t n;
+  float lr, b1, b2, eps, inv_bc1, inv_bc2;
+};
+HostAdamJob make_host_adam_job(void *ready, const float *grad, float *master, float *m, float *v, void *weights,
+                               uint64_t n, const hmy_adam &hp);
+int default_host_threads();   // min(16, hardware threads), or HMY_HOST_THREADS
+// Jobs run in submission order on a dispatcher thread + worker pool; drain() returns once
+// every submitted job has been applied (HMY_OK or the first error).
+class HostUpdater {
+ public:
+  // hooks run on the dispatcher thread: thread_init(arg, NULL) once at its start,
+  // wait_ready(arg, job.ready) before each job; both return HMY_OK or an error code
+  typedef int (*Hook)(void *arg, void *ready);
+  HostUpdater(int nthreads, Hook thread_init, Hook wait_ready, void *hook_arg);
+  ~HostUpdater();
+  HostUpdater(const HostUpdater &) = delete;
+  HostUpdater &operator=(const HostUpdater &) = delete;
+  void submit(const HostAdamJob &job);
+  int drain();
+  int threads() const;
+
+ private:
+  struct Impl;
+  Impl *p;
+};
 // grid_cap bounds the workgroups: a copy to pinned host memory needs few of them to fill
 // the link and must not crowd the compute units
 int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st, int grid_cap = 2048);

@@ -42,7 +42,7 @@ def oracle_step(cfg, master, m, v, ids, tg, hp):
 
 
 def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps=(1,), seed=0, weight_scale=1.0,
-                    lr=1e-3, order=0):
+                    lr=1e-3, order=0, update_site=0):
     from paper_2202_01306_amd import binding as B
     from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     tol = 1e-4 if cfg["precision"] == "fp32" else 2e-2
@@ -57,11 +57,12 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
     st.load(params, m0, v0)
     if budget is None:
         budget = 1 << 40
-    sched = B.make_schedule(*sched_ends, order=order) if sched_ends is not None else None
-    if sched is None and order:
+    sched = B.make_schedule(*sched_ends, order=order, update_site=update_site) if sched_ends is not None else None
+    if sched is None and (order or update_site):
         sched = B.hmy_plan(st.spec, budget, cfg["M"], cfg["b"])
-        sched.order = order
-    closed_form = osw.closed_form_microbatch_major if order else osw.closed_form
+        sched.order, sched.update_site = order, update_site
+    cf = osw.closed_form_microbatch_major if order else osw.closed_form
+    closed_form = lambda *a: cf(*a, update_on_host=bool(update_site))
     master, m, v = f64(params), f64(m0), f64(v0)
     with Engine(st, budget, cfg["M"], cfg["b"], sched) as eng:
         P_F, P_B = eng.packs
@@ -187,6 +188,26 @@ def test_both_orders_give_the_same_gradients_on_the_gpu():
         assert max_rel_err(g1[k], g0[k]) < 1e-5, k
         assert max_rel_err(w1[k] - params[k], w0[k] - params[k]) < 1e-3, k
         assert max_rel_err(a1[k], a0[k]) < 1e-5 and max_rel_err(b1[k], b0[k]) < 1e-5, k
+
+
+# ---- the Weight Update task on the CPU ----
+
+@pytest.mark.parametrize("ends", [([], [6]), ([5], [1, 5, 6]), ([1, 2, 3, 4, 5], [1, 2, 3, 4, 5, 6])])
+@pytest.mark.parametrize("order", [0, 1])
+def test_update_on_host_tiny_fp32(ends, order):
+    say(f"tiny fp32, update on the host, order {order}, schedule {ends}")
+    cfg = dict(synth.CONFIGS["tiny"], M=3)
+    run_and_compare(cfg, sched_ends=ends, zero_state=False, steps=(3, 4), weight_scale=4.0, order=order, update_site=1)
+
+
+def test_update_on_host_bf16_planned_several_packs():
+    say("bf16, update on the host, planned schedule with several packs, two iterations")
+    cfg = tiny_cfg(n_blocks=4, d_model=128, n_heads=2, d_ffn=512, seq_len=128, vocab=1000, precision="bf16", M=3, b=2)
+    ospec = oracle_spec(cfg)
+    prof = opk.layer_profile(ospec, cfg["M"], cfg["b"], "bf16")
+    budget = opk.reserved_bytes(ospec, cfg["M"], cfg["b"], "bf16") + int(2.2 * max(p["mem_bwd"] for p in prof))
+    stats = run_and_compare(cfg, budget=budget, zero_state=False, steps=(5, 6), weight_scale=3.0, update_site=1)
+    assert stats["h2d"]["K"] == stats["d2h"]["K"] == stats["d2h"]["W"] == 0
 
 
 def test_single_microbatch_single_sequence():

@@ -200,6 +200,13 @@ def _cmp_counters(cfg, P_F, P_B):
     got_mm = B.hmy_count_swaps(spec, sched, cfg["M"], cfg["b"])
     want_mm = osw.closed_form_microbatch_major(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
     assert got_mm["h2d"] == want_mm["h2d"] and got_mm["d2h"] == want_mm["d2h"]
+    # the update task on the CPU, in both orders
+    for order, cf in ((B.HMY_ORDER_LAYER_PACK_MAJOR, osw.closed_form),
+                      (B.HMY_ORDER_MICROBATCH_MAJOR, osw.closed_form_microbatch_major)):
+        sched.order, sched.update_site = order, B.HMY_UPDATE_ON_HOST
+        got_h = B.hmy_count_swaps(spec, sched, cfg["M"], cfg["b"])
+        want_h = cf(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"], update_on_host=True)
+        assert got_h["h2d"] == want_h["h2d"] and got_h["d2h"] == want_h["d2h"]
     return got
 
 
@@ -235,6 +242,57 @@ def test_swap_counters_equal_closed_form_on_every_packing_of_a_small_model(preci
     assert n > 30
 
 
+# ------------------------------------------------------- update on the host ---
+
+@pytest.mark.parametrize("precision,threads,n", [("fp32", 1, 1000), ("fp32", 5, 100003), ("bf16", 3, 64 * 7 + 1),
+                                                 ("bf16", 16, 300007), ("bf16", 0, 17)])
+def test_host_adam_matches_the_oracle_update(precision, threads, n):
+    """The CPU-side Weight Update (Section 4.4) against the oracle's Adam, element by
+    element: fp32 arithmetic against fp64, so 1e-6 of the largest value; the bf16 weight
+    is exactly the round-to-nearest-even of the fp32 master it was made from."""
+    rng = np.random.default_rng(n)
+    w = (rng.standard_normal(n) * 0.05).astype(np.float32)
+    g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    g[::7] = 0.0
+    m = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    v = (rng.random(n) * 1e-5).astype(np.float32)
+    f32 = lambda x: float(np.float32(x))
+    hp = om.AdamHP(lr=f32(3e-4), beta1=f32(0.9), beta2=f32(0.999), eps=f32(1e-8), step=7)
+    w_ref, m_ref, v_ref = om.adam_update(w.astype(np.float64), g.astype(np.float64), m.astype(np.float64),
+                                         v.astype(np.float64), hp)
+    mixed = precision == "bf16"
+    master, mm, vv, gg = w.copy(), m.copy(), v.copy(), g.copy()
+    w16 = np.zeros(n, np.uint16)
+    ptr = lambda a: a.ctypes.data
+    if mixed:
+        B.hmy_host_adam(B.HMY_PREC_BF16, ptr(gg), ptr(master), ptr(mm), ptr(vv), ptr(w16), n, hp.lr, hp.beta1, hp.beta2,
+                        hp.eps, hp.step, threads)
+    else:
+        B.hmy_host_adam(B.HMY_PREC_FP32, ptr(gg), None, ptr(mm), ptr(vv), ptr(master), n, hp.lr, hp.beta1, hp.beta2,
+                        hp.eps, hp.step, threads)
+    assert np.array_equal(gg, g)
+    assert np.abs(mm - m_ref).max() < 1e-6 * np.abs(m_ref).max()
+    assert np.abs(vv - v_ref).max() < 1e-6 * np.abs(v_ref).max()
+    # the stored fp32 weight carries its own rounding (half an ulp of |w|) on top of the update's
+    assert np.abs(master - w_ref).max() < 2.0 ** -24 * np.abs(w).max() + 1e-6 * np.abs(w_ref - w).max()
+    if mixed:
+        want = synth.round_bf16(master)
+        got = (w16.astype(np.uint32) << 16).view(np.float32)
+        assert np.array_equal(got, want)
+
+
+def test_host_adam_argument_errors():
+    a = np.zeros(8, np.float32)
+    p = a.ctypes.data
+    for args in ((B.HMY_PREC_BF16, p, None, p, p, p, 8), (B.HMY_PREC_FP32, p, p, p, p, p, 8), (7, p, None, p, p, p, 8),
+                 (B.HMY_PREC_FP32, None, None, p, p, p, 8)):
+        with pytest.raises(B.HmyError) as e:
+            B.hmy_host_adam(*args, 1e-3, 0.9, 0.999, 1e-8, 1)
+        assert e.value.code == B.HMY_E_INVALID
+    with pytest.raises(B.HmyError):
+        B.hmy_host_adam(B.HMY_PREC_FP32, p, None, p, p, p, 8, 1e-3, 0.9, 0.999, 1e-8, 0)    # step is 1-based
+
+
 # ------------------------------------------------------------------ errors ---
 
 def test_error_paths_return_codes_not_crashes():
@@ -258,6 +316,9 @@ def test_error_paths_return_codes_not_crashes():
     assert e.value.code == B.HMY_E_BAD_SCHEDULE
     with pytest.raises(B.HmyError) as e:                # a task order that does not exist
         B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4], order=2), 2, 2)
+    assert e.value.code == B.HMY_E_BAD_SCHEDULE
+    with pytest.raises(B.HmyError) as e:                # nor this update site
+        B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4], update_site=-1), 2, 2)
     assert e.value.code == B.HMY_E_BAD_SCHEDULE
     assert B.lib.hmy_strerror(B.HMY_E_HIP) == b"HIP runtime error"
     assert B.lib.hmy_model_size(None, None, None) == B.HMY_E_INVALID
