@@ -149,13 +149,14 @@ typedef struct hmy_stats {
   uint64_t d2h[HMY_NKINDS]; /* bytes enqueued device->host, per kind */
   double loss;              /* sum over target positions / number of targets */
   double t_iter_s;          /* wall time of the iteration (host clock)      */
+  /* the next four only at profiling level >= 1 (hmy_set_profiling), else 0: */
   double t_compute_s;       /* compute stream: first kernel to last (events) */
   double t_h2d_busy_s;      /* sum of H2D copy durations (events)           */
   double t_d2h_busy_s;      /* sum of D2H copy durations (events)           */
   double t_stall_s;         /* time the compute stream spent waiting on swaps */
   uint64_t n_targets;
   /* per GEMM kernel variant (index = 2*ta + tb): launches, algorithmic flops
-   * (2*M*N*K each) and, only while hmy_set_profiling is on, summed durations */
+   * (2*M*N*K each) and, only at profiling level 2, summed durations */
   uint64_t gemm_calls[4];
   double gemm_flops[4];
   double gemm_s[4];
@@ -251,9 +252,13 @@ int hmy_bind_state(hmy_handle *h, const hmy_host_state *state);
  * counters.  Returns with all streams idle. */
 int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out);
 int hmy_destroy(hmy_handle *h);
-/* Bracket every GEMM launch of the next iterations with timing events (fills
- * hmy_stats.gemm_s; costs two event records per launch).  Off by default. */
-int hmy_set_profiling(hmy_handle *h, int32_t on);
+/* What the next iterations time with HIP events, beyond the byte counters, the loss and
+ * t_iter_s, which are always filled: level 0 (default) nothing -- timing events between
+ * the copies and around the compute stream's waits cost a few percent of the iteration;
+ * 1: every copy, every wait of the compute stream on a swap, and the compute span
+ * (t_compute_s, t_h2d_busy_s, t_d2h_busy_s, t_stall_s); 2: also every GEMM launch
+ * (gemm_s; two more event records per launch). */
+int hmy_set_profiling(hmy_handle *h, int32_t level);
 
 /* 0 = reference kernels (plain tiled loops); 1 = MFMA kernels where they exist
  * (default: the GEMM that streams tiles HBM -> LDS with the load-to-LDS instruction

@@ -263,8 +263,9 @@ def hmy_destroy(h) -> None:
     _check(lib.hmy_destroy(h))
 
 
-def hmy_set_profiling(h, on: bool) -> None:
-    _check(lib.hmy_set_profiling(h, int(bool(on))))
+def hmy_set_profiling(h, level: int) -> None:
+    """0: counters, loss, host-clock time; 1: + copy / stall / compute spans; 2: + every GEMM launch."""
+    _check(lib.hmy_set_profiling(h, int(level)))
 
 
 def _p(x):

@@ -255,7 +255,7 @@ __global__ __launch_bounds__(NJ <= 2 ? 1024 : 512) void k_layernorm_bwd_reg(cons
                                                           const E *gamma, const E *res, E *dx, float *dgamma, float *dbeta,
                                                           int T, int d, float *partial) {
   constexpr int VEC = ElemTraits<E>::VEC;
-  extern __shared__ float lds[];   // per wave: dgamma[d], dbeta[d]
+  extern __shared__ __align__(16) float lds[];   // per wave: dgamma[d], dbeta[d]
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
   float dg[NJ][VEC], db[NJ][VEC];
   Vec16<E> gm[NJ];
@@ -269,14 +269,18 @@ __global__ __launch_bounds__(NJ <= 2 ? 1024 : 512) void k_layernorm_bwd_reg(cons
   for (int row = blockIdx.x * waves + wave; row < T; row += gridDim.x * waves) {
     const E *xr = x + uint64_t(row) * d, *dyr = dy + uint64_t(row) * d;
     const float mu = mean[row], rs = rstd[row];
-    Vec16<E> xv[NJ], gv[NJ];
+    const E *rr = res ? res + uint64_t(row) * d : nullptr;
+    Vec16<E> xv[NJ], gv[NJ], rv[NJ];
     float s1 = 0.f, s2 = 0.f;
+    // every load of the row is issued before anything waits: with about one row per wave there is
+    // nothing else to hide the second round trip behind
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int c = VEC * (lane + kWave * j);
       if (c < d) {
         xv[j] = load16(xr + c);
         gv[j] = load16(dyr + c);
+        if (rr) rv[j] = load16(rr + c);
       }
     }
 #pragma unroll
@@ -298,20 +302,17 @@ __global__ __launch_bounds__(NJ <= 2 ? 1024 : 512) void k_layernorm_bwd_reg(cons
     s1 = wave_sum(s1) / float(d);
     s2 = wave_sum(s2) / float(d);
     E *dxr = dx + uint64_t(row) * d;
-    const E *rr = res ? res + uint64_t(row) * d : nullptr;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int c = VEC * (lane + kWave * j);
       if (c < d) {
-        Vec16<E> rv;
-        if (rr) rv = load16(rr + c);
         Vec16<E> o;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
           const float xh = (to_f32(xv[j].v[k]) - mu) * rs;
           const float dxh = to_f32(gv[j].v[k]) * to_f32(gm[j].v[k]);
           float v = (dxh - s1 - xh * s2) * rs;
-          if (rr) v += to_f32(rv.v[k]);
+          if (rr) v += to_f32(rv[j].v[k]);
           o.v[k] = from_f32<E>(v);
         }
         store16(dxr + c, o);
@@ -323,10 +324,11 @@ __global__ __launch_bounds__(NJ <= 2 ? 1024 : 512) void k_layernorm_bwd_reg(cons
   for (int j = 0; j < NJ; ++j) {
     const int c = VEC * (lane + kWave * j);
     if (c < d) {
+      // 16-byte stores: scalar ones from lanes VEC floats apart would pile onto a few LDS banks
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) {
-        mine[c + k] = dg[j][k];
-        mine[d + c + k] = db[j][k];
+      for (int k = 0; k < VEC; k += 4) {
+        *reinterpret_cast<float4 *>(mine + c + k) = make_float4(dg[j][k], dg[j][k + 1], dg[j][k + 2], dg[j][k + 3]);
+        *reinterpret_cast<float4 *>(mine + d + c + k) = make_float4(db[j][k], db[j][k + 1], db[j][k + 2], db[j][k + 3]);
       }
     }
   }

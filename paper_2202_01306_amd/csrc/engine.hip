@@ -7,8 +7,9 @@
 //   s_in    token ids, weight packs (prefetched one visit ahead, in n_micro pieces
 //           interleaved with the microbatch loop) and checkpoints coming back
 //   s_kin   optimizer state coming in, chunk by chunk, up to the ring's depth ahead
-//   s_upd   the fused Adam kernel (which also writes its results to the host)
-//   s_out   everything going to the host: checkpoints, updated state, gradients
+//   s_out   everything going to the host: checkpoints, updated state, gradients; also the
+//           fused Adam kernel, which writes its results to the host itself (s_upd is an
+//           alias of s_out: the engine stays within the 4 hardware queues a process has)
 // All ordering is by events; the host thread only enqueues and finally waits.
 //
 // A "visit" is one task of the ordered list: forward packs in order, then
@@ -71,6 +72,7 @@ struct hmy_handle {
   hmy_stats st{};
   int err = HMY_OK;
   bool timing = true;
+  int profile_level = 0;      // 0 counters only, 1 copy / stall / compute spans, 2 also every GEMM launch
   bool profile_gemm = false;
   // true: the Adam kernel writes its results directly into the pinned host arrays;
   // false: results go to the ring / slot and leave by hipMemcpyAsync on s_out
@@ -901,8 +903,12 @@ int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_m
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_comp, hipStreamNonBlocking));
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_in, hipStreamNonBlocking));
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_kin, hipStreamNonBlocking));
-  HIPCHK(h, hipStreamCreateWithFlags(&h->s_upd, hipStreamNonBlocking));
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_out, hipStreamNonBlocking));
+  // Four streams, not five: a process has 4 hardware queues by default, a fifth stream shares one
+  // with another stream, and every event wait queued on it then also holds up that stream's kernels
+  // (measured: an engine whose update stream landed on the compute stream's queue ran 30 % slower).
+  // The update kernels and the checkpoint writes barely overlap in time, so they share s_out.
+  h->s_upd = h->s_out;
   if (h->packs.update_site == HMY_UPDATE_ON_HOST && !h->err) {
     h->updater = new HostUpdater(default_host_threads(), updater_thread_init, updater_wait, h);
   }
@@ -957,7 +963,7 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
   }
   h->err = HMY_OK;
   HIPCHK(h, hipSetDevice(h->device));
-  h->timing = out != nullptr;
+  h->timing = out != nullptr && h->profile_level >= 1;
   auto t0 = std::chrono::steady_clock::now();
   run_in_order(h, mb, *adam);
   // always drain, even after an error, so no stream still touches caller memory
@@ -974,7 +980,9 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
   auto t1 = std::chrono::steady_clock::now();
   if (h->err) return h->err;
   double loss = 0.0;
-  HIPCHK(h, hipMemcpy(&loss, h->base + h->arena.res.misc, sizeof(double), hipMemcpyDeviceToHost));
+  // on the compute stream, not the null stream: that one would claim a hardware queue of its own
+  HIPCHK(h, hipMemcpyAsync(&loss, h->base + h->arena.res.misc, sizeof(double), hipMemcpyDeviceToHost, h->s_comp));
+  HIPCHK(h, hipStreamSynchronize(h->s_comp));
   if (out) {
     h->st.loss = loss;
     h->st.t_iter_s = std::chrono::duration<double>(t1 - t0).count();
@@ -1007,9 +1015,11 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
   return h->err;
 }
 
-int hmy_set_profiling(hmy_handle *h, int32_t on) {
+int hmy_set_profiling(hmy_handle *h, int32_t level) {
   if (!h) return fail(HMY_E_INVALID, "null handle");
-  h->profile_gemm = on != 0;
+  if (level < 0 || level > 2) return fail(HMY_E_INVALID, "profiling level %d (0..2)", level);
+  h->profile_level = level;
+  h->profile_gemm = level >= 2;
   return HMY_OK;
 }
 
@@ -1022,7 +1032,7 @@ int hmy_destroy(hmy_handle *h) {
     if (h->s_comp) { hipStreamSynchronize(h->s_comp); hipStreamDestroy(h->s_comp); }
     if (h->s_in) { hipStreamSynchronize(h->s_in); hipStreamDestroy(h->s_in); }
     if (h->s_kin) { hipStreamSynchronize(h->s_kin); hipStreamDestroy(h->s_kin); }
-    if (h->s_upd) { hipStreamSynchronize(h->s_upd); hipStreamDestroy(h->s_upd); }
+    if (h->s_upd && h->s_upd != h->s_out) { hipStreamSynchronize(h->s_upd); hipStreamDestroy(h->s_upd); }
     if (h->s_out) { hipStreamSynchronize(h->s_out); hipStreamDestroy(h->s_out); }
     for (hipEvent_t e : h->sync_events) hipEventDestroy(e);
     for (hipEvent_t e : h->time_events) hipEventDestroy(e);
