@@ -217,6 +217,7 @@ def main() -> int:
                      "unit": "TFLOP/s", "frac": dom_tflops / peak, "traffic": None,
                      "launches": prof["gemm_calls"][dom],
                      "avg_launch_us": prof["gemm_s"][dom] / max(prof["gemm_calls"][dom], 1) * 1e6,
+                     "event_pair_us_subtracted_per_launch": prof["t_event_pair_s"] * 1e6,
                      "all_variants_TFLOPs": [prof["gemm_flops"][i] / max(prof["gemm_s"][i], 1e-12) / 1e12
                                              if prof["gemm_calls"][i] else None for i in range(4)]},
         "loss": stats["loss"],

@@ -160,6 +160,10 @@ typedef struct hmy_stats {
   uint64_t gemm_calls[4];
   double gemm_flops[4];
   double gemm_s[4];
+  /* level 2: what two event records cost with nothing between them (smallest of a few
+   * such pairs at the start of the iteration); already subtracted once per launch
+   * from gemm_s, so that gemm_s is kernel time as a kernel trace reports it */
+  double t_event_pair_s;
 } hmy_stats;
 
 typedef struct hmy_tensor_desc {

@@ -75,7 +75,8 @@ class hmy_stats(C.Structure):
     _fields_ = [("h2d", C.c_uint64 * HMY_NKINDS), ("d2h", C.c_uint64 * HMY_NKINDS), ("loss", C.c_double),
                 ("t_iter_s", C.c_double), ("t_compute_s", C.c_double), ("t_h2d_busy_s", C.c_double),
                 ("t_d2h_busy_s", C.c_double), ("t_stall_s", C.c_double), ("n_targets", C.c_uint64),
-                ("gemm_calls", C.c_uint64 * 4), ("gemm_flops", C.c_double * 4), ("gemm_s", C.c_double * 4)]
+                ("gemm_calls", C.c_uint64 * 4), ("gemm_flops", C.c_double * 4), ("gemm_s", C.c_double * 4),
+                ("t_event_pair_s", C.c_double)]
 
 
 class hmy_tensor_desc(C.Structure):
@@ -203,7 +204,8 @@ def _stats_dict(st: hmy_stats):
                 d2h={k: st.d2h[i] for i, k in enumerate(KIND_NAMES)},
                 loss=st.loss, t_iter_s=st.t_iter_s, t_compute_s=st.t_compute_s, t_h2d_busy_s=st.t_h2d_busy_s,
                 t_d2h_busy_s=st.t_d2h_busy_s, t_stall_s=st.t_stall_s, n_targets=st.n_targets,
-                gemm_calls=list(st.gemm_calls), gemm_flops=list(st.gemm_flops), gemm_s=list(st.gemm_s))
+                gemm_calls=list(st.gemm_calls), gemm_flops=list(st.gemm_flops), gemm_s=list(st.gemm_s),
+                t_event_pair_s=st.t_event_pair_s)
 
 
 def hmy_count_swaps(spec, sched, n_micro, micro_batch):

@@ -269,18 +269,14 @@ __global__ __launch_bounds__(NJ <= 2 ? 1024 : 512) void k_layernorm_bwd_reg(cons
   for (int row = blockIdx.x * waves + wave; row < T; row += gridDim.x * waves) {
     const E *xr = x + uint64_t(row) * d, *dyr = dy + uint64_t(row) * d;
     const float mu = mean[row], rs = rstd[row];
-    const E *rr = res ? res + uint64_t(row) * d : nullptr;
-    Vec16<E> xv[NJ], gv[NJ], rv[NJ];
+    Vec16<E> xv[NJ], gv[NJ];
     float s1 = 0.f, s2 = 0.f;
-    // every load of the row is issued before anything waits: with about one row per wave there is
-    // nothing else to hide the second round trip behind
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int c = VEC * (lane + kWave * j);
       if (c < d) {
         xv[j] = load16(xr + c);
         gv[j] = load16(dyr + c);
-        if (rr) rv[j] = load16(rr + c);
       }
     }
 #pragma unroll
@@ -302,17 +298,20 @@ __global__ __launch_bounds__(NJ <= 2 ? 1024 : 512) void k_layernorm_bwd_reg(cons
     s1 = wave_sum(s1) / float(d);
     s2 = wave_sum(s2) / float(d);
     E *dxr = dx + uint64_t(row) * d;
+    const E *rr = res ? res + uint64_t(row) * d : nullptr;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int c = VEC * (lane + kWave * j);
       if (c < d) {
+        Vec16<E> rv;
+        if (rr) rv = load16(rr + c);
         Vec16<E> o;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
           const float xh = (to_f32(xv[j].v[k]) - mu) * rs;
           const float dxh = to_f32(gv[j].v[k]) * to_f32(gm[j].v[k]);
           float v = (dxh - s1 - xh * s2) * rs;
-          if (rr) v += to_f32(rv[j].v[k]);
+          if (rr) v += to_f32(rv.v[k]);
           o.v[k] = from_f32<E>(v);
         }
         store16(dxr + c, o);
