@@ -25,7 +25,7 @@ def all_packings(R):
 
 @pytest.mark.parametrize("causal", [1, 0])
 def test_layer_pack_major_is_bit_identical_to_microbatch_major(causal):
-    """The paper's correctness claim (Section 5.2): the swapped, regrouped
+    """The paper's correctness claim (Section 5.4, "Correctness of Training"): the swapped, regrouped
     schedule gives exactly what ordinary training gives."""
     cfg = tiny_cfg(n_blocks=3, causal=causal, M=3, b=2)
     spec = oracle_spec(cfg)
