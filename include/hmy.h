@@ -95,8 +95,8 @@ typedef struct hmy_budget {
 #define HMY_ORDER_LAYER_PACK_MAJOR 0
 #define HMY_ORDER_MICROBATCH_MAJOR 1
 
-/* Where the Weight Update task of a pack runs (Section 4.4: "all tasks run on GPUs,
- * but ... the update task [can be] offloaded to the CPU").  ON_DEVICE: optimizer state
+/* Where the Weight Update task of a pack runs (Section 4.4, first paragraph: the Runtime
+ * can place that one task on the CPU instead of the GPU).  ON_DEVICE: optimizer state
  * comes in, the fused Adam kernel runs on the GPU, state, weights and gradient go out.
  * ON_HOST: only the pack's gradient goes out; a pool of CPU threads inside the library
  * applies the same Adam arithmetic to the caller's pinned arrays in place while the
