@@ -113,8 +113,34 @@ __device__ __forceinline__ bf16x8 acc_to_frag(const f32x16 &a, int c) {
 // tile row (0..31) held in accumulator register r by a lane of half h
 __device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r / 4) + 4 * h + r % 4; }
 
+// Which 128-row block, head and sequence a workgroup takes (1-D grid of nrb * H * b workgroups).
+// With a causal mask the work of a row block grows with the number of keys (queries) it sees, from 1
+// to nrb units.  Workgroups are handed out in linear order, round-robin over the 8 XCDs, and a launch
+// of the usual size is resident all at once (about two workgroups per compute unit), so the order IS
+// the placement: a grid with the row block in its fastest dimension puts every heaviest block on one
+// XCD and pairs equal weights on a compute unit (16 units on some, 2 on others, where 9 would do).
+// Here the (row block, head, sequence) triples are ranked by weight, heaviest first, and dealt out in
+// rounds of one workgroup per compute unit, every other round backwards: a unit that got a heavy block
+// in one round gets a light one in the next, and each XCD sees every weight equally often.
+struct BlockCoord { int rb, head, seq; };
+__device__ __forceinline__ BlockCoord block_coord(int nrb, int H, int causal, bool heaviest_is_last_row_block) {
+  const int n = gridDim.x, l = blockIdx.x, bh_count = n / nrb;
+  int r = l;
+  if (causal) {
+    constexpr int kUnits = 256;
+    const int round = l / kUnits, first = round * kUnits, len = min(kUnits, n - first);
+    if (round & 1) r = first + (len - 1 - (l - first));
+  }
+  const int rank = r / bh_count, bh = r % bh_count;
+  BlockCoord c;
+  c.rb = !causal ? rank : (heaviest_is_last_row_block ? nrb - 1 - rank : rank);
+  c.head = bh % H;
+  c.seq = bh / H;
+  return c;
+}
+
 // ---------------------------------------------------------------------------------
-// Forward.  grid (ceil(s/128), H, b).  Wave w owns queries q0 + 32w .. +31.
+// Forward.  grid (ceil(s/128) * H * b).  Wave w owns queries q0 + 32w .. +31.
 template <int DH>
 __global__ __launch_bounds__(kThreads) void k_attn_fwd_mfma(const bf16_t *qkv, bf16_t *o, float *lse, int s, int H,
                                                             int causal) {
@@ -124,9 +150,8 @@ __global__ __launch_bounds__(kThreads) void k_attn_fwd_mfma(const bf16_t *qkv, b
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
   const int d = H * DH;
   const int64_t ld = 3 * int64_t(d);
-  const int head = blockIdx.y, seq = blockIdx.z;
-  // causal: the last query blocks see the most keys; launch order = blockIdx order, so they go first
-  const int q0 = (causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kBlockRows;
+  const BlockCoord bc = block_coord((s + kBlockRows - 1) / kBlockRows, H, causal, true);   // the last query blocks see the most keys
+  const int head = bc.head, seq = bc.seq, q0 = bc.rb * kBlockRows;
   const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
   const int qw = q0 + 32 * wave;                 // first query of this wave
   const int q = qw + lane % 32;                  // this lane's query
@@ -267,8 +292,8 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dq_mfma(const bf16_t *qkv
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
   const int d = H * DH;
   const int64_t ld = 3 * int64_t(d);
-  const int head = blockIdx.y, seq = blockIdx.z;
-  const int q0 = (causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kBlockRows;   // most keys first
+  const BlockCoord bc = block_coord((s + kBlockRows - 1) / kBlockRows, H, causal, true);
+  const int head = bc.head, seq = bc.seq, q0 = bc.rb * kBlockRows;
   const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
   const bf16_t *gbase = d_o + int64_t(seq) * s * d + head * DH;
   const int qw = q0 + 32 * wave, q = qw + lane % 32, q_ld = min(q, s - 1);
@@ -366,8 +391,8 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dkv_mfma(const bf16_t *qk
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
   const int d = H * DH;
   const int64_t ld = 3 * int64_t(d);
-  const int head = blockIdx.y, seq = blockIdx.z;
-  const int j0 = blockIdx.x * kBlockRows;
+  const BlockCoord bc = block_coord((s + kBlockRows - 1) / kBlockRows, H, causal, false);   // the first key blocks are seen by the most queries
+  const int head = bc.head, seq = bc.seq, j0 = bc.rb * kBlockRows;
   const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
   const bf16_t *gbase = d_o + int64_t(seq) * s * d + head * DH;
   const float *lbase = lse + (int64_t(seq) * H + head) * s, *dbase = delta + (int64_t(seq) * H + head) * s;
@@ -485,7 +510,7 @@ inline int check_launch(const char *what) {
 
 template <int DH>
 int fwd_t(const void *qkv, void *o, float *lse, int b, int s, int H, int causal, hipStream_t st) {
-  dim3 grid((s + kBlockRows - 1) / kBlockRows, H, b);
+  const dim3 grid(((s + kBlockRows - 1) / kBlockRows) * H * b);
   hipLaunchKernelGGL((k_attn_fwd_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (bf16_t *)o, lse, s, H,
                      causal);
   return check_launch("attn_fwd_mfma");
@@ -497,7 +522,7 @@ int bwd_t(const void *qkv, const void *o, const void *d_o, const float *lse, flo
   const int64_t n = int64_t(T) * H * (DH / 8);
   hipLaunchKernelGGL((k_attn_delta_mfma<DH>), dim3(int((n + 255) / 256)), dim3(256), 0, st, (const bf16_t *)o,
                      (const bf16_t *)d_o, delta, T, s, H);
-  dim3 grid((s + kBlockRows - 1) / kBlockRows, H, b);
+  const dim3 grid(((s + kBlockRows - 1) / kBlockRows) * H * b);
   hipLaunchKernelGGL((k_attn_bwd_dq_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
                      delta, (bf16_t *)dqkv, s, H, causal);
   hipLaunchKernelGGL((k_attn_bwd_dkv_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (const bf16_t *)d_o,
