@@ -164,6 +164,72 @@ __global__ void k_layernorm_fwd(const E *x, const E *gamma, const E *beta, E *y,
   }
 }
 
+// The same for rows of at most 64 * VEC * NJ elements, with the row kept in registers: one
+// trip to memory instead of three dependent ones (the kernel is a single wave of rows at the
+// sizes it runs at, so its time is latency, not bandwidth).  Same arithmetic: mean, then
+// biased variance about the mean.
+template <typename E, int NJ>
+__global__ void k_layernorm_fwd_reg(const E *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T,
+                                    int d, float eps) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  Vec16<E> gm[NJ], bt[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = VEC * (lane + kWave * j);
+    if (c < d) {
+      gm[j] = load16(gamma + c);
+      bt[j] = load16(beta + c);
+    }
+  }
+  for (int row = blockIdx.x * kWavesPerBlock + wave; row < T; row += gridDim.x * kWavesPerBlock) {
+    const E *xr = x + uint64_t(row) * d;
+    Vec16<E> xv[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c = VEC * (lane + kWave * j);
+      if (c < d) xv[j] = load16(xr + c);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      if (VEC * (lane + kWave * j) < d) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) s += to_f32(xv[j].v[k]);
+      }
+    }
+    const float mu = wave_sum(s) / float(d);
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      if (VEC * (lane + kWave * j) < d) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+          const float t = to_f32(xv[j].v[k]) - mu;
+          q += t * t;
+        }
+      }
+    }
+    const float rs = rsqrtf(wave_sum(q) / float(d) + eps);
+    if (lane == 0) {
+      mean[row] = mu;
+      rstd[row] = rs;
+    }
+    E *yr = y + uint64_t(row) * d;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c = VEC * (lane + kWave * j);
+      if (c < d) {
+        Vec16<E> o;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k)
+          o.v[k] = from_f32<E>(to_f32(gm[j].v[k]) * ((to_f32(xv[j].v[k]) - mu) * rs) + to_f32(bt[j].v[k]));
+        store16(yr + c, o);
+      }
+    }
+  }
+}
+
 // dx = res + (dxhat - mean(dxhat) - xhat*mean(dxhat*xhat)) * rstd, dxhat = dy*gamma;
 // dgamma += sum_rows dy*xhat, dbeta += sum_rows dy.  Per-block partial column
 // sums live in LDS (2*d floats) and are flushed with one atomic per column.
@@ -658,13 +724,22 @@ int launch_embed_bwd(int prec, const int32_t *ids, const void *dx, float *dwte, 
   return check_launch("embed_bwd");
 }
 
+template <typename E>
+void launch_ln_fwd(const E *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T, int d, float eps,
+                   hipStream_t st) {
+  const int nj = (d + kWave * ElemTraits<E>::VEC - 1) / (kWave * ElemTraits<E>::VEC);
+  const dim3 g(grid_for(T, kWavesPerBlock, 8192)), b(kBlock);
+  if (nj == 1) hipLaunchKernelGGL((k_layernorm_fwd_reg<E, 1>), g, b, 0, st, x, gamma, beta, y, mean, rstd, T, d, eps);
+  else if (nj == 2) hipLaunchKernelGGL((k_layernorm_fwd_reg<E, 2>), g, b, 0, st, x, gamma, beta, y, mean, rstd, T, d, eps);
+  else if (nj <= 4) hipLaunchKernelGGL((k_layernorm_fwd_reg<E, 4>), g, b, 0, st, x, gamma, beta, y, mean, rstd, T, d, eps);
+  else if (nj <= 8) hipLaunchKernelGGL((k_layernorm_fwd_reg<E, 8>), g, b, 0, st, x, gamma, beta, y, mean, rstd, T, d, eps);
+  else hipLaunchKernelGGL(k_layernorm_fwd<E>, g, b, 0, st, x, gamma, beta, y, mean, rstd, T, d, eps);
+}
+
 int launch_layernorm_fwd(int prec, const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd,
                          int T, int d, float eps, stream_t st) {
   if (T < 1 || d % 8) return fail(HMY_E_INVALID, "layernorm_fwd: bad shape");
-  DISPATCH_PREC(prec, {
-    hipLaunchKernelGGL(k_layernorm_fwd<E>, dim3(grid_for(T, kWavesPerBlock, 8192)), dim3(kBlock), 0, (hipStream_t)st,
-                       (const E *)x, (const E *)gamma, (const E *)beta, (E *)y, mean, rstd, T, d, eps);
-  });
+  DISPATCH_PREC(prec, launch_ln_fwd<E>((const E *)x, (const E *)gamma, (const E *)beta, (E *)y, mean, rstd, T, d, eps, (hipStream_t)st));
   return check_launch("layernorm_fwd");
 }
 template <typename E>
