@@ -169,7 +169,7 @@ __global__ void k_layernorm_fwd(const E *x, const E *gamma, const E *beta, E *y,
 // sizes it runs at, so its time is latency, not bandwidth).  Same arithmetic: mean, then
 // biased variance about the mean.
 template <typename E, int NJ>
-__global__ void k_layernorm_fwd_reg(const E *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T,
+__global__ __launch_bounds__(kBlock) void k_layernorm_fwd_reg(const E *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T,
                                     int d, float eps) {
   constexpr int VEC = ElemTraits<E>::VEC;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
@@ -317,7 +317,11 @@ __global__ void k_gelu_bwd(const E *dg, const E *u, E *du, uint64_t nvec) {
 // LDS, the workgroup adds the rows up, and one row per workgroup goes to the workspace
 // (or, without one, into dgamma / dbeta with atomics).
 template <typename E, int NJ>
-__global__ __launch_bounds__(NJ <= 2 ? 1024 : 512) void k_layernorm_bwd_reg(const E *dy, const E *x, const float *mean, const float *rstd,
+// one workgroup of 16 / 8 / 4 waves per compute unit (its LDS rows allow no more), i.e. 4 / 2 / 1 waves per
+// SIMD: the bounds tell the compiler that it may use 128 / 256 / 512 registers; left to itself it aimed at 64
+// and spilled the row to scratch memory
+__global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
+    __attribute__((amdgpu_waves_per_eu(1, NJ <= 1 ? 4 : NJ <= 4 ? 2 : 1))) void k_layernorm_bwd_reg(const E *dy, const E *x, const float *mean, const float *rstd,
                                                           const E *gamma, const E *res, E *dx, float *dgamma, float *dbeta,
                                                           int T, int d, float *partial) {
   constexpr int VEC = ElemTraits<E>::VEC;
@@ -747,10 +751,12 @@ void launch_ln_bwd(const E *dy, const E *x, const float *mean, const float *rstd
                    float *dgamma, float *dbeta, int T, int d, hipStream_t st, float *ws, uint64_t ws_bytes) {
   constexpr int VEC = ElemTraits<E>::VEC;
   const int nj = (d + kWave * VEC - 1) / (kWave * VEC);
-  // as many waves per workgroup as 128 KiB of LDS holds rows of 2 d floats (16 at most):
-  // with one row per wave nearly every row of the microbatch is in flight at once
+  // waves per workgroup: as many as 128 KiB of LDS holds rows of 2 d floats, and as the registers allow
+  // without spilling (16 for rows of one 16-byte vector per lane, 8 up to four vectors, 4 beyond; measured
+  // at d = 1024 bf16: 16 waves with spills 22 us, 8 waves 15 us, 4 waves 20 us)
   int waves = 16;
-  while (waves > 1 && (uint64_t(waves) * 2 * d * 4 > (128u << 10) || (nj > 2 && waves > 8))) waves /= 2;
+  while (waves > 1 && (uint64_t(waves) * 2 * d * 4 > (128u << 10) || (nj > 1 && waves > 8) || (nj > 4 && waves > 4)))
+    waves /= 2;   // also the kernels' launch bounds
   const int grid = grid_for(T, waves, kLnBlocks);
   float *partial = ws && ws_bytes >= uint64_t(grid) * 2 * d * 4 && nj <= 8 ? ws : nullptr;
   const size_t lds = size_t(waves) * 2 * d * 4;
