@@ -39,6 +39,43 @@ def attention_flops(cfg, packs) -> float:
     return fwd * (L + recomputed) + 2.5 * fwd * L
 
 
+# HBM traffic per launch of the forward-variant GEMM at the gpt2m shapes, in bytes: FETCH_SIZE and WRITE_SIZE
+# (KiB per dispatch) from two `rocprofv3 --pmc` runs over `kernel_probe.py --only gemm --reps 1 --sets 1`, scaled
+# by what the same counters read for a streaming kernel of known size (k_gelu_bwd, 64 MiB in / 32 MiB out:
+# FETCH x 2.0, WRITE x 1.0).  Kept here because counters cannot be collected inside the benchmark run itself.
+GPT2M_NT_GEMM_TRAFFIC = {          # shape: (fetched KiB as counted, written KiB)
+    "qkv": (28168.6, 24576.0), "out": (16560.5, 8192.0), "ffn1": (33913.8, 65536.0), "ffn2": (53424.5, 8192.0),
+    "logits": (68840.6, 101015.6),   # 512-row chunk, fp32 logits
+}
+
+
+def nt_gemm_traffic_per_launch(config_name, cfg, packs, nt_calls):
+    """(measured, algorithmic) average HBM bytes per launch of the forward-variant GEMM over one
+    iteration, or None where no counters were collected for the workload's shapes."""
+    if config_name != "gpt2m":
+        return None
+    P_F, P_B = packs
+    L, M = cfg["n_blocks"], cfg["M"]
+    is_block = lambda layer: 1 <= layer <= L
+    last_a, last_e = P_B[-1]
+    n_last = sum(1 for l in range(last_a, last_e) if is_block(l))
+    block_fwd = M * (2 * L - n_last)                        # forward pass + recompute, last pack once
+    # the recompute of a backward pack stops before the FFN2 GEMM of its last block (its output is not needed)
+    skipped = M * sum(1 for (a, e) in P_B[:-1] if is_block(e - 1))
+    calls = {"qkv": block_fwd, "out": block_fwd, "ffn1": block_fwd, "ffn2": block_fwd - skipped}
+    calls["logits"] = nt_calls - sum(calls.values())
+    if calls["logits"] < 0:
+        return None
+    total = sum(calls[k] * (2.0 * f + w) * 1024 for k, (f, w) in GPT2M_NT_GEMM_TRAFFIC.items())
+    # what the same launches must move at least: each operand and result once (bf16; fp32 logits)
+    T, d, f, V, R = cfg["b"] * cfg["seq_len"], cfg["d_model"], cfg["d_ffn"], cfg["vocab"], 512
+    ldl = (V + 7) // 8 * 8
+    algo = {"qkv": 2 * (T * d + 3 * d * d + 3 * d + T * 3 * d), "out": 2 * (T * d + d * d + d + 2 * T * d),
+            "ffn1": 2 * (T * d + f * d + f + 2 * T * f), "ffn2": 2 * (T * f + d * f + d + 2 * T * d),
+            "logits": 2 * (R * d + V * d) + 4 * R * ldl}
+    return total / nt_calls, sum(calls[k] * algo[k] for k in algo) / nt_calls
+
+
 def cpu_baseline(cfg):
     """Time the fp64 oracle, as it stands, on a bounded sample of the workload:
     embedding, ONE block and the head, forward and backward, on one microbatch at
@@ -187,6 +224,7 @@ def main() -> int:
     d2h = sum(stats["d2h"].values())
     copy_s = stats["t_h2d_busy_s"] + stats["t_d2h_busy_s"]
     total_flops = gemm_flops + attention_flops(cfg, packs)
+    traffic = nt_gemm_traffic_per_launch(a.config, cfg, packs, prof["gemm_calls"][0]) if dom == 0 else None
     out = {
         "metric": "samples/sec per iteration under HBM budget; swap GB/iter; MFMA util %",
         "value": samples / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -214,7 +252,10 @@ def main() -> int:
                         "h2d_copy_busy": stats["t_h2d_busy_s"] * 1e3, "d2h_copy_busy": stats["t_d2h_busy_s"] * 1e3},
         "mfma_util_pct": 100.0 * gemm_flops / max(gemm_s, 1e-12) / 1e12 / peak,
         "roofline": {"bound": "mfma", "kernel": VARIANTS[dom], "achieved": dom_tflops, "peak": peak,
-                     "unit": "TFLOP/s", "frac": dom_tflops / peak, "traffic": None,
+                     "unit": "TFLOP/s", "frac": dom_tflops / peak,
+                     "traffic": traffic[0] if traffic else None,
+                     "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; stored, not live)",
+                     "algorithmic_bytes_per_launch": traffic[1] if traffic else None,
                      "launches": prof["gemm_calls"][dom],
                      "avg_launch_us": prof["gemm_s"][dom] / max(prof["gemm_calls"][dom], 1) * 1e6,
                      "event_pair_us_subtracted_per_launch": prof["t_event_pair_s"] * 1e6,

@@ -215,7 +215,7 @@ struct Epi {
 };
 
 template <bool TA, bool TB, int BK, int S>
-__global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, int grid_n) {
+__global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, int grid_n, int splits) {
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   constexpr int TILE = BM * BK;            // elements per operand per stage
   constexpr int L = 2 * (BK / 16);         // load-to-LDS instructions per thread per K tile
@@ -224,10 +224,20 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
   const int wm = wave / 2, wn = wave % 2;
-  // tile order: contiguous tile-id range per XCD, then bands of 8 tile rows walked column by column
-  int bid = blockIdx.x;
-  const int nb = gridDim.x, grid_m = nb / grid_n;
-  if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;
+  // Workgroup b runs on XCD b % 8, each with an L2 of its own.  Without a split of the contraction: XCD x gets
+  // the x-th contiguous range of tile ids (ranges differ by at most one), tiles ordered in bands of 8 tile rows
+  // walked column by column, so that neighbours in time share operand tiles in that L2.  With a split (few
+  // tiles, long K): the split index varies fastest, so an XCD works on ONE K range of every tile and each
+  // byte of A and B is fetched by one XCD only (with the tile fastest, every XCD streamed all of A).
+  int bid = blockIdx.x, split_idx = 0;
+  const int nb = gridDim.x / splits, grid_m = nb / grid_n;
+  if (splits > 1) {
+    split_idx = bid % splits;
+    bid /= splits;
+  } else {
+    const int x = bid % 8, per = nb / 8, extra = nb % 8;
+    bid = x * per + min(x, extra) + bid / 8;
+  }
   constexpr int kBand = 8;
   const int band = bid / (kBand * grid_n), first_m = band * kBand;
   const int band_rows = min(grid_m - first_m, kBand);
@@ -243,7 +253,7 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk_all = p.K / BK;
-  const int kt0 = blockIdx.y * tiles_per_split;
+  const int kt0 = split_idx * tiles_per_split;
   const int n = min(nk_all, kt0 + tiles_per_split) - kt0;   // K tiles of this workgroup
   Dma<TA, BK> da;
   Dma<TB, BK> db;
@@ -319,7 +329,7 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   };
   int stage = 0;      // stage holding tile t
   int freed = S - 1;  // stage of tile t-1: free since the barrier inside that tile
-  const bool split = gridDim.y > 1;
+  const bool split = splits > 1;
   Epi e;
   e.init(p, m0, n0);
   const int m_tile = m0 + wm * 64, n_tile = n0 + wn * 64;
@@ -449,13 +459,13 @@ inline int check_launch(const char *what) {
 }
 
 template <int BK, int S>
-int launch_cfg(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int tiles_per_split, int gn, hipStream_t s) {
+int launch_cfg(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int tiles_per_split, int gn, int splits, hipStream_t s) {
   const size_t lds = size_t(S) * 2 * BM * BK * sizeof(bf16_t);
   dim3 block(NT);
-  if (!g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<false, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
-  else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_dma<false, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
-  else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<true, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
-  else hipLaunchKernelGGL((k_gemm_dma<true, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn);
+  if (!g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<false, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn, splits);
+  else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_dma<false, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn, splits);
+  else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<true, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn, splits);
+  else hipLaunchKernelGGL((k_gemm_dma<true, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn, splits);
   return check_launch("gemm_dma");
 }
 
@@ -499,14 +509,14 @@ int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st) {
   const int nk = g.K / bk;
   const int tps = (nk + splits - 1) / splits;
   splits = (nk + tps - 1) / tps;
-  dim3 grid(gm * gn, splits);
+  dim3 grid(gm * gn * splits);
   hipStream_t s = (hipStream_t)st;
   if (bk == 64) {
-    if (stages == 3) return launch_cfg<64, 3>(g, p, grid, tps, gn, s);
-    return launch_cfg<64, 4>(g, p, grid, tps, gn, s);
+    if (stages == 3) return launch_cfg<64, 3>(g, p, grid, tps, gn, splits, s);
+    return launch_cfg<64, 4>(g, p, grid, tps, gn, splits, s);
   }
-  if (stages == 3) return launch_cfg<32, 3>(g, p, grid, tps, gn, s);
-  return launch_cfg<32, 4>(g, p, grid, tps, gn, s);
+  if (stages == 3) return launch_cfg<32, 3>(g, p, grid, tps, gn, splits, s);
+  return launch_cfg<32, 4>(g, p, grid, tps, gn, splits, s);
 }
 
 }  // namespace hmy

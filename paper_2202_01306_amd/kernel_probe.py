@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Run every hot kernel of the iteration on its own, at the shapes of a workload.
 
-    python paper_2202_01306_amd/kernel_probe.py [--config gpt2m] [--reps 20] [--sets 6]
+    python paper_2202_01306_amd/kernel_probe.py [--config gpt2m] [--reps 20] [--sets 6] [--only "gemm fwd"]
 
 Device tensors only (no pinned host memory, no engine), so the script also runs
 under `rocprofv3 --pmc ...`, which is how the per-kernel counters in profiles/ are
@@ -26,6 +26,7 @@ def main() -> int:
     ap.add_argument("--config", default="gpt2m")
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--sets", type=int, default=6)
+    ap.add_argument("--only", default="", help="run only the kernels whose line starts with this text, e.g. 'gemm fwd'")
     a = ap.parse_args()
     import torch
     from paper_2202_01306_amd import binding as B
@@ -49,6 +50,8 @@ def main() -> int:
         return (torch.randn(*shape, device="cuda", generator=g) * scale).to(dtype)
 
     def timed(name, fns, work, unit):
+        if not name.startswith(a.only):
+            return
         for fn in fns:
             fn()
         torch.cuda.synchronize()
@@ -62,17 +65,19 @@ def main() -> int:
         rate = work / (us * 1e-6) / (1e12 if unit == "TFLOP/s" else 1e9)
         print(f"{name:44s} {us:9.1f} us  {rate:9.1f} {unit}", flush=True)
 
-    def gemm(name, M, N, K, ta, tb, acc=False, bias=False, res=False, gelu=False, lda=None, ldb=None, ldc=None):
+    def gemm(name, M, N, K, ta, tb, acc=False, bias=False, res=False, gelu=False, lda=None, ldb=None, ldc=None, c32=False):
+        if not name.startswith(a.only):
+            return
         lda = lda or (M if ta else K)
         ldb = ldb or (N if tb else K)
         ldc = ldc or N
         As = [rnd(K if ta else M, lda, scale=0.5) for _ in range(n)]
         Bs = [rnd(K if tb else N, ldb, scale=0.02) for _ in range(n)]
-        Cs = [torch.zeros(M, ldc, device="cuda", dtype=torch.float32 if acc else dt) for _ in range(n)]
+        Cs = [torch.zeros(M, ldc, device="cuda", dtype=torch.float32 if acc or c32 else dt) for _ in range(n)]
         bs = rnd(N) if bias else None
         rs = [rnd(M, N) for _ in range(n)] if res else None
         gs = [torch.empty(M, N, device="cuda", dtype=dt) for _ in range(n)] if gelu else None
-        fns = [(lambda i=i: B.hmy_k_gemm(pc, M, N, K, As[i], lda, Bs[i], ldb, Cs[i], ldc, ta=ta, tb=tb, c_fp32=int(acc),
+        fns = [(lambda i=i: B.hmy_k_gemm(pc, M, N, K, As[i], lda, Bs[i], ldb, Cs[i], ldc, ta=ta, tb=tb, c_fp32=int(acc or c32),
                                          accumulate=int(acc), bias=bs, res=rs[i] if res else None, ldr=N if res else 0,
                                          gelu_out=gs[i] if gelu else None)) for i in range(n)]
         timed(name, fns, 2.0 * M * N * K, "TFLOP/s")
@@ -82,7 +87,7 @@ def main() -> int:
     gemm("gemm fwd  out    [T,d]  = o Wo^T + b + x", T, d, d, 0, 0, bias=True, res=True)
     gemm("gemm fwd  ffn1   [T,f]  = h W1^T + b, gelu", T, f, d, 0, 0, bias=True, gelu=True)
     gemm("gemm fwd  ffn2   [T,d]  = g W2^T + b + x", T, d, f, 0, 0, bias=True, res=True)
-    gemm("gemm fwd  logits [R,V]  = z Wh^T", R, V, d, 0, 0, ldc=ldl)
+    gemm("gemm fwd  logits [R,V]  = z Wh^T (fp32 out)", R, V, d, 0, 0, ldc=ldl, c32=True)
     gemm("gemm dgrad ffn2  [T,f]  = dy W2", T, f, d, 0, 1)
     gemm("gemm dgrad ffn1  [T,d]  = du W1", T, d, f, 0, 1)
     gemm("gemm dgrad out   [T,d]  = dy Wo", T, d, d, 0, 1)
