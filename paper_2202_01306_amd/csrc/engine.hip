@@ -336,8 +336,9 @@ void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer
                                h->s_comp, ln_ws, ln_ws_bytes));                                        // D = dx_in
 }
 
-// Final norm, vocabulary projection, loss and their backward, chunked over rows
-// so the [rows, vocab] logits never exceed one chunk.  Writes dL/dx into D.
+// Final norm, vocabulary projection, loss and their backward.  The fp32 logits exist one chunk of
+// rows at a time; their gradient (element type) is kept for the whole microbatch, so that the two
+// GEMMs consuming it run once with T rows.  Writes dL/dx into D.
 void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, char *region,
                            const char *x_in, int mb, char *D, float inv_ntgt) {
   const hmy_model_spec &s = h->model.spec;
@@ -363,25 +364,26 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
       g.C = logits; g.ldc = ha.ldl; g.c_fp32 = 1;
       run_gemm(h, g);
     }
-    KCHK(h, launch_xent(prec, logits, tgt_dev(h, mb) + r0, loss_acc, dlogits, rows, V, ha.ldl, inv_ntgt, h->s_comp));
-    {  // dz = dlogits Wh: few output tiles and a vocabulary-long contraction, so it is
-       // accumulated in fp32 (split over workgroups) and rounded afterwards
-      float *dz32 = (float *)(region + ha.dz32);
-      KCHK(h, launch_fill_zero(dz32, uint64_t(rows) * d * 4, h->s_comp));
-      hmy_gemm_desc g = gemm_desc(prec, rows, d, V);
-      g.A = dlogits; g.lda = ha.ldl;
-      g.B = wh; g.ldb = d; g.tb = 1;
-      g.C = dz32; g.ldc = d; g.c_fp32 = 1; g.accumulate = 1;
-      run_gemm(h, g);
-      KCHK(h, launch_convert_f32(prec, dz32, dz + uint64_t(r0) * d * E, uint64_t(rows) * d, h->s_comp));
-    }
-    {  // dWh += dlogits^T z
-      hmy_gemm_desc g = gemm_desc(prec, V, d, rows);
-      g.A = dlogits; g.lda = ha.ldl; g.ta = 1;
-      g.B = zc; g.ldb = d; g.tb = 1;
-      g.C = g_wh; g.ldc = d; g.c_fp32 = 1; g.accumulate = 1;
-      run_gemm(h, g);
-    }
+    KCHK(h, launch_xent(prec, logits, tgt_dev(h, mb) + r0, loss_acc, dlogits + uint64_t(r0) * ha.ldl * E, rows, V, ha.ldl,
+                        inv_ntgt, h->s_comp));
+  }
+  {  // dz = dlogits Wh: a vocabulary-long contraction (ragged, and split over workgroups when T is
+     // small), so it is accumulated in fp32 and rounded afterwards
+    float *dz32 = (float *)(region + ha.dz32);
+    KCHK(h, launch_fill_zero(dz32, uint64_t(T) * d * 4, h->s_comp));
+    hmy_gemm_desc g = gemm_desc(prec, T, d, V);
+    g.A = dlogits; g.lda = ha.ldl;
+    g.B = wh; g.ldb = d; g.tb = 1;
+    g.C = dz32; g.ldc = d; g.c_fp32 = 1; g.accumulate = 1;
+    run_gemm(h, g);
+    KCHK(h, launch_convert_f32(prec, dz32, dz, uint64_t(T) * d, h->s_comp));
+  }
+  {  // dWh += dlogits^T z
+    hmy_gemm_desc g = gemm_desc(prec, V, d, T);
+    g.A = dlogits; g.lda = ha.ldl; g.ta = 1;
+    g.B = z; g.ldb = d; g.tb = 1;
+    g.C = g_wh; g.ldc = d; g.c_fp32 = 1; g.accumulate = 1;
+    run_gemm(h, g);
   }
   KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, g_lnf_g, g_lnf_b, T, d, h->s_comp,
                                (float *)(h->base + h->arena.res.ln_ws), uint64_t(kLnBlocks) * 2 * d * 4));

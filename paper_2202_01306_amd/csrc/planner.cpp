@@ -54,8 +54,11 @@ HeadActs head_acts(const hmy_model_spec &s, int micro_batch) {
   h.mean = take(T * 4);
   h.rstd = take(T * 4);
   h.logits = take(uint64_t(h.chunk_rows) * h.ldl * 4);
-  h.dlogits = take(uint64_t(h.chunk_rows) * h.ldl * E);
-  h.dz32 = take(uint64_t(h.chunk_rows) * d * 4);   // fp32 accumulator of the split-K input gradient
+  // the gradient of the logits is kept for the whole microbatch: the two GEMMs that consume it then run once
+  // per microbatch with T rows instead of once per chunk (the weight-gradient one would otherwise read and write
+  // the fp32 [vocab, d] accumulator once per chunk, which is what bounded it)
+  h.dlogits = take(T * h.ldl * E);
+  h.dz32 = take(T * d * 4);   // fp32 accumulator of the input gradient (its contraction may be split)
   h.size = off;
   return h;
 }

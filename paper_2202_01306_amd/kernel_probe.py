@@ -92,12 +92,12 @@ def main() -> int:
     gemm("gemm dgrad ffn1  [T,d]  = du W1", T, d, f, 0, 1)
     gemm("gemm dgrad out   [T,d]  = dy Wo", T, d, d, 0, 1)
     gemm("gemm dgrad qkv   [T,d]  = dqkv Wqkv", T, d, 3 * d, 0, 1)
-    gemm("gemm dgrad head  [R,d] += dlogits Wh", R, d, V, 0, 1, acc=True, lda=ldl)
+    gemm("gemm dgrad head  [T,d] += dlogits Wh", T, d, V, 0, 1, acc=True, lda=ldl)
     gemm("gemm wgrad ffn2  [d,f] += dy^T g", d, f, T, 1, 1, acc=True)
     gemm("gemm wgrad ffn1  [f,d] += du^T h", f, d, T, 1, 1, acc=True)
     gemm("gemm wgrad out   [d,d] += dy^T o", d, d, T, 1, 1, acc=True)
     gemm("gemm wgrad qkv   [3d,d] += dqkv^T a", 3 * d, d, T, 1, 1, acc=True)
-    gemm("gemm wgrad head  [V,d] += dlogits^T z", V, d, R, 1, 1, acc=True, lda=ldl)
+    gemm("gemm wgrad head  [V,d] += dlogits^T z", V, d, T, 1, 1, acc=True, lda=ldl)
 
     b = cfg["b"]
     causal = int(cfg["causal"])
