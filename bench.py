@@ -69,7 +69,7 @@ def nt_gemm_traffic_per_launch(config_name, cfg, packs, nt_calls):
     total = sum(calls[k] * (2.0 * f + w) * 1024 for k, (f, w) in GPT2M_NT_GEMM_TRAFFIC.items())
     # what the same launches must move at least: each operand and result once (bf16; fp32 logits)
     T, d, f, V, R = cfg["b"] * cfg["seq_len"], cfg["d_model"], cfg["d_ffn"], cfg["vocab"], 512
-    ldl = (V + 7) // 8 * 8
+    ldl = (V + 63) // 64 * 64
     algo = {"qkv": 2 * (T * d + 3 * d * d + 3 * d + T * 3 * d), "out": 2 * (T * d + d * d + d + 2 * T * d),
             "ffn1": 2 * (T * d + f * d + f + 2 * T * f), "ffn2": 2 * (T * f + d * f + d + 2 * T * d),
             "logits": 2 * (R * d + V * d) + 4 * R * ldl}

@@ -125,11 +125,11 @@ def block_act_bytes(spec, b: int, precision: str) -> int:
 def head_act_bytes(spec, b: int, precision: str) -> int:
     """Head input, final-LN output, its (mean, rstd), one chunk of logits (fp32),
     their gradient for the whole microbatch (element type; rows padded to a
-    multiple of 8), plus an fp32 [T, d] accumulator for the gradient of the LN output."""
+    multiple of 64 elements), plus an fp32 [T, d] accumulator for the gradient of the LN output."""
     E = elem_bytes(precision)
     T, d = b * spec.seq_len, spec.d_model
     rows = min(T, LOGIT_ROWS)
-    ldl = (spec.vocab + 7) // 8 * 8
+    ldl = (spec.vocab + 63) // 64 * 64
     sizes = [T * d * E, T * d * E, T * 4, T * 4, rows * ldl * 4, T * ldl * E, T * d * 4]
     return sum(_a256(x) for x in sizes)
 

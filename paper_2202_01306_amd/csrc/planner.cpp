@@ -46,7 +46,7 @@ HeadActs head_acts(const hmy_model_spec &s, int micro_batch) {
   const uint64_t T = uint64_t(micro_batch) * s.seq_len, d = s.d_model;
   HeadActs h;
   h.chunk_rows = int(std::min<uint64_t>(T, kLogitRows));
-  h.ldl = (int64_t(s.vocab) + 7) / 8 * 8;
+  h.ldl = (int64_t(s.vocab) + 63) / 64 * 64;   // rows start on 128-byte lines (element type) for the GEMMs that read them
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) { uint64_t o = off; off += a256(bytes); return o; };
   h.x_in = take(T * d * E);

@@ -42,7 +42,7 @@ def main() -> int:
     dt, pc = torch.bfloat16, B.HMY_PREC_BF16
     T, d, f, H, s, V = cfg["b"] * cfg["seq_len"], cfg["d_model"], cfg["d_ffn"], cfg["n_heads"], cfg["seq_len"], cfg["vocab"]
     dh, R = d // H, 512                      # R: rows of one vocabulary-projection chunk
-    ldl = (V + 7) // 8 * 8
+    ldl = (V + 63) // 64 * 64
     n = max(1, a.sets)
     g = torch.Generator(device="cuda").manual_seed(0)
 
