@@ -75,7 +75,7 @@ typedef struct hmy_model_spec {
 typedef struct hmy_budget {
   uint64_t hbm_budget_bytes; /* everything the library keeps in HBM must fit                   */
   uint32_t host_link_MBps;   /* per direction, for the runtime estimate; 0 = 48000             */
-  uint32_t compute_GFLOPs;   /* sustained model flops/s for the runtime estimate; 0 = 330000   */
+  uint32_t compute_GFLOPs;   /* sustained model flops/s for the runtime estimate; 0 = 380000   */
   uint32_t max_extra_packs;  /* 0: first feasible pack count (Algorithm 2 alone); n: also try the
                                 next n feasible pack counts and keep the smallest estimated
                                 iteration time (the search of Algorithm 1)                      */

@@ -261,7 +261,7 @@ def merge_last_packs(P_B):
 
 
 def plan(spec, budget: int, M: int, b: int, precision: str, search: int = 0, link_MBps: int = 48000,
-         compute_GFLOPs: int = 330000):
+         compute_GFLOPs: int = 380000):
     """Backward packs by Algorithm 2 on (t_bwd, mem_bwd) with capacity budget -
     reserve and the whole-arena test; then forward packs on (t_fwd, mem_fwd)
     over the layers before the last backward pack with capacity N_SLOTS * slot.

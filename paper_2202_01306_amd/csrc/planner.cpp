@@ -306,7 +306,7 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
 
 int plan_packs(const Model &m, const hmy_budget &b, int n_micro, int micro_batch, Packs *out) {
   const uint64_t budget = b.hbm_budget_bytes;
-  const uint64_t link = b.host_link_MBps ? b.host_link_MBps : 48000, rate = b.compute_GFLOPs ? b.compute_GFLOPs : 330000;
+  const uint64_t link = b.host_link_MBps ? b.host_link_MBps : 48000, rate = b.compute_GFLOPs ? b.compute_GFLOPs : 380000;
   std::vector<hmy_layer_profile> prof;
   layer_profile(m, n_micro, micro_batch, &prof);
   const Reserved res = reserved_layout(m, n_micro, micro_batch);

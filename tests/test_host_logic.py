@@ -112,7 +112,7 @@ def test_pack_count_search_matches_the_oracle_and_never_estimates_worse(name):
     spec, ospec = B.make_spec(cfg), oracle_spec(cfg)
     first = B.hmy_plan(spec, cfg["budget"], cfg["M"], cfg["b"])
     for link, rate in ((0, 0), (25000, 600000)):
-        kw = dict(link_MBps=link or 48000, compute_GFLOPs=rate or 330000)
+        kw = dict(link_MBps=link or 48000, compute_GFLOPs=rate or 380000)
         s = B.hmy_plan(spec, cfg["budget"], cfg["M"], cfg["b"], search=64, link_MBps=link, compute_GFLOPs=rate)
         P_F, P_B = B.schedule_packs(s)
         want = opk.plan(ospec, cfg["budget"], cfg["M"], cfg["b"], cfg["precision"], search=64, **kw)
