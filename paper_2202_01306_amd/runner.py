@@ -66,16 +66,20 @@ class TrainingState:
             self._bufs.append(p)
             return p
 
-        self.weights = pinned(np.uint16 if self.mixed else np.float32)   # bf16 bit patterns in mixed mode
-        self.master = pinned(np.float32) if self.mixed else None
-        self.adam_m = pinned(np.float32)
-        self.adam_v = pinned(np.float32)
-        self.grads = pinned(np.float32)
+        try:
+            self.weights = pinned(np.uint16 if self.mixed else np.float32)   # bf16 bit patterns in mixed mode
+            self.master = pinned(np.float32) if self.mixed else None
+            self.adam_m = pinned(np.float32)
+            self.adam_v = pinned(np.float32)
+            self.grads = pinned(np.float32)
+        except B.HmyError:
+            self.close()      # page-locked memory ran out half way: give back what was taken
+            raise
         for p in (self.adam_m, self.adam_v, self.grads):
             p.a[:] = 0
 
     def close(self) -> None:
-        for p in self._bufs:
+        for p in getattr(self, "_bufs", []):
             p.free()
         self._bufs = []
 

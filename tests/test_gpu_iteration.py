@@ -22,6 +22,26 @@ def say(msg):
     print(msg, flush=True)
 
 
+@pytest.fixture(autouse=True)
+def _release_pinned_state():
+    """Page-locked host memory is scarce on the GPU machines: whatever a test allocates through
+    TrainingState is freed when the test ends, pass or fail (a failing test's frames would
+    otherwise keep tens of GB locked and starve the tests after it)."""
+    from paper_2202_01306_amd import runner
+    made = []
+    orig = runner.TrainingState.__init__
+
+    def init(self, *a, **k):
+        made.append(self)
+        orig(self, *a, **k)
+
+    runner.TrainingState.__init__ = init
+    yield
+    runner.TrainingState.__init__ = orig
+    for st in made:
+        st.close()
+
+
 def one_layer_budget(cfg):
     ospec = oracle_spec(cfg)
     prof = opk.layer_profile(ospec, cfg["M"], cfg["b"], cfg["precision"])
@@ -325,7 +345,10 @@ def test_full_size_properties(name, order):
     from paper_2202_01306_amd import binding as B
     from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     cfg = dict(synth.CONFIGS[name])
-    st = TrainingState(cfg)
+    try:
+        st = TrainingState(cfg)
+    except B.HmyError as e:
+        pytest.skip(f"cannot page-lock the host state on this box: {e}")
     st.fill_random(0)
     say("  state filled")
     before = st.master.a.copy()
@@ -367,49 +390,58 @@ def test_full_size_properties(name, order):
 
 
 @pytest.mark.timeout(900)
-def test_6b7_width_sixteen_blocks_full_microbatch_list():
-    """The 6.7 B decoder's width, sequence length, vocabulary, microbatch list and 32 GB budget at 16 of
-    its 32 blocks (3.6 G parameters, 65 GB of pinned state): all 32 blocks need 124 GB of page-locked
-    host memory, and the boxes this was developed on refuse to lock more than about 70-80 GB (the
-    allocation fails cleanly; then this test is skipped too).  Checks as for the other full-size runs:
-    closed-form counters, loss at initialisation, finite gradients that are non-zero in every kind of
-    tensor, step-1 update on sampled tensors."""
-    say("6.7B width, 16 blocks, 16 x 1 x 2048 tokens, 32 GB budget")
+def test_6b7_width_twelve_blocks_full_microbatch_list():
+    """The 6.7 B decoder's width, sequence length, vocabulary, microbatch list and 32 GB budget at 12 of
+    its 32 blocks (2.8 G parameters, 51 GB of pinned state): all 32 blocks need 124 GB of page-locked
+    host memory, and the boxes this was developed on refuse to lock more than 70-80 GB, some less (the
+    allocation fails cleanly; then this test is skipped).  16 blocks ran on most boxes (the design doc has
+    those figures).  Checks as for the other full-size runs: closed-form counters, loss at
+    initialisation, finite gradients that are non-zero in every kind of tensor, step-1 update on
+    sampled tensors."""
+    say("6.7B width, 12 blocks, 16 x 1 x 2048 tokens, 32 GB budget")
     from paper_2202_01306_amd import binding as B
     from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
-    cfg = dict(synth.CONFIGS["gpt6b7"], n_blocks=16)
+    cfg = dict(synth.CONFIGS["gpt6b7"], n_blocks=12)
     try:
         st = TrainingState(cfg)
     except B.HmyError as e:
         pytest.skip(f"cannot page-lock the host state on this box: {e}")
-    st.fill_random(0)
-    say("  state filled")
-    lay = {t["name"]: t for t in st.layout}
-    names = ("h1.wqkv", "h8.w2", "h16.w1", "h16.b1", "wte", "wpe", "lnf_g", "wh")
-    before = {k: st.master.a[lay[k]["offset"]:lay[k]["offset"] + lay[k]["count"]].copy() for k in names}
-    ids = synth.gen_tokens(cfg, 0)
-    tg = synth.gen_targets(cfg, ids, 0)
-    lr, eps = 1e-4, 1e-8
-    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], search=BENCH_PACK_SEARCH) as eng:
-        eng.set_batch(ids, tg)
-        stats = eng.step(lr=lr, eps=eps, step=1)
-        P_F, P_B = eng.packs
-        assert eng.arena["total"] <= cfg["budget"]
-    say(f"  iteration done: loss {stats['loss']:.4f}, {len(P_B)} backward packs, {stats['t_iter_s']:.2f} s")
-    want = osw.closed_form(oracle_spec(cfg), P_F, P_B, cfg["M"], cfg["b"], "bf16")
-    assert stats["h2d"] == want["h2d"] and stats["d2h"] == want["d2h"]
-    expect_loss = math.log(cfg["vocab"]) + 0.5 * cfg["d_model"] * 0.02 ** 2
-    assert abs(stats["loss"] - expect_loss) < 0.01 * expect_loss, (stats["loss"], expect_loss)
-    for k in names:
-        t = lay[k]
-        sl = slice(t["offset"], t["offset"] + t["count"])
-        g = st.grads.a[sl].astype(np.float64)
-        assert np.isfinite(g).all() and np.abs(g).max() > 0, k
-        expect = before[k].astype(np.float64) - lr * g / (np.abs(g) + eps)
-        assert np.abs(st.master.a[sl] - expect).max() < 2e-3 * lr, k
-        assert np.array_equal(st.weights.a[sl].view(np.int16),
-                              torch.from_numpy(st.master.a[sl]).to(torch.bfloat16).view(torch.int16).numpy()), k
-    st.close()
+    try:
+        st.fill_random(0)
+        say("  state filled")
+        lay = {t["name"]: t for t in st.layout}
+        names = ("h1.wqkv", "h6.w2", "h12.w1", "h12.b1", "wte", "wpe", "lnf_g", "wh")
+        before = {k: st.master.a[lay[k]["offset"]:lay[k]["offset"] + lay[k]["count"]].copy() for k in names}
+        ids = synth.gen_tokens(cfg, 0)
+        tg = synth.gen_targets(cfg, ids, 0)
+        lr, eps = 1e-4, 1e-8
+        try:
+            eng = Engine(st, cfg["budget"], cfg["M"], cfg["b"], search=BENCH_PACK_SEARCH)
+        except B.HmyError as e:
+            if "out of memory" in str(e):
+                pytest.skip(f"cannot page-lock the checkpoint stash on this box: {e}")
+            raise
+        with eng:
+            eng.set_batch(ids, tg)
+            stats = eng.step(lr=lr, eps=eps, step=1)
+            P_F, P_B = eng.packs
+            assert eng.arena["total"] <= cfg["budget"]
+        say(f"  iteration done: loss {stats['loss']:.4f}, {len(P_B)} backward packs, {stats['t_iter_s']:.2f} s")
+        want = osw.closed_form(oracle_spec(cfg), P_F, P_B, cfg["M"], cfg["b"], "bf16")
+        assert stats["h2d"] == want["h2d"] and stats["d2h"] == want["d2h"]
+        expect_loss = math.log(cfg["vocab"]) + 0.5 * cfg["d_model"] * 0.02 ** 2
+        assert abs(stats["loss"] - expect_loss) < 0.01 * expect_loss, (stats["loss"], expect_loss)
+        for k in names:
+            t = lay[k]
+            sl = slice(t["offset"], t["offset"] + t["count"])
+            g = st.grads.a[sl].astype(np.float64)
+            assert np.isfinite(g).all() and np.abs(g).max() > 0, k
+            expect = before[k].astype(np.float64) - lr * g / (np.abs(g) + eps)
+            assert np.abs(st.master.a[sl] - expect).max() < 2e-3 * lr, k
+            assert np.array_equal(st.weights.a[sl].view(np.int16),
+                                  torch.from_numpy(st.master.a[sl]).to(torch.bfloat16).view(torch.int16).numpy()), k
+    finally:
+        st.close()      # 51 GB of page-locked memory must not outlive the test, pass or fail
 
 
 @pytest.mark.timeout(900)
