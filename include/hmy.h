@@ -180,15 +180,15 @@ typedef struct hmy_tensor_desc {
 typedef struct hmy_layer_profile {
   int64_t t_fwd, t_bwd;   /* forward; recompute + backward                       */
   uint64_t params;
-  uint64_t mem_fwd;       /* 2 * weight bytes (double-buffered)                    */
-  uint64_t mem_bwd;       /* 2 * (weight + fp32 gradient) bytes + activations      */
+  uint64_t mem_fwd;       /* 3 * weight bytes (three weight slots)                 */
+  uint64_t mem_bwd;       /* 3 * (weight + fp32 gradient) bytes + activations      */
   uint64_t act_bwd;       /* activations one microbatch keeps for backward         */
 } hmy_layer_profile;
 
 typedef struct hmy_arena_plan {
   uint64_t total;         /* bytes of HBM the iteration needs (<= budget)          */
   uint64_t reserved;      /* everything that does not depend on the packs          */
-  uint64_t slot_bytes;    /* one weight slot (there are two)                       */
+  uint64_t slot_bytes;    /* one weight slot (there are three)                     */
   uint64_t act_bytes;     /* activation workspace of the largest backward pack     */
   uint64_t k_chunk_params;/* optimizer state streams through a ring of such chunks */
 } hmy_arena_plan;
