@@ -26,6 +26,12 @@ typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;       // 4 wavefronts, 32 rows of the block tile each
+// At least two waves per SIMD, i.e. at most 256 registers per lane: the compiler then keeps the MFMA
+// accumulators in ordinary vector registers.  Left free to use the accumulation registers it moved the
+// score and output tiles back and forth with v_accvgpr_read / write around every softmax and rescaling
+// (about 100 extra vector instructions per 32 x 32 subtile in kernels that are bound by exactly those).
+// The dK/dV kernel at head dimension 128 needs more than 256 registers and keeps the default.
+#define HMY_MFMA_IN_VGPRS __attribute__((amdgpu_waves_per_eu(2)))
 constexpr int kBlockRows = 128;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -142,7 +148,7 @@ __device__ __forceinline__ BlockCoord block_coord(int nrb, int H, int causal, bo
 // ---------------------------------------------------------------------------------
 // Forward.  grid (ceil(s/128) * H * b).  Wave w owns queries q0 + 32w .. +31.
 template <int DH>
-__global__ __launch_bounds__(kThreads) void k_attn_fwd_mfma(const bf16_t *qkv, bf16_t *o, float *lse, int s, int H,
+__global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_fwd_mfma(const bf16_t *qkv, bf16_t *o, float *lse, int s, int H,
                                                             int causal) {
   typedef Cfg<DH> C;
   __shared__ __attribute__((aligned(16))) bf16_t sK[2][C::TILE * C::PITCH];
@@ -283,7 +289,7 @@ __global__ void k_attn_delta_mfma(const bf16_t *o, const bf16_t *d_o, float *del
 // ---------------------------------------------------------------------------------
 // dQ.  grid (ceil(s/128), H, b).  Wave w owns queries q0+32w..; K and V tiles stream.
 template <int DH>
-__global__ __launch_bounds__(kThreads) void k_attn_bwd_dq_mfma(const bf16_t *qkv, const bf16_t *d_o, const float *lse,
+__global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_bwd_dq_mfma(const bf16_t *qkv, const bf16_t *d_o, const float *lse,
                                                                const float *delta, bf16_t *dqkv, int s, int H,
                                                                int causal) {
   typedef Cfg<DH> C;
@@ -381,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_bwd_dq_mfma(const bf16_t *qkv
 // ---------------------------------------------------------------------------------
 // dK, dV.  grid (ceil(s/128), H, b).  Wave w owns keys j0+32w..; Q and dO tiles stream.
 template <int DH>
-__global__ __launch_bounds__(kThreads) void k_attn_bwd_dkv_mfma(const bf16_t *qkv, const bf16_t *d_o, const float *lse,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH == 128 ? 1 : 2))) void k_attn_bwd_dkv_mfma(const bf16_t *qkv, const bf16_t *d_o, const float *lse,
                                                                 const float *delta, bf16_t *dqkv, int s, int H,
                                                                 int causal) {
   typedef Cfg<DH> C;
