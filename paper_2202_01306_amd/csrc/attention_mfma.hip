@@ -168,7 +168,18 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_fwd_mfma(co
   f32x16 acc_o[C::DTILES];
 #pragma unroll
   for (int t = 0; t < C::DTILES; ++t) acc_o[t] = zero16();
-  float m_run = -INFINITY, l_run = 0.f;
+  // Row sums come out of the matrix cores as well: a row of ones in the role of V^T makes every
+  // register of acc_l the sum over keys of this lane's query's probabilities (both half-waves' keys),
+  // which takes sixteen additions per 32 keys off the vector ALU, the unit this kernel is bound by.
+  f32x16 acc_l = zero16();
+  bf16x8 ones;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) ones[k] = static_cast<__bf16>(1.f);
+  // m_run is the REFERENCE the exponentials are taken against, not the exact running maximum: it is
+  // raised (and everything accumulated rescaled) only when some row's scores outgrow it by more than
+  // kSlack, so probabilities stay below 2^kSlack and most tiles skip the rescaling altogether
+  constexpr float kSlack = 8.f;
+  float m_run = -INFINITY;
   const float sc = rsqrtf(float(DH)) * kLog2e;   // scores in log2 units
   const int k_end = causal ? min(s, q0 + kBlockRows) : s;
   const int n_tiles = (k_end + C::TILE - 1) / C::TILE;
@@ -210,32 +221,28 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_fwd_mfma(co
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, st[r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;     // log2 units (sc > 0)
-        const float m_new = fmaxf(m_run, mx);
-        // rows that have seen no key yet keep m = -inf; use 0 as the reference to stay finite
-        const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          st[r] = fast_exp2(fmaf(st[r], sc, -m_ref));
-          psum += st[r];
-        }
-        if (__any(m_new != m_run)) {   // some row's maximum moved: rescale what was accumulated
-          const float corr = fast_exp2(m_run - m_ref);
-          l_run *= corr;
+        if (__any(mx > m_run + kSlack)) {   // some row outgrew its reference: raise it, rescale what was accumulated
+          const float m_new = fmaxf(m_run, mx);
+          const float corr = m_new == -INFINITY ? 1.f : fast_exp2(m_run - m_new);
+          acc_l[0] *= corr;
 #pragma unroll
           for (int t = 0; t < C::DTILES; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_o[t][r] *= corr;
+          m_run = m_new;
         }
-        l_run += psum;
-        m_run = m_new;
-        // O^T[dh, query] += V^T P^T
+        // rows that have seen no key yet keep m = -inf; use 0 as the reference to stay finite
+        const float m_ref = m_run == -INFINITY ? 0.f : m_run;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[r] = fast_exp2(fmaf(st[r], sc, -m_ref));
+        // O^T[dh, query] += V^T P^T, and the row sums
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
           const bf16x8 fp = acc_to_frag(st, c);
 #pragma unroll
           for (int t = 0; t < C::DTILES; ++t)
             acc_o[t] = mfma(frag_col<DH>(sV[cur], 32 * sub + 16 * c, 32 * t, lane), fp, acc_o[t]);
+          acc_l = mfma(ones, fp, acc_l);
         }
       }
     }
@@ -245,7 +252,7 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_fwd_mfma(co
     }
     __syncthreads();
   }
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = acc_l[0];
   if (q < s) {
     const float inv = 1.f / l_tot;
     bf16_t *orow = o + (int64_t(seq) * s + q) * d + head * DH;
