@@ -143,8 +143,10 @@ struct Epi {
   // the same function as u/2 (1 + tanh z), z = c (u + a u^3), in fewer instructions: the
   // epilogue's arithmetic runs with the matrix cores idle, so it is paid in full.
   static __device__ __forceinline__ float gelu_fast(float u) {
-    const float c2 = -2.f * 0.7978845608028654f, a = 0.044715f;
-    return __fdividef(u, 1.f + __expf(c2 * (u + a * u * u * u)));
+    // exp(-2z) as one exp2 with the constants folded, and the hardware reciprocal: __fdividef and
+    // __expf expand to a ten-instruction IEEE division and an extra multiply
+    const float k = -2.f * 0.7978845608028654f * 1.4426950408889634f, a = 0.044715f;
+    return u * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(k * (u + a * u * u * u)));
   }
   // what the output stage reads from global memory for 8 columns of one row: the residual
   // (bf16) or, for an accumulating fp32 C, C itself.  Fetched before the last K tile so
@@ -159,17 +161,23 @@ struct Epi {
       r.hi = *reinterpret_cast<const float4 *>(c + 4);
     }
   }
-  __device__ __forceinline__ void emit_fast(const DmaP &p, int m, int nn, float (&v)[8], const Pre &r) const {
-    if (p.bias) {
-      const Vec16<bf16_t> b = load16(p.bias + nn);
+  // v[0..7] += the eight bf16 values held in the 16 bytes of `raw`, taken apart with integer operations on
+  // the registers: reading them through a pointer of another type made the compiler keep `raw` in scratch memory
+  static __device__ __forceinline__ void add_bf16x8(float (&v)[8], const float4 &raw) {
+    const uint32_t u[4] = {__float_as_uint(raw.x), __float_as_uint(raw.y), __float_as_uint(raw.z), __float_as_uint(raw.w)};
 #pragma unroll
-      for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
+    for (int c = 0; c < 4; ++c) {
+      v[2 * c] += __uint_as_float(u[c] << 16);
+      v[2 * c + 1] += __uint_as_float(u[c] & 0xffff0000u);
     }
-    if (p.res) {
-      const Vec16<bf16_t> b = *reinterpret_cast<const Vec16<bf16_t> *>(&r.lo);
-#pragma unroll
-      for (int c = 0; c < 8; ++c) v[c] += to_f32(b.v[c]);
-    }
+  }
+  // `bias8`: the lane's 8 bias values, the same for every row it emits.  Loaded once with the prefetch: a
+  // load inside this function would wait on the memory counter, which also counts the stores of the
+  // previous call, and so serialise the eight store rounds of a wave.
+  __device__ __forceinline__ void emit_fast(const DmaP &p, int m, int nn, float (&v)[8], const Pre &r,
+                                            const float4 &bias8) const {
+    if (p.bias) add_bf16x8(v, bias8);
+    if (p.res) add_bf16x8(v, r.lo);
     const int64_t ci = int64_t(m) * p.ldc + nn;
     if (p.c_fp32) {
       float *c = static_cast<float *>(p.C) + ci;
@@ -335,9 +343,11 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   e.init(p, m0, n0);
   const int m_tile = m0 + wm * 64, n_tile = n0 + wn * 64;
   Epi::Pre pre[2][4];
+  float4 bias8 = make_float4(0.f, 0.f, 0.f, 0.f);
   // lane's share of the output: slab i (32 rows), pass q -> row 8 q + lane/8, columns 8 (lane%8) .. +7
   auto prefetch_outputs = [&]() {
     if (split || !e.fast) return;
+    if (p.bias) bias8 = *reinterpret_cast<const float4 *>(p.bias + n_tile + 8 * (lane % 8));
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -440,7 +450,7 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
         float v[8];
         *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
         *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
-        e.emit_fast(p, m_tile + 32 * i + row, n_tile + c0, v, pre[i][q]);
+        e.emit_fast(p, m_tile + 32 * i + row, n_tile + c0, v, pre[i][q], bias8);
       }
     } else {
 #pragma unroll 1
