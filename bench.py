@@ -131,6 +131,8 @@ def main() -> int:
     ap.add_argument("--reference-kernels", action="store_true", help="time the plain (non-MFMA) kernels")
     ap.add_argument("--order", choices=("layer-pack-major", "microbatch-major"), default="layer-pack-major",
                     help="microbatch-major: the order the paper compares against, over the same packs (ablation)")
+    ap.add_argument("--gradients", choices=("exported", "device"), default="exported",
+                    help="device: the update drops the gradient it consumed, as in the paper (no dW on the link)")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the two extra short runs (update on the host; microbatch-major order) reported under 'variants'")
     ap.add_argument("--update-site", choices=("device", "host"), default="device",
@@ -165,10 +167,11 @@ def main() -> int:
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
     sched = None
-    if a.order == "microbatch-major" or a.update_site == "host":
+    if a.order == "microbatch-major" or a.update_site == "host" or a.gradients == "device":
         sched = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search)
         sched.order = B.HMY_ORDER_MICROBATCH_MAJOR if a.order == "microbatch-major" else B.HMY_ORDER_LAYER_PACK_MAJOR
         sched.update_site = B.HMY_UPDATE_ON_HOST if a.update_site == "host" else B.HMY_UPDATE_ON_DEVICE
+        sched.gradients = B.HMY_GRADIENTS_ON_DEVICE if a.gradients == "device" else B.HMY_GRADIENTS_EXPORTED
     with Engine(st, cfg["budget"], cfg["M"], cfg["b"], sched, search=a.pack_search) as eng:
         eng.set_batch(ids, tg)
         step = 1
@@ -192,14 +195,20 @@ def main() -> int:
         B.hmy_set_profiling(eng.handle, 0)
         packs, arena = eng.packs, eng.arena
 
-    # Two ablations over the SAME packs, outside the timed region of the headline number:
-    # the paper's optimizer offload (Weight Update on CPU threads) and the order it compares against.
+    # Three variants over the SAME packs, outside the timed region of the headline number: the paper's
+    # optimizer offload (Weight Update on CPU threads), the paper's own dW traffic (none: the update drops
+    # the gradient it consumed instead of exporting it), and the order the method is compared against.
     variants = {}
     if not a.no_variants and a.order == "layer-pack-major" and a.update_site == "device" and not a.reference_kernels:
-        for name, order, site, n in (("update_on_host", B.HMY_ORDER_LAYER_PACK_MAJOR, B.HMY_UPDATE_ON_HOST, max(2, a.steps)),
-                                     ("microbatch_major", B.HMY_ORDER_MICROBATCH_MAJOR, B.HMY_UPDATE_ON_DEVICE, 2)):
+        LPM, MBM = B.HMY_ORDER_LAYER_PACK_MAJOR, B.HMY_ORDER_MICROBATCH_MAJOR
+        DEV, HOST = B.HMY_UPDATE_ON_DEVICE, B.HMY_UPDATE_ON_HOST
+        for name, order, site, grads, n in (("update_on_host", LPM, HOST, B.HMY_GRADIENTS_EXPORTED, max(2, a.steps)),
+                                            ("gradients_on_device", LPM, DEV, B.HMY_GRADIENTS_ON_DEVICE, max(2, a.steps)),
+                                            ("microbatch_major", MBM, DEV, B.HMY_GRADIENTS_EXPORTED, 2)):
+            if name == "gradients_on_device" and a.gradients == "device":
+                continue
             vs = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search)
-            vs.order, vs.update_site = order, site
+            vs.order, vs.update_site, vs.gradients = order, site, grads
             with Engine(st, cfg["budget"], cfg["M"], cfg["b"], vs) as eng:
                 eng.set_batch(ids, tg)
                 eng.step(step=step, want_stats=False)
@@ -234,7 +243,7 @@ def main() -> int:
                                f"ffn={cfg['d_ffn']} seq={cfg['seq_len']} vocab={cfg['vocab']}, "
                                f"{cfg['M']} microbatches x {cfg['b']} sequences",
                    "hbm_budget_bytes": cfg["budget"], "arena_bytes": arena["total"],
-                   "order": a.order, "update_site": a.update_site, "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
+                   "order": a.order, "update_site": a.update_site, "gradients": a.gradients, "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
                    "kernels": "reference" if a.reference_kernels else "mfma"},
         "tflops": total_flops / (ms * 1e-3) / 1e12,
         "swap": {"h2d_GB_per_iter": h2d / 1e9, "d2h_GB_per_iter": d2h / 1e9,

@@ -105,18 +105,32 @@ typedef struct hmy_budget {
 #define HMY_UPDATE_ON_DEVICE 0
 #define HMY_UPDATE_ON_HOST 1
 
+/* What happens to a pack's fp32 gradient once its update has consumed it on the device
+ * (Section 3, second optimisation: the update runs while W and dW are still resident, so
+ * the method itself never moves dW).  EXPORTED: the update also writes it to
+ * hmy_state.grads, for callers that want to look at gradients (4 bytes per parameter
+ * more on the device->host link, counted under HMY_KIND_DW).  ON_DEVICE: it is dropped;
+ * hmy_state.grads is not written by a layer-pack-major iteration and may be NULL there.
+ * No effect with HMY_UPDATE_ON_HOST, where the exported gradient is the update's input,
+ * and none on the gradient sums that HMY_ORDER_MICROBATCH_MAJOR parks in hmy_state.grads
+ * between microbatches (only the final sums stay behind). */
+#define HMY_GRADIENTS_EXPORTED 0
+#define HMY_GRADIENTS_ON_DEVICE 1
+
 /* Configuration (Section 4.3.1): forward and backward layer packs as exclusive
  * end indices over the R layers.  Backward packs cover 0..R; forward packs cover
  * exactly the layers before the last backward pack (Algorithm 2, lines 1-2).
  * Microbatch sizes U_F = U_B = micro_batch are given by the caller.
- * order: HMY_ORDER_*, update_site: HMY_UPDATE_*; hmy_plan returns LAYER_PACK_MAJOR
- * and ON_DEVICE, any value other than those defined above is HMY_E_BAD_SCHEDULE. */
+ * order: HMY_ORDER_*, update_site: HMY_UPDATE_*, gradients: HMY_GRADIENTS_*; hmy_plan
+ * returns LAYER_PACK_MAJOR, ON_DEVICE and EXPORTED (all 0), any value other than those
+ * defined above is HMY_E_BAD_SCHEDULE. */
 typedef struct hmy_schedule {
   int32_t n_fwd_packs, n_bwd_packs;
   int32_t fwd_pack_end[HMY_MAX_LAYERS];
   int32_t bwd_pack_end[HMY_MAX_LAYERS];
   int32_t order;
   int32_t update_site;
+  int32_t gradients;
 } hmy_schedule;
 
 /* One minibatch as a list of n_micro microbatches of micro_batch sequences. */

@@ -24,8 +24,10 @@ Readings (the paper leaves these open):
     Harmony count is in, in, out);
   * the last backward pack is shared with the forward pass (jit-compute), so
     its weights come in once, not twice: 3|W| becomes 3|W| - |W_last|;
-  * the paper moves no dW at all; an API that returns gradients exports them
-    once (own kind, g_bytes per parameter) so W and K still match the paper;
+  * the paper moves no dW at all (Section 3, second optimisation: the update
+    consumes it while it is resident); an API that returns gradients exports them
+    once (own kind, g_bytes per parameter) so W and K still match the paper, and
+    `export_gradients=False` is the paper's own count;
   * activations between packs stay in device memory on one GPU (X/Y, dY/dX = 0);
   * pack 0's checkpoint is the token ids, and the last pack needs none, so
     max(n_B - 2, 0) checkpoints per microbatch cross the link each way.
@@ -53,8 +55,13 @@ def _pcount(spec, a, e):
     return sum(om.layer_param_count(spec, l) for l in range(a, e))
 
 
-def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False):
+def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False,
+                export_gradients: bool = True):
     """Layer-pack-major volumes.  Returns {'h2d': {kind: bytes}, 'd2h': {...}}.
+
+    export_gradients=False: the update on the device drops the gradient it has
+    consumed, as in the paper, where dW never moves (no effect with update_on_host,
+    where the gradient is what the CPU reads).
 
     update_on_host: the Weight Update task runs on the CPU (Section 4.4, first
     paragraph: the Runtime supports offloading it).  The optimizer state and the
@@ -79,11 +86,13 @@ def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_
     h2d["ids"] = 2 * M * T * 4
     if update_on_host:
         h2d["K"] = d2h["K"] = d2h["W"] = 0
+    elif not export_gradients:
+        d2h["dW"] = 0
     return {"h2d": h2d, "d2h": d2h}
 
 
 def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str,
-                                 update_on_host: bool = False):
+                                 update_on_host: bool = False, export_gradients: bool = True):
     """Same packs, same one-pack-at-a-time residency, but every microbatch runs
     through all packs before the next one starts (the per-GPU-swap order of
     Section 3, "Intuitive Example").  Weights come in M times.  A pack's gradient
@@ -93,18 +102,20 @@ def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precis
     microbatch's.  Readings: the first microbatch starts from a zero-filled buffer
     (nothing to bring in); the last microbatch's gradient is consumed on the device
     by the update that follows it and leaves once, as the exported gradient -- so
-    M - 1 times in and M times out, against the paper's 2m + 2 for a system that
-    also swaps around a separate update phase."""
-    out = closed_form(spec, P_F, P_B, M, b, precision, update_on_host)
+    M - 1 times in and M times out (M - 1 out when a device update drops it instead
+    of exporting it), against the paper's 2m + 2 for a system that also swaps around
+    a separate update phase."""
+    out = closed_form(spec, P_F, P_B, M, b, precision, update_on_host, export_gradients)
     w_c, k_B, g_B = bytes_per_param(precision)
     P_all = _pcount(spec, 0, spec.n_layers)
     out["h2d"]["W"] *= M
     out["h2d"]["dW"] = (M - 1) * g_B * P_all
-    out["d2h"]["dW"] = M * g_B * P_all
+    out["d2h"]["dW"] += (M - 1) * g_B * P_all
     return out
 
 
-def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False):
+def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False,
+           export_gradients: bool = True):
     """Add up what every task of the ordered list swaps."""
     w_c, k_B, g_B = bytes_per_param(precision)
     T = b * spec.seq_len
@@ -131,11 +142,13 @@ def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_ho
             h2d["K"] += k_B * npar
             d2h["K"] += k_B * npar
             d2h["W"] += w_c * npar
-            d2h["dW"] += g_B * npar
+            if export_gradients:
+                d2h["dW"] += g_B * npar
     return {"h2d": h2d, "d2h": d2h}
 
 
-def ledger_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False):
+def ledger_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False,
+                            export_gradients: bool = True):
     """Add up what every task of the microbatch-major list swaps."""
     w_c, k_B, g_B = bytes_per_param(precision)
     T = b * spec.seq_len
@@ -165,7 +178,8 @@ def ledger_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: 
             h2d["K"] += k_B * npar
             d2h["K"] += k_B * npar
             d2h["W"] += w_c * npar
-            d2h["dW"] += g_B * npar
+            if export_gradients:
+                d2h["dW"] += g_B * npar
     return {"h2d": h2d, "d2h": d2h}
 
 

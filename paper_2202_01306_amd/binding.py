@@ -20,6 +20,7 @@ KIND_NAMES = ("W", "dW", "K", "sX", "XY", "dXdY", "ids")
 HMY_PREC_FP32, HMY_PREC_BF16 = 0, 1
 HMY_ORDER_LAYER_PACK_MAJOR, HMY_ORDER_MICROBATCH_MAJOR = 0, 1
 HMY_UPDATE_ON_DEVICE, HMY_UPDATE_ON_HOST = 0, 1
+HMY_GRADIENTS_EXPORTED, HMY_GRADIENTS_ON_DEVICE = 0, 1
 (HMY_OK, HMY_E_INVALID, HMY_E_BUDGET_TOO_SMALL, HMY_E_BAD_SCHEDULE, HMY_E_HIP,
  HMY_E_NOT_BOUND, HMY_E_NO_DEVICE) = (0, -1, -2, -3, -4, -5, -6)
 
@@ -53,7 +54,7 @@ def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0) -> hmy_bu
 class hmy_schedule(C.Structure):
     _fields_ = [("n_fwd_packs", C.c_int32), ("n_bwd_packs", C.c_int32),
                 ("fwd_pack_end", C.c_int32 * HMY_MAX_LAYERS), ("bwd_pack_end", C.c_int32 * HMY_MAX_LAYERS),
-                ("order", C.c_int32), ("update_site", C.c_int32)]
+                ("order", C.c_int32), ("update_site", C.c_int32), ("gradients", C.c_int32)]
 
 
 class hmy_minibatch(C.Structure):
@@ -128,10 +129,11 @@ def make_spec(cfg) -> hmy_model_spec:
                           cfg["vocab"], int(cfg["causal"]), prec, float(cfg.get("ln_eps", 1e-5)))
 
 
-def make_schedule(fwd_ends, bwd_ends, order=0, update_site=0) -> hmy_schedule:
+def make_schedule(fwd_ends, bwd_ends, order=0, update_site=0, gradients=0) -> hmy_schedule:
     s = hmy_schedule()
     s.order = order
     s.update_site = update_site
+    s.gradients = gradients
     s.n_fwd_packs, s.n_bwd_packs = len(fwd_ends), len(bwd_ends)
     for i, e in enumerate(fwd_ends):
         s.fwd_pack_end[i] = e

@@ -591,7 +591,7 @@ __global__ void k_adam(const float *grad, float *master, float *m, float *v, W *
 // (out_*: host pointers, written over the host link as full 16/32-byte vectors).
 // MIXED: master/m/v fp32 + bf16 weight.  !MIXED: the fp32 weight is the master
 // (in_master = the weight in HBM, out_w is fp32 and out_master is not used).
-// Eight elements per thread per step; n may have a tail.
+// out_g == nullptr: the gradient is not exported.  Eight elements per thread per step; n may have a tail.
 template <bool MIXED>
 __global__ void k_adam_out(const float *grad, const float *in_master, const float *in_m, const float *in_v,
                            float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
@@ -629,7 +629,7 @@ __global__ void k_adam_out(const float *grad, const float *in_master, const floa
       for (int h = 0; h < 2; ++h) {
         *reinterpret_cast<float4 *>(out_m + base + 4 * h) = *reinterpret_cast<const float4 *>(m + 4 * h);
         *reinterpret_cast<float4 *>(out_v + base + 4 * h) = *reinterpret_cast<const float4 *>(v + 4 * h);
-        *reinterpret_cast<float4 *>(out_g + base + 4 * h) = *reinterpret_cast<const float4 *>(g + 4 * h);
+        if (out_g) *reinterpret_cast<float4 *>(out_g + base + 4 * h) = *reinterpret_cast<const float4 *>(g + 4 * h);
         if (MIXED) *reinterpret_cast<float4 *>(out_master + base + 4 * h) = *reinterpret_cast<const float4 *>(w + 4 * h);
         else *reinterpret_cast<float4 *>(static_cast<float *>(out_w) + base + 4 * h) = *reinterpret_cast<const float4 *>(w + 4 * h);
       }
@@ -643,7 +643,7 @@ __global__ void k_adam_out(const float *grad, const float *in_master, const floa
       for (int k = 0; k < 8 && base + k < n; ++k) {
         out_m[base + k] = m[k];
         out_v[base + k] = v[k];
-        out_g[base + k] = g[k];
+        if (out_g) out_g[base + k] = g[k];
         if (MIXED) {
           out_master[base + k] = w[k];
           static_cast<bf16_t *>(out_w)[base + k] = from_f32<bf16_t>(w[k]);

@@ -549,18 +549,19 @@ void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
     wait(h, h->s_upd, rec(h, h->s_kin));
   }
   if (u.next == 0) wait(h, h->s_upd, u.bwd_done);
+  const bool export_g = h->packs.gradients == HMY_GRADIENTS_EXPORTED;
   if (h->fused_swap_out) {
-    // the update kernel itself writes state, weights and gradients to the host arrays
-    // (device->host over the link at vector width); bytes are counted as for copies
+    // the update kernel itself writes state, weights and (if exported) gradients to the host
+    // arrays (device->host over the link at vector width); bytes are counted as for copies
     h->st.d2h[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
     h->st.d2h[HMY_KIND_W] += n * E;
-    h->st.d2h[HMY_KIND_DW] += n * 4;
+    if (export_g) h->st.d2h[HMY_KIND_DW] += n * 4;
     if (!h->dry && !h->err) {
       const size_t a = trec(h, h->s_upd);
       KCHK(h, launch_adam_out(h->model.spec.precision, pp.dW + lo, mixed ? r_master : (const float *)(pp.W + lo * E),
                               r_m, r_v, mixed ? h->host.master + g0 : nullptr, h->host.adam_m + g0,
-                              h->host.adam_v + g0, (char *)h->host.weights + g0 * E, h->host.grads + g0, n, hp,
-                              it.compute_done, h->s_upd));
+                              h->host.adam_v + g0, (char *)h->host.weights + g0 * E,
+                              export_g ? h->host.grads + g0 : nullptr, n, hp, it.compute_done, h->s_upd));
       const size_t b2 = trec(h, h->s_upd);
       span(h, a, b2, 1);
       if (zc) span(h, a, b2, 0);   // the same kernel carries the host->device half
@@ -574,7 +575,7 @@ void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
     d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.adam_m + g0, r_m, n * 4, h->s_out);
     d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.adam_v + g0, r_v, n * 4, h->s_out);
     d2h(h, HMY_KIND_W, h->dry ? nullptr : (char *)h->host.weights + g0 * E, pp.W + lo * E, n * E, h->s_out);
-    d2h(h, HMY_KIND_DW, h->dry ? nullptr : h->host.grads + g0, pp.dW + lo, n * 4, h->s_out);
+    if (export_g) d2h(h, HMY_KIND_DW, h->dry ? nullptr : h->host.grads + g0, pp.dW + lo, n * 4, h->s_out);
     it.k_free[r] = rec(h, h->s_out);
   }
   if (++u.next == u.n_chunks) {   // the pack has left: its slot may be refilled
@@ -946,8 +947,14 @@ int hmy_get_schedule(const hmy_handle *h, hmy_schedule *out) {
 int hmy_bind_state(hmy_handle *h, const hmy_host_state *state) {
   if (!h || !state) return fail(HMY_E_INVALID, "null argument");
   const bool mixed = h->model.spec.precision == HMY_PREC_BF16;
-  if (!state->weights || !state->adam_m || !state->adam_v || !state->grads)
-    return fail(HMY_E_INVALID, "weights, adam_m, adam_v and grads must be given");
+  if (!state->weights || !state->adam_m || !state->adam_v)
+    return fail(HMY_E_INVALID, "weights, adam_m and adam_v must be given");
+  // the gradient array is written unless the update consumes the gradient on the device and drops it
+  const bool grads_unused = h->packs.gradients == HMY_GRADIENTS_ON_DEVICE && h->packs.update_site == HMY_UPDATE_ON_DEVICE &&
+                            h->packs.order == HMY_ORDER_LAYER_PACK_MAJOR;
+  if (!state->grads && !grads_unused)
+    return fail(HMY_E_INVALID, "grads must be given (only a layer-pack-major schedule with the update on the device "
+                               "and HMY_GRADIENTS_ON_DEVICE leaves it unwritten)");
   if (mixed && !state->master) return fail(HMY_E_INVALID, "bf16 precision needs an fp32 master array");
   if (!mixed && state->master) return fail(HMY_E_INVALID, "fp32 precision: master must be NULL (weights are the master)");
   if (state->n_params != h->model.n_params)

@@ -150,9 +150,12 @@ int schedule_to_packs(const Model &m, const hmy_schedule *s, Packs *out) {
     return fail(HMY_E_BAD_SCHEDULE, "unknown task order %d", s->order);
   if (s->update_site != HMY_UPDATE_ON_DEVICE && s->update_site != HMY_UPDATE_ON_HOST)
     return fail(HMY_E_BAD_SCHEDULE, "unknown update site %d", s->update_site);
+  if (s->gradients != HMY_GRADIENTS_EXPORTED && s->gradients != HMY_GRADIENTS_ON_DEVICE)
+    return fail(HMY_E_BAD_SCHEDULE, "unknown gradient disposal %d", s->gradients);
   Packs p;
   p.order = s->order;
   p.update_site = s->update_site;
+  p.gradients = s->gradients;
   int pos = 0;
   for (int i = 0; i < s->n_bwd_packs; ++i) {
     int e = s->bwd_pack_end[i];
@@ -182,6 +185,7 @@ void packs_to_schedule(const Packs &p, hmy_schedule *out) {
   out->n_bwd_packs = int(p.bwd.size());
   out->order = p.order;
   out->update_site = p.update_site;
+  out->gradients = p.gradients;
   for (size_t i = 0; i < p.fwd.size(); ++i) out->fwd_pack_end[i] = p.fwd[i].e;
   for (size_t i = 0; i < p.bwd.size(); ++i) out->bwd_pack_end[i] = p.bwd[i].e;
 }

@@ -52,7 +52,9 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 class TrainingState:
     """Caller-owned pinned host state in the library's tensor layout."""
 
-    def __init__(self, cfg):
+    def __init__(self, cfg, with_grads: bool = True):
+        """with_grads=False: no gradient array (only for schedules with HMY_GRADIENTS_ON_DEVICE, layer-pack-major
+        order and the update on the device, which never write it)."""
         self.cfg = cfg
         self.spec = B.make_spec(cfg)
         self.layout = B.hmy_layout(self.spec)
@@ -71,12 +73,13 @@ class TrainingState:
             self.master = pinned(np.float32) if self.mixed else None
             self.adam_m = pinned(np.float32)
             self.adam_v = pinned(np.float32)
-            self.grads = pinned(np.float32)
+            self.grads = pinned(np.float32) if with_grads else None
         except B.HmyError:
             self.close()      # page-locked memory ran out half way: give back what was taken
             raise
         for p in (self.adam_m, self.adam_v, self.grads):
-            p.a[:] = 0
+            if p is not None:
+                p.a[:] = 0
 
     def close(self) -> None:
         for p in getattr(self, "_bufs", []):
@@ -156,13 +159,18 @@ class Engine:
         self.M, self.b = n_micro, micro_batch
         # fails with HMY_E_NO_DEVICE when there is no GPU: there is no CPU fallback
         self.handle = B.hmy_create(state.spec, budget_bytes, n_micro, micro_batch, sched, device, search=search)
-        self.sched = B.hmy_get_schedule(self.handle)
-        self.packs = B.schedule_packs(self.sched)
-        self.arena = B.hmy_arena(state.spec, self.sched, n_micro, micro_batch)
-        B.hmy_bind_state(self.handle, state.weights.ptr, state.master.ptr if state.mixed else None, state.adam_m.ptr,
-                         state.adam_v.ptr, state.grads.ptr, state.n_params)
         self._ids = None
         self._tgt = None
+        try:
+            self.sched = B.hmy_get_schedule(self.handle)
+            self.packs = B.schedule_packs(self.sched)
+            self.arena = B.hmy_arena(state.spec, self.sched, n_micro, micro_batch)
+            B.hmy_bind_state(self.handle, state.weights.ptr, state.master.ptr if state.mixed else None,
+                             state.adam_m.ptr, state.adam_v.ptr,
+                             state.grads.ptr if state.grads is not None else None, state.n_params)
+        except B.HmyError:
+            self.close()      # the handle holds the whole device arena
+            raise
 
     def set_batch(self, ids: np.ndarray, targets: np.ndarray) -> None:
         s = self.state.cfg["seq_len"]

@@ -62,7 +62,7 @@ def oracle_step(cfg, master, m, v, ids, tg, hp):
 
 
 def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps=(1,), seed=0, weight_scale=1.0,
-                    lr=1e-3, order=0, update_site=0):
+                    lr=1e-3, order=0, update_site=0, gradients=0):
     from paper_2202_01306_amd import binding as B
     from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     tol = 1e-4 if cfg["precision"] == "fp32" else 2e-2
@@ -73,16 +73,19 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
     m0, v0 = synth.gen_adam_state(cfg, seed, zero=zero_state)
     ids = synth.gen_tokens(cfg, seed)
     tg = synth.gen_targets(cfg, ids, seed)
-    st = TrainingState(cfg)
+    # a gradient dropped on the device never reaches the host array: then there need not be one
+    no_export = bool(gradients) and not order and not update_site
+    st = TrainingState(cfg, with_grads=not no_export)
     st.load(params, m0, v0)
     if budget is None:
         budget = 1 << 40
-    sched = B.make_schedule(*sched_ends, order=order, update_site=update_site) if sched_ends is not None else None
-    if sched is None and (order or update_site):
+    sched = (B.make_schedule(*sched_ends, order=order, update_site=update_site, gradients=gradients)
+             if sched_ends is not None else None)
+    if sched is None and (order or update_site or gradients):
         sched = B.hmy_plan(st.spec, budget, cfg["M"], cfg["b"])
-        sched.order, sched.update_site = order, update_site
+        sched.order, sched.update_site, sched.gradients = order, update_site, gradients
     cf = osw.closed_form_microbatch_major if order else osw.closed_form
-    closed_form = lambda *a: cf(*a, update_on_host=bool(update_site))
+    closed_form = lambda *a: cf(*a, update_on_host=bool(update_site), export_gradients=not gradients)
     master, m, v = f64(params), f64(m0), f64(v0)
     with Engine(st, budget, cfg["M"], cfg["b"], sched) as eng:
         P_F, P_B = eng.packs
@@ -99,11 +102,17 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
             assert stats["h2d"] == want["h2d"] and stats["d2h"] == want["d2h"]
             assert stats["n_targets"] == om.count_targets(tg)
             assert abs(stats["loss"] - loss) <= tol * abs(loss), (stats["loss"], loss)
-            g_gpu = st.named("grads")
-            worst = max((max_rel_err(g_gpu[k], grads[k]), k) for k in grads)
-            say(f"  step {step}: loss {stats['loss']:.6f} (ref {loss:.6f}); worst grad err {worst[0]:.2e} at {worst[1]}")
-            for k in grads:
-                assert max_rel_err(g_gpu[k], grads[k]) < tol, ("grad", k)
+            if no_export:
+                # nothing to look at: m, v and the update below are what the gradient went into
+                say(f"  step {step}: loss {stats['loss']:.6f} (ref {loss:.6f}); gradients stay on the device")
+            elif gradients and order and not update_site:
+                pass    # the host array holds sums parked before the last microbatch: not the gradient
+            else:
+                g_gpu = st.named("grads")
+                worst = max((max_rel_err(g_gpu[k], grads[k]), k) for k in grads)
+                say(f"  step {step}: loss {stats['loss']:.6f} (ref {loss:.6f}); worst grad err {worst[0]:.2e} at {worst[1]}")
+                for k in grads:
+                    assert max_rel_err(g_gpu[k], grads[k]) < tol, ("grad", k)
             new_master = st.named("master" if st.mixed else "weights")
             for k in w2:
                 if zero_state:
@@ -228,6 +237,41 @@ def test_update_on_host_bf16_planned_several_packs():
     budget = opk.reserved_bytes(ospec, cfg["M"], cfg["b"], "bf16") + int(2.2 * max(p["mem_bwd"] for p in prof))
     stats = run_and_compare(cfg, budget=budget, zero_state=False, steps=(5, 6), weight_scale=3.0, update_site=1)
     assert stats["h2d"]["K"] == stats["d2h"]["K"] == stats["d2h"]["W"] == 0
+
+
+# ---- gradients consumed and dropped on the device (the paper's own dW traffic: none) ----
+
+@pytest.mark.parametrize("ends", [([], [6]), ([5], [1, 5, 6]), ([1, 2, 3, 4, 5], [1, 2, 3, 4, 5, 6])])
+@pytest.mark.parametrize("order,update_site", [(0, 0), (1, 0), (0, 1)])
+def test_gradients_on_device_tiny_fp32(ends, order, update_site):
+    say(f"tiny fp32, gradients not exported, order {order}, update site {update_site}, schedule {ends}")
+    cfg = dict(synth.CONFIGS["tiny"], M=3)
+    stats = run_and_compare(cfg, sched_ends=ends, zero_state=False, steps=(3, 4), weight_scale=4.0, order=order,
+                            update_site=update_site, gradients=1)
+    n = 4 * sum(om.layer_param_count(oracle_spec(cfg), l) for l in range(oracle_spec(cfg).n_layers))
+    assert stats["d2h"]["dW"] == (n if update_site else (cfg["M"] - 1) * n if order else 0)
+
+
+def test_gradients_on_device_bf16_planned_several_packs():
+    say("bf16, gradients not exported, planned schedule with several packs, two iterations")
+    cfg = tiny_cfg(n_blocks=4, d_model=128, n_heads=2, d_ffn=512, seq_len=128, vocab=1000, precision="bf16", M=3, b=2)
+    ospec = oracle_spec(cfg)
+    prof = opk.layer_profile(ospec, cfg["M"], cfg["b"], "bf16")
+    budget = opk.reserved_bytes(ospec, cfg["M"], cfg["b"], "bf16") + int(2.2 * max(p["mem_bwd"] for p in prof))
+    stats = run_and_compare(cfg, budget=budget, zero_state=False, steps=(5, 6), weight_scale=3.0, gradients=1)
+    assert stats["d2h"]["dW"] == stats["h2d"]["dW"] == 0 and stats["d2h"]["K"] > 0
+
+
+def test_gradient_array_is_required_when_it_would_be_written():
+    from paper_2202_01306_amd import binding as B
+    from paper_2202_01306_amd.runner import Engine, TrainingState
+    cfg = dict(synth.CONFIGS["tiny"], M=2)
+    for kw in (dict(), dict(gradients=1, update_site=1), dict(gradients=1, order=1)):
+        st = TrainingState(cfg, with_grads=False)
+        with pytest.raises(B.HmyError) as e:
+            Engine(st, 1 << 40, cfg["M"], cfg["b"], B.make_schedule([5], [1, 5, 6], **kw))
+        assert e.value.code == B.HMY_E_INVALID
+        st.close()
 
 
 def test_single_microbatch_single_sequence():

@@ -207,6 +207,14 @@ def _cmp_counters(cfg, P_F, P_B):
         got_h = B.hmy_count_swaps(spec, sched, cfg["M"], cfg["b"])
         want_h = cf(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"], update_on_host=True)
         assert got_h["h2d"] == want_h["h2d"] and got_h["d2h"] == want_h["d2h"]
+        # the consumed gradient dropped on the device instead of exported, at both update sites
+        for site in (B.HMY_UPDATE_ON_DEVICE, B.HMY_UPDATE_ON_HOST):
+            sched.update_site, sched.gradients = site, B.HMY_GRADIENTS_ON_DEVICE
+            got_d = B.hmy_count_swaps(spec, sched, cfg["M"], cfg["b"])
+            want_d = cf(ospec, P_F, P_B, cfg["M"], cfg["b"], cfg["precision"], update_on_host=bool(site),
+                        export_gradients=False)
+            assert got_d["h2d"] == want_d["h2d"] and got_d["d2h"] == want_d["d2h"]
+        sched.gradients = B.HMY_GRADIENTS_EXPORTED
     return got
 
 
@@ -319,6 +327,9 @@ def test_error_paths_return_codes_not_crashes():
     assert e.value.code == B.HMY_E_BAD_SCHEDULE
     with pytest.raises(B.HmyError) as e:                # nor this update site
         B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4], update_site=-1), 2, 2)
+    assert e.value.code == B.HMY_E_BAD_SCHEDULE
+    with pytest.raises(B.HmyError) as e:                # nor this way to dispose of gradients
+        B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4], gradients=2), 2, 2)
     assert e.value.code == B.HMY_E_BAD_SCHEDULE
     assert B.lib.hmy_strerror(B.HMY_E_HIP) == b"HIP runtime error"
     assert B.lib.hmy_model_size(None, None, None) == B.HMY_E_INVALID

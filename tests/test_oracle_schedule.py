@@ -222,6 +222,41 @@ def test_update_on_host_moves_only_the_gradient():
                 assert mm["h2d"]["K"] == mm["d2h"]["K"] == mm["d2h"]["W"] == 0 and mm["d2h"]["dW"] == M * g_B * P
 
 
+def test_gradients_dropped_on_the_device_is_the_papers_own_count():
+    """Section 3, second optimisation: the update consumes dW while it is resident, so in
+    the paper dW never crosses the link.  With export_gradients=False the closed form and
+    the ledger say so; W, K and checkpoints are untouched, and with the update on the host
+    the switch changes nothing (there the gradient is the update's input).  Microbatch-major:
+    M - 1 out and M - 1 in remain (the parking between microbatches)."""
+    spec = om.Spec(4, 8, 2, 24, 4, 16)
+    R = spec.n_layers
+    for precision in ("fp32", "bf16"):
+        w_c, k_B, g_B = osw.bytes_per_param(precision)
+        P = sum(om.layer_param_count(spec, l) for l in range(R))
+        for M, b in ((1, 1), (3, 2)):
+            for P_B in list(all_packings(R))[::3]:
+                last_start = P_B[-1][0]
+                P_F = [(0, last_start)] if last_start else []
+                args = (spec, P_F, P_B, M, b, precision)
+                exp, drop = osw.closed_form(*args), osw.closed_form(*args, export_gradients=False)
+                assert drop == osw.ledger(*args, export_gradients=False)
+                assert drop["d2h"]["dW"] == 0 and drop["h2d"]["dW"] == 0
+                assert exp["d2h"]["dW"] - drop["d2h"]["dW"] == g_B * P
+                for d in ("h2d", "d2h"):
+                    for k in osw.KINDS:
+                        if (d, k) != ("d2h", "dW"):
+                            assert exp[d][k] == drop[d][k]
+                assert osw.closed_form(*args, update_on_host=True, export_gradients=False) == \
+                    osw.closed_form(*args, update_on_host=True) == \
+                    osw.ledger(*args, update_on_host=True, export_gradients=False)
+                mm = osw.closed_form_microbatch_major(*args, export_gradients=False)
+                assert mm == osw.ledger_microbatch_major(*args, export_gradients=False)
+                assert mm["d2h"]["dW"] == mm["h2d"]["dW"] == (M - 1) * g_B * P
+                assert osw.closed_form_microbatch_major(*args, update_on_host=True, export_gradients=False) == \
+                    osw.ledger_microbatch_major(*args, update_on_host=True, export_gradients=False) == \
+                    osw.closed_form_microbatch_major(*args, update_on_host=True)
+
+
 def test_weight_volume_reduces_to_3W_when_last_pack_is_counted_twice():
     spec = om.Spec(3, 8, 2, 16, 4, 16)
     P_B = [(0, 2), (2, 4), (4, 5)]
