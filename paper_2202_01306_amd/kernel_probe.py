@@ -27,6 +27,7 @@ def main() -> int:
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--sets", type=int, default=6)
     ap.add_argument("--only", default="", help="run only the kernels whose line starts with this text, e.g. 'gemm fwd'")
+    ap.add_argument("--micro-batch", type=int, default=0, help="sequences per microbatch instead of the configuration's")
     a = ap.parse_args()
     import torch
     from paper_2202_01306_amd import binding as B
@@ -35,7 +36,9 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("kernel_probe.py needs a GPU", file=sys.stderr)
         return 3
-    cfg = synth.CONFIGS[a.config]
+    cfg = dict(synth.CONFIGS[a.config])
+    if a.micro_batch > 0:
+        cfg["b"] = a.micro_batch
     if cfg["precision"] != "bf16":
         print("kernel_probe.py times the bf16 kernels; pick a bf16 config", file=sys.stderr)
         return 2
