@@ -74,12 +74,14 @@ typedef struct hmy_model_spec {
  * plus a sustained compute rate for the runtime estimate. */
 typedef struct hmy_budget {
   uint64_t hbm_budget_bytes; /* everything the library keeps in HBM must fit                   */
-  uint32_t host_link_MBps;   /* per direction, for the runtime estimate; 0 = 48000             */
-  uint32_t compute_GFLOPs;   /* sustained model flops/s for the runtime estimate; 0 = 380000   */
+  uint32_t host_link_MBps;   /* per direction, for the runtime estimate; 0 = 40000             */
+  uint32_t compute_GFLOPs;   /* sustained model flops/s for the runtime estimate; 0 = 420000   */
   uint32_t max_extra_packs;  /* 0: first feasible pack count (Algorithm 2 alone); n: also try the
                                 next n feasible pack counts and keep the smallest estimated
                                 iteration time (the search of Algorithm 1)                      */
-  uint32_t reserved_;
+  uint32_t update_site;      /* HMY_UPDATE_*: where the planned iteration will run its Weight Update
+                                tasks; the estimate moves only the gradient over the link for
+                                ON_HOST, and hmy_plan returns a schedule with this update site   */
 } hmy_budget;
 
 /* Order in which the tasks of one iteration run over the packs.

@@ -191,7 +191,11 @@ def arena_bytes(spec, P_F, P_B, M: int, b: int, precision: str):
     return reserved_bytes(spec, M, b, precision) + N_SLOTS * slot + act, slot, act
 
 
-def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_MBps: int, compute_GFLOPs: int) -> int:
+HOST_PARAMS_PER_NS = 6      # CPU update threads: about 6 parameters per nanosecond
+
+
+def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_MBps: int, compute_GFLOPs: int,
+                          update_on_host: bool = False) -> int:
     """Runtime estimate of one iteration (the role of the paper's Runtime Estimator,
     reduced to one GPU): an event-driven walk of the task list over the compute
     stream and the two directions of the host link, in integer nanoseconds.
@@ -199,7 +203,9 @@ def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_M
     are requested when the previous visit starts computing and its slot (visit
     index mod 2) is free; a backward visit's update moves the optimizer state in and
     (state + weights + fp32 gradients) out after its compute ends; the two links
-    are each one queue.  Checkpoint traffic is ignored."""
+    are each one queue.  Checkpoint traffic is ignored.  update_on_host: nothing comes
+    in for the update, only the fp32 gradient goes out, and the CPU threads are one
+    more queue (Section 4.4: the update task placed on the CPU)."""
     from . import model as om
     E = elem_bytes(precision)
     kB = 12 if precision == "bf16" else 8
@@ -215,17 +221,20 @@ def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_M
         return sum(om.layer_param_count(spec, l) for l in range(a, e))
     visits = []
     for (a, e) in P_F:
-        visits.append((False, t_flops(M * sum(prof[l]["t_fwd"] for l in range(a, e))), t_bytes(E * npar(a, e)), 0, 0))
+        visits.append((False, t_flops(M * sum(prof[l]["t_fwd"] for l in range(a, e))), t_bytes(E * npar(a, e)), 0, 0, 0))
     for (a, e) in reversed(P_B):
         P = npar(a, e)
-        visits.append((True, t_flops(M * sum(prof[l]["t_bwd"] for l in range(a, e))), t_bytes(E * P),
-                       t_bytes(kB * P), t_bytes((kB + E + 4) * P)))
-    h2d_free = d2h_free = comp_free = 0
+        comp = t_flops(M * sum(prof[l]["t_bwd"] for l in range(a, e)))
+        if update_on_host:
+            visits.append((True, comp, t_bytes(E * P), 0, t_bytes(4 * P), P // HOST_PARAMS_PER_NS))
+        else:
+            visits.append((True, comp, t_bytes(E * P), t_bytes(kB * P), t_bytes((kB + E + 4) * P), 0))
+    h2d_free = d2h_free = comp_free = cpu_free = 0
     slot_free = [0] * N_SLOTS
     w_ready = [0] * (len(visits) + 1)
     w_ready[0] = visits[0][2]
     h2d_free = w_ready[0]
-    for v, (bwd, comp, w, kin, out) in enumerate(visits):
+    for v, (bwd, comp, w, kin, out, cpu) in enumerate(visits):
         comp_start = max(comp_free, w_ready[v])
         if v + 1 < len(visits):
             s = max(comp_start, slot_free[(v + 1) % N_SLOTS], h2d_free)
@@ -236,12 +245,16 @@ def estimate_iteration_ns(spec, P_F, P_B, M: int, b: int, precision: str, link_M
         if not bwd:
             slot_free[v % N_SLOTS] = comp_end
         else:
-            kin_end = max(comp_end, h2d_free) + kin
-            h2d_free = kin_end
+            kin_end = comp_end
+            if not update_on_host:
+                kin_end = max(comp_end, h2d_free) + kin
+                h2d_free = kin_end
             out_end = max(max(comp_end, d2h_free) + out, kin_end)
             d2h_free = out_end
             slot_free[v % N_SLOTS] = out_end
-    return max(comp_free, d2h_free)
+            if update_on_host:
+                cpu_free = max(cpu_free, out_end) + cpu
+    return max(comp_free, d2h_free, cpu_free)
 
 
 def taper_first_pack(P_B):
@@ -260,8 +273,8 @@ def merge_last_packs(P_B):
     return list(P_B[:-2]) + [(P_B[-2][0], P_B[-1][1])]
 
 
-def plan(spec, budget: int, M: int, b: int, precision: str, search: int = 0, link_MBps: int = 48000,
-         compute_GFLOPs: int = 380000):
+def plan(spec, budget: int, M: int, b: int, precision: str, search: int = 0, link_MBps: int = 40000,
+         compute_GFLOPs: int = 420000, update_on_host: bool = False):
     """Backward packs by Algorithm 2 on (t_bwd, mem_bwd) with capacity budget -
     reserve and the whole-arena test; then forward packs on (t_fwd, mem_fwd)
     over the layers before the last backward pack with capacity N_SLOTS * slot.
@@ -287,7 +300,7 @@ def plan(spec, budget: int, M: int, b: int, precision: str, search: int = 0, lin
             state["failed"] = True
             return
         def offer(P_F):
-            ns = estimate_iteration_ns(spec, P_F, P_B, M, b, precision, link_MBps, compute_GFLOPs)
+            ns = estimate_iteration_ns(spec, P_F, P_B, M, b, precision, link_MBps, compute_GFLOPs, update_on_host)
             if state["best"] is None or ns < state["ns"]:
                 state["best"], state["ns"] = (P_F, P_B), ns
 

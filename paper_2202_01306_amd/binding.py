@@ -44,11 +44,11 @@ class hmy_model_spec(C.Structure):
 
 class hmy_budget(C.Structure):
     _fields_ = [("hbm_budget_bytes", C.c_uint64), ("host_link_MBps", C.c_uint32), ("compute_GFLOPs", C.c_uint32),
-                ("max_extra_packs", C.c_uint32), ("reserved_", C.c_uint32)]
+                ("max_extra_packs", C.c_uint32), ("update_site", C.c_uint32)]
 
 
-def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0) -> hmy_budget:
-    return hmy_budget(int(budget_bytes), int(link_MBps), int(compute_GFLOPs), int(search), 0)
+def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0, update_site=0) -> hmy_budget:
+    return hmy_budget(int(budget_bytes), int(link_MBps), int(compute_GFLOPs), int(search), int(update_site))
 
 
 class hmy_schedule(C.Structure):
@@ -180,9 +180,10 @@ def hmy_profile(spec, n_micro, micro_batch):
     return prof, res.value
 
 
-def hmy_plan(spec, budget_bytes, n_micro, micro_batch, search=0, link_MBps=0, compute_GFLOPs=0) -> hmy_schedule:
+def hmy_plan(spec, budget_bytes, n_micro, micro_batch, search=0, link_MBps=0, compute_GFLOPs=0,
+             update_site=0) -> hmy_schedule:
     s = hmy_schedule()
-    b = make_budget(budget_bytes, search, link_MBps, compute_GFLOPs)
+    b = make_budget(budget_bytes, search, link_MBps, compute_GFLOPs, update_site)
     _check(lib.hmy_plan(C.byref(spec), C.byref(b), n_micro, micro_batch, C.byref(s)))
     return s
 

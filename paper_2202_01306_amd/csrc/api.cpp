@@ -98,8 +98,8 @@ int hmy_estimate(const hmy_model_spec *spec, const hmy_schedule *sched, const hm
   if (rc) return rc;
   std::vector<hmy_layer_profile> prof;
   layer_profile(m, n_micro, micro_batch, &prof);
-  *iteration_ns = estimate_iteration_ns(m, prof, p, n_micro, budget->host_link_MBps ? budget->host_link_MBps : 48000,
-                                        budget->compute_GFLOPs ? budget->compute_GFLOPs : 380000);
+  *iteration_ns = estimate_iteration_ns(m, prof, p, n_micro, budget->host_link_MBps ? budget->host_link_MBps : 40000,
+                                        budget->compute_GFLOPs ? budget->compute_GFLOPs : 420000);
   return HMY_OK;
 }
 

@@ -268,21 +268,26 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
   const uint64_t E = m.elem_bytes(), kB = 4 * uint64_t(m.k_arrays());
   auto t_bytes = [&](uint64_t bytes) { return (bytes * 1000 + link_MBps - 1) / link_MBps; };
   auto t_flops = [&](uint64_t flops) { return (flops + compute_GFLOPs - 1) / compute_GFLOPs; };
-  struct V { bool bwd; uint64_t comp, w, kin, out; };
+  // with the update on the host only the gradient crosses the link, and the CPU threads (about 6 parameters
+  // per nanosecond on the machines measured) are one more queue
+  const bool host = p.update_site == HMY_UPDATE_ON_HOST;
+  constexpr uint64_t kHostParamsPerNs = 6;
+  struct V { bool bwd; uint64_t comp, w, kin, out, cpu; };
   std::vector<V> vs;
   for (const Pack &q : p.fwd) {
     uint64_t fl = 0;
     for (int l = q.a; l < q.e; ++l) fl += uint64_t(prof[l].t_fwd);
-    vs.push_back({false, t_flops(fl * n_micro), t_bytes(E * m.params_in(q.a, q.e)), 0, 0});
+    vs.push_back({false, t_flops(fl * n_micro), t_bytes(E * m.params_in(q.a, q.e)), 0, 0, 0});
   }
   for (int k = int(p.bwd.size()) - 1; k >= 0; --k) {
     const Pack &q = p.bwd[k];
     uint64_t fl = 0;
     for (int l = q.a; l < q.e; ++l) fl += uint64_t(prof[l].t_bwd);
     const uint64_t P = m.params_in(q.a, q.e);
-    vs.push_back({true, t_flops(fl * n_micro), t_bytes(E * P), t_bytes(kB * P), t_bytes((kB + E + 4) * P)});
+    if (host) vs.push_back({true, t_flops(fl * n_micro), t_bytes(E * P), 0, t_bytes(4 * P), P / kHostParamsPerNs});
+    else vs.push_back({true, t_flops(fl * n_micro), t_bytes(E * P), t_bytes(kB * P), t_bytes((kB + E + 4) * P), 0});
   }
-  uint64_t h2d_free = 0, d2h_free = 0, comp_free = 0, slot_free[kSlots] = {};
+  uint64_t h2d_free = 0, d2h_free = 0, comp_free = 0, cpu_free = 0, slot_free[kSlots] = {};
   std::vector<uint64_t> w_ready(vs.size() + 1, 0);
   w_ready[0] = vs[0].w;
   h2d_free = w_ready[0];
@@ -298,21 +303,27 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
     if (!vs[v].bwd) {
       slot_free[v % kSlots] = comp_end;
     } else {
-      const uint64_t kin_end = std::max(comp_end, h2d_free) + vs[v].kin;
-      h2d_free = kin_end;
+      uint64_t kin_end = comp_end;
+      if (!host) {
+        kin_end = std::max(comp_end, h2d_free) + vs[v].kin;
+        h2d_free = kin_end;
+      }
       const uint64_t out_end = std::max(std::max(comp_end, d2h_free) + vs[v].out, kin_end);
       d2h_free = out_end;
       slot_free[v % kSlots] = out_end;
+      if (host) cpu_free = std::max(cpu_free, out_end) + vs[v].cpu;
     }
   }
-  return std::max(comp_free, d2h_free);
+  return std::max(comp_free, std::max(d2h_free, cpu_free));
 }
 
 int plan_packs(const Model &m, const hmy_budget &b, int n_micro, int micro_batch, Packs *out) {
   const uint64_t budget = b.hbm_budget_bytes;
-  const uint64_t link = b.host_link_MBps ? b.host_link_MBps : 48000, rate = b.compute_GFLOPs ? b.compute_GFLOPs : 380000;
+  const uint64_t link = b.host_link_MBps ? b.host_link_MBps : 40000, rate = b.compute_GFLOPs ? b.compute_GFLOPs : 420000;
   std::vector<hmy_layer_profile> prof;
   layer_profile(m, n_micro, micro_batch, &prof);
+  if (b.update_site != HMY_UPDATE_ON_DEVICE && b.update_site != HMY_UPDATE_ON_HOST)
+    return fail(HMY_E_INVALID, "budget: unknown update site %u", b.update_site);
   const Reserved res = reserved_layout(m, n_micro, micro_batch);
   if (budget <= res.size)
     return fail(HMY_E_BUDGET_TOO_SMALL, "budget %llu B does not cover the pack-independent reserve %llu B",
@@ -347,6 +358,7 @@ int plan_packs(const Model &m, const hmy_budget &b, int n_micro, int micro_batch
   auto consider = [&](const std::vector<Pack> &bwd) {
     Packs p;
     p.bwd = bwd;
+    p.update_site = int(b.update_site);
     // forward packs over the layers before the last backward pack; they share the
     // weight slots sized by the backward packing
     const int RF = p.bwd.back().a;

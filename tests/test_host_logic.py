@@ -112,7 +112,7 @@ def test_pack_count_search_matches_the_oracle_and_never_estimates_worse(name):
     spec, ospec = B.make_spec(cfg), oracle_spec(cfg)
     first = B.hmy_plan(spec, cfg["budget"], cfg["M"], cfg["b"])
     for link, rate in ((0, 0), (25000, 600000)):
-        kw = dict(link_MBps=link or 48000, compute_GFLOPs=rate or 380000)
+        kw = dict(link_MBps=link or 40000, compute_GFLOPs=rate or 420000)
         s = B.hmy_plan(spec, cfg["budget"], cfg["M"], cfg["b"], search=64, link_MBps=link, compute_GFLOPs=rate)
         P_F, P_B = B.schedule_packs(s)
         want = opk.plan(ospec, cfg["budget"], cfg["M"], cfg["b"], cfg["precision"], search=64, **kw)
@@ -122,6 +122,20 @@ def test_pack_count_search_matches_the_oracle_and_never_estimates_worse(name):
                                                kw["link_MBps"], kw["compute_GFLOPs"])
         assert ns <= B.hmy_estimate(spec, first, cfg["M"], cfg["b"], link, rate)
         assert B.hmy_arena(spec, s, cfg["M"], cfg["b"])["total"] <= cfg["budget"]
+        # planned for the Weight Update on the CPU: the schedule says so, plan and estimate equal the oracle's
+        sh = B.hmy_plan(spec, cfg["budget"], cfg["M"], cfg["b"], search=64, link_MBps=link, compute_GFLOPs=rate,
+                        update_site=B.HMY_UPDATE_ON_HOST)
+        assert sh.update_site == B.HMY_UPDATE_ON_HOST
+        P_Fh, P_Bh = B.schedule_packs(sh)
+        assert (P_Fh, P_Bh) == opk.plan(ospec, cfg["budget"], cfg["M"], cfg["b"], cfg["precision"], search=64,
+                                        update_on_host=True, **kw)
+        nsh = B.hmy_estimate(spec, sh, cfg["M"], cfg["b"], link, rate)
+        assert nsh == opk.estimate_iteration_ns(ospec, P_Fh, P_Bh, cfg["M"], cfg["b"], cfg["precision"],
+                                                kw["link_MBps"], kw["compute_GFLOPs"], update_on_host=True)
+        s.update_site = B.HMY_UPDATE_ON_HOST            # the device plan run with the update on the host
+        assert nsh <= B.hmy_estimate(spec, s, cfg["M"], cfg["b"], link, rate)
+        s.update_site = B.HMY_UPDATE_ON_DEVICE
+        assert nsh <= ns                                # less traffic, never a longer estimate
 
 
 def test_runtime_estimate_closed_forms():
@@ -144,6 +158,16 @@ def test_runtime_estimate_closed_forms():
     # device->host moves (12 + 2 + 4) B/param once; host->device moves 12 B/param of state + weights twice minus the last pack
     d2h_ns = 18 * n * 1000
     assert d2h_ns <= slow <= d2h_ns + 2 * 2 * n * 1000 + 12 * n * 1000 + 100
+    # the update on the host: only the weights come in and only the 4 B/param gradient goes out; with a slow link
+    # the weight loads (twice, minus the last pack) are the longer queue, the CPU (6 parameters/ns) comes after
+    host = B.make_schedule([2, 4], [2, 4, 5], update_site=B.HMY_UPDATE_ON_HOST)
+    slow_h = B.hmy_estimate(spec, host, 2, 2, link_MBps=1, compute_GFLOPs=4_000_000_000)
+    n_last = prof[4]["params"]
+    w_in_ns = 2 * (2 * n - n_last) * 1000
+    assert w_in_ns <= slow_h <= w_in_ns + 4 * n * 1000 + n // 6 + 100
+    fast_h = B.hmy_estimate(spec, host, 2, 2, link_MBps=4_000_000_000, compute_GFLOPs=rate)
+    first_pack = prof[0]["params"] + prof[1]["params"]        # updated last: nothing left to hide its CPU time
+    assert abs(fast_h - (fast_link + first_pack // 6)) <= 10
 
 
 def test_tiny_config_budget_gives_one_layer_per_pack():
