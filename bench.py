@@ -133,6 +133,8 @@ def main() -> int:
                     help="microbatch-major: the order the paper compares against, over the same packs (ablation)")
     ap.add_argument("--gradients", choices=("exported", "device"), default="exported",
                     help="device: the update drops the gradient it consumed, as in the paper (no dW on the link)")
+    ap.add_argument("--resident-state", action="store_true",
+                    help="keep optimizer state on the device in what the budget leaves free behind the arena")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the two extra short runs (update on the host; microbatch-major order) reported under 'variants'")
     ap.add_argument("--update-site", choices=("device", "host"), default="device",
@@ -167,11 +169,12 @@ def main() -> int:
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
     sched = None
-    if a.order == "microbatch-major" or a.update_site == "host" or a.gradients == "device":
+    if a.order == "microbatch-major" or a.update_site == "host" or a.gradients == "device" or a.resident_state:
         site = B.HMY_UPDATE_ON_HOST if a.update_site == "host" else B.HMY_UPDATE_ON_DEVICE
         sched = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search, update_site=site)
         sched.order = B.HMY_ORDER_MICROBATCH_MAJOR if a.order == "microbatch-major" else B.HMY_ORDER_LAYER_PACK_MAJOR
         sched.gradients = B.HMY_GRADIENTS_ON_DEVICE if a.gradients == "device" else B.HMY_GRADIENTS_EXPORTED
+        sched.resident_state = B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET if a.resident_state else B.HMY_STATE_SWAPPED
     with Engine(st, cfg["budget"], cfg["M"], cfg["b"], sched, search=a.pack_search) as eng:
         eng.set_batch(ids, tg)
         step = 1
@@ -193,24 +196,30 @@ def main() -> int:
         prof = eng.step(step=step, want_stats=True)
         step += 1
         B.hmy_set_profiling(eng.handle, 0)
-        packs, arena = eng.packs, eng.arena
+        packs, arena, resident = eng.packs, eng.arena, eng.resident_params()
+        eng.sync_state()
 
-    # Three variants outside the timed region of the headline number: the paper's
-    # optimizer offload (Weight Update on CPU threads), the paper's own dW traffic (none: the update drops
-    # the gradient it consumed instead of exporting it), and the order the method is compared against.
+    # Variants outside the timed region of the headline number: the paper's optimizer offload (Weight Update on
+    # CPU threads), the paper's own dW traffic (none: the update drops the gradient it consumed instead of
+    # exporting it), optimizer state kept on the device in what the budget leaves free behind the arena (then
+    # the host arrays hold that state only after hmy_sync_state), both, and the order the method is compared against.
     variants = {}
     if not a.no_variants and a.order == "layer-pack-major" and a.update_site == "device" and not a.reference_kernels:
         LPM, MBM = B.HMY_ORDER_LAYER_PACK_MAJOR, B.HMY_ORDER_MICROBATCH_MAJOR
         DEV, HOST = B.HMY_UPDATE_ON_DEVICE, B.HMY_UPDATE_ON_HOST
-        for name, order, site, grads, n in (("update_on_host", LPM, HOST, B.HMY_GRADIENTS_EXPORTED, max(2, a.steps)),
-                                            ("gradients_on_device", LPM, DEV, B.HMY_GRADIENTS_ON_DEVICE, max(2, a.steps)),
-                                            ("microbatch_major", MBM, DEV, B.HMY_GRADIENTS_EXPORTED, 2)):
-            if name == "gradients_on_device" and a.gradients == "device":
-                continue
+        SWAP, RES = B.HMY_STATE_SWAPPED, B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET
+        EXP, DROP = B.HMY_GRADIENTS_EXPORTED, B.HMY_GRADIENTS_ON_DEVICE
+        for name, order, site, grads, res, n in (("update_on_host", LPM, HOST, EXP, SWAP, max(2, a.steps)),
+                                                 ("gradients_on_device", LPM, DEV, DROP, SWAP, max(2, a.steps)),
+                                                 ("resident_state", LPM, DEV, EXP, RES, max(2, a.steps)),
+                                                 ("resident_state+gradients_on_device", LPM, DEV, DROP, RES, max(2, a.steps)),
+                                                 ("microbatch_major", MBM, DEV, EXP, SWAP, 2)):
+            if (grads == DROP) == (a.gradients == "device") and (res == RES) == a.resident_state and order == LPM and site == DEV:
+                continue    # that is the headline run itself
             # the host variant over the packs the planner picks for it (its estimate knows that only the
             # gradient crosses the link then); the other two over the headline's packs
             vs = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search, update_site=site)
-            vs.order, vs.gradients = order, grads
+            vs.order, vs.gradients, vs.resident_state = order, grads, res
             with Engine(st, cfg["budget"], cfg["M"], cfg["b"], vs) as eng:
                 eng.set_batch(ids, tg)
                 eng.step(step=step, want_stats=False)
@@ -220,8 +229,9 @@ def main() -> int:
                     vstats = eng.step(step=step, want_stats=True)
                     step += 1
                 vms = (time.perf_counter() - t0) / n * 1e3
-                vpacks = eng.packs
-            variants[name] = {"fwd_packs": vpacks[0], "bwd_packs": vpacks[1],
+                vpacks, vres = eng.packs, eng.resident_params()
+                eng.sync_state()      # the next variant starts from complete host arrays
+            variants[name] = {"fwd_packs": vpacks[0], "bwd_packs": vpacks[1], "resident_state_params": vres,
                               "value": cfg["M"] * cfg["b"] / (vms * 1e-3), "unit": "samples/s", "ms_per_step": vms, "steps": n,
                               "h2d_GB_per_iter": sum(vstats["h2d"].values()) / 1e9,
                               "d2h_GB_per_iter": sum(vstats["d2h"].values()) / 1e9}
@@ -247,7 +257,7 @@ def main() -> int:
                                f"ffn={cfg['d_ffn']} seq={cfg['seq_len']} vocab={cfg['vocab']}, "
                                f"{cfg['M']} microbatches x {cfg['b']} sequences",
                    "hbm_budget_bytes": cfg["budget"], "arena_bytes": arena["total"],
-                   "order": a.order, "update_site": a.update_site, "gradients": a.gradients, "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
+                   "order": a.order, "update_site": a.update_site, "gradients": a.gradients, "resident_state_params": resident, "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
                    "kernels": "reference" if a.reference_kernels else "mfma"},
         "tflops": total_flops / (ms * 1e-3) / 1e12,
         "swap": {"h2d_GB_per_iter": h2d / 1e9, "d2h_GB_per_iter": d2h / 1e9,

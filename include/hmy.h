@@ -119,13 +119,28 @@ typedef struct hmy_budget {
 #define HMY_GRADIENTS_EXPORTED 0
 #define HMY_GRADIENTS_ON_DEVICE 1
 
+/* Optimizer state kept on the device (Algorithm 3 lists, beside the CPU-GPU swap, a
+ * channel that pins a tensor on the GPU).  SWAPPED: all of it lives in the caller's host
+ * arrays and crosses the link in and out at every update.  RESIDENT_IN_SPARE_BUDGET: what
+ * the HBM budget leaves unused after the arena (hmy_arena) holds optimizer state in whole
+ * chunks of k_chunk_params parameters, starting with the chunk that is updated LAST in the
+ * iteration (the first layers: their update has no compute left to hide behind) and going
+ * backwards through the update order.  A resident chunk is read from the host arrays at
+ * its first update after hmy_bind_state and from then on updated in place on the device:
+ * its (master,) m and v cross the link neither way, only its weights and gradient go out.
+ * The host arrays do not follow: hmy_sync_state writes the resident state back to them.
+ * Only with HMY_UPDATE_ON_DEVICE; ignored with ON_HOST, where the state never moves. */
+#define HMY_STATE_SWAPPED 0
+#define HMY_STATE_RESIDENT_IN_SPARE_BUDGET 1
+
 /* Configuration (Section 4.3.1): forward and backward layer packs as exclusive
  * end indices over the R layers.  Backward packs cover 0..R; forward packs cover
  * exactly the layers before the last backward pack (Algorithm 2, lines 1-2).
  * Microbatch sizes U_F = U_B = micro_batch are given by the caller.
- * order: HMY_ORDER_*, update_site: HMY_UPDATE_*, gradients: HMY_GRADIENTS_*; hmy_plan
- * returns LAYER_PACK_MAJOR, ON_DEVICE and EXPORTED (all 0), any value other than those
- * defined above is HMY_E_BAD_SCHEDULE. */
+ * order: HMY_ORDER_*, update_site: HMY_UPDATE_*, gradients: HMY_GRADIENTS_*,
+ * resident_state: HMY_STATE_*; hmy_plan returns LAYER_PACK_MAJOR, EXPORTED and SWAPPED
+ * (all 0) and the update site of its budget argument; any value other than those defined
+ * above is HMY_E_BAD_SCHEDULE. */
 typedef struct hmy_schedule {
   int32_t n_fwd_packs, n_bwd_packs;
   int32_t fwd_pack_end[HMY_MAX_LAYERS];
@@ -133,6 +148,7 @@ typedef struct hmy_schedule {
   int32_t order;
   int32_t update_site;
   int32_t gradients;
+  int32_t resident_state;
 } hmy_schedule;
 
 /* One minibatch as a list of n_micro microbatches of micro_batch sequences. */
@@ -151,7 +167,9 @@ typedef struct hmy_adam {
  * order (hmy_layout), no padding.  weights: bf16 (HMY_PREC_BF16) or fp32.
  * master: fp32, only for HMY_PREC_BF16 (NULL otherwise: the fp32 weights are the
  * master).  adam_m, adam_v, grads: fp32.  After hmy_iteration they hold the
- * updated weights/state and this iteration's accumulated gradients. */
+ * updated weights/state and this iteration's accumulated gradients (state that the
+ * schedule keeps resident on the device: after hmy_sync_state).  Binding again makes
+ * the engine read resident state afresh from the arrays. */
 typedef struct hmy_host_state {
   void *weights;
   float *master;
@@ -271,6 +289,13 @@ int hmy_bind_state(hmy_handle *h, const hmy_host_state *state);
 /* One iteration: gradients of the minibatch, Adam on every tensor, swap-byte
  * counters.  Returns with all streams idle. */
 int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out);
+/* Parameters whose optimizer state is resident on the device (0 unless the schedule says
+ * HMY_STATE_RESIDENT_IN_SPARE_BUDGET and the budget leaves room for at least one chunk). */
+int hmy_resident_params(const hmy_handle *h, uint64_t *n_params);
+/* Write the resident optimizer state back to the bound host arrays (synchronous; not part
+ * of any iteration's counters).  A no-op without resident state.  hmy_destroy does not
+ * call it: the arrays may be gone by then. */
+int hmy_sync_state(hmy_handle *h);
 int hmy_destroy(hmy_handle *h);
 /* What the next iterations time with HIP events, beyond the byte counters, the loss and
  * t_iter_s, which are always filled: level 0 (default) nothing -- timing events between

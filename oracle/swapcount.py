@@ -56,8 +56,14 @@ def _pcount(spec, a, e):
 
 
 def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False,
-                export_gradients: bool = True):
+                export_gradients: bool = True, resident_K_params: int = 0, resident_K_loaded: bool = True):
     """Layer-pack-major volumes.  Returns {'h2d': {kind: bytes}, 'd2h': {...}}.
+
+    resident_K_params: parameters whose optimizer state is pinned on the device
+    (Algorithm 3 lists a channel that keeps a tensor on the GPU beside the CPU-GPU
+    swap): their K crosses the link neither way, except once, inwards, in the first
+    iteration after the host arrays were handed over (resident_K_loaded=False).
+    Their weights and gradients move like everybody else's.
 
     export_gradients=False: the update on the device drops the gradient it has
     consumed, as in the paper, where dW never moves (no effect with update_on_host,
@@ -86,13 +92,20 @@ def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_
     h2d["ids"] = 2 * M * T * 4
     if update_on_host:
         h2d["K"] = d2h["K"] = d2h["W"] = 0
-    elif not export_gradients:
-        d2h["dW"] = 0
+    else:
+        if not 0 <= resident_K_params <= P_all:
+            raise ValueError("resident_K_params")
+        d2h["K"] -= k_B * resident_K_params
+        if resident_K_loaded:
+            h2d["K"] -= k_B * resident_K_params
+        if not export_gradients:
+            d2h["dW"] = 0
     return {"h2d": h2d, "d2h": d2h}
 
 
 def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str,
-                                 update_on_host: bool = False, export_gradients: bool = True):
+                                 update_on_host: bool = False, export_gradients: bool = True,
+                                 resident_K_params: int = 0, resident_K_loaded: bool = True):
     """Same packs, same one-pack-at-a-time residency, but every microbatch runs
     through all packs before the next one starts (the per-GPU-swap order of
     Section 3, "Intuitive Example").  Weights come in M times.  A pack's gradient
@@ -105,7 +118,8 @@ def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precis
     M - 1 times in and M times out (M - 1 out when a device update drops it instead
     of exporting it), against the paper's 2m + 2 for a system that also swaps around
     a separate update phase."""
-    out = closed_form(spec, P_F, P_B, M, b, precision, update_on_host, export_gradients)
+    out = closed_form(spec, P_F, P_B, M, b, precision, update_on_host, export_gradients, resident_K_params,
+                      resident_K_loaded)
     w_c, k_B, g_B = bytes_per_param(precision)
     P_all = _pcount(spec, 0, spec.n_layers)
     out["h2d"]["W"] *= M

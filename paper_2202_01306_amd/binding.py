@@ -21,6 +21,7 @@ HMY_PREC_FP32, HMY_PREC_BF16 = 0, 1
 HMY_ORDER_LAYER_PACK_MAJOR, HMY_ORDER_MICROBATCH_MAJOR = 0, 1
 HMY_UPDATE_ON_DEVICE, HMY_UPDATE_ON_HOST = 0, 1
 HMY_GRADIENTS_EXPORTED, HMY_GRADIENTS_ON_DEVICE = 0, 1
+HMY_STATE_SWAPPED, HMY_STATE_RESIDENT_IN_SPARE_BUDGET = 0, 1
 (HMY_OK, HMY_E_INVALID, HMY_E_BUDGET_TOO_SMALL, HMY_E_BAD_SCHEDULE, HMY_E_HIP,
  HMY_E_NOT_BOUND, HMY_E_NO_DEVICE) = (0, -1, -2, -3, -4, -5, -6)
 
@@ -54,7 +55,7 @@ def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0, update_si
 class hmy_schedule(C.Structure):
     _fields_ = [("n_fwd_packs", C.c_int32), ("n_bwd_packs", C.c_int32),
                 ("fwd_pack_end", C.c_int32 * HMY_MAX_LAYERS), ("bwd_pack_end", C.c_int32 * HMY_MAX_LAYERS),
-                ("order", C.c_int32), ("update_site", C.c_int32), ("gradients", C.c_int32)]
+                ("order", C.c_int32), ("update_site", C.c_int32), ("gradients", C.c_int32), ("resident_state", C.c_int32)]
 
 
 class hmy_minibatch(C.Structure):
@@ -105,7 +106,7 @@ class hmy_gemm_desc(C.Structure):
 
 EXPORTS = [
     "hmy_strerror", "hmy_last_error", "hmy_model_size", "hmy_layout", "hmy_profile", "hmy_plan", "hmy_estimate", "hmy_arena",
-    "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state",
+    "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state", "hmy_resident_params", "hmy_sync_state",
     "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
     "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
     "hmy_k_gemm", "hmy_k_attn_fwd", "hmy_k_attn_bwd", "hmy_k_xent", "hmy_k_adam", "hmy_host_adam",
@@ -129,11 +130,12 @@ def make_spec(cfg) -> hmy_model_spec:
                           cfg["vocab"], int(cfg["causal"]), prec, float(cfg.get("ln_eps", 1e-5)))
 
 
-def make_schedule(fwd_ends, bwd_ends, order=0, update_site=0, gradients=0) -> hmy_schedule:
+def make_schedule(fwd_ends, bwd_ends, order=0, update_site=0, gradients=0, resident_state=0) -> hmy_schedule:
     s = hmy_schedule()
     s.order = order
     s.update_site = update_site
     s.gradients = gradients
+    s.resident_state = resident_state
     s.n_fwd_packs, s.n_bwd_packs = len(fwd_ends), len(bwd_ends)
     for i, e in enumerate(fwd_ends):
         s.fwd_pack_end[i] = e
@@ -253,6 +255,16 @@ def hmy_get_schedule(h) -> hmy_schedule:
 def hmy_bind_state(h, weights_ptr, master_ptr, m_ptr, v_ptr, grads_ptr, n_params):
     st = hmy_host_state(weights_ptr, master_ptr, m_ptr, v_ptr, grads_ptr, n_params)
     _check(lib.hmy_bind_state(h, C.byref(st)))
+
+
+def hmy_resident_params(h) -> int:
+    n = C.c_uint64()
+    _check(lib.hmy_resident_params(h, C.byref(n)))
+    return n.value
+
+
+def hmy_sync_state(h):
+    _check(lib.hmy_sync_state(h))
 
 
 def hmy_iteration(h, n_micro, micro_batch, ids_ptr, targets_ptr, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8,

@@ -40,6 +40,7 @@ struct Visit {
   int slot;
   uint64_t poff;     // element offset of the pack's first parameter
   uint64_t nparams;
+  int index;         // position in hmy_handle::visits (copies of a visit keep it)
 };
 
 struct hmy_handle {
@@ -79,6 +80,14 @@ struct hmy_handle {
   bool fused_swap_out = true;
   bool k_zero_copy = false;   // the update kernel reads optimizer state straight from pinned host memory
   HostUpdater *updater = nullptr;   // Weight Update on the CPU (packs.update_site == HMY_UPDATE_ON_HOST)
+  // Optimizer state resident on the device (HMY_STATE_RESIDENT_IN_SPARE_BUDGET): whole update chunks, numbered
+  // in update order over the backward visits; the last res_chunks of them live behind the arena
+  std::vector<int> first_chunk;   // per visit: number of its first chunk (-1: forward visit)
+  int total_chunks = 0;
+  int res_chunks = 0;
+  uint64_t res_off = 0;           // byte offset of the resident region from base
+  std::vector<char> res_loaded;   // per resident chunk: read from the host arrays since the last bind
+  uint64_t chunk_state_bytes() const { return uint64_t(model.k_arrays()) * arena.res.karr_bytes; }
 };
 
 #define HIPCHK(h, call)                                                                      \
@@ -525,14 +534,26 @@ void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
   const PackPtrs pp = pack_ptrs(h, v);
   const uint64_t lo = uint64_t(u.next) * R.k_chunk_params;
   const uint64_t n = std::min<uint64_t>(R.k_chunk_params, v.nparams - lo);
-  const int r = it.k_count++ % kKRing;
-  char *ring = h->base + R.kring + uint64_t(r) * h->model.k_arrays() * R.karr_bytes;
+  const uint64_t g0 = v.poff + lo;  // element offset in the host arrays
+  const bool zc = h->fused_swap_out && h->k_zero_copy;
+  // a chunk whose state lives on the device: updated in place there, nothing of it crosses the link
+  const int rslot = h->first_chunk[v.index] + u.next - (h->total_chunks - h->res_chunks);
+  const bool resident = rslot >= 0 && !zc;
+  const int r = resident ? 0 : it.k_count++ % kKRing;
+  char *ring = resident ? h->base + h->res_off + uint64_t(rslot) * h->chunk_state_bytes()
+                        : h->base + R.kring + uint64_t(r) * h->model.k_arrays() * R.karr_bytes;
   float *r_master = mixed ? (float *)ring : nullptr;
   float *r_m = (float *)(ring + (mixed ? 1 : 0) * R.karr_bytes);
   float *r_v = (float *)(ring + (mixed ? 2 : 1) * R.karr_bytes);
-  const uint64_t g0 = v.poff + lo;  // element offset in the host arrays
-  const bool zc = h->fused_swap_out && h->k_zero_copy;
-  if (zc) {
+  if (resident) {
+    if (!h->res_loaded[rslot]) {   // first update since the arrays were bound: read it as a swapped chunk would be
+      if (mixed) h2d(h, HMY_KIND_K, r_master, h->dry ? nullptr : h->host.master + g0, n * 4, h->s_kin);
+      h2d(h, HMY_KIND_K, r_m, h->dry ? nullptr : h->host.adam_m + g0, n * 4, h->s_kin);
+      h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_kin);
+      wait(h, h->s_upd, rec(h, h->s_kin));
+      if (!h->err) h->res_loaded[rslot] = 1;
+    }
+  } else if (zc) {
     // no staging copy: the state crosses the link inside the update kernel's own loads
     h->st.h2d[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
     if (!h->dry) {
@@ -553,30 +574,33 @@ void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
   if (h->fused_swap_out) {
     // the update kernel itself writes state, weights and (if exported) gradients to the host
     // arrays (device->host over the link at vector width); bytes are counted as for copies
-    h->st.d2h[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
+    if (!resident) h->st.d2h[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
     h->st.d2h[HMY_KIND_W] += n * E;
     if (export_g) h->st.d2h[HMY_KIND_DW] += n * 4;
     if (!h->dry && !h->err) {
       const size_t a = trec(h, h->s_upd);
       KCHK(h, launch_adam_out(h->model.spec.precision, pp.dW + lo, mixed ? r_master : (const float *)(pp.W + lo * E),
-                              r_m, r_v, mixed ? h->host.master + g0 : nullptr, h->host.adam_m + g0,
-                              h->host.adam_v + g0, (char *)h->host.weights + g0 * E,
+                              r_m, r_v, !mixed ? nullptr : resident ? r_master : h->host.master + g0,
+                              resident ? r_m : h->host.adam_m + g0, resident ? r_v : h->host.adam_v + g0,
+                              (char *)h->host.weights + g0 * E,
                               export_g ? h->host.grads + g0 : nullptr, n, hp, it.compute_done, h->s_upd));
       const size_t b2 = trec(h, h->s_upd);
       span(h, a, b2, 1);
       if (zc) span(h, a, b2, 0);   // the same kernel carries the host->device half
     }
-    it.k_free[r] = rec(h, h->s_upd);
+    if (!resident) it.k_free[r] = rec(h, h->s_upd);
   } else {
     KCHK(h, launch_adam(h->model.spec.precision, pp.dW + lo, r_master, r_m, r_v, pp.W + lo * E, n, hp, h->s_upd));
     hipEvent_t e = rec(h, h->s_upd);
     wait(h, h->s_out, e);
-    if (mixed) d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.master + g0, r_master, n * 4, h->s_out);
-    d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.adam_m + g0, r_m, n * 4, h->s_out);
-    d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.adam_v + g0, r_v, n * 4, h->s_out);
+    if (!resident) {
+      if (mixed) d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.master + g0, r_master, n * 4, h->s_out);
+      d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.adam_m + g0, r_m, n * 4, h->s_out);
+      d2h(h, HMY_KIND_K, h->dry ? nullptr : h->host.adam_v + g0, r_v, n * 4, h->s_out);
+    }
     d2h(h, HMY_KIND_W, h->dry ? nullptr : (char *)h->host.weights + g0 * E, pp.W + lo * E, n * E, h->s_out);
     if (export_g) d2h(h, HMY_KIND_DW, h->dry ? nullptr : h->host.grads + g0, pp.dW + lo, n * 4, h->s_out);
-    it.k_free[r] = rec(h, h->s_out);
+    if (!resident) it.k_free[r] = rec(h, h->s_out);
   }
   if (++u.next == u.n_chunks) {   // the pack has left: its slot may be refilled
     it.slot_free[v.slot] = rec(h, h->fused_swap_out ? h->s_upd : h->s_out);
@@ -854,12 +878,40 @@ static int init_handle(hmy_handle *h, const hmy_model_spec *spec, const hmy_sche
     v.slot = int(h->visits.size() % kSlots);
     v.poff = h->model.layer_off[p.a];
     v.nparams = h->model.params_in(p.a, p.e);
+    v.index = int(h->visits.size());
     h->visits.push_back(v);
   };
   for (const Pack &q : h->packs.fwd) mk(false, false, q);
   for (int k = int(h->packs.bwd.size()) - 1; k >= 0; --k) mk(true, k == int(h->packs.bwd.size()) - 1, h->packs.bwd[k]);
+  h->first_chunk.assign(h->visits.size(), -1);
+  h->total_chunks = 0;
+  const uint64_t c = h->arena.res.k_chunk_params;
+  for (size_t vi = 0; vi < h->visits.size(); ++vi) {
+    if (!h->visits[vi].bwd) continue;
+    h->first_chunk[vi] = h->total_chunks;
+    h->total_chunks += int((h->visits[vi].nparams + c - 1) / c);
+  }
   return HMY_OK;
 }
+
+namespace {
+// calls f(resident slot, first element in the host arrays, elements) for every resident chunk
+template <typename F> void for_each_resident_chunk(const hmy_handle *h, F f) {
+  const uint64_t c = h->arena.res.k_chunk_params;
+  const int first_resident = h->total_chunks - h->res_chunks;
+  for (size_t vi = 0; vi < h->visits.size(); ++vi) {
+    const Visit &v = h->visits[vi];
+    if (!v.bwd) continue;
+    const int nc = int((v.nparams + c - 1) / c);
+    for (int k = 0; k < nc; ++k) {
+      const int slot = h->first_chunk[vi] + k - first_resident;
+      if (slot < 0) continue;
+      const uint64_t lo = uint64_t(k) * c;
+      f(slot, v.poff + lo, std::min<uint64_t>(c, v.nparams - lo));
+    }
+  }
+}
+}  // namespace
 
 extern "C" {
 
@@ -904,6 +956,14 @@ int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_m
   }
   h->device = hip_device;
   HIPCHK(h, hipSetDevice(hip_device));
+  // what the budget (and a caller's arena) leaves free behind the arena holds optimizer state
+  if (h->packs.resident_state == HMY_STATE_RESIDENT_IN_SPARE_BUDGET && h->packs.update_site == HMY_UPDATE_ON_DEVICE) {
+    uint64_t room = budget->hbm_budget_bytes > h->arena.total ? budget->hbm_budget_bytes - h->arena.total : 0;
+    if (arena) room = std::min(room, arena_bytes > h->arena.total ? arena_bytes - h->arena.total : 0);
+    h->res_chunks = int(std::min<uint64_t>(uint64_t(h->total_chunks), room / h->chunk_state_bytes()));
+    h->res_off = h->arena.total;
+    h->res_loaded.assign(size_t(h->res_chunks), 0);
+  }
   if (arena) {
     if (arena_bytes < h->arena.total || (reinterpret_cast<uintptr_t>(arena) & 255)) {
       delete h;
@@ -912,7 +972,7 @@ int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_m
     }
     h->base = static_cast<char *>(arena);
   } else {
-    HIPCHK(h, hipMalloc(reinterpret_cast<void **>(&h->base), h->arena.total));
+    HIPCHK(h, hipMalloc(reinterpret_cast<void **>(&h->base), h->arena.total + uint64_t(h->res_chunks) * h->chunk_state_bytes()));
     h->own_arena = true;
   }
   HIPCHK(h, hipStreamCreateWithFlags(&h->s_comp, hipStreamNonBlocking));
@@ -962,11 +1022,39 @@ int hmy_bind_state(hmy_handle *h, const hmy_host_state *state) {
                 (unsigned long long)h->model.n_params);
   h->host = *state;
   h->bound = true;
+  std::fill(h->res_loaded.begin(), h->res_loaded.end(), 0);   // resident state is read afresh from these arrays
   const char *zc = std::getenv("HMY_FUSED_SWAP_OUT");
   if (zc) h->fused_swap_out = std::atoi(zc) != 0;
   const char *kz = std::getenv("HMY_K_ZERO_COPY");
   if (kz) h->k_zero_copy = std::atoi(kz) != 0;
   return HMY_OK;
+}
+
+int hmy_resident_params(const hmy_handle *h, uint64_t *n_params) {
+  if (!h || !n_params) return fail(HMY_E_INVALID, "null argument");
+  uint64_t total = 0;
+  for_each_resident_chunk(h, [&](int, uint64_t, uint64_t n) { total += n; });
+  *n_params = total;
+  return HMY_OK;
+}
+
+int hmy_sync_state(hmy_handle *h) {
+  if (!h) return fail(HMY_E_INVALID, "null handle");
+  if (!h->res_chunks) return HMY_OK;
+  if (!h->bound) return fail(HMY_E_NOT_BOUND, "hmy_bind_state has not been called");
+  h->err = HMY_OK;
+  HIPCHK(h, hipSetDevice(h->device));
+  HIPCHK(h, hipDeviceSynchronize());
+  const bool mixed = h->model.spec.precision == HMY_PREC_BF16;
+  const uint64_t arr = h->arena.res.karr_bytes;
+  for_each_resident_chunk(h, [&](int slot, uint64_t g0, uint64_t n) {
+    if (!h->res_loaded[slot]) return;   // never updated since the bind: the arrays are current
+    const char *src = h->base + h->res_off + uint64_t(slot) * h->chunk_state_bytes();
+    if (mixed) HIPCHK(h, hipMemcpy(h->host.master + g0, src, n * 4, hipMemcpyDeviceToHost));
+    HIPCHK(h, hipMemcpy(h->host.adam_m + g0, src + (mixed ? 1 : 0) * arr, n * 4, hipMemcpyDeviceToHost));
+    HIPCHK(h, hipMemcpy(h->host.adam_v + g0, src + (mixed ? 2 : 1) * arr, n * 4, hipMemcpyDeviceToHost));
+  });
+  return h->err;
 }
 
 int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out) {

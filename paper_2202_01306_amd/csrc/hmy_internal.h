@@ -81,7 +81,7 @@ Reserved reserved_layout(const Model &m, int n_micro, int micro_batch);
 void layer_profile(const Model &m, int n_micro, int micro_batch, std::vector<hmy_layer_profile> *out);
 
 struct Pack { int a, e; };
-struct Packs { std::vector<Pack> fwd, bwd; int order = HMY_ORDER_LAYER_PACK_MAJOR; int update_site = HMY_UPDATE_ON_DEVICE; int gradients = HMY_GRADIENTS_EXPORTED; };
+struct Packs { std::vector<Pack> fwd, bwd; int order = HMY_ORDER_LAYER_PACK_MAJOR; int update_site = HMY_UPDATE_ON_DEVICE; int gradients = HMY_GRADIENTS_EXPORTED; int resident_state = HMY_STATE_SWAPPED; };
 
 int schedule_to_packs(const Model &m, const hmy_schedule *s, Packs *out);
 void packs_to_schedule(const Packs &p, hmy_schedule *out);

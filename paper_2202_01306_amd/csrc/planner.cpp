@@ -152,7 +152,10 @@ int schedule_to_packs(const Model &m, const hmy_schedule *s, Packs *out) {
     return fail(HMY_E_BAD_SCHEDULE, "unknown update site %d", s->update_site);
   if (s->gradients != HMY_GRADIENTS_EXPORTED && s->gradients != HMY_GRADIENTS_ON_DEVICE)
     return fail(HMY_E_BAD_SCHEDULE, "unknown gradient disposal %d", s->gradients);
+  if (s->resident_state != HMY_STATE_SWAPPED && s->resident_state != HMY_STATE_RESIDENT_IN_SPARE_BUDGET)
+    return fail(HMY_E_BAD_SCHEDULE, "unknown state residency %d", s->resident_state);
   Packs p;
+  p.resident_state = s->resident_state;
   p.order = s->order;
   p.update_site = s->update_site;
   p.gradients = s->gradients;
@@ -186,6 +189,7 @@ void packs_to_schedule(const Packs &p, hmy_schedule *out) {
   out->order = p.order;
   out->update_site = p.update_site;
   out->gradients = p.gradients;
+  out->resident_state = p.resident_state;
   for (size_t i = 0; i < p.fwd.size(); ++i) out->fwd_pack_end[i] = p.fwd[i].e;
   for (size_t i = 0; i < p.bwd.size(); ++i) out->bwd_pack_end[i] = p.bwd[i].e;
 }

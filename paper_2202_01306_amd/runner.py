@@ -182,6 +182,20 @@ class Engine:
         self._ids.a[:] = np.ascontiguousarray(ids, dtype=np.int32).reshape(-1)
         self._tgt.a[:] = np.ascontiguousarray(targets, dtype=np.int32).reshape(-1)
 
+    def resident_params(self) -> int:
+        """Parameters whose optimizer state the schedule keeps on the device."""
+        return B.hmy_resident_params(self.handle)
+
+    def sync_state(self) -> None:
+        """Write optimizer state that is resident on the device back to the TrainingState's arrays."""
+        B.hmy_sync_state(self.handle)
+
+    def rebind(self) -> None:
+        """After the TrainingState's arrays were rewritten by the caller: resident state is read from them again."""
+        st = self.state
+        B.hmy_bind_state(self.handle, st.weights.ptr, st.master.ptr if st.mixed else None, st.adam_m.ptr, st.adam_v.ptr,
+                         st.grads.ptr if st.grads is not None else None, st.n_params)
+
     def step(self, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, step=1, want_stats=True):
         return B.hmy_iteration(self.handle, self.M, self.b, self._ids.ptr, self._tgt.ptr, lr, beta1, beta2, eps, step,
                                want_stats)

@@ -61,8 +61,27 @@ def oracle_step(cfg, master, m, v, ids, tg, hp):
     return loss, grads, w2, m2, v2
 
 
+def budget_with_resident_chunks(cfg, sched, n_chunks):
+    """(budget, parameters resident): arena + room for n_chunks update chunks of optimizer state.  Chunks are
+    numbered in update order (backward packs last to first, each in pieces of k_chunk_params); the LAST ones stay."""
+    from paper_2202_01306_amd import binding as B
+    spec = B.make_spec(cfg)
+    arena = B.hmy_arena(spec, sched, cfg["M"], cfg["b"])
+    c = arena["k_chunk_params"]
+    arrays = 3 if cfg["precision"] == "bf16" else 2            # (master,) m, v
+    chunk_bytes = arrays * ((c * 4 + 255) // 256 * 256)
+    _, P_B = B.schedule_packs(sched)
+    ospec = oracle_spec(cfg)
+    sizes = []
+    for a, e in reversed(P_B):
+        P = sum(om.layer_param_count(ospec, l) for l in range(a, e))
+        sizes += [min(c, P - lo) for lo in range(0, P, c)]
+    n = min(n_chunks, len(sizes))
+    return arena["total"] + n * chunk_bytes + chunk_bytes // 2, sum(sizes[len(sizes) - n:])
+
+
 def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps=(1,), seed=0, weight_scale=1.0,
-                    lr=1e-3, order=0, update_site=0, gradients=0):
+                    lr=1e-3, order=0, update_site=0, gradients=0, resident_chunks=None):
     from paper_2202_01306_amd import binding as B
     from paper_2202_01306_amd.runner import BENCH_PACK_SEARCH, Engine, TrainingState
     tol = 1e-4 if cfg["precision"] == "fp32" else 2e-2
@@ -81,22 +100,30 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
         budget = 1 << 40
     sched = (B.make_schedule(*sched_ends, order=order, update_site=update_site, gradients=gradients)
              if sched_ends is not None else None)
+    P_res = 0
+    if resident_chunks is not None:
+        # a budget that leaves room for exactly this many chunks of optimizer state behind the arena
+        sched.resident_state = B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET
+        budget, P_res = budget_with_resident_chunks(cfg, sched, resident_chunks)
     if sched is None and (order or update_site or gradients):
         sched = B.hmy_plan(st.spec, budget, cfg["M"], cfg["b"])
         sched.order, sched.update_site, sched.gradients = order, update_site, gradients
     cf = osw.closed_form_microbatch_major if order else osw.closed_form
-    closed_form = lambda *a: cf(*a, update_on_host=bool(update_site), export_gradients=not gradients)
+    closed_form = lambda *a: cf(*a, update_on_host=bool(update_site), export_gradients=not gradients,
+                                resident_K_params=P_res, resident_K_loaded=False)   # every step follows a (re)bind
     master, m, v = f64(params), f64(m0), f64(v0)
     with Engine(st, budget, cfg["M"], cfg["b"], sched) as eng:
         P_F, P_B = eng.packs
         say(f"  packs P_F={P_F} P_B={P_B} arena={eng.arena['total']} B")
         assert eng.arena["total"] <= budget
+        assert eng.resident_params() == P_res
         eng.set_batch(ids, tg)
         for step in steps:
             f32 = lambda x: float(np.float32(x))     # the C ABI carries fp32 hyper-parameters
             hp = om.AdamHP(lr=f32(lr), beta1=f32(0.9), beta2=f32(0.999), eps=f32(1e-8), step=step)
             stats = eng.step(lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, step=step)
             loss, grads, w2, m2, v2 = oracle_step(cfg, master, m, v, ids, tg, hp)
+            eng.sync_state()          # resident optimizer state, if any, back into the host arrays
             # counters: bit-exact against the closed form
             want = closed_form(oracle_spec(cfg), P_F, P_B, cfg["M"], cfg["b"], cfg["precision"])
             assert stats["h2d"] == want["h2d"] and stats["d2h"] == want["d2h"]
@@ -142,6 +169,8 @@ def run_and_compare(cfg, *, sched_ends=None, budget=None, zero_state=True, steps
             master = f64({k: a.astype(np.float32) for k, a in w2.items()})
             m = f64({k: a.astype(np.float32) for k, a in m2.items()})
             v = f64({k: a.astype(np.float32) for k, a in v2.items()})
+            if P_res:
+                eng.rebind()          # the arrays were rewritten: resident state is read from them again
     return stats
 
 
@@ -272,6 +301,66 @@ def test_gradient_array_is_required_when_it_would_be_written():
             Engine(st, 1 << 40, cfg["M"], cfg["b"], B.make_schedule([5], [1, 5, 6], **kw))
         assert e.value.code == B.HMY_E_INVALID
         st.close()
+
+
+# ---- optimizer state resident on the device in what the budget leaves free ----
+
+@pytest.mark.parametrize("order", [0, 1])
+@pytest.mark.parametrize("ends,chunks", [(([5], [1, 5, 6]), 1), (([5], [1, 5, 6]), 2), (([1, 2, 3, 4, 5], [1, 2, 3, 4, 5, 6]), 4),
+                                         (([], [6]), 99)])
+def test_resident_state_tiny_fp32(ends, chunks, order):
+    say(f"tiny fp32, {chunks} resident chunk(s), order {order}, schedule {ends}")
+    cfg = dict(synth.CONFIGS["tiny"], M=3)
+    run_and_compare(cfg, sched_ends=ends, zero_state=False, steps=(3, 4), weight_scale=4.0, order=order,
+                    resident_chunks=chunks)
+
+
+def test_resident_state_bf16_gradients_dropped():
+    say("bf16, two resident chunks, gradients not exported")
+    cfg = tiny_cfg(n_blocks=4, d_model=128, n_heads=2, d_ffn=512, seq_len=128, vocab=1000, precision="bf16", M=3, b=2)
+    stats = run_and_compare(cfg, sched_ends=([2, 5], [1, 2, 4, 5, 6]), zero_state=False, steps=(5, 6), weight_scale=3.0,
+                            gradients=1, resident_chunks=2)
+    assert stats["d2h"]["dW"] == 0
+
+
+def test_resident_state_three_iterations_without_touching_the_host_arrays():
+    """Steady state: after the first iteration the resident chunks' state crosses the link neither way, the host
+    arrays hold it only after hmy_sync_state, and three iterations end where the oracle's three end."""
+    from paper_2202_01306_amd import binding as B
+    from paper_2202_01306_amd.runner import Engine, TrainingState
+    say("tiny fp32, three iterations with resident state, one sync at the end")
+    cfg = dict(synth.CONFIGS["tiny"], M=3)
+    params = synth.gen_params(cfg, 3, bench_init=False)
+    m0, v0 = synth.gen_adam_state(cfg, 3, zero=False)
+    ids = synth.gen_tokens(cfg, 3)
+    tg = synth.gen_targets(cfg, ids, 3)
+    sched = B.make_schedule([5], [1, 5, 6], resident_state=B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET)
+    budget, P_res = budget_with_resident_chunks(cfg, sched, 2)
+    assert P_res > 0
+    st = TrainingState(cfg)
+    st.load(params, m0, v0)
+    master, m, v = f64(params), f64(m0), f64(v0)
+    ospec = oracle_spec(cfg)
+    with Engine(st, budget, cfg["M"], cfg["b"], sched) as eng:
+        P_F, P_B = eng.packs
+        assert eng.resident_params() == P_res
+        eng.set_batch(ids, tg)
+        m_before = st.adam_m.a.copy()
+        for i, step in enumerate((2, 3, 4)):
+            f32 = lambda x: float(np.float32(x))
+            hp = om.AdamHP(lr=f32(1e-3), beta1=f32(0.9), beta2=f32(0.999), eps=f32(1e-8), step=step)
+            stats = eng.step(lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, step=step)
+            want = osw.closed_form(ospec, P_F, P_B, cfg["M"], cfg["b"], "fp32", resident_K_params=P_res,
+                                   resident_K_loaded=i > 0)
+            assert stats["h2d"] == want["h2d"] and stats["d2h"] == want["d2h"], step
+            _, _, master, m, v = oracle_step(cfg, master, m, v, ids, tg, hp)
+        # resident m never came home: P_res elements of the host array are as they were handed over
+        assert int((st.adam_m.a == m_before).sum()) >= P_res
+        eng.sync_state()
+        got_w, got_m, got_v = st.named("weights"), st.named("m"), st.named("v")
+        for k in master:
+            assert max_rel_err(got_w[k], master[k]) < 1e-4, k
+            assert max_rel_err(got_m[k], m[k]) < 1e-4 and max_rel_err(got_v[k], v[k]) < 2.5e-4, k
 
 
 def test_single_microbatch_single_sequence():

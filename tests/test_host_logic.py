@@ -355,5 +355,11 @@ def test_error_paths_return_codes_not_crashes():
     with pytest.raises(B.HmyError) as e:                # nor this way to dispose of gradients
         B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4], gradients=2), 2, 2)
     assert e.value.code == B.HMY_E_BAD_SCHEDULE
+    with pytest.raises(B.HmyError) as e:                # nor this residency
+        B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4], resident_state=5), 2, 2)
+    assert e.value.code == B.HMY_E_BAD_SCHEDULE
+    # without an engine (and a budget) there is nothing resident: the dry count is the swapped one
+    assert B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4], resident_state=1), 2, 2) == \
+        B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4]), 2, 2)
     assert B.lib.hmy_strerror(B.HMY_E_HIP) == b"HIP runtime error"
     assert B.lib.hmy_model_size(None, None, None) == B.HMY_E_INVALID

@@ -257,6 +257,38 @@ def test_gradients_dropped_on_the_device_is_the_papers_own_count():
                     osw.closed_form_microbatch_major(*args, update_on_host=True)
 
 
+def test_resident_optimizer_state_leaves_the_link_alone():
+    """Optimizer state pinned on the device (Algorithm 3's GPU-pinned channel): for P_res resident parameters
+    the appendix's K volume 2 |K| shrinks by their share both ways; the first iteration still reads them once;
+    W, dW, checkpoints do not change; nothing to pin when the update runs on the host."""
+    spec = om.Spec(4, 8, 2, 24, 4, 16)
+    R = spec.n_layers
+    P = sum(om.layer_param_count(spec, l) for l in range(R))
+    for precision in ("fp32", "bf16"):
+        w_c, k_B, g_B = osw.bytes_per_param(precision)
+        for M, b in ((1, 1), (3, 2)):
+            for P_B in list(all_packings(R))[::5]:
+                last_start = P_B[-1][0]
+                P_F = [(0, last_start)] if last_start else []
+                args = (spec, P_F, P_B, M, b, precision)
+                base = osw.closed_form(*args)
+                assert base["h2d"]["K"] + base["d2h"]["K"] == osw.paper_K_volume(1, k_B * P)
+                for P_res in (0, 1, P // 3, P):
+                    for cf in (osw.closed_form, osw.closed_form_microbatch_major):
+                        plain = cf(*args)
+                        steady = cf(*args, resident_K_params=P_res)
+                        first = cf(*args, resident_K_params=P_res, resident_K_loaded=False)
+                        assert steady["h2d"]["K"] == steady["d2h"]["K"] == k_B * (P - P_res)
+                        assert first["h2d"]["K"] == k_B * P and first["d2h"]["K"] == k_B * (P - P_res)
+                        for d in ("h2d", "d2h"):
+                            for k in osw.KINDS:
+                                if k != "K":
+                                    assert plain[d][k] == steady[d][k] == first[d][k]
+                        assert cf(*args, update_on_host=True, resident_K_params=P_res) == cf(*args, update_on_host=True)
+                with pytest.raises(ValueError):
+                    osw.closed_form(*args, resident_K_params=P + 1)
+
+
 def test_weight_volume_reduces_to_3W_when_last_pack_is_counted_twice():
     spec = om.Spec(3, 8, 2, 16, 4, 16)
     P_B = [(0, 2), (2, 4), (4, 5)]
