@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+HOST_LINK_GBPS_ALONE = 54.0    # pinned host <-> HBM, one direction, nothing else running (measured on the GPU machine)
 PEAK_FP32_TFLOPS = 157.3
 VARIANTS = ("gemm_mfma<A[M,K],B[N,K]> (forward, recompute)", "gemm_mfma<A[M,K],B[K,N]> (input gradient)",
             "gemm_mfma<A[K,M],B[N,K]>", "gemm_mfma<A[K,M],B[K,N]> (weight gradient)")
@@ -284,6 +285,12 @@ def main() -> int:
                      "event_pair_us_subtracted_per_launch": prof["t_event_pair_s"] * 1e6,
                      "all_variants_TFLOPs": [prof["gemm_flops"][i] / max(prof["gemm_s"][i], 1e-12) / 1e12
                                              if prof["gemm_calls"][i] else None for i in range(4)]},
+        # the whole step against what bounds it from below: all of its flops at the MFMA peak, or the busier
+        # direction of the host link at the rate the link gives with the device otherwise idle (measured, 54 GB/s)
+        "step_bound": {"mfma_ms": total_flops / (peak * 1e12) * 1e3,
+                       "host_link_ms": max(h2d, d2h) / (HOST_LINK_GBPS_ALONE * 1e9) * 1e3,
+                       "host_link_GBps_alone": HOST_LINK_GBPS_ALONE,
+                       "frac": max(total_flops / (peak * 1e12), max(h2d, d2h) / (HOST_LINK_GBPS_ALONE * 1e9)) / (ms * 1e-3)},
         "loss": stats["loss"],
     }
     if variants:
