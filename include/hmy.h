@@ -135,7 +135,7 @@ typedef struct hmy_budget {
 
 /* Configuration (Section 4.3.1): forward and backward layer packs as exclusive
  * end indices over the R layers.  Backward packs cover 0..R; forward packs cover
- * exactly the layers before the last backward pack (Algorithm 2, lines 1-2).
+ * exactly the layers before the last backward pack (the opening steps of Algorithm 2).
  * Microbatch sizes U_F = U_B = micro_batch are given by the caller.
  * order: HMY_ORDER_*, update_site: HMY_UPDATE_*, gradients: HMY_GRADIENTS_*,
  * resident_state: HMY_STATE_*; hmy_plan returns LAYER_PACK_MAJOR, EXPORTED and SWAPPED
