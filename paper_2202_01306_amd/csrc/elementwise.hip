@@ -596,26 +596,35 @@ template <bool MIXED>
 __global__ void k_adam_out(const float *grad, const float *in_master, const float *in_m, const float *in_v,
                            float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
                            float lr, float b1, float b2, float eps, float inv_bc1, float inv_bc2) {
+  // A wavefront takes 512 consecutive elements per step as two runs of 256: lane l holds elements
+  // 4 l .. 4 l + 3 of each run, so that every store instruction writes one contiguous KiB (half a KiB for the
+  // bf16 weight).  With eight consecutive elements per lane each instruction left 16-byte holes between
+  // lanes, which the path to the host has to stitch together from two instructions.
+  const int lane = threadIdx.x % kWave;
+  const uint64_t wave = (uint64_t(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
   const uint64_t stride = uint64_t(gridDim.x) * blockDim.x * 8;
-  for (uint64_t base = (uint64_t(blockIdx.x) * blockDim.x + threadIdx.x) * 8; base < n; base += stride) {
+  for (uint64_t wb = wave * 512; wb < n; wb += stride) {
     float g[8], w[8], m[8], v[8];
-    const bool full = base + 8 <= n;
-    if (full) {
+    uint64_t at[2];
+    bool full[2];
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        *reinterpret_cast<float4 *>(g + 4 * h) = *reinterpret_cast<const float4 *>(grad + base + 4 * h);
-        *reinterpret_cast<float4 *>(w + 4 * h) = *reinterpret_cast<const float4 *>(in_master + base + 4 * h);
-        *reinterpret_cast<float4 *>(m + 4 * h) = *reinterpret_cast<const float4 *>(in_m + base + 4 * h);
-        *reinterpret_cast<float4 *>(v + 4 * h) = *reinterpret_cast<const float4 *>(in_v + base + 4 * h);
-      }
-    } else {
+    for (int h = 0; h < 2; ++h) {
+      at[h] = wb + 256 * h + 4 * lane;
+      full[h] = at[h] + 4 <= n;
+      if (full[h]) {
+        *reinterpret_cast<float4 *>(g + 4 * h) = *reinterpret_cast<const float4 *>(grad + at[h]);
+        *reinterpret_cast<float4 *>(w + 4 * h) = *reinterpret_cast<const float4 *>(in_master + at[h]);
+        *reinterpret_cast<float4 *>(m + 4 * h) = *reinterpret_cast<const float4 *>(in_m + at[h]);
+        *reinterpret_cast<float4 *>(v + 4 * h) = *reinterpret_cast<const float4 *>(in_v + at[h]);
+      } else {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const bool ok = base + k < n;
-        g[k] = ok ? grad[base + k] : 0.f;
-        w[k] = ok ? in_master[base + k] : 0.f;
-        m[k] = ok ? in_m[base + k] : 0.f;
-        v[k] = ok ? in_v[base + k] : 0.f;
+        for (int k = 0; k < 4; ++k) {
+          const bool ok = at[h] + k < n;
+          g[4 * h + k] = ok ? grad[at[h] + k] : 0.f;
+          w[4 * h + k] = ok ? in_master[at[h] + k] : 0.f;
+          m[4 * h + k] = ok ? in_m[at[h] + k] : 0.f;
+          v[4 * h + k] = ok ? in_v[at[h] + k] : 0.f;
+        }
       }
     }
 #pragma unroll
@@ -624,31 +633,33 @@ __global__ void k_adam_out(const float *grad, const float *in_master, const floa
       v[k] = b2 * v[k] + (1.f - b2) * g[k] * g[k];
       w[k] = w[k] - lr * (m[k] * inv_bc1) / (sqrtf(v[k] * inv_bc2) + eps);
     }
-    if (full) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        *reinterpret_cast<float4 *>(out_m + base + 4 * h) = *reinterpret_cast<const float4 *>(m + 4 * h);
-        *reinterpret_cast<float4 *>(out_v + base + 4 * h) = *reinterpret_cast<const float4 *>(v + 4 * h);
-        if (out_g) *reinterpret_cast<float4 *>(out_g + base + 4 * h) = *reinterpret_cast<const float4 *>(g + 4 * h);
-        if (MIXED) *reinterpret_cast<float4 *>(out_master + base + 4 * h) = *reinterpret_cast<const float4 *>(w + 4 * h);
-        else *reinterpret_cast<float4 *>(static_cast<float *>(out_w) + base + 4 * h) = *reinterpret_cast<const float4 *>(w + 4 * h);
-      }
-      if (MIXED) {
-        Vec16<bf16_t> o;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) o.v[k] = from_f32<bf16_t>(w[k]);
-        store16(static_cast<bf16_t *>(out_w) + base, o);
-      }
-    } else {
-      for (int k = 0; k < 8 && base + k < n; ++k) {
-        out_m[base + k] = m[k];
-        out_v[base + k] = v[k];
-        if (out_g) out_g[base + k] = g[k];
+    for (int h = 0; h < 2; ++h) {
+      if (full[h]) {
+        *reinterpret_cast<float4 *>(out_m + at[h]) = *reinterpret_cast<const float4 *>(m + 4 * h);
+        *reinterpret_cast<float4 *>(out_v + at[h]) = *reinterpret_cast<const float4 *>(v + 4 * h);
+        if (out_g) *reinterpret_cast<float4 *>(out_g + at[h]) = *reinterpret_cast<const float4 *>(g + 4 * h);
         if (MIXED) {
-          out_master[base + k] = w[k];
-          static_cast<bf16_t *>(out_w)[base + k] = from_f32<bf16_t>(w[k]);
+          *reinterpret_cast<float4 *>(out_master + at[h]) = *reinterpret_cast<const float4 *>(w + 4 * h);
+          bf16_t o[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) o[k] = from_f32<bf16_t>(w[4 * h + k]);
+          *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(out_w) + at[h]) = *reinterpret_cast<const uint2 *>(o);
         } else {
-          static_cast<float *>(out_w)[base + k] = w[k];
+          *reinterpret_cast<float4 *>(static_cast<float *>(out_w) + at[h]) = *reinterpret_cast<const float4 *>(w + 4 * h);
+        }
+      } else {
+        for (int k = 0; k < 4 && at[h] + k < n; ++k) {
+          const uint64_t j = at[h] + k;
+          out_m[j] = m[4 * h + k];
+          out_v[j] = v[4 * h + k];
+          if (out_g) out_g[j] = g[4 * h + k];
+          if (MIXED) {
+            out_master[j] = w[4 * h + k];
+            static_cast<bf16_t *>(out_w)[j] = from_f32<bf16_t>(w[4 * h + k]);
+          } else {
+            static_cast<float *>(out_w)[j] = w[4 * h + k];
+          }
         }
       }
     }
