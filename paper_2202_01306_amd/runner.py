@@ -154,11 +154,14 @@ class Engine:
     """One hmy handle bound to a TrainingState."""
 
     def __init__(self, state: TrainingState, budget_bytes: int, n_micro: int, micro_batch: int, sched=None,
-                 device: int = 0, search: int = 0):
+                 device: int = 0, search: int = 0, arena_ptr: int = 0, arena_bytes: int = 0):
+        """arena_ptr / arena_bytes: device memory of the caller's (256-byte aligned, at least the arena's size) for the
+        engine to live in, instead of an allocation of its own; the caller keeps it alive until close()."""
         self.state = state
         self.M, self.b = n_micro, micro_batch
         # fails with HMY_E_NO_DEVICE when there is no GPU: there is no CPU fallback
-        self.handle = B.hmy_create(state.spec, budget_bytes, n_micro, micro_batch, sched, device, search=search)
+        self.handle = B.hmy_create(state.spec, budget_bytes, n_micro, micro_batch, sched, device, arena_ptr=arena_ptr,
+                                   arena_bytes=arena_bytes, search=search)
         self._ids = None
         self._tgt = None
         try:

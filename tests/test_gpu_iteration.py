@@ -363,6 +363,61 @@ def test_resident_state_three_iterations_without_touching_the_host_arrays():
             assert max_rel_err(got_m[k], m[k]) < 1e-4 and max_rel_err(got_v[k], v[k]) < 2.5e-4, k
 
 
+def test_engine_in_a_callers_arena():
+    """hmy_create with device memory of the caller's: same results as with its own allocation, nothing written
+    outside the arena's size, too small an arena refused, and resident state limited to what the arena has room for."""
+    from paper_2202_01306_amd import binding as B
+    from paper_2202_01306_amd.runner import Engine, TrainingState
+    say("tiny fp32 in a caller-provided arena")
+    cfg = dict(synth.CONFIGS["tiny"], M=3)
+    params = synth.gen_params(cfg, 5, bench_init=False)
+    m0, v0 = synth.gen_adam_state(cfg, 5, zero=False)
+    ids = synth.gen_tokens(cfg, 5)
+    tg = synth.gen_targets(cfg, ids, 5)
+    sched = B.make_schedule([5], [1, 5, 6])
+    need = B.hmy_arena(B.make_spec(cfg), sched, cfg["M"], cfg["b"])["total"]
+    guard = 4096
+
+    def one_step(**kw):
+        st = TrainingState(cfg)
+        st.load(params, m0, v0)
+        with Engine(st, 1 << 40, cfg["M"], cfg["b"], kw.pop("sched", sched), **kw) as eng:
+            eng.set_batch(ids, tg)
+            stats = eng.step(lr=1e-3, step=3)
+            res = eng.resident_params()
+            eng.sync_state()
+        out = (stats, st.named("weights"), st.named("m"), st.named("grads"), res)
+        st.close()
+        return out
+
+    own = one_step()
+    buf = torch.full((need + guard,), 0x5A, dtype=torch.uint8, device="cuda")
+    assert buf.data_ptr() % 256 == 0
+    mine = one_step(arena_ptr=buf.data_ptr(), arena_bytes=need)
+    assert bool((buf[need:] == 0x5A).all())                      # nothing beyond the arena was touched
+    assert mine[0]["h2d"] == own[0]["h2d"] and mine[0]["d2h"] == own[0]["d2h"] and mine[4] == 0
+    assert abs(mine[0]["loss"] - own[0]["loss"]) <= 1e-6 * abs(own[0]["loss"])
+    for k in own[1]:
+        assert max_rel_err(mine[1][k], own[1][k]) < 1e-5 and max_rel_err(mine[2][k], own[2][k]) < 1e-5, k
+        assert max_rel_err(mine[3][k], own[3][k]) < 1e-5, k
+    with pytest.raises(B.HmyError) as e:
+        one_step(arena_ptr=buf.data_ptr(), arena_bytes=need - 256)
+    assert e.value.code == B.HMY_E_INVALID
+    with pytest.raises(B.HmyError) as e:
+        one_step(arena_ptr=buf.data_ptr() + 64, arena_bytes=need)  # not 256-byte aligned
+    assert e.value.code == B.HMY_E_INVALID
+    # resident state lives behind the arena in the caller's memory: one chunk's worth of room, one chunk resident
+    rs = B.make_schedule([5], [1, 5, 6], resident_state=B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET)
+    _, P_one = budget_with_resident_chunks(cfg, rs, 1)
+    c = B.hmy_arena(B.make_spec(cfg), rs, cfg["M"], cfg["b"])["k_chunk_params"]
+    chunk_bytes = 2 * ((c * 4 + 255) // 256 * 256)
+    big = torch.full((need + chunk_bytes + guard,), 0x5A, dtype=torch.uint8, device="cuda")
+    res_run = one_step(sched=rs, arena_ptr=big.data_ptr(), arena_bytes=need + chunk_bytes + 100)
+    assert res_run[4] == P_one and bool((big[need + chunk_bytes:] == 0x5A).all())
+    for k in own[1]:
+        assert max_rel_err(res_run[1][k], own[1][k]) < 1e-5 and max_rel_err(res_run[2][k], own[2][k]) < 1e-5, k
+
+
 def test_single_microbatch_single_sequence():
     say("fp32, M=1, b=1")
     cfg = tiny_cfg(n_blocks=2, d_model=64, n_heads=2, d_ffn=128, seq_len=16, vocab=50, M=1, b=1)
