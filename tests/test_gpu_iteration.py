@@ -363,6 +363,40 @@ def test_resident_state_three_iterations_without_touching_the_host_arrays():
             assert max_rel_err(got_m[k], m[k]) < 1e-4 and max_rel_err(got_v[k], v[k]) < 2.5e-4, k
 
 
+def test_profiling_levels_time_what_they_say_and_change_no_result():
+    from paper_2202_01306_amd import binding as B
+    from paper_2202_01306_amd.runner import Engine, TrainingState
+    say("profiling levels 0, 1, 2 on a small bf16 model")
+    cfg = tiny_cfg(n_blocks=2, d_model=128, n_heads=2, d_ffn=512, seq_len=128, vocab=1000, precision="bf16", M=2, b=2)
+    params = synth.gen_params(cfg, 7, bench_init=False)
+    m0, v0 = synth.gen_adam_state(cfg, 7, zero=False)
+    ids = synth.gen_tokens(cfg, 7)
+    tg = synth.gen_targets(cfg, ids, 7)
+    seen = {}
+    for level in (0, 1, 2):
+        st = TrainingState(cfg)
+        st.load(params, m0, v0)
+        with Engine(st, 1 << 40, cfg["M"], cfg["b"], B.make_schedule([1, 2], [1, 2, 4])) as eng:
+            eng.set_batch(ids, tg)
+            B.hmy_set_profiling(eng.handle, level)
+            stats = eng.step(lr=1e-3, step=2)
+            if level == 2:
+                with pytest.raises(B.HmyError) as e:
+                    B.hmy_set_profiling(eng.handle, 3)
+                assert e.value.code == B.HMY_E_INVALID
+        seen[level] = (stats, st.weights.a.copy())
+        st.close()
+        assert stats["t_iter_s"] > 0 and sum(stats["gemm_calls"]) > 0 and sum(stats["gemm_flops"]) > 0
+        timed_copies = stats["t_compute_s"] > 0 and stats["t_h2d_busy_s"] > 0 and stats["t_d2h_busy_s"] > 0
+        timed_gemms = sum(stats["gemm_s"]) > 0 and stats["t_event_pair_s"] > 0
+        assert timed_copies == (level >= 1) and timed_gemms == (level >= 2), (level, stats)
+    for level in (1, 2):     # same bytes, same launches; the loss and the weights agree up to the order of atomic adds
+        assert seen[level][0]["h2d"] == seen[0][0]["h2d"] and seen[level][0]["d2h"] == seen[0][0]["d2h"]
+        assert seen[level][0]["gemm_calls"] == seen[0][0]["gemm_calls"]
+        assert abs(seen[level][0]["loss"] - seen[0][0]["loss"]) <= 1e-5 * abs(seen[0][0]["loss"])
+        assert int((seen[level][1] != seen[0][1]).sum()) <= seen[0][1].size // 100
+
+
 def test_engine_in_a_callers_arena():
     """hmy_create with device memory of the caller's: same results as with its own allocation, nothing written
     outside the arena's size, too small an arena refused, and resident state limited to what the arena has room for."""
