@@ -344,7 +344,9 @@ int hmy_k_colsum(int32_t prec, const void *a, float *out, int32_t T, int32_t N, 
  * gelu_out = gelu(C).  A is [M,K] (ta=0) or stored [K,M] (ta=1); B is stored
  * [N,K] (tb=0: y = x W^T) or [K,N] (tb=1).  A, B, bias, res, gelu_out have
  * element type E(prec); C has type E, or fp32 if c_fp32.  accumulate: C += (only
- * with c_fp32).  Leading dimensions in elements. */
+ * with c_fp32).  Leading dimensions in elements.  gelu_out may be C itself: then C
+ * ends up holding gelu of the (rounded) result and nothing else is stored -- what a
+ * forward pass wants that keeps no pre-activation for a backward pass. */
 typedef struct hmy_gemm_desc {
   int32_t prec, M, N, K;
   int32_t ta, tb, c_fp32, accumulate;

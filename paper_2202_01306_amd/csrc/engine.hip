@@ -303,7 +303,7 @@ BlockPtrs block_ptrs(const hmy_handle *h, char *region) {
 // the resident boundary buffer (in place); in a backward visit they are distinct
 // saved buffers and y == nullptr skips the second MLP GEMM (output not needed).
 void block_forward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, const BlockPtrs &A,
-                   const char *x_in, char *x_mid, char *y) {
+                   const char *x_in, char *x_mid, char *y, bool keep_preactivation) {
   const hmy_model_spec &s = h->model.spec;
   const int prec = s.precision, T = h->b * s.seq_len, d = s.d_model, f = s.d_ffn;
   const int t0 = h->model.first_tensor[layer];
@@ -313,7 +313,8 @@ void block_forward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer,
   KCHK(h, launch_attn_fwd(prec, A.qkv, A.o, A.lse, h->b, s.seq_len, s.n_heads, d / s.n_heads, s.causal, h->s_comp));
   linear_fwd(h, A.o, W(WO), W(BO), x_in, x_mid, nullptr, T, d, d);
   KCHK(h, launch_layernorm_fwd(prec, x_mid, W(LN2_G), W(LN2_B), A.hh, A.ln2_mean, A.ln2_rstd, T, d, s.ln_eps, h->s_comp));
-  linear_fwd(h, A.hh, W(W1), W(B1), nullptr, A.u, A.g, T, f, d);
+  // the MLP's pre-activation u is only read by a backward pass: without one, only gelu(u) is stored
+  linear_fwd(h, A.hh, W(W1), W(B1), nullptr, keep_preactivation ? A.u : A.g, A.g, T, f, d);
   if (y) linear_fwd(h, A.g, W(W2), W(B2), x_mid, y, nullptr, T, d, f);
 }
 
@@ -452,7 +453,7 @@ void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int 
       KCHK(h, launch_embed_fwd(s.precision, ids_dev(h, mb), wptr(h, v, pp, t0), wptr(h, v, pp, t0 + 1), X, T, d,
                                s.seq_len, s.vocab, h->s_comp));
     } else {
-      block_forward(h, v, pp, layer, scratch, X, X, X);
+      block_forward(h, v, pp, layer, scratch, X, X, X, false);
     }
   }
 }
@@ -500,7 +501,7 @@ void backward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int
                                d, s.seq_len, s.vocab, h->s_comp));
     } else if (layer <= L) {
       const BlockPtrs A = block_ptrs(h, act_region(h, v.pack, layer));
-      block_forward(h, v, pp, layer, A, input_of(layer), A.x_mid, has_next ? input_of(layer + 1) : nullptr);
+      block_forward(h, v, pp, layer, A, input_of(layer), A.x_mid, has_next ? input_of(layer + 1) : nullptr, true);
     } else {
       head_forward_backward(h, v, pp, layer, act_region(h, v.pack, layer), input_of(layer), mb, D, it.inv_ntgt);
     }

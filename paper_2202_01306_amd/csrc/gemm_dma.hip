@@ -198,7 +198,8 @@ struct Epi {
       Vec16<bf16_t> o;
 #pragma unroll
       for (int k = 0; k < 8; ++k) o.v[k] = from_f32<bf16_t>(v[k]);
-      store16(static_cast<bf16_t *>(p.C) + ci, o);
+      // gelu_out == C: only the activation is wanted (a forward pass that keeps nothing for a backward pass)
+      if (p.gelu_out != static_cast<bf16_t *>(p.C)) store16(static_cast<bf16_t *>(p.C) + ci, o);
       if (p.gelu_out) {
         Vec16<bf16_t> g;
 #pragma unroll

@@ -162,6 +162,8 @@ def _gemm_case(prec, pc, dt, tol, M, N, K, ta, tb, c_fp32, accumulate, bias, res
     if accumulate:
         ref = ref + host(Cd)[:, :N]
     gout = torch.zeros(M, ldc, device="cuda", dtype=dt) if gelu else None
+    if gelu == "in place":
+        gout = Cd                       # only gelu(C) is wanted: it replaces C
     B.hmy_set_kernel_path(use_mfma)
     try:
         B.hmy_k_gemm(pc, M, N, K, dev(A, dt), lda, dev(Bm, dt), ldb, Cd, ldc, ta=ta, tb=tb, c_fp32=c_fp32,
@@ -171,6 +173,11 @@ def _gemm_case(prec, pc, dt, tol, M, N, K, ta, tb, c_fp32, accumulate, bias, res
     finally:
         B.hmy_set_kernel_path(True)
     scale = math.sqrt(K)   # entries are sums of K unit-variance products
+    if gelu == "in place":
+        gref = om.gelu_fwd(synth.round_bf16(ref.astype(np.float32)).astype(np.float64) if prec == "bf16" else ref)
+        # where the rounding of C falls on the other side the activation moves by one bf16 step of C
+        assert np.abs(got[:, :N] - gref).max() / max(np.abs(gref).max(), scale) < tol, "gelu in place"
+        return
     assert np.abs(got[:, :N] - ref).max() / max(np.abs(ref).max(), scale) < tol, "C"
     if pad:   # columns beyond N are never written
         assert np.array_equal(got[:, N:], host(dev(c0, cdt))[:, N:])
@@ -202,6 +209,8 @@ def test_gemm_bf16_epilogues(use_mfma):
     _gemm_case(*args, 200, 136, 72, 0, 0, 0, 0, True, False, False, use_mfma)       # bias
     _gemm_case(*args, 200, 136, 72, 0, 0, 0, 0, True, True, False, use_mfma)        # bias + residual
     _gemm_case(*args, 200, 136, 72, 0, 0, 0, 0, True, False, True, use_mfma)        # bias + gelu output
+    _gemm_case(*args, 200, 136, 72, 0, 0, 0, 0, True, False, "in place", use_mfma)  # bias + gelu, the only output
+    _gemm_case(*args, 384, 256, 128, 0, 0, 0, 0, True, False, "in place", use_mfma) # ... on whole tiles (16-byte stores)
     _gemm_case(*args, 200, 136, 72, 0, 0, 1, 0, False, False, False, use_mfma)      # fp32 C (logits)
     _gemm_case(*args, 136, 72, 200, 1, 1, 1, 1, False, False, False, use_mfma)      # wgrad: fp32 C +=
     _gemm_case(*args, 100, 1001, 64, 0, 0, 1, 0, False, False, False, use_mfma, 7)  # ragged N, padded ldc
@@ -215,6 +224,7 @@ def test_gemm_fp32(ta, tb):
     _gemm_case(*args, 130, 72, 100, ta, tb, 0, 0, True, True, False, True)
     _gemm_case(*args, 64, 200, 33, ta, tb, 1, 1, False, False, False, True)
     _gemm_case(*args, 128, 512, 128, ta, tb, 0, 0, True, False, True, True)
+    _gemm_case(*args, 128, 512, 128, ta, tb, 0, 0, True, False, "in place", True)
 
 
 def test_gemm_rejects_bad_arguments():
