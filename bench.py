@@ -285,6 +285,14 @@ def main() -> int:
                      "event_pair_us_subtracted_per_launch": prof["t_event_pair_s"] * 1e6,
                      "all_variants_TFLOPs": [prof["gemm_flops"][i] / max(prof["gemm_s"][i], 1e-12) / 1e12
                                              if prof["gemm_calls"][i] else None for i in range(4)]},
+        # the kernels that write to the host (fused Adam + write-back, checkpoint copies) own the other stream:
+        # bytes they moved over the time they ran (events of the level-1 step) against the link alone
+        "roofline_host_link": {"bound": "host_link", "kernel": "k_adam_out + k_copy_out (device->host)",
+                               "achieved": d2h / 1e9 / max(stats["t_d2h_busy_s"], 1e-12), "peak": HOST_LINK_GBPS_ALONE,
+                               "unit": "GB/s", "frac": d2h / 1e9 / max(stats["t_d2h_busy_s"], 1e-12) / HOST_LINK_GBPS_ALONE,
+                               "busy_ms": stats["t_d2h_busy_s"] * 1e3,
+                               "note": "peak = what the same kernels reach with nothing else running (measured); "
+                                       "throttled on purpose beside the compute stream"},
         # the whole step against what bounds it from below: all of its flops at the MFMA peak, or the busier
         # direction of the host link at the rate the link gives with the device otherwise idle (measured, 54 GB/s)
         "step_bound": {"mfma_ms": total_flops / (peak * 1e12) * 1e3,
