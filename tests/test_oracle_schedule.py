@@ -1,6 +1,8 @@
 """Pins for the layer-pack-major driver, the swap-volume counts and the
 balanced-time packing of the oracle."""
 import itertools
+import math
+import os
 
 import numpy as np
 import pytest
@@ -118,6 +120,61 @@ def test_residency_machine_reproduces_the_papers_weight_volumes():
         # jit-compute shares the last pack between the passes
         i, o = osw.residency_machine(osw.steps_layer_pack_major(R, m, True), pack_bytes, False)
         assert (i, o) == (2 * W - pack_bytes[-1], W)
+
+
+def _golden_rows(name):
+    path = os.path.join(os.path.dirname(__file__), "golden", name)
+    return [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+
+
+def test_paper_stated_swap_volumes():
+    """tests/golden/paper_swap_volumes.txt holds the volumes the paper states (Section 3 'Intuitive Example',
+    appendix 'Additional Swap Analysis'), typed from its text.  The residency machine, which knows nothing of
+    those formulas, reproduces every single-GPU row; the N-GPU rows are N independent copies (data parallelism)
+    or one copy (pipeline); the oracle's own statement of the formulas agrees with all of them."""
+    rows = _golden_rows("paper_swap_volumes.txt")
+    assert len(rows) == 15
+    R = 5
+    unit = [700] * R               # equal layers, one layer fits: the setting of the paper's example
+    total = sum(unit)
+    for kind, scheme, m, N, want in rows:
+        m, N, want = int(m), int(N), int(want)
+        if kind == "W" and scheme in ("per_gpu_swap_dp", "per_gpu_swap_pp"):
+            i, o = osw.residency_machine(osw.steps_microbatch_major(R, m, True), unit, True)
+            copies = N if scheme.endswith("_dp") else 1
+            assert copies * (i + o) == want * total
+            if scheme.endswith("_dp"):
+                assert osw.paper_W_volume_per_gpu_swap_dp(m, N, total) == want * total
+        elif kind == "W":
+            i, o = osw.residency_machine(osw.steps_layer_pack_major(R, m, False), unit, False)
+            copies = N if scheme.endswith("_dp") else 1
+            assert copies * (i + o) == want * total
+            if scheme.endswith("_dp"):
+                assert osw.paper_W_volume_harmony_dp(N, total) == want * total
+        elif kind == "dW":
+            # the gradient buffer in a virtual memory that writes back all it evicts: resident only in backward
+            # passes (m of them, each swapping every pack in and out) and in the update phase (once more each way)
+            steps = []
+            for _ in range(m):
+                steps += [(p, True) for p in reversed(range(R))] + [osw.FLUSH]
+            steps += [(p, True) for p in range(R)]
+            i, o = osw.residency_machine(steps, unit, True)
+            assert N * (i + o) == want * total == osw.paper_dW_volume_per_gpu_swap_dp(m, N, total)
+        else:
+            i, o = osw.residency_machine([(p, True) for p in range(R)], unit, True)
+            assert N * (i + o) == want * total == osw.paper_K_volume(N, total)
+
+
+def test_paper_stated_workloads():
+    """tests/golden/paper_workloads.txt: layer counts, sequence lengths and sizes as Section 5.1 lists them; the
+    synthetic stand-ins have those shapes, and their parameter counts truncate to the sizes the paper prints."""
+    for name, cfg_name, layers, seq, size in _golden_rows("paper_workloads.txt"):
+        cfg = synth.CONFIGS[cfg_name]
+        assert cfg["n_blocks"] == int(layers) and cfg["seq_len"] == int(seq), name
+        if size != "-":
+            spec = oracle_spec(cfg)
+            n = sum(om.layer_param_count(spec, l) for l in range(spec.n_layers)) - cfg["vocab"] * cfg["d_model"]
+            assert f"{math.floor(n / 1e8) / 10:.1f}B" == size, (name, n)     # tied head, as the models are published
 
 
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
