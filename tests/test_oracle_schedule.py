@@ -408,6 +408,30 @@ def test_infeasible_when_one_layer_exceeds_capacity():
     assert opk.balanced_time_packing([], [], 10) == []
 
 
+def test_paper_table_of_layer_packs_has_the_structure_the_planner_builds():
+    """tests/golden/paper_detailed_packs.txt (appendix table 'Detailed scheduling result').  What does not depend
+    on the paper's measured layer times: packs are contiguous and cover the model; the forward packs cover exactly
+    the layers before the last backward pack (the opening steps of Algorithm 2); over the uniform transformer
+    layers pack sizes differ by at most one; and Algorithm 2 on equal layers with the table's largest pack as
+    capacity gives the same NUMBER of packs of each size (which ones are the shorter packs is the paper's
+    profile's doing)."""
+    table = {}
+    for row in _golden_rows("paper_detailed_packs.txt"):
+        table[(row[0], row[1])] = [(int(a), int(b) + 1) for a, b in (p.split("-") for p in row[2:])]
+    assert set(table) == {("BERT96", "P_F"), ("BERT96", "P_B"), ("GPT2", "P_F"), ("GPT2", "P_B")}
+    for model in ("BERT96", "GPT2"):
+        P_F, P_B = table[(model, "P_F")], table[(model, "P_B")]
+        for packs in (P_F, P_B):
+            assert packs[0][0] == 0 and all(p[1] == q[0] for p, q in zip(packs, packs[1:]))
+        assert P_F[-1][1] == P_B[-1][0] == opk.forward_layers_given_backward(P_B)
+        for packs in (P_F, P_B[:-1]):                          # the last backward pack also holds the output layers
+            sizes = [e - a for a, e in packs]
+            assert max(sizes) - min(sizes) <= 1
+            n = packs[-1][1]
+            mine = opk.balanced_time_packing([10] * n, [1] * n, max(sizes))
+            assert sorted(e - a for a, e in mine) == sorted(sizes), (model, sizes)
+
+
 def test_uniform_transformer_layers_give_pack_sizes_differing_by_at_most_one():
     """Shape of the paper's Table 'detailed scheduling result': BERT96's forward
     packs are 21 packs of 4 layers and 3 packs of 3 over 93 layers; GPT2's
