@@ -24,6 +24,10 @@ Readings where the listing is silent:
     twice plus the largest pack's activations, which can come from different
     packs).
 Times and memories are integers (analytic flop and byte counts).
+
+Parity unpinned: the exact pack boundaries of the paper's table of layer packs
+(they come from its measured layer times).  Pinned instead: properties, brute
+force on small cases, and the structure of that table (pack counts per size).
 """
 from __future__ import annotations
 
