@@ -363,3 +363,20 @@ def test_error_paths_return_codes_not_crashes():
         B.hmy_count_swaps(spec, B.make_schedule([2], [2, 4]), 2, 2)
     assert B.lib.hmy_strerror(B.HMY_E_HIP) == b"HIP runtime error"
     assert B.lib.hmy_model_size(None, None, None) == B.HMY_E_INVALID
+
+
+def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_fallback():
+    """One GPU only: `--gpus N` with N > 1 ends with a message and a non-zero status before anything is loaded;
+    without a GPU the benchmark says so instead of timing something else."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and not r.stdout.strip()
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "1", "--warmup", "0"],
+                           capture_output=True, text=True, timeout=300)
+        assert r.returncode != 0 and "needs a GPU" in r.stderr and not r.stdout.strip()
+
