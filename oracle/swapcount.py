@@ -128,9 +128,31 @@ def closed_form_microbatch_major(spec: om.Spec, P_F, P_B, M: int, b: int, precis
     return out
 
 
+def update_chunks(spec: om.Spec, P_B, chunk_params: int):
+    """The pieces in which the update tasks handle optimizer state, in the order the
+    iteration reaches them: backward packs in reverse (Algorithm 3), each pack's
+    parameters in storage order in runs of chunk_params.  Returns a list of
+    (pack, index within the pack, parameters)."""
+    out = []
+    for pack in reversed(P_B):
+        n = _pcount(spec, *pack)
+        for c in range(-(-n // chunk_params)):
+            out.append((pack, c, min(chunk_params, n - c * chunk_params)))
+    return out
+
+
 def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False,
-           export_gradients: bool = True):
-    """Add up what every task of the ordered list swaps."""
+           export_gradients: bool = True, chunk_params: int | None = None, resident=frozenset(),
+           resident_loaded: bool = True):
+    """Add up what every task of the ordered list swaps.
+
+    resident: set of (pack, index) from update_chunks(spec, P_B, chunk_params) whose
+    optimizer state is pinned on the device (Algorithm 3 lists such a channel beside the
+    CPU-GPU swap): an update task moves that piece's state neither way, except inwards
+    once, at its first update after the host arrays were handed over
+    (resident_loaded=False).  Weights and gradients of the piece move as always."""
+    if resident and chunk_params is None:
+        raise ValueError("resident pieces need chunk_params")
     w_c, k_B, g_B = bytes_per_param(precision)
     T = b * spec.seq_len
     act = T * spec.d_model * w_c
@@ -153,11 +175,18 @@ def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_ho
         elif update_on_host:
             d2h["dW"] += g_B * npar       # all the CPU needs from the device
         else:
-            h2d["K"] += k_B * npar
-            d2h["K"] += k_B * npar
-            d2h["W"] += w_c * npar
-            if export_gradients:
-                d2h["dW"] += g_B * npar
+            pieces = [(t.pack, 0, npar)] if chunk_params is None else \
+                [p for p in update_chunks(spec, [t.pack], chunk_params)]
+            for (pack, c, n) in pieces:
+                if (pack, c) in resident:
+                    if not resident_loaded:
+                        h2d["K"] += k_B * n
+                else:
+                    h2d["K"] += k_B * n
+                    d2h["K"] += k_B * n
+                d2h["W"] += w_c * n
+                if export_gradients:
+                    d2h["dW"] += g_B * n
     return {"h2d": h2d, "d2h": d2h}
 
 

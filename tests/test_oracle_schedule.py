@@ -10,6 +10,7 @@ import pytest
 from oracle import model as om
 from oracle import packing as opk
 from oracle import schedule as osch
+from oracle import simulate as osim
 from oracle import swapcount as osw
 from paper_2202_01306_amd import synth
 from tests.helpers import f64, oracle_spec, tiny_cfg
@@ -344,6 +345,21 @@ def test_resident_optimizer_state_leaves_the_link_alone():
                         assert cf(*args, update_on_host=True, resident_K_params=P_res) == cf(*args, update_on_host=True)
                 with pytest.raises(ValueError):
                     osw.closed_form(*args, resident_K_params=P + 1)
+                # the closed form's residency terms against a walk that knows nothing of them: the ledger visits
+                # the update tasks piece by piece and skips the optimizer state of pieces marked resident
+                for chunk in (7, 100, 10 ** 6):
+                    pieces = osw.update_chunks(spec, P_B, chunk)
+                    assert sum(n for (_, _, n) in pieces) == P
+                    for n_res in (0, 1, len(pieces) // 2, len(pieces)):
+                        chosen = pieces[len(pieces) - n_res:]         # the pieces updated last
+                        res_set = {(pack, c) for (pack, c, _) in chosen}
+                        P_res = sum(n for (_, _, n) in chosen)
+                        for loaded in (True, False):
+                            for export in (True, False):
+                                assert osw.ledger(*args, export_gradients=export, chunk_params=chunk, resident=res_set,
+                                                  resident_loaded=loaded) == \
+                                    osw.closed_form(*args, export_gradients=export, resident_K_params=P_res,
+                                                    resident_K_loaded=loaded)
 
 
 def test_weight_volume_reduces_to_3W_when_last_pack_is_counted_twice():
@@ -467,23 +483,124 @@ def test_forward_packing_covers_layers_before_last_backward_pack():
     assert max(e - a for a, e in P_F) >= max(e - a for a, e in P_B[:-1])
 
 
-def test_reshaped_packings_stay_valid_coverings():
-    """The planner's reshaping moves (tapered first pack, merged last packs) keep a
-    packing contiguous, ordered and covering, whatever it starts from."""
-    for R in (2, 3, 5, 9):
-        for cuts in ([], [1], [2], [1, 3], [2, 4, 7]):
-            ends = sorted(set(c for c in cuts if 0 < c < R)) + [R]
-            P_B, a = [], 0
-            for e in ends:
-                P_B.append((a, e))
-                a = e
-            for Q in (opk.taper_first_pack(P_B), opk.merge_last_packs(P_B),
-                      opk.taper_first_pack(opk.merge_last_packs(P_B))):
-                assert Q[0][0] == 0 and Q[-1][1] == R
-                assert all(x[0] < x[1] for x in Q)
-                assert all(Q[i][1] == Q[i + 1][0] for i in range(len(Q) - 1))
-            t = opk.taper_first_pack(P_B)
-            if P_B[0][1] >= 2:
-                assert t[0] == (0, 1) and t[1] == (1, 2)
-            g = opk.merge_last_packs(P_B)
-            assert len(g) == max(1, len(P_B) - 1) and g[-1][1] == R
+# -------------------------------------------------------------- simulation ---
+# The event-driven estimate of an iteration (Section 4.3.1, Runtime Estimator), pinned by
+# schedules walked by hand.  Toy model: embedding 160, blocks 736, head 144 parameters
+# (d = 8, f = 24, s = 4, V = 16); fp32 (4 B weights, 8 B optimizer state, 4 B exported
+# gradient per parameter); two microbatches; a checkpoint of 64 bytes per microbatch.
+from fractions import Fraction as Fr
+
+
+def _toy(n_blocks):
+    spec = om.Spec(n_blocks, 8, 2, 24, 4, 16)
+    assert [om.layer_param_count(spec, l) for l in range(spec.n_layers)] == [160] + [736] * n_blocks + [144]
+    return spec
+
+
+def _sim(spec, P_F, P_B, t_fwd, t_bwd, slots=3, distance=1, host=False, n_in=Fr(1, 64), n_out=Fr(1, 64), **kw):
+    ops = osim.iteration_ops(spec, P_F, P_B, t_fwd, t_bwd, 2, 2, 64, 64, 4, 8, 4, n_in, n_out, slots=slots,
+                             distance=distance, update_on_host=host, host_ns_per_param=Fr(1, 8), **kw)
+    return osim.run(ops)
+
+
+def test_generic_simulator_on_a_three_operation_example():
+    """Two resources by hand: b waits for a; c shares a's resource and queues behind it;
+    d may not end before c although it is shorter."""
+    ops = [osim.Op("a", "x", Fr(5)), osim.Op("c", "x", Fr(7)), osim.Op("b", "y", Fr(2), after_end=["a"]),
+           osim.Op("d", "y", Fr(1), after_start=["c"], not_before_end=["c"])]
+    assert osim.run(ops) == {"a": (0, 5), "c": (5, 12), "b": (5, 7), "d": (7, 12)}
+    with pytest.raises(AssertionError):
+        osim.run([osim.Op("a", "x", Fr(1), after_end=["b"]), osim.Op("b", "y", Fr(1), after_end=["a"])])
+
+
+def test_simulated_iteration_three_visits_worked_by_hand():
+    """P_F = [0,2), P_B = [0,2) [2,4); link 1/64 ns per byte both ways.
+    W0 = (160+736)*4/64 = 56, C0 = 2*(1+10) = 22; W1 = (736+144)/16 = 55, C1 = 2*(30+12) = 84,
+    K1 = 880*8/64 = 110, Out1 = 880*16/64 = 220; W2 = 56, C2 = 2*(3+30) = 66, K2 = 112, Out2 = 224.
+    W0 0-56; C0 56-78; W1 (asked at 56) 56-111; C1 111-195; W2 (asked at 111) 111-167;
+    K1 (asked at 195) 195-305; Out1 195-415; C2 195-261; K2 305-417; Out2 415-639."""
+    t = _sim(_toy(2), [(0, 2)], [(0, 2), (2, 4)], [1, 10, 10, 4], [3, 30, 30, 12])
+    want = {"W0": (0, 56), "C0": (56, 78), "W1": (56, 111), "C1": (111, 195), "W2": (111, 167), "K1": (195, 305),
+            "Out1": (195, 415), "C2": (195, 261), "K2": (305, 417), "Out2": (415, 639)}
+    assert t == want
+    # two slots change nothing here: the slot of visit 2 was a forward visit's, free since 78
+    assert _sim(_toy(2), [(0, 2)], [(0, 2), (2, 4)], [1, 10, 10, 4], [3, 30, 30, 12], slots=2) == want
+
+
+def test_simulated_iteration_with_checkpoints_and_host_update_worked_by_hand():
+    """P_F = [0,3), four one-layer backward packs: checkpoints at layers 1 and 2.
+    Device update, compute-bound (times 10/100/100/40 forward, 30/300/300/120 backward):
+    W0 = 1632*4/64 = 102; C0 = 2*210 = 420; Sout0 = 2 checkpoints * 2 * 64/64 = 4; W1 = 9, C1 = 240, K1 = 18,
+    Out1 = 36; visits 2, 3: W 46, C 600, K 92, Out 184, Sin 2; visit 4: W 10, C 60, K 20, Out 40.
+    W0 0-102; C0 102-522; Sout0 102-106; W1 102-111; C1 522-762; W2 522-568; K1 762-780; Out1 762-798;
+    C2 762-1362; Sin2 780-782; W3 782-828; K2 1362-1454; Out2 1362-1546; C3 1362-1962; Sin3 1454-1456;
+    W4 1456-1466; K3 1962-2054; Out3 1962-2146; C4 1962-2022; K4 2054-2074; Out4 2146-2186."""
+    spec = _toy(2)
+    P_F, P_B = [(0, 3)], [(0, 1), (1, 2), (2, 3), (3, 4)]
+    t = _sim(spec, P_F, P_B, [10, 100, 100, 40], [30, 300, 300, 120])
+    assert t["Sout0"] == (102, 106) and t["Sin2"] == (780, 782) and t["W3"] == (782, 828) and t["Sin3"] == (1454, 1456)
+    assert t["K3"] == (1962, 2054) and t["Out3"] == (1962, 2146) and t["C4"] == (1962, 2022)
+    assert max(e for _, e in t.values()) == t["Out4"][1] == 2186
+    # the update on the CPU (backward times 30/200/200/120, CPU at 8 parameters per ns): only the gradient leaves
+    # Out1 = 144*4/64 = 9, Cpu1 = 18; Out 46 and Cpu 92 for the blocks; Out4 = 10, Cpu4 = 20
+    # C1 522-762; Out1 762-771; Cpu1 771-789; C2 762-1162; Out2 1162-1208; Cpu2 1208-1300; C3 1162-1562;
+    # Out3 1562-1608; Cpu3 1608-1700; C4 1562-1622; Out4 1622-1632; Cpu4 1700-1720
+    h = _sim(spec, P_F, P_B, [10, 100, 100, 40], [30, 200, 200, 120], host=True)
+    assert "K1" not in h and h["Out2"] == (1162, 1208) and h["Cpu3"] == (1608, 1700) and h["Cpu4"] == (1700, 1720)
+    assert max(e for _, e in h.values()) == 1720
+
+
+def test_simulated_iteration_two_slots_against_three_worked_by_hand():
+    """Seven visits (P_F = [0,5), six one-layer backward packs), device->host at 1/32 ns per byte:
+    W0 = 3104*4/64 = 194, C0 = 2*410 = 820, Sout0 = 4*2*64/32 = 16; visit 1: W 9, C 240, K 18, Out 144*16/32 = 72;
+    visits 2..5: W 46, C 400, K 92, Out 368, Sin 2; visit 6: W 10, C 60, K 20, Out 80.
+    Two slots: W4 needs visit 2's slot, which Out2 leaves at 2022, so C4 starts at 2068 instead of 2054 and
+    everything behind it is 14 later: 3316 against 3302 with three slots (W4 at 1748, visit 1's slot)."""
+    spec = _toy(4)
+    P_F, P_B = [(0, 5)], [(i, i + 1) for i in range(6)]
+    tf, tb = [10, 100, 100, 100, 100, 40], [30, 200, 200, 200, 200, 120]
+    two = _sim(spec, P_F, P_B, tf, tb, slots=2, n_out=Fr(1, 32))
+    assert two["W3"] == (1326, 1372) and two["W4"] == (2022, 2068) and two["K3"] == (2068, 2160)
+    assert two["C4"] == (2068, 2468) and two["W6"] == (2836, 2846) and two["Out6"] == (3236, 3316)
+    three = _sim(spec, P_F, P_B, tf, tb, slots=3, n_out=Fr(1, 32))
+    assert three["W3"] == (1274, 1320) and three["W4"] == (1748, 1794) and three["C4"] == (2054, 2454)
+    assert max(e for _, e in three.values()) == 3302 and max(e for _, e in two.values()) == 3316
+    for slots, distance in ((3, 2), (4, 1), (4, 2), (4, 3)):
+        assert max(e for _, e in _sim(spec, P_F, P_B, tf, tb, slots=slots, distance=distance,
+                                      n_out=Fr(1, 32)).values()) == 3302
+
+
+def test_simulated_iteration_limits_and_monotonicity():
+    """With a link of unbounded speed the iteration is the sum of the visits' compute times; with unbounded
+    compute it is at least each direction's serial traffic and at most their sum; a faster link, more slots or
+    a larger prefetch distance never make it longer."""
+    rng = np.random.default_rng(5)
+    spec = _toy(3)
+    R = spec.n_layers
+    P = [om.layer_param_count(spec, l) for l in range(R)]
+    for P_B in list(all_packings(R))[::2]:
+        P_F = [(0, P_B[-1][0])] if P_B[-1][0] else []
+        tf = [int(x) for x in rng.integers(1, 50, R)]
+        tb = [3 * x for x in tf]
+        n_vis_F = sum(tf[l] for (a, e) in P_F for l in range(a, e))
+        total_compute = 2 * (n_vis_F + sum(tb))
+        tiny = Fr(1, 10 ** 12)
+        t = _sim(spec, P_F, P_B, tf, tb, n_in=tiny, n_out=tiny)
+        assert 0 <= max(e for _, e in t.values()) - total_compute < Fr(1, 1000)
+        zero = [0] * R
+        t = _sim(spec, P_F, P_B, zero, zero)
+        n_ck = max(len(P_B) - 2, 0)
+        h2d = Fr(4 * (2 * sum(P) - sum(P[P_B[-1][0]:])) + 8 * sum(P) + n_ck * 2 * 64, 64)
+        d2h = Fr(16 * sum(P) + n_ck * 2 * 64, 64)
+        end = max(e for _, e in t.values())
+        assert max(h2d, d2h) <= end <= h2d + d2h
+        prev = None
+        for slots, distance in ((2, 1), (3, 1), (3, 2), (4, 3)):
+            end = max(e for _, e in _sim(spec, P_F, P_B, tf, tb, slots=slots, distance=distance).values())
+            assert prev is None or end <= prev
+            prev = end
+            assert max(e for _, e in _sim(spec, P_F, P_B, tf, tb, slots=slots, distance=distance, n_in=Fr(1, 128),
+                                          n_out=Fr(1, 128)).values()) <= end
+        # dropping the consumed gradient shortens the outgoing operation of every update
+        assert max(e for _, e in _sim(spec, P_F, P_B, tf, tb, export_gradients=False).values()) <= \
+            max(e for _, e in _sim(spec, P_F, P_B, tf, tb).values())
