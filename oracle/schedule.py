@@ -102,12 +102,33 @@ def task_list_microbatch_major(spec: om.Spec, P_F, P_B, M: int):
     return tasks
 
 
+def regroup(parts, rows_per_part: int):
+    """Row blocks of one minibatch cut into pieces of another size: the rows of all
+    `parts` in order, re-split into blocks of rows_per_part rows."""
+    import numpy as np
+    rows = np.concatenate(parts, axis=0)
+    assert rows.shape[0] % rows_per_part == 0
+    return [rows[i:i + rows_per_part].copy() for i in range(0, rows.shape[0], rows_per_part)]
+
+
 def iteration_layer_pack_major(spec: om.Spec, params, ids, targets, P_F, P_B,
-                               m, v, hp: om.AdamHP, order: str = "layer_pack_major"):
+                               m, v, hp: om.AdamHP, order: str = "layer_pack_major", U_F: int | None = None):
     """One iteration in task-list order.  Returns dict(loss, grads, weights, m, v).
-    order = "microbatch_major" executes task_list_microbatch_major instead."""
+    order = "microbatch_major" executes task_list_microbatch_major instead.
+
+    U_F: forward microbatch size of the configuration 4-tuple (Section 4.3.1; Algorithm 1
+    searches U_F and U_B separately).  ids is [M_B, U_B, s]: the backward tasks, and the
+    last pack that is shared with them, run its microbatches as given; with U_F set, the
+    forward tasks run the same M_B * U_B sequences in microbatches of U_F sequences, and
+    the activations and checkpoints they leave are re-cut into the backward microbatches
+    (every row belongs to one sequence, so only the grouping changes).  Gradients are
+    summed over the backward microbatches in ascending order, as in the definition."""
     M = ids.shape[0]
     n_tgt = om.count_targets(targets)
+    if U_F is not None and U_F != ids.shape[1]:
+        if order != "layer_pack_major":
+            raise ValueError("distinct forward and backward microbatch sizes need the layer-pack-major order")
+        return _iteration_distinct_fb(spec, params, ids, targets, P_F, P_B, m, v, hp, U_F, n_tgt)
     if order == "layer_pack_major":
         tasks = task_list(spec, P_F, P_B)
     elif order == "microbatch_major":
@@ -154,6 +175,65 @@ def iteration_layer_pack_major(spec: om.Spec, params, ids, targets, P_F, P_B,
                     om.accumulate(grads, g)
                 X[mb] = dy               # gradient w.r.t. the pack's input
         else:  # 'A': jit-update of this pack's tensors
+            for layer in range(a, e):
+                for name in om.layer_param_shapes(spec, layer):
+                    new_w[name], new_m[name], new_v[name] = om.adam_update(
+                        params[name], grads[name], m[name], v[name], hp)
+    assert not stash, "every checkpoint must be consumed exactly once"
+    return {"loss": float(loss), "grads": grads, "weights": new_w, "m": new_m, "v": new_v}
+
+
+def _iteration_distinct_fb(spec: om.Spec, params, ids, targets, P_F, P_B, m, v, hp: om.AdamHP, U_F: int, n_tgt: int):
+    M_B, U_B, s = ids.shape
+    D = M_B * U_B
+    if D % U_F:
+        raise ValueError("U_F must divide the minibatch")
+    M_F = D // U_F
+    ids_F = ids.reshape(M_F, U_F, s)
+    tg_F = targets.reshape(M_F, U_F, s)
+    tasks = task_list(spec, P_F, P_B)
+    X_F = [None] * M_F
+    stash_F = {}                      # layer -> list over forward microbatches
+    for t in tasks:
+        if t.kind != "F":
+            continue
+        a, e = t.pack
+        for mb in range(M_F):
+            x = X_F[mb]
+            for layer in range(a, e):
+                if layer in t.stash_out_layers:
+                    stash_F.setdefault(layer, [None] * M_F)[mb] = x.copy()
+                x, _ = om.layer_fwd(layer, x, params, spec, ids_F[mb], tg_F[mb], n_tgt)
+            X_F[mb] = x
+    # the hand-over between the passes: same rows, cut into the backward microbatches
+    X = regroup(X_F, U_B * s) if P_F else [None] * M_B
+    stash = {(layer, mb): x for layer, parts in stash_F.items() for mb, x in enumerate(regroup(parts, U_B * s))}
+    grads: dict = {}
+    loss = 0.0
+    new_w, new_m, new_v = {}, {}, {}
+    for t in tasks:
+        a, e = t.pack
+        if t.kind == "B":
+            for mb in range(M_B):
+                if a == 0:
+                    x = None
+                elif t.is_last_pack:
+                    x = X[mb]
+                else:
+                    x = stash.pop((t.stash_in_layer, mb))
+                caches = {}
+                for layer in range(a, e):
+                    x, caches[layer] = om.layer_fwd(layer, x, params, spec, ids[mb], targets[mb], n_tgt)
+                if t.is_last_pack:
+                    loss += x
+                    dy = None
+                else:
+                    dy = X[mb]
+                for layer in reversed(range(a, e)):
+                    dy, g = om.layer_bwd(layer, dy, caches[layer], params, spec, U_B)
+                    om.accumulate(grads, g)
+                X[mb] = dy
+        elif t.kind == "A":
             for layer in range(a, e):
                 for name in om.layer_param_shapes(spec, layer):
                     new_w[name], new_m[name], new_v[name] = om.adam_update(

@@ -56,8 +56,14 @@ def _pcount(spec, a, e):
 
 
 def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False,
-                export_gradients: bool = True, resident_K_params: int = 0, resident_K_loaded: bool = True):
+                export_gradients: bool = True, resident_K_params: int = 0, resident_K_loaded: bool = True,
+                M_F: int | None = None, b_F: int | None = None):
     """Layer-pack-major volumes.  Returns {'h2d': {kind: bytes}, 'd2h': {...}}.
+
+    M, b: the backward pass's microbatches (M_B of U_B sequences).  M_F, b_F: the forward
+    pass's (M_F of U_F), if the configuration uses distinct sizes (Section 4.3.1); the
+    checkpoints then go out once per forward microbatch in its size and come back once per
+    backward microbatch in that one's -- the same bytes, since both cover the minibatch.
 
     resident_K_params: parameters whose optimizer state is pinned on the device
     (Algorithm 3 lists a channel that keeps a tensor on the GPU beside the CPU-GPU
@@ -88,7 +94,11 @@ def closed_form(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_
     h2d["K"] = k_B * P_all
     d2h["K"] = k_B * P_all
     h2d["sX"] = M * a * n_ckpt
-    d2h["sX"] = M * a * n_ckpt
+    if M_F is None and b_F is None:
+        M_F, b_F = M, b
+    if M_F * b_F != M * b:
+        raise ValueError("both passes must cover the same minibatch")
+    d2h["sX"] = M_F * (b_F * spec.seq_len * spec.d_model * w_c) * n_ckpt
     h2d["ids"] = 2 * M * T * 4
     if update_on_host:
         h2d["K"] = d2h["K"] = d2h["W"] = 0
@@ -143,8 +153,9 @@ def update_chunks(spec: om.Spec, P_B, chunk_params: int):
 
 def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_host: bool = False,
            export_gradients: bool = True, chunk_params: int | None = None, resident=frozenset(),
-           resident_loaded: bool = True):
-    """Add up what every task of the ordered list swaps.
+           resident_loaded: bool = True, M_F: int | None = None, b_F: int | None = None):
+    """Add up what every task of the ordered list swaps.  M, b are the backward pass's
+    microbatches; forward tasks run M_F microbatches of b_F sequences (default: the same).
 
     resident: set of (pack, index) from update_chunks(spec, P_B, chunk_params) whose
     optimizer state is pinned on the device (Algorithm 3 lists such a channel beside the
@@ -160,13 +171,16 @@ def ledger(spec: om.Spec, P_F, P_B, M: int, b: int, precision: str, update_on_ho
     d2h = dict.fromkeys(KINDS, 0)
     h2d["ids"] += M * T * 4       # token ids
     h2d["ids"] += M * T * 4       # targets
+    if M_F is None and b_F is None:
+        M_F, b_F = M, b
+    act_F = b_F * spec.seq_len * spec.d_model * w_c
     for t in osch.task_list(spec, P_F, P_B):
         npar = _pcount(spec, *t.pack)
         if t.kind == "F":
             h2d["W"] += w_c * npar
             for _layer in t.stash_out_layers:
-                for _mb in range(M):
-                    d2h["sX"] += act
+                for _mb in range(M_F):
+                    d2h["sX"] += act_F
         elif t.kind == "B":
             h2d["W"] += w_c * npar
             if t.stash_in_layer is not None:

@@ -53,6 +53,44 @@ def test_layer_pack_major_is_bit_identical_to_microbatch_major(causal):
     assert tried > 16
 
 
+def test_distinct_forward_and_backward_microbatch_sizes_give_the_same_iteration():
+    """Section 4.3.1: the configuration is a 4-tuple with its own microbatch size per pass (Algorithm 1 sweeps
+    U_F and U_B separately).  Re-cutting the minibatch for the forward pass regroups rows, nothing else: with
+    U_F = U_B the driver is the bit-identical one above; with another U_F every result agrees with the definition
+    up to the rounding order inside the library's matrix products (1e-12 of each tensor's largest value), and the
+    checkpoint volume is the same bytes cut differently."""
+    cfg = tiny_cfg(n_blocks=3, M=3, b=4)
+    spec = oracle_spec(cfg)
+    params = f64(synth.gen_params(cfg, 2, bench_init=False))
+    m0, v0 = (f64(x) for x in synth.gen_adam_state(cfg, 2, zero=False))
+    ids = synth.gen_tokens(cfg, 2)
+    tg = synth.gen_targets(cfg, ids, 2)
+    hp = om.AdamHP(step=10)
+    ref = om.training_iteration(spec, params, ids, tg, m0, v0, hp)
+    for P_F, P_B in (([(0, 2), (2, 4)], [(0, 1), (1, 2), (2, 4), (4, 5)]), ([(0, 3)], [(0, 3), (3, 5)]),
+                     ([], [(0, 5)]), ([(0, 1), (1, 4)], [(0, 2), (2, 3), (3, 4), (4, 5)])):
+        same = osch.iteration_layer_pack_major(spec, params, ids, tg, P_F, P_B, m0, v0, hp, U_F=4)
+        for k in ("grads", "weights", "m", "v"):
+            for name in params:
+                np.testing.assert_array_equal(same[k][name], ref[k][name])
+        for U_F in (1, 2, 3, 6, 12):
+            out = osch.iteration_layer_pack_major(spec, params, ids, tg, P_F, P_B, m0, v0, hp, U_F=U_F)
+            assert abs(out["loss"] - ref["loss"]) < 1e-13 * abs(ref["loss"])
+            for k in ("grads", "weights", "m", "v"):
+                for name in params:
+                    scale = max(np.abs(ref[k][name]).max(), 1e-300)
+                    assert np.abs(out[k][name] - ref[k][name]).max() <= 1e-12 * scale, (U_F, k, name)
+            M_F = 12 // U_F
+            for prec in ("fp32", "bf16"):
+                cf = osw.closed_form(spec, P_F, P_B, 3, 4, prec, M_F=M_F, b_F=U_F)
+                assert cf == osw.closed_form(spec, P_F, P_B, 3, 4, prec)
+                assert cf == osw.ledger(spec, P_F, P_B, 3, 4, prec, M_F=M_F, b_F=U_F)
+    with pytest.raises(ValueError):
+        osch.iteration_layer_pack_major(spec, params, ids, tg, [(0, 3)], [(0, 3), (3, 5)], m0, v0, hp, U_F=5)
+    with pytest.raises(ValueError):
+        osw.closed_form(spec, [(0, 3)], [(0, 3), (3, 5)], 3, 4, "fp32", M_F=5, b_F=2)
+
+
 def test_microbatch_major_over_packs_is_bit_identical_too():
     """The comparison order of Section 3 (every microbatch on its own through all packs,
     gradients summed across microbatches, update after the last one) is ordinary
