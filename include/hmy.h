@@ -334,6 +334,19 @@ int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float
                         const float *rstd, const void *gamma, const void *res, void *dx,
                         float *dgamma, float *dbeta, int32_t T, int32_t d, void *stream,
                         float *workspace, uint64_t workspace_bytes);
+/* hmy_k_layernorm_bwd for callers that cannot allocate device memory (code under HIP graph
+ * capture, serving loops, harnesses that forbid hipMalloc): same arguments without the
+ * workspace, same kernels, same results.  The per-workgroup partial sums go to an 8 MiB array
+ * that the library's code object holds on every GPU it is loaded on (its address on the current
+ * device is looked up at the first call there); the call allocates and frees nothing.
+ * Limit: d <= 4096 (HMY_E_INVALID with a message beyond; the variant with a caller's workspace
+ * has no such limit).  The current device must be the stream's.  All calls on one GPU share
+ * the array: calls that may overlap there (different streams, different threads) race on it
+ * and must be ordered by the caller; calls on one stream are ordered already.  Nothing in
+ * the array has to be cleared between calls. */
+int hmy_k_layernorm_bwd_static(int32_t prec, const void *dy, const void *x, const float *mean,
+                               const float *rstd, const void *gamma, const void *res, void *dx,
+                               float *dgamma, float *dbeta, int32_t T, int32_t d, void *stream);
 /* g = gelu_tanh(u); du = dg * gelu'(u) (du may alias dg) */
 int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream);
 int hmy_k_gelu_bwd(int32_t prec, const void *dg, const void *u, void *du, uint64_t n, void *stream);

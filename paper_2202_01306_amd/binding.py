@@ -108,7 +108,7 @@ EXPORTS = [
     "hmy_strerror", "hmy_last_error", "hmy_model_size", "hmy_layout", "hmy_profile", "hmy_plan", "hmy_estimate", "hmy_arena",
     "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state", "hmy_resident_params", "hmy_sync_state",
     "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
-    "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
+    "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_layernorm_bwd_static", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
     "hmy_k_gemm", "hmy_k_attn_fwd", "hmy_k_attn_bwd", "hmy_k_xent", "hmy_k_adam", "hmy_host_adam",
 ]
 
@@ -311,6 +311,11 @@ def hmy_k_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, 
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib.hmy_k_layernorm_bwd(prec, _p(dy), _p(x), _p(mean), _p(rstd), _p(gamma), _p(res), _p(dx),
                                    _p(dgamma), _p(dbeta), T, d, _p(stream), _p(workspace), C.c_uint64(ws_bytes)))
+
+
+def hmy_k_layernorm_bwd_static(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None):
+    _check(lib.hmy_k_layernorm_bwd_static(prec, _p(dy), _p(x), _p(mean), _p(rstd), _p(gamma), _p(res), _p(dx),
+                                          _p(dgamma), _p(dbeta), T, d, _p(stream)))
 
 
 def hmy_k_gelu_fwd(prec, u, g, n, stream=None):

@@ -155,6 +155,12 @@ int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float
   return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream, workspace,
                               workspace_bytes);
 }
+int hmy_k_layernorm_bwd_static(int32_t prec, const void *dy, const void *x, const float *mean, const float *rstd,
+                               const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int32_t T,
+                               int32_t d, void *stream) {
+  NOTNULL(dy); NOTNULL(x); NOTNULL(mean); NOTNULL(rstd); NOTNULL(gamma); NOTNULL(dx); NOTNULL(dgamma); NOTNULL(dbeta);
+  return launch_layernorm_bwd_static(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream);
+}
 int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream) {
   NOTNULL(u); NOTNULL(g);
   return launch_gelu_fwd(prec, u, g, n, stream);

@@ -2,6 +2,7 @@
 // softmax cross-entropy, fused Adam, fill and copy.  One wavefront (64 lanes)
 // per row for the row reductions; 16-byte accesses along the contiguous axis.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 
@@ -791,6 +792,54 @@ int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *m
                      d, (hipStream_t)st, workspace, workspace_bytes);
   });
   return check_launch("layernorm_bwd");
+}
+
+// ---- LayerNorm backward for callers that cannot allocate -----------------------------
+// The partial-sum rows of k_layernorm_bwd_reg live in a file-scope device array instead of a
+// caller's workspace.  Every GPU the library runs on holds its own copy of the array at its own
+// address; in host code the array's name is only a handle for hipGetSymbolAddress, so the address
+// is looked up once per device (with that device current) and kept.
+constexpr int kStaticLnMaxD = 4096;   // widest row the static workspace serves
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) float g_ln_bwd_scratch[uint64_t(kLnBlocks) * 2 * kStaticLnMaxD];   // 8 MiB
+namespace {
+std::atomic<float *> g_ln_bwd_scratch_ptr[kMaxDevices];
+
+// device address of the scratch array on the current device (nullptr + error recorded on failure)
+float *ln_bwd_scratch_on_current_device() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(HMY_E_HIP, "layernorm_bwd_static: no current device (%s)", hipGetErrorString(e));
+    return nullptr;
+  }
+  float *p = g_ln_bwd_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  void *addr = nullptr;
+  e = hipGetSymbolAddress(&addr, HIP_SYMBOL(g_ln_bwd_scratch));
+  if (e != hipSuccess || !addr) {
+    fail(HMY_E_HIP, "layernorm_bwd_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+    return nullptr;
+  }
+  // two threads racing here look up the same address: either store is right
+  g_ln_bwd_scratch_ptr[dev].store(static_cast<float *>(addr), std::memory_order_release);
+  return static_cast<float *>(addr);
+}
+}  // namespace
+
+int launch_layernorm_bwd_static(int prec, const void *dy, const void *x, const float *mean, const float *rstd,
+                                const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int T, int d,
+                                stream_t st) {
+  if (T < 1 || d < 8 || d % 8) return fail(HMY_E_INVALID, "layernorm_bwd_static: bad shape");
+  if (d > kStaticLnMaxD)
+    return fail(HMY_E_INVALID, "layernorm_bwd_static: d = %d exceeds the static workspace's limit of %d columns; "
+                               "use hmy_k_layernorm_bwd with a workspace of the caller's", d, kStaticLnMaxD);
+  float *ws = ln_bwd_scratch_on_current_device();
+  if (!ws) return HMY_E_HIP;
+  // nothing in the workspace has to start at zero: every workgroup overwrites its whole row before
+  // the reduction kernel, ordered behind it on the stream, reads the rows of this launch only
+  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, st, ws,
+                              uint64_t(kLnBlocks) * 2 * d * 4);
 }
 
 int launch_gelu_fwd(int prec, const void *u, void *g, uint64_t n, stream_t st) {

@@ -114,6 +114,9 @@ int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *m
                          const float *rstd, const void *gamma, const void *res, void *dx,
                          float *dgamma, float *dbeta, int T, int d, stream_t st, float *workspace = nullptr,
                          uint64_t workspace_bytes = 0);
+int launch_layernorm_bwd_static(int prec, const void *dy, const void *x, const float *mean, const float *rstd,
+                                const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int T, int d,
+                                stream_t st);
 int launch_gelu_fwd(int prec, const void *u, void *g, uint64_t n, stream_t st);
 int launch_gelu_bwd(int prec, const void *dg, const void *u, void *du, uint64_t n, stream_t st);
 int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st);
