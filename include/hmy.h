@@ -70,18 +70,44 @@ typedef struct hmy_model_spec {
   float ln_eps;
 } hmy_model_spec;
 
+/* Per-layer times measured on the device for one microbatch size (Section 4.2, Profiler:
+ * "runs each layer individually and records ... compute time"), as hmy_measure_profile
+ * returns them.  Times are nanoseconds for ONE microbatch of micro_batch sequences. */
+typedef struct hmy_measured_profile {
+  int32_t micro_batch;
+  int32_t reserved_;
+  uint64_t embed_fwd_ns, embed_bwd_ns;
+  uint64_t block_fwd_ns;  /* forward of one block in a forward task (nothing kept)          */
+  uint64_t block_bwd_ns;  /* one block in a backward task: forward keeping what backward
+                             needs (the recompute), then backward                          */
+  uint64_t head_ns;       /* final LayerNorm + vocabulary projection + loss, forward and
+                             backward (the head only ever runs in the last pack)           */
+} hmy_measured_profile;
+
 /* The machine model of Algorithm 1: memory capacity alpha, host-link bandwidth beta,
- * plus a sustained compute rate for the runtime estimate. */
+ * plus what the runtime estimate needs to turn the analytic profile into times, and
+ * the ranges its configuration search may sweep.  A zero-filled struct but for
+ * hbm_budget_bytes plans Algorithm 2 alone with three weight slots, prefetch distance 1
+ * and the caller's microbatch size in both passes. */
 typedef struct hmy_budget {
   uint64_t hbm_budget_bytes; /* everything the library keeps in HBM must fit                   */
   uint32_t host_link_MBps;   /* per direction, for the runtime estimate; 0 = 40000             */
-  uint32_t compute_GFLOPs;   /* sustained model flops/s for the runtime estimate; 0 = 420000   */
+  uint32_t compute_GFLOPs;   /* sustained model flops/s for layers without a measured time;
+                                0 = 420000                                                     */
   uint32_t max_extra_packs;  /* 0: first feasible pack count (Algorithm 2 alone); n: also try the
                                 next n feasible pack counts and keep the smallest estimated
                                 iteration time (the search of Algorithm 1)                      */
   uint32_t update_site;      /* HMY_UPDATE_*: where the planned iteration will run its Weight Update
                                 tasks; the estimate moves only the gradient over the link for
                                 ON_HOST, and hmy_plan returns a schedule with this update site   */
+  uint32_t min_weight_slots; /* hmy_plan tries every slot count in [min, max] (Section 4.4:       */
+  uint32_t max_weight_slots; /* prefetch and double buffering); 0 = 3; range 2..HMY_MAX_WEIGHT_SLOTS */
+  uint32_t max_fwd_micro_batch; /* U_FMAX and U_BMAX of Algorithm 1: hmy_plan sweeps the divisors  */
+  uint32_t max_bwd_micro_batch; /* of the minibatch up to these; 0 = only the caller's micro_batch */
+  uint32_t n_measured;       /* entries of `measured`                                          */
+  const hmy_measured_profile *measured; /* host; a layer's time at a microbatch size comes from
+                                the entry with that micro_batch if there is one, else from
+                                flops / compute_GFLOPs; may be NULL                            */
 } hmy_budget;
 
 /* Order in which the tasks of one iteration run over the packs.
@@ -133,14 +159,32 @@ typedef struct hmy_budget {
 #define HMY_STATE_SWAPPED 0
 #define HMY_STATE_RESIDENT_IN_SPARE_BUDGET 1
 
-/* Configuration (Section 4.3.1): forward and backward layer packs as exclusive
- * end indices over the R layers.  Backward packs cover 0..R; forward packs cover
- * exactly the layers before the last backward pack (the opening steps of Algorithm 2).
- * Microbatch sizes U_F = U_B = micro_batch are given by the caller.
+/* How device->host traffic leaves (Section 4.4: the swap-out stream).  KERNEL: through the
+ * library's own throttled kernels that store to the pinned host arrays (the update kernel
+ * writes its results there itself).  MEMCPY: hipMemcpyAsync on the swap-out stream, after an
+ * update kernel that leaves its results in HBM.  Same bytes, same counters, same results. */
+#define HMY_SWAP_OUT_KERNEL 0
+#define HMY_SWAP_OUT_MEMCPY 1
+
+#define HMY_MAX_WEIGHT_SLOTS 4
+
+/* Configuration (Section 4.3.1: the 4-tuple U_F, P_F, U_B, P_B): forward and backward layer
+ * packs as exclusive end indices over the R layers.  Backward packs cover 0..R; forward packs
+ * cover exactly the layers before the last backward pack (the opening steps of Algorithm 2).
+ * fwd_micro_batch, bwd_micro_batch: U_F and U_B in sequences; 0 = the caller's micro_batch.
+ * Each must divide the minibatch (n_micro * micro_batch sequences): the forward tasks run it
+ * as microbatches of U_F, the backward tasks (and the last pack, which runs forward and
+ * backward together) as microbatches of U_B, gradients summed in ascending order of those.
+ * HMY_ORDER_MICROBATCH_MAJOR needs U_F = U_B.
+ * weight_slots (Section 4.4, double buffering): HBM slots that hold a pack's weights and,
+ * in a backward task, its gradient; task v uses slot v mod weight_slots; 0 = 3.
+ * prefetch_distance: the weights of task v + distance travel while task v computes;
+ * 0 = 1; must be below weight_slots.  With distance + 1 slots the load of a task waits for
+ * the write-back of the task that held its slot; one more slot lets it go ahead.
  * order: HMY_ORDER_*, update_site: HMY_UPDATE_*, gradients: HMY_GRADIENTS_*,
- * resident_state: HMY_STATE_*; hmy_plan returns LAYER_PACK_MAJOR, EXPORTED and SWAPPED
- * (all 0) and the update site of its budget argument; any value other than those defined
- * above is HMY_E_BAD_SCHEDULE. */
+ * resident_state: HMY_STATE_*, swap_out: HMY_SWAP_OUT_*; hmy_plan returns LAYER_PACK_MAJOR,
+ * EXPORTED, SWAPPED, KERNEL (all 0) and the update site of its budget argument; any value
+ * other than those defined above is HMY_E_BAD_SCHEDULE. */
 typedef struct hmy_schedule {
   int32_t n_fwd_packs, n_bwd_packs;
   int32_t fwd_pack_end[HMY_MAX_LAYERS];
@@ -149,6 +193,10 @@ typedef struct hmy_schedule {
   int32_t update_site;
   int32_t gradients;
   int32_t resident_state;
+  int32_t swap_out;
+  int32_t weight_slots;
+  int32_t prefetch_distance;
+  int32_t fwd_micro_batch, bwd_micro_batch;
 } hmy_schedule;
 
 /* One minibatch as a list of n_micro microbatches of micro_batch sequences. */
@@ -208,24 +256,38 @@ typedef struct hmy_tensor_desc {
   uint64_t count;          /* rows*cols */
 } hmy_tensor_desc;
 
-/* Analytic per-layer profile phi(type, U, layer) for one microbatch of
- * micro_batch sequences (the paper measures it, Section 4.2; here it is
- * computed): integer "times" (flops) and byte footprints. */
+/* Per-layer profile phi(type, U, layer) (Section 4.2) for one forward microbatch of U_F and
+ * one backward microbatch of U_B sequences: times in nanoseconds (measured where the budget
+ * brings a measurement for that microbatch size, else flops / compute rate, rounded up),
+ * flop counts, and the byte footprints Algorithm 2 packs by. */
 typedef struct hmy_layer_profile {
-  int64_t t_fwd, t_bwd;   /* forward; recompute + backward                       */
+  int64_t ns_fwd;         /* the layer in a forward task                                   */
+  int64_t ns_bwd;         /* the layer in a backward task: recompute + backward            */
+  int64_t flops_fwd;      /* per forward microbatch; a backward task costs three times the
+                             forward flops of its own microbatch size                      */
   uint64_t params;
-  uint64_t mem_fwd;       /* 3 * weight bytes (three weight slots)                 */
-  uint64_t mem_bwd;       /* 3 * (weight + fp32 gradient) bytes + activations      */
-  uint64_t act_bwd;       /* activations one microbatch keeps for backward         */
+  uint64_t mem_fwd;       /* weight_slots * weight bytes                                   */
+  uint64_t mem_bwd;       /* weight_slots * (weight + fp32 gradient) bytes + activations   */
+  uint64_t act_bwd;       /* activations one backward microbatch keeps                     */
 } hmy_layer_profile;
 
 typedef struct hmy_arena_plan {
   uint64_t total;         /* bytes of HBM the iteration needs (<= budget)          */
   uint64_t reserved;      /* everything that does not depend on the packs          */
-  uint64_t slot_bytes;    /* one weight slot (there are three)                     */
+  uint64_t slot_bytes;    /* one weight slot                                       */
   uint64_t act_bytes;     /* activation workspace of the largest backward pack     */
   uint64_t k_chunk_params;/* optimizer state streams through a ring of such chunks */
+  int32_t weight_slots;   /* as resolved from the schedule                         */
+  int32_t prefetch_distance;
+  int32_t fwd_micro_batch, bwd_micro_batch;
 } hmy_arena_plan;
+
+/* One buffer of the HBM arena (hmy_arena_regions): byte range [offset, offset + bytes)
+ * from the arena's base. */
+typedef struct hmy_region {
+  char name[HMY_NAME_LEN];
+  uint64_t offset, bytes;
+} hmy_region;
 
 typedef struct hmy_handle hmy_handle;
 
@@ -243,26 +305,39 @@ int hmy_model_size(const hmy_model_spec *spec, int32_t *n_layers, uint64_t *n_pa
  * capacity of out in entries. */
 int hmy_layout(const hmy_model_spec *spec, hmy_tensor_desc *out, int32_t cap, int32_t *n);
 
-/* Per-layer profile (out has R entries) and the pack-independent reserve. */
-int hmy_profile(const hmy_model_spec *spec, int32_t n_micro, int32_t micro_batch,
-                hmy_layer_profile *out, uint64_t *reserved_bytes);
+/* Per-layer profile (out has R entries) and the pack-independent reserve, for the
+ * microbatch sizes and slot count of *sched (NULL: the caller's micro_batch in both passes,
+ * three slots; only those fields of it are read) and the rates / measurements of *budget
+ * (NULL: the default rates). */
+int hmy_profile(const hmy_model_spec *spec, const hmy_budget *budget, const hmy_schedule *sched,
+                int32_t n_micro, int32_t micro_batch, hmy_layer_profile *out, uint64_t *reserved_bytes);
 
-/* Balanced-time packing (Algorithm 2) under the budget: backward packs first,
- * forward packs over the layers before the last backward pack. */
+/* The configuration search of Algorithm 1 (Section 4.3.1) over what *budget lets it sweep:
+ * backward microbatch size, weight slots, backward packs by balanced-time packing
+ * (Algorithm 2) under the budget -- backward packs first, forward packs over the layers
+ * before the last backward pack --, forward microbatch size; the configuration with the
+ * smallest estimated iteration time (hmy_estimate) is returned. */
 int hmy_plan(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_micro,
              int32_t micro_batch, hmy_schedule *out);
 
 /* Runtime estimate (integer nanoseconds) of one iteration for a schedule: an
- * event-driven walk of the task list over the compute stream and the two
- * directions of the host link (Section 4.3.1, "Runtime Estimator"), with the
- * rates given in *budget.  This is what hmy_plan minimises when it searches.
- * It models the layer-pack-major order only (sched->order is not looked at). */
+ * event-driven walk of the task list over the compute stream, the two directions of
+ * the host link and, for HMY_UPDATE_ON_HOST, the CPU (Section 4.3.1, "Runtime
+ * Estimator"), from the per-layer profile (hmy_profile) and the link rate of *budget.
+ * This is what hmy_plan minimises.  It models the layer-pack-major order with swapped
+ * optimizer state only (sched->order and ->resident_state are not looked at). */
 int hmy_estimate(const hmy_model_spec *spec, const hmy_schedule *sched, const hmy_budget *budget,
                  int32_t n_micro, int32_t micro_batch, uint64_t *iteration_ns);
 
 /* Validate a schedule and size the HBM arena it needs. */
 int hmy_arena(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro,
               int32_t micro_batch, hmy_arena_plan *out);
+
+/* Every buffer the engine addresses inside that arena, in address order: the
+ * pack-independent buffers by name, "slot0".."slotN", and "acts".  out may be NULL to
+ * query *n only; cap is the capacity of out in entries. */
+int hmy_arena_regions(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro,
+                      int32_t micro_batch, hmy_region *out, int32_t cap, int32_t *n);
 
 /* Walk the iteration's task list (in sched->order) exactly as hmy_iteration does,
  * touching no device: fills only the byte counters of *out. */
@@ -275,7 +350,10 @@ int hmy_count_swaps(const hmy_model_spec *spec, const hmy_schedule *sched, int32
 int hmy_host_alloc(uint64_t bytes, void **out);
 int hmy_host_free(void *p);
 
-/* Create the engine on `hip_device`.  sched == NULL plans with hmy_plan.
+/* Create the Runtime for one configuration (Section 4.4: "executes the task graph ...
+ * with swap-in / compute / swap-out streams"; Section 4.3.2: one task per layer pack and
+ * pass) on `hip_device`.  sched == NULL plans with hmy_plan; n_micro x micro_batch is the
+ * minibatch as hmy_iteration will receive it.
  * arena: device pointer to at least hmy_arena().total bytes, 256-byte aligned,
  * owned by the caller for the handle's lifetime; NULL lets the library
  * allocate it.  Fails with HMY_E_BUDGET_TOO_SMALL if the arena exceeds the
@@ -284,11 +362,28 @@ int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_m
                int32_t micro_batch, const hmy_schedule *sched, int32_t hip_device,
                void *arena, uint64_t arena_bytes, hmy_handle **out);
 int hmy_get_schedule(const hmy_handle *h, hmy_schedule *out);
+/* Hand over the model state that lives in host memory (Section 3: weights, gradients and
+ * optimizer state stay in pinned CPU memory and are swapped per layer pack; Figure
+ * "Tensors that need to be swapped").  The arrays stay the caller's; the library reads
+ * and writes them during hmy_iteration only. */
 int hmy_bind_state(hmy_handle *h, const hmy_host_state *state);
 
-/* One iteration: gradients of the minibatch, Adam on every tensor, swap-byte
+/* One iteration (Section 3, "Key Optimizations"; task order of Algorithm 3 at N = 1):
+ * forward tasks over the forward packs, each over all microbatches (input-batch grouping);
+ * the last pack forward + backward per microbatch (jit-compute); backward tasks in reverse
+ * with recompute from the stashed pack input (Section 4.3.1), each followed by its Weight
+ * Update (jit-update); swap-byte counters per tensor kind (appendix "Additional Swap
+ * Analysis").  Produces the minibatch's gradients, Adam on every tensor, the loss and the
  * counters.  Returns with all streams idle. */
 int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out);
+
+/* The Profiler of Section 4.2 for this library's kernels: runs the embedding, one block
+ * and the head on `hip_device`, forward and backward as the tasks would run them, for one
+ * microbatch of micro_batch sequences (zero inputs: the kernels' time does not depend on
+ * the values), `reps` times each after one warm-up, and reports the average times.
+ * Allocates its own device memory (a one-block arena) and frees it; needs no host state. */
+int hmy_measure_profile(const hmy_model_spec *spec, int32_t micro_batch, int32_t hip_device,
+                        int32_t reps, hmy_measured_profile *out);
 /* Parameters whose optimizer state is resident on the device (0 unless the schedule says
  * HMY_STATE_RESIDENT_IN_SPARE_BUDGET and the budget leaves room for at least one chunk). */
 int hmy_resident_params(const hmy_handle *h, uint64_t *n_params);
@@ -307,10 +402,11 @@ int hmy_set_profiling(hmy_handle *h, int32_t level);
 
 /* 0 = reference kernels (plain tiled loops); 1 = MFMA kernels where they exist
  * (default: the GEMM that streams tiles HBM -> LDS with the load-to-LDS instruction
- * when the shape allows it, else the register-staged one); 2 = the first,
- * 128x128x64 register-staged MFMA GEMM; 3 = the register-staged K-tile-32 MFMA GEMM
- * for every shape.  Attention uses its MFMA kernels for 1..3.  Process-wide; for
- * tests and A/B timing. */
+ * when the shape allows it, else the register-staged one).  2 and 3 are for tests only:
+ * they force the register-staged MFMA GEMMs (the 128x128x64 one; the K-tile-32 one for
+ * every shape) that the default path uses for ragged or misaligned operands, so that
+ * those kernels can be checked on shapes where they would not be chosen.  Attention uses
+ * its MFMA kernels for 1..3.  Process-wide. */
 int hmy_set_kernel_path(int32_t use_mfma);
 
 /* ---- single kernels (all pointers DEVICE, stream = hipStream_t or NULL) ---

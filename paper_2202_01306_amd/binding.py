@@ -22,6 +22,8 @@ HMY_ORDER_LAYER_PACK_MAJOR, HMY_ORDER_MICROBATCH_MAJOR = 0, 1
 HMY_UPDATE_ON_DEVICE, HMY_UPDATE_ON_HOST = 0, 1
 HMY_GRADIENTS_EXPORTED, HMY_GRADIENTS_ON_DEVICE = 0, 1
 HMY_STATE_SWAPPED, HMY_STATE_RESIDENT_IN_SPARE_BUDGET = 0, 1
+HMY_SWAP_OUT_KERNEL, HMY_SWAP_OUT_MEMCPY = 0, 1
+HMY_MAX_WEIGHT_SLOTS = 4
 (HMY_OK, HMY_E_INVALID, HMY_E_BUDGET_TOO_SMALL, HMY_E_BAD_SCHEDULE, HMY_E_HIP,
  HMY_E_NOT_BOUND, HMY_E_NO_DEVICE) = (0, -1, -2, -3, -4, -5, -6)
 
@@ -43,19 +45,46 @@ class hmy_model_spec(C.Structure):
                                          "causal", "precision")] + [("ln_eps", C.c_float)]
 
 
+class hmy_measured_profile(C.Structure):
+    _fields_ = [("micro_batch", C.c_int32), ("reserved_", C.c_int32), ("embed_fwd_ns", C.c_uint64),
+                ("embed_bwd_ns", C.c_uint64), ("block_fwd_ns", C.c_uint64), ("block_bwd_ns", C.c_uint64),
+                ("head_ns", C.c_uint64)]
+
+
+MEASURED_FIELDS = ("micro_batch", "embed_fwd_ns", "embed_bwd_ns", "block_fwd_ns", "block_bwd_ns", "head_ns")
+
+
 class hmy_budget(C.Structure):
     _fields_ = [("hbm_budget_bytes", C.c_uint64), ("host_link_MBps", C.c_uint32), ("compute_GFLOPs", C.c_uint32),
-                ("max_extra_packs", C.c_uint32), ("update_site", C.c_uint32)]
+                ("max_extra_packs", C.c_uint32), ("update_site", C.c_uint32), ("min_weight_slots", C.c_uint32),
+                ("max_weight_slots", C.c_uint32), ("max_fwd_micro_batch", C.c_uint32),
+                ("max_bwd_micro_batch", C.c_uint32), ("n_measured", C.c_uint32),
+                ("measured", C.POINTER(hmy_measured_profile))]
 
 
-def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0, update_site=0) -> hmy_budget:
-    return hmy_budget(int(budget_bytes), int(link_MBps), int(compute_GFLOPs), int(search), int(update_site))
+def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0, update_site=0, slots=(0, 0), max_fwd_micro_batch=0,
+                max_bwd_micro_batch=0, measured=None) -> hmy_budget:
+    """slots: (min, max) weight slots to sweep (0 = 3); measured: list of dicts with MEASURED_FIELDS (what
+    hmy_measure_profile returns), one per microbatch size."""
+    b = hmy_budget(int(budget_bytes), int(link_MBps), int(compute_GFLOPs), int(search), int(update_site),
+                   int(slots[0]), int(slots[1]), int(max_fwd_micro_batch), int(max_bwd_micro_batch), 0, None)
+    if measured:
+        arr = (hmy_measured_profile * len(measured))()
+        for i, mp in enumerate(measured):
+            for f in MEASURED_FIELDS:
+                setattr(arr[i], f, int(mp[f]))
+        b.n_measured = len(measured)
+        b.measured = C.cast(arr, C.POINTER(hmy_measured_profile))
+        b._keep = arr      # the struct only holds the address
+    return b
 
 
 class hmy_schedule(C.Structure):
     _fields_ = [("n_fwd_packs", C.c_int32), ("n_bwd_packs", C.c_int32),
                 ("fwd_pack_end", C.c_int32 * HMY_MAX_LAYERS), ("bwd_pack_end", C.c_int32 * HMY_MAX_LAYERS),
-                ("order", C.c_int32), ("update_site", C.c_int32), ("gradients", C.c_int32), ("resident_state", C.c_int32)]
+                ("order", C.c_int32), ("update_site", C.c_int32), ("gradients", C.c_int32), ("resident_state", C.c_int32),
+                ("swap_out", C.c_int32), ("weight_slots", C.c_int32), ("prefetch_distance", C.c_int32),
+                ("fwd_micro_batch", C.c_int32), ("bwd_micro_batch", C.c_int32)]
 
 
 class hmy_minibatch(C.Structure):
@@ -87,13 +116,18 @@ class hmy_tensor_desc(C.Structure):
 
 
 class hmy_layer_profile(C.Structure):
-    _fields_ = [("t_fwd", C.c_int64), ("t_bwd", C.c_int64), ("params", C.c_uint64),
+    _fields_ = [("ns_fwd", C.c_int64), ("ns_bwd", C.c_int64), ("flops_fwd", C.c_int64), ("params", C.c_uint64),
                 ("mem_fwd", C.c_uint64), ("mem_bwd", C.c_uint64), ("act_bwd", C.c_uint64)]
 
 
 class hmy_arena_plan(C.Structure):
     _fields_ = [("total", C.c_uint64), ("reserved", C.c_uint64), ("slot_bytes", C.c_uint64),
-                ("act_bytes", C.c_uint64), ("k_chunk_params", C.c_uint64)]
+                ("act_bytes", C.c_uint64), ("k_chunk_params", C.c_uint64), ("weight_slots", C.c_int32),
+                ("prefetch_distance", C.c_int32), ("fwd_micro_batch", C.c_int32), ("bwd_micro_batch", C.c_int32)]
+
+
+class hmy_region(C.Structure):
+    _fields_ = [("name", C.c_char * HMY_NAME_LEN), ("offset", C.c_uint64), ("bytes", C.c_uint64)]
 
 
 class hmy_gemm_desc(C.Structure):
@@ -106,6 +140,7 @@ class hmy_gemm_desc(C.Structure):
 
 EXPORTS = [
     "hmy_strerror", "hmy_last_error", "hmy_model_size", "hmy_layout", "hmy_profile", "hmy_plan", "hmy_estimate", "hmy_arena",
+    "hmy_arena_regions", "hmy_measure_profile",
     "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state", "hmy_resident_params", "hmy_sync_state",
     "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
     "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_layernorm_bwd_static", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
@@ -130,12 +165,18 @@ def make_spec(cfg) -> hmy_model_spec:
                           cfg["vocab"], int(cfg["causal"]), prec, float(cfg.get("ln_eps", 1e-5)))
 
 
-def make_schedule(fwd_ends, bwd_ends, order=0, update_site=0, gradients=0, resident_state=0) -> hmy_schedule:
+def make_schedule(fwd_ends, bwd_ends, order=0, update_site=0, gradients=0, resident_state=0, swap_out=0, slots=0,
+                  distance=0, fwd_micro_batch=0, bwd_micro_batch=0) -> hmy_schedule:
     s = hmy_schedule()
     s.order = order
     s.update_site = update_site
     s.gradients = gradients
     s.resident_state = resident_state
+    s.swap_out = swap_out
+    s.weight_slots = slots
+    s.prefetch_distance = distance
+    s.fwd_micro_batch = fwd_micro_batch
+    s.bwd_micro_batch = bwd_micro_batch
     s.n_fwd_packs, s.n_bwd_packs = len(fwd_ends), len(bwd_ends)
     for i, e in enumerate(fwd_ends):
         s.fwd_pack_end[i] = e
@@ -172,28 +213,32 @@ def hmy_layout(spec):
             for t in arr]
 
 
-def hmy_profile(spec, n_micro, micro_batch):
+def hmy_profile(spec, n_micro, micro_batch, sched=None, budget=None):
+    """-> (per-layer profile, pack-independent reserve in bytes) for the microbatch sizes and slot count of
+    `sched` (None: the caller's micro_batch, three slots) and the rates / measurements of `budget` (a make_budget)."""
     R, _ = hmy_model_size(spec)
     arr = (hmy_layer_profile * R)()
     res = C.c_uint64()
-    _check(lib.hmy_profile(C.byref(spec), n_micro, micro_batch, arr, C.byref(res)))
-    prof = [dict(t_fwd=p.t_fwd, t_bwd=p.t_bwd, params=p.params, mem_fwd=p.mem_fwd, mem_bwd=p.mem_bwd,
-                 act_bwd=p.act_bwd) for p in arr]
+    _check(lib.hmy_profile(C.byref(spec), C.byref(budget) if budget is not None else None,
+                           C.byref(sched) if sched is not None else None, n_micro, micro_batch, arr, C.byref(res)))
+    prof = [dict(ns_fwd=p.ns_fwd, ns_bwd=p.ns_bwd, flops_fwd=p.flops_fwd, params=p.params, mem_fwd=p.mem_fwd,
+                 mem_bwd=p.mem_bwd, act_bwd=p.act_bwd) for p in arr]
     return prof, res.value
 
 
 def hmy_plan(spec, budget_bytes, n_micro, micro_batch, search=0, link_MBps=0, compute_GFLOPs=0,
-             update_site=0) -> hmy_schedule:
+             update_site=0, **budget_kw) -> hmy_schedule:
+    """budget_kw: slots=(min, max), max_fwd_micro_batch, max_bwd_micro_batch, measured (see make_budget)."""
     s = hmy_schedule()
-    b = make_budget(budget_bytes, search, link_MBps, compute_GFLOPs, update_site)
+    b = make_budget(budget_bytes, search, link_MBps, compute_GFLOPs, update_site, **budget_kw)
     _check(lib.hmy_plan(C.byref(spec), C.byref(b), n_micro, micro_batch, C.byref(s)))
     return s
 
 
-def hmy_estimate(spec, sched, n_micro, micro_batch, link_MBps=0, compute_GFLOPs=0) -> int:
+def hmy_estimate(spec, sched, n_micro, micro_batch, link_MBps=0, compute_GFLOPs=0, measured=None) -> int:
     ns = C.c_uint64()
-    _check(lib.hmy_estimate(C.byref(spec), C.byref(sched), C.byref(make_budget(0, 0, link_MBps, compute_GFLOPs)),
-                            n_micro, micro_batch, C.byref(ns)))
+    b = make_budget(0, 0, link_MBps, compute_GFLOPs, measured=measured)
+    _check(lib.hmy_estimate(C.byref(spec), C.byref(sched), C.byref(b), n_micro, micro_batch, C.byref(ns)))
     return ns.value
 
 
@@ -201,7 +246,24 @@ def hmy_arena(spec, sched, n_micro, micro_batch):
     a = hmy_arena_plan()
     _check(lib.hmy_arena(C.byref(spec), C.byref(sched), n_micro, micro_batch, C.byref(a)))
     return dict(total=a.total, reserved=a.reserved, slot_bytes=a.slot_bytes, act_bytes=a.act_bytes,
-                k_chunk_params=a.k_chunk_params)
+                k_chunk_params=a.k_chunk_params, weight_slots=a.weight_slots, prefetch_distance=a.prefetch_distance,
+                fwd_micro_batch=a.fwd_micro_batch, bwd_micro_batch=a.bwd_micro_batch)
+
+
+def hmy_arena_regions(spec, sched, n_micro, micro_batch):
+    """-> [(name, offset, bytes)] of every buffer the engine addresses inside its arena."""
+    n = C.c_int32()
+    _check(lib.hmy_arena_regions(C.byref(spec), C.byref(sched), n_micro, micro_batch, None, 0, C.byref(n)))
+    arr = (hmy_region * n.value)()
+    _check(lib.hmy_arena_regions(C.byref(spec), C.byref(sched), n_micro, micro_batch, arr, n.value, C.byref(n)))
+    return [(r.name.decode(), r.offset, r.bytes) for r in arr]
+
+
+def hmy_measure_profile(spec, micro_batch, device=0, reps=3):
+    """Per-layer times of this library's kernels on the device for one microbatch size (needs a GPU)."""
+    mp = hmy_measured_profile()
+    _check(lib.hmy_measure_profile(C.byref(spec), micro_batch, device, reps, C.byref(mp)))
+    return {f: getattr(mp, f) for f in MEASURED_FIELDS}
 
 
 def _stats_dict(st: hmy_stats):
@@ -237,9 +299,10 @@ def hmy_host_free(ptr: int) -> None:
 
 
 def hmy_create(spec, budget_bytes, n_micro, micro_batch, sched=None, device=0, arena_ptr=None, arena_bytes=0,
-               search=0, link_MBps=0, compute_GFLOPs=0):
+               search=0, link_MBps=0, compute_GFLOPs=0, **budget_kw):
     h = C.c_void_p()
-    _check(lib.hmy_create(C.byref(spec), C.byref(make_budget(budget_bytes, search, link_MBps, compute_GFLOPs)),
+    budget = make_budget(budget_bytes, search, link_MBps, compute_GFLOPs, **budget_kw)
+    _check(lib.hmy_create(C.byref(spec), C.byref(budget),
                           n_micro, micro_batch,
                           C.byref(sched) if sched is not None else None, device,
                           C.c_void_p(arena_ptr) if arena_ptr else None, C.c_uint64(arena_bytes), C.byref(h)))

@@ -57,18 +57,28 @@ int hmy_layout(const hmy_model_spec *spec, hmy_tensor_desc *out, int32_t cap, in
   return HMY_OK;
 }
 
-int hmy_profile(const hmy_model_spec *spec, int32_t n_micro, int32_t micro_batch, hmy_layer_profile *out,
-                uint64_t *reserved_bytes) {
+int hmy_profile(const hmy_model_spec *spec, const hmy_budget *budget, const hmy_schedule *sched, int32_t n_micro,
+                int32_t micro_batch, hmy_layer_profile *out, uint64_t *reserved_bytes) {
   Model m;
   int rc = build_model(spec, &m);
   if (rc) return rc;
-  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
+  Packs p;   // only the microbatch sizes and the slot count matter here
+  if (sched) {
+    if (sched->weight_slots < 0 || sched->fwd_micro_batch < 0 || sched->bwd_micro_batch < 0)
+      return fail(HMY_E_BAD_SCHEDULE, "negative slot count or microbatch size");
+    p.slots = sched->weight_slots;
+    p.uF = sched->fwd_micro_batch;
+    p.uB = sched->bwd_micro_batch;
+  }
+  Split sp;
+  rc = resolve(&p, n_micro, micro_batch, &sp);
+  if (rc) return rc;
   if (out) {
     std::vector<hmy_layer_profile> prof;
-    layer_profile(m, n_micro, micro_batch, &prof);
+    layer_profile(m, rates_of(budget), sp, p.slots, &prof);
     for (int l = 0; l < m.R; ++l) out[l] = prof[l];
   }
-  if (reserved_bytes) *reserved_bytes = reserved_layout(m, n_micro, micro_batch).size;
+  if (reserved_bytes) *reserved_bytes = reserved_layout(m, sp).size;
   return HMY_OK;
 }
 
@@ -78,7 +88,6 @@ int hmy_plan(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_mic
   Model m;
   int rc = build_model(spec, &m);
   if (rc) return rc;
-  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
   Packs p;
   rc = plan_packs(m, *budget, n_micro, micro_batch, &p);
   if (rc) return rc;
@@ -92,14 +101,31 @@ int hmy_estimate(const hmy_model_spec *spec, const hmy_schedule *sched, const hm
   Model m;
   int rc = build_model(spec, &m);
   if (rc) return rc;
-  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
   Packs p;
   rc = schedule_to_packs(m, sched, &p);
   if (rc) return rc;
+  Split sp;
+  rc = resolve(&p, n_micro, micro_batch, &sp);
+  if (rc) return rc;
+  const Rates r = rates_of(budget);
   std::vector<hmy_layer_profile> prof;
-  layer_profile(m, n_micro, micro_batch, &prof);
-  *iteration_ns = estimate_iteration_ns(m, prof, p, n_micro, budget->host_link_MBps ? budget->host_link_MBps : 40000,
-                                        budget->compute_GFLOPs ? budget->compute_GFLOPs : 420000);
+  layer_profile(m, r, sp, p.slots, &prof);
+  *iteration_ns = estimate_iteration_ns(m, prof, p, sp, r.link_MBps);
+  return HMY_OK;
+}
+
+// schedule -> resolved packs, split and arena, with the checks every consumer of an arena wants
+static int arena_of(const hmy_model_spec *spec, const hmy_schedule *sched, int n_micro, int micro_batch, Model *m,
+                    Packs *p, Split *sp, Arena *a) {
+  int rc = build_model(spec, m);
+  if (rc) return rc;
+  rc = schedule_to_packs(*m, sched, p);
+  if (rc) return rc;
+  rc = resolve(p, n_micro, micro_batch, sp);
+  if (rc) return rc;
+  *a = arena_layout(*m, *p, *sp);
+  for (const Pack &q : p->fwd)
+    if (pack_state_fwd(*m, q) > a->slot_bytes) return fail(HMY_E_BAD_SCHEDULE, "forward pack over slot");
   return HMY_OK;
 }
 
@@ -107,21 +133,53 @@ int hmy_arena(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_m
               hmy_arena_plan *out) {
   if (!out) return fail(HMY_E_INVALID, "null argument");
   Model m;
-  int rc = build_model(spec, &m);
-  if (rc) return rc;
-  if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
   Packs p;
-  rc = schedule_to_packs(m, sched, &p);
+  Split sp;
+  Arena a;
+  int rc = arena_of(spec, sched, n_micro, micro_batch, &m, &p, &sp, &a);
   if (rc) return rc;
-  const Arena a = arena_layout(m, p, n_micro, micro_batch);
-  for (const Pack &q : p.fwd)
-    if (pack_state_fwd(m, q) > a.slot_bytes) return fail(HMY_E_BAD_SCHEDULE, "forward pack over slot");
   out->total = a.total;
   out->reserved = a.res.size;
   out->slot_bytes = a.slot_bytes;
   out->act_bytes = a.act_bytes;
   out->k_chunk_params = a.res.k_chunk_params;
+  out->weight_slots = p.slots;
+  out->prefetch_distance = p.distance;
+  out->fwd_micro_batch = p.uF;
+  out->bwd_micro_batch = p.uB;
   return HMY_OK;
+}
+
+int hmy_arena_regions(const hmy_model_spec *spec, const hmy_schedule *sched, int32_t n_micro, int32_t micro_batch,
+                      hmy_region *out, int32_t cap, int32_t *n) {
+  if (!n) return fail(HMY_E_INVALID, "null n");
+  Model m;
+  Packs p;
+  Split sp;
+  Arena a;
+  int rc = arena_of(spec, sched, n_micro, micro_batch, &m, &p, &sp, &a);
+  if (rc) return rc;
+  const std::vector<Region> regs = arena_regions(m, a, sp);
+  *n = int32_t(regs.size());
+  if (!out) return HMY_OK;
+  if (cap < *n) return fail(HMY_E_INVALID, "arena_regions: capacity %d < %d regions", cap, *n);
+  for (size_t i = 0; i < regs.size(); ++i) {
+    std::memset(&out[i], 0, sizeof(out[i]));
+    std::strncpy(out[i].name, regs[i].name.c_str(), HMY_NAME_LEN - 1);
+    out[i].offset = regs[i].offset;
+    out[i].bytes = regs[i].bytes;
+  }
+  return HMY_OK;
+}
+
+int hmy_measure_profile(const hmy_model_spec *spec, int32_t micro_batch, int32_t hip_device, int32_t reps,
+                        hmy_measured_profile *out) {
+  if (!out) return fail(HMY_E_INVALID, "null argument");
+  if (micro_batch < 1 || reps < 1 || reps > 1000) return fail(HMY_E_INVALID, "micro_batch >= 1, reps in 1..1000");
+  Model m;
+  int rc = build_model(spec, &m);
+  if (rc) return rc;
+  return run_measure_profile(m, micro_batch, hip_device, reps, out);
 }
 
 int hmy_set_kernel_path(int32_t use_mfma) {

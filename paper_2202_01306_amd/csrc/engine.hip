@@ -15,7 +15,10 @@
 // A "visit" is one task of the ordered list: forward packs in order, then
 // backward packs in reverse, each followed by its update (jit-update).  The
 // first backward visit is the last pack, run forward+backward per microbatch
-// (jit-compute).  Visit v uses weight slot v % kSlots.
+// (jit-compute).  Visit v uses weight slot v % S (S = the schedule's weight_slots); the
+// weights of visit v + distance are prefetched while visit v computes.  The forward visits
+// run the minibatch in microbatches of U_F sequences, the backward visits in microbatches
+// of U_B (Section 4.3.1: the configuration's two microbatch sizes).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -47,7 +50,9 @@ struct hmy_handle {
   Model model;
   Packs packs;
   Arena arena;
-  int M = 0, b = 0;
+  Split sp{};
+  int M = 0, b = 0;     // backward pass: microbatches and sequences in each (sp.MB(), sp.uB)
+  int MF = 0, bF = 0;   // forward pass (sp.MF(), sp.uF)
   int device = -1;
   bool dry = false;
   char *base = nullptr;
@@ -55,10 +60,11 @@ struct hmy_handle {
   hipStream_t s_comp = nullptr, s_in = nullptr, s_kin = nullptr, s_upd = nullptr, s_out = nullptr;
   hmy_host_state host{};
   bool bound = false;
-  char *stash_host = nullptr;   // pinned: checkpoints [n_ckpt][M][x_bytes]
+  char *stash_host = nullptr;   // pinned: checkpoints [n_ckpt][rows of the minibatch][d]
   std::vector<int> ckpt_layers; // first layers of backward packs 1..n_B-2
   std::vector<Visit> visits;
-  BlockActs bacts;
+  BlockActs bacts;     // one block's saved activations at the backward microbatch size
+  BlockActs bacts_F;   // the forward pass's scratch block at its own microbatch size
   HeadActs hacts;
 
   // per-iteration bookkeeping
@@ -75,10 +81,9 @@ struct hmy_handle {
   bool timing = true;
   int profile_level = 0;      // 0 counters only, 1 copy / stall / compute spans, 2 also every GEMM launch
   bool profile_gemm = false;
-  // true: the Adam kernel writes its results directly into the pinned host arrays;
-  // false: results go to the ring / slot and leave by hipMemcpyAsync on s_out
+  // true (HMY_SWAP_OUT_KERNEL): the Adam kernel writes its results directly into the pinned host arrays;
+  // false (HMY_SWAP_OUT_MEMCPY): results go to the ring / slot and leave by hipMemcpyAsync on s_out
   bool fused_swap_out = true;
-  bool k_zero_copy = false;   // the update kernel reads optimizer state straight from pinned host memory
   HostUpdater *updater = nullptr;   // Weight Update on the CPU (packs.update_site == HMY_UPDATE_ON_HOST)
   // Optimizer state resident on the device (HMY_STATE_RESIDENT_IN_SPARE_BUDGET): whole update chunks, numbered
   // in update order over the backward visits; the last res_chunks of them live behind the arena
@@ -211,11 +216,15 @@ const char *wptr(const hmy_handle *h, const Visit &v, const PackPtrs &p, int ten
 float *gptr(const hmy_handle *h, const Visit &v, const PackPtrs &p, int tensor) {
   return p.dW + (h->model.tensors[tensor].offset - v.poff);
 }
-char *Xbuf(const hmy_handle *h, int mb) { return h->base + h->arena.res.X + uint64_t(mb) * h->arena.res.x_bytes; }
-char *inring(const hmy_handle *h, int r) { return h->base + h->arena.res.inring + uint64_t(r) * h->arena.res.x_bytes; }
-char *outring(const hmy_handle *h, int r) { return h->base + h->arena.res.outring + uint64_t(r) * h->arena.res.x_bytes; }
-const int32_t *ids_dev(const hmy_handle *h, int mb) {
-  return reinterpret_cast<const int32_t *>(h->base + h->arena.res.ids) + uint64_t(mb) * h->b * h->model.spec.seq_len;
+// the boundary activations of the minibatch are one [rows, d] array: microbatch mb of either pass is a run of rows
+char *Xbuf(const hmy_handle *h, int mb, bool fwd) {
+  return h->base + h->arena.res.X + uint64_t(mb) * (fwd ? h->arena.res.x_bytes_F : h->arena.res.x_bytes_B);
+}
+char *inring(const hmy_handle *h, int r) { return h->base + h->arena.res.inring + uint64_t(r) * h->arena.res.in_bytes; }
+char *outring(const hmy_handle *h, int r) { return h->base + h->arena.res.outring + uint64_t(r) * h->arena.res.out_bytes; }
+const int32_t *ids_dev(const hmy_handle *h, int mb, bool fwd) {
+  return reinterpret_cast<const int32_t *>(h->base + h->arena.res.ids) +
+         uint64_t(mb) * (fwd ? h->bF : h->b) * h->model.spec.seq_len;
 }
 const int32_t *tgt_dev(const hmy_handle *h, int mb) {
   return reinterpret_cast<const int32_t *>(h->base + h->arena.res.targets) + uint64_t(mb) * h->b * h->model.spec.seq_len;
@@ -288,8 +297,7 @@ struct BlockPtrs {
   char *x_in, *a, *qkv, *o, *x_mid, *hh, *u, *g;
   float *ln1_mean, *ln1_rstd, *ln2_mean, *ln2_rstd, *lse;
 };
-BlockPtrs block_ptrs(const hmy_handle *h, char *region) {
-  const BlockActs &b = h->bacts;
+BlockPtrs block_ptrs(const BlockActs &b, char *region) {
   BlockPtrs p;
   p.x_in = region + b.x_in; p.a = region + b.a; p.qkv = region + b.qkv; p.o = region + b.o;
   p.x_mid = region + b.x_mid; p.hh = region + b.h; p.u = region + b.u; p.g = region + b.g;
@@ -303,14 +311,14 @@ BlockPtrs block_ptrs(const hmy_handle *h, char *region) {
 // the resident boundary buffer (in place); in a backward visit they are distinct
 // saved buffers and y == nullptr skips the second MLP GEMM (output not needed).
 void block_forward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, const BlockPtrs &A,
-                   const char *x_in, char *x_mid, char *y, bool keep_preactivation) {
+                   const char *x_in, char *x_mid, char *y, bool keep_preactivation, int b) {
   const hmy_model_spec &s = h->model.spec;
-  const int prec = s.precision, T = h->b * s.seq_len, d = s.d_model, f = s.d_ffn;
+  const int prec = s.precision, T = b * s.seq_len, d = s.d_model, f = s.d_ffn;
   const int t0 = h->model.first_tensor[layer];
   auto W = [&](int i) { return wptr(h, v, pp, t0 + i); };
   KCHK(h, launch_layernorm_fwd(prec, x_in, W(LN1_G), W(LN1_B), A.a, A.ln1_mean, A.ln1_rstd, T, d, s.ln_eps, h->s_comp));
   linear_fwd(h, A.a, W(WQKV), W(BQKV), nullptr, A.qkv, nullptr, T, 3 * d, d);
-  KCHK(h, launch_attn_fwd(prec, A.qkv, A.o, A.lse, h->b, s.seq_len, s.n_heads, d / s.n_heads, s.causal, h->s_comp));
+  KCHK(h, launch_attn_fwd(prec, A.qkv, A.o, A.lse, b, s.seq_len, s.n_heads, d / s.n_heads, s.causal, h->s_comp));
   linear_fwd(h, A.o, W(WO), W(BO), x_in, x_mid, nullptr, T, d, d);
   KCHK(h, launch_layernorm_fwd(prec, x_mid, W(LN2_G), W(LN2_B), A.hh, A.ln2_mean, A.ln2_rstd, T, d, s.ln_eps, h->s_comp));
   // the MLP's pre-activation u is only read by a backward pass: without one, only gelu(u) is stored
@@ -408,7 +416,7 @@ struct PendingUpdate {
 struct IterState {
   PendingUpdate upd;
   bool compute_done = false;   // nothing is left to enqueue on the compute stream
-  hipEvent_t slot_free[kSlots] = {};
+  hipEvent_t slot_free[kMaxSlots] = {};
   hipEvent_t in_free[kInRing] = {};
   hipEvent_t in_ready[kInRing] = {};
   hipEvent_t out_free[kOutRing] = {};
@@ -425,17 +433,19 @@ int ckpt_index(const hmy_handle *h, int layer) {
     if (h->ckpt_layers[i] == layer) return int(i);
   return -1;
 }
-char *stash_slot(const hmy_handle *h, int ck, int mb) {
-  return h->stash_host + (uint64_t(ck) * h->M + mb) * h->arena.res.x_bytes;
+// checkpoint ck of the whole minibatch is one [rows, d] array like X; either pass addresses its own microbatch in it
+char *stash_slot(const hmy_handle *h, int ck, int mb, bool fwd) {
+  const Reserved &r = h->arena.res;
+  return h->stash_host + uint64_t(ck) * (uint64_t(h->M) * r.x_bytes_B) + uint64_t(mb) * (fwd ? r.x_bytes_F : r.x_bytes_B);
 }
 
 void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int mb) {
   const hmy_model_spec &s = h->model.spec;
-  const int T = h->b * s.seq_len, d = s.d_model;
-  const uint64_t xb = uint64_t(T) * d * h->model.elem_bytes();
+  const int T = h->bF * s.seq_len, d = s.d_model;
+  const uint64_t xb = h->arena.res.x_bytes_F;
   const PackPtrs pp = pack_ptrs(h, v);
-  char *X = Xbuf(h, mb);
-  const BlockPtrs scratch = block_ptrs(h, h->base + h->arena.act_off);
+  char *X = Xbuf(h, mb, true);
+  const BlockPtrs scratch = block_ptrs(h->bacts_F, h->base + h->arena.act_off);
   for (int layer = v.pack.a; layer < v.pack.e; ++layer) {
     const int ck = ckpt_index(h, layer);
     if (ck >= 0) {  // this layer's input is a backward pack's checkpoint: send it to the host
@@ -444,16 +454,16 @@ void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int 
       KCHK(h, launch_copy(outring(h, q), X, xb, h->s_comp));
       hipEvent_t e = rec(h, h->s_comp);
       wait(h, h->s_out, e);
-      if (h->fused_swap_out) d2h_kernel(h, HMY_KIND_SX, stash_slot(h, ck, mb), outring(h, q), xb, h->s_out);
-      else d2h(h, HMY_KIND_SX, stash_slot(h, ck, mb), outring(h, q), xb, h->s_out);
+      if (h->fused_swap_out) d2h_kernel(h, HMY_KIND_SX, stash_slot(h, ck, mb, true), outring(h, q), xb, h->s_out);
+      else d2h(h, HMY_KIND_SX, stash_slot(h, ck, mb, true), outring(h, q), xb, h->s_out);
       it.out_free[q] = rec(h, h->s_out);
     }
     if (layer == 0) {
       const int t0 = h->model.first_tensor[0];
-      KCHK(h, launch_embed_fwd(s.precision, ids_dev(h, mb), wptr(h, v, pp, t0), wptr(h, v, pp, t0 + 1), X, T, d,
+      KCHK(h, launch_embed_fwd(s.precision, ids_dev(h, mb, true), wptr(h, v, pp, t0), wptr(h, v, pp, t0 + 1), X, T, d,
                                s.seq_len, s.vocab, h->s_comp));
     } else {
-      block_forward(h, v, pp, layer, scratch, X, X, X, false);
+      block_forward(h, v, pp, layer, scratch, X, X, X, false, h->bF);
     }
   }
 }
@@ -461,11 +471,11 @@ void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int 
 // enqueue whatever brings the input of backward visit v, microbatch mb, into inring[mb % kInRing]
 void issue_pack_input(hmy_handle *h, IterState &it, const Visit &v, int mb) {
   const int r = mb % kInRing;
-  const uint64_t xb = uint64_t(h->b) * h->model.spec.seq_len * h->model.spec.d_model * h->model.elem_bytes();
+  const uint64_t xb = h->arena.res.x_bytes_B;
   it.in_ready[r] = nullptr;
   if (v.pack.a == 0) return;  // starts at the embedding: restarts from the token ids
   if (v.last) {               // still resident from the forward pass
-    KCHK(h, launch_copy(inring(h, r), Xbuf(h, mb), xb, h->s_comp));
+    KCHK(h, launch_copy(inring(h, r), Xbuf(h, mb, false), xb, h->s_comp));
     return;
   }
   const int ck = ckpt_index(h, v.pack.a);
@@ -474,7 +484,7 @@ void issue_pack_input(hmy_handle *h, IterState &it, const Visit &v, int mb) {
     it.stash_waited = true;
   }
   wait(h, h->s_in, it.in_free[r]);
-  h2d(h, HMY_KIND_SX, inring(h, r), stash_slot(h, ck, mb), xb, h->s_in);
+  h2d(h, HMY_KIND_SX, inring(h, r), stash_slot(h, ck, mb, false), xb, h->s_in);
   it.in_ready[r] = rec(h, h->s_in);
 }
 
@@ -483,7 +493,7 @@ void backward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int
   const int T = h->b * s.seq_len, d = s.d_model, L = s.n_blocks;
   const PackPtrs pp = pack_ptrs(h, v);
   const int r = mb % kInRing;
-  char *D = Xbuf(h, mb);
+  char *D = Xbuf(h, mb, false);
   comp_wait(h, it.in_ready[r]);
   // where each layer of the pack reads its input
   auto input_of = [&](int layer) -> char * {
@@ -497,11 +507,11 @@ void backward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int
     if (layer == 0) {
       if (!has_next) continue;  // embedding alone: its backward needs only ids and dY
       const int t0 = h->model.first_tensor[0];
-      KCHK(h, launch_embed_fwd(s.precision, ids_dev(h, mb), wptr(h, v, pp, t0), wptr(h, v, pp, t0 + 1), input_of(1), T,
+      KCHK(h, launch_embed_fwd(s.precision, ids_dev(h, mb, false), wptr(h, v, pp, t0), wptr(h, v, pp, t0 + 1), input_of(1), T,
                                d, s.seq_len, s.vocab, h->s_comp));
     } else if (layer <= L) {
-      const BlockPtrs A = block_ptrs(h, act_region(h, v.pack, layer));
-      block_forward(h, v, pp, layer, A, input_of(layer), A.x_mid, has_next ? input_of(layer + 1) : nullptr, true);
+      const BlockPtrs A = block_ptrs(h->bacts, act_region(h, v.pack, layer));
+      block_forward(h, v, pp, layer, A, input_of(layer), A.x_mid, has_next ? input_of(layer + 1) : nullptr, true, h->b);
     } else {
       head_forward_backward(h, v, pp, layer, act_region(h, v.pack, layer), input_of(layer), mb, D, it.inv_ntgt);
     }
@@ -510,10 +520,10 @@ void backward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int
   for (int layer = std::min(v.pack.e - 1, L); layer >= v.pack.a; --layer) {
     if (layer == 0) {
       const int t0 = h->model.first_tensor[0];
-      KCHK(h, launch_embed_bwd(s.precision, ids_dev(h, mb), D, gptr(h, v, pp, t0), gptr(h, v, pp, t0 + 1), T, d,
+      KCHK(h, launch_embed_bwd(s.precision, ids_dev(h, mb, false), D, gptr(h, v, pp, t0), gptr(h, v, pp, t0 + 1), T, d,
                                s.seq_len, s.vocab, h->s_comp));
     } else {
-      const BlockPtrs A = block_ptrs(h, act_region(h, v.pack, layer));
+      const BlockPtrs A = block_ptrs(h->bacts, act_region(h, v.pack, layer));
       block_backward(h, v, pp, layer, A, input_of(layer), D);
     }
   }
@@ -536,10 +546,9 @@ void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
   const uint64_t lo = uint64_t(u.next) * R.k_chunk_params;
   const uint64_t n = std::min<uint64_t>(R.k_chunk_params, v.nparams - lo);
   const uint64_t g0 = v.poff + lo;  // element offset in the host arrays
-  const bool zc = h->fused_swap_out && h->k_zero_copy;
   // a chunk whose state lives on the device: updated in place there, nothing of it crosses the link
   const int rslot = h->first_chunk[v.index] + u.next - (h->total_chunks - h->res_chunks);
-  const bool resident = rslot >= 0 && !zc;
+  const bool resident = rslot >= 0;
   const int r = resident ? 0 : it.k_count++ % kKRing;
   char *ring = resident ? h->base + h->res_off + uint64_t(rslot) * h->chunk_state_bytes()
                         : h->base + R.kring + uint64_t(r) * h->model.k_arrays() * R.karr_bytes;
@@ -553,14 +562,6 @@ void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
       h2d(h, HMY_KIND_K, r_v, h->dry ? nullptr : h->host.adam_v + g0, n * 4, h->s_kin);
       wait(h, h->s_upd, rec(h, h->s_kin));
       if (!h->err) h->res_loaded[rslot] = 1;
-    }
-  } else if (zc) {
-    // no staging copy: the state crosses the link inside the update kernel's own loads
-    h->st.h2d[HMY_KIND_K] += uint64_t(h->model.k_arrays()) * n * 4;
-    if (!h->dry) {
-      r_master = mixed ? h->host.master + g0 : nullptr;
-      r_m = h->host.adam_m + g0;
-      r_v = h->host.adam_v + g0;
     }
   } else {
     // on a stream of their own, so that chunk c+1 arrives while chunk c is updated
@@ -587,7 +588,6 @@ void update_chunk(hmy_handle *h, IterState &it, const hmy_adam &hp) {
                               export_g ? h->host.grads + g0 : nullptr, n, hp, it.compute_done, h->s_upd));
       const size_t b2 = trec(h, h->s_upd);
       span(h, a, b2, 1);
-      if (zc) span(h, a, b2, 0);   // the same kernel carries the host->device half
     }
     if (!resident) it.k_free[r] = rec(h, h->s_upd);
   } else {
@@ -677,12 +677,17 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
   const size_t t_first = trec(h, h->s_comp);
   calibrate_event_pair(h);
 
-  // weight prefetch of a visit in M pieces
-  auto w_piece = [&](const Visit &v, int piece) {
+  // weight prefetch of a visit in `pieces` pieces.  Its slot was last used by the visit S places earlier: if that
+  // one's update is still being handed out chunk by chunk, all of it has to be enqueued first, or the event
+  // that says "the slot is free" does not exist yet.
+  auto w_piece = [&](const Visit &v, int piece, int pieces) {
     const uint64_t total = uint64_t(E) * v.nparams;
-    const uint64_t chunk = a256((total + M - 1) / M);
+    const uint64_t chunk = a256((total + pieces - 1) / pieces);
     const uint64_t lo = std::min(total, chunk * piece), hi = std::min(total, chunk * (piece + 1));
-    if (piece == 0) wait(h, h->s_in, it.slot_free[v.slot]);
+    if (piece == 0) {
+      if (it.upd.v && it.upd.v->slot == v.slot) update_progress(h, it, hp, -1);
+      wait(h, h->s_in, it.slot_free[v.slot]);
+    }
     if (hi > lo) {
       char *dst = h->base + h->arena.slot_off[v.slot] + lo;
       const char *src = h->dry ? nullptr : (const char *)h->host.weights + v.poff * E + lo;
@@ -690,35 +695,40 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
     }
   };
 
-  const int nv = int(h->visits.size());
-  for (int p = 0; p < M; ++p) w_piece(h->visits[0], p);
-  hipEvent_t ev_w = rec(h, h->s_in);
+  const int nv = int(h->visits.size()), dist = h->packs.distance;
+  std::vector<hipEvent_t> ev_w(size_t(nv), nullptr);   // per visit: its weights have arrived
+  for (int vi = 0; vi < std::min(dist, nv); ++vi) {
+    w_piece(h->visits[vi], 0, 1);
+    ev_w[vi] = rec(h, h->s_in);
+  }
   for (int vi = 0; vi < nv; ++vi) {
     const Visit &v = h->visits[vi];
-    const Visit *next = vi + 1 < nv ? &h->visits[vi + 1] : nullptr;
-    comp_wait(h, ev_w);
+    const Visit *ahead = vi + dist < nv ? &h->visits[vi + dist] : nullptr;   // the visit whose weights travel now
+    const bool final_visit = vi + 1 == nv;
+    const int Mv = v.bwd ? M : h->MF;                                        // microbatches of this visit's pass
+    comp_wait(h, ev_w[vi]);
     if (vi == 0) comp_wait(h, ev_ids);
     if (v.bwd) {
       if (!it.stash_all_out) it.stash_all_out = rec(h, h->s_out);  // every checkpoint has been queued out
       const PackPtrs pp = pack_ptrs(h, v);
       KCHK(h, launch_fill_zero(pp.dW, v.nparams * 4, h->s_comp));
     }
-    for (int m = 0; m < M; ++m) {
+    for (int m = 0; m < Mv; ++m) {
       h->tag = 1000 * vi + m;
       if (v.bwd) {
         // checkpoints are requested kInRing - 1 microbatches ahead: the copy engine's queue
         // may hold optimizer chunks in front of them that wait for their ring slots
         const bool from_host = !v.last && v.pack.a != 0;
         if (m == 0)
-          for (int q = 0; q < (from_host ? std::min(M, kInRing - 1) : 1); ++q) issue_pack_input(h, it, v, q);
-        if (from_host && m + kInRing - 1 < M) issue_pack_input(h, it, v, m + kInRing - 1);
+          for (int q = 0; q < (from_host ? std::min(Mv, kInRing - 1) : 1); ++q) issue_pack_input(h, it, v, q);
+        if (from_host && m + kInRing - 1 < Mv) issue_pack_input(h, it, v, m + kInRing - 1);
       }
-      if (next) w_piece(*next, m);
+      if (ahead) w_piece(*ahead, m, Mv);
       // this microbatch's share of the previous visit's update
       // (not behind a final visit that is the embedding alone: it is over in a moment, and
       // what is left of the update then runs at the full link rate)
-      const bool tiny_last = !next && v.pack.a == 0 && v.pack.e == 1;
-      if (it.upd.v && !tiny_last) update_progress(h, it, hp, (it.upd.n_chunks * (m + 1) + M - 1) / M);
+      const bool tiny_last = final_visit && v.pack.a == 0 && v.pack.e == 1;
+      if (it.upd.v && !tiny_last) update_progress(h, it, hp, (it.upd.n_chunks * (m + 1) + Mv - 1) / Mv);
       if (v.bwd) {
         if (m > 0 && (v.last || v.pack.a == 0)) issue_pack_input(h, it, v, m);
         backward_visit_microbatch(h, it, v, m);
@@ -726,11 +736,11 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
         forward_visit_microbatch(h, it, v, m);
       }
     }
-    if (next) ev_w = rec(h, h->s_in);
+    if (ahead) ev_w[vi + dist] = rec(h, h->s_in);
     if (!v.bwd) {
       it.slot_free[v.slot] = rec(h, h->s_comp);
     } else {
-      if (!next) it.compute_done = true;   // nothing else will be enqueued on the compute stream
+      if (final_visit) it.compute_done = true;   // nothing else will be enqueued on the compute stream
       pack_update_begin(h, it, v, rec(h, h->s_comp), hp);
     }
   }
@@ -776,12 +786,14 @@ void run_iteration_microbatch_major(hmy_handle *h, const hmy_minibatch *mb, cons
   for (int m = 0; m < M; ++m)
     for (int vi = 0; vi < nv; ++vi) {
       Visit v = h->visits[vi];
-      v.slot = int(seq.size() % kSlots);
+      v.slot = int(seq.size() % size_t(h->packs.slots));
       seq.push_back(v);
     }
   std::vector<hipEvent_t> grads_home(nv, nullptr);   // per visit of a microbatch: its gradient sums have reached the host
 
   auto load_weights = [&](const Visit &v) {
+    // the slot's last user may still have its update handed out chunk by chunk: all of it first (see run_iteration)
+    if (it.upd.v && it.upd.v->slot == v.slot) update_progress(h, it, hp, -1);
     wait(h, h->s_in, it.slot_free[v.slot]);
     h2d(h, HMY_KIND_W, h->base + h->arena.slot_off[v.slot], h->dry ? nullptr : (const char *)h->host.weights + v.poff * E,
         uint64_t(E) * v.nparams, h->s_in);
@@ -850,8 +862,6 @@ static int init_handle(hmy_handle *h, const hmy_model_spec *spec, const hmy_sche
   int rc = build_model(spec, &h->model);
   if (rc) return rc;
   if (n_micro < 1 || micro_batch < 1) return fail(HMY_E_INVALID, "n_micro and micro_batch must be >= 1");
-  h->M = n_micro;
-  h->b = micro_batch;
   if (sched) {
     rc = schedule_to_packs(h->model, sched, &h->packs);
   } else {
@@ -859,15 +869,23 @@ static int init_handle(hmy_handle *h, const hmy_model_spec *spec, const hmy_sche
     rc = plan_packs(h->model, *budget, n_micro, micro_batch, &h->packs);
   }
   if (rc) return rc;
-  h->arena = arena_layout(h->model, h->packs, n_micro, micro_batch);
+  rc = resolve(&h->packs, n_micro, micro_batch, &h->sp);
+  if (rc) return rc;
+  h->M = h->sp.MB();
+  h->b = h->sp.uB;
+  h->MF = h->sp.MF();
+  h->bF = h->sp.uF;
+  h->fused_swap_out = h->packs.swap_out == HMY_SWAP_OUT_KERNEL;
+  h->arena = arena_layout(h->model, h->packs, h->sp);
   // forward packs must fit a weight slot
   for (const Pack &q : h->packs.fwd)
     if (pack_state_fwd(h->model, q) > h->arena.slot_bytes) return fail(HMY_E_BAD_SCHEDULE, "forward pack over slot");
   if (budget && h->arena.total > budget->hbm_budget_bytes)
     return fail(sched ? HMY_E_BAD_SCHEDULE : HMY_E_BUDGET_TOO_SMALL, "schedule needs %llu B of HBM, budget is %llu B",
                 (unsigned long long)h->arena.total, (unsigned long long)budget->hbm_budget_bytes);
-  h->bacts = block_acts(h->model.spec, micro_batch);
-  h->hacts = head_acts(h->model.spec, micro_batch);
+  h->bacts = block_acts(h->model.spec, h->b);
+  h->bacts_F = block_acts(h->model.spec, h->bF);
+  h->hacts = head_acts(h->model.spec, h->b);
   h->ckpt_layers.clear();
   for (size_t k = 1; k + 1 < h->packs.bwd.size(); ++k) h->ckpt_layers.push_back(h->packs.bwd[k].a);
   h->visits.clear();
@@ -876,7 +894,7 @@ static int init_handle(hmy_handle *h, const hmy_model_spec *spec, const hmy_sche
     v.bwd = bwd;
     v.last = last;
     v.pack = p;
-    v.slot = int(h->visits.size() % kSlots);
+    v.slot = int(h->visits.size() % size_t(h->packs.slots));
     v.poff = h->model.layer_off[p.a];
     v.nparams = h->model.params_in(p.a, p.e);
     v.index = int(h->visits.size());
@@ -913,6 +931,92 @@ template <typename F> void for_each_resident_chunk(const hmy_handle *h, F f) {
   }
 }
 }  // namespace
+
+// ---- the Profiler (Section 4.2): each layer on its own, timed on the device -------------
+namespace {
+// small pseudo-random values (|x| < 0.05) in the element type: kernels whose operands are all zero
+// draw less power and run at other clocks than in a real iteration
+__global__ void k_fill_pattern(uint32_t *p, uint64_t n_words, int bf16) {
+  const uint64_t stride = uint64_t(gridDim.x) * blockDim.x;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n_words; i += stride) {
+    uint32_t x = uint32_t(i) * 2654435761u;
+    x ^= x >> 15;
+    x *= 2246822519u;
+    x ^= x >> 13;
+    const float a = (float(x & 0xFFFF) * (1.0f / 65536.0f) - 0.5f) * 0.1f;
+    const float b = (float(x >> 16) * (1.0f / 65536.0f) - 0.5f) * 0.1f;
+    if (bf16) p[i] = (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xFFFF0000u);
+    else p[i] = __float_as_uint(a);
+  }
+}
+}  // namespace
+
+int hmy::run_measure_profile(const Model &m, int micro_batch, int hip_device, int reps, hmy_measured_profile *out) {
+  // a one-block copy of the model, one layer per pack: embedding | block | head
+  hmy_model_spec s1 = m.spec;
+  s1.n_blocks = 1;
+  hmy_schedule sc;
+  std::memset(&sc, 0, sizeof(sc));
+  sc.n_fwd_packs = 2;
+  sc.fwd_pack_end[0] = 1; sc.fwd_pack_end[1] = 2;
+  sc.n_bwd_packs = 3;
+  sc.bwd_pack_end[0] = 1; sc.bwd_pack_end[1] = 2; sc.bwd_pack_end[2] = 3;
+  hmy_handle h;
+  int rc = init_handle(&h, &s1, &sc, nullptr, 1, micro_batch);
+  if (rc) return rc;
+  h.ckpt_layers.clear();   // layers run on their own: nothing is stashed
+  h.timing = false;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1 || hip_device < 0 || hip_device >= ndev)
+    return fail(HMY_E_NO_DEVICE, "no usable HIP device %d (found %d)", hip_device, ndev);
+  h.device = hip_device;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  HIPCHK(&h, hipSetDevice(hip_device));
+  HIPCHK(&h, hipMalloc(reinterpret_cast<void **>(&h.base), h.arena.total));
+  HIPCHK(&h, hipStreamCreateWithFlags(&h.s_comp, hipStreamNonBlocking));
+  HIPCHK(&h, hipEventCreate(&e0));
+  HIPCHK(&h, hipEventCreate(&e1));
+  if (!h.err) {
+    hipLaunchKernelGGL(k_fill_pattern, dim3(2048), dim3(256), 0, h.s_comp, reinterpret_cast<uint32_t *>(h.base),
+                       h.arena.total / 4, h.model.spec.precision == HMY_PREC_BF16 ? 1 : 0);
+    // token ids and targets must be valid indices: all zero
+    KCHK(&h, launch_fill_zero(h.base + h.arena.res.ids, uint64_t(micro_batch) * s1.seq_len * 4, h.s_comp));
+    KCHK(&h, launch_fill_zero(h.base + h.arena.res.targets, uint64_t(micro_batch) * s1.seq_len * 4, h.s_comp));
+    KCHK(&h, launch_fill_zero(h.base + h.arena.res.misc, 4096, h.s_comp));
+  }
+  IterState it;
+  it.inv_ntgt = 1.0f / float(uint64_t(micro_batch) * s1.seq_len);
+  auto timed = [&](const Visit &v) -> uint64_t {
+    auto once = [&]() {
+      if (v.bwd) backward_visit_microbatch(&h, it, v, 0);
+      else forward_visit_microbatch(&h, it, v, 0);
+      h.sync_used = 0;   // the events a visit records for the swap engine are of no use here: recycle them
+    };
+    once();   // warm-up: code objects, caches, clocks
+    HIPCHK(&h, hipEventRecord(e0, h.s_comp));
+    for (int r = 0; r < reps; ++r) once();
+    HIPCHK(&h, hipEventRecord(e1, h.s_comp));
+    HIPCHK(&h, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIPCHK(&h, hipEventElapsedTime(&ms, e0, e1));
+    return uint64_t(double(ms) * 1e6 / reps + 0.5);
+  };
+  std::memset(out, 0, sizeof(*out));
+  out->micro_batch = micro_batch;
+  // visits: forward embedding, forward block, last pack (head, forward + backward), block (recompute + backward),
+  // embedding alone (backward only: its recompute is not needed)
+  out->embed_fwd_ns = timed(h.visits[0]);
+  out->block_fwd_ns = timed(h.visits[1]);
+  out->head_ns = timed(h.visits[2]);
+  out->block_bwd_ns = timed(h.visits[3]);
+  out->embed_bwd_ns = timed(h.visits[4]);
+  if (h.s_comp) { hipStreamSynchronize(h.s_comp); hipStreamDestroy(h.s_comp); }
+  if (e0) hipEventDestroy(e0);
+  if (e1) hipEventDestroy(e1);
+  for (hipEvent_t e : h.sync_events) hipEventDestroy(e);
+  if (h.base) hipFree(h.base);
+  return h.err;
+}
 
 extern "C" {
 
@@ -988,7 +1092,7 @@ int hmy_create(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_m
   if (h->packs.update_site == HMY_UPDATE_ON_HOST && !h->err) {
     h->updater = new HostUpdater(default_host_threads(), updater_thread_init, updater_wait, h);
   }
-  const uint64_t stash_bytes = uint64_t(h->ckpt_layers.size()) * h->M * h->arena.res.x_bytes;
+  const uint64_t stash_bytes = uint64_t(h->ckpt_layers.size()) * h->M * h->arena.res.x_bytes_B;
   if (stash_bytes) HIPCHK(h, hipHostMalloc(reinterpret_cast<void **>(&h->stash_host), stash_bytes, hipHostMallocDefault));
   if (h->err) {
     int e = h->err;
@@ -1024,10 +1128,6 @@ int hmy_bind_state(hmy_handle *h, const hmy_host_state *state) {
   h->host = *state;
   h->bound = true;
   std::fill(h->res_loaded.begin(), h->res_loaded.end(), 0);   // resident state is read afresh from these arrays
-  const char *zc = std::getenv("HMY_FUSED_SWAP_OUT");
-  if (zc) h->fused_swap_out = std::atoi(zc) != 0;
-  const char *kz = std::getenv("HMY_K_ZERO_COPY");
-  if (kz) h->k_zero_copy = std::atoi(kz) != 0;
   return HMY_OK;
 }
 
@@ -1061,8 +1161,9 @@ int hmy_sync_state(hmy_handle *h) {
 int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out) {
   if (!h || !mb || !adam) return fail(HMY_E_INVALID, "null argument");
   if (!h->bound) return fail(HMY_E_NOT_BOUND, "hmy_bind_state has not been called");
-  if (mb->n_micro != h->M || mb->micro_batch != h->b)
-    return fail(HMY_E_INVALID, "minibatch is %dx%d, handle was created for %dx%d", mb->n_micro, mb->micro_batch, h->M, h->b);
+  if (int64_t(mb->n_micro) * mb->micro_batch != h->sp.D || mb->n_micro < 1)
+    return fail(HMY_E_INVALID, "minibatch is %dx%d sequences, handle was created for %d", mb->n_micro, mb->micro_batch,
+                h->sp.D);
   if (!mb->token_ids || !mb->targets) return fail(HMY_E_INVALID, "null token_ids/targets");
   if (adam->step < 1) return fail(HMY_E_INVALID, "adam step is 1-based");
   const hmy_model_spec &s = h->model.spec;

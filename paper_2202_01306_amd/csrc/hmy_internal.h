@@ -41,13 +41,14 @@ int build_model(const hmy_model_spec *spec, Model *out);
 // ---- analytic profile and arena ---------------------------------------------
 inline uint64_t a256(uint64_t x) { return (x + 255) & ~uint64_t(255); }
 
-constexpr int kSlots = 3;              // weight slots: in use, being prefetched, being updated and written back
+constexpr int kMaxSlots = HMY_MAX_WEIGHT_SLOTS;   // weight slots of a schedule: 2 .. kMaxSlots
+constexpr int kDefaultSlots = 3;       // in use, being prefetched, being updated and written back
 constexpr int kOutRing = 4;            // staging buffers for checkpoints going out
 constexpr int kInRing = 4;             // pack-input buffers (checkpoints coming in, up to three microbatches ahead)
 constexpr int kKRing = 3;              // optimizer-state ring slots
 constexpr uint64_t kKChunkMax = 4ull << 20;  // parameters per optimizer chunk
-constexpr int kLogitRows = 512;
-constexpr int kLnBlocks = 256;         // workgroups of a LayerNorm backward, each leaving one row of partial sums        // rows of the vocabulary projection per chunk
+constexpr int kLogitRows = 512;        // rows of the vocabulary projection per chunk
+constexpr int kLnBlocks = 256;         // workgroups of a LayerNorm backward, each leaving one row of partial sums
 
 struct BlockActs {  // byte offsets of one block's saved activations inside its region
   uint64_t x_in, a, qkv, o, x_mid, h, u, g, ln1_mean, ln1_rstd, ln2_mean, ln2_rstd, lse, size;
@@ -60,14 +61,37 @@ struct HeadActs {
 BlockActs block_acts(const hmy_model_spec &s, int micro_batch);
 HeadActs head_acts(const hmy_model_spec &s, int micro_batch);
 
+struct Pack { int a, e; };
+// One configuration: the 4-tuple of Section 4.3.1 plus how the runtime executes it.  uF / uB = 0 and
+// slots / distance = 0 stand for "the caller's microbatch size" and the defaults until resolve() fills them in.
+struct Packs {
+  std::vector<Pack> fwd, bwd;
+  int order = HMY_ORDER_LAYER_PACK_MAJOR;
+  int update_site = HMY_UPDATE_ON_DEVICE;
+  int gradients = HMY_GRADIENTS_EXPORTED;
+  int resident_state = HMY_STATE_SWAPPED;
+  int swap_out = HMY_SWAP_OUT_KERNEL;
+  int slots = 0, distance = 0;
+  int uF = 0, uB = 0;
+};
+// The minibatch of D sequences cut into MF forward microbatches of uF and MB backward microbatches of uB.
+struct Split {
+  int D, uF, uB;
+  int MF() const { return D / uF; }
+  int MB() const { return D / uB; }
+};
+// fills in the defaults of p (slots, distance, uF, uB) for a minibatch of n_micro x micro_batch and checks them
+int resolve(Packs *p, int n_micro, int micro_batch, Split *out);
+
 struct Reserved {  // pack-independent arena regions, byte offsets from the arena base
-  uint64_t X;         // n_micro buffers of x_bytes
-  uint64_t x_bytes;   // a256(T*d*E)
-  uint64_t inring;    // kInRing buffers of x_bytes
-  uint64_t outring;   // kOutRing buffers of x_bytes
-  uint64_t gbig;      // T*max(f,3d)*E : dg/du and dqkv
-  uint64_t gsmall;    // T*d*E : dh, do, da, dz
-  uint64_t delta;     // T*H*4
+  uint64_t X;         // the minibatch's boundary activations, [D*s, d] contiguous
+  uint64_t x_bytes_F, x_bytes_B;   // one forward / backward microbatch of it (unpadded)
+  uint64_t in_bytes, out_bytes;    // a256 of those: one buffer of the rings
+  uint64_t inring;    // kInRing buffers of in_bytes
+  uint64_t outring;   // kOutRing buffers of out_bytes
+  uint64_t gbig;      // T_B*max(f,3d)*E : dg/du and dqkv
+  uint64_t gsmall;    // T_B*d*E : dh, do, da, dz
+  uint64_t delta;     // T_B*H*4
   uint64_t ids, targets;
   uint64_t misc;      // loss accumulators
   uint64_t ln_ws;     // kLnBlocks x 2 d fp32 partial sums of dgamma, dbeta
@@ -76,30 +100,38 @@ struct Reserved {  // pack-independent arena regions, byte offsets from the aren
   uint64_t k_chunk_params;
   uint64_t size;
 };
-Reserved reserved_layout(const Model &m, int n_micro, int micro_batch);
+Reserved reserved_layout(const Model &m, const Split &sp);
 
-void layer_profile(const Model &m, int n_micro, int micro_batch, std::vector<hmy_layer_profile> *out);
-
-struct Pack { int a, e; };
-struct Packs { std::vector<Pack> fwd, bwd; int order = HMY_ORDER_LAYER_PACK_MAJOR; int update_site = HMY_UPDATE_ON_DEVICE; int gradients = HMY_GRADIENTS_EXPORTED; int resident_state = HMY_STATE_SWAPPED; };
+// rates and measurements the profile turns flop counts into times with (defaults filled in)
+struct Rates {
+  uint64_t link_MBps = 40000, compute_GFLOPs = 420000;
+  const hmy_measured_profile *measured = nullptr;
+  uint32_t n_measured = 0;
+};
+Rates rates_of(const hmy_budget *b);
+void layer_profile(const Model &m, const Rates &r, const Split &sp, int slots, std::vector<hmy_layer_profile> *out);
 
 int schedule_to_packs(const Model &m, const hmy_schedule *s, Packs *out);
 void packs_to_schedule(const Packs &p, hmy_schedule *out);
 
 struct Arena {
   Reserved res;
+  int slots;
   uint64_t slot_bytes;
-  uint64_t slot_off[kSlots];
+  uint64_t slot_off[kMaxSlots];
   uint64_t act_off, act_bytes;
   uint64_t total;
 };
-Arena arena_layout(const Model &m, const Packs &p, int n_micro, int micro_batch);
+// p must have been resolved
+Arena arena_layout(const Model &m, const Packs &p, const Split &sp);
 uint64_t pack_state_bwd(const Model &m, Pack p);   // a256(E*P) + a256(4*P)
 uint64_t pack_state_fwd(const Model &m, Pack p);   // a256(E*P)
+struct Region { std::string name; uint64_t offset, bytes; };
+std::vector<Region> arena_regions(const Model &m, const Arena &a, const Split &sp);
 
 int plan_packs(const Model &m, const hmy_budget &budget, int n_micro, int micro_batch, Packs *out);
-uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profile> &prof, const Packs &p, int n_micro,
-                               uint64_t link_MBps, uint64_t compute_GFLOPs);
+uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profile> &prof, const Packs &p,
+                               const Split &sp, uint64_t link_MBps);
 
 // ---- kernel launchers (all pointers device; stream is a hipStream_t) ---------
 typedef void *stream_t;
@@ -178,6 +210,7 @@ class HostUpdater {
 // grid_cap bounds the workgroups: a copy to pinned host memory needs few of them to fill
 // the link and must not crowd the compute units
 int launch_copy(void *dst, const void *src, uint64_t bytes, stream_t st, int grid_cap = 2048);
+int run_measure_profile(const Model &m, int micro_batch, int hip_device, int reps, hmy_measured_profile *out);
 int launch_copy_out(void *dst_host, const void *src, uint64_t bytes, stream_t st);
 int launch_convert_f32(int prec, const float *src, void *dst, uint64_t n, stream_t st);
 

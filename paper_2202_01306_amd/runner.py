@@ -49,12 +49,27 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << 16).view(np.float32)
 
 
+class Pageable:
+    """An ordinary (not page-locked) host buffer with the interface of Pinned."""
+
+    def __init__(self, count: int, dtype):
+        self.a = np.zeros(int(count), dtype=dtype)
+        self.ptr = self.a.ctypes.data
+
+    def free(self) -> None:
+        self.a = None
+        self.ptr = 0
+
+
 class TrainingState:
     """Caller-owned pinned host state in the library's tensor layout."""
 
-    def __init__(self, cfg, with_grads: bool = True):
+    def __init__(self, cfg, with_grads: bool = True, pageable_optimizer_state: bool = False):
         """with_grads=False: no gradient array (only for schedules with HMY_GRADIENTS_ON_DEVICE, layer-pack-major
-        order and the update on the device, which never write it)."""
+        order and the update on the device, which never write it).
+        pageable_optimizer_state=True: master, m and v in ordinary memory -- only for schedules with
+        HMY_UPDATE_ON_HOST, where nothing but the library's CPU threads touches them (page-locked memory is
+        scarce: the weights and gradients, which do cross the link, still get it)."""
         self.cfg = cfg
         self.spec = B.make_spec(cfg)
         self.layout = B.hmy_layout(self.spec)
@@ -63,16 +78,16 @@ class TrainingState:
         n = self.n_params
         self._bufs = []
 
-        def pinned(dtype):
-            p = Pinned(n, dtype)
+        def pinned(dtype, pageable=False):
+            p = Pageable(n, dtype) if pageable else Pinned(n, dtype)
             self._bufs.append(p)
             return p
 
         try:
             self.weights = pinned(np.uint16 if self.mixed else np.float32)   # bf16 bit patterns in mixed mode
-            self.master = pinned(np.float32) if self.mixed else None
-            self.adam_m = pinned(np.float32)
-            self.adam_v = pinned(np.float32)
+            self.master = pinned(np.float32, pageable_optimizer_state) if self.mixed else None
+            self.adam_m = pinned(np.float32, pageable_optimizer_state)
+            self.adam_v = pinned(np.float32, pageable_optimizer_state)
             self.grads = pinned(np.float32) if with_grads else None
         except B.HmyError:
             self.close()      # page-locked memory ran out half way: give back what was taken
@@ -124,21 +139,39 @@ class TrainingState:
         if v is not None:
             self._flat_set(self.adam_v, v)
 
-    def fill_random(self, seed: int = 0, std: float = 0.02) -> None:
+    def fill_random(self, seed: int = 0, std: float = 0.02, tile: int = 0) -> None:
         """Benchmark init without the named round trip: matrices N(0, std^2),
-        LayerNorm gains 1, everything else 0."""
+        LayerNorm gains 1, everything else 0.  tile > 0: draw that many values once and
+        fill every matrix with runs of them (for models of billions of parameters, whose
+        drawing would take minutes; a matrix no larger than the tile has no repeats)."""
         rng = np.random.default_rng(seed)
         tgt = (self.master if self.mixed else self.weights).a
+        pool = rng.standard_normal(tile, dtype=np.float32) * np.float32(std) if tile else None
+        pool16 = f32_to_bf16_bits(pool) if tile and self.mixed else None
+        start = 0
         for t in self.layout:
             sl = tgt[t["offset"]:t["offset"] + t["count"]]
             base = t["name"].split(".")[-1]
-            if t["cols"] > 1:
+            if t["cols"] > 1 and tile:
+                wsl = self.weights.a[t["offset"]:t["offset"] + t["count"]]
+                for lo in range(0, t["count"], tile):      # each matrix starts somewhere else in the pool
+                    n = min(tile, t["count"] - lo)
+                    k = min(n, tile - start)
+                    sl[lo:lo + k] = pool[start:start + k]
+                    sl[lo + k:lo + n] = pool[:n - k]
+                    if self.mixed:
+                        wsl[lo:lo + k] = pool16[start:start + k]
+                        wsl[lo + k:lo + n] = pool16[:n - k]
+                start = (start + 7919 * 1024) % tile
+            elif t["cols"] > 1:
                 sl[:] = rng.standard_normal(t["count"], dtype=np.float32) * np.float32(std)
             elif base.endswith("_g"):
                 sl[:] = 1.0
             else:
                 sl[:] = 0.0
-        if self.mixed:
+            if tile and self.mixed and t["cols"] == 1:
+                self.weights.a[t["offset"]:t["offset"] + t["count"]] = f32_to_bf16_bits(sl)
+        if self.mixed and not tile:
             self._round_weights()
         self.adam_m.a[:] = 0
         self.adam_v.a[:] = 0
@@ -154,14 +187,15 @@ class Engine:
     """One hmy handle bound to a TrainingState."""
 
     def __init__(self, state: TrainingState, budget_bytes: int, n_micro: int, micro_batch: int, sched=None,
-                 device: int = 0, search: int = 0, arena_ptr: int = 0, arena_bytes: int = 0):
+                 device: int = 0, search: int = 0, arena_ptr: int = 0, arena_bytes: int = 0, **budget_kw):
         """arena_ptr / arena_bytes: device memory of the caller's (256-byte aligned, at least the arena's size) for the
-        engine to live in, instead of an allocation of its own; the caller keeps it alive until close()."""
+        engine to live in, instead of an allocation of its own; the caller keeps it alive until close().
+        budget_kw: what the planner may sweep when sched is None (binding.make_budget)."""
         self.state = state
         self.M, self.b = n_micro, micro_batch
         # fails with HMY_E_NO_DEVICE when there is no GPU: there is no CPU fallback
         self.handle = B.hmy_create(state.spec, budget_bytes, n_micro, micro_batch, sched, device, arena_ptr=arena_ptr,
-                                   arena_bytes=arena_bytes, search=search)
+                                   arena_bytes=arena_bytes, search=search, **budget_kw)
         self._ids = None
         self._tgt = None
         try:
