@@ -25,3 +25,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def progress(capsys):
+    """Print a line past pytest's capture: long oracle computations report each step they finish, so that
+    whoever watches the run sees work going on."""
+    def _say(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+    return _say
