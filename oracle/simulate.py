@@ -36,6 +36,11 @@ v mod S of S slots.
             C(v) ends and cannot end before K(v) has arrived.  On the host: only the
             gradient goes out, then the CPU applies the update (its own queue).
   result    the time the last operation ends.
+  slowdown  (optional) kernels run slower while the device->host link is busy beside them.  Given
+            a second set of per-layer times taken beside link traffic, a visit's compute time is
+            its time alone plus the difference to that second time, in proportion to the share of
+            its time alone for which the device->host link still has work queued when it starts
+            (what earlier updates left unfinished, plus its own checkpoints), at most all of it.
 
 Pins (tests/test_oracle_schedule.py): schedules worked by hand; with a link of
 unbounded speed the result is the sum of the compute times, with unbounded compute
@@ -63,6 +68,10 @@ class Op:
     after_end: list = field(default_factory=list)
     after_start: list = field(default_factory=list)
     not_before_end: list = field(default_factory=list)
+    # (resource, duration beside a busy resource): the operation takes `duration` if that resource is idle
+    # when it starts and stretches towards the second figure in proportion to the share of `duration` for
+    # which the operations listed before it on that resource still keep it busy
+    stretch: tuple | None = None
 
 
 def run(ops):
@@ -71,16 +80,18 @@ def run(ops):
     by_name = {o.name: o for o in ops}
     assert len(by_name) == len(ops), "operation names must be unique"
     prev_on_resource = {}
+    last_listed = {}          # per operation: the last operation listed before it on each resource
     last = {}
     for o in ops:
         prev_on_resource[o.name] = last.get(o.resource)
+        last_listed[o.name] = dict(last)
         last[o.resource] = o.name
-    times = {}
+    starts, times = {}, {}
     visiting = set()
 
-    def solve(name):
-        if name in times:
-            return times[name]
+    def start_of(name):
+        if name in starts:
+            return starts[name]
         assert name not in visiting, f"dependency cycle through {name}"
         visiting.add(name)
         o = by_name[name]
@@ -90,11 +101,25 @@ def run(ops):
         for d in o.after_end:
             start = max(start, solve(d)[1])
         for d in o.after_start:
-            start = max(start, solve(d)[0])
-        end = start + o.duration
+            start = max(start, start_of(d))
+        visiting.discard(name)
+        starts[name] = start
+        return start
+
+    def solve(name):
+        if name in times:
+            return times[name]
+        o = by_name[name]
+        start = start_of(name)
+        duration = o.duration
+        if o.stretch is not None and o.duration > 0:
+            resource, beside = o.stretch
+            before = last_listed[name].get(resource)
+            backlog = max(Fraction(0), solve(before)[1] - start) if before is not None else Fraction(0)
+            duration = o.duration + (Fraction(beside) - o.duration) * min(Fraction(1), backlog / o.duration)
+        end = start + duration
         for d in o.not_before_end:
             end = max(end, solve(d)[1])
-        visiting.discard(name)
         times[name] = (start, end)
         return times[name]
 
@@ -111,13 +136,15 @@ def run(ops):
 
 def iteration_ops(spec: om.Spec, P_F, P_B, t_fwd, t_bwd, M_F: int, M_B: int, act_bytes_F: int, act_bytes_B: int,
                   w_c: int, k_B: int, g_B: int, ns_per_byte_in, ns_per_byte_out, slots: int = 3, distance: int = 1,
-                  update_on_host: bool = False, host_ns_per_param=Fraction(1, 6), export_gradients: bool = True):
+                  update_on_host: bool = False, host_ns_per_param=Fraction(1, 6), export_gradients: bool = True,
+                  t_fwd_beside=None, t_bwd_beside=None):
     """Operations of one layer-pack-major iteration.
 
     t_fwd[l], t_bwd[l]: time of layer l for ONE microbatch of the forward / backward
     microbatch size (t_bwd = recompute + backward, or forward + backward for the last
     pack); M_F, M_B: microbatches per pass; act_bytes_F / act_bytes_B: bytes of one
-    microbatch's checkpoint in each pass."""
+    microbatch's checkpoint in each pass.  t_fwd_beside / t_bwd_beside: the same times
+    taken beside link traffic (the slowdown rule); None = no slowdown."""
     assert slots >= 2 and 1 <= distance < slots
     tasks = osch.task_list(spec, P_F, P_B)
     visits = [t for t in tasks if t.kind in "FB"]
@@ -143,14 +170,17 @@ def iteration_ops(spec: om.Spec, P_F, P_B, t_fwd, t_bwd, M_F: int, M_B: int, act
         P = npar(t)
         if t.kind == "F":
             dur = M_F * sum(F(t_fwd[l]) for l in range(*t.pack))
+            beside = M_F * sum(F(t_fwd_beside[l]) for l in range(*t.pack)) if t_fwd_beside is not None else None
         else:
             dur = M_B * sum(F(t_bwd[l]) for l in range(*t.pack))
+            beside = M_B * sum(F(t_bwd_beside[l]) for l in range(*t.pack)) if t_bwd_beside is not None else None
         if t.kind == "B" and t.stash_in_layer is not None:
             ops.append(Op(f"Sin{v}", "h2d", F(M_B * act_bytes_B) * ns_per_byte_in, after_start=[f"C{v}"]))
         if t.kind == "F" and t.stash_out_layers:
             ops.append(Op(f"Sout{v}", "d2h", F(len(t.stash_out_layers) * M_F * act_bytes_F) * ns_per_byte_out,
                           after_start=[f"C{v}"]))
-        ops.append(Op(f"C{v}", "comp", dur, after_end=[f"W{v}"]))
+        ops.append(Op(f"C{v}", "comp", dur, after_end=[f"W{v}"],
+                      stretch=("d2h", beside) if beside is not None else None))
         if t.kind == "F":
             left_slot[v] = f"C{v}"
         elif update_on_host:

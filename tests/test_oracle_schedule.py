@@ -642,3 +642,33 @@ def test_simulated_iteration_limits_and_monotonicity():
         # dropping the consumed gradient shortens the outgoing operation of every update
         assert max(e for _, e in _sim(spec, P_F, P_B, tf, tb, export_gradients=False).values()) <= \
             max(e for _, e in _sim(spec, P_F, P_B, tf, tb).values())
+
+
+def test_simulated_slowdown_beside_a_busy_link_worked_by_hand():
+    """The generic rule first: c takes 10 alone and 16 beside a busy `y`; `y` has work listed before c that ends at
+    4, 10 or 30 while c starts at 0: backlog 4 / 10 / 30 of c's 10 -> 10 + 6 * 0.4 = 12.4, 16, 16; nothing listed: 10.
+    Then the three-visit iteration of the first hand-worked test with backward times doubled beside traffic
+    (C2 = 66 alone, 132 beside): when C2 starts at 195 the outgoing link holds Out1 until 415, a backlog of 220 > 66,
+    so C2 takes all of 132 and ends at 327; K2 (asked at 327, link free at 305) 327-439, Out2 415-639 as before.
+    C1 starts at 111 with nothing outgoing queued: 84 as alone."""
+    for busy_until, want in ((4, Fr(62, 5)), (10, 16), (30, 16)):
+        t = osim.run([osim.Op("w", "y", Fr(busy_until)), osim.Op("c", "x", Fr(10), stretch=("y", 16))])
+        assert t["c"] == (0, want)
+    assert osim.run([osim.Op("c", "x", Fr(10), stretch=("y", 16)), osim.Op("w", "y", Fr(30))])["c"] == (0, 10)
+    tf, tb = [1, 10, 10, 4], [3, 30, 30, 12]
+    t = _sim(_toy(2), [(0, 2)], [(0, 2), (2, 4)], tf, tb, t_fwd_beside=tf, t_bwd_beside=[2 * x for x in tb])
+    assert t["C1"] == (111, 195) and t["C2"] == (195, 327) and t["K2"] == (327, 439) and t["Out2"] == (415, 639)
+    # the same second set of times changes nothing; a larger one never shortens the iteration
+    same = _sim(_toy(2), [(0, 2)], [(0, 2), (2, 4)], tf, tb, t_fwd_beside=tf, t_bwd_beside=tb)
+    assert same == _sim(_toy(2), [(0, 2)], [(0, 2), (2, 4)], tf, tb)
+    spec = _toy(4)
+    P_F, P_B = [(0, 5)], [(i, i + 1) for i in range(6)]
+    tf, tb = [10, 100, 100, 100, 100, 40], [30, 200, 200, 200, 200, 120]
+    base = max(e for _, e in _sim(spec, P_F, P_B, tf, tb, n_out=Fr(1, 32)).values())
+    prev = base
+    for k in (Fr(11, 10), Fr(3, 2), 2):
+        end = max(e for _, e in _sim(spec, P_F, P_B, tf, tb, n_out=Fr(1, 32), t_fwd_beside=[k * x for x in tf],
+                                     t_bwd_beside=[k * x for x in tb]).values())
+        assert end >= prev
+        prev = end
+    assert prev > base
