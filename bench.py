@@ -120,6 +120,78 @@ def cpu_baseline(cfg):
     }
 
 
+def measured_profiles(B, spec, sizes, reps=3):
+    """The Profiler step (Section 4.2): per-layer times of this library's kernels on the device, one entry per
+    microbatch size the planner may consider."""
+    return [B.hmy_measure_profile(spec, u, reps=reps) for u in sizes]
+
+
+def plan_kwargs(a, measured):
+    """What the planner may sweep in this run (binding.make_budget)."""
+    kw = dict(search=a.pack_search, slots=(a.min_slots, a.max_slots))
+    if measured:
+        kw["measured"] = measured
+    return kw
+
+
+def step_bound(total_flops, h2d, d2h, ms, peak):
+    """The step against what bounds it from below: all of its flops at the MFMA peak, or the busier direction of
+    the host link at the rate the link gives with the device otherwise idle (measured, 54 GB/s)."""
+    mfma_s, link_s = total_flops / (peak * 1e12), max(h2d, d2h) / (HOST_LINK_GBPS_ALONE * 1e9)
+    return {"mfma_ms": mfma_s * 1e3, "host_link_ms": link_s * 1e3, "host_link_GBps_alone": HOST_LINK_GBPS_ALONE,
+            "frac": max(mfma_s, link_s) / (ms * 1e-3)}
+
+
+def run_other_workload(B, synth, Engine, TrainingState, name, a, steps=2, update_site="device"):
+    """A short run of another of the named workloads, planned the same way: its own measured profile, packs,
+    time per step, swap volumes and bounds.  Returns a dict for the JSON line, or one that says why it did not run."""
+    cfg = dict(synth.CONFIGS[name])
+    host = update_site == "host"
+    try:
+        st = TrainingState(cfg, pageable_optimizer_state=host)
+    except (B.HmyError, MemoryError) as e:
+        return {"skipped": f"cannot hold the host state on this box: {e}"}
+    try:
+        st.fill_random(0, tile=1 << 27)
+        ids = synth.gen_tokens(cfg, 0)
+        tg = synth.gen_targets(cfg, ids, 0)
+        meas = None if a.analytic_profile else measured_profiles(B, st.spec, [cfg["b"]])
+        site = B.HMY_UPDATE_ON_HOST if host else B.HMY_UPDATE_ON_DEVICE
+        try:
+            eng = Engine(st, cfg["budget"], cfg["M"], cfg["b"], update_site=site, **plan_kwargs(a, meas))
+        except B.HmyError as e:
+            return {"skipped": f"engine: {e}"}
+        with eng:
+            eng.set_batch(ids, tg)
+            eng.step(step=1, want_stats=False)
+            t0 = time.perf_counter()
+            for i in range(steps):
+                stats = eng.step(step=2 + i, want_stats=True)
+            ms = (time.perf_counter() - t0) / steps * 1e3
+            B.hmy_set_profiling(eng.handle, 2)
+            prof = eng.step(step=2 + steps, want_stats=True)
+            packs, arena, sched = eng.packs, eng.arena, eng.sched
+            est_ms = B.hmy_estimate(st.spec, sched, cfg["M"], cfg["b"], measured=meas) / 1e6
+        peak = PEAK_BF16_TFLOPS if cfg["precision"] == "bf16" else PEAK_FP32_TFLOPS
+        h2d, d2h = sum(stats["h2d"].values()), sum(stats["d2h"].values())
+        flops = sum(prof["gemm_flops"]) + attention_flops(cfg, packs)
+        return {"workload": f"{name}: {cfg['n_blocks']} blocks d={cfg['d_model']} heads={cfg['n_heads']} ffn={cfg['d_ffn']} "
+                            f"seq={cfg['seq_len']} vocab={cfg['vocab']}, {cfg['M']} microbatches x {cfg['b']} sequences",
+                "hbm_budget_bytes": cfg["budget"], "arena_bytes": arena["total"], "update_site": update_site,
+                "optimizer_state_memory": "pageable" if host else "pinned",
+                "weight_slots": arena["weight_slots"], "prefetch_distance": arena["prefetch_distance"],
+                "fwd_packs": packs[0], "bwd_packs": packs[1], "steps": steps,
+                "value": cfg["M"] * cfg["b"] / (ms * 1e-3), "unit": "samples/s", "ms_per_step": ms,
+                "planner_estimate_ms": est_ms, "estimate_over_measured": est_ms / ms,
+                "tflops": flops / (ms * 1e-3) / 1e12,
+                "gemm_variants_TFLOPs": [prof["gemm_flops"][i] / max(prof["gemm_s"][i], 1e-12) / 1e12
+                                         if prof["gemm_calls"][i] else None for i in range(4)],
+                "h2d_GB_per_iter": h2d / 1e9, "d2h_GB_per_iter": d2h / 1e9, "loss": stats["loss"],
+                "step_bound": step_bound(flops, h2d, d2h, ms, peak)}
+    finally:
+        st.close()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +201,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pack-search", type=int, default=None,
                     help="how many pack counts beyond the first feasible one the planner may try (0 = Algorithm 2 alone)")
+    ap.add_argument("--min-slots", type=int, default=2, help="fewest weight slots the planner may choose")
+    ap.add_argument("--max-slots", type=int, default=4, help="most weight slots the planner may choose")
+    ap.add_argument("--analytic-profile", action="store_true",
+                    help="plan from flop counts over one sustained rate instead of per-layer times measured at start-up")
     ap.add_argument("--reference-kernels", action="store_true", help="time the plain (non-MFMA) kernels")
     ap.add_argument("--order", choices=("layer-pack-major", "microbatch-major"), default="layer-pack-major",
                     help="microbatch-major: the order the paper compares against, over the same packs (ablation)")
@@ -137,15 +213,20 @@ def main() -> int:
     ap.add_argument("--resident-state", action="store_true",
                     help="keep optimizer state on the device in what the budget leaves free behind the arena")
     ap.add_argument("--no-variants", action="store_true",
-                    help="skip the two extra short runs (update on the host; microbatch-major order) reported under 'variants'")
+                    help="skip the extra short runs reported under 'variants' and 'other_workloads'")
     ap.add_argument("--update-site", choices=("device", "host"), default="device",
                     help="host: the Weight Update task runs on CPU threads (the paper's optimizer offload); "
                          "optimizer state then never crosses the link")
+    ap.add_argument("--counters", action="store_true",
+                    help="for runs under `rocprofv3 --pmc`, where every dispatch is serialised: ONE iteration, no warm-up, "
+                         "no variants, no CPU baseline, and a line on stderr after every visit")
     a = ap.parse_args()
     if a.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {a.gpus} is not supported",
               file=sys.stderr)
         return 2
+    if a.counters:
+        a.steps, a.warmup, a.no_variants, a.no_cpu_baseline, a.analytic_profile = 1, 0, True, True, True
 
     # No PyTorch in this process: the library then runs on the HIP runtime it was
     # linked against (ROCm's own), not on the older copy bundled with the wheel.
@@ -169,58 +250,76 @@ def main() -> int:
     st.fill_random(0)
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
-    sched = None
-    if a.order == "microbatch-major" or a.update_site == "host" or a.gradients == "device" or a.resident_state:
-        site = B.HMY_UPDATE_ON_HOST if a.update_site == "host" else B.HMY_UPDATE_ON_DEVICE
-        sched = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search, update_site=site)
-        sched.order = B.HMY_ORDER_MICROBATCH_MAJOR if a.order == "microbatch-major" else B.HMY_ORDER_LAYER_PACK_MAJOR
-        sched.gradients = B.HMY_GRADIENTS_ON_DEVICE if a.gradients == "device" else B.HMY_GRADIENTS_EXPORTED
-        sched.resident_state = B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET if a.resident_state else B.HMY_STATE_SWAPPED
-    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], sched, search=a.pack_search) as eng:
+    D = cfg["M"] * cfg["b"]
+    # the Profiler step: this library's kernels timed per layer, for the caller's microbatch size and the ones
+    # the configuration search of the 'configuration_search' variant may pick instead
+    sweep_sizes = sorted({u for u in (cfg["b"] // 2, cfg["b"], 2 * cfg["b"]) if u >= 1 and D % u == 0})
+    measured = None if (a.analytic_profile or a.reference_kernels) else measured_profiles(B, st.spec, sweep_sizes)
+    site = B.HMY_UPDATE_ON_HOST if a.update_site == "host" else B.HMY_UPDATE_ON_DEVICE
+    pkw = plan_kwargs(a, measured)
+    sched = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], update_site=site, **pkw)
+    sched.order = B.HMY_ORDER_MICROBATCH_MAJOR if a.order == "microbatch-major" else B.HMY_ORDER_LAYER_PACK_MAJOR
+    sched.gradients = B.HMY_GRADIENTS_ON_DEVICE if a.gradients == "device" else B.HMY_GRADIENTS_EXPORTED
+    sched.resident_state = B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET if a.resident_state else B.HMY_STATE_SWAPPED
+    estimate_ms = B.hmy_estimate(st.spec, sched, cfg["M"], cfg["b"], measured=measured) / 1e6
+    with Engine(st, cfg["budget"], cfg["M"], cfg["b"], sched) as eng:
         eng.set_batch(ids, tg)
         step = 1
+        if a.counters:
+            B.hmy_set_progress(eng.handle, True)
         for _ in range(a.warmup):
             eng.step(step=step, want_stats=False)
             step += 1
         t0 = time.perf_counter()                           # every step returns with all streams idle
         for _ in range(a.steps):
-            eng.step(step=step, want_stats=True)           # profiling level 0: byte counters and loss only
+            stats = eng.step(step=step, want_stats=True)   # profiling level 0: byte counters and loss only
             step += 1
         dt = time.perf_counter() - t0
-        # two more identical steps outside the timed region: one with events around every copy and every
-        # wait of the compute stream (link rates, stall, hidden fraction), one with events around every
-        # GEMM launch as well (the roofline block); the events themselves cost a few percent
-        B.hmy_set_profiling(eng.handle, 1)
-        stats = eng.step(step=step, want_stats=True)
-        step += 1
-        B.hmy_set_profiling(eng.handle, 2)
-        prof = eng.step(step=step, want_stats=True)
-        step += 1
-        B.hmy_set_profiling(eng.handle, 0)
+        prof = stats
+        if not a.counters:
+            # two more identical steps outside the timed region: one with events around every copy and every
+            # wait of the compute stream (link rates, stall, hidden fraction), one with events around every
+            # GEMM launch as well (the roofline block); the events themselves cost a few percent
+            B.hmy_set_profiling(eng.handle, 1)
+            stats = eng.step(step=step, want_stats=True)
+            step += 1
+            B.hmy_set_profiling(eng.handle, 2)
+            prof = eng.step(step=step, want_stats=True)
+            step += 1
+            B.hmy_set_profiling(eng.handle, 0)
         packs, arena, resident = eng.packs, eng.arena, eng.resident_params()
         eng.sync_state()
 
     # Variants outside the timed region of the headline number: the paper's optimizer offload (Weight Update on
     # CPU threads), the paper's own dW traffic (none: the update drops the gradient it consumed instead of
     # exporting it), optimizer state kept on the device in what the budget leaves free behind the arena (then
-    # the host arrays hold that state only after hmy_sync_state), both, and the order the method is compared against.
+    # the host arrays hold that state only after hmy_sync_state), both, the configuration search of Algorithm 1
+    # free to choose another microbatch size per pass, and the order the method is compared against.
     variants = {}
+    others = {}
     if not a.no_variants and a.order == "layer-pack-major" and a.update_site == "device" and not a.reference_kernels:
         LPM, MBM = B.HMY_ORDER_LAYER_PACK_MAJOR, B.HMY_ORDER_MICROBATCH_MAJOR
         DEV, HOST = B.HMY_UPDATE_ON_DEVICE, B.HMY_UPDATE_ON_HOST
         SWAP, RES = B.HMY_STATE_SWAPPED, B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET
         EXP, DROP = B.HMY_GRADIENTS_EXPORTED, B.HMY_GRADIENTS_ON_DEVICE
-        for name, order, site, grads, res, n in (("update_on_host", LPM, HOST, EXP, SWAP, max(2, a.steps)),
-                                                 ("gradients_on_device", LPM, DEV, DROP, SWAP, max(2, a.steps)),
-                                                 ("resident_state", LPM, DEV, EXP, RES, max(2, a.steps)),
-                                                 ("resident_state+gradients_on_device", LPM, DEV, DROP, RES, max(2, a.steps)),
-                                                 ("microbatch_major", MBM, DEV, EXP, SWAP, 2)):
-            if (grads == DROP) == (a.gradients == "device") and (res == RES) == a.resident_state and order == LPM and site == DEV:
+        for name, order, vsite, grads, res, n, sweep in (
+                ("update_on_host", LPM, HOST, EXP, SWAP, max(2, a.steps), False),
+                ("gradients_on_device", LPM, DEV, DROP, SWAP, max(2, a.steps), False),
+                ("resident_state", LPM, DEV, EXP, RES, max(2, a.steps), False),
+                ("resident_state+gradients_on_device", LPM, DEV, DROP, RES, max(2, a.steps), False),
+                ("configuration_search", LPM, DEV, EXP, SWAP, max(2, a.steps), True),
+                ("microbatch_major", MBM, DEV, EXP, SWAP, 2, False)):
+            if (grads == DROP) == (a.gradients == "device") and (res == RES) == a.resident_state and order == LPM \
+                    and vsite == DEV and not sweep:
                 continue    # that is the headline run itself
             # the host variant over the packs the planner picks for it (its estimate knows that only the
-            # gradient crosses the link then); the other two over the headline's packs
-            vs = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], search=a.pack_search, update_site=site)
+            # gradient crosses the link then); the others over the headline's packs
+            kw = dict(pkw)
+            if sweep:
+                kw.update(max_fwd_micro_batch=sweep_sizes[-1], max_bwd_micro_batch=sweep_sizes[-1])
+            vs = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], update_site=vsite, **kw)
             vs.order, vs.gradients, vs.resident_state = order, grads, res
+            vest = B.hmy_estimate(st.spec, vs, cfg["M"], cfg["b"], measured=measured) / 1e6
             with Engine(st, cfg["budget"], cfg["M"], cfg["b"], vs) as eng:
                 eng.set_batch(ids, tg)
                 eng.step(step=step, want_stats=False)
@@ -230,12 +329,25 @@ def main() -> int:
                     vstats = eng.step(step=step, want_stats=True)
                     step += 1
                 vms = (time.perf_counter() - t0) / n * 1e3
-                vpacks, vres = eng.packs, eng.resident_params()
+                vpacks, vres, varena = eng.packs, eng.resident_params(), eng.arena
                 eng.sync_state()      # the next variant starts from complete host arrays
             variants[name] = {"fwd_packs": vpacks[0], "bwd_packs": vpacks[1], "resident_state_params": vres,
+                              "weight_slots": varena["weight_slots"], "prefetch_distance": varena["prefetch_distance"],
+                              "fwd_micro_batch": varena["fwd_micro_batch"], "bwd_micro_batch": varena["bwd_micro_batch"],
                               "value": cfg["M"] * cfg["b"] / (vms * 1e-3), "unit": "samples/s", "ms_per_step": vms, "steps": n,
+                              "planner_estimate_ms": None if (order == MBM or res == RES) else vest,
                               "h2d_GB_per_iter": sum(vstats["h2d"].values()) / 1e9,
                               "d2h_GB_per_iter": sum(vstats["d2h"].values()) / 1e9}
+    st.close()      # page-locked memory back before the other workloads take theirs
+    if not a.no_variants and a.config == "gpt2m" and a.order == "layer-pack-major" and a.update_site == "device" \
+            and not a.reference_kernels:
+        # the other named workloads, two steps each: the encoder (compute-bound), the 1.5 B decoder, and the
+        # 6.7 B decoder whole with the update on the host (124 GB of page-locked state does not fit this box;
+        # with the optimizer on the CPU only weights and gradients need locking)
+        others["bertl"] = run_other_workload(B, synth, Engine, TrainingState, "bertl", a)
+        others["gpt2xl"] = run_other_workload(B, synth, Engine, TrainingState, "gpt2xl", a)
+        others["gpt6b7_update_on_host"] = run_other_workload(B, synth, Engine, TrainingState, "gpt6b7", a,
+                                                             update_site="host")
 
     ms = dt / a.steps * 1e3
     samples = cfg["M"] * cfg["b"]
@@ -258,7 +370,14 @@ def main() -> int:
                                f"ffn={cfg['d_ffn']} seq={cfg['seq_len']} vocab={cfg['vocab']}, "
                                f"{cfg['M']} microbatches x {cfg['b']} sequences",
                    "hbm_budget_bytes": cfg["budget"], "arena_bytes": arena["total"],
-                   "order": a.order, "update_site": a.update_site, "gradients": a.gradients, "resident_state_params": resident, "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
+                   "order": a.order, "update_site": a.update_site, "gradients": a.gradients, "resident_state_params": resident,
+                   "fwd_packs": packs[0], "bwd_packs": packs[1], "pack_search": a.pack_search,
+                   "weight_slots": arena["weight_slots"], "prefetch_distance": arena["prefetch_distance"],
+                   "weight_slots_swept": [a.min_slots, a.max_slots],
+                   "fwd_micro_batch": arena["fwd_micro_batch"], "bwd_micro_batch": arena["bwd_micro_batch"],
+                   "profile": "measured per layer at start-up" if measured else "flops over one sustained rate",
+                   "measured_profile_ns": measured,
+                   "planner_estimate_ms": estimate_ms, "estimate_over_measured": estimate_ms / ms,
                    "kernels": "reference" if a.reference_kernels else "mfma"},
         "tflops": total_flops / (ms * 1e-3) / 1e12,
         "swap": {"h2d_GB_per_iter": h2d / 1e9, "d2h_GB_per_iter": d2h / 1e9,
@@ -278,7 +397,8 @@ def main() -> int:
         "roofline": {"bound": "mfma", "kernel": VARIANTS[dom], "achieved": dom_tflops, "peak": peak,
                      "unit": "TFLOP/s", "frac": dom_tflops / peak,
                      "traffic": traffic[0] if traffic else None,
-                     "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; stored, not live)",
+                     "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; stored, not live: "
+                                     "profiles/gpt2m_forward_gemm_hbm_traffic.md)",
                      "algorithmic_bytes_per_launch": traffic[1] if traffic else None,
                      "launches": prof["gemm_calls"][dom],
                      "avg_launch_us": prof["gemm_s"][dom] / max(prof["gemm_calls"][dom], 1) * 1e6,
@@ -293,16 +413,13 @@ def main() -> int:
                                "busy_ms": stats["t_d2h_busy_s"] * 1e3,
                                "note": "peak = what the same kernels reach with nothing else running (measured); "
                                        "throttled on purpose beside the compute stream"},
-        # the whole step against what bounds it from below: all of its flops at the MFMA peak, or the busier
-        # direction of the host link at the rate the link gives with the device otherwise idle (measured, 54 GB/s)
-        "step_bound": {"mfma_ms": total_flops / (peak * 1e12) * 1e3,
-                       "host_link_ms": max(h2d, d2h) / (HOST_LINK_GBPS_ALONE * 1e9) * 1e3,
-                       "host_link_GBps_alone": HOST_LINK_GBPS_ALONE,
-                       "frac": max(total_flops / (peak * 1e12), max(h2d, d2h) / (HOST_LINK_GBPS_ALONE * 1e9)) / (ms * 1e-3)},
+        "step_bound": step_bound(total_flops, h2d, d2h, ms, peak),
         "loss": stats["loss"],
     }
     if variants:
         out["variants"] = variants
+    if others:
+        out["other_workloads"] = others
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

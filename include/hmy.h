@@ -72,7 +72,11 @@ typedef struct hmy_model_spec {
 
 /* Per-layer times measured on the device for one microbatch size (Section 4.2, Profiler:
  * "runs each layer individually and records ... compute time"), as hmy_measure_profile
- * returns them.  Times are nanoseconds for ONE microbatch of micro_batch sequences. */
+ * returns them.  Times are nanoseconds for ONE microbatch of micro_batch sequences.  Every
+ * time comes twice: with the device to itself, and (`_beside`) while host-link traffic runs
+ * on other streams as it does beside the compute stream in an iteration (copies arriving
+ * from pinned host memory; for the backward figures also a throttled kernel writing to it):
+ * kernels run some 10-30 % slower then.  A `_beside` field of 0 means "as alone". */
 typedef struct hmy_measured_profile {
   int32_t micro_batch;
   int32_t reserved_;
@@ -82,6 +86,7 @@ typedef struct hmy_measured_profile {
                              needs (the recompute), then backward                          */
   uint64_t head_ns;       /* final LayerNorm + vocabulary projection + loss, forward and
                              backward (the head only ever runs in the last pack)           */
+  uint64_t embed_fwd_beside_ns, embed_bwd_beside_ns, block_fwd_beside_ns, block_bwd_beside_ns, head_beside_ns;
 } hmy_measured_profile;
 
 /* The machine model of Algorithm 1: memory capacity alpha, host-link bandwidth beta,
@@ -263,6 +268,8 @@ typedef struct hmy_tensor_desc {
 typedef struct hmy_layer_profile {
   int64_t ns_fwd;         /* the layer in a forward task                                   */
   int64_t ns_bwd;         /* the layer in a backward task: recompute + backward            */
+  int64_t ns_fwd_beside;  /* the same two beside host-link traffic (= the figures above     */
+  int64_t ns_bwd_beside;  /* unless the budget brings measurements of both)                */
   int64_t flops_fwd;      /* per forward microbatch; a backward task costs three times the
                              forward flops of its own microbatch size                      */
   uint64_t params;
@@ -324,6 +331,8 @@ int hmy_plan(const hmy_model_spec *spec, const hmy_budget *budget, int32_t n_mic
  * event-driven walk of the task list over the compute stream, the two directions of
  * the host link and, for HMY_UPDATE_ON_HOST, the CPU (Section 4.3.1, "Runtime
  * Estimator"), from the per-layer profile (hmy_profile) and the link rate of *budget.
+ * A task's compute time lies between its layers' times alone and beside link traffic, in
+ * proportion to the share of it for which the outgoing link has work queued at its start.
  * This is what hmy_plan minimises.  It models the layer-pack-major order with swapped
  * optimizer state only (sched->order and ->resident_state are not looked at). */
 int hmy_estimate(const hmy_model_spec *spec, const hmy_schedule *sched, const hmy_budget *budget,
@@ -379,9 +388,12 @@ int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, 
 
 /* The Profiler of Section 4.2 for this library's kernels: runs the embedding, one block
  * and the head on `hip_device`, forward and backward as the tasks would run them, for one
- * microbatch of micro_batch sequences (zero inputs: the kernels' time does not depend on
- * the values), `reps` times each after one warm-up, and reports the average times.
- * Allocates its own device memory (a one-block arena) and frees it; needs no host state. */
+ * microbatch of micro_batch sequences (pseudo-random inputs: the kernels' time does not
+ * depend on the values, but all-zero operands draw less power and clock higher), `reps`
+ * times each after a warm-up, once with the device to itself and once beside host-link
+ * traffic on two more streams (see hmy_measured_profile), and reports the average times.
+ * Allocates its own device memory (a one-block arena, two 128 MiB staging buffers) and
+ * frees it; needs no host state. */
 int hmy_measure_profile(const hmy_model_spec *spec, int32_t micro_batch, int32_t hip_device,
                         int32_t reps, hmy_measured_profile *out);
 /* Parameters whose optimizer state is resident on the device (0 unless the schedule says
@@ -399,6 +411,11 @@ int hmy_destroy(hmy_handle *h);
  * (t_compute_s, t_h2d_busy_s, t_d2h_busy_s, t_stall_s); 2: also every GEMM launch
  * (gemm_s; two more event records per launch). */
 int hmy_set_profiling(hmy_handle *h, int32_t level);
+/* on != 0: a layer-pack-major iteration waits for the compute stream after every visit and
+ * prints one line per visit to stderr.  For runs under a tool that serialises every kernel
+ * dispatch (counter collection), where an iteration takes minutes: the lines show that it
+ * advances.  Costs the overlap between visits; never use it for timing. */
+int hmy_set_progress(hmy_handle *h, int32_t on);
 
 /* 0 = reference kernels (plain tiled loops); 1 = MFMA kernels where they exist
  * (default: the GEMM that streams tiles HBM -> LDS with the load-to-LDS instruction
@@ -413,21 +430,30 @@ int hmy_set_kernel_path(int32_t use_mfma);
  * prec selects the element type E of activations/weights (HMY_PREC_*).  These
  * are the per-layer operations of one microbatch, T = rows. */
 
-/* x[T,d] = wte[id] + wpe[t % s] */
-int hmy_k_embed_fwd(int32_t prec, const int32_t *ids, const void *wte, const void *wpe, void *x,
+/* The residual stream -- the activations x that run from block to block and, on the way
+ * back, their gradients -- is fp32 in every precision: each block adds a small update to a
+ * large running sum, and rounding that sum to bf16 after every addition piles the errors of
+ * 2 * n_blocks roundings into every gradient.  So the x, res and dx arguments below are
+ * float arrays whatever prec is; gamma, beta, y, dy and everything else a block computes
+ * have the element type E(prec). */
+
+/* x[T,d] (fp32) = wte[id] + wpe[t % s] */
+int hmy_k_embed_fwd(int32_t prec, const int32_t *ids, const void *wte, const void *wpe, float *x,
                     int32_t T, int32_t d, int32_t s, int32_t vocab, void *stream);
-/* dwte[id] += dx, dwpe[t % s] += dx  (fp32 accumulators) */
-int hmy_k_embed_bwd(int32_t prec, const int32_t *ids, const void *dx, float *dwte, float *dwpe,
+/* dwte[id] += dx, dwpe[t % s] += dx  (dx fp32; fp32 accumulators) */
+int hmy_k_embed_bwd(int32_t prec, const int32_t *ids, const float *dx, float *dwte, float *dwpe,
                     int32_t T, int32_t d, int32_t s, int32_t vocab, void *stream);
-/* y = gamma * (x-mean)*rstd + beta; mean,rstd [T] fp32 saved */
-int hmy_k_layernorm_fwd(int32_t prec, const void *x, const void *gamma, const void *beta, void *y,
+/* y (type E) = gamma * (x-mean)*rstd + beta; x fp32; mean,rstd [T] fp32 saved */
+int hmy_k_layernorm_fwd(int32_t prec, const float *x, const void *gamma, const void *beta, void *y,
                         float *mean, float *rstd, int32_t T, int32_t d, float eps, void *stream);
-/* dx = (res ? res : 0) + LN'(dy); dgamma,dbeta += (fp32).  dx may alias res.
+/* dx (fp32) = (res ? res : 0) + LN'(dy); dgamma,dbeta += (fp32).  dy has type E; x, res and
+ * dx are fp32; dx may alias res.  dx_e (may be NULL): a copy of dx rounded to type E, which is
+ * what the GEMMs that consume this gradient read.
  * workspace (device, may be NULL): with at least 256 * 2 * d floats the per-workgroup
  * partial sums of dgamma / dbeta go there and a second kernel adds them up; without it
  * they are added with atomics (same result up to summation order, slower). */
-int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float *mean,
-                        const float *rstd, const void *gamma, const void *res, void *dx,
+int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const float *x, const float *mean,
+                        const float *rstd, const void *gamma, const float *res, float *dx, void *dx_e,
                         float *dgamma, float *dbeta, int32_t T, int32_t d, void *stream,
                         float *workspace, uint64_t workspace_bytes);
 /* hmy_k_layernorm_bwd for callers that cannot allocate device memory (code under HIP graph
@@ -440,9 +466,10 @@ int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float
  * the array: calls that may overlap there (different streams, different threads) race on it
  * and must be ordered by the caller; calls on one stream are ordered already.  Nothing in
  * the array has to be cleared between calls. */
-int hmy_k_layernorm_bwd_static(int32_t prec, const void *dy, const void *x, const float *mean,
-                               const float *rstd, const void *gamma, const void *res, void *dx,
-                               float *dgamma, float *dbeta, int32_t T, int32_t d, void *stream);
+int hmy_k_layernorm_bwd_static(int32_t prec, const void *dy, const float *x, const float *mean,
+                               const float *rstd, const void *gamma, const float *res, float *dx,
+                               void *dx_e, float *dgamma, float *dbeta, int32_t T, int32_t d,
+                               void *stream);
 /* g = gelu_tanh(u); du = dg * gelu'(u) (du may alias dg) */
 int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream);
 int hmy_k_gelu_bwd(int32_t prec, const void *dg, const void *u, void *du, uint64_t n, void *stream);
@@ -453,7 +480,8 @@ int hmy_k_colsum(int32_t prec, const void *a, float *out, int32_t T, int32_t N, 
  * gelu_out = gelu(C).  A is [M,K] (ta=0) or stored [K,M] (ta=1); B is stored
  * [N,K] (tb=0: y = x W^T) or [K,N] (tb=1).  A, B, bias, res, gelu_out have
  * element type E(prec); C has type E, or fp32 if c_fp32.  accumulate: C += (only
- * with c_fp32).  Leading dimensions in elements.  gelu_out may be C itself: then C
+ * with c_fp32).  res_fp32: res is an fp32 array (the residual stream; C is then fp32 too:
+ * c_fp32 must be set).  Leading dimensions in elements.  gelu_out may be C itself: then C
  * ends up holding gelu of the (rounded) result and nothing else is stored -- what a
  * forward pass wants that keeps no pre-activation for a backward pass. */
 typedef struct hmy_gemm_desc {
@@ -465,6 +493,7 @@ typedef struct hmy_gemm_desc {
   const void *bias;
   const void *res; int64_t ldr;
   void *gelu_out;
+  int32_t res_fp32;
 } hmy_gemm_desc;
 int hmy_k_gemm(const hmy_gemm_desc *g, void *stream);
 

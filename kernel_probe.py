@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Run every hot kernel of the iteration on its own, at the shapes of a workload.
 
-    python paper_2202_01306_amd/kernel_probe.py [--config gpt2m] [--reps 20] [--sets 6] [--only "gemm fwd"]
+    python kernel_probe.py [--config gpt2m] [--reps 20] [--sets 6] [--only "gemm fwd"]
 
 Device tensors only (no pinned host memory, no engine), so the script also runs
 under `rocprofv3 --pmc ...`, which is how the per-kernel counters in profiles/ are
@@ -16,7 +16,7 @@ import argparse
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -76,12 +76,14 @@ def main() -> int:
         ldc = ldc or N
         As = [rnd(K if ta else M, lda, scale=0.5) for _ in range(n)]
         Bs = [rnd(K if tb else N, ldb, scale=0.02) for _ in range(n)]
-        Cs = [torch.zeros(M, ldc, device="cuda", dtype=torch.float32 if acc or c32 else dt) for _ in range(n)]
+        # a residual is the fp32 residual stream: the output is fp32 too
+        Cs = [torch.zeros(M, ldc, device="cuda", dtype=torch.float32 if acc or c32 or res else dt) for _ in range(n)]
         bs = rnd(N) if bias else None
-        rs = [rnd(M, N) for _ in range(n)] if res else None
+        rs = [rnd(M, N, dtype=torch.float32) for _ in range(n)] if res else None
         gs = [torch.empty(M, N, device="cuda", dtype=dt) for _ in range(n)] if gelu else None
-        fns = [(lambda i=i: B.hmy_k_gemm(pc, M, N, K, As[i], lda, Bs[i], ldb, Cs[i], ldc, ta=ta, tb=tb, c_fp32=int(acc or c32),
-                                         accumulate=int(acc), bias=bs, res=rs[i] if res else None, ldr=N if res else 0,
+        fns = [(lambda i=i: B.hmy_k_gemm(pc, M, N, K, As[i], lda, Bs[i], ldb, Cs[i], ldc, ta=ta, tb=tb,
+                                         c_fp32=int(acc or c32 or res), accumulate=int(acc), bias=bs,
+                                         res=rs[i] if res else None, ldr=N if res else 0, res_fp32=int(res),
                                          gelu_out=gs[i] if gelu else None)) for i in range(n)]
         timed(name, fns, 2.0 * M * N * K, "TFLOP/s")
 
@@ -117,18 +119,20 @@ def main() -> int:
           [(lambda i=i: B.hmy_k_attn_bwd(pc, qkv[i], o[i], do[i], lse[i], delta, dqkv, b, s, H, dh, causal)) for i in range(n)],
           2.5 * att_flops, "TFLOP/s")
 
-    x = [rnd(T, d) for _ in range(n)]
+    x = [rnd(T, d, dtype=torch.float32) for _ in range(n)]      # the residual stream is fp32
     dy = [rnd(T, d) for _ in range(n)]
     gam, bet = torch.ones(d, device="cuda", dtype=dt), torch.zeros(d, device="cuda", dtype=dt)
     y = torch.empty(T, d, device="cuda", dtype=dt)
     mean, rstd = torch.empty(T, device="cuda"), torch.empty(T, device="cuda")
     timed("layernorm forward", [(lambda i=i: B.hmy_k_layernorm_fwd(pc, x[i], gam, bet, y, mean, rstd, T, d, synth.LN_EPS)) for i in range(n)],
-          2.0 * T * d * 2, "GB/s")
+          T * d * (4.0 + 2.0), "GB/s")
     dgm, dbt = torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda")
     ws = torch.empty(256 * 2 * d, device="cuda")
+    dx32 = torch.empty(T, d, device="cuda")
     timed("layernorm backward (+ partial-sum reduce)",
-          [(lambda i=i: B.hmy_k_layernorm_bwd(pc, dy[i], x[i], mean, rstd, gam, x[(i + 1) % n], y, dgm, dbt, T, d, workspace=ws))
-           for i in range(n)], 4.0 * T * d * 2, "GB/s")
+          [(lambda i=i: B.hmy_k_layernorm_bwd(pc, dy[i], x[i], mean, rstd, gam, x[(i + 1) % n], dx32, dgm, dbt, T, d, workspace=ws,
+                                              dx_e=y))
+           for i in range(n)], T * d * (2.0 + 4 + 4 + 4 + 2), "GB/s")     # dy, x, res in; dx (fp32) and its bf16 copy out
     u = [rnd(T, f) for _ in range(n)]
     dg = [rnd(T, f) for _ in range(n)]
     du = torch.empty(T, f, device="cuda", dtype=dt)

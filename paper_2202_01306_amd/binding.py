@@ -48,10 +48,13 @@ class hmy_model_spec(C.Structure):
 class hmy_measured_profile(C.Structure):
     _fields_ = [("micro_batch", C.c_int32), ("reserved_", C.c_int32), ("embed_fwd_ns", C.c_uint64),
                 ("embed_bwd_ns", C.c_uint64), ("block_fwd_ns", C.c_uint64), ("block_bwd_ns", C.c_uint64),
-                ("head_ns", C.c_uint64)]
+                ("head_ns", C.c_uint64), ("embed_fwd_beside_ns", C.c_uint64), ("embed_bwd_beside_ns", C.c_uint64),
+                ("block_fwd_beside_ns", C.c_uint64), ("block_bwd_beside_ns", C.c_uint64), ("head_beside_ns", C.c_uint64)]
 
 
 MEASURED_FIELDS = ("micro_batch", "embed_fwd_ns", "embed_bwd_ns", "block_fwd_ns", "block_bwd_ns", "head_ns")
+MEASURED_BESIDE_FIELDS = ("embed_fwd_beside_ns", "embed_bwd_beside_ns", "block_fwd_beside_ns", "block_bwd_beside_ns",
+                          "head_beside_ns")
 
 
 class hmy_budget(C.Structure):
@@ -73,6 +76,8 @@ def make_budget(budget_bytes, search=0, link_MBps=0, compute_GFLOPs=0, update_si
         for i, mp in enumerate(measured):
             for f in MEASURED_FIELDS:
                 setattr(arr[i], f, int(mp[f]))
+            for f in MEASURED_BESIDE_FIELDS:      # optional: 0 = as alone
+                setattr(arr[i], f, int(mp.get(f, 0)))
         b.n_measured = len(measured)
         b.measured = C.cast(arr, C.POINTER(hmy_measured_profile))
         b._keep = arr      # the struct only holds the address
@@ -116,7 +121,8 @@ class hmy_tensor_desc(C.Structure):
 
 
 class hmy_layer_profile(C.Structure):
-    _fields_ = [("ns_fwd", C.c_int64), ("ns_bwd", C.c_int64), ("flops_fwd", C.c_int64), ("params", C.c_uint64),
+    _fields_ = [("ns_fwd", C.c_int64), ("ns_bwd", C.c_int64), ("ns_fwd_beside", C.c_int64), ("ns_bwd_beside", C.c_int64),
+                ("flops_fwd", C.c_int64), ("params", C.c_uint64),
                 ("mem_fwd", C.c_uint64), ("mem_bwd", C.c_uint64), ("act_bwd", C.c_uint64)]
 
 
@@ -135,14 +141,14 @@ class hmy_gemm_desc(C.Structure):
                 ("ta", C.c_int32), ("tb", C.c_int32), ("c_fp32", C.c_int32), ("accumulate", C.c_int32),
                 ("A", C.c_void_p), ("lda", C.c_int64), ("B", C.c_void_p), ("ldb", C.c_int64),
                 ("C", C.c_void_p), ("ldc", C.c_int64), ("bias", C.c_void_p),
-                ("res", C.c_void_p), ("ldr", C.c_int64), ("gelu_out", C.c_void_p)]
+                ("res", C.c_void_p), ("ldr", C.c_int64), ("gelu_out", C.c_void_p), ("res_fp32", C.c_int32)]
 
 
 EXPORTS = [
     "hmy_strerror", "hmy_last_error", "hmy_model_size", "hmy_layout", "hmy_profile", "hmy_plan", "hmy_estimate", "hmy_arena",
     "hmy_arena_regions", "hmy_measure_profile",
     "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state", "hmy_resident_params", "hmy_sync_state",
-    "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
+    "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_progress", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
     "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_layernorm_bwd_static", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
     "hmy_k_gemm", "hmy_k_attn_fwd", "hmy_k_attn_bwd", "hmy_k_xent", "hmy_k_adam", "hmy_host_adam",
 ]
@@ -221,7 +227,8 @@ def hmy_profile(spec, n_micro, micro_batch, sched=None, budget=None):
     res = C.c_uint64()
     _check(lib.hmy_profile(C.byref(spec), C.byref(budget) if budget is not None else None,
                            C.byref(sched) if sched is not None else None, n_micro, micro_batch, arr, C.byref(res)))
-    prof = [dict(ns_fwd=p.ns_fwd, ns_bwd=p.ns_bwd, flops_fwd=p.flops_fwd, params=p.params, mem_fwd=p.mem_fwd,
+    prof = [dict(ns_fwd=p.ns_fwd, ns_bwd=p.ns_bwd, ns_fwd_beside=p.ns_fwd_beside, ns_bwd_beside=p.ns_bwd_beside,
+                 flops_fwd=p.flops_fwd, params=p.params, mem_fwd=p.mem_fwd,
                  mem_bwd=p.mem_bwd, act_bwd=p.act_bwd) for p in arr]
     return prof, res.value
 
@@ -260,10 +267,11 @@ def hmy_arena_regions(spec, sched, n_micro, micro_batch):
 
 
 def hmy_measure_profile(spec, micro_batch, device=0, reps=3):
-    """Per-layer times of this library's kernels on the device for one microbatch size (needs a GPU)."""
+    """Per-layer times of this library's kernels on the device for one microbatch size, alone and beside
+    host-link traffic (needs a GPU)."""
     mp = hmy_measured_profile()
     _check(lib.hmy_measure_profile(C.byref(spec), micro_batch, device, reps, C.byref(mp)))
-    return {f: getattr(mp, f) for f in MEASURED_FIELDS}
+    return {f: getattr(mp, f) for f in MEASURED_FIELDS + MEASURED_BESIDE_FIELDS}
 
 
 def _stats_dict(st: hmy_stats):
@@ -348,6 +356,11 @@ def hmy_set_profiling(h, level: int) -> None:
     _check(lib.hmy_set_profiling(h, int(level)))
 
 
+def hmy_set_progress(h, on: bool) -> None:
+    """A line on stderr after every visit (the iteration then waits for each visit's kernels)."""
+    _check(lib.hmy_set_progress(h, int(bool(on))))
+
+
 def _p(x):
     """Device/host address of a torch tensor, an int, or None."""
     if x is None:
@@ -370,14 +383,16 @@ def hmy_k_layernorm_fwd(prec, x, gamma, beta, y, mean, rstd, T, d, eps, stream=N
                                    C.c_float(eps), _p(stream)))
 
 
-def hmy_k_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None, workspace=None):
+def hmy_k_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None, workspace=None,
+                        dx_e=None):
+    """x, res, dx: fp32 (the residual stream); dy, gamma: element type; dx_e: optional element-typed copy of dx."""
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib.hmy_k_layernorm_bwd(prec, _p(dy), _p(x), _p(mean), _p(rstd), _p(gamma), _p(res), _p(dx),
+    _check(lib.hmy_k_layernorm_bwd(prec, _p(dy), _p(x), _p(mean), _p(rstd), _p(gamma), _p(res), _p(dx), _p(dx_e),
                                    _p(dgamma), _p(dbeta), T, d, _p(stream), _p(workspace), C.c_uint64(ws_bytes)))
 
 
-def hmy_k_layernorm_bwd_static(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None):
-    _check(lib.hmy_k_layernorm_bwd_static(prec, _p(dy), _p(x), _p(mean), _p(rstd), _p(gamma), _p(res), _p(dx),
+def hmy_k_layernorm_bwd_static(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None, dx_e=None):
+    _check(lib.hmy_k_layernorm_bwd_static(prec, _p(dy), _p(x), _p(mean), _p(rstd), _p(gamma), _p(res), _p(dx), _p(dx_e),
                                           _p(dgamma), _p(dbeta), T, d, _p(stream)))
 
 
@@ -394,9 +409,9 @@ def hmy_k_colsum(prec, a, out, T, N, stream=None):
 
 
 def hmy_k_gemm(prec, M, N, K, A, lda, B, ldb, Cc, ldc, ta=0, tb=0, c_fp32=0, accumulate=0, bias=None, res=None,
-               ldr=0, gelu_out=None, stream=None):
+               ldr=0, gelu_out=None, stream=None, res_fp32=0):
     g = hmy_gemm_desc(prec, M, N, K, ta, tb, c_fp32, accumulate, _p(A), lda, _p(B), ldb, _p(Cc), ldc,
-                      _p(bias), _p(res), ldr, _p(gelu_out))
+                      _p(bias), _p(res), ldr, _p(gelu_out), res_fp32)
     _check(lib.hmy_k_gemm(C.byref(g), _p(stream)))
 
 

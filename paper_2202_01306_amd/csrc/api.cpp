@@ -191,33 +191,33 @@ int hmy_set_kernel_path(int32_t use_mfma) {
 #define NOTNULL(p) \
   if (!(p)) return fail(HMY_E_INVALID, "%s: null pointer %s", __func__, #p)
 
-int hmy_k_embed_fwd(int32_t prec, const int32_t *ids, const void *wte, const void *wpe, void *x, int32_t T, int32_t d,
+int hmy_k_embed_fwd(int32_t prec, const int32_t *ids, const void *wte, const void *wpe, float *x, int32_t T, int32_t d,
                     int32_t s, int32_t vocab, void *stream) {
   NOTNULL(ids); NOTNULL(wte); NOTNULL(wpe); NOTNULL(x);
   return launch_embed_fwd(prec, ids, wte, wpe, x, T, d, s, vocab, stream);
 }
-int hmy_k_embed_bwd(int32_t prec, const int32_t *ids, const void *dx, float *dwte, float *dwpe, int32_t T, int32_t d,
+int hmy_k_embed_bwd(int32_t prec, const int32_t *ids, const float *dx, float *dwte, float *dwpe, int32_t T, int32_t d,
                     int32_t s, int32_t vocab, void *stream) {
   NOTNULL(ids); NOTNULL(dx); NOTNULL(dwte); NOTNULL(dwpe);
   return launch_embed_bwd(prec, ids, dx, dwte, dwpe, T, d, s, vocab, stream);
 }
-int hmy_k_layernorm_fwd(int32_t prec, const void *x, const void *gamma, const void *beta, void *y, float *mean,
+int hmy_k_layernorm_fwd(int32_t prec, const float *x, const void *gamma, const void *beta, void *y, float *mean,
                         float *rstd, int32_t T, int32_t d, float eps, void *stream) {
   NOTNULL(x); NOTNULL(gamma); NOTNULL(beta); NOTNULL(y); NOTNULL(mean); NOTNULL(rstd);
   return launch_layernorm_fwd(prec, x, gamma, beta, y, mean, rstd, T, d, eps, stream);
 }
-int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const void *x, const float *mean, const float *rstd,
-                        const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int32_t T, int32_t d,
-                        void *stream, float *workspace, uint64_t workspace_bytes) {
+int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const float *x, const float *mean, const float *rstd,
+                        const void *gamma, const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta, int32_t T,
+                        int32_t d, void *stream, float *workspace, uint64_t workspace_bytes) {
   NOTNULL(dy); NOTNULL(x); NOTNULL(mean); NOTNULL(rstd); NOTNULL(gamma); NOTNULL(dx); NOTNULL(dgamma); NOTNULL(dbeta);
-  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream, workspace,
+  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, stream, workspace,
                               workspace_bytes);
 }
-int hmy_k_layernorm_bwd_static(int32_t prec, const void *dy, const void *x, const float *mean, const float *rstd,
-                               const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int32_t T,
-                               int32_t d, void *stream) {
+int hmy_k_layernorm_bwd_static(int32_t prec, const void *dy, const float *x, const float *mean, const float *rstd,
+                               const void *gamma, const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta,
+                               int32_t T, int32_t d, void *stream) {
   NOTNULL(dy); NOTNULL(x); NOTNULL(mean); NOTNULL(rstd); NOTNULL(gamma); NOTNULL(dx); NOTNULL(dgamma); NOTNULL(dbeta);
-  return launch_layernorm_bwd_static(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream);
+  return launch_layernorm_bwd_static(prec, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, stream);
 }
 int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream) {
   NOTNULL(u); NOTNULL(g);

@@ -70,9 +70,40 @@ __global__ void k_convert_f32(const float *src, E *dst, uint64_t nvec) {
   }
 }
 
+// ---- the residual stream ----------------------------------------------------------
+// The activations that run from block to block (x, and their gradients on the way back) are
+// fp32 in every precision: each block adds a small update to a large running sum, and rounding
+// that sum to bf16 after every addition lets the errors of 2 x n_blocks roundings pile up in
+// it (about 1.5 % of its size after 24 blocks, which every gradient then inherits).  Everything
+// a block computes from the stream is still the element type E.
+template <int VEC> __device__ __forceinline__ void load_stream(const float *p, float (&v)[VEC]) {
+#pragma unroll
+  for (int k = 0; k < VEC; k += 4) {
+    const float4 a = *reinterpret_cast<const float4 *>(p + k);
+    v[k] = a.x; v[k + 1] = a.y; v[k + 2] = a.z; v[k + 3] = a.w;
+  }
+}
+template <int VEC> __device__ __forceinline__ void store_stream(float *p, const float (&v)[VEC]) {
+#pragma unroll
+  for (int k = 0; k < VEC; k += 4) *reinterpret_cast<float4 *>(p + k) = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+}
+
+// dst[i] = float(src[i])
+template <typename E>
+__global__ void k_convert_to_f32(const E *src, float *dst, uint64_t nvec) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec; i += uint64_t(gridDim.x) * blockDim.x) {
+    const Vec16<E> a = load16(src + i * VEC);
+    float v[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) v[k] = to_f32(a.v[k]);
+    store_stream<VEC>(dst + i * VEC, v);
+  }
+}
+
 // ---- embedding ---------------------------------------------------------------
 template <typename E>
-__global__ void k_embed_fwd(const int32_t *ids, const E *wte, const E *wpe, E *x, int T, int d, int s) {
+__global__ void k_embed_fwd(const int32_t *ids, const E *wte, const E *wpe, float *x, int T, int d, int s) {
   constexpr int VEC = ElemTraits<E>::VEC;
   const int vec_per_row = d / VEC;
   const uint64_t total = uint64_t(T) * vec_per_row;
@@ -80,30 +111,29 @@ __global__ void k_embed_fwd(const int32_t *ids, const E *wte, const E *wpe, E *x
     const int t = int(i / vec_per_row), c = int(i % vec_per_row) * VEC;
     const Vec16<E> a = load16(wte + uint64_t(ids[t]) * d + c);
     const Vec16<E> p = load16(wpe + uint64_t(t % s) * d + c);
-    Vec16<E> o;
+    float o[VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) o.v[k] = from_f32<E>(to_f32(a.v[k]) + to_f32(p.v[k]));
-    store16(x + uint64_t(t) * d + c, o);
+    for (int k = 0; k < VEC; ++k) o[k] = to_f32(a.v[k]) + to_f32(p.v[k]);
+    store_stream<VEC>(x + uint64_t(t) * d + c, o);
   }
 }
 // dwte[id[t]] += dx[t]  (rows may repeat: atomics)
-template <typename E>
-__global__ void k_embed_bwd_wte(const int32_t *ids, const E *dx, float *dwte, int T, int d) {
-  constexpr int VEC = ElemTraits<E>::VEC;
+__global__ void k_embed_bwd_wte(const int32_t *ids, const float *dx, float *dwte, int T, int d) {
+  constexpr int VEC = 4;
   const int vec_per_row = d / VEC;
   const uint64_t total = uint64_t(T) * vec_per_row;
   for (uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += uint64_t(gridDim.x) * blockDim.x) {
     const int t = int(i / vec_per_row), c = int(i % vec_per_row) * VEC;
-    const Vec16<E> g = load16(dx + uint64_t(t) * d + c);
+    float g[VEC];
+    load_stream<VEC>(dx + uint64_t(t) * d + c, g);
     float *dst = dwte + uint64_t(ids[t]) * d + c;
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) atomicAdd(dst + k, to_f32(g.v[k]));
+    for (int k = 0; k < VEC; ++k) atomicAdd(dst + k, g[k]);
   }
 }
 // dwpe[j] += sum over sequences of dx[i*s + j]  (one owner per element: no atomics)
-template <typename E>
-__global__ void k_embed_bwd_wpe(const E *dx, float *dwpe, int T, int d, int s) {
-  constexpr int VEC = ElemTraits<E>::VEC;
+__global__ void k_embed_bwd_wpe(const float *dx, float *dwpe, int T, int d, int s) {
+  constexpr int VEC = 4;
   const int vec_per_row = d / VEC;
   const int nseq = T / s;
   const uint64_t total = uint64_t(s) * vec_per_row;
@@ -113,9 +143,10 @@ __global__ void k_embed_bwd_wpe(const E *dx, float *dwpe, int T, int d, int s) {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) acc[k] = 0.f;
     for (int q = 0; q < nseq; ++q) {
-      const Vec16<E> g = load16(dx + (uint64_t(q) * s + j) * d + c);
+      float g[VEC];
+      load_stream<VEC>(dx + (uint64_t(q) * s + j) * d + c, g);
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) acc[k] += to_f32(g.v[k]);
+      for (int k = 0; k < VEC; ++k) acc[k] += g[k];
     }
     float *dst = dwpe + uint64_t(j) * d + c;
 #pragma unroll
@@ -125,27 +156,30 @@ __global__ void k_embed_bwd_wpe(const E *dx, float *dwpe, int T, int d, int s) {
 
 // ---- LayerNorm -----------------------------------------------------------------
 // One wavefront per row.  Mean, then biased variance about the mean, then the
-// normalised output; the row is re-read from cache between passes.
+// normalised output; the row is re-read from cache between passes.  x is the fp32
+// residual stream; gamma, beta and the output have the element type.
 template <typename E>
-__global__ void k_layernorm_fwd(const E *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T, int d,
+__global__ void k_layernorm_fwd(const float *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T, int d,
                                 float eps) {
   constexpr int VEC = ElemTraits<E>::VEC;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   for (int row = blockIdx.x * kWavesPerBlock + wave; row < T; row += gridDim.x * kWavesPerBlock) {
-    const E *xr = x + uint64_t(row) * d;
+    const float *xr = x + uint64_t(row) * d;
     float s = 0.f;
     for (int c = lane * VEC; c < d; c += kWave * VEC) {
-      const Vec16<E> v = load16(xr + c);
+      float v[VEC];
+      load_stream<VEC>(xr + c, v);
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) s += to_f32(v.v[k]);
+      for (int k = 0; k < VEC; ++k) s += v[k];
     }
     const float mu = wave_sum(s) / float(d);
     float q = 0.f;
     for (int c = lane * VEC; c < d; c += kWave * VEC) {
-      const Vec16<E> v = load16(xr + c);
+      float v[VEC];
+      load_stream<VEC>(xr + c, v);
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
-        const float t = to_f32(v.v[k]) - mu;
+        const float t = v[k] - mu;
         q += t * t;
       }
     }
@@ -156,10 +190,12 @@ __global__ void k_layernorm_fwd(const E *x, const E *gamma, const E *beta, E *y,
     }
     E *yr = y + uint64_t(row) * d;
     for (int c = lane * VEC; c < d; c += kWave * VEC) {
-      const Vec16<E> v = load16(xr + c), g = load16(gamma + c), b = load16(beta + c);
+      float v[VEC];
+      load_stream<VEC>(xr + c, v);
+      const Vec16<E> g = load16(gamma + c), b = load16(beta + c);
       Vec16<E> o;
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) o.v[k] = from_f32<E>(to_f32(g.v[k]) * ((to_f32(v.v[k]) - mu) * rs) + to_f32(b.v[k]));
+      for (int k = 0; k < VEC; ++k) o.v[k] = from_f32<E>(to_f32(g.v[k]) * ((v[k] - mu) * rs) + to_f32(b.v[k]));
       store16(yr + c, o);
     }
   }
@@ -170,7 +206,7 @@ __global__ void k_layernorm_fwd(const E *x, const E *gamma, const E *beta, E *y,
 // sizes it runs at, so its time is latency, not bandwidth).  Same arithmetic: mean, then
 // biased variance about the mean.
 template <typename E, int NJ>
-__global__ __launch_bounds__(kBlock) void k_layernorm_fwd_reg(const E *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T,
+__global__ __launch_bounds__(kBlock) void k_layernorm_fwd_reg(const float *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T,
                                     int d, float eps) {
   constexpr int VEC = ElemTraits<E>::VEC;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
@@ -184,19 +220,19 @@ __global__ __launch_bounds__(kBlock) void k_layernorm_fwd_reg(const E *x, const 
     }
   }
   for (int row = blockIdx.x * kWavesPerBlock + wave; row < T; row += gridDim.x * kWavesPerBlock) {
-    const E *xr = x + uint64_t(row) * d;
-    Vec16<E> xv[NJ];
+    const float *xr = x + uint64_t(row) * d;
+    float xv[NJ][VEC];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int c = VEC * (lane + kWave * j);
-      if (c < d) xv[j] = load16(xr + c);
+      if (c < d) load_stream<VEC>(xr + c, xv[j]);
     }
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       if (VEC * (lane + kWave * j) < d) {
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) s += to_f32(xv[j].v[k]);
+        for (int k = 0; k < VEC; ++k) s += xv[j][k];
       }
     }
     const float mu = wave_sum(s) / float(d);
@@ -206,7 +242,7 @@ __global__ __launch_bounds__(kBlock) void k_layernorm_fwd_reg(const E *x, const 
       if (VEC * (lane + kWave * j) < d) {
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
-          const float t = to_f32(xv[j].v[k]) - mu;
+          const float t = xv[j][k] - mu;
           q += t * t;
         }
       }
@@ -224,7 +260,7 @@ __global__ __launch_bounds__(kBlock) void k_layernorm_fwd_reg(const E *x, const 
         Vec16<E> o;
 #pragma unroll
         for (int k = 0; k < VEC; ++k)
-          o.v[k] = from_f32<E>(to_f32(gm[j].v[k]) * ((to_f32(xv[j].v[k]) - mu) * rs) + to_f32(bt[j].v[k]));
+          o.v[k] = from_f32<E>(to_f32(gm[j].v[k]) * ((xv[j][k] - mu) * rs) + to_f32(bt[j].v[k]));
         store16(yr + c, o);
       }
     }
@@ -232,11 +268,12 @@ __global__ __launch_bounds__(kBlock) void k_layernorm_fwd_reg(const E *x, const 
 }
 
 // dx = res + (dxhat - mean(dxhat) - xhat*mean(dxhat*xhat)) * rstd, dxhat = dy*gamma;
-// dgamma += sum_rows dy*xhat, dbeta += sum_rows dy.  Per-block partial column
-// sums live in LDS (2*d floats) and are flushed with one atomic per column.
+// dgamma += sum_rows dy*xhat, dbeta += sum_rows dy.  x, res and dx are the fp32 residual stream;
+// dx_e, if given, receives dx rounded to the element type (the copy that feeds the GEMMs).
+// Per-block partial column sums live in LDS (2*d floats) and are flushed with one atomic per column.
 template <typename E>
-__global__ void k_layernorm_bwd(const E *dy, const E *x, const float *mean, const float *rstd, const E *gamma,
-                                const E *res, E *dx, float *dgamma, float *dbeta, int T, int d) {
+__global__ void k_layernorm_bwd(const E *dy, const float *x, const float *mean, const float *rstd, const E *gamma,
+                                const float *res, float *dx, E *dx_e, float *dgamma, float *dbeta, int T, int d) {
   constexpr int VEC = ElemTraits<E>::VEC;
   extern __shared__ float lds[];
   float *s_dg = lds, *s_db = lds + d;
@@ -244,14 +281,17 @@ __global__ void k_layernorm_bwd(const E *dy, const E *x, const float *mean, cons
   __syncthreads();
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   for (int row = blockIdx.x * kWavesPerBlock + wave; row < T; row += gridDim.x * kWavesPerBlock) {
-    const E *xr = x + uint64_t(row) * d, *dyr = dy + uint64_t(row) * d;
+    const float *xr = x + uint64_t(row) * d;
+    const E *dyr = dy + uint64_t(row) * d;
     const float mu = mean[row], rs = rstd[row];
     float s1 = 0.f, s2 = 0.f;
     for (int c = lane * VEC; c < d; c += kWave * VEC) {
-      const Vec16<E> xv = load16(xr + c), gv = load16(dyr + c), gm = load16(gamma + c);
+      float xv[VEC];
+      load_stream<VEC>(xr + c, xv);
+      const Vec16<E> gv = load16(dyr + c), gm = load16(gamma + c);
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
-        const float xh = (to_f32(xv.v[k]) - mu) * rs;
+        const float xh = (xv[k] - mu) * rs;
         const float g = to_f32(gv.v[k]);
         const float dxh = g * to_f32(gm.v[k]);
         s1 += dxh;
@@ -262,22 +302,25 @@ __global__ void k_layernorm_bwd(const E *dy, const E *x, const float *mean, cons
     }
     s1 = wave_sum(s1) / float(d);
     s2 = wave_sum(s2) / float(d);
-    E *dxr = dx + uint64_t(row) * d;
-    const E *rr = res ? res + uint64_t(row) * d : nullptr;
+    float *dxr = dx + uint64_t(row) * d;
+    const float *rr = res ? res + uint64_t(row) * d : nullptr;
     for (int c = lane * VEC; c < d; c += kWave * VEC) {
-      const Vec16<E> xv = load16(xr + c), gv = load16(dyr + c), gm = load16(gamma + c);
-      Vec16<E> rv;
-      if (rr) rv = load16(rr + c);
-      Vec16<E> o;
+      float xv[VEC], rv[VEC], o[VEC];
+      load_stream<VEC>(xr + c, xv);
+      const Vec16<E> gv = load16(dyr + c), gm = load16(gamma + c);
+      if (rr) load_stream<VEC>(rr + c, rv);
+      Vec16<E> oe;
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
-        const float xh = (to_f32(xv.v[k]) - mu) * rs;
+        const float xh = (xv[k] - mu) * rs;
         const float dxh = to_f32(gv.v[k]) * to_f32(gm.v[k]);
         float v = (dxh - s1 - xh * s2) * rs;
-        if (rr) v += to_f32(rv.v[k]);
-        o.v[k] = from_f32<E>(v);
+        if (rr) v += rv[k];
+        o[k] = v;
+        oe.v[k] = from_f32<E>(v);
       }
-      store16(dxr + c, o);
+      store_stream<VEC>(dxr + c, o);
+      if (dx_e) store16(dx_e + uint64_t(row) * d + c, oe);
     }
   }
   __syncthreads();
@@ -322,8 +365,8 @@ template <typename E, int NJ>
 // SIMD: the bounds tell the compiler that it may use 128 / 256 / 512 registers; left to itself it aimed at 64
 // and spilled the row to scratch memory
 __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
-    __attribute__((amdgpu_waves_per_eu(1, NJ <= 1 ? 4 : NJ <= 4 ? 2 : 1))) void k_layernorm_bwd_reg(const E *dy, const E *x, const float *mean, const float *rstd,
-                                                          const E *gamma, const E *res, E *dx, float *dgamma, float *dbeta,
+    __attribute__((amdgpu_waves_per_eu(1, NJ <= 1 ? 4 : NJ <= 4 ? 2 : 1))) void k_layernorm_bwd_reg(const E *dy, const float *x, const float *mean, const float *rstd,
+                                                          const E *gamma, const float *res, float *dx, E *dx_e, float *dgamma, float *dbeta,
                                                           int T, int d, float *partial) {
   constexpr int VEC = ElemTraits<E>::VEC;
   extern __shared__ __align__(16) float lds[];   // per wave: dgamma[d], dbeta[d]
@@ -338,15 +381,17 @@ __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
     for (int k = 0; k < VEC; ++k) dg[j][k] = db[j][k] = 0.f;
   }
   for (int row = blockIdx.x * waves + wave; row < T; row += gridDim.x * waves) {
-    const E *xr = x + uint64_t(row) * d, *dyr = dy + uint64_t(row) * d;
+    const float *xr = x + uint64_t(row) * d;
+    const E *dyr = dy + uint64_t(row) * d;
     const float mu = mean[row], rs = rstd[row];
-    Vec16<E> xv[NJ], gv[NJ];
+    float xv[NJ][VEC];
+    Vec16<E> gv[NJ];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int c = VEC * (lane + kWave * j);
       if (c < d) {
-        xv[j] = load16(xr + c);
+        load_stream<VEC>(xr + c, xv[j]);
         gv[j] = load16(dyr + c);
       }
     }
@@ -356,7 +401,8 @@ __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
       if (c < d) {
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
-          const float xh = (to_f32(xv[j].v[k]) - mu) * rs;
+          const float xh = (xv[j][k] - mu) * rs;
+          xv[j][k] = xh;   // only the normalised value is needed from here on
           const float g = to_f32(gv[j].v[k]);
           const float dxh = g * to_f32(gm[j].v[k]);
           s1 += dxh;
@@ -368,24 +414,25 @@ __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
     }
     s1 = wave_sum(s1) / float(d);
     s2 = wave_sum(s2) / float(d);
-    E *dxr = dx + uint64_t(row) * d;
-    const E *rr = res ? res + uint64_t(row) * d : nullptr;
+    float *dxr = dx + uint64_t(row) * d;
+    const float *rr = res ? res + uint64_t(row) * d : nullptr;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int c = VEC * (lane + kWave * j);
       if (c < d) {
-        Vec16<E> rv;
-        if (rr) rv = load16(rr + c);
-        Vec16<E> o;
+        float rv[VEC], o[VEC];
+        if (rr) load_stream<VEC>(rr + c, rv);
+        Vec16<E> oe;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
-          const float xh = (to_f32(xv[j].v[k]) - mu) * rs;
           const float dxh = to_f32(gv[j].v[k]) * to_f32(gm[j].v[k]);
-          float v = (dxh - s1 - xh * s2) * rs;
-          if (rr) v += to_f32(rv.v[k]);
-          o.v[k] = from_f32<E>(v);
+          float v = (dxh - s1 - xv[j][k] * s2) * rs;
+          if (rr) v += rv[k];
+          o[k] = v;
+          oe.v[k] = from_f32<E>(v);
         }
-        store16(dxr + c, o);
+        store_stream<VEC>(dxr + c, o);
+        if (dx_e) store16(dx_e + uint64_t(row) * d + c, oe);
       }
     }
   }
@@ -714,34 +761,41 @@ int launch_convert_f32(int prec, const float *src, void *dst, uint64_t n, stream
   return check_launch("convert_f32");
 }
 
-int launch_embed_fwd(int prec, const int32_t *ids, const void *wte, const void *wpe, void *x, int T, int d, int s,
+int launch_embed_fwd(int prec, const int32_t *ids, const void *wte, const void *wpe, float *x, int T, int d, int s,
                      int vocab, stream_t st) {
   (void)vocab;
   if (T < 1 || d % 8 || s < 1) return fail(HMY_E_INVALID, "embed_fwd: bad shape");
   DISPATCH_PREC(prec, {
     const uint64_t work = uint64_t(T) * (d / ElemTraits<E>::VEC);
     hipLaunchKernelGGL(k_embed_fwd<E>, dim3(grid_for(work, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st, ids,
-                       (const E *)wte, (const E *)wpe, (E *)x, T, d, s);
+                       (const E *)wte, (const E *)wpe, x, T, d, s);
   });
   return check_launch("embed_fwd");
 }
-int launch_embed_bwd(int prec, const int32_t *ids, const void *dx, float *dwte, float *dwpe, int T, int d, int s,
+int launch_embed_bwd(int prec, const int32_t *ids, const float *dx, float *dwte, float *dwpe, int T, int d, int s,
                      int vocab, stream_t st) {
   (void)vocab;
+  if (prec != HMY_PREC_FP32 && prec != HMY_PREC_BF16) return fail(HMY_E_INVALID, "unknown precision %d", prec);
   if (T < 1 || d % 8 || s < 1 || T % s) return fail(HMY_E_INVALID, "embed_bwd: bad shape");
-  DISPATCH_PREC(prec, {
-    const uint64_t work = uint64_t(T) * (d / ElemTraits<E>::VEC);
-    hipLaunchKernelGGL(k_embed_bwd_wte<E>, dim3(grid_for(work, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st, ids,
-                       (const E *)dx, dwte, T, d);
-    const uint64_t work2 = uint64_t(s) * (d / ElemTraits<E>::VEC);
-    hipLaunchKernelGGL(k_embed_bwd_wpe<E>, dim3(grid_for(work2, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st,
-                       (const E *)dx, dwpe, T, d, s);
-  });
+  const uint64_t work = uint64_t(T) * (d / 4);
+  hipLaunchKernelGGL(k_embed_bwd_wte, dim3(grid_for(work, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st, ids, dx, dwte, T,
+                     d);
+  const uint64_t work2 = uint64_t(s) * (d / 4);
+  hipLaunchKernelGGL(k_embed_bwd_wpe, dim3(grid_for(work2, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st, dx, dwpe, T, d, s);
   return check_launch("embed_bwd");
+}
+int launch_convert_to_f32(int prec, const void *src, float *dst, uint64_t n, stream_t st) {
+  if (n % 8) return fail(HMY_E_INVALID, "convert: n must be a multiple of 8");
+  DISPATCH_PREC(prec, {
+    const uint64_t nvec = n / ElemTraits<E>::VEC;
+    hipLaunchKernelGGL(k_convert_to_f32<E>, dim3(grid_for(nvec, kBlock, 4096)), dim3(kBlock), 0, (hipStream_t)st,
+                       (const E *)src, dst, nvec);
+  });
+  return check_launch("convert_to_f32");
 }
 
 template <typename E>
-void launch_ln_fwd(const E *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T, int d, float eps,
+void launch_ln_fwd(const float *x, const E *gamma, const E *beta, E *y, float *mean, float *rstd, int T, int d, float eps,
                    hipStream_t st) {
   const int nj = (d + kWave * ElemTraits<E>::VEC - 1) / (kWave * ElemTraits<E>::VEC);
   const dim3 g(grid_for(T, kWavesPerBlock, 8192)), b(kBlock);
@@ -752,15 +806,16 @@ void launch_ln_fwd(const E *x, const E *gamma, const E *beta, E *y, float *mean,
   else hipLaunchKernelGGL(k_layernorm_fwd<E>, g, b, 0, st, x, gamma, beta, y, mean, rstd, T, d, eps);
 }
 
-int launch_layernorm_fwd(int prec, const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd,
+int launch_layernorm_fwd(int prec, const float *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd,
                          int T, int d, float eps, stream_t st) {
   if (T < 1 || d % 8) return fail(HMY_E_INVALID, "layernorm_fwd: bad shape");
-  DISPATCH_PREC(prec, launch_ln_fwd<E>((const E *)x, (const E *)gamma, (const E *)beta, (E *)y, mean, rstd, T, d, eps, (hipStream_t)st));
+  DISPATCH_PREC(prec, launch_ln_fwd<E>(x, (const E *)gamma, (const E *)beta, (E *)y, mean, rstd, T, d, eps, (hipStream_t)st));
   return check_launch("layernorm_fwd");
 }
 template <typename E>
-void launch_ln_bwd(const E *dy, const E *x, const float *mean, const float *rstd, const E *gamma, const E *res, E *dx,
-                   float *dgamma, float *dbeta, int T, int d, hipStream_t st, float *ws, uint64_t ws_bytes) {
+void launch_ln_bwd(const E *dy, const float *x, const float *mean, const float *rstd, const E *gamma, const float *res,
+                   float *dx, E *dx_e, float *dgamma, float *dbeta, int T, int d, hipStream_t st, float *ws,
+                   uint64_t ws_bytes) {
   constexpr int VEC = ElemTraits<E>::VEC;
   const int nj = (d + kWave * VEC - 1) / (kWave * VEC);
   // waves per workgroup: as many as 128 KiB of LDS holds rows of 2 d floats, and as the registers allow
@@ -773,23 +828,23 @@ void launch_ln_bwd(const E *dy, const E *x, const float *mean, const float *rstd
   float *partial = ws && ws_bytes >= uint64_t(grid) * 2 * d * 4 && nj <= 8 ? ws : nullptr;
   const size_t lds = size_t(waves) * 2 * d * 4;
   const dim3 g(grid), b(waves * kWave);
-  if (nj == 1) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 1>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, partial);
-  else if (nj == 2) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 2>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, partial);
-  else if (nj <= 4) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 4>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, partial);
-  else if (nj <= 8) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 8>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, partial);
+  if (nj == 1) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 1>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, partial);
+  else if (nj == 2) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 2>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, partial);
+  else if (nj <= 4) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 4>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, partial);
+  else if (nj <= 8) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 8>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, partial);
   else
     hipLaunchKernelGGL(k_layernorm_bwd<E>, dim3(grid_for(T, kWavesPerBlock, 512)), dim3(kBlock), size_t(2) * d * 4, st, dy, x, mean,
-                       rstd, gamma, res, dx, dgamma, dbeta, T, d);
+                       rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d);
   if (partial) hipLaunchKernelGGL(k_ln_bwd_reduce, dim3((2 * d + 63) / 64), dim3(256), 0, st, partial, grid, d, dgamma, dbeta);
 }
 
-int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
-                         const void *res, void *dx, float *dgamma, float *dbeta, int T, int d, stream_t st,
+int launch_layernorm_bwd(int prec, const void *dy, const float *x, const float *mean, const float *rstd, const void *gamma,
+                         const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta, int T, int d, stream_t st,
                          float *workspace, uint64_t workspace_bytes) {
   if (T < 1 || d % 8 || d > 8192) return fail(HMY_E_INVALID, "layernorm_bwd: bad shape");
   DISPATCH_PREC(prec, {
-    launch_ln_bwd<E>((const E *)dy, (const E *)x, mean, rstd, (const E *)gamma, (const E *)res, (E *)dx, dgamma, dbeta, T,
-                     d, (hipStream_t)st, workspace, workspace_bytes);
+    launch_ln_bwd<E>((const E *)dy, x, mean, rstd, (const E *)gamma, res, dx, (E *)dx_e, dgamma, dbeta, T, d,
+                     (hipStream_t)st, workspace, workspace_bytes);
   });
   return check_launch("layernorm_bwd");
 }
@@ -827,9 +882,9 @@ float *ln_bwd_scratch_on_current_device() {
 }
 }  // namespace
 
-int launch_layernorm_bwd_static(int prec, const void *dy, const void *x, const float *mean, const float *rstd,
-                                const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int T, int d,
-                                stream_t st) {
+int launch_layernorm_bwd_static(int prec, const void *dy, const float *x, const float *mean, const float *rstd,
+                                const void *gamma, const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta,
+                                int T, int d, stream_t st) {
   if (T < 1 || d < 8 || d % 8) return fail(HMY_E_INVALID, "layernorm_bwd_static: bad shape");
   if (d > kStaticLnMaxD)
     return fail(HMY_E_INVALID, "layernorm_bwd_static: d = %d exceeds the static workspace's limit of %d columns; "
@@ -838,7 +893,7 @@ int launch_layernorm_bwd_static(int prec, const void *dy, const void *x, const f
   if (!ws) return HMY_E_HIP;
   // nothing in the workspace has to start at zero: every workgroup overwrites its whole row before
   // the reduction kernel, ordered behind it on the stream, reads the rows of this launch only
-  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, st, ws,
+  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, st, ws,
                               uint64_t(kLnBlocks) * 2 * d * 4);
 }
 

@@ -80,6 +80,7 @@ struct hmy_handle {
   int err = HMY_OK;
   bool timing = true;
   int profile_level = 0;      // 0 counters only, 1 copy / stall / compute spans, 2 also every GEMM launch
+  bool progress = false;      // wait for the compute stream after every visit and say so on stderr
   bool profile_gemm = false;
   // true (HMY_SWAP_OUT_KERNEL): the Adam kernel writes its results directly into the pinned host arrays;
   // false (HMY_SWAP_OUT_MEMCPY): results go to the ring / slot and leave by hipMemcpyAsync on s_out
@@ -217,8 +218,8 @@ float *gptr(const hmy_handle *h, const Visit &v, const PackPtrs &p, int tensor) 
   return p.dW + (h->model.tensors[tensor].offset - v.poff);
 }
 // the boundary activations of the minibatch are one [rows, d] array: microbatch mb of either pass is a run of rows
-char *Xbuf(const hmy_handle *h, int mb, bool fwd) {
-  return h->base + h->arena.res.X + uint64_t(mb) * (fwd ? h->arena.res.x_bytes_F : h->arena.res.x_bytes_B);
+float *Xbuf(const hmy_handle *h, int mb, bool fwd) {
+  return (float *)(h->base + h->arena.res.X + uint64_t(mb) * (fwd ? h->arena.res.x_bytes_F : h->arena.res.x_bytes_B));
 }
 char *inring(const hmy_handle *h, int r) { return h->base + h->arena.res.inring + uint64_t(r) * h->arena.res.in_bytes; }
 char *outring(const hmy_handle *h, int r) { return h->base + h->arena.res.outring + uint64_t(r) * h->arena.res.out_bytes; }
@@ -260,8 +261,8 @@ void run_gemm(hmy_handle *h, const hmy_gemm_desc &g) {
   const size_t b = h->profile_gemm ? trec(h, h->s_comp) : size_t(-1);
   span(h, a, b, 10 + variant);
 }
-// C[M,N] = A[M,K] W[N,K]^T + bias (+ res)
-void linear_fwd(hmy_handle *h, const void *A, const void *W, const void *bias, const void *res, void *C,
+// C[M,N] = A[M,K] W[N,K]^T + bias (+ res).  With a residual, res and C are the fp32 residual stream.
+void linear_fwd(hmy_handle *h, const void *A, const void *W, const void *bias, const float *res, void *C,
                 void *gelu_out, int M, int N, int K) {
   hmy_gemm_desc g = gemm_desc(h->model.spec.precision, M, N, K);
   g.A = A; g.lda = K;
@@ -269,6 +270,7 @@ void linear_fwd(hmy_handle *h, const void *A, const void *W, const void *bias, c
   g.C = C; g.ldc = N;
   g.bias = bias;
   g.res = res; g.ldr = N;
+  if (res) g.res_fp32 = g.c_fp32 = 1;
   g.gelu_out = gelu_out;
   run_gemm(h, g);
 }
@@ -294,13 +296,14 @@ void linear_bwd(hmy_handle *h, const void *dY, const void *X, const void *W, voi
 }
 
 struct BlockPtrs {
-  char *x_in, *a, *qkv, *o, *x_mid, *hh, *u, *g;
+  float *x_in, *x_mid;   // the residual stream: fp32
+  char *a, *qkv, *o, *hh, *u, *g;
   float *ln1_mean, *ln1_rstd, *ln2_mean, *ln2_rstd, *lse;
 };
 BlockPtrs block_ptrs(const BlockActs &b, char *region) {
   BlockPtrs p;
-  p.x_in = region + b.x_in; p.a = region + b.a; p.qkv = region + b.qkv; p.o = region + b.o;
-  p.x_mid = region + b.x_mid; p.hh = region + b.h; p.u = region + b.u; p.g = region + b.g;
+  p.x_in = (float *)(region + b.x_in); p.a = region + b.a; p.qkv = region + b.qkv; p.o = region + b.o;
+  p.x_mid = (float *)(region + b.x_mid); p.hh = region + b.h; p.u = region + b.u; p.g = region + b.g;
   p.ln1_mean = (float *)(region + b.ln1_mean); p.ln1_rstd = (float *)(region + b.ln1_rstd);
   p.ln2_mean = (float *)(region + b.ln2_mean); p.ln2_rstd = (float *)(region + b.ln2_rstd);
   p.lse = (float *)(region + b.lse);
@@ -311,7 +314,7 @@ BlockPtrs block_ptrs(const BlockActs &b, char *region) {
 // the resident boundary buffer (in place); in a backward visit they are distinct
 // saved buffers and y == nullptr skips the second MLP GEMM (output not needed).
 void block_forward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, const BlockPtrs &A,
-                   const char *x_in, char *x_mid, char *y, bool keep_preactivation, int b) {
+                   const float *x_in, float *x_mid, float *y, bool keep_preactivation, int b) {
   const hmy_model_spec &s = h->model.spec;
   const int prec = s.precision, T = b * s.seq_len, d = s.d_model, f = s.d_ffn;
   const int t0 = h->model.first_tensor[layer];
@@ -326,9 +329,10 @@ void block_forward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer,
   if (y) linear_fwd(h, A.g, W(W2), W(B2), x_mid, y, nullptr, T, d, f);
 }
 
-// Backward of one block; D holds dL/dy on entry and dL/dx_in on exit (in place).
+// Backward of one block; D (fp32) holds dL/dy on entry and dL/dx_in on exit (in place), and the buffer
+// `dlow` holds the same values rounded to the element type: that copy is what the GEMMs read.
 void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, const BlockPtrs &A,
-                    const char *x_in, char *D) {
+                    const float *x_in, float *D) {
   const hmy_model_spec &s = h->model.spec;
   const int prec = s.precision, T = h->b * s.seq_len, d = s.d_model, f = s.d_ffn;
   const int t0 = h->model.first_tensor[layer];
@@ -336,29 +340,30 @@ void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer
   auto G = [&](int i) { return gptr(h, v, pp, t0 + i); };
   char *gbig = h->base + h->arena.res.gbig;
   char *gsmall = h->base + h->arena.res.gsmall;
+  char *dlow = h->base + h->arena.res.dlow;
   float *delta = (float *)(h->base + h->arena.res.delta);
   float *ln_ws = (float *)(h->base + h->arena.res.ln_ws);
   const uint64_t ln_ws_bytes = uint64_t(kLnBlocks) * 2 * d * 4;
   // y = x_mid + W2 gelu(W1 LN2(x_mid) + b1) + b2
-  linear_bwd(h, D, A.g, W(W2), gbig, G(W2), G(B2), T, d, f);                     // dg
+  linear_bwd(h, dlow, A.g, W(W2), gbig, G(W2), G(B2), T, d, f);                  // dg
   KCHK(h, launch_gelu_bwd(prec, gbig, A.u, gbig, uint64_t(T) * f, h->s_comp));   // du
   linear_bwd(h, gbig, A.hh, W(W1), gsmall, G(W1), G(B1), T, f, d);               // dh
-  KCHK(h, launch_layernorm_bwd(prec, gsmall, A.x_mid, A.ln2_mean, A.ln2_rstd, W(LN2_G), D, D, G(LN2_G), G(LN2_B), T, d,
-                               h->s_comp, ln_ws, ln_ws_bytes));                                        // D = dx_mid
+  KCHK(h, launch_layernorm_bwd(prec, gsmall, A.x_mid, A.ln2_mean, A.ln2_rstd, W(LN2_G), D, D, dlow, G(LN2_G), G(LN2_B),
+                               T, d, h->s_comp, ln_ws, ln_ws_bytes));                                  // D = dx_mid
   // x_mid = x_in + Wo attn(Wqkv LN1(x_in) + bqkv) + bo
-  linear_bwd(h, D, A.o, W(WO), gsmall, G(WO), G(BO), T, d, d);                   // do
+  linear_bwd(h, dlow, A.o, W(WO), gsmall, G(WO), G(BO), T, d, d);                // do
   KCHK(h, launch_attn_bwd(prec, A.qkv, A.o, gsmall, A.lse, delta, gbig, h->b, s.seq_len, s.n_heads, d / s.n_heads,
                           s.causal, h->s_comp));                                   // dqkv
   linear_bwd(h, gbig, A.a, W(WQKV), gsmall, G(WQKV), G(BQKV), T, 3 * d, d);      // da
-  KCHK(h, launch_layernorm_bwd(prec, gsmall, x_in, A.ln1_mean, A.ln1_rstd, W(LN1_G), D, D, G(LN1_G), G(LN1_B), T, d,
-                               h->s_comp, ln_ws, ln_ws_bytes));                                        // D = dx_in
+  KCHK(h, launch_layernorm_bwd(prec, gsmall, x_in, A.ln1_mean, A.ln1_rstd, W(LN1_G), D, D, dlow, G(LN1_G), G(LN1_B), T,
+                               d, h->s_comp, ln_ws, ln_ws_bytes));                                     // D = dx_in
 }
 
 // Final norm, vocabulary projection, loss and their backward.  The fp32 logits exist one chunk of
 // rows at a time; their gradient (element type) is kept for the whole microbatch, so that the two
 // GEMMs consuming it run once with T rows.  Writes dL/dx into D.
 void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer, char *region,
-                           const char *x_in, int mb, char *D, float inv_ntgt) {
+                           const float *x_in, int mb, float *D, float inv_ntgt) {
   const hmy_model_spec &s = h->model.spec;
   const int prec = s.precision, T = h->b * s.seq_len, d = s.d_model, V = s.vocab, E = h->model.elem_bytes();
   const HeadActs &ha = h->hacts;
@@ -403,8 +408,9 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
     g.C = g_wh; g.ldc = d; g.c_fp32 = 1; g.accumulate = 1;
     run_gemm(h, g);
   }
-  KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, g_lnf_g, g_lnf_b, T, d, h->s_comp,
-                               (float *)(h->base + h->arena.res.ln_ws), uint64_t(kLnBlocks) * 2 * d * 4));
+  KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, h->base + h->arena.res.dlow, g_lnf_g,
+                               g_lnf_b, T, d, h->s_comp, (float *)(h->base + h->arena.res.ln_ws),
+                               uint64_t(kLnBlocks) * 2 * d * 4));
 }
 
 struct PendingUpdate {
@@ -436,22 +442,23 @@ int ckpt_index(const hmy_handle *h, int layer) {
 // checkpoint ck of the whole minibatch is one [rows, d] array like X; either pass addresses its own microbatch in it
 char *stash_slot(const hmy_handle *h, int ck, int mb, bool fwd) {
   const Reserved &r = h->arena.res;
-  return h->stash_host + uint64_t(ck) * (uint64_t(h->M) * r.x_bytes_B) + uint64_t(mb) * (fwd ? r.x_bytes_F : r.x_bytes_B);
+  return h->stash_host + uint64_t(ck) * (uint64_t(h->M) * r.ck_bytes_B) + uint64_t(mb) * (fwd ? r.ck_bytes_F : r.ck_bytes_B);
 }
 
 void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int mb) {
   const hmy_model_spec &s = h->model.spec;
   const int T = h->bF * s.seq_len, d = s.d_model;
-  const uint64_t xb = h->arena.res.x_bytes_F;
+  const uint64_t xb = h->arena.res.ck_bytes_F;
   const PackPtrs pp = pack_ptrs(h, v);
-  char *X = Xbuf(h, mb, true);
+  float *X = Xbuf(h, mb, true);
   const BlockPtrs scratch = block_ptrs(h->bacts_F, h->base + h->arena.act_off);
   for (int layer = v.pack.a; layer < v.pack.e; ++layer) {
     const int ck = ckpt_index(h, layer);
     if (ck >= 0) {  // this layer's input is a backward pack's checkpoint: send it to the host
       const int q = it.out_count++ % kOutRing;
       comp_wait(h, it.out_free[q]);
-      KCHK(h, launch_copy(outring(h, q), X, xb, h->s_comp));
+      // the checkpoint leaves rounded to the element type (one rounding per pack boundary)
+      KCHK(h, launch_convert_f32(s.precision, X, outring(h, q), uint64_t(T) * d, h->s_comp));
       hipEvent_t e = rec(h, h->s_comp);
       wait(h, h->s_out, e);
       if (h->fused_swap_out) d2h_kernel(h, HMY_KIND_SX, stash_slot(h, ck, mb, true), outring(h, q), xb, h->s_out);
@@ -468,14 +475,21 @@ void forward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int 
   }
 }
 
-// enqueue whatever brings the input of backward visit v, microbatch mb, into inring[mb % kInRing]
+// where the first layer of a backward visit's pack reads its input (fp32, inside the pack's workspace)
+float *first_input(const hmy_handle *h, const Visit &v) {
+  char *reg = act_region(h, v.pack, v.pack.a);
+  return (float *)(v.pack.a <= h->model.spec.n_blocks ? reg + h->bacts.x_in : reg + h->hacts.x_in);
+}
+
+// enqueue whatever brings the input of backward visit v, microbatch mb: a checkpoint from the host into
+// inring[mb % kInRing] (element type), or the still resident activations into the pack's workspace
 void issue_pack_input(hmy_handle *h, IterState &it, const Visit &v, int mb) {
   const int r = mb % kInRing;
-  const uint64_t xb = h->arena.res.x_bytes_B;
+  const uint64_t xb = h->arena.res.ck_bytes_B;
   it.in_ready[r] = nullptr;
   if (v.pack.a == 0) return;  // starts at the embedding: restarts from the token ids
-  if (v.last) {               // still resident from the forward pass
-    KCHK(h, launch_copy(inring(h, r), Xbuf(h, mb, false), xb, h->s_comp));
+  if (v.last) {               // still resident from the forward pass: straight into the first layer's input buffer
+    KCHK(h, launch_copy(first_input(h, v), Xbuf(h, mb, false), h->arena.res.x_bytes_B, h->s_comp));
     return;
   }
   const int ck = ckpt_index(h, v.pack.a);
@@ -493,14 +507,17 @@ void backward_visit_microbatch(hmy_handle *h, IterState &it, const Visit &v, int
   const int T = h->b * s.seq_len, d = s.d_model, L = s.n_blocks;
   const PackPtrs pp = pack_ptrs(h, v);
   const int r = mb % kInRing;
-  char *D = Xbuf(h, mb, false);
+  float *D = Xbuf(h, mb, false);
   comp_wait(h, it.in_ready[r]);
   // where each layer of the pack reads its input
-  auto input_of = [&](int layer) -> char * {
-    if (layer == v.pack.a) return inring(h, r);
+  auto input_of = [&](int layer) -> float * {
     char *reg = act_region(h, v.pack, layer);
-    return layer <= L ? reg + h->bacts.x_in : reg + h->hacts.x_in;
+    return (float *)(layer <= L ? reg + h->bacts.x_in : reg + h->hacts.x_in);
   };
+  if (it.in_ready[r])   // a checkpoint has arrived in the ring: widen it into the first layer's input
+    KCHK(h, launch_convert_to_f32(s.precision, inring(h, r), first_input(h, v), uint64_t(T) * d, h->s_comp));
+  if (!v.last)          // the gradient handed down by the pack above, rounded for the GEMMs that read it
+    KCHK(h, launch_convert_f32(s.precision, D, h->base + h->arena.res.dlow, uint64_t(T) * d, h->s_comp));
   // (re)compute the pack's forward, keeping what backward needs
   for (int layer = v.pack.a; layer < v.pack.e; ++layer) {
     const bool has_next = layer + 1 < v.pack.e;
@@ -706,6 +723,11 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
     const Visit *ahead = vi + dist < nv ? &h->visits[vi + dist] : nullptr;   // the visit whose weights travel now
     const bool final_visit = vi + 1 == nv;
     const int Mv = v.bwd ? M : h->MF;                                        // microbatches of this visit's pass
+    // The slot those weights go to may still belong to the pack whose update is being handed out during this
+    // visit (prefetch distance = slots - 1).  Then the load cannot start before that update has left anyway:
+    // it is requested behind the update's last chunk, in the visit's last microbatch, instead of holding up the
+    // link's queue (checkpoint reads of this visit included) from the visit's start.
+    const bool defer = ahead && it.upd.v && it.upd.v->slot == ahead->slot;
     comp_wait(h, ev_w[vi]);
     if (vi == 0) comp_wait(h, ev_ids);
     if (v.bwd) {
@@ -723,12 +745,14 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
           for (int q = 0; q < (from_host ? std::min(Mv, kInRing - 1) : 1); ++q) issue_pack_input(h, it, v, q);
         if (from_host && m + kInRing - 1 < Mv) issue_pack_input(h, it, v, m + kInRing - 1);
       }
-      if (ahead) w_piece(*ahead, m, Mv);
+      if (ahead && !defer) w_piece(*ahead, m, Mv);
       // this microbatch's share of the previous visit's update
       // (not behind a final visit that is the embedding alone: it is over in a moment, and
       // what is left of the update then runs at the full link rate)
       const bool tiny_last = final_visit && v.pack.a == 0 && v.pack.e == 1;
       if (it.upd.v && !tiny_last) update_progress(h, it, hp, (it.upd.n_chunks * (m + 1) + Mv - 1) / Mv);
+      if (ahead && defer && m == Mv - 1)
+        for (int piece = 0; piece < Mv; ++piece) w_piece(*ahead, piece, Mv);
       if (v.bwd) {
         if (m > 0 && (v.last || v.pack.a == 0)) issue_pack_input(h, it, v, m);
         backward_visit_microbatch(h, it, v, m);
@@ -742,6 +766,13 @@ void run_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam &hp) {
     } else {
       if (final_visit) it.compute_done = true;   // nothing else will be enqueued on the compute stream
       pack_update_begin(h, it, v, rec(h, h->s_comp), hp);
+    }
+    if (h->progress && !h->dry && !h->err) {
+      // for runs under a profiler that serialises every dispatch: a line per visit, once its kernels have run
+      HIPCHK(h, hipStreamSynchronize(h->s_comp));
+      std::fprintf(stderr, "hmy: visit %d of %d done (%s pack [%d, %d), %d microbatches)\n", vi + 1, nv,
+                   v.bwd ? "backward" : "forward", v.pack.a, v.pack.e, Mv);
+      std::fflush(stderr);
     }
   }
   it.compute_done = true;
@@ -971,9 +1002,17 @@ int hmy::run_measure_profile(const Model &m, int micro_batch, int hip_device, in
     return fail(HMY_E_NO_DEVICE, "no usable HIP device %d (found %d)", hip_device, ndev);
   h.device = hip_device;
   hipEvent_t e0 = nullptr, e1 = nullptr;
+  // what runs beside the layers in an iteration: weights and optimizer state arriving (copy engine), results
+  // leaving (the throttled host-writing kernel); one staging buffer on each side
+  constexpr uint64_t kLoadBytes = 64ull << 20;
+  char *load_host = nullptr, *load_dev = nullptr;
   HIPCHK(&h, hipSetDevice(hip_device));
   HIPCHK(&h, hipMalloc(reinterpret_cast<void **>(&h.base), h.arena.total));
   HIPCHK(&h, hipStreamCreateWithFlags(&h.s_comp, hipStreamNonBlocking));
+  HIPCHK(&h, hipStreamCreateWithFlags(&h.s_in, hipStreamNonBlocking));
+  HIPCHK(&h, hipStreamCreateWithFlags(&h.s_out, hipStreamNonBlocking));
+  HIPCHK(&h, hipHostMalloc(reinterpret_cast<void **>(&load_host), 2 * kLoadBytes, hipHostMallocDefault));
+  HIPCHK(&h, hipMalloc(reinterpret_cast<void **>(&load_dev), 2 * kLoadBytes));
   HIPCHK(&h, hipEventCreate(&e0));
   HIPCHK(&h, hipEventCreate(&e1));
   if (!h.err) {
@@ -986,31 +1025,53 @@ int hmy::run_measure_profile(const Model &m, int micro_batch, int hip_device, in
   }
   IterState it;
   it.inv_ntgt = 1.0f / float(uint64_t(micro_batch) * s1.seq_len);
-  auto timed = [&](const Visit &v) -> uint64_t {
+  auto timed = [&](const Visit &v, uint64_t *beside_ns) -> uint64_t {
     auto once = [&]() {
       if (v.bwd) backward_visit_microbatch(&h, it, v, 0);
       else forward_visit_microbatch(&h, it, v, 0);
       h.sync_used = 0;   // the events a visit records for the swap engine are of no use here: recycle them
     };
+    auto run = [&](int n) -> double {
+      HIPCHK(&h, hipEventRecord(e0, h.s_comp));
+      for (int r = 0; r < n; ++r) once();
+      HIPCHK(&h, hipEventRecord(e1, h.s_comp));
+      HIPCHK(&h, hipEventSynchronize(e1));
+      float ms = 0.f;
+      HIPCHK(&h, hipEventElapsedTime(&ms, e0, e1));
+      return double(ms);
+    };
     once();   // warm-up: code objects, caches, clocks
-    HIPCHK(&h, hipEventRecord(e0, h.s_comp));
-    for (int r = 0; r < reps; ++r) once();
-    HIPCHK(&h, hipEventRecord(e1, h.s_comp));
-    HIPCHK(&h, hipEventSynchronize(e1));
-    float ms = 0.f;
-    HIPCHK(&h, hipEventElapsedTime(&ms, e0, e1));
-    return uint64_t(double(ms) * 1e6 / reps + 0.5);
+    const double alone_ms = run(reps) / reps;
+    if (!h.err) {
+      // enough traffic to last through the timed launches (about 40 GB/s each way beside kernels): incoming copies
+      // for every visit, outgoing stores only for backward visits, whose updates are what writes to the host
+      const int n_copies = int(std::min(400.0, 2.0 * reps * alone_ms * 1e-3 * 40e9 / double(kLoadBytes))) + 2;
+      // (each of these queues holds at most a few hundred operations of 64 MiB)
+      for (int c = 0; c < n_copies; ++c) {
+        HIPCHK(&h, hipMemcpyAsync(load_dev, load_host, kLoadBytes, hipMemcpyHostToDevice, h.s_in));
+        if (v.bwd) KCHK(&h, launch_copy_out(load_host + kLoadBytes, load_dev + kLoadBytes, kLoadBytes, h.s_out));
+      }
+    }
+    const double beside_ms = run(reps) / reps;
+    hipStreamSynchronize(h.s_in);   // let what is left of the traffic drain before the next layer's turn
+    hipStreamSynchronize(h.s_out);
+    *beside_ns = uint64_t(std::max(alone_ms, beside_ms) * 1e6 + 0.5);
+    return uint64_t(alone_ms * 1e6 + 0.5);
   };
   std::memset(out, 0, sizeof(*out));
   out->micro_batch = micro_batch;
   // visits: forward embedding, forward block, last pack (head, forward + backward), block (recompute + backward),
   // embedding alone (backward only: its recompute is not needed)
-  out->embed_fwd_ns = timed(h.visits[0]);
-  out->block_fwd_ns = timed(h.visits[1]);
-  out->head_ns = timed(h.visits[2]);
-  out->block_bwd_ns = timed(h.visits[3]);
-  out->embed_bwd_ns = timed(h.visits[4]);
+  out->embed_fwd_ns = timed(h.visits[0], &out->embed_fwd_beside_ns);
+  out->block_fwd_ns = timed(h.visits[1], &out->block_fwd_beside_ns);
+  out->head_ns = timed(h.visits[2], &out->head_beside_ns);
+  out->block_bwd_ns = timed(h.visits[3], &out->block_bwd_beside_ns);
+  out->embed_bwd_ns = timed(h.visits[4], &out->embed_bwd_beside_ns);
   if (h.s_comp) { hipStreamSynchronize(h.s_comp); hipStreamDestroy(h.s_comp); }
+  if (h.s_in) { hipStreamSynchronize(h.s_in); hipStreamDestroy(h.s_in); }
+  if (h.s_out) { hipStreamSynchronize(h.s_out); hipStreamDestroy(h.s_out); }
+  if (load_host) hipHostFree(load_host);
+  if (load_dev) hipFree(load_dev);
   if (e0) hipEventDestroy(e0);
   if (e1) hipEventDestroy(e1);
   for (hipEvent_t e : h.sync_events) hipEventDestroy(e);
@@ -1238,6 +1299,12 @@ int hmy_set_profiling(hmy_handle *h, int32_t level) {
   if (level < 0 || level > 2) return fail(HMY_E_INVALID, "profiling level %d (0..2)", level);
   h->profile_level = level;
   h->profile_gemm = level >= 2;
+  return HMY_OK;
+}
+
+int hmy_set_progress(hmy_handle *h, int32_t on) {
+  if (!h) return fail(HMY_E_INVALID, "null handle");
+  h->progress = on != 0;
   return HMY_OK;
 }
 

@@ -30,14 +30,16 @@ struct GemmP {
   void *gelu_out;
   int M, N, K;
   int64_t lda, ldb, ldc, ldr;
-  int c_fp32, accumulate;
+  int c_fp32, accumulate, res_fp32;
 };
 
 // ---- shared epilogue ---------------------------------------------------------
 template <typename E>
 __device__ __forceinline__ void epilogue_store(const GemmP &p, int m, int n, float v) {
   if (p.bias) v += to_f32(static_cast<const E *>(p.bias)[n]);
-  if (p.res) v += to_f32(static_cast<const E *>(p.res)[int64_t(m) * p.ldr + n]);
+  if (p.res)
+    v += p.res_fp32 ? static_cast<const float *>(p.res)[int64_t(m) * p.ldr + n]
+                    : to_f32(static_cast<const E *>(p.res)[int64_t(m) * p.ldr + n]);
   const int64_t ci = int64_t(m) * p.ldc + n;
   if (p.c_fp32) {
     float *c = static_cast<float *>(p.C);
@@ -301,7 +303,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(GemmP p, int tiles_per_spl
         if (m >= p.M) continue;
         const int64_t ci = int64_t(m) * p.ldc + n;
         float v = acc[i][j][r] + bias_v;
-        if (p.res) v += to_f32(static_cast<const bf16_t *>(p.res)[int64_t(m) * p.ldr + n]);
+        if (p.res)
+          v += p.res_fp32 ? static_cast<const float *>(p.res)[int64_t(m) * p.ldr + n]
+                          : to_f32(static_cast<const bf16_t *>(p.res)[int64_t(m) * p.ldr + n]);
         if (split) {
           atomicAdd(static_cast<float *>(p.C) + ci, v);   // C += partial
         } else if (p.c_fp32) {
@@ -332,6 +336,7 @@ int launch_gemm(const hmy_gemm_desc &g, stream_t st) {
   if (g.accumulate && !g.c_fp32) return fail(HMY_E_INVALID, "gemm: accumulate needs an fp32 C");
   if (g.gelu_out && g.c_fp32) return fail(HMY_E_INVALID, "gemm: gelu output needs an element-typed C");
   if (g.prec != HMY_PREC_FP32 && g.prec != HMY_PREC_BF16) return fail(HMY_E_INVALID, "gemm: unknown precision");
+  if (g.res_fp32 && g.res && !g.c_fp32) return fail(HMY_E_INVALID, "gemm: an fp32 residual needs an fp32 C");
   const int64_t min_lda = g.ta ? g.M : g.K, min_ldb = g.tb ? g.N : g.K;
   if (g.lda < min_lda || g.ldb < min_ldb || g.ldc < g.N || (g.res && g.ldr < g.N))
     return fail(HMY_E_INVALID, "gemm: leading dimension too small");
@@ -340,6 +345,7 @@ int launch_gemm(const hmy_gemm_desc &g, stream_t st) {
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldr = g.ldr;
   p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate;
+  p.res_fp32 = g.res_fp32 || g.prec == HMY_PREC_FP32;
   hipStream_t s = (hipStream_t)st;
   // 32-bit element offsets inside the kernel: every operand must span fewer than 2^31 elements
   const int64_t a_span = int64_t(g.ta ? g.K : g.M) * g.lda, b_span = int64_t(g.tb ? g.K : g.N) * g.ldb;
@@ -376,6 +382,13 @@ int launch_gemm(const hmy_gemm_desc &g, stream_t st) {
     else hipLaunchKernelGGL((k_gemm_mfma<true, true>), grid, block, 0, s, p, tiles_per_split, gn);
     return check_launch("gemm_mfma");
   }
+  // bf16 operands that the matrix-core kernels cannot take (not 16-byte aligned, or a leading dimension that is
+  // not a multiple of 8 elements) are an error while those kernels are selected: the plain kernel below would be
+  // tens of times slower, and nobody would be told
+  if (g.prec == HMY_PREC_BF16 && g_use_mfma)
+    return fail(HMY_E_INVALID, "gemm: bf16 operands must be 16-byte aligned with leading dimensions that are multiples "
+                               "of 8 elements (lda %lld, ldb %lld) and span less than 2^31 elements",
+                (long long)g.lda, (long long)g.ldb);
   const int64_t a_sm = g.ta ? 1 : g.lda, a_sk = g.ta ? g.lda : 1;
   const int64_t b_sn = g.tb ? 1 : g.ldb, b_sk = g.tb ? g.ldb : 1;
   dim3 grid((g.N + 63) / 64, (g.M + 63) / 64), block(256);

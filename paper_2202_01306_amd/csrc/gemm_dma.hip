@@ -47,7 +47,7 @@ struct DmaP {
   int M, N, K;
   uint32_t lda, ldb;
   int64_t ldc, ldr;
-  int c_fp32, accumulate;
+  int c_fp32, accumulate, res_fp32;
 };
 
 // element address inside a [row][k] tile of BK columns (BK/8 chunks per row)
@@ -63,6 +63,11 @@ __device__ __forceinline__ int addr_kr(int k, int col) {
 
 // one wavefront-wide 16-byte-per-lane copy HBM -> LDS.  lds_addr is wave-uniform (the
 // hardware adds 16 * lane); the global address is base + byte offset per lane.
+// The statement overwrites m0 and cannot say so: the compiler rejects m0 in a clobber list as a
+// reserved register ("may lead to undefined behaviour").  That is safe here because the compiler
+// keeps no value of its own in m0 across statements: whenever code it generates reads m0 (indexed
+// register moves, messages, its own LDS-direct loads) it writes m0 immediately before, and this
+// file uses none of those constructs.
 __device__ __forceinline__ void dma16(const void *base, uint32_t byte_off, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
@@ -134,6 +139,7 @@ struct Epi {
     const int esz = p.c_fp32 ? 4 : 2;
     bool ok = (reinterpret_cast<uintptr_t>(p.C) & 15) == 0 && (p.ldc * esz) % 16 == 0;
     if (p.res) ok = ok && (reinterpret_cast<uintptr_t>(p.res) & 15) == 0 && p.ldr % 8 == 0;
+    if (p.res && p.res_fp32 && p.accumulate) ok = false;   // both would want the prefetch registers
     if (p.bias) ok = ok && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;
     if (p.gelu_out) ok = ok && (reinterpret_cast<uintptr_t>(p.gelu_out) & 15) == 0;
     fast = ok && m0 + BM <= p.M && n0 + BM <= p.N;
@@ -153,7 +159,11 @@ struct Epi {
   // that its latency hides behind that tile's multiplies.
   struct Pre { float4 lo, hi; };
   __device__ __forceinline__ void prefetch(const DmaP &p, int m, int nn, Pre &r) const {
-    if (p.res) {
+    if (p.res && p.res_fp32) {   // the fp32 residual stream: 8 columns are 32 bytes
+      const float *x = reinterpret_cast<const float *>(p.res) + int64_t(m) * p.ldr + nn;
+      r.lo = *reinterpret_cast<const float4 *>(x);
+      r.hi = *reinterpret_cast<const float4 *>(x + 4);
+    } else if (p.res) {
       r.lo = *reinterpret_cast<const float4 *>(p.res + int64_t(m) * p.ldr + nn);
     } else if (p.c_fp32 && p.accumulate) {
       const float *c = static_cast<const float *>(p.C) + int64_t(m) * p.ldc + nn;
@@ -177,7 +187,12 @@ struct Epi {
   __device__ __forceinline__ void emit_fast(const DmaP &p, int m, int nn, float (&v)[8], const Pre &r,
                                             const float4 &bias8) const {
     if (p.bias) add_bf16x8(v, bias8);
-    if (p.res) add_bf16x8(v, r.lo);
+    if (p.res && p.res_fp32) {
+      v[0] += r.lo.x; v[1] += r.lo.y; v[2] += r.lo.z; v[3] += r.lo.w;
+      v[4] += r.hi.x; v[5] += r.hi.y; v[6] += r.hi.z; v[7] += r.hi.w;
+    } else if (p.res) {
+      add_bf16x8(v, r.lo);
+    }
     const int64_t ci = int64_t(m) * p.ldc + nn;
     if (p.c_fp32) {
       float *c = static_cast<float *>(p.C) + ci;
@@ -211,7 +226,9 @@ struct Epi {
   // one element; src points at its fp32 value in LDS
   __device__ __forceinline__ void emit_one(const DmaP &p, int m, int nn, float v) const {
     if (p.bias) v += to_f32(p.bias[nn]);
-    if (p.res) v += to_f32(p.res[int64_t(m) * p.ldr + nn]);
+    if (p.res)
+      v += p.res_fp32 ? reinterpret_cast<const float *>(p.res)[int64_t(m) * p.ldr + nn]
+                      : to_f32(p.res[int64_t(m) * p.ldr + nn]);
     const int64_t ci = int64_t(m) * p.ldc + nn;
     if (p.c_fp32) {
       float *c = static_cast<float *>(p.C) + ci;
@@ -503,7 +520,7 @@ int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st) {
   p.gelu_out = static_cast<bf16_t *>(g.gelu_out);
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.lda = uint32_t(g.lda); p.ldb = uint32_t(g.ldb); p.ldc = g.ldc; p.ldr = g.ldr;
-  p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate;
+  p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate; p.res_fp32 = g.res_fp32;
   static const int force_bk = env_int("HMY_GEMM_BK", 0), force_s = env_int("HMY_GEMM_STAGES", 0);
   const int gm = (g.M + BM - 1) / BM, gn = (g.N + BM - 1) / BM;
   // split the contraction over workgroups (fp32 atomics into C) only while that fills

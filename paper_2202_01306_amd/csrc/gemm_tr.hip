@@ -33,7 +33,7 @@ struct BigP {
   int M, N, K;
   uint32_t lda, ldb;
   int64_t ldc, ldr;
-  int c_fp32, accumulate;
+  int c_fp32, accumulate, res_fp32;
 };
 
 // element address inside a [row][k] tile (chunks swizzled by the row)
@@ -233,7 +233,9 @@ __global__ __launch_bounds__(NT) void k_gemm_mfma32(BigP p, int tiles_per_split,
         if (m >= p.M) continue;
         const int64_t ci = int64_t(m) * p.ldc + n;
         float v = acc[i][j][r] + bias_v;
-        if (p.res) v += to_f32(p.res[int64_t(m) * p.ldr + n]);
+        if (p.res)
+          v += p.res_fp32 ? reinterpret_cast<const float *>(p.res)[int64_t(m) * p.ldr + n]
+                          : to_f32(p.res[int64_t(m) * p.ldr + n]);
         if (split) {
           atomicAdd(static_cast<float *>(p.C) + ci, v);
         } else if (p.c_fp32) {
@@ -263,7 +265,7 @@ int launch_gemm_mfma32(const hmy_gemm_desc &g, stream_t st) {
   p.gelu_out = static_cast<bf16_t *>(g.gelu_out);
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.lda = uint32_t(g.lda); p.ldb = uint32_t(g.ldb); p.ldc = g.ldc; p.ldr = g.ldr;
-  p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate;
+  p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate; p.res_fp32 = g.res_fp32;
   const int gm = (g.M + BM - 1) / BM, gn = (g.N + BM - 1) / BM, nk = (g.K + BK - 1) / BK;
   // split the contraction over workgroups (fp32 atomics into C) when an accumulating
   // GEMM has too few output tiles to fill 256 compute units several times over

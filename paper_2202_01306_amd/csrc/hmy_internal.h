@@ -84,13 +84,15 @@ struct Split {
 int resolve(Packs *p, int n_micro, int micro_batch, Split *out);
 
 struct Reserved {  // pack-independent arena regions, byte offsets from the arena base
-  uint64_t X;         // the minibatch's boundary activations, [D*s, d] contiguous
+  uint64_t X;         // the minibatch's boundary activations (fp32), [D*s, d] contiguous
   uint64_t x_bytes_F, x_bytes_B;   // one forward / backward microbatch of it (unpadded)
+  uint64_t ck_bytes_F, ck_bytes_B; // the same microbatch as a checkpoint: rounded to the element type
   uint64_t in_bytes, out_bytes;    // a256 of those: one buffer of the rings
   uint64_t inring;    // kInRing buffers of in_bytes
   uint64_t outring;   // kOutRing buffers of out_bytes
   uint64_t gbig;      // T_B*max(f,3d)*E : dg/du and dqkv
   uint64_t gsmall;    // T_B*d*E : dh, do, da, dz
+  uint64_t dlow;      // T_B*d*E : the gradient of the residual stream rounded to the element type, for the GEMMs
   uint64_t delta;     // T_B*H*4
   uint64_t ids, targets;
   uint64_t misc;      // loss accumulators
@@ -136,19 +138,21 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
 // ---- kernel launchers (all pointers device; stream is a hipStream_t) ---------
 typedef void *stream_t;
 
-int launch_embed_fwd(int prec, const int32_t *ids, const void *wte, const void *wpe, void *x,
+// x, dx, res: the fp32 residual stream (whatever prec is); dx_e: optional copy of dx in the element type
+int launch_embed_fwd(int prec, const int32_t *ids, const void *wte, const void *wpe, float *x,
                      int T, int d, int s, int vocab, stream_t st);
-int launch_embed_bwd(int prec, const int32_t *ids, const void *dx, float *dwte, float *dwpe,
+int launch_embed_bwd(int prec, const int32_t *ids, const float *dx, float *dwte, float *dwpe,
                      int T, int d, int s, int vocab, stream_t st);
-int launch_layernorm_fwd(int prec, const void *x, const void *gamma, const void *beta, void *y,
+int launch_layernorm_fwd(int prec, const float *x, const void *gamma, const void *beta, void *y,
                          float *mean, float *rstd, int T, int d, float eps, stream_t st);
-int launch_layernorm_bwd(int prec, const void *dy, const void *x, const float *mean,
-                         const float *rstd, const void *gamma, const void *res, void *dx,
+int launch_layernorm_bwd(int prec, const void *dy, const float *x, const float *mean,
+                         const float *rstd, const void *gamma, const float *res, float *dx, void *dx_e,
                          float *dgamma, float *dbeta, int T, int d, stream_t st, float *workspace = nullptr,
                          uint64_t workspace_bytes = 0);
-int launch_layernorm_bwd_static(int prec, const void *dy, const void *x, const float *mean, const float *rstd,
-                                const void *gamma, const void *res, void *dx, float *dgamma, float *dbeta, int T, int d,
-                                stream_t st);
+int launch_layernorm_bwd_static(int prec, const void *dy, const float *x, const float *mean, const float *rstd,
+                                const void *gamma, const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta,
+                                int T, int d, stream_t st);
+int launch_convert_to_f32(int prec, const void *src, float *dst, uint64_t n, stream_t st);
 int launch_gelu_fwd(int prec, const void *u, void *g, uint64_t n, stream_t st);
 int launch_gelu_bwd(int prec, const void *dg, const void *u, void *du, uint64_t n, stream_t st);
 int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st);

@@ -27,11 +27,11 @@ BlockActs block_acts(const hmy_model_spec &s, int micro_batch) {
   BlockActs b;
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) { uint64_t o = off; off += a256(bytes); return o; };
-  b.x_in = take(T * d * E);
+  b.x_in = take(T * d * 4);    // the residual stream is fp32 whatever E is
   b.a = take(T * d * E);
   b.qkv = take(3 * T * d * E);
   b.o = take(T * d * E);
-  b.x_mid = take(T * d * E);
+  b.x_mid = take(T * d * 4);
   b.h = take(T * d * E);
   b.u = take(T * f * E);
   b.g = take(T * f * E);
@@ -52,7 +52,7 @@ HeadActs head_acts(const hmy_model_spec &s, int micro_batch) {
   h.ldl = (int64_t(s.vocab) + 63) / 64 * 64;   // rows start on 128-byte lines (element type) for the GEMMs that read them
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) { uint64_t o = off; off += a256(bytes); return o; };
-  h.x_in = take(T * d * E);
+  h.x_in = take(T * d * 4);
   h.z = take(T * d * E);
   h.mean = take(T * 4);
   h.rstd = take(T * 4);
@@ -96,15 +96,18 @@ Reserved reserved_layout(const Model &m, const Split &sp) {
   Reserved r;
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) { uint64_t o = off; off += a256(bytes); return o; };
-  r.x_bytes_F = TF * d * E;
-  r.x_bytes_B = TB * d * E;
-  r.in_bytes = a256(r.x_bytes_B);
-  r.out_bytes = a256(r.x_bytes_F);
-  r.X = take(Tall * d * E);   // one row per token of the minibatch: either pass's microbatch m is a run of its rows
+  r.x_bytes_F = TF * d * 4;   // the residual stream (boundary activations, their gradients) is fp32
+  r.x_bytes_B = TB * d * 4;
+  r.ck_bytes_F = TF * d * E;  // checkpoints cross the link rounded to the element type
+  r.ck_bytes_B = TB * d * E;
+  r.in_bytes = a256(r.ck_bytes_B);
+  r.out_bytes = a256(r.ck_bytes_F);
+  r.X = take(Tall * d * 4);   // one row per token of the minibatch: either pass's microbatch m is a run of its rows
   r.inring = take(kInRing * r.in_bytes);
   r.outring = take(kOutRing * r.out_bytes);
   r.gbig = take(TB * std::max<uint64_t>(f, 3 * d) * E);
   r.gsmall = take(TB * d * E);
+  r.dlow = take(TB * d * E);
   r.delta = take(TB * H * 4);
   r.ids = take(Tall * 4);
   r.targets = take(Tall * 4);
@@ -160,19 +163,26 @@ void layer_profile(const Model &m, const Rates &r, const Split &sp, int slots, s
     p.flops_fwd = layer_flops(m, l, sp.uF);
     p.ns_fwd = ns_of(p.flops_fwd);
     p.ns_bwd = ns_of(3 * layer_flops(m, l, sp.uB));   // recompute + backward (twice the forward flops)
+    // beside link traffic: the measured figure if there is one (never below the time alone), else the same
+    auto beside = [](uint64_t alone, uint64_t b) { return int64_t(std::max(alone, b)); };
+    int64_t fb = 0, bb = 0;
     if (l == 0) {
       p.act_bwd = 0;
-      if (mF) p.ns_fwd = int64_t(mF->embed_fwd_ns);
-      if (mB) p.ns_bwd = int64_t(mB->embed_fwd_ns + mB->embed_bwd_ns);
+      if (mF) p.ns_fwd = int64_t(mF->embed_fwd_ns), fb = beside(mF->embed_fwd_ns, mF->embed_fwd_beside_ns);
+      if (mB)
+        p.ns_bwd = int64_t(mB->embed_fwd_ns + mB->embed_bwd_ns),
+        bb = beside(mB->embed_fwd_ns, mB->embed_fwd_beside_ns) + beside(mB->embed_bwd_ns, mB->embed_bwd_beside_ns);
     } else if (l <= s.n_blocks) {
       p.act_bwd = act_block;
-      if (mF) p.ns_fwd = int64_t(mF->block_fwd_ns);
-      if (mB) p.ns_bwd = int64_t(mB->block_bwd_ns);
+      if (mF) p.ns_fwd = int64_t(mF->block_fwd_ns), fb = beside(mF->block_fwd_ns, mF->block_fwd_beside_ns);
+      if (mB) p.ns_bwd = int64_t(mB->block_bwd_ns), bb = beside(mB->block_bwd_ns, mB->block_bwd_beside_ns);
     } else {
       p.act_bwd = act_head;
-      if (mF) p.ns_fwd = int64_t(mF->head_ns);
-      if (mB) p.ns_bwd = int64_t(mB->head_ns);
+      if (mF) p.ns_fwd = int64_t(mF->head_ns), fb = beside(mF->head_ns, mF->head_beside_ns);
+      if (mB) p.ns_bwd = int64_t(mB->head_ns), bb = beside(mB->head_ns, mB->head_beside_ns);
     }
+    p.ns_fwd_beside = mF ? fb : p.ns_fwd;
+    p.ns_bwd_beside = mB ? bb : p.ns_bwd;
     p.mem_fwd = uint64_t(slots) * E * p.params;
     p.mem_bwd = uint64_t(slots) * (E + 4) * p.params + p.act_bwd;
   }
@@ -212,11 +222,12 @@ std::vector<Region> arena_regions(const Model &m, const Arena &a, const Split &s
   const hmy_model_spec &s = m.spec;
   const uint64_t E = m.elem_bytes(), d = s.d_model, Tall = uint64_t(sp.D) * s.seq_len, TB = uint64_t(sp.uB) * s.seq_len;
   std::vector<Region> v;
-  v.push_back({"X", r.X, Tall * d * E});
+  v.push_back({"X", r.X, Tall * d * 4});
   v.push_back({"inring", r.inring, kInRing * r.in_bytes});
   v.push_back({"outring", r.outring, kOutRing * r.out_bytes});
   v.push_back({"gbig", r.gbig, TB * std::max<uint64_t>(s.d_ffn, 3 * d) * E});
   v.push_back({"gsmall", r.gsmall, TB * d * E});
+  v.push_back({"dlow", r.dlow, TB * d * E});
   v.push_back({"delta", r.delta, TB * uint64_t(s.n_heads) * 4});
   v.push_back({"ids", r.ids, Tall * 4});
   v.push_back({"targets", r.targets, Tall * 4});
@@ -375,6 +386,8 @@ static bool balanced_time_packing(const std::vector<int64_t> &t, const std::vect
 //              and state, weights and the exported gradient start out (device->host), ending no earlier
 //              than the state has arrived; on the host only the gradient goes out and the CPU
 //              (about 6 parameters per nanosecond on the machines measured) is one more queue.
+//   slowdown : a visit computes for its layers' times alone, stretched towards their times beside link traffic
+//              in proportion to the share of it for which the device->host link has work queued at its start.
 //   result   : when the last queue falls idle.
 uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profile> &prof, const Packs &p,
                                const Split &sp, uint64_t link_MBps) {
@@ -384,7 +397,7 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
   const bool export_g = host || p.gradients == HMY_GRADIENTS_EXPORTED;
   constexpr uint64_t kHostParamsPerNs = 6;
   const uint64_t x_all = uint64_t(sp.D) * m.spec.seq_len * m.spec.d_model * E;   // one checkpoint of the whole minibatch
-  struct V { bool bwd; uint64_t comp, w, kin, out, cpu, sin, sout; };
+  struct V { bool bwd; uint64_t comp, w, kin, out, cpu, sin, sout, comp_beside; };
   std::vector<V> vs;
   auto is_ckpt = [&](int layer) {
     for (size_t k = 1; k + 1 < p.bwd.size(); ++k)
@@ -392,21 +405,27 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
     return false;
   };
   for (const Pack &q : p.fwd) {
-    uint64_t ns = 0, n_ck = 0;
+    uint64_t ns = 0, nb = 0, n_ck = 0;
     for (int l = q.a; l < q.e; ++l) {
       ns += uint64_t(prof[l].ns_fwd);
+      nb += uint64_t(prof[l].ns_fwd_beside);
       n_ck += is_ckpt(l);
     }
-    vs.push_back({false, ns * sp.MF(), t_bytes(E * m.params_in(q.a, q.e)), 0, 0, 0, 0, n_ck ? t_bytes(n_ck * x_all) : 0});
+    vs.push_back({false, ns * sp.MF(), t_bytes(E * m.params_in(q.a, q.e)), 0, 0, 0, 0, n_ck ? t_bytes(n_ck * x_all) : 0,
+                  nb * sp.MF()});
   }
   for (int k = int(p.bwd.size()) - 1; k >= 0; --k) {
     const Pack &q = p.bwd[k];
-    uint64_t ns = 0;
-    for (int l = q.a; l < q.e; ++l) ns += uint64_t(prof[l].ns_bwd);
+    uint64_t ns = 0, nb = 0;
+    for (int l = q.a; l < q.e; ++l) {
+      ns += uint64_t(prof[l].ns_bwd);
+      nb += uint64_t(prof[l].ns_bwd_beside);
+    }
     const uint64_t P = m.params_in(q.a, q.e);
     const uint64_t sin = (k > 0 && k + 1 < int(p.bwd.size())) ? t_bytes(x_all) : 0;
-    if (host) vs.push_back({true, ns * sp.MB(), t_bytes(E * P), 0, t_bytes(4 * P), P / kHostParamsPerNs, sin, 0});
-    else vs.push_back({true, ns * sp.MB(), t_bytes(E * P), t_bytes(kB * P), t_bytes((kB + E + (export_g ? 4 : 0)) * P), 0, sin, 0});
+    if (host) vs.push_back({true, ns * sp.MB(), t_bytes(E * P), 0, t_bytes(4 * P), P / kHostParamsPerNs, sin, 0, nb * sp.MB()});
+    else vs.push_back({true, ns * sp.MB(), t_bytes(E * P), t_bytes(kB * P), t_bytes((kB + E + (export_g ? 4 : 0)) * P), 0, sin, 0,
+                       nb * sp.MB()});
   }
   const int n = int(vs.size()), S = p.slots, D = p.distance;
   uint64_t h2d_free = 0, d2h_free = 0, comp_free = 0, cpu_free = 0;
@@ -421,7 +440,15 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
       if (v + D - S >= 0) s0 = std::max(s0, left[v + D - S]);
       w_ready[v + D] = h2d_free = s0 + vs[v + D].w;
     }
-    const uint64_t comp_end = comp_start + vs[v].comp;
+    // kernels run slower while the host-writing update is busy beside them: the visit's time moves from its
+    // time alone towards its time beside link traffic, in proportion to the share of it for which the outgoing
+    // link still has work queued now (earlier updates, this visit's checkpoints)
+    uint64_t comp = vs[v].comp;
+    if (vs[v].comp_beside > comp && d2h_free > comp_start) {
+      const uint64_t backlog = std::min(d2h_free - comp_start, comp);
+      comp += uint64_t((__uint128_t)(vs[v].comp_beside - comp) * backlog / comp);
+    }
+    const uint64_t comp_end = comp_start + comp;
     comp_free = comp_end;
     if (!vs[v].bwd) {
       left[v] = comp_end;

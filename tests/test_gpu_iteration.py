@@ -303,6 +303,8 @@ def test_measured_profile_feeds_the_planner():
         say(f"  {mp}")
         assert all(mp[k] > 0 for k in B.MEASURED_FIELDS)
         assert mp["block_bwd_ns"] > mp["block_fwd_ns"]          # recompute + backward against one forward
+        # every time also beside host-link traffic, never reported below the time alone
+        assert all(mp[k] >= mp[k.replace("_beside", "")] for k in B.MEASURED_BESIDE_FIELDS)
     prof, _ = B.hmy_profile(spec, 4, 2, budget=B.make_budget(0, measured=meas))
     assert (prof[1]["ns_fwd"], prof[1]["ns_bwd"], prof[-1]["ns_bwd"]) == \
         (meas[1]["block_fwd_ns"], meas[1]["block_bwd_ns"], meas[1]["head_ns"])

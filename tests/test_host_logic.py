@@ -112,6 +112,12 @@ def test_profile_takes_measured_times_where_the_budget_brings_them():
             dict(micro_batch=4, embed_fwd_ns=21, embed_bwd_ns=23, block_fwd_ns=1900, block_bwd_ns=6000, head_ns=1300)]
     got, _ = B.hmy_profile(spec, 4, 2, budget=B.make_budget(0, measured=meas))
     assert [(p["ns_fwd"], p["ns_bwd"]) for p in got] == [(11, 24), (1000, 3100), (1000, 3100), (700, 700)]
+    assert all(p["ns_fwd_beside"] == p["ns_fwd"] and p["ns_bwd_beside"] == p["ns_bwd"] for p in got)   # none measured
+    assert all(p["ns_fwd_beside"] == p["ns_fwd"] and p["ns_bwd_beside"] == p["ns_bwd"] for p in analytic)
+    # times beside link traffic, where measured (never below the time alone)
+    both = [dict(meas[0], embed_bwd_beside_ns=20, block_fwd_beside_ns=900, block_bwd_beside_ns=4000, head_beside_ns=800)]
+    got, _ = B.hmy_profile(spec, 4, 2, budget=B.make_budget(0, measured=both))
+    assert [(p["ns_fwd_beside"], p["ns_bwd_beside"]) for p in got] == [(11, 11 + 20), (1000, 4000), (1000, 4000), (800, 800)]
     got, _ = B.hmy_profile(spec, 4, 2, sched=B.make_schedule([], [], fwd_micro_batch=4), budget=B.make_budget(0, measured=meas))
     assert [(p["ns_fwd"], p["ns_bwd"]) for p in got] == [(21, 24), (1900, 3100), (1900, 3100), (1300, 700)]
     got, _ = B.hmy_profile(spec, 4, 2, sched=B.make_schedule([], [], fwd_micro_batch=8, bwd_micro_batch=1),
@@ -296,7 +302,8 @@ def simulate_like_the_library(cfg, sched, link_MBps=40000, compute_GFLOPs=420000
     ops = osim.iteration_ops(ospec, P_F, P_B, [p["ns_fwd"] for p in prof], [p["ns_bwd"] for p in prof], D // uF, D // uB,
                              uF * row, uB * row, w_c, k_B, g_B, per_byte, per_byte, slots=a["weight_slots"],
                              distance=a["prefetch_distance"], update_on_host=bool(sched.update_site),
-                             export_gradients=not sched.gradients)
+                             export_gradients=not sched.gradients,
+                             t_fwd_beside=[p["ns_fwd_beside"] for p in prof], t_bwd_beside=[p["ns_bwd_beside"] for p in prof])
     return max(e for _, e in osim.run(ops).values()), len(ops)
 
 
@@ -344,7 +351,23 @@ def test_estimate_on_schedules_worked_by_hand():
     assert B.hmy_estimate(spec, a, 2, 1, **rates) == 1015040
     a.update_site = B.HMY_UPDATE_ON_HOST
     assert B.hmy_estimate(spec, a, 2, 1, **rates) == 929461
+    # (e) schedule (a) with per-layer times given as measurements (microbatch size 1: embedding 256 forward, 256
+    #     backward, so 512 in a backward task; block 102400 / 307200; head 8192) and the block's backward time beside
+    #     link traffic twice its time alone (614400):
+    #     W0 0-28928; C0 = 2*(256+102400) -234240; W1 -31232; C1 = 2*8192 starts at 234240 with nothing outgoing
+    #     queued: as alone -> 250624; W2 (asked at 234240) -263168; K1 (asked at 250624, behind W2) 263168-267776;
+    #     Out1 250624-259840, held to 267776 by K1; C2 = 2*(512+307200) = 615424 alone, 1229824 beside traffic,
+    #     starts at 263168 (its weights) while the outgoing link is busy until 267776: a backlog of 4608 ns, so it
+    #     takes 615424 + 614400 * 4608 / 615424 = 620024 (rounded down) -> 883192; K2 -941048; Out2 883192-998904.
+    meas = [dict(micro_batch=1, embed_fwd_ns=256, embed_bwd_ns=256, block_fwd_ns=102400, block_bwd_ns=307200, head_ns=8192,
+                 block_bwd_beside_ns=614400)]
+    e = B.make_schedule([2], [2, 3])
+    assert B.hmy_estimate(spec, e, 2, 1, link_MBps=1000, measured=meas) == 998904
+    assert B.hmy_estimate(spec, e, 2, 1, link_MBps=1000, measured=[dict(meas[0], block_bwd_beside_ns=0)]) == 994304
     slow = dict(link_MBps=100, compute_GFLOPs=1)
+    stretched = B.hmy_estimate(spec, e, 2, 1, link_MBps=100, measured=meas)
+    assert stretched > B.hmy_estimate(spec, e, 2, 1, link_MBps=100, measured=[dict(meas[0], block_bwd_beside_ns=0)])
+    assert_estimate_matches_simulation(cfg, e, link_MBps=100, measured=meas)
     c = B.make_schedule([1, 2], [1, 2, 3], slots=2)
     assert B.hmy_estimate(spec, c, 1, 1, **slow) == 2114560
     c.weight_slots = 3
@@ -379,8 +402,10 @@ def test_estimate_equals_the_oracles_simulation_on_every_packing_of_a_small_mode
     cfg = tiny_cfg(n_blocks=3, d_model=64, n_heads=2, d_ffn=128, seq_len=16, vocab=50, precision="bf16", M=4, b=2)
     rng = np.random.default_rng(11)
     n = 0
-    meas = [dict(micro_batch=2, embed_fwd_ns=300, embed_bwd_ns=900, block_fwd_ns=9000, block_bwd_ns=31000, head_ns=5000),
-            dict(micro_batch=8, embed_fwd_ns=1000, embed_bwd_ns=3000, block_fwd_ns=30000, block_bwd_ns=99000, head_ns=17000)]
+    meas = [dict(micro_batch=2, embed_fwd_ns=300, embed_bwd_ns=900, block_fwd_ns=9000, block_bwd_ns=31000, head_ns=5000,
+                 embed_bwd_beside_ns=1300, block_fwd_beside_ns=9500, block_bwd_beside_ns=40000, head_beside_ns=5900),
+            dict(micro_batch=8, embed_fwd_ns=1000, embed_bwd_ns=3000, block_fwd_ns=30000, block_bwd_ns=99000, head_ns=17000,
+                 block_bwd_beside_ns=120000)]
     for P_B in all_packings(5):
         fw = list(all_packings(P_B[-1][0])) if P_B[-1][0] else [[]]
         for P_F in fw[::2]:

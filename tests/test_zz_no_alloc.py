@@ -30,12 +30,13 @@ def _case(B, prec, pc, dt, tol, T, d, seed):
         torch.cuda.synchronize()
         return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
-    x, g, bt = rnd((T, d), 2.0), rnd((d,)) + 1, rnd((d,), 0.1)
+    # x, res and dx are the fp32 residual stream; dy, gamma, beta have the element type
+    x, g, bt = (rng.standard_normal((T, d)) * 2.0).astype(np.float32), rnd((d,)) + 1, rnd((d,), 0.1)
     g = synth.round_bf16(g) if prec == "bf16" else g
-    dy, res = rnd((T, d)), rnd((T, d))
+    dy, res = rnd((T, d)), rng.standard_normal((T, d)).astype(np.float32)
     dg0, db0 = rng.standard_normal(d).astype(np.float32), rng.standard_normal(d).astype(np.float32)
-    xd, gd, bd, dyd, resd = dev(x, dt), dev(g, dt), dev(bt, dt), dev(dy, dt), dev(res, dt)
-    y = torch.empty_like(xd)
+    xd, gd, bd, dyd, resd = dev(x, torch.float32), dev(g, dt), dev(bt, dt), dev(dy, dt), dev(res, torch.float32)
+    y = torch.empty(T, d, device="cuda", dtype=dt)
     mean, rstd = torch.empty(T, device="cuda"), torch.empty(T, device="cuda")
     B.hmy_k_layernorm_fwd(pc, xd, gd, bd, y, mean, rstd, T, d, synth.LN_EPS)
     # the existing entry point, with a workspace of the caller's
@@ -50,7 +51,7 @@ def _case(B, prec, pc, dt, tol, T, d, seed):
     _, (xhat, rs) = om.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), bt.astype(np.float64), synth.LN_EPS)
     dxr, dgr, dbr = om.layernorm_bwd(dy.astype(np.float64), (xhat, rs), g.astype(np.float64))
     etol = tol if prec == "bf16" else 2e-5
-    assert max_rel_err(host(dx_b), dxr + res) < tol
+    assert max_rel_err(host(dx_b), dxr + res) < (tol if prec == "bf16" else 2e-5)
     assert max_rel_err(host(dg_b) - dg0, dgr) < etol
     assert max_rel_err(host(db_b) - db0, dbr) < etol
 
