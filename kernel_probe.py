@@ -27,6 +27,8 @@ def main() -> int:
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--sets", type=int, default=6)
     ap.add_argument("--only", default="", help="run only the kernels whose line starts with this text, e.g. 'gemm fwd'")
+    ap.add_argument("--pad", type=int, default=0, help="elements added to the leading dimensions of the GEMM operands "
+                    "(what strides that are powers of two cost)")
     ap.add_argument("--micro-batch", type=int, default=0, help="sequences per microbatch instead of the configuration's")
     a = ap.parse_args()
     import torch
@@ -71,8 +73,8 @@ def main() -> int:
     def gemm(name, M, N, K, ta, tb, acc=False, bias=False, res=False, gelu=False, lda=None, ldb=None, ldc=None, c32=False):
         if not name.startswith(a.only):
             return
-        lda = lda or (M if ta else K)
-        ldb = ldb or (N if tb else K)
+        lda = (lda or (M if ta else K)) + a.pad
+        ldb = (ldb or (N if tb else K)) + a.pad
         ldc = ldc or N
         As = [rnd(K if ta else M, lda, scale=0.5) for _ in range(n)]
         Bs = [rnd(K if tb else N, ldb, scale=0.02) for _ in range(n)]

@@ -22,7 +22,8 @@
 // same contraction order as the 16-byte read of the other layout.
 //
 // Tuning switches (read once per process): HMY_GEMM_BK = 32 | 64 and
-// HMY_GEMM_STAGES = 3 | 4 override the K tile and the ring depth.
+// HMY_GEMM_STAGES = 3 | 4 override the K tile and the ring depth of the 128x128 kernel,
+// HMY_GEMM_TILE = 128 | 256 the choice between it and the 256x256 kernel.
 #include <algorithm>
 #include <cstdlib>
 
@@ -135,14 +136,14 @@ template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_wai
 // path is element-wise and kept rolled, so that it costs no instruction-cache space.
 struct Epi {
   bool fast;
-  __device__ __forceinline__ void init(const DmaP &p, int m0, int n0) {
+  __device__ __forceinline__ void init(const DmaP &p, int m0, int n0, int side = BM) {
     const int esz = p.c_fp32 ? 4 : 2;
     bool ok = (reinterpret_cast<uintptr_t>(p.C) & 15) == 0 && (p.ldc * esz) % 16 == 0;
     if (p.res) ok = ok && (reinterpret_cast<uintptr_t>(p.res) & 15) == 0 && p.ldr % 8 == 0;
     if (p.res && p.res_fp32 && p.accumulate) ok = false;   // both would want the prefetch registers
     if (p.bias) ok = ok && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;
     if (p.gelu_out) ok = ok && (reinterpret_cast<uintptr_t>(p.gelu_out) & 15) == 0;
-    fast = ok && m0 + BM <= p.M && n0 + BM <= p.N;
+    fast = ok && m0 + side <= p.M && n0 + side <= p.N;
   }
   // tanh-form GELU with the hardware exponential: the argument is a bf16 value and so is
   // the result, which the 2-ulp exponential does not disturb.  Written as u * sigmoid(2z),
@@ -481,6 +482,194 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   }
 }
 
+// The same GEMM on a 256x256 block tile for outputs large enough to give every compute unit one: what bounds the
+// 128x128 kernel is the rate at which the L2 caches feed the load-to-LDS instructions of all compute units together,
+// and a tile of twice the side moves half the bytes per multiply.  Eight waves of 128x64 (4x2 multiplies of 32x32x16
+// per 16-deep step, two waves per SIMD), K tiles of 32, the same ring of S stages.  Each operand's 256 rows are kept
+// as two 128-row sub-tiles in the layouts of the 128x128 kernel; waves 0-3 copy the first sub-tile of A and of B,
+// waves 4-7 the second, each group splitting its sub-tile the way the four waves of that kernel do.
+template <bool TA, bool TB, int S>
+__global__ __launch_bounds__(512) void k_gemm_dma256(DmaP p, int grid_n) {
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  constexpr int BK = 32, BT = 256;
+  constexpr int SUB = BM * BK;        // elements of one 128-row sub-tile (8 KiB)
+  constexpr int STAGE = 4 * SUB;      // elements of one stage: A rows 0-127, A rows 128-255, B likewise (32 KiB)
+  constexpr int L = 4;                // load-to-LDS instructions per thread per K tile
+  static_assert(S >= 3, "one stage is multiplied, one is the next to be, the others are in flight");
+  static_assert((S - 1) * L <= 63, "vmcnt is a 6-bit counter");
+  static_assert(S * STAGE * 2 >= 128 * 1024, "the output stage needs 16 KiB of LDS per wave");
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int wm = wave / 4, wn = wave % 4;     // this wave's outputs: rows 128 wm .. +127, columns 64 wn .. +63
+  const int half = wave / 4, w4 = wave % 4;   // the sub-tile of each operand this wave copies, and its share of it
+  // workgroup -> tile as in the 128x128 kernel (the contraction is never split here: the fp32 atomics of a split
+  // make the sum's order, and with it a result that is rounded afterwards, differ from run to run)
+  int bid = blockIdx.x;
+  const int nb = gridDim.x, grid_m = nb / grid_n;
+  {
+    const int x = bid % 8, per = nb / 8, extra = nb % 8;
+    bid = x * per + min(x, extra) + bid / 8;
+  }
+  constexpr int kBand = 4;
+  const int band = bid / (kBand * grid_n), first_m = band * kBand;
+  const int band_rows = min(grid_m - first_m, kBand);
+  const int in_band = bid - band * kBand * grid_n;
+  const int m0 = (first_m + in_band % band_rows) * BT, n0 = (in_band / band_rows) * BT;
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int n = p.K / BK;   // K tiles
+  Dma<TA, BK> da;
+  Dma<TB, BK> db;
+  da.init(p.lda, m0 + BM * half, p.M, lane, w4);
+  db.init(p.ldb, n0 + BM * half, p.N, lane, w4);
+  const uint32_t lds0 = uint32_t(reinterpret_cast<uintptr_t>(smem));
+  const uint32_t a_off = uint32_t(half) * uint32_t(2 * SUB), b_off = uint32_t(4 * SUB) + a_off;   // bytes inside a stage
+  const uint64_t a_kstep = TA ? uint64_t(BK) * p.lda : uint64_t(BK);
+  const uint64_t b_kstep = TB ? uint64_t(BK) * p.ldb : uint64_t(BK);
+  const bf16_t *a_next = p.A, *b_next = p.B;
+#pragma unroll
+  for (int s = 0; s < S; ++s)
+    if (s < n) {
+      da.issue(a_next, lds0 + uint32_t(s) * uint32_t(2 * STAGE) + a_off, w4);
+      db.issue(b_next, lds0 + uint32_t(s) * uint32_t(2 * STAGE) + b_off, w4);
+      a_next += a_kstep;
+      b_next += b_kstep;
+    }
+
+  const int a_sub = wm * SUB, b_sub = 2 * SUB + (wn / 2) * SUB, brow = (wn % 2) * 64;
+  bf16x8 fa[2][4], fb[2][2];   // fragments of one 16-deep step, read one step ahead of their multiplies
+  if (n > S - 1) wait_vm<(S - 1) * L>();
+  else wait_vm<0>();
+  __syncthreads();
+  if (n > 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[0][i] = frag<TA, BK>(smem + a_sub, 32 * i, 0, lane);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) fb[0][j] = frag<TB, BK>(smem + b_sub, brow + 32 * j, 0, lane);
+  }
+#define HMY_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define HMY_MFMA(i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0)
+  // One 16-deep step: eight multiplies on fragment buffer `cur`; behind six of them one of the six fragment reads of the
+  // next step (from stage `nstage`, step `nks`, into buffer `nxt`); with `fetch`, behind four of them the four
+  // load-to-LDS instructions that bring the next tile into stage `fstage`.
+  auto step = [&](int cur, int nxt, bool reads, int nstage, int nks, bool fetch, int fstage) {
+    const bf16_t *a_s = smem + nstage * STAGE + a_sub, *b_s = smem + nstage * STAGE + b_sub;
+    const uint32_t fl = lds0 + uint32_t(fstage) * uint32_t(2 * STAGE);
+    HMY_FENCE();
+    HMY_MFMA(0, 0);
+    HMY_FENCE();
+    if (reads) fa[nxt][0] = frag<TA, BK>(a_s, 0, nks, lane);
+    HMY_FENCE();
+    HMY_MFMA(0, 1);
+    HMY_FENCE();
+    if (reads) fb[nxt][0] = frag<TB, BK>(b_s, brow, nks, lane);
+    HMY_FENCE();
+    HMY_MFMA(1, 0);
+    HMY_FENCE();
+    if (reads) fb[nxt][1] = frag<TB, BK>(b_s, brow + 32, nks, lane);
+    HMY_FENCE();
+    HMY_MFMA(1, 1);
+    HMY_FENCE();
+    if (reads) fa[nxt][1] = frag<TA, BK>(a_s, 32, nks, lane);
+    if (fetch) da.issue_one(a_next, fl + a_off, w4, 0);
+    HMY_FENCE();
+    HMY_MFMA(2, 0);
+    HMY_FENCE();
+    if (reads) fa[nxt][2] = frag<TA, BK>(a_s, 64, nks, lane);
+    if (fetch) db.issue_one(b_next, fl + b_off, w4, 0);
+    HMY_FENCE();
+    HMY_MFMA(2, 1);
+    HMY_FENCE();
+    if (reads) fa[nxt][3] = frag<TA, BK>(a_s, 96, nks, lane);
+    if (fetch) da.issue_one(a_next, fl + a_off, w4, 1);
+    HMY_FENCE();
+    HMY_MFMA(3, 0);
+    HMY_FENCE();
+    if (fetch) db.issue_one(b_next, fl + b_off, w4, 1);
+    HMY_FENCE();
+    HMY_MFMA(3, 1);
+    HMY_FENCE();
+  };
+  int stage = 0;      // stage holding tile t
+  Epi e;
+  e.init(p, m0, n0, BT);
+  const int m_tile = m0 + wm * 128, n_tile = n0 + wn * 64;
+  // what the output stage adds, fetched one 32-row slab ahead: slab i, pass q -> row 32 i + 8 q + lane/8, columns 8 (lane%8) .. +7
+  Epi::Pre pre[2][4];
+  float4 bias8 = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto prefetch_slab = [&](int i, int buf) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) e.prefetch(p, m_tile + 32 * i + 8 * q + lane / 8, n_tile + 8 * (lane % 8), pre[buf][q]);
+  };
+  for (int t = 0; t + 1 < n; ++t) {
+    const int next = stage + 1 == S ? 0 : stage + 1;
+    step(0, 1, true, stage, 1, false, 0);
+    // every read of tile t has been issued.  Tiles up to t+S-1 have been requested: tile t+1 has landed once at most
+    // the S-2 behind it are outstanding.
+    if (t + S - 1 < n) wait_vm<(S - 2) * L>();
+    else wait_vm<0>();
+    __syncthreads();   // tile t+1 visible to every wave; every wave is done reading tile t
+    const bool fetch = t + S < n;   // tile t+S goes to the stage tile t has just left: S-1 tiles ahead of its use
+    step(1, 0, true, next, 0, fetch, stage);
+    if (fetch) {
+      a_next += a_kstep;
+      b_next += b_kstep;
+    }
+    stage = next;
+  }
+  if (e.fast) {
+    if (p.bias) bias8 = *reinterpret_cast<const float4 *>(p.bias + n_tile + 8 * (lane % 8));
+    prefetch_slab(0, 0);
+  }
+  if (n > 0) {   // last tile: nothing left to fetch or wait for
+    step(0, 1, true, stage, 1, false, 0);
+    step(1, 0, false, stage, 0, false, 0);
+  }
+#undef HMY_MFMA
+#undef HMY_FENCE
+
+  // output stage as in the 128x128 kernel: 32 rows at a time through LDS, alternating between two 8 KiB buffers per
+  // wave so that one slab's stores to memory overlap the next slab's way through LDS
+  __syncthreads();   // every wave has finished reading the operand stages
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float *slab = reinterpret_cast<float *>(smem) + wave * 4096 + (i & 1) * 2048;
+    if (e.fast && i + 1 < 4) prefetch_slab(i + 1, (i + 1) & 1);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r / 4) + 4 * (lane / 32) + r % 4, col = 32 * j + lane % 32;
+        slab[row * 64 + (col ^ (((row >> 2) & 1) << 5))] = acc[i][j][r];
+      }
+    if (e.fast) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = 8 * q + lane / 8, c0 = 8 * (lane % 8);
+        const float *src = slab + row * 64 + (c0 ^ (((row >> 2) & 1) << 5));
+        float v[8];
+        *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
+        *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
+        e.emit_fast(p, m_tile + 32 * i + row, n_tile + c0, v, pre[i & 1][q], bias8);
+      }
+    } else {
+#pragma unroll 1
+      for (int idx = lane; idx < 32 * 64; idx += 64) {   // one row of 64 columns per pass
+        const int row = idx / 64, col = idx % 64;
+        const int m = m_tile + 32 * i + row, nn = n_tile + col;
+        if (m < p.M && nn < p.N) e.emit_one(p, m, nn, slab[row * 64 + (col ^ (((row >> 2) & 1) << 5))]);
+      }
+    }
+  }
+}
+
 inline int check_launch(const char *what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(HMY_E_HIP, "launch of %s failed: %s", what, hipGetErrorString(e));
@@ -496,6 +685,17 @@ int launch_cfg(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int tiles_per_s
   else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma<true, false, BK, S>), grid, block, lds, s, p, tiles_per_split, gn, splits);
   else hipLaunchKernelGGL((k_gemm_dma<true, true, BK, S>), grid, block, lds, s, p, tiles_per_split, gn, splits);
   return check_launch("gemm_dma");
+}
+
+template <int S>
+int launch_cfg256(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int gn, hipStream_t s) {
+  const size_t lds = size_t(S) * 4 * BM * 32 * sizeof(bf16_t);
+  dim3 block(512);
+  if (!g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma256<false, false, S>), grid, block, lds, s, p, gn);
+  else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_dma256<false, true, S>), grid, block, lds, s, p, gn);
+  else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma256<true, false, S>), grid, block, lds, s, p, gn);
+  else hipLaunchKernelGGL((k_gemm_dma256<true, true, S>), grid, block, lds, s, p, gn);
+  return check_launch("gemm_dma256");
 }
 
 int env_int(const char *name, int dflt) {
@@ -522,12 +722,22 @@ int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st) {
   p.lda = uint32_t(g.lda); p.ldb = uint32_t(g.ldb); p.ldc = g.ldc; p.ldr = g.ldr;
   p.c_fp32 = g.c_fp32; p.accumulate = g.accumulate; p.res_fp32 = g.res_fp32;
   static const int force_bk = env_int("HMY_GEMM_BK", 0), force_s = env_int("HMY_GEMM_STAGES", 0);
+  static const int force_tile = env_int("HMY_GEMM_TILE", 0);   // 128 | 256: that block tile for every shape it can take
+  const bool can_split = g.accumulate && g.c_fp32 && !g.bias && !g.res;
+  {
+    // 256x256 tiles when they still give most compute units a workgroup (and a second round, if there is one, is
+    // at least half full): half the operand bytes per multiply through the L2 caches
+    const int gm2 = (g.M + 255) / 256, gn2 = (g.N + 255) / 256, wgs = gm2 * gn2;
+    const bool fills = wgs >= 176 && (wgs <= 256 || wgs >= 384);
+    if (force_tile != 128 && g.M >= 256 && g.N >= 256 && (force_tile == 256 || fills))
+      return launch_cfg256<4>(g, p, dim3(wgs), gn2, (hipStream_t)st);
+  }
   const int gm = (g.M + BM - 1) / BM, gn = (g.N + BM - 1) / BM;
   // split the contraction over workgroups (fp32 atomics into C) only while that fills
   // idle compute units: with one workgroup per unit already, a deeper K loop beats more
   // workgroups that each pay a prologue and an atomic epilogue
   int splits = 1;
-  if (g.accumulate && g.c_fp32 && !g.bias && !g.res && gm * gn <= 128)
+  if (can_split && gm * gn <= 128)
     splits = std::max(1, std::min(256 / (gm * gn), g.K / 256));
   // few workgroups: one per compute unit, deep K tiles and a deep ring; many: smaller
   // stages so that several are resident and overlap each other's prologue and epilogue

@@ -142,9 +142,10 @@ def test_embedding_fwd_bwd_with_repeated_ids(prec, pc, dt, tol):
     assert max_rel_err(host(dwpe), g["wpe"]) < 1e-5
 
 
-def _gemm_case(prec, pc, dt, tol, M, N, K, ta, tb, c_fp32, accumulate, bias, res, gelu, use_mfma, pad=0, res_fp32=0):
+def _gemm_case(prec, pc, dt, tol, M, N, K, ta, tb, c_fp32, accumulate, bias, res, gelu, use_mfma, pad=0, res_fp32=0,
+               row_pad=0):
     rng = np.random.default_rng(M * 7 + N * 3 + K + ta * 2 + tb)
-    lda = M if ta else K + pad        # padding only on rows whose contiguous axis is K
+    lda = M + row_pad if ta else K + pad        # pad: rows whose contiguous axis is K; row_pad: A stored [K, M]
     ldb = N if tb else K + pad
     A = rnd(rng, (K, lda) if ta else (M, lda), prec)
     Bm = rnd(rng, (K, ldb) if tb else (N, ldb), prec)
@@ -224,6 +225,35 @@ def test_gemm_bf16_epilogues(use_mfma):
     _gemm_case(*args, 136, 72, 200, 1, 1, 1, 1, False, False, False, use_mfma)      # wgrad: fp32 C +=
     _gemm_case(*args, 100, 1001, 64, 0, 0, 1, 0, False, False, False, use_mfma, 8)  # ragged N, padded ldc and lda
     _gemm_case(*args, 1000, 64, 96, 1, 1, 1, 1, False, False, False, use_mfma)      # ragged M (vocab-like), K=96
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 1), (1, 0)])
+@pytest.mark.parametrize("K", [96, 320])
+def test_gemm_bf16_large_outputs_all_layouts(ta, tb, K):
+    """Outputs large enough for the 256x256 block tile (one workgroup per compute unit or more), with a ragged last
+    tile row and column; K of fewer and of more tiles than the ring has stages."""
+    say(f"gemm bf16 large ta={ta} tb={tb} K={K}")
+    _gemm_case("bf16", 1, torch.bfloat16, 2e-2, 3600, 3336, K, ta, tb, 0, 0, False, False, False, True)
+
+
+def test_gemm_bf16_large_outputs_epilogues():
+    args = ("bf16", 1, torch.bfloat16, 2e-2)
+    say("gemm bf16 large: bias + gelu")
+    _gemm_case(*args, 4096, 3072, 64, 0, 0, 0, 0, True, False, True, True)
+    say("gemm bf16 large: bias + gelu in place")
+    _gemm_case(*args, 4096, 3072, 64, 0, 0, 0, 0, True, False, "in place", True)
+    say("gemm bf16 large: bias + fp32 residual stream")
+    _gemm_case(*args, 4096, 3072, 160, 0, 0, 1, 0, True, True, False, True, res_fp32=1)
+    say("gemm bf16 large: bias + bf16 residual")
+    _gemm_case(*args, 4096, 3072, 64, 0, 0, 0, 0, True, True, False, True)
+    say("gemm bf16 large: fp32 C +=")
+    _gemm_case(*args, 3072, 4096, 128, 1, 1, 1, 1, False, False, False, True)
+    _gemm_case(*args, 50257, 1024, 96, 1, 1, 1, 1, False, False, False, True, row_pad=47)   # vocabulary rows, ragged
+    say("gemm bf16: fp32 C +=, contraction split over workgroups (128x128 tiles)")
+    _gemm_case(*args, 1024, 1024, 4096, 1, 1, 1, 1, False, False, False, True)
+    _gemm_case(*args, 1536, 1024, 2048 + 32, 0, 1, 1, 1, False, False, False, True)    # the last split has two K tiles
+    say("gemm bf16 large: fp32 logits, ragged vocabulary, padded leading dimensions")
+    _gemm_case(*args, 512, 50257, 64, 0, 0, 1, 0, False, False, False, True, 8)
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 1)])
