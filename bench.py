@@ -40,14 +40,18 @@ def attention_flops(cfg, packs) -> float:
     return fwd * (L + recomputed) + 2.5 * fwd * L
 
 
-# HBM traffic per launch of the forward-variant GEMM at the gpt2m shapes, in bytes: FETCH_SIZE and WRITE_SIZE
-# (KiB per dispatch) from two `rocprofv3 --pmc` runs over `kernel_probe.py --only gemm --reps 1 --sets 1`, scaled
-# by what the same counters read for a streaming kernel of known size (k_gelu_bwd, 64 MiB in / 32 MiB out:
-# FETCH x 2.0, WRITE x 1.0).  Kept here because counters cannot be collected inside the benchmark run itself.
-GPT2M_NT_GEMM_TRAFFIC = {          # shape: (fetched KiB as counted, written KiB)
-    "qkv": (28168.6, 24576.0), "out": (16560.5, 8192.0), "ffn1": (33913.8, 65536.0), "ffn2": (53424.5, 8192.0),
-    "logits": (68840.6, 101015.6),   # 512-row chunk, fp32 logits
-}
+# HBM traffic of the forward-variant GEMM launches of one gpt2m iteration: FETCH_SIZE and WRITE_SIZE (KiB per
+# dispatch, averaged per kernel and grid) from two `rocprofv3 --pmc` runs over `bench.py --counters`, i.e. over the
+# launches of a real iteration.  Copied from profiles/gpt2m_forward_gemm_hbm_traffic.md, which has the commands; kept
+# here because counters cannot be collected inside the timed run itself.  FETCH_SIZE is scaled by 2.0 and
+# WRITE_SIZE by 1.0: what the same counters read for a streaming kernel of known size (k_gelu_bwd, 64 MiB in /
+# 32 MiB out).
+GPT2M_FWD_GEMM_TRAFFIC = [   # (what, kernel, grid threads, dispatches, FETCH_SIZE KiB as counted, WRITE_SIZE KiB)
+    ("ffn1", "k_gemm_dma256<false, false, 4>", 131072, 368, 24813.5, 49864.3),
+    ("qkv", "k_gemm_dma256<false, false, 4>", 98304, 368, 20713.5, 24576.0),
+    ("logits, 512-row chunk", "k_gemm_dma256<false, false, 4>", 201728, 64, 60230.4, 100542.5),
+    ("out and ffn2", "k_gemm_dma<false, false, 64, 4>", 65536, 672, 37292.1, 16384.0),
+]
 
 
 def nt_gemm_traffic_per_launch(config_name, cfg, packs, nt_calls):
@@ -55,26 +59,30 @@ def nt_gemm_traffic_per_launch(config_name, cfg, packs, nt_calls):
     iteration, or None where no counters were collected for the workload's shapes."""
     if config_name != "gpt2m":
         return None
+    measured = (sum(n * (2.0 * f + w) * 1024 for (_, _, _, n, f, w) in GPT2M_FWD_GEMM_TRAFFIC)
+                / sum(n for (_, _, _, n, _, _) in GPT2M_FWD_GEMM_TRAFFIC))
+    # what the launches of THIS run must move at least: each operand and result once (bf16; the residual stream and
+    # the logits fp32); FFN1 writes its pre-activation too where a backward pass will need it
     P_F, P_B = packs
     L, M = cfg["n_blocks"], cfg["M"]
     is_block = lambda layer: 1 <= layer <= L
     last_a, last_e = P_B[-1]
     n_last = sum(1 for l in range(last_a, last_e) if is_block(l))
     block_fwd = M * (2 * L - n_last)                        # forward pass + recompute, last pack once
+    kept = M * L                                            # every block once with its activations kept
     # the recompute of a backward pack stops before the FFN2 GEMM of its last block (its output is not needed)
     skipped = M * sum(1 for (a, e) in P_B[:-1] if is_block(e - 1))
-    calls = {"qkv": block_fwd, "out": block_fwd, "ffn1": block_fwd, "ffn2": block_fwd - skipped}
+    calls = {"qkv": block_fwd, "out": block_fwd, "ffn1_kept": kept, "ffn1": block_fwd - kept,
+             "ffn2": block_fwd - skipped}
     calls["logits"] = nt_calls - sum(calls.values())
     if calls["logits"] < 0:
         return None
-    total = sum(calls[k] * (2.0 * f + w) * 1024 for k, (f, w) in GPT2M_NT_GEMM_TRAFFIC.items())
-    # what the same launches must move at least: each operand and result once (bf16; fp32 logits)
     T, d, f, V, R = cfg["b"] * cfg["seq_len"], cfg["d_model"], cfg["d_ffn"], cfg["vocab"], 512
     ldl = (V + 63) // 64 * 64
-    algo = {"qkv": 2 * (T * d + 3 * d * d + 3 * d + T * 3 * d), "out": 2 * (T * d + d * d + d + 2 * T * d),
-            "ffn1": 2 * (T * d + f * d + f + 2 * T * f), "ffn2": 2 * (T * f + d * f + d + 2 * T * d),
-            "logits": 2 * (R * d + V * d) + 4 * R * ldl}
-    return total / nt_calls, sum(calls[k] * algo[k] for k in algo) / nt_calls
+    algo = {"qkv": 2 * (T * d + 3 * d * d + 3 * d + T * 3 * d), "out": 2 * (T * d + d * d + d) + 8 * T * d,
+            "ffn1_kept": 2 * (T * d + f * d + f + 2 * T * f), "ffn1": 2 * (T * d + f * d + f + T * f),
+            "ffn2": 2 * (T * f + d * f + d) + 8 * T * d, "logits": 2 * (R * d + V * d) + 4 * R * ldl}
+    return measured, sum(calls[k] * algo[k] for k in algo) / nt_calls
 
 
 def cpu_baseline(cfg):

@@ -640,16 +640,21 @@ __global__ void k_adam(const float *grad, float *master, float *m, float *v, W *
 // MIXED: master/m/v fp32 + bf16 weight.  !MIXED: the fp32 weight is the master
 // (in_master = the weight in HBM, out_w is fp32 and out_master is not used).
 // out_g == nullptr: the gradient is not exported.  Eight elements per thread per step; n may have a tail.
+// At most 64 registers: the kernel runs beside the compute stream's, and the largest of those leave 64 registers per
+// lane of a compute unit they occupy -- with more, a unit that holds one wave of this kernel could not take their workgroup.
 template <bool MIXED>
-__global__ void k_adam_out(const float *grad, const float *in_master, const float *in_m, const float *in_v,
+__global__ __attribute__((amdgpu_waves_per_eu(8))) void k_adam_out(const float *grad, const float *in_master, const float *in_m, const float *in_v,
                            float *out_master, float *out_m, float *out_v, void *out_w, float *out_g, uint64_t n,
                            float lr, float b1, float b2, float eps, float inv_bc1, float inv_bc2) {
   // A wavefront takes 512 consecutive elements per step as two runs of 256: lane l holds elements
   // 4 l .. 4 l + 3 of each run, so that every store instruction writes one contiguous KiB (half a KiB for the
   // bf16 weight).  With eight consecutive elements per lane each instruction left 16-byte holes between
   // lanes, which the path to the host has to stitch together from two instructions.
+  // The wave's position is kept in scalar registers (it is the same for all lanes), so that every access is a
+  // uniform base plus a lane offset of 32 bits: per-lane 64-bit addresses for nine arrays would cost the registers
+  // that the cap above takes away.
   const int lane = threadIdx.x % kWave;
-  const uint64_t wave = (uint64_t(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
+  const uint64_t wave = uint64_t(__builtin_amdgcn_readfirstlane(int((blockIdx.x * blockDim.x + threadIdx.x) / kWave)));
   const uint64_t stride = uint64_t(gridDim.x) * blockDim.x * 8;
   for (uint64_t wb = wave * 512; wb < n; wb += stride) {
     float g[8], w[8], m[8], v[8];
