@@ -222,7 +222,10 @@ typedef struct hmy_adam {
  * master).  adam_m, adam_v, grads: fp32.  After hmy_iteration they hold the
  * updated weights/state and this iteration's accumulated gradients (state that the
  * schedule keeps resident on the device: after hmy_sync_state).  Binding again makes
- * the engine read resident state afresh from the arrays. */
+ * the engine read resident state afresh from the arrays.
+ * With HMY_UPDATE_ON_HOST master, adam_m and adam_v may be ordinary (pageable) memory:
+ * only the library's CPU threads touch them; weights and grads, which cross the
+ * link, must be page-locked in every case. */
 typedef struct hmy_host_state {
   void *weights;
   float *master;

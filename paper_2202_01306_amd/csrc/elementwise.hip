@@ -640,6 +640,13 @@ __global__ void k_adam(const float *grad, float *master, float *m, float *v, W *
 // MIXED: master/m/v fp32 + bf16 weight.  !MIXED: the fp32 weight is the master
 // (in_master = the weight in HBM, out_w is fp32 and out_master is not used).
 // out_g == nullptr: the gradient is not exported.  Eight elements per thread per step; n may have a tail.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// 16 bytes to pinned host memory as a streaming store (nothing of it needs to stay in the L2 on the way out)
+__device__ __forceinline__ void store_host4(float *dst, const float *src) {
+  __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(src), reinterpret_cast<f32x4 *>(dst));
+}
+
 // At most 64 registers: the kernel runs beside the compute stream's, and the largest of those leave 64 registers per
 // lane of a compute unit they occupy -- with more, a unit that holds one wave of this kernel could not take their workgroup.
 template <bool MIXED>
@@ -689,17 +696,17 @@ __global__ __attribute__((amdgpu_waves_per_eu(8))) void k_adam_out(const float *
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       if (full[h]) {
-        *reinterpret_cast<float4 *>(out_m + at[h]) = *reinterpret_cast<const float4 *>(m + 4 * h);
-        *reinterpret_cast<float4 *>(out_v + at[h]) = *reinterpret_cast<const float4 *>(v + 4 * h);
-        if (out_g) *reinterpret_cast<float4 *>(out_g + at[h]) = *reinterpret_cast<const float4 *>(g + 4 * h);
+        store_host4(out_m + at[h], m + 4 * h);
+        store_host4(out_v + at[h], v + 4 * h);
+        if (out_g) store_host4(out_g + at[h], g + 4 * h);
         if (MIXED) {
-          *reinterpret_cast<float4 *>(out_master + at[h]) = *reinterpret_cast<const float4 *>(w + 4 * h);
+          store_host4(out_master + at[h], w + 4 * h);
           bf16_t o[4];
 #pragma unroll
           for (int k = 0; k < 4; ++k) o[k] = from_f32<bf16_t>(w[4 * h + k]);
-          *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(out_w) + at[h]) = *reinterpret_cast<const uint2 *>(o);
+          __builtin_nontemporal_store(*reinterpret_cast<const u32x2 *>(o), reinterpret_cast<u32x2 *>(static_cast<bf16_t *>(out_w) + at[h]));
         } else {
-          *reinterpret_cast<float4 *>(static_cast<float *>(out_w) + at[h]) = *reinterpret_cast<const float4 *>(w + 4 * h);
+          store_host4(static_cast<float *>(out_w) + at[h], w + 4 * h);
         }
       } else {
         for (int k = 0; k < 4 && at[h] + k < n; ++k) {
