@@ -452,13 +452,17 @@ int hmy_k_layernorm_fwd(int32_t prec, const float *x, const void *gamma, const v
 /* dx (fp32) = (res ? res : 0) + LN'(dy); dgamma,dbeta += (fp32).  dy has type E; x, res and
  * dx are fp32; dx may alias res.  dx_e (may be NULL): a copy of dx rounded to type E, which is
  * what the GEMMs that consume this gradient read.
- * workspace (device, may be NULL): with at least 256 * 2 * d floats the per-workgroup
- * partial sums of dgamma / dbeta go there and a second kernel adds them up; without it
- * they are added with atomics (same result up to summation order, slower). */
+ * dres_sum (may be NULL; needs res): dres_sum[d] += column sums of res.  res is the gradient
+ * arriving over the residual connection, which is also the gradient of the output of the linear
+ * layer that closes the branch: its column sums are that layer's bias gradient, taken here
+ * from the fp32 values while they pass through anyway.
+ * workspace (device, may be NULL): with at least 256 * 2 * d floats (256 * 3 * d with
+ * dres_sum) the per-workgroup partial sums go there and a second kernel adds them up;
+ * without it they are added with atomics (same result up to summation order, slower). */
 int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const float *x, const float *mean,
                         const float *rstd, const void *gamma, const float *res, float *dx, void *dx_e,
-                        float *dgamma, float *dbeta, int32_t T, int32_t d, void *stream,
-                        float *workspace, uint64_t workspace_bytes);
+                        float *dgamma, float *dbeta, float *dres_sum, int32_t T, int32_t d,
+                        void *stream, float *workspace, uint64_t workspace_bytes);
 /* hmy_k_layernorm_bwd for callers that cannot allocate device memory (code under HIP graph
  * capture, serving loops, harnesses that forbid hipMalloc): same arguments without the
  * workspace, same kernels, same results.  The per-workgroup partial sums go to an 8 MiB array
@@ -476,6 +480,10 @@ int hmy_k_layernorm_bwd_static(int32_t prec, const void *dy, const float *x, con
 /* g = gelu_tanh(u); du = dg * gelu'(u) (du may alias dg) */
 int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *stream);
 int hmy_k_gelu_bwd(int32_t prec, const void *dg, const void *u, void *du, uint64_t n, void *stream);
+/* the same on a [T,N] matrix, with db[N] += column sums of du as stored (the gradient of the
+ * bias in front of the activation), so that du is not read again for them */
+int hmy_k_gelu_bwd_colsum(int32_t prec, const void *dg, const void *u, void *du, float *db,
+                          int32_t T, int32_t N, void *stream);
 /* out[N] += column sums of a[T,N]  (fp32 accumulators; bias gradients) */
 int hmy_k_colsum(int32_t prec, const void *a, float *out, int32_t T, int32_t N, void *stream);
 

@@ -129,16 +129,20 @@ def main() -> int:
     timed("layernorm forward", [(lambda i=i: B.hmy_k_layernorm_fwd(pc, x[i], gam, bet, y, mean, rstd, T, d, synth.LN_EPS)) for i in range(n)],
           T * d * (4.0 + 2.0), "GB/s")
     dgm, dbt = torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda")
-    ws = torch.empty(256 * 2 * d, device="cuda")
+    ws = torch.empty(256 * 3 * d, device="cuda")
     dx32 = torch.empty(T, d, device="cuda")
-    timed("layernorm backward (+ partial-sum reduce)",
+    dbias = torch.zeros(d, device="cuda")
+    timed("layernorm backward (+ bias gradient, + partial-sum reduce)",
           [(lambda i=i: B.hmy_k_layernorm_bwd(pc, dy[i], x[i], mean, rstd, gam, x[(i + 1) % n], dx32, dgm, dbt, T, d, workspace=ws,
-                                              dx_e=y))
+                                              dx_e=y, dres_sum=dbias))
            for i in range(n)], T * d * (2.0 + 4 + 4 + 4 + 2), "GB/s")     # dy, x, res in; dx (fp32) and its bf16 copy out
     u = [rnd(T, f) for _ in range(n)]
     dg = [rnd(T, f) for _ in range(n)]
     du = torch.empty(T, f, device="cuda", dtype=dt)
     timed("gelu backward", [(lambda i=i: B.hmy_k_gelu_bwd(pc, dg[i], u[i], du, T * f)) for i in range(n)], 3.0 * T * f * 2, "GB/s")
+    db1 = torch.zeros(f, device="cuda")
+    timed("gelu backward + bias gradient", [(lambda i=i: B.hmy_k_gelu_bwd_colsum(pc, dg[i], u[i], du, db1, T, f)) for i in range(n)],
+          3.0 * T * f * 2, "GB/s")
     for N in (d, 3 * d, f):
         out = torch.zeros(N, device="cuda")
         src = u if N == f else [rnd(T, N) for _ in range(n)]

@@ -149,7 +149,7 @@ EXPORTS = [
     "hmy_arena_regions", "hmy_measure_profile",
     "hmy_count_swaps", "hmy_host_alloc", "hmy_host_free", "hmy_create", "hmy_get_schedule", "hmy_bind_state", "hmy_resident_params", "hmy_sync_state",
     "hmy_iteration", "hmy_destroy", "hmy_set_profiling", "hmy_set_progress", "hmy_set_kernel_path", "hmy_k_embed_fwd", "hmy_k_embed_bwd",
-    "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_layernorm_bwd_static", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_colsum",
+    "hmy_k_layernorm_fwd", "hmy_k_layernorm_bwd", "hmy_k_layernorm_bwd_static", "hmy_k_gelu_fwd", "hmy_k_gelu_bwd", "hmy_k_gelu_bwd_colsum", "hmy_k_colsum",
     "hmy_k_gemm", "hmy_k_attn_fwd", "hmy_k_attn_bwd", "hmy_k_xent", "hmy_k_adam", "hmy_host_adam",
 ]
 
@@ -384,11 +384,13 @@ def hmy_k_layernorm_fwd(prec, x, gamma, beta, y, mean, rstd, T, d, eps, stream=N
 
 
 def hmy_k_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None, workspace=None,
-                        dx_e=None):
-    """x, res, dx: fp32 (the residual stream); dy, gamma: element type; dx_e: optional element-typed copy of dx."""
+                        dx_e=None, dres_sum=None):
+    """x, res, dx: fp32 (the residual stream); dy, gamma: element type; dx_e: optional element-typed copy of dx;
+    dres_sum: optional fp32 [d], += column sums of res."""
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib.hmy_k_layernorm_bwd(prec, _p(dy), _p(x), _p(mean), _p(rstd), _p(gamma), _p(res), _p(dx), _p(dx_e),
-                                   _p(dgamma), _p(dbeta), T, d, _p(stream), _p(workspace), C.c_uint64(ws_bytes)))
+                                   _p(dgamma), _p(dbeta), _p(dres_sum), T, d, _p(stream), _p(workspace),
+                                   C.c_uint64(ws_bytes)))
 
 
 def hmy_k_layernorm_bwd_static(prec, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, T, d, stream=None, dx_e=None):
@@ -402,6 +404,10 @@ def hmy_k_gelu_fwd(prec, u, g, n, stream=None):
 
 def hmy_k_gelu_bwd(prec, dg, u, du, n, stream=None):
     _check(lib.hmy_k_gelu_bwd(prec, _p(dg), _p(u), _p(du), C.c_uint64(n), _p(stream)))
+
+
+def hmy_k_gelu_bwd_colsum(prec, dg, u, du, db, T, N, stream=None):
+    _check(lib.hmy_k_gelu_bwd_colsum(prec, _p(dg), _p(u), _p(du), _p(db), T, N, _p(stream)))
 
 
 def hmy_k_colsum(prec, a, out, T, N, stream=None):

@@ -207,11 +207,11 @@ int hmy_k_layernorm_fwd(int32_t prec, const float *x, const void *gamma, const v
   return launch_layernorm_fwd(prec, x, gamma, beta, y, mean, rstd, T, d, eps, stream);
 }
 int hmy_k_layernorm_bwd(int32_t prec, const void *dy, const float *x, const float *mean, const float *rstd,
-                        const void *gamma, const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta, int32_t T,
-                        int32_t d, void *stream, float *workspace, uint64_t workspace_bytes) {
+                        const void *gamma, const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta,
+                        float *dres_sum, int32_t T, int32_t d, void *stream, float *workspace, uint64_t workspace_bytes) {
   NOTNULL(dy); NOTNULL(x); NOTNULL(mean); NOTNULL(rstd); NOTNULL(gamma); NOTNULL(dx); NOTNULL(dgamma); NOTNULL(dbeta);
-  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, stream, workspace,
-                              workspace_bytes);
+  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, dres_sum, T, d, stream,
+                              workspace, workspace_bytes);
 }
 int hmy_k_layernorm_bwd_static(int32_t prec, const void *dy, const float *x, const float *mean, const float *rstd,
                                const void *gamma, const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta,
@@ -226,6 +226,11 @@ int hmy_k_gelu_fwd(int32_t prec, const void *u, void *g, uint64_t n, void *strea
 int hmy_k_gelu_bwd(int32_t prec, const void *dg, const void *u, void *du, uint64_t n, void *stream) {
   NOTNULL(dg); NOTNULL(u); NOTNULL(du);
   return launch_gelu_bwd(prec, dg, u, du, n, stream);
+}
+int hmy_k_gelu_bwd_colsum(int32_t prec, const void *dg, const void *u, void *du, float *db, int32_t T, int32_t N,
+                          void *stream) {
+  NOTNULL(dg); NOTNULL(u); NOTNULL(du); NOTNULL(db);
+  return launch_gelu_bwd_colsum(prec, dg, u, du, db, T, N, stream);
 }
 int hmy_k_colsum(int32_t prec, const void *a, float *out, int32_t T, int32_t N, void *stream) {
   NOTNULL(a); NOTNULL(out);

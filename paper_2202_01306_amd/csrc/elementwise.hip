@@ -354,12 +354,64 @@ __global__ void k_gelu_bwd(const E *dg, const E *u, E *du, uint64_t nvec) {
   }
 }
 
+// The same with the column sums of du (the gradient of the bias in front of the activation) added into
+// `db`: grid and reduction of k_colsum, so that du is not read again by a kernel of its own.  The sums are
+// taken over du as stored (rounded to E), which is what that kernel would have read.
+template <typename E>
+__global__ void k_gelu_bwd_colsum(const E *dg, const E *u, E *du, float *db, int T, int N, int rows_per_split) {
+  constexpr int VEC = ElemTraits<E>::VEC;
+  __shared__ float part[kWavesPerBlock][kWave * VEC];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int c = (blockIdx.x * kWave + lane) * VEC;
+  const int r0 = blockIdx.y * rows_per_split, r1 = min(T, r0 + rows_per_split);
+  float acc[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) acc[k] = 0.f;
+  if (c < N) {
+    auto one = [&](const Vec16<E> &a, const Vec16<E> &b, int r) {
+      Vec16<E> o;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        o.v[k] = from_f32<E>(to_f32(b.v[k]) * gelu_grad_f(to_f32(a.v[k])));
+        acc[k] += to_f32(o.v[k]);
+      }
+      store16(du + uint64_t(r) * N + c, o);
+    };
+    int r = r0 + wave;
+    for (; r + kWavesPerBlock < r1; r += 2 * kWavesPerBlock) {   // two rows in flight
+      const uint64_t i0 = uint64_t(r) * N + c, i1 = uint64_t(r + kWavesPerBlock) * N + c;
+      const Vec16<E> a0 = load16(u + i0), b0 = load16(dg + i0), a1 = load16(u + i1), b1 = load16(dg + i1);
+      one(a0, b0, r);
+      one(a1, b1, r + kWavesPerBlock);
+    }
+    for (; r < r1; r += kWavesPerBlock) {
+      const uint64_t i0 = uint64_t(r) * N + c;
+      one(load16(u + i0), load16(dg + i0), r);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) part[wave][lane * VEC + k] = acc[k];
+  __syncthreads();
+  for (int i = threadIdx.x; i < kWave * VEC; i += blockDim.x) {
+    const int col = blockIdx.x * kWave * VEC + i;
+    if (col < N) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) t += part[w][i];
+      atomicAdd(db + col, t);
+    }
+  }
+}
+
 // LayerNorm backward for rows of at most 64 * VEC * NJ elements: lane l owns columns
 // VEC * (l + 64 j) .. + VEC - 1, j < NJ, and keeps their dgamma / dbeta partial sums in
 // registers over all the rows its wave visits; one pass over x and dy (kept in
 // registers between the two phases).  Each wave then writes its sums to its own row of
 // LDS, the workgroup adds the rows up, and one row per workgroup goes to the workspace
-// (or, without one, into dgamma / dbeta with atomics).
+// (or, without one, into dgamma / dbeta with atomics).  With `dres` the column sums of `res` are
+// taken along in the same way (ns = 3 sums per column instead of 2): `res` is the gradient that arrives
+// over the residual connection, i.e. the gradient of the output of the linear layer that closes the
+// branch, and its column sums are the gradient of that layer's bias.
 template <typename E, int NJ>
 // one workgroup of 16 / 8 / 4 waves per compute unit (its LDS rows allow no more), i.e. 4 / 2 / 1 waves per
 // SIMD: the bounds tell the compiler that it may use 128 / 256 / 512 registers; left to itself it aimed at 64
@@ -367,18 +419,20 @@ template <typename E, int NJ>
 __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
     __attribute__((amdgpu_waves_per_eu(1, NJ <= 1 ? 4 : NJ <= 4 ? 2 : 1))) void k_layernorm_bwd_reg(const E *dy, const float *x, const float *mean, const float *rstd,
                                                           const E *gamma, const float *res, float *dx, E *dx_e, float *dgamma, float *dbeta,
-                                                          int T, int d, float *partial) {
+                                                          float *dres, int T, int d, float *partial) {
   constexpr int VEC = ElemTraits<E>::VEC;
-  extern __shared__ __align__(16) float lds[];   // per wave: dgamma[d], dbeta[d]
+  extern __shared__ __align__(16) float lds[];   // per wave: dgamma[d], dbeta[d] (, dres[d])
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
-  float dg[NJ][VEC], db[NJ][VEC];
+  const bool sum_res = dres != nullptr;
+  const int ns = sum_res ? 3 : 2;
+  float dg[NJ][VEC], db[NJ][VEC], dr[NJ][VEC];
   Vec16<E> gm[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int c = VEC * (lane + kWave * j);
     if (c < d) gm[j] = load16(gamma + c);
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) dg[j][k] = db[j][k] = 0.f;
+    for (int k = 0; k < VEC; ++k) dg[j][k] = db[j][k] = dr[j][k] = 0.f;
   }
   for (int row = blockIdx.x * waves + wave; row < T; row += gridDim.x * waves) {
     const float *xr = x + uint64_t(row) * d;
@@ -428,6 +482,7 @@ __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
           const float dxh = to_f32(gv[j].v[k]) * to_f32(gm[j].v[k]);
           float v = (dxh - s1 - xv[j][k] * s2) * rs;
           if (rr) v += rv[k];
+          if (sum_res) dr[j][k] += rv[k];
           o[k] = v;
           oe.v[k] = from_f32<E>(v);
         }
@@ -436,7 +491,7 @@ __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
       }
     }
   }
-  float *mine = lds + uint64_t(wave) * 2 * d;
+  float *mine = lds + uint64_t(wave) * ns * d;
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int c = VEC * (lane + kWave * j);
@@ -446,43 +501,48 @@ __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
       for (int k = 0; k < VEC; k += 4) {
         *reinterpret_cast<float4 *>(mine + c + k) = make_float4(dg[j][k], dg[j][k + 1], dg[j][k + 2], dg[j][k + 3]);
         *reinterpret_cast<float4 *>(mine + d + c + k) = make_float4(db[j][k], db[j][k + 1], db[j][k + 2], db[j][k + 3]);
+        if (sum_res)
+          *reinterpret_cast<float4 *>(mine + 2 * d + c + k) = make_float4(dr[j][k], dr[j][k + 1], dr[j][k + 2], dr[j][k + 3]);
       }
     }
   }
   __syncthreads();
-  float *row = partial ? partial + uint64_t(blockIdx.x) * 2 * d : nullptr;
-  for (int c = threadIdx.x; c < 2 * d; c += blockDim.x) {
+  float *row = partial ? partial + uint64_t(blockIdx.x) * ns * d : nullptr;
+  for (int c = threadIdx.x; c < ns * d; c += blockDim.x) {
     float t = 0.f;
-    for (int w = 0; w < waves; ++w) t += lds[uint64_t(w) * 2 * d + c];
+    for (int w = 0; w < waves; ++w) t += lds[uint64_t(w) * ns * d + c];
     if (row) row[c] = t;   // one row of sums per workgroup; k_ln_bwd_reduce adds them up
-    else atomicAdd(c < d ? &dgamma[c] : &dbeta[c - d], t);
+    else atomicAdd(c < d ? &dgamma[c] : c < 2 * d ? &dbeta[c - d] : &dres[c - 2 * d], t);
   }
 }
 
-// dgamma += column sums of partial[:, 0:d], dbeta += those of partial[:, d:2d].  The
-// launches that accumulate into one tensor are ordered on their stream, so plain adds do.
-__global__ void k_ln_bwd_reduce(const float *partial, int rows, int d, float *dgamma, float *dbeta) {
+// dgamma += column sums of partial[:, 0:d], dbeta += those of partial[:, d:2d] and, with rows of 3 d sums,
+// dres += those of partial[:, 2d:3d].  The launches that accumulate into one tensor are ordered on their
+// stream, so plain adds do.
+__global__ void k_ln_bwd_reduce(const float *partial, int rows, int d, int ns, float *dgamma, float *dbeta, float *dres) {
   __shared__ float part[4][64];
   const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;   // 64 columns x 4 interleaved row groups
   const int c = blockIdx.x * 64 + tx;
+  const int w = ns * d;   // floats per row of partial sums
   float t = 0.f;
-  if (c < 2 * d) {
+  if (c < w) {
     int r = ty;
     for (; r + 28 < rows; r += 32) {
       float v[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) v[q] = partial[uint64_t(r + 4 * q) * 2 * d + c];
+      for (int q = 0; q < 8; ++q) v[q] = partial[uint64_t(r + 4 * q) * w + c];
 #pragma unroll
       for (int q = 0; q < 8; ++q) t += v[q];
     }
-    for (; r < rows; r += 4) t += partial[uint64_t(r) * 2 * d + c];
+    for (; r < rows; r += 4) t += partial[uint64_t(r) * w + c];
   }
   part[ty][tx] = t;
   __syncthreads();
-  if (ty == 0 && c < 2 * d) {
+  if (ty == 0 && c < w) {
     t = part[0][tx] + part[1][tx] + part[2][tx] + part[3][tx];
     if (c < d) dgamma[c] += t;
-    else dbeta[c - d] += t;
+    else if (c < 2 * d) dbeta[c - d] += t;
+    else dres[c - 2 * d] += t;
   }
 }
 
@@ -826,36 +886,45 @@ int launch_layernorm_fwd(int prec, const float *x, const void *gamma, const void
 }
 template <typename E>
 void launch_ln_bwd(const E *dy, const float *x, const float *mean, const float *rstd, const E *gamma, const float *res,
-                   float *dx, E *dx_e, float *dgamma, float *dbeta, int T, int d, hipStream_t st, float *ws,
+                   float *dx, E *dx_e, float *dgamma, float *dbeta, float *dres, int T, int d, hipStream_t st, float *ws,
                    uint64_t ws_bytes) {
   constexpr int VEC = ElemTraits<E>::VEC;
   const int nj = (d + kWave * VEC - 1) / (kWave * VEC);
+  const int ns = dres ? 3 : 2;   // sums per column
   // waves per workgroup: as many as 128 KiB of LDS holds rows of 2 d floats, and as the registers allow
   // without spilling (16 for rows of one 16-byte vector per lane, 8 up to four vectors, 4 beyond; measured
   // at d = 1024 bf16: 16 waves with spills 22 us, 8 waves 15 us, 4 waves 20 us)
   int waves = 16;
-  while (waves > 1 && (uint64_t(waves) * 2 * d * 4 > (128u << 10) || (nj > 1 && waves > 8) || (nj > 4 && waves > 4)))
+  while (waves > 1 && (uint64_t(waves) * ns * d * 4 > (128u << 10) || (nj > 1 && waves > 8) || (nj > 4 && waves > 4)))
     waves /= 2;   // also the kernels' launch bounds
   const int grid = grid_for(T, waves, kLnBlocks);
-  float *partial = ws && ws_bytes >= uint64_t(grid) * 2 * d * 4 && nj <= 8 ? ws : nullptr;
-  const size_t lds = size_t(waves) * 2 * d * 4;
+  float *partial = ws && ws_bytes >= uint64_t(grid) * ns * d * 4 && nj <= 8 ? ws : nullptr;
+  const size_t lds = size_t(waves) * ns * d * 4;
   const dim3 g(grid), b(waves * kWave);
-  if (nj == 1) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 1>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, partial);
-  else if (nj == 2) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 2>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, partial);
-  else if (nj <= 4) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 4>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, partial);
-  else if (nj <= 8) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 8>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, partial);
+  if (nj == 1) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 1>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, dres, T, d, partial);
+  else if (nj == 2) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 2>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, dres, T, d, partial);
+  else if (nj <= 4) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 4>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, dres, T, d, partial);
+  else if (nj <= 8) hipLaunchKernelGGL((k_layernorm_bwd_reg<E, 8>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, dres, T, d, partial);
   else
     hipLaunchKernelGGL(k_layernorm_bwd<E>, dim3(grid_for(T, kWavesPerBlock, 512)), dim3(kBlock), size_t(2) * d * 4, st, dy, x, mean,
                        rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d);
-  if (partial) hipLaunchKernelGGL(k_ln_bwd_reduce, dim3((2 * d + 63) / 64), dim3(256), 0, st, partial, grid, d, dgamma, dbeta);
+  if (partial)
+    hipLaunchKernelGGL(k_ln_bwd_reduce, dim3((ns * d + 63) / 64), dim3(256), 0, st, partial, grid, d, ns, dgamma, dbeta, dres);
 }
 
 int launch_layernorm_bwd(int prec, const void *dy, const float *x, const float *mean, const float *rstd, const void *gamma,
-                         const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta, int T, int d, stream_t st,
-                         float *workspace, uint64_t workspace_bytes) {
+                         const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta, float *dres_sum, int T,
+                         int d, stream_t st, float *workspace, uint64_t workspace_bytes) {
   if (T < 1 || d % 8 || d > 8192) return fail(HMY_E_INVALID, "layernorm_bwd: bad shape");
+  if (dres_sum && !res) return fail(HMY_E_INVALID, "layernorm_bwd: column sums of a residual gradient that is not given");
   DISPATCH_PREC(prec, {
-    launch_ln_bwd<E>((const E *)dy, x, mean, rstd, (const E *)gamma, res, dx, (E *)dx_e, dgamma, dbeta, T, d,
+    if (dres_sum && d > 8 * kWave * ElemTraits<E>::VEC) {
+      // rows too wide for the register kernel: the sums get a pass of their own, before dx (which may be res) is written
+      const int rc = launch_colsum(HMY_PREC_FP32, res, dres_sum, T, d, st);
+      if (rc != HMY_OK) return rc;
+      dres_sum = nullptr;
+    }
+    launch_ln_bwd<E>((const E *)dy, x, mean, rstd, (const E *)gamma, res, dx, (E *)dx_e, dgamma, dbeta, dres_sum, T, d,
                      (hipStream_t)st, workspace, workspace_bytes);
   });
   return check_launch("layernorm_bwd");
@@ -905,7 +974,7 @@ int launch_layernorm_bwd_static(int prec, const void *dy, const float *x, const 
   if (!ws) return HMY_E_HIP;
   // nothing in the workspace has to start at zero: every workgroup overwrites its whole row before
   // the reduction kernel, ordered behind it on the stream, reads the rows of this launch only
-  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, T, d, st, ws,
+  return launch_layernorm_bwd(prec, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, nullptr, T, d, st, ws,
                               uint64_t(kLnBlocks) * 2 * d * 4);
 }
 
@@ -926,6 +995,20 @@ int launch_gelu_bwd(int prec, const void *dg, const void *u, void *du, uint64_t 
                        (const E *)dg, (const E *)u, (E *)du, nvec);
   });
   return check_launch("gelu_bwd");
+}
+
+int launch_gelu_bwd_colsum(int prec, const void *dg, const void *u, void *du, float *db, int T, int N, stream_t st) {
+  if (T < 1 || N % 8) return fail(HMY_E_INVALID, "gelu_bwd_colsum: bad shape");
+  DISPATCH_PREC(prec, {
+    const int cols_per_block = kWave * ElemTraits<E>::VEC;
+    const int gx = (N + cols_per_block - 1) / cols_per_block;
+    int splits = std::max(1, std::min(T / 16, 2048 / gx));
+    const int rows_per_split = (T + splits - 1) / splits;
+    splits = (T + rows_per_split - 1) / rows_per_split;
+    hipLaunchKernelGGL(k_gelu_bwd_colsum<E>, dim3(gx, splits), dim3(kBlock), 0, (hipStream_t)st, (const E *)dg,
+                       (const E *)u, (E *)du, db, T, N, rows_per_split);
+  });
+  return check_launch("gelu_bwd_colsum");
 }
 
 int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st) {

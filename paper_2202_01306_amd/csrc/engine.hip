@@ -343,20 +343,23 @@ void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer
   char *dlow = h->base + h->arena.res.dlow;
   float *delta = (float *)(h->base + h->arena.res.delta);
   float *ln_ws = (float *)(h->base + h->arena.res.ln_ws);
-  const uint64_t ln_ws_bytes = uint64_t(kLnBlocks) * 2 * d * 4;
+  const uint64_t ln_ws_bytes = uint64_t(kLnBlocks) * 3 * d * 4;
+  // Three of the four bias gradients (column sums of a linear layer's output gradient) are taken by the kernel that
+  // has that gradient in its registers anyway: b2's and bo's by the LayerNorm backward that reads the gradient
+  // stream D as its residual input (from the fp32 values), b1's by the GELU backward that produces du.
   // y = x_mid + W2 gelu(W1 LN2(x_mid) + b1) + b2
-  linear_bwd(h, dlow, A.g, W(W2), gbig, G(W2), G(B2), T, d, f);                  // dg
-  KCHK(h, launch_gelu_bwd(prec, gbig, A.u, gbig, uint64_t(T) * f, h->s_comp));   // du
-  linear_bwd(h, gbig, A.hh, W(W1), gsmall, G(W1), G(B1), T, f, d);               // dh
+  linear_bwd(h, dlow, A.g, W(W2), gbig, G(W2), nullptr, T, d, f);                // dg
+  KCHK(h, launch_gelu_bwd_colsum(prec, gbig, A.u, gbig, G(B1), T, f, h->s_comp));   // du, db1
+  linear_bwd(h, gbig, A.hh, W(W1), gsmall, G(W1), nullptr, T, f, d);             // dh
   KCHK(h, launch_layernorm_bwd(prec, gsmall, A.x_mid, A.ln2_mean, A.ln2_rstd, W(LN2_G), D, D, dlow, G(LN2_G), G(LN2_B),
-                               T, d, h->s_comp, ln_ws, ln_ws_bytes));                                  // D = dx_mid
+                               G(B2), T, d, h->s_comp, ln_ws, ln_ws_bytes));                           // D = dx_mid, db2
   // x_mid = x_in + Wo attn(Wqkv LN1(x_in) + bqkv) + bo
-  linear_bwd(h, dlow, A.o, W(WO), gsmall, G(WO), G(BO), T, d, d);                // do
+  linear_bwd(h, dlow, A.o, W(WO), gsmall, G(WO), nullptr, T, d, d);              // do
   KCHK(h, launch_attn_bwd(prec, A.qkv, A.o, gsmall, A.lse, delta, gbig, h->b, s.seq_len, s.n_heads, d / s.n_heads,
                           s.causal, h->s_comp));                                   // dqkv
   linear_bwd(h, gbig, A.a, W(WQKV), gsmall, G(WQKV), G(BQKV), T, 3 * d, d);      // da
-  KCHK(h, launch_layernorm_bwd(prec, gsmall, x_in, A.ln1_mean, A.ln1_rstd, W(LN1_G), D, D, dlow, G(LN1_G), G(LN1_B), T,
-                               d, h->s_comp, ln_ws, ln_ws_bytes));                                     // D = dx_in
+  KCHK(h, launch_layernorm_bwd(prec, gsmall, x_in, A.ln1_mean, A.ln1_rstd, W(LN1_G), D, D, dlow, G(LN1_G), G(LN1_B),
+                               G(BO), T, d, h->s_comp, ln_ws, ln_ws_bytes));                           // D = dx_in, dbo
 }
 
 // Final norm, vocabulary projection, loss and their backward.  The fp32 logits exist one chunk of
@@ -409,8 +412,8 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
     run_gemm(h, g);
   }
   KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, h->base + h->arena.res.dlow, g_lnf_g,
-                               g_lnf_b, T, d, h->s_comp, (float *)(h->base + h->arena.res.ln_ws),
-                               uint64_t(kLnBlocks) * 2 * d * 4));
+                               g_lnf_b, nullptr, T, d, h->s_comp, (float *)(h->base + h->arena.res.ln_ws),
+                               uint64_t(kLnBlocks) * 3 * d * 4));
 }
 
 struct PendingUpdate {

@@ -96,7 +96,7 @@ struct Reserved {  // pack-independent arena regions, byte offsets from the aren
   uint64_t delta;     // T_B*H*4
   uint64_t ids, targets;
   uint64_t misc;      // loss accumulators
-  uint64_t ln_ws;     // kLnBlocks x 2 d fp32 partial sums of dgamma, dbeta
+  uint64_t ln_ws;     // kLnBlocks x 3 d fp32 partial sums of dgamma, dbeta and the bias gradient taken along
   uint64_t kring;     // kKRing slots of k_arrays * karr_bytes
   uint64_t karr_bytes;
   uint64_t k_chunk_params;
@@ -147,14 +147,15 @@ int launch_layernorm_fwd(int prec, const float *x, const void *gamma, const void
                          float *mean, float *rstd, int T, int d, float eps, stream_t st);
 int launch_layernorm_bwd(int prec, const void *dy, const float *x, const float *mean,
                          const float *rstd, const void *gamma, const float *res, float *dx, void *dx_e,
-                         float *dgamma, float *dbeta, int T, int d, stream_t st, float *workspace = nullptr,
-                         uint64_t workspace_bytes = 0);
+                         float *dgamma, float *dbeta, float *dres_sum, int T, int d, stream_t st,
+                         float *workspace = nullptr, uint64_t workspace_bytes = 0);
 int launch_layernorm_bwd_static(int prec, const void *dy, const float *x, const float *mean, const float *rstd,
                                 const void *gamma, const float *res, float *dx, void *dx_e, float *dgamma, float *dbeta,
                                 int T, int d, stream_t st);
 int launch_convert_to_f32(int prec, const void *src, float *dst, uint64_t n, stream_t st);
 int launch_gelu_fwd(int prec, const void *u, void *g, uint64_t n, stream_t st);
 int launch_gelu_bwd(int prec, const void *dg, const void *u, void *du, uint64_t n, stream_t st);
+int launch_gelu_bwd_colsum(int prec, const void *dg, const void *u, void *du, float *db, int T, int N, stream_t st);
 int launch_colsum(int prec, const void *a, float *out, int T, int N, stream_t st);
 int launch_gemm(const hmy_gemm_desc &g, stream_t st);
 

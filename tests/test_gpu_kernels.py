@@ -89,6 +89,19 @@ def test_layernorm_fwd_bwd(prec, pc, dt, tol, T, d):
     assert max_rel_err(host(dxd), dxr) < tol
     assert max_rel_err(host(dgd2) - dg0, dgr) < (tol if prec == "bf16" else 2e-5)
     assert max_rel_err(host(dbd2) - db0, dbr) < (tol if prec == "bf16" else 2e-5)
+    # the column sums of the residual gradient taken along (a bias gradient), in place over res, with and
+    # without the workspace; everything else as before
+    for ws in (None, torch.full((256 * 3 * d,), float("nan"), device="cuda")):
+        dgd3, dbd3 = dev(dg0, torch.float32), dev(db0, torch.float32)
+        s0 = rng.standard_normal(d).astype(np.float32)
+        sd, resd = dev(s0, torch.float32), dev(res, torch.float32)
+        B.hmy_k_layernorm_bwd(pc, dev(dy, dt), xd, mean, rstd, gd, resd, resd, dgd3, dbd3, T, d, workspace=ws, dres_sum=sd)
+        assert max_rel_err(host(sd) - s0, res.astype(np.float64).sum(axis=0)) < 1e-5
+        assert max_rel_err(host(resd), dxr + res) < (tol if prec == "bf16" else 2e-5)
+        assert max_rel_err(host(dgd3) - dg0, dgr) < (tol if prec == "bf16" else 2e-5)
+        assert max_rel_err(host(dbd3) - db0, dbr) < (tol if prec == "bf16" else 2e-5)
+    with pytest.raises(B.HmyError):      # sums of a residual that is not there
+        B.hmy_k_layernorm_bwd(pc, dev(dy, dt), xd, mean, rstd, gd, None, dxd, dgd, dbd, T, d, dres_sum=dgd2)
 
 
 @pytest.mark.parametrize("prec,pc,dt,tol", PRECS)
@@ -104,6 +117,24 @@ def test_gelu_fwd_bwd(prec, pc, dt, tol):
     dgd = dev(dg, dt)
     B.hmy_k_gelu_bwd(pc, dgd, ud, dgd, n)     # in place
     assert max_rel_err(host(dgd), om.gelu_bwd(dg.astype(np.float64), u.astype(np.float64))) < (tol if prec == "bf16" else 2e-6)
+
+
+@pytest.mark.parametrize("prec,pc,dt,tol", PRECS)
+@pytest.mark.parametrize("T,N", [(3, 8), (257, 3072), (1000, 136), (4096, 4096)])
+def test_gelu_bwd_with_column_sums(prec, pc, dt, tol, T, N):
+    say(f"gelu backward + column sums {prec} {T}x{N}")
+    rng = np.random.default_rng(T * 3 + N)
+    u, dg = rnd(rng, (T, N), prec, 2.5), rnd(rng, (T, N), prec)
+    db0 = rng.standard_normal(N).astype(np.float32)
+    ud, dgd, dbd = dev(u, dt), dev(dg, dt), dev(db0, torch.float32)
+    B.hmy_k_gelu_bwd_colsum(pc, dgd, ud, dgd, dbd, T, N)     # in place, as the engine runs it
+    ref = om.gelu_bwd(dg.astype(np.float64), u.astype(np.float64))
+    assert max_rel_err(host(dgd), ref) < (tol if prec == "bf16" else 2e-6)
+    # the sums are those of the stored values, exactly what a separate pass over du would have added
+    assert max_rel_err(host(dbd) - db0, host(dgd).astype(np.float64).sum(axis=0)) < 1e-5
+    same = dev(dg, dt)
+    B.hmy_k_gelu_bwd(pc, same, ud, same, T * N)
+    assert torch.equal(same, dgd)
 
 
 @pytest.mark.parametrize("prec,pc,dt,tol", PRECS)
