@@ -136,6 +136,10 @@ def main() -> int:
           [(lambda i=i: B.hmy_k_layernorm_bwd(pc, dy[i], x[i], mean, rstd, gam, x[(i + 1) % n], dx32, dgm, dbt, T, d, workspace=ws,
                                               dx_e=y, dres_sum=dbias))
            for i in range(n)], T * d * (2.0 + 4 + 4 + 4 + 2), "GB/s")     # dy, x, res in; dx (fp32) and its bf16 copy out
+    timed("layernorm backward (+ bias gradient), sums by atomics",
+          [(lambda i=i: B.hmy_k_layernorm_bwd(pc, dy[i], x[i], mean, rstd, gam, x[(i + 1) % n], dx32, dgm, dbt, T, d, dx_e=y,
+                                              dres_sum=dbias))
+           for i in range(n)], T * d * (2.0 + 4 + 4 + 4 + 2), "GB/s")
     u = [rnd(T, f) for _ in range(n)]
     dg = [rnd(T, f) for _ in range(n)]
     du = torch.empty(T, f, device="cuda", dtype=dt)

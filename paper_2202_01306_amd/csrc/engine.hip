@@ -342,8 +342,9 @@ void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer
   char *gsmall = h->base + h->arena.res.gsmall;
   char *dlow = h->base + h->arena.res.dlow;
   float *delta = (float *)(h->base + h->arena.res.delta);
-  float *ln_ws = (float *)(h->base + h->arena.res.ln_ws);
-  const uint64_t ln_ws_bytes = uint64_t(kLnBlocks) * 3 * d * 4;
+  // The per-workgroup sums of the LayerNorm backward kernels go into the gradients with atomics, not through a
+  // workspace and a second kernel: alone on the device the two take the same time (19.9 against 20.1 us), but inside
+  // the iteration every small launch costs more than its work (the reduction kernel 11.5 us for 5 us of work).
   // Three of the four bias gradients (column sums of a linear layer's output gradient) are taken by the kernel that
   // has that gradient in its registers anyway: b2's and bo's by the LayerNorm backward that reads the gradient
   // stream D as its residual input (from the fp32 values), b1's by the GELU backward that produces du.
@@ -352,14 +353,14 @@ void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer
   KCHK(h, launch_gelu_bwd_colsum(prec, gbig, A.u, gbig, G(B1), T, f, h->s_comp));   // du, db1
   linear_bwd(h, gbig, A.hh, W(W1), gsmall, G(W1), nullptr, T, f, d);             // dh
   KCHK(h, launch_layernorm_bwd(prec, gsmall, A.x_mid, A.ln2_mean, A.ln2_rstd, W(LN2_G), D, D, dlow, G(LN2_G), G(LN2_B),
-                               G(B2), T, d, h->s_comp, ln_ws, ln_ws_bytes));                           // D = dx_mid, db2
+                               G(B2), T, d, h->s_comp));                                               // D = dx_mid, db2
   // x_mid = x_in + Wo attn(Wqkv LN1(x_in) + bqkv) + bo
   linear_bwd(h, dlow, A.o, W(WO), gsmall, G(WO), nullptr, T, d, d);              // do
   KCHK(h, launch_attn_bwd(prec, A.qkv, A.o, gsmall, A.lse, delta, gbig, h->b, s.seq_len, s.n_heads, d / s.n_heads,
                           s.causal, h->s_comp));                                   // dqkv
   linear_bwd(h, gbig, A.a, W(WQKV), gsmall, G(WQKV), G(BQKV), T, 3 * d, d);      // da
   KCHK(h, launch_layernorm_bwd(prec, gsmall, x_in, A.ln1_mean, A.ln1_rstd, W(LN1_G), D, D, dlow, G(LN1_G), G(LN1_B),
-                               G(BO), T, d, h->s_comp, ln_ws, ln_ws_bytes));                           // D = dx_in, dbo
+                               G(BO), T, d, h->s_comp));                                               // D = dx_in, dbo
 }
 
 // Final norm, vocabulary projection, loss and their backward.  The fp32 logits exist one chunk of
@@ -412,8 +413,7 @@ void head_forward_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, in
     run_gemm(h, g);
   }
   KCHK(h, launch_layernorm_bwd(prec, dz, x_in, mean, rstd, lnf_g, nullptr, D, h->base + h->arena.res.dlow, g_lnf_g,
-                               g_lnf_b, nullptr, T, d, h->s_comp, (float *)(h->base + h->arena.res.ln_ws),
-                               uint64_t(kLnBlocks) * 3 * d * 4));
+                               g_lnf_b, nullptr, T, d, h->s_comp));
 }
 
 struct PendingUpdate {
@@ -1006,7 +1006,8 @@ int hmy::run_measure_profile(const Model &m, int micro_batch, int hip_device, in
   h.device = hip_device;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   // what runs beside the layers in an iteration: weights and optimizer state arriving (copy engine), results
-  // leaving (the throttled host-writing kernel); one staging buffer on each side
+  // leaving (the update kernel that writes to the host, launched as it is beside the compute stream: how much it
+  // slows other kernels goes with the rate it reaches); one staging buffer on each side
   constexpr uint64_t kLoadBytes = 64ull << 20;
   char *load_host = nullptr, *load_dev = nullptr;
   HIPCHK(&h, hipSetDevice(hip_device));
@@ -1025,7 +1026,19 @@ int hmy::run_measure_profile(const Model &m, int micro_batch, int hip_device, in
     KCHK(&h, launch_fill_zero(h.base + h.arena.res.ids, uint64_t(micro_batch) * s1.seq_len * 4, h.s_comp));
     KCHK(&h, launch_fill_zero(h.base + h.arena.res.targets, uint64_t(micro_batch) * s1.seq_len * 4, h.s_comp));
     KCHK(&h, launch_fill_zero(h.base + h.arena.res.misc, 4096, h.s_comp));
+    KCHK(&h, launch_fill_zero(load_dev + kLoadBytes, kLoadBytes, h.s_comp));   // the update kernel's inputs: all zero
   }
+  // as many parameters per update launch as both staging buffers hold: 16 bytes each in, at most 20 out
+  const uint64_t upd_n = (kLoadBytes / 20) & ~uint64_t(255);
+  const bool mixed = s1.precision == HMY_PREC_BF16;
+  hmy_adam upd_hp;
+  upd_hp.lr = 1e-4f; upd_hp.beta1 = 0.9f; upd_hp.beta2 = 0.999f; upd_hp.eps = 1e-8f; upd_hp.step = 1;
+  auto update_out = [&]() {
+    const float *in = reinterpret_cast<const float *>(load_dev + kLoadBytes);
+    float *outp = reinterpret_cast<float *>(load_host + kLoadBytes);
+    return launch_adam_out(s1.precision, in, in + upd_n, in + 2 * upd_n, in + 3 * upd_n, mixed ? outp : nullptr,
+                           outp + upd_n, outp + 2 * upd_n, outp + 4 * upd_n, outp + 3 * upd_n, upd_n, upd_hp, false, h.s_out);
+  };
   IterState it;
   it.inv_ntgt = 1.0f / float(uint64_t(micro_batch) * s1.seq_len);
   auto timed = [&](const Visit &v, uint64_t *beside_ns) -> uint64_t {
@@ -1052,7 +1065,7 @@ int hmy::run_measure_profile(const Model &m, int micro_batch, int hip_device, in
       // (each of these queues holds at most a few hundred operations of 64 MiB)
       for (int c = 0; c < n_copies; ++c) {
         HIPCHK(&h, hipMemcpyAsync(load_dev, load_host, kLoadBytes, hipMemcpyHostToDevice, h.s_in));
-        if (v.bwd) KCHK(&h, launch_copy_out(load_host + kLoadBytes, load_dev + kLoadBytes, kLoadBytes, h.s_out));
+        if (v.bwd) KCHK(&h, update_out());
       }
     }
     const double beside_ms = run(reps) / reps;

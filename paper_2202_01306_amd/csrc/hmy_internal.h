@@ -96,7 +96,6 @@ struct Reserved {  // pack-independent arena regions, byte offsets from the aren
   uint64_t delta;     // T_B*H*4
   uint64_t ids, targets;
   uint64_t misc;      // loss accumulators
-  uint64_t ln_ws;     // kLnBlocks x 3 d fp32 partial sums of dgamma, dbeta and the bias gradient taken along
   uint64_t kring;     // kKRing slots of k_arrays * karr_bytes
   uint64_t karr_bytes;
   uint64_t k_chunk_params;

@@ -112,7 +112,6 @@ Reserved reserved_layout(const Model &m, const Split &sp) {
   r.ids = take(Tall * 4);
   r.targets = take(Tall * 4);
   r.misc = take(4096);
-  r.ln_ws = take(uint64_t(kLnBlocks) * 3 * d * 4);
   uint64_t maxp = 0;
   for (int l = 0; l < m.R; ++l) maxp = std::max(maxp, m.params_in(l, l + 1));
   r.k_chunk_params = std::min<uint64_t>(kKChunkMax, maxp);
@@ -232,7 +231,6 @@ std::vector<Region> arena_regions(const Model &m, const Arena &a, const Split &s
   v.push_back({"ids", r.ids, Tall * 4});
   v.push_back({"targets", r.targets, Tall * 4});
   v.push_back({"misc", r.misc, 4096});
-  v.push_back({"ln_ws", r.ln_ws, uint64_t(kLnBlocks) * 3 * d * 4});
   v.push_back({"kring", r.kring, uint64_t(kKRing) * m.k_arrays() * r.karr_bytes});
   for (int i = 0; i < a.slots; ++i) v.push_back({"slot" + std::to_string(i), a.slot_off[i], a.slot_bytes});
   v.push_back({"acts", a.act_off, a.act_bytes});

@@ -207,7 +207,6 @@ def _needs(cfg, sched_info):
             "delta": TB * H * 4,
             "ids": D * s_ * 4, "targets": D * s_ * 4,
             "misc": 8,                           # the fp64 loss accumulator
-            "ln_ws": 2 * d * 4,
             "kring": 2 * (3 if E == 2 else 2) * 4 * 1}
 
 
