@@ -44,13 +44,13 @@ def attention_flops(cfg, packs) -> float:
 # dispatch, averaged per kernel and grid) from two `rocprofv3 --pmc` runs over `bench.py --counters`, i.e. over the
 # launches of a real iteration.  Copied from profiles/gpt2m_forward_gemm_hbm_traffic.md, which has the commands; kept
 # here because counters cannot be collected inside the timed run itself.  FETCH_SIZE is scaled by 2.0 and
-# WRITE_SIZE by 1.0: what the same counters read for a streaming kernel of known size (k_gelu_bwd, 64 MiB in /
-# 32 MiB out).
+# WRITE_SIZE by 1.0: what the same counters read for a streaming kernel of known size (k_gelu_bwd_colsum, 64 MiB in /
+# 32 MiB plus 4 MiB of atomic additions out).
 GPT2M_FWD_GEMM_TRAFFIC = [   # (what, kernel, grid threads, dispatches, FETCH_SIZE KiB as counted, WRITE_SIZE KiB)
     ("ffn1", "k_gemm_dma256<false, false, 4>", 131072, 368, 24813.5, 49864.3),
     ("qkv", "k_gemm_dma256<false, false, 4>", 98304, 368, 20713.5, 24576.0),
-    ("logits, 512-row chunk", "k_gemm_dma256<false, false, 4>", 201728, 64, 60230.4, 100542.5),
-    ("out and ffn2", "k_gemm_dma<false, false, 64, 4>", 65536, 672, 37292.1, 16384.0),
+    ("logits, 512-row chunk", "k_gemm_dma256<false, false, 4>", 201728, 64, 60208.6, 100539.9),
+    ("out and ffn2", "k_gemm_dma<false, false, 64, 4>", 65536, 672, 37292.2, 16384.0),
 ]
 
 
