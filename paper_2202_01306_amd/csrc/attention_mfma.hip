@@ -199,46 +199,59 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_fwd_mfma(co
     }
     const bool wave_active = !causal || k0 <= qw + 31;   // some query of this wave sees this tile
     if (wave_active) {
+      // The 32-key subtiles of the tile go through each stage together: their score products are independent chains
+      // of multiplies that overlap, the row maximum and the decision to rescale are taken once over all of them, and
+      // the exponentials of one overlap the multiplies of another.  A subtile that lies wholly past this wave's
+      // queries (second half of a diagonal tile) is carried along fully masked: its probabilities are exact zeros.
+      constexpr int NS = C::TILE / 32;
+      f32x16 st[NS];
 #pragma unroll
-      for (int sub = 0; sub < C::TILE / 32; ++sub) {
+      for (int sub = 0; sub < NS; ++sub) st[sub] = zero16();
+      // S^T[key, query] = K Q^T
+#pragma unroll
+      for (int c = 0; c < C::KSTEPS; ++c)
+#pragma unroll
+        for (int sub = 0; sub < NS; ++sub)
+          st[sub] = mfma(frag_row<DH>(sK[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fq[c], st[sub]);
+#pragma unroll
+      for (int sub = 0; sub < NS; ++sub) {
         const int kb = k0 + 32 * sub;                     // first key of the 32-key subtile
-        if (causal && kb > qw + 31) continue;
-        // S^T[key, query] = K Q^T
-        f32x16 st = zero16();
-#pragma unroll
-        for (int c = 0; c < C::KSTEPS; ++c)
-          st = mfma(frag_row<DH>(sK[cur], 32 * sub + lane % 32, 16 * c + 8 * h2), fq[c], st);
         // keys past the sequence end or (causal) past the query: only the diagonal and
         // the last subtile need the per-element test
         if (kb + 32 > s || (causal && kb + 31 > qw)) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int key = kb + acc_row(r, h2);
-            if (!(key < s && (!causal || key <= q))) st[r] = -INFINITY;
+            if (!(key < s && (!causal || key <= q))) st[sub][r] = -INFINITY;
           }
         }
-        float mx = st[0];
+      }
+      float mx = st[0][0];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, st[r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;     // log2 units (sc > 0)
-        if (__any(mx > m_run + kSlack)) {   // some row outgrew its reference: raise it, rescale what was accumulated
-          const float m_new = fmaxf(m_run, mx);
-          const float corr = m_new == -INFINITY ? 1.f : fast_exp2(m_run - m_new);
-          acc_l[0] *= corr;
+      for (int sub = 0; sub < NS; ++sub)
 #pragma unroll
-          for (int t = 0; t < C::DTILES; ++t)
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[sub][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;     // log2 units (sc > 0)
+      if (__any(mx > m_run + kSlack)) {   // some row outgrew its reference: raise it, rescale what was accumulated
+        const float m_new = fmaxf(m_run, mx);
+        const float corr = m_new == -INFINITY ? 1.f : fast_exp2(m_run - m_new);
+        acc_l[0] *= corr;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[t][r] *= corr;
-          m_run = m_new;
-        }
-        // rows that have seen no key yet keep m = -inf; use 0 as the reference to stay finite
-        const float m_ref = m_run == -INFINITY ? 0.f : m_run;
+        for (int t = 0; t < C::DTILES; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st[r] = fast_exp2(fmaf(st[r], sc, -m_ref));
+          for (int r = 0; r < 16; ++r) acc_o[t][r] *= corr;
+        m_run = m_new;
+      }
+      // rows that have seen no key yet keep m = -inf; use 0 as the reference to stay finite
+      const float m_ref = m_run == -INFINITY ? 0.f : m_run;
+#pragma unroll
+      for (int sub = 0; sub < NS; ++sub) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[sub][r] = fast_exp2(fmaf(st[sub][r], sc, -m_ref));
         // O^T[dh, query] += V^T P^T, and the row sums
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-          const bf16x8 fp = acc_to_frag(st, c);
+          const bf16x8 fp = acc_to_frag(st[sub], c);
 #pragma unroll
           for (int t = 0; t < C::DTILES; ++t)
             acc_o[t] = mfma(frag_col<DH>(sV[cur], 32 * sub + 16 * c, 32 * t, lane), fp, acc_o[t]);
