@@ -511,10 +511,11 @@ int hmy_k_gemm(const hmy_gemm_desc *g, void *stream);
 /* qkv[T,3d] (q|k|v thirds, head h = columns h*dh..) -> o[T,d], lse[b,H,s] fp32 */
 int hmy_k_attn_fwd(int32_t prec, const void *qkv, void *o, float *lse, int32_t b, int32_t s,
                    int32_t H, int32_t dh, int32_t causal, void *stream);
-/* dqkv[T,3d] from do[T,d]; delta[b,H,s] fp32 is scratch */
+/* dqkv[T,3d] from do[T,d]; delta[b,H,s] fp32 is scratch.  dbias (may be NULL): dbias[3d] +=
+ * column sums of dqkv as stored, the gradient of the bias of the projection that produced qkv. */
 int hmy_k_attn_bwd(int32_t prec, const void *qkv, const void *o, const void *d_o, const float *lse,
-                   float *delta, void *dqkv, int32_t b, int32_t s, int32_t H, int32_t dh,
-                   int32_t causal, void *stream);
+                   float *delta, void *dqkv, float *dbias, int32_t b, int32_t s, int32_t H,
+                   int32_t dh, int32_t causal, void *stream);
 /* rows with target>=0: loss_acc[0] += (lse - logit[target]) * inv_ntgt (fp64 atomics); dlogits = (softmax - onehot) * inv_ntgt; other rows: dlogits = 0.
  * logits fp32 [T,V] row stride ldl; dlogits type E, same stride. */
 int hmy_k_xent(int32_t prec, const float *logits, const int32_t *targets, double *loss_acc,

@@ -425,8 +425,8 @@ def hmy_k_attn_fwd(prec, qkv, o, lse, b, s, H, dh, causal, stream=None):
     _check(lib.hmy_k_attn_fwd(prec, _p(qkv), _p(o), _p(lse), b, s, H, dh, int(causal), _p(stream)))
 
 
-def hmy_k_attn_bwd(prec, qkv, o, d_o, lse, delta, dqkv, b, s, H, dh, causal, stream=None):
-    _check(lib.hmy_k_attn_bwd(prec, _p(qkv), _p(o), _p(d_o), _p(lse), _p(delta), _p(dqkv), b, s, H, dh,
+def hmy_k_attn_bwd(prec, qkv, o, d_o, lse, delta, dqkv, b, s, H, dh, causal, stream=None, dbias=None):
+    _check(lib.hmy_k_attn_bwd(prec, _p(qkv), _p(o), _p(d_o), _p(lse), _p(delta), _p(dqkv), _p(dbias), b, s, H, dh,
                               int(causal), _p(stream)))
 
 

@@ -246,9 +246,9 @@ int hmy_k_attn_fwd(int32_t prec, const void *qkv, void *o, float *lse, int32_t b
   return launch_attn_fwd(prec, qkv, o, lse, b, s, H, dh, causal, stream);
 }
 int hmy_k_attn_bwd(int32_t prec, const void *qkv, const void *o, const void *d_o, const float *lse, float *delta,
-                   void *dqkv, int32_t b, int32_t s, int32_t H, int32_t dh, int32_t causal, void *stream) {
+                   void *dqkv, float *dbias, int32_t b, int32_t s, int32_t H, int32_t dh, int32_t causal, void *stream) {
   NOTNULL(qkv); NOTNULL(o); NOTNULL(d_o); NOTNULL(lse); NOTNULL(delta); NOTNULL(dqkv);
-  return launch_attn_bwd(prec, qkv, o, d_o, lse, delta, dqkv, b, s, H, dh, causal, stream);
+  return launch_attn_bwd(prec, qkv, o, d_o, lse, delta, dqkv, dbias, b, s, H, dh, causal, stream);
 }
 int hmy_k_xent(int32_t prec, const float *logits, const int32_t *targets, double *loss_acc, void *dlogits, int32_t T,
                int32_t V, int64_t ldl, float inv_ntgt, void *stream) {

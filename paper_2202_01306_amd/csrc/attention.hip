@@ -287,11 +287,14 @@ int launch_attn_fwd(int prec, const void *qkv, void *o, float *lse, int b, int s
   DISPATCH_ATTN(prec, dh, attn_fwd_t, qkv, o, lse, b, s, H, causal, (hipStream_t)st);
 }
 int launch_attn_bwd(int prec, const void *qkv, const void *o, const void *d_o, const float *lse, float *delta, void *dqkv,
-                    int b, int s, int H, int dh, int causal, stream_t st) {
+                    float *dbias, int b, int s, int H, int dh, int causal, stream_t st) {
   if (b < 1 || s < 1 || H < 1) return fail(HMY_E_INVALID, "attn_bwd: bad shape");
   if (prec == HMY_PREC_BF16 && g_use_mfma)
-    return launch_attn_bwd_mfma(qkv, o, d_o, lse, delta, dqkv, b, s, H, dh, causal, st);
-  DISPATCH_ATTN(prec, dh, attn_bwd_t, qkv, o, d_o, lse, delta, dqkv, b, s, H, causal, (hipStream_t)st);
+    return launch_attn_bwd_mfma(qkv, o, d_o, lse, delta, dqkv, dbias, b, s, H, dh, causal, st);
+  // the plain kernels leave the bias gradient to a pass of its own over dqkv
+  const int rc = [&]() -> int { DISPATCH_ATTN(prec, dh, attn_bwd_t, qkv, o, d_o, lse, delta, dqkv, b, s, H, causal, (hipStream_t)st); }();
+  if (rc != HMY_OK || !dbias) return rc;
+  return launch_colsum(prec, dqkv, dbias, b * s, 3 * H * dh, st);
 }
 
 }  // namespace hmy

@@ -119,6 +119,24 @@ __device__ __forceinline__ bf16x8 acc_to_frag(const f32x16 &a, int c) {
 // tile row (0..31) held in accumulator register r by a lane of half h
 __device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r / 4) + 4 * h + r % 4; }
 
+// db[32 t + 8 j + 4 h + k] += sum over the wave's 32 rows of the values stored from acc[t][4 j + k] (scaled and
+// rounded to bf16 as they are stored; rows that are not stored count as zero): the bias gradient of the QKV
+// projection, taken while the gradient of its output is still in registers.  Lanes of one half-wave hold the same
+// columns of 32 different rows: five exchange steps add them up, lane 0 of the half sends the sum.
+template <int NT>
+__device__ __forceinline__ void bias_grad_sums(float *db, const f32x16 (&acc)[NT], float scale, bool row_stored, int lane) {
+  const int h = lane / 32;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float v = row_stored ? static_cast<float>(static_cast<__bf16>(acc[t][r] * scale)) : 0.f;
+#pragma unroll
+      for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
+      if (lane % 32 == 0) atomicAdd(db + 32 * t + 8 * (r / 4) + 4 * h + r % 4, v);
+    }
+}
+
 // Which 128-row block, head and sequence a workgroup takes (1-D grid of nrb * H * b workgroups).
 // With a causal mask the work of a row block grows with the number of keys (queries) it sees, from 1
 // to nrb units.  Workgroups are handed out in linear order, round-robin over the 8 XCDs, and a launch
@@ -283,35 +301,14 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_fwd_mfma(co
 }
 
 // ---------------------------------------------------------------------------------
-// delta[seq,head,i] = sum_c dO[i,c] * O[i,c]; one wavefront per 64/(DH/8) rows.
-template <int DH>
-__global__ void k_attn_delta_mfma(const bf16_t *o, const bf16_t *d_o, float *delta, int T, int s, int H) {
-  constexpr int LPR = DH / 8;                       // lanes per (row, head)
-  const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int64_t item = gid / LPR;
-  const int part = int(gid % LPR);
-  const bool ok = item < int64_t(T) * H;
-  float acc = 0.f;
-  int t = 0, head = 0;
-  if (ok) {
-    t = int(item / H);
-    head = int(item % H);
-    const int64_t off = int64_t(t) * H * DH + head * DH + part * 8;
-    const Vec16<bf16_t> a = load16(o + off), b = load16(d_o + off);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc = fmaf(to_f32(a.v[k]), to_f32(b.v[k]), acc);
-  }
-#pragma unroll
-  for (int m = LPR / 2; m > 0; m >>= 1) acc += __shfl_xor(acc, m, 64);
-  if (ok && part == 0) delta[(int64_t(t / s) * H + head) * s + t % s] = acc;
-}
-
-// ---------------------------------------------------------------------------------
 // dQ.  grid (ceil(s/128), H, b).  Wave w owns queries q0+32w..; K and V tiles stream.
+// Also delta[seq,head,q] = sum_c dO[q,c] * O[q,c], which this kernel needs per query and the dK/dV kernel, launched
+// behind it, reads per streamed query row: each lane holds half of its query's dO row as multiply operands already, so
+// the sum is 4 DH / 16 multiply-adds and one exchange with the lane that holds the other half, and no kernel of its own.
 template <int DH>
-__global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_bwd_dq_mfma(const bf16_t *qkv, const bf16_t *d_o, const float *lse,
-                                                               const float *delta, bf16_t *dqkv, int s, int H,
-                                                               int causal) {
+__global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_bwd_dq_mfma(const bf16_t *qkv, const bf16_t *o, const bf16_t *d_o,
+                                                               const float *lse, float *delta, bf16_t *dqkv, float *dbias,
+                                                               int s, int H, int causal) {
   typedef Cfg<DH> C;
   __shared__ __attribute__((aligned(16))) bf16_t sK[2][C::TILE * C::PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t sV[2][C::TILE * C::PITCH];
@@ -322,15 +319,21 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_bwd_dq_mfma
   const int head = bc.head, seq = bc.seq, q0 = bc.rb * kBlockRows;
   const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
   const bf16_t *gbase = d_o + int64_t(seq) * s * d + head * DH;
+  const bf16_t *obase = o + int64_t(seq) * s * d + head * DH;
   const int qw = q0 + 32 * wave, q = qw + lane % 32, q_ld = min(q, s - 1);
   bf16x8 fq[C::KSTEPS], fg[C::KSTEPS];
+  float dl = 0.f;
 #pragma unroll
   for (int c = 0; c < C::KSTEPS; ++c) {
     fq[c] = frag_global(base, ld, q_ld, 16 * c + 8 * h2);
     fg[c] = frag_global(gbase, d, q_ld, 16 * c + 8 * h2);
+    const bf16x8 fo = frag_global(obase, d, q_ld, 16 * c + 8 * h2);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) dl = fmaf(static_cast<float>(fg[c][k]), static_cast<float>(fo[k]), dl);
   }
+  dl += __shfl_xor(dl, 32, 64);   // the other half of the row
+  if (h2 == 0 && q < s) delta[(int64_t(seq) * H + head) * s + q] = dl;
   const float L = lse[(int64_t(seq) * H + head) * s + q_ld] * kLog2e;   // log2 units
-  const float dl = delta[(int64_t(seq) * H + head) * s + q_ld];
   const float scale = rsqrtf(float(DH)), sc = scale * kLog2e;
   f32x16 acc_q[C::DTILES];
 #pragma unroll
@@ -402,14 +405,15 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_bwd_dq_mfma
         *reinterpret_cast<bf16x4 *>(row + 32 * t + 8 * j + 4 * h2) = v;
       }
   }
+  if (dbias) bias_grad_sums<C::DTILES>(dbias + head * DH, acc_q, scale, q < s, lane);
 }
 
 // ---------------------------------------------------------------------------------
 // dK, dV.  grid (ceil(s/128), H, b).  Wave w owns keys j0+32w..; Q and dO tiles stream.
 template <int DH>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH == 128 ? 1 : 2))) void k_attn_bwd_dkv_mfma(const bf16_t *qkv, const bf16_t *d_o, const float *lse,
-                                                                const float *delta, bf16_t *dqkv, int s, int H,
-                                                                int causal) {
+                                                                const float *delta, bf16_t *dqkv, float *dbias, int s,
+                                                                int H, int causal) {
   typedef Cfg<DH> C;
   __shared__ __attribute__((aligned(16))) bf16_t sQ[2][C::TILE * C::PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t sG[2][C::TILE * C::PITCH];
@@ -526,6 +530,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH == 
         *reinterpret_cast<bf16x4 *>(row + 2 * d + 32 * t + 8 * j + 4 * h2) = vv;
       }
   }
+  if (dbias) {
+    bias_grad_sums<C::DTILES>(dbias + d + head * DH, acc_k, scale, key < s, lane);
+    bias_grad_sums<C::DTILES>(dbias + 2 * d + head * DH, acc_v, 1.f, key < s, lane);
+  }
 }
 
 inline int check_launch(const char *what) {
@@ -542,17 +550,13 @@ int fwd_t(const void *qkv, void *o, float *lse, int b, int s, int H, int causal,
   return check_launch("attn_fwd_mfma");
 }
 template <int DH>
-int bwd_t(const void *qkv, const void *o, const void *d_o, const float *lse, float *delta, void *dqkv, int b, int s, int H,
-          int causal, hipStream_t st) {
-  const int T = b * s;
-  const int64_t n = int64_t(T) * H * (DH / 8);
-  hipLaunchKernelGGL((k_attn_delta_mfma<DH>), dim3(int((n + 255) / 256)), dim3(256), 0, st, (const bf16_t *)o,
-                     (const bf16_t *)d_o, delta, T, s, H);
+int bwd_t(const void *qkv, const void *o, const void *d_o, const float *lse, float *delta, void *dqkv, float *dbias, int b,
+          int s, int H, int causal, hipStream_t st) {
   const dim3 grid(((s + kBlockRows - 1) / kBlockRows) * H * b);
-  hipLaunchKernelGGL((k_attn_bwd_dq_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
-                     delta, (bf16_t *)dqkv, s, H, causal);
+  hipLaunchKernelGGL((k_attn_bwd_dq_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (const bf16_t *)o,
+                     (const bf16_t *)d_o, lse, delta, (bf16_t *)dqkv, dbias, s, H, causal);   // writes delta for the next kernel
   hipLaunchKernelGGL((k_attn_bwd_dkv_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (const bf16_t *)d_o,
-                     lse, delta, (bf16_t *)dqkv, s, H, causal);
+                     lse, delta, (bf16_t *)dqkv, dbias, s, H, causal);
   return check_launch("attn_bwd_mfma");
 }
 
@@ -565,10 +569,10 @@ int launch_attn_fwd_mfma(const void *qkv, void *o, float *lse, int b, int s, int
   return fail(HMY_E_INVALID, "attention: unsupported head dim %d", dh);
 }
 int launch_attn_bwd_mfma(const void *qkv, const void *o, const void *d_o, const float *lse, float *delta, void *dqkv,
-                         int b, int s, int H, int dh, int causal, stream_t st) {
-  if (dh == 32) return bwd_t<32>(qkv, o, d_o, lse, delta, dqkv, b, s, H, causal, (hipStream_t)st);
-  if (dh == 64) return bwd_t<64>(qkv, o, d_o, lse, delta, dqkv, b, s, H, causal, (hipStream_t)st);
-  if (dh == 128) return bwd_t<128>(qkv, o, d_o, lse, delta, dqkv, b, s, H, causal, (hipStream_t)st);
+                         float *dbias, int b, int s, int H, int dh, int causal, stream_t st) {
+  if (dh == 32) return bwd_t<32>(qkv, o, d_o, lse, delta, dqkv, dbias, b, s, H, causal, (hipStream_t)st);
+  if (dh == 64) return bwd_t<64>(qkv, o, d_o, lse, delta, dqkv, dbias, b, s, H, causal, (hipStream_t)st);
+  if (dh == 128) return bwd_t<128>(qkv, o, d_o, lse, delta, dqkv, dbias, b, s, H, causal, (hipStream_t)st);
   return fail(HMY_E_INVALID, "attention: unsupported head dim %d", dh);
 }
 

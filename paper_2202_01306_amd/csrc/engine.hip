@@ -345,9 +345,10 @@ void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer
   // The per-workgroup sums of the LayerNorm backward kernels go into the gradients with atomics, not through a
   // workspace and a second kernel: alone on the device the two take the same time (19.9 against 20.1 us), but inside
   // the iteration every small launch costs more than its work (the reduction kernel 11.5 us for 5 us of work).
-  // Three of the four bias gradients (column sums of a linear layer's output gradient) are taken by the kernel that
-  // has that gradient in its registers anyway: b2's and bo's by the LayerNorm backward that reads the gradient
-  // stream D as its residual input (from the fp32 values), b1's by the GELU backward that produces du.
+  // The bias gradients (column sums of a linear layer's output gradient) are taken by the kernel that has that
+  // gradient in its registers anyway: b2's and bo's by the LayerNorm backward that reads the gradient stream D as its
+  // residual input (from the fp32 values), b1's by the GELU backward that produces du, bqkv's by the attention
+  // backward kernels that produce dqkv.
   // y = x_mid + W2 gelu(W1 LN2(x_mid) + b1) + b2
   linear_bwd(h, dlow, A.g, W(W2), gbig, G(W2), nullptr, T, d, f);                // dg
   KCHK(h, launch_gelu_bwd_colsum(prec, gbig, A.u, gbig, G(B1), T, f, h->s_comp));   // du, db1
@@ -356,9 +357,9 @@ void block_backward(hmy_handle *h, const Visit &v, const PackPtrs &pp, int layer
                                G(B2), T, d, h->s_comp));                                               // D = dx_mid, db2
   // x_mid = x_in + Wo attn(Wqkv LN1(x_in) + bqkv) + bo
   linear_bwd(h, dlow, A.o, W(WO), gsmall, G(WO), nullptr, T, d, d);              // do
-  KCHK(h, launch_attn_bwd(prec, A.qkv, A.o, gsmall, A.lse, delta, gbig, h->b, s.seq_len, s.n_heads, d / s.n_heads,
-                          s.causal, h->s_comp));                                   // dqkv
-  linear_bwd(h, gbig, A.a, W(WQKV), gsmall, G(WQKV), G(BQKV), T, 3 * d, d);      // da
+  KCHK(h, launch_attn_bwd(prec, A.qkv, A.o, gsmall, A.lse, delta, gbig, G(BQKV), h->b, s.seq_len, s.n_heads,
+                          d / s.n_heads, s.causal, h->s_comp));                    // dqkv, dbqkv
+  linear_bwd(h, gbig, A.a, W(WQKV), gsmall, G(WQKV), nullptr, T, 3 * d, d);      // da
   KCHK(h, launch_layernorm_bwd(prec, gsmall, x_in, A.ln1_mean, A.ln1_rstd, W(LN1_G), D, D, dlow, G(LN1_G), G(LN1_B),
                                G(BO), T, d, h->s_comp));                                               // D = dx_in, dbo
 }

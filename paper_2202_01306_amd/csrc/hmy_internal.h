@@ -164,11 +164,11 @@ int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st);
 int launch_attn_fwd(int prec, const void *qkv, void *o, float *lse, int b, int s, int H, int dh,
                     int causal, stream_t st);
 int launch_attn_bwd(int prec, const void *qkv, const void *o, const void *d_o, const float *lse,
-                    float *delta, void *dqkv, int b, int s, int H, int dh, int causal,
+                    float *delta, void *dqkv, float *dbias, int b, int s, int H, int dh, int causal,
                     stream_t st);
 int launch_attn_fwd_mfma(const void *qkv, void *o, float *lse, int b, int s, int H, int dh, int causal, stream_t st);
 int launch_attn_bwd_mfma(const void *qkv, const void *o, const void *d_o, const float *lse, float *delta, void *dqkv,
-                         int b, int s, int H, int dh, int causal, stream_t st);
+                         float *dbias, int b, int s, int H, int dh, int causal, stream_t st);
 int launch_xent(int prec, const float *logits, const int32_t *targets, double *loss_acc,
                 void *dlogits, int T, int V, int64_t ldl, float inv_ntgt, stream_t st);
 int launch_adam(int prec, const float *grad, float *master, float *m, float *v, void *w_out,

@@ -350,6 +350,18 @@ def _attention_case(prec, pc, dt, tol, causal, b, s, H, dh):
     got = host(dqkv)
     for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
         assert max_rel_err(got[:, sl], ref[:, sl]) < tol, name
+    # once more with the bias gradient of the QKV projection taken along: the column sums of dqkv as stored, added
+    # onto what is there; dqkv and delta as before
+    db0 = rng.standard_normal(3 * d).astype(np.float32)
+    dbd = dev(db0, torch.float32)
+    dqkv2 = torch.full((T, 3 * d), float("nan"), device="cuda", dtype=dt)
+    delta2 = torch.full((b * H * s,), float("nan"), device="cuda")
+    B.hmy_k_attn_bwd(pc, qd, o, dev(do, dt), lse, delta2, dqkv2, b, s, H, dh, causal, dbias=dbd)
+    assert torch.equal(dqkv2, dqkv)
+    assert max_rel_err(host(delta2), host(delta)) < 1e-5
+    assert max_rel_err(host(delta2).reshape(b, H, s), (do.astype(np.float64) * host(o)).reshape(b, s, H, dh).sum(-1).transpose(0, 2, 1)) < 1e-4
+    sums = got.astype(np.float64).sum(axis=0)
+    assert np.abs(host(dbd) - db0 - sums).max() < 1e-4 * max(np.abs(sums).max(), np.abs(db0).max(), 1.0)
 
 
 @pytest.mark.parametrize("prec,pc,dt,tol", PRECS)
