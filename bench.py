@@ -128,7 +128,7 @@ def cpu_baseline(cfg):
     }
 
 
-def measured_profiles(B, spec, sizes, reps=3):
+def measured_profiles(B, spec, sizes, reps=10):
     """The Profiler step (Section 4.2): per-layer times of this library's kernels on the device, one entry per
     microbatch size the planner may consider."""
     return [B.hmy_measure_profile(spec, u, reps=reps) for u in sizes]
