@@ -13,6 +13,10 @@
 // accumulator to operand without leaving registers.
 //
 // qkv is [T, 3d] with q | k | v thirds, head h at columns h*DH..; lse is [b,H,s].
+// HMY_ATTN_SPLIT=0 (read once per process) runs the forward pass at head dimension 64 on the four-wave kernel
+// instead of the eight-wave one, for timing the two against each other.
+#include <cstdlib>
+
 #include "dev_common.h"
 #include "hmy_internal.h"
 
@@ -58,16 +62,16 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // or beyond n_valid are zero.  Two phases, so that the loads of the next tile are in
 // flight while the current one is multiplied: fetch into registers, put into LDS after
 // the compute.
-template <int DH, int ROWS>
+template <int DH, int ROWS, int NT = kThreads>
 struct TileRegs {
   static constexpr int CPR = DH / 8;
-  static constexpr int N = ROWS * CPR / kThreads;
-  static_assert(N >= 1 && ROWS * CPR % kThreads == 0, "tile does not divide over the workgroup");
+  static constexpr int N = ROWS * CPR / NT;
+  static_assert(N >= 1 && ROWS * CPR % NT == 0, "tile does not divide over the workgroup");
   Vec16<bf16_t> v[N];
   __device__ __forceinline__ void fetch(const bf16_t *src, int64_t ld, int n_valid, int tid) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int q = tid + i * kThreads, r = q / CPR, c = (q % CPR) * 8;
+      const int q = tid + i * NT, r = q / CPR, c = (q % CPR) * 8;
       if (r < n_valid) {
         v[i] = load16(src + int64_t(r) * ld + c);
       } else {
@@ -79,7 +83,7 @@ struct TileRegs {
   __device__ __forceinline__ void put(bf16_t *lds, int tid) const {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int q = tid + i * kThreads, r = q / CPR, c = (q % CPR) * 8;
+      const int q = tid + i * NT, r = q / CPR, c = (q % CPR) * 8;
       store16(lds + r * Cfg<DH>::PITCH + c, v[i]);
     }
   }
@@ -297,6 +301,146 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_fwd_mfma(co
         *reinterpret_cast<bf16x4 *>(orow + 32 * t + 8 * j + 4 * h2) = v;
       }
     if (h2 == 0) lse[(int64_t(seq) * H + head) * s + q] = (m_run + log2f(l_tot)) * kLn2;
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Forward for key tiles of two 32-key subtiles (head dimensions up to 64): eight waves per workgroup.  Wave w takes
+// the queries q0 + 32 (w % 4) .. + 31 and, of every key tile, only subtile w / 4: two waves share each group of
+// queries and split its keys, each with a running reference, row sum and output accumulator of its own, which the
+// pair merges through LDS at the end.  The same work in twice as many, half as long chains: the kernel is bound by
+// each wave's serial chain (multiplies, maximum, exponentials, multiplies), and with four waves per SIMD instead of
+// two the vector unit of one wave works while the matrix unit of another does.
+template <int DH>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void k_attn_fwd_mfma_split(const bf16_t *qkv, bf16_t *o, float *lse, int s, int H,
+                                                                                                    int causal) {
+  typedef Cfg<DH> C;
+  static_assert(C::TILE == 64, "two subtiles per key tile");
+  constexpr int NTHR = 512;
+  constexpr int kTileElems = C::TILE * C::PITCH;
+  // K and V tiles, double buffered; afterwards the same bytes carry one wave's state to its partner
+  __shared__ __attribute__((aligned(16))) bf16_t smem[4 * kTileElems];
+  static_assert(4 * kTileElems * 2 >= 4 * 64 * (2 + 16 * C::DTILES) * 4, "the merge needs 2 + 16 DTILES floats per lane of four waves");
+  auto sK = [&](int buf) { return smem + buf * kTileElems; };
+  auto sV = [&](int buf) { return smem + (2 + buf) * kTileElems; };
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
+  const int rg = wave % 4, sub = wave / 4;
+  const int d = H * DH;
+  const int64_t ld = 3 * int64_t(d);
+  const BlockCoord bc = block_coord((s + kBlockRows - 1) / kBlockRows, H, causal, true);
+  const int head = bc.head, seq = bc.seq, q0 = bc.rb * kBlockRows;
+  const bf16_t *base = qkv + int64_t(seq) * s * ld + head * DH;
+  const int qw = q0 + 32 * rg, q = qw + lane % 32, q_ld = min(q, s - 1);
+  bf16x8 fq[C::KSTEPS];
+#pragma unroll
+  for (int c = 0; c < C::KSTEPS; ++c) fq[c] = frag_global(base, ld, q_ld, 16 * c + 8 * h2);
+  f32x16 acc_o[C::DTILES];
+#pragma unroll
+  for (int t = 0; t < C::DTILES; ++t) acc_o[t] = zero16();
+  f32x16 acc_l = zero16();   // row sums from the matrix cores, as in the kernel above
+  bf16x8 ones;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) ones[k] = static_cast<__bf16>(1.f);
+  constexpr float kSlack = 8.f;   // the exponent reference is raised only when a row outgrows it by this much
+  float m_run = -INFINITY;
+  const float sc = rsqrtf(float(DH)) * kLog2e;   // scores in log2 units
+  const int k_end = causal ? min(s, q0 + kBlockRows) : s;
+  const int n_tiles = (k_end + C::TILE - 1) / C::TILE;
+  TileRegs<DH, C::TILE, NTHR> rk, rv;
+  rk.fetch(base + d, ld, min(C::TILE, s), tid);
+  rv.fetch(base + 2 * d, ld, min(C::TILE, s), tid);
+  rk.put(sK(0), tid);
+  rv.put(sV(0), tid);
+  __syncthreads();
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int cur = kt & 1, k0 = kt * C::TILE;
+    const bool more = kt + 1 < n_tiles;
+    if (more) {   // next tile's loads fly during this tile's multiplies
+      const int kn = k0 + C::TILE;
+      rk.fetch(base + d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+      rv.fetch(base + 2 * d + int64_t(kn) * ld, ld, min(C::TILE, s - kn), tid);
+    }
+    const int kb = k0 + 32 * sub;   // first key of this wave's subtile
+    if (kb < s && (!causal || kb <= qw + 31)) {   // some query of this wave sees some key of it
+      // S^T[key, query] = K Q^T
+      f32x16 st = zero16();
+#pragma unroll
+      for (int c = 0; c < C::KSTEPS; ++c)
+        st = mfma(frag_row<DH>(sK(cur), 32 * sub + lane % 32, 16 * c + 8 * h2), fq[c], st);
+      if (kb + 32 > s || (causal && kb + 31 > qw)) {   // ragged or diagonal subtile: per-element test
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kb + acc_row(r, h2);
+          if (!(key < s && (!causal || key <= q))) st[r] = -INFINITY;
+        }
+      }
+      float mx = st[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, st[r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;     // log2 units (sc > 0)
+      if (__any(mx > m_run + kSlack)) {   // some row outgrew its reference: raise it, rescale what was accumulated
+        const float m_new = fmaxf(m_run, mx);
+        const float corr = m_new == -INFINITY ? 1.f : fast_exp2(m_run - m_new);
+        acc_l[0] *= corr;
+#pragma unroll
+        for (int t = 0; t < C::DTILES; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[t][r] *= corr;
+        m_run = m_new;
+      }
+      const float m_ref = m_run == -INFINITY ? 0.f : m_run;   // a row that has seen no key yet
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st[r] = fast_exp2(fmaf(st[r], sc, -m_ref));
+      // O^T[dh, query] += V^T P^T, and the row sums
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16x8 fp = acc_to_frag(st, c);
+#pragma unroll
+        for (int t = 0; t < C::DTILES; ++t)
+          acc_o[t] = mfma(frag_col<DH>(sV(cur), 32 * sub + 16 * c, 32 * t, lane), fp, acc_o[t]);
+        acc_l = mfma(ones, fp, acc_l);
+      }
+    }
+    if (more) {
+      rk.put(sK(cur ^ 1), tid);
+      rv.put(sV(cur ^ 1), tid);
+    }
+    __syncthreads();
+  }
+  // merge the two key subsets of each query: the wave of the second subtile hands over its reference, row sum and
+  // accumulator ([value][lane] floats: conflict-free both ways); the first rescales both to the larger reference
+  constexpr int NV = 2 + 16 * C::DTILES;
+  float *xch = reinterpret_cast<float *>(smem) + rg * (NV * 64);
+  if (sub == 1) {
+    xch[lane] = m_run;
+    xch[64 + lane] = acc_l[0];
+#pragma unroll
+    for (int t = 0; t < C::DTILES; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) xch[(2 + 16 * t + r) * 64 + lane] = acc_o[t][r];
+  }
+  __syncthreads();
+  if (sub == 1) return;
+  const float m_b = xch[lane], l_b = xch[64 + lane];
+  const float m_tot = fmaxf(m_run, m_b);   // finite: the first subtile of the first tile holds key 0, which every query sees
+  const float ca = fast_exp2(m_run - m_tot), cb = m_b == -INFINITY ? 0.f : fast_exp2(m_b - m_tot);
+  const float l_tot = acc_l[0] * ca + l_b * cb;
+  if (q < s) {
+    const float inv = 1.f / l_tot;
+    bf16_t *orow = o + (int64_t(seq) * s + q) * d + head * DH;
+#pragma unroll
+    for (int t = 0; t < C::DTILES; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x4 v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int r = 4 * j + k;
+          v[k] = static_cast<__bf16>((acc_o[t][r] * ca + xch[(2 + 16 * t + r) * 64 + lane] * cb) * inv);
+        }
+        *reinterpret_cast<bf16x4 *>(orow + 32 * t + 8 * j + 4 * h2) = v;
+      }
+    if (h2 == 0) lse[(int64_t(seq) * H + head) * s + q] = (m_tot + log2f(l_tot)) * kLn2;
   }
 }
 
@@ -545,6 +689,14 @@ inline int check_launch(const char *what) {
 template <int DH>
 int fwd_t(const void *qkv, void *o, float *lse, int b, int s, int H, int causal, hipStream_t st) {
   const dim3 grid(((s + kBlockRows - 1) / kBlockRows) * H * b);
+  static const bool split = std::getenv("HMY_ATTN_SPLIT") == nullptr || std::atoi(std::getenv("HMY_ATTN_SPLIT")) != 0;
+  if constexpr (DH == 64) {   // two 32-key subtiles per key tile, and enough 16-byte pieces in a tile for 512 threads
+    if (split) {
+      hipLaunchKernelGGL((k_attn_fwd_mfma_split<DH>), grid, dim3(512), 0, st, (const bf16_t *)qkv, (bf16_t *)o, lse, s, H,
+                         causal);
+      return check_launch("attn_fwd_mfma_split");
+    }
+  }
   hipLaunchKernelGGL((k_attn_fwd_mfma<DH>), grid, dim3(kThreads), 0, st, (const bf16_t *)qkv, (bf16_t *)o, lse, s, H,
                      causal);
   return check_launch("attn_fwd_mfma");
