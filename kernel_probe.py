@@ -120,6 +120,10 @@ def main() -> int:
     timed("attention backward (dQ with delta, dK/dV)",
           [(lambda i=i: B.hmy_k_attn_bwd(pc, qkv[i], o[i], do[i], lse[i], delta, dqkv, b, s, H, dh, causal)) for i in range(n)],
           2.5 * att_flops, "TFLOP/s")
+    dbias = torch.zeros(3 * d, device="cuda")
+    timed("attention backward with the QKV bias gradient",
+          [(lambda i=i: B.hmy_k_attn_bwd(pc, qkv[i], o[i], do[i], lse[i], delta, dqkv, b, s, H, dh, causal, dbias=dbias))
+           for i in range(n)], 2.5 * att_flops, "TFLOP/s")
 
     x = [rnd(T, d, dtype=torch.float32) for _ in range(n)]      # the residual stream is fp32
     dy = [rnd(T, d) for _ in range(n)]

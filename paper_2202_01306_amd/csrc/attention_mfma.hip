@@ -123,22 +123,35 @@ __device__ __forceinline__ bf16x8 acc_to_frag(const f32x16 &a, int c) {
 // tile row (0..31) held in accumulator register r by a lane of half h
 __device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r / 4) + 4 * h + r % 4; }
 
-// db[32 t + 8 j + 4 h + k] += sum over the wave's 32 rows of the values stored from acc[t][4 j + k] (scaled and
-// rounded to bf16 as they are stored; rows that are not stored count as zero): the bias gradient of the QKV
-// projection, taken while the gradient of its output is still in registers.  Lanes of one half-wave hold the same
-// columns of 32 different rows: five exchange steps add them up, lane 0 of the half sends the sum.
+// db[c] += sum over the workgroup's 128 rows of the values stored from the accumulators (scaled and rounded to bf16
+// as they are stored; rows that are not stored count as zero): the bias gradient of the QKV projection, taken while
+// the gradient of its output is still in registers.  acc[t][r] of lane l in wave w belongs to row 32 w + l % 32,
+// column 32 t + 8 (r / 4) + 4 (l / 32) + r % 4.  The values pass through LDS, 64 columns at a time (rows padded to
+// an odd number of floats so that the lanes of a wave, which hold different rows, fall on different banks); every
+// thread then adds up a share of one column, and one atomic per thread leaves the workgroup -- a few wide atomic
+// instructions instead of one narrow one per value and wave.  Every thread of the workgroup must call this.
+constexpr int kBiasCols = 64, kBiasPitch = kBiasCols + 1;
 template <int NT>
-__device__ __forceinline__ void bias_grad_sums(float *db, const f32x16 (&acc)[NT], float scale, bool row_stored, int lane) {
-  const int h = lane / 32;
+__device__ __forceinline__ void bias_grad_sums(float *db, const f32x16 (&acc)[NT], float scale, bool row_stored, float *lds,
+                                               int tid) {
+  const int lane = tid % 64, h = lane / 32, row = 32 * (tid / 64) + lane % 32;
+  constexpr int G = NT < 2 ? NT : 2, W = 32 * G;   // accumulator tiles and columns per pass
 #pragma unroll
-  for (int t = 0; t < NT; ++t)
+  for (int g = 0; g < NT; g += G) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float v = row_stored ? static_cast<float>(static_cast<__bf16>(acc[t][r] * scale)) : 0.f;
+    for (int t = 0; t < G; ++t)
 #pragma unroll
-      for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
-      if (lane % 32 == 0) atomicAdd(db + 32 * t + 8 * (r / 4) + 4 * h + r % 4, v);
-    }
+      for (int r = 0; r < 16; ++r)
+        lds[row * kBiasPitch + 32 * t + 8 * (r / 4) + 4 * h + r % 4] =
+            row_stored ? static_cast<float>(static_cast<__bf16>(acc[g + t][r] * scale)) : 0.f;
+    __syncthreads();
+    const int col = tid % W, part = tid / W;
+    constexpr int kParts = kThreads / W;
+    float sum = 0.f;
+    for (int rr = part; rr < kBlockRows; rr += kParts) sum += lds[rr * kBiasPitch + col];
+    atomicAdd(db + 32 * g + col, sum);
+    __syncthreads();
+  }
 }
 
 // Which 128-row block, head and sequence a workgroup takes (1-D grid of nrb * H * b workgroups).
@@ -456,6 +469,7 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_bwd_dq_mfma
   typedef Cfg<DH> C;
   __shared__ __attribute__((aligned(16))) bf16_t sK[2][C::TILE * C::PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t sV[2][C::TILE * C::PITCH];
+  __shared__ float sB[kBlockRows * kBiasPitch];   // the bias gradient's way through LDS
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
   const int d = H * DH;
   const int64_t ld = 3 * int64_t(d);
@@ -549,7 +563,7 @@ __global__ __launch_bounds__(kThreads) HMY_MFMA_IN_VGPRS void k_attn_bwd_dq_mfma
         *reinterpret_cast<bf16x4 *>(row + 32 * t + 8 * j + 4 * h2) = v;
       }
   }
-  if (dbias) bias_grad_sums<C::DTILES>(dbias + head * DH, acc_q, scale, q < s, lane);
+  if (dbias) bias_grad_sums<C::DTILES>(dbias + head * DH, acc_q, scale, q < s, sB, tid);
 }
 
 // ---------------------------------------------------------------------------------
@@ -562,6 +576,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH == 
   __shared__ __attribute__((aligned(16))) bf16_t sQ[2][C::TILE * C::PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t sG[2][C::TILE * C::PITCH];
   __shared__ __attribute__((aligned(16))) float sL[2][C::TILE], sD[2][C::TILE];
+  __shared__ float sB[kBlockRows * kBiasPitch];   // the bias gradient's way through LDS
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, h2 = lane / 32;
   const int d = H * DH;
   const int64_t ld = 3 * int64_t(d);
@@ -675,8 +690,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH == 
       }
   }
   if (dbias) {
-    bias_grad_sums<C::DTILES>(dbias + d + head * DH, acc_k, scale, key < s, lane);
-    bias_grad_sums<C::DTILES>(dbias + 2 * d + head * DH, acc_v, 1.f, key < s, lane);
+    bias_grad_sums<C::DTILES>(dbias + d + head * DH, acc_k, scale, key < s, sB, tid);
+    bias_grad_sums<C::DTILES>(dbias + 2 * d + head * DH, acc_v, 1.f, key < s, sB, tid);
   }
 }
 
