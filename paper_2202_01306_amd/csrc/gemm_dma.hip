@@ -21,8 +21,8 @@
 // ds_read_b64_tr_b16 with k rows 8h..8h+3 and 8h+4..8h+7 (h = lane/32), which is the
 // same contraction order as the 16-byte read of the other layout.
 //
-// Tuning switches (read once per process): HMY_GEMM_BK = 32 | 64 and
-// HMY_GEMM_STAGES = 3 | 4 override the K tile and the ring depth of the 128x128 kernel,
+// Tuning switches (read once per process): HMY_GEMM_BK = 32 | 64 overrides the K tile of
+// both kernels, HMY_GEMM_STAGES = 3 | 4 the ring depth of the 128x128 kernel,
 // HMY_GEMM_TILE = 128 | 256 the choice between it and the 256x256 kernel.
 #include <algorithm>
 #include <cstdlib>
@@ -485,17 +485,24 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
 // The same GEMM on a 256x256 block tile for outputs large enough to give every compute unit one: what bounds the
 // 128x128 kernel is the rate at which the L2 caches feed the load-to-LDS instructions of all compute units together,
 // and a tile of twice the side moves half the bytes per multiply.  Eight waves of 128x64 (4x2 multiplies of 32x32x16
-// per 16-deep step, two waves per SIMD), K tiles of 32, the same ring of S stages.  Each operand's 256 rows are kept
-// as two 128-row sub-tiles in the layouts of the 128x128 kernel; waves 0-3 copy the first sub-tile of A and of B,
-// waves 4-7 the second, each group splitting its sub-tile the way the four waves of that kernel do.
-template <bool TA, bool TB, int S>
+// per 16-deep step, two waves per SIMD) over 128 KiB of LDS: a ring of four stages of K tiles of 32, or two stages of
+// K tiles of 64.  With the contraction index contiguous in memory a K tile of 32 takes 64 bytes of every operand
+// row, half a cache line, and the other half a tile later, when the line has left the compute unit's cache again;
+// a K tile of 64 takes whole lines, and the loads to LDS alone then run a quarter faster.  Two stages mean that a
+// tile is requested only when the tile before the one being multiplied has been left by every wave, one tile (64
+// multiplies per SIMD) before its first use.  Each operand's 256 rows are kept as two 128-row sub-tiles in the
+// layouts of the 128x128 kernel; waves 0-3 copy the first sub-tile of A and of B, waves 4-7 the second, each group
+// splitting its sub-tile the way the four waves of that kernel do.
+template <bool TA, bool TB, int BK, int S>
 __global__ __launch_bounds__(512) void k_gemm_dma256(DmaP p, int grid_n) {
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
-  constexpr int BK = 32, BT = 256;
-  constexpr int SUB = BM * BK;        // elements of one 128-row sub-tile (8 KiB)
-  constexpr int STAGE = 4 * SUB;      // elements of one stage: A rows 0-127, A rows 128-255, B likewise (32 KiB)
-  constexpr int L = 4;                // load-to-LDS instructions per thread per K tile
-  static_assert(S >= 3, "one stage is multiplied, one is the next to be, the others are in flight");
+  constexpr int BT = 256;
+  constexpr int SUB = BM * BK;        // elements of one 128-row sub-tile
+  constexpr int STAGE = 4 * SUB;      // elements of one stage: A rows 0-127, A rows 128-255, B likewise
+  constexpr int NJ = BK / 16;         // load-to-LDS instructions per thread, operand and K tile
+  constexpr int L = 2 * NJ;           // load-to-LDS instructions per thread per K tile
+  constexpr int KS = BK / 16;         // 16-deep steps per K tile
+  static_assert(S >= 2, "one stage is multiplied while the others are in flight");
   static_assert((S - 1) * L <= 63, "vmcnt is a 6-bit counter");
   static_assert(S * STAGE * 2 >= 128 * 1024, "the output stage needs 16 KiB of LDS per wave");
   const int tid = threadIdx.x, lane = tid % 64;
@@ -557,44 +564,58 @@ __global__ __launch_bounds__(512) void k_gemm_dma256(DmaP p, int grid_n) {
 #define HMY_FENCE() __builtin_amdgcn_sched_barrier(0)
 #define HMY_MFMA(i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0)
   // One 16-deep step: eight multiplies on fragment buffer `cur`; behind six of them one of the six fragment reads of the
-  // next step (from stage `nstage`, step `nks`, into buffer `nxt`); with `fetch`, behind four of them the four
-  // load-to-LDS instructions that bring the next tile into stage `fstage`.
+  // next step (from stage `nstage`, step `nks`, into buffer `nxt`); with `fetch`, the load-to-LDS instructions that
+  // bring the next tile into stage `fstage`, one behind a multiply each: four of them (K tile 32) behind the last
+  // five multiplies, eight (K tile 64) behind all.
   auto step = [&](int cur, int nxt, bool reads, int nstage, int nks, bool fetch, int fstage) {
     const bf16_t *a_s = smem + nstage * STAGE + a_sub, *b_s = smem + nstage * STAGE + b_sub;
     const uint32_t fl = lds0 + uint32_t(fstage) * uint32_t(2 * STAGE);
+    // slot k = behind the k-th multiply
+    auto fetch_slot = [&](int k) {
+      if (!fetch) return;
+      const int i = NJ == 2 ? k - 3 : k;   // which of the tile's L instructions
+      if (i < 0 || i >= L) return;
+      if (i % 2 == 0) da.issue_one(a_next, fl + a_off, w4, i / 2);
+      else db.issue_one(b_next, fl + b_off, w4, i / 2);
+    };
     HMY_FENCE();
     HMY_MFMA(0, 0);
     HMY_FENCE();
     if (reads) fa[nxt][0] = frag<TA, BK>(a_s, 0, nks, lane);
+    fetch_slot(0);
     HMY_FENCE();
     HMY_MFMA(0, 1);
     HMY_FENCE();
     if (reads) fb[nxt][0] = frag<TB, BK>(b_s, brow, nks, lane);
+    fetch_slot(1);
     HMY_FENCE();
     HMY_MFMA(1, 0);
     HMY_FENCE();
     if (reads) fb[nxt][1] = frag<TB, BK>(b_s, brow + 32, nks, lane);
+    fetch_slot(2);
     HMY_FENCE();
     HMY_MFMA(1, 1);
     HMY_FENCE();
     if (reads) fa[nxt][1] = frag<TA, BK>(a_s, 32, nks, lane);
-    if (fetch) da.issue_one(a_next, fl + a_off, w4, 0);
+    fetch_slot(3);
     HMY_FENCE();
     HMY_MFMA(2, 0);
     HMY_FENCE();
     if (reads) fa[nxt][2] = frag<TA, BK>(a_s, 64, nks, lane);
-    if (fetch) db.issue_one(b_next, fl + b_off, w4, 0);
+    fetch_slot(4);
     HMY_FENCE();
     HMY_MFMA(2, 1);
     HMY_FENCE();
     if (reads) fa[nxt][3] = frag<TA, BK>(a_s, 96, nks, lane);
-    if (fetch) da.issue_one(a_next, fl + a_off, w4, 1);
+    fetch_slot(5);
     HMY_FENCE();
     HMY_MFMA(3, 0);
     HMY_FENCE();
-    if (fetch) db.issue_one(b_next, fl + b_off, w4, 1);
+    fetch_slot(6);
     HMY_FENCE();
     HMY_MFMA(3, 1);
+    HMY_FENCE();
+    fetch_slot(7);
     HMY_FENCE();
   };
   int stage = 0;      // stage holding tile t
@@ -610,14 +631,15 @@ __global__ __launch_bounds__(512) void k_gemm_dma256(DmaP p, int grid_n) {
   };
   for (int t = 0; t + 1 < n; ++t) {
     const int next = stage + 1 == S ? 0 : stage + 1;
-    step(0, 1, true, stage, 1, false, 0);
+#pragma unroll
+    for (int ks = 0; ks + 1 < KS; ++ks) step(ks % 2, (ks + 1) % 2, true, stage, ks + 1, false, 0);
     // every read of tile t has been issued.  Tiles up to t+S-1 have been requested: tile t+1 has landed once at most
     // the S-2 behind it are outstanding.
     if (t + S - 1 < n) wait_vm<(S - 2) * L>();
     else wait_vm<0>();
     __syncthreads();   // tile t+1 visible to every wave; every wave is done reading tile t
     const bool fetch = t + S < n;   // tile t+S goes to the stage tile t has just left: S-1 tiles ahead of its use
-    step(1, 0, true, next, 0, fetch, stage);
+    step((KS - 1) % 2, 0, true, next, 0, fetch, stage);
     if (fetch) {
       a_next += a_kstep;
       b_next += b_kstep;
@@ -629,8 +651,9 @@ __global__ __launch_bounds__(512) void k_gemm_dma256(DmaP p, int grid_n) {
     prefetch_slab(0, 0);
   }
   if (n > 0) {   // last tile: nothing left to fetch or wait for
-    step(0, 1, true, stage, 1, false, 0);
-    step(1, 0, false, stage, 0, false, 0);
+#pragma unroll
+    for (int ks = 0; ks + 1 < KS; ++ks) step(ks % 2, (ks + 1) % 2, true, stage, ks + 1, false, 0);
+    step((KS - 1) % 2, 0, false, stage, 0, false, 0);
   }
 #undef HMY_MFMA
 #undef HMY_FENCE
@@ -687,14 +710,14 @@ int launch_cfg(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int tiles_per_s
   return check_launch("gemm_dma");
 }
 
-template <int S>
+template <int BK, int S>
 int launch_cfg256(const hmy_gemm_desc &g, const DmaP &p, dim3 grid, int gn, hipStream_t s) {
-  const size_t lds = size_t(S) * 4 * BM * 32 * sizeof(bf16_t);
+  const size_t lds = size_t(S) * 4 * BM * BK * sizeof(bf16_t);
   dim3 block(512);
-  if (!g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma256<false, false, S>), grid, block, lds, s, p, gn);
-  else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_dma256<false, true, S>), grid, block, lds, s, p, gn);
-  else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma256<true, false, S>), grid, block, lds, s, p, gn);
-  else hipLaunchKernelGGL((k_gemm_dma256<true, true, S>), grid, block, lds, s, p, gn);
+  if (!g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma256<false, false, BK, S>), grid, block, lds, s, p, gn);
+  else if (!g.ta && g.tb) hipLaunchKernelGGL((k_gemm_dma256<false, true, BK, S>), grid, block, lds, s, p, gn);
+  else if (g.ta && !g.tb) hipLaunchKernelGGL((k_gemm_dma256<true, false, BK, S>), grid, block, lds, s, p, gn);
+  else hipLaunchKernelGGL((k_gemm_dma256<true, true, BK, S>), grid, block, lds, s, p, gn);
   return check_launch("gemm_dma256");
 }
 
@@ -729,8 +752,13 @@ int launch_gemm_dma(const hmy_gemm_desc &g, stream_t st) {
     // at least half full): half the operand bytes per multiply through the L2 caches
     const int gm2 = (g.M + 255) / 256, gn2 = (g.N + 255) / 256, wgs = gm2 * gn2;
     const bool fills = wgs >= 176 && (wgs <= 256 || wgs >= 384);
-    if (force_tile != 128 && g.M >= 256 && g.N >= 256 && (force_tile == 256 || fills))
-      return launch_cfg256<4>(g, p, dim3(wgs), gn2, (hipStream_t)st);
+    if (force_tile != 128 && g.M >= 256 && g.N >= 256 && (force_tile == 256 || fills)) {
+      // K tiles of 64 where an operand has the contraction index contiguous (whole cache lines of its rows)
+      bool deep = (!g.ta || !g.tb) && g.K % 64 == 0;
+      if (force_bk == 32 || (force_bk == 64 && g.K % 64 == 0)) deep = force_bk == 64;
+      return deep ? launch_cfg256<64, 2>(g, p, dim3(wgs), gn2, (hipStream_t)st)
+                  : launch_cfg256<32, 4>(g, p, dim3(wgs), gn2, (hipStream_t)st);
+    }
   }
   const int gm = (g.M + BM - 1) / BM, gn = (g.N + BM - 1) / BM;
   // split the contraction over workgroups (fp32 atomics into C) only while that fills
