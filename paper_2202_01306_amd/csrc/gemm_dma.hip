@@ -131,11 +131,18 @@ __device__ __forceinline__ bf16x8 frag(const bf16_t *s, int row32, int ks, int l
 
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// Output stage for 8 consecutive columns of one row.  `fast`: the workgroup's tile lies
-// inside C and every pointer and leading dimension allows 16-byte accesses; the other
-// path is element-wise and kept rolled, so that it costs no instruction-cache space.
+// Output stage for 8 consecutive columns of one row.  `fast`: every pointer and leading
+// dimension allows 16-byte accesses; `inside`: the workgroup's tile lies inside C.  A
+// tile that sticks out still leaves through the 16-byte path wherever a row's group of
+// 8 columns lies inside C (a 1600-wide output ends in the middle of a tile: element by
+// element that tile took longer than the whole K loop); what remains, and everything
+// when `fast` is false, goes element by element through a loop kept rolled, so that it
+// costs no instruction-cache space.
 struct Epi {
-  bool fast;
+  bool fast, inside;
+  __device__ __forceinline__ bool whole8(const DmaP &p, int m, int nn) const {
+    return inside || (m < p.M && nn + 8 <= p.N);
+  }
   __device__ __forceinline__ void init(const DmaP &p, int m0, int n0, int side = BM) {
     const int esz = p.c_fp32 ? 4 : 2;
     bool ok = (reinterpret_cast<uintptr_t>(p.C) & 15) == 0 && (p.ldc * esz) % 16 == 0;
@@ -143,7 +150,8 @@ struct Epi {
     if (p.res && p.res_fp32 && p.accumulate) ok = false;   // both would want the prefetch registers
     if (p.bias) ok = ok && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;
     if (p.gelu_out) ok = ok && (reinterpret_cast<uintptr_t>(p.gelu_out) & 15) == 0;
-    fast = ok && m0 + side <= p.M && n0 + side <= p.N;
+    fast = ok;
+    inside = m0 + side <= p.M && n0 + side <= p.N;
   }
   // tanh-form GELU with the hardware exponential: the argument is a bf16 value and so is
   // the result, which the 2-ulp exponential does not disturb.  Written as u * sigmoid(2z),
@@ -160,6 +168,7 @@ struct Epi {
   // that its latency hides behind that tile's multiplies.
   struct Pre { float4 lo, hi; };
   __device__ __forceinline__ void prefetch(const DmaP &p, int m, int nn, Pre &r) const {
+    if (!whole8(p, m, nn)) return;
     if (p.res && p.res_fp32) {   // the fp32 residual stream: 8 columns are 32 bytes
       const float *x = reinterpret_cast<const float *>(p.res) + int64_t(m) * p.ldr + nn;
       r.lo = *reinterpret_cast<const float4 *>(x);
@@ -238,6 +247,21 @@ struct Epi {
       const bf16_t o = from_f32<bf16_t>(v);
       static_cast<bf16_t *>(p.C)[ci] = o;
       if (p.gelu_out) p.gelu_out[ci] = from_f32<bf16_t>(gelu_f(to_f32(o)));
+    }
+  }
+  // a row's group of 8 columns, whose fp32 values lie at src in LDS: in one piece where the group lies inside C,
+  // else whatever of it does, element by element
+  __device__ __forceinline__ void emit8(const DmaP &p, int m, int nn, const float *src, const Pre &r,
+                                        const float4 &bias8) const {
+    if (whole8(p, m, nn)) {
+      float v[8];
+      *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
+      *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
+      emit_fast(p, m, nn, v, r, bias8);
+    } else if (m < p.M) {
+#pragma unroll 1
+      for (int k = 0; k < 8; ++k)
+        if (nn + k < p.N) emit_one(p, m, nn + k, src[k]);
     }
   }
 };
@@ -366,7 +390,8 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
   // lane's share of the output: slab i (32 rows), pass q -> row 8 q + lane/8, columns 8 (lane%8) .. +7
   auto prefetch_outputs = [&]() {
     if (split || !e.fast) return;
-    if (p.bias) bias8 = *reinterpret_cast<const float4 *>(p.bias + n_tile + 8 * (lane % 8));
+    if (p.bias && (e.inside || n_tile + 8 * (lane % 8) + 8 <= p.N))
+      bias8 = *reinterpret_cast<const float4 *>(p.bias + n_tile + 8 * (lane % 8));
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -466,10 +491,7 @@ __global__ __launch_bounds__(NT) void k_gemm_dma(DmaP p, int tiles_per_split, in
       for (int q = 0; q < 4; ++q) {
         const int row = 8 * q + lane / 8, c0 = 8 * (lane % 8);
         const float *src = slab + row * 64 + (c0 ^ (((row >> 2) & 1) << 5));
-        float v[8];
-        *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
-        *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
-        e.emit_fast(p, m_tile + 32 * i + row, n_tile + c0, v, pre[i][q], bias8);
+        e.emit8(p, m_tile + 32 * i + row, n_tile + c0, src, pre[i][q], bias8);
       }
     } else {
 #pragma unroll 1
@@ -647,7 +669,8 @@ __global__ __launch_bounds__(512) void k_gemm_dma256(DmaP p, int grid_n) {
     stage = next;
   }
   if (e.fast) {
-    if (p.bias) bias8 = *reinterpret_cast<const float4 *>(p.bias + n_tile + 8 * (lane % 8));
+    if (p.bias && (e.inside || n_tile + 8 * (lane % 8) + 8 <= p.N))
+      bias8 = *reinterpret_cast<const float4 *>(p.bias + n_tile + 8 * (lane % 8));
     prefetch_slab(0, 0);
   }
   if (n > 0) {   // last tile: nothing left to fetch or wait for
@@ -677,10 +700,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma256(DmaP p, int grid_n) {
       for (int q = 0; q < 4; ++q) {
         const int row = 8 * q + lane / 8, c0 = 8 * (lane % 8);
         const float *src = slab + row * 64 + (c0 ^ (((row >> 2) & 1) << 5));
-        float v[8];
-        *reinterpret_cast<float4 *>(v) = *reinterpret_cast<const float4 *>(src);
-        *reinterpret_cast<float4 *>(v + 4) = *reinterpret_cast<const float4 *>(src + 4);
-        e.emit_fast(p, m_tile + 32 * i + row, n_tile + c0, v, pre[i & 1][q], bias8);
+        e.emit8(p, m_tile + 32 * i + row, n_tile + c0, src, pre[i & 1][q], bias8);
       }
     } else {
 #pragma unroll 1
