@@ -225,6 +225,9 @@ def main() -> int:
     ap.add_argument("--update-site", choices=("device", "host"), default="device",
                     help="host: the Weight Update task runs on CPU threads (the paper's optimizer offload); "
                          "optimizer state then never crosses the link")
+    ap.add_argument("--fwd-packs", default="", help="forward pack ends instead of the planner's, e.g. 2,6,14,25 "
+                    "(the last backward pack's first layer closes the list)")
+    ap.add_argument("--bwd-packs", default="", help="backward pack ends instead of the planner's, e.g. 1,3,7,26")
     ap.add_argument("--counters", action="store_true",
                     help="for runs under `rocprofv3 --pmc`, where every dispatch is serialised: ONE iteration, no warm-up, "
                          "no variants, no CPU baseline, and a line on stderr after every visit")
@@ -253,8 +256,13 @@ def main() -> int:
     try:
         st = TrainingState(cfg)        # pinned host memory: the first call that needs the GPU
     except B.HmyError as e:
-        print(f"bench.py needs a GPU (there is no CPU fallback): {e}", file=sys.stderr)
-        return 3
+        if a.update_site == "host" and "out of memory" in str(e):
+            # more state than this machine will page-lock: with the update on the host only CPU threads touch
+            # master, m and v, which may then be ordinary memory
+            st = TrainingState(cfg, pageable_optimizer_state=True)
+        else:
+            print(f"bench.py needs a GPU (there is no CPU fallback): {e}", file=sys.stderr)
+            return 3
     st.fill_random(0)
     ids = synth.gen_tokens(cfg, 0)
     tg = synth.gen_targets(cfg, ids, 0)
@@ -266,6 +274,12 @@ def main() -> int:
     site = B.HMY_UPDATE_ON_HOST if a.update_site == "host" else B.HMY_UPDATE_ON_DEVICE
     pkw = plan_kwargs(a, measured)
     sched = B.hmy_plan(st.spec, cfg["budget"], cfg["M"], cfg["b"], update_site=site, **pkw)
+    for given, n_field, end_field in ((a.fwd_packs, "n_fwd_packs", "fwd_pack_end"), (a.bwd_packs, "n_bwd_packs", "bwd_pack_end")):
+        if given:   # the caller's packs; hmy_create rejects them if they do not fit the budget
+            ends = [int(x) for x in given.split(",")]
+            setattr(sched, n_field, len(ends))
+            for i, e in enumerate(ends):
+                getattr(sched, end_field)[i] = e
     sched.order = B.HMY_ORDER_MICROBATCH_MAJOR if a.order == "microbatch-major" else B.HMY_ORDER_LAYER_PACK_MAJOR
     sched.gradients = B.HMY_GRADIENTS_ON_DEVICE if a.gradients == "device" else B.HMY_GRADIENTS_EXPORTED
     sched.resident_state = B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET if a.resident_state else B.HMY_STATE_SWAPPED
