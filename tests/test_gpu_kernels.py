@@ -174,7 +174,7 @@ def test_embedding_fwd_bwd_with_repeated_ids(prec, pc, dt, tol):
 
 
 def _gemm_case(prec, pc, dt, tol, M, N, K, ta, tb, c_fp32, accumulate, bias, res, gelu, use_mfma, pad=0, res_fp32=0,
-               row_pad=0):
+               row_pad=0, ldc=None):
     rng = np.random.default_rng(M * 7 + N * 3 + K + ta * 2 + tb)
     lda = M + row_pad if ta else K + pad        # pad: rows whose contiguous axis is K; row_pad: A stored [K, M]
     ldb = N if tb else K + pad
@@ -189,7 +189,7 @@ def _gemm_case(prec, pc, dt, tol, M, N, K, ta, tb, c_fp32, accumulate, bias, res
         ref = ref + biasv
     if res:
         ref = ref + resv
-    ldc = N + (8 if pad else 0)
+    ldc = ldc or N + (8 if pad else 0)
     cdt = torch.float32 if c_fp32 else dt
     c0 = rng.standard_normal((M, ldc)).astype(np.float32)
     Cd = dev(c0, cdt)
@@ -214,7 +214,7 @@ def _gemm_case(prec, pc, dt, tol, M, N, K, ta, tb, c_fp32, accumulate, bias, res
         assert np.abs(got[:, :N] - gref).max() / max(np.abs(gref).max(), scale) < tol, "gelu in place"
         return
     assert np.abs(got[:, :N] - ref).max() / max(np.abs(ref).max(), scale) < tol, "C"
-    if pad:   # columns beyond N are never written
+    if ldc > N:   # columns beyond N are never written
         assert np.array_equal(got[:, N:], host(dev(c0, cdt))[:, N:])
     if gelu:
         gref = om.gelu_fwd(got[:, :N])          # gelu of the stored (rounded) C
@@ -285,6 +285,24 @@ def test_gemm_bf16_large_outputs_epilogues():
     _gemm_case(*args, 1536, 1024, 2048 + 32, 0, 1, 1, 1, False, False, False, True)    # the last split has two K tiles
     say("gemm bf16 large: fp32 logits, ragged vocabulary, padded leading dimensions")
     _gemm_case(*args, 512, 50257, 64, 0, 0, 1, 0, False, False, False, True, 8)
+
+
+def test_gemm_bf16_tiles_that_stick_out_of_c():
+    """Outputs whose width is no multiple of the block tile, with 16-byte aligned rows: whole groups of 8 columns of an
+    edge tile leave through the vector path, a ragged last group element by element; nothing beyond N is written."""
+    args = ("bf16", 1, torch.bfloat16, 2e-2)
+    say("gemm bf16 edge tiles: fp32 C, ragged width, aligned rows")
+    _gemm_case(*args, 200, 333, 128, 0, 0, 1, 0, False, False, False, True, ldc=336)
+    _gemm_case(*args, 200, 333, 128, 0, 0, 1, 1, False, False, False, True, ldc=336)      # +=
+    say("gemm bf16 edge tiles: bf16 C, bias + gelu, ragged width")
+    _gemm_case(*args, 200, 333, 128, 0, 0, 0, 0, True, False, True, True, ldc=336)
+    say("gemm bf16 edge tiles: 1600 wide, bias + fp32 residual stream")
+    _gemm_case(*args, 2048, 1600, 64, 0, 0, 1, 0, True, True, False, True, res_fp32=1)
+    _gemm_case(*args, 1600, 1608, 256, 1, 1, 1, 1, False, False, False, True)            # weight gradient, ragged rows too
+    say("gemm bf16 edge tiles, 256x256: fp32 C with a ragged width; bf16 C with bias + gelu")
+    _gemm_case(*args, 4096, 2999, 64, 0, 0, 1, 0, False, False, False, True, ldc=3008)
+    _gemm_case(*args, 4000, 3000, 96, 0, 0, 0, 0, True, False, True, True)
+    _gemm_case(*args, 4000, 3000, 64, 0, 1, 0, 0, True, True, False, True)
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 1)])
