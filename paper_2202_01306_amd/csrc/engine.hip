@@ -1115,7 +1115,12 @@ int hmy_host_alloc(uint64_t bytes, void **out) {
   if (!out) return fail(HMY_E_INVALID, "null out");
   *out = nullptr;
   hipError_t e = hipHostMalloc(out, bytes ? bytes : 1, hipHostMallocDefault);
-  if (e != hipSuccess) return fail(HMY_E_HIP, "hipHostMalloc(%llu): %s", (unsigned long long)bytes, hipGetErrorString(e));
+  if (e != hipSuccess) {
+    // the runtime also remembers the failure as its "last error": taken out here, or the next launch check of a
+    // caller who goes on (with less, or with ordinary memory) would report this allocation's failure as its own
+    (void)hipGetLastError();
+    return fail(HMY_E_HIP, "hipHostMalloc(%llu): %s", (unsigned long long)bytes, hipGetErrorString(e));
+  }
   return HMY_OK;
 }
 int hmy_host_free(void *p) {
