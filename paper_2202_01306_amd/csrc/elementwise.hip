@@ -516,6 +516,133 @@ __global__ __launch_bounds__(NJ <= 1 ? 1024 : NJ <= 4 ? 512 : 256)
   }
 }
 
+// The same for wider rows: WPR waves share a row, each owning a band of 2 * 64 * VEC columns (two 16-byte
+// vectors per lane, as in the register kernel's best case), so that a row of 1600 or 4096 columns neither spills
+// nor leaves one wave per SIMD.  A workgroup of 8 waves works on 8 / WPR rows at a time; the two row sums meet in
+// LDS (one barrier per row, two alternating buffers), added in the same order by every wave of the row.  Every
+// wave runs the same number of rounds (rows past the end are skipped inside the round), so the barriers match.
+template <typename E, int WPR>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_layernorm_bwd_wide(
+    const E *dy, const float *x, const float *mean, const float *rstd, const E *gamma, const float *res, float *dx, E *dx_e,
+    float *dgamma, float *dbeta, float *dres, int T, int d, float *partial) {
+  constexpr int VEC = ElemTraits<E>::VEC, NJ = 2, kWaves = 8, kSlots = kWaves / WPR, kBand = NJ * kWave * VEC;
+  extern __shared__ __align__(16) float lds[];   // per row slot: dgamma[d], dbeta[d] (, dres[d]); then the row sums' exchange
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int slot = wave / WPR, col0 = (wave % WPR) * kBand;
+  const bool sum_res = dres != nullptr;
+  const int ns = sum_res ? 3 : 2;
+  float *xch = lds + uint64_t(kSlots) * ns * d;   // [2][kWaves][2]
+  float dg[NJ][VEC], db[NJ][VEC], dr[NJ][VEC];
+  Vec16<E> gm[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = col0 + VEC * (lane + kWave * j);
+    if (c < d) gm[j] = load16(gamma + c);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) dg[j][k] = db[j][k] = dr[j][k] = 0.f;
+  }
+  int round = 0;
+  for (int base = blockIdx.x * kSlots; base < T; base += gridDim.x * kSlots, ++round) {
+    const int row = base + slot;
+    const bool live = row < T;
+    const float *xr = x + uint64_t(live ? row : 0) * d;
+    const E *dyr = dy + uint64_t(live ? row : 0) * d;
+    const float mu = live ? mean[row] : 0.f, rs = live ? rstd[row] : 0.f;
+    float xv[NJ][VEC];
+    Vec16<E> gv[NJ];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c = col0 + VEC * (lane + kWave * j);
+      if (live && c < d) {
+        load_stream<VEC>(xr + c, xv[j]);
+        gv[j] = load16(dyr + c);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c = col0 + VEC * (lane + kWave * j);
+      if (live && c < d) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+          const float xh = (xv[j][k] - mu) * rs;
+          xv[j][k] = xh;
+          const float g = to_f32(gv[j].v[k]);
+          const float dxh = g * to_f32(gm[j].v[k]);
+          s1 += dxh;
+          s2 += dxh * xh;
+          dg[j][k] += g * xh;
+          db[j][k] += g;
+        }
+      }
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    float *mine = xch + (round & 1) * (2 * kWaves);
+    if (lane == 0) {
+      mine[2 * wave] = s1;
+      mine[2 * wave + 1] = s2;
+    }
+    __syncthreads();
+    s1 = s2 = 0.f;
+#pragma unroll
+    for (int w = 0; w < WPR; ++w) {
+      s1 += mine[2 * (slot * WPR + w)];
+      s2 += mine[2 * (slot * WPR + w) + 1];
+    }
+    s1 /= float(d);
+    s2 /= float(d);
+    if (live) {
+      float *dxr = dx + uint64_t(row) * d;
+      const float *rr = res ? res + uint64_t(row) * d : nullptr;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int c = col0 + VEC * (lane + kWave * j);
+        if (c < d) {
+          float rv[VEC], o[VEC];
+          if (rr) load_stream<VEC>(rr + c, rv);
+          Vec16<E> oe;
+#pragma unroll
+          for (int k = 0; k < VEC; ++k) {
+            const float dxh = to_f32(gv[j].v[k]) * to_f32(gm[j].v[k]);
+            float v = (dxh - s1 - xv[j][k] * s2) * rs;
+            if (rr) v += rv[k];
+            if (sum_res) dr[j][k] += rv[k];
+            o[k] = v;
+            oe.v[k] = from_f32<E>(v);
+          }
+          store_stream<VEC>(dxr + c, o);
+          if (dx_e) store16(dx_e + uint64_t(row) * d + c, oe);
+        }
+      }
+    }
+  }
+  // the waves of a row slot hold disjoint bands of columns: together they fill the slot's row of sums
+  float *mine = lds + uint64_t(slot) * ns * d;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = col0 + VEC * (lane + kWave * j);
+    if (c < d) {
+#pragma unroll
+      for (int k = 0; k < VEC; k += 4) {
+        *reinterpret_cast<float4 *>(mine + c + k) = make_float4(dg[j][k], dg[j][k + 1], dg[j][k + 2], dg[j][k + 3]);
+        *reinterpret_cast<float4 *>(mine + d + c + k) = make_float4(db[j][k], db[j][k + 1], db[j][k + 2], db[j][k + 3]);
+        if (sum_res)
+          *reinterpret_cast<float4 *>(mine + 2 * d + c + k) = make_float4(dr[j][k], dr[j][k + 1], dr[j][k + 2], dr[j][k + 3]);
+      }
+    }
+  }
+  __syncthreads();
+  float *out_row = partial ? partial + uint64_t(blockIdx.x) * ns * d : nullptr;
+  for (int c = threadIdx.x; c < ns * d; c += blockDim.x) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < kSlots; ++w) t += lds[uint64_t(w) * ns * d + c];
+    if (out_row) out_row[c] = t;
+    else atomicAdd(c < d ? &dgamma[c] : c < 2 * d ? &dbeta[c - d] : &dres[c - 2 * d], t);
+  }
+}
+
 // dgamma += column sums of partial[:, 0:d], dbeta += those of partial[:, d:2d] and, with rows of 3 d sums,
 // dres += those of partial[:, 2d:3d].  The launches that accumulate into one tensor are ordered on their
 // stream, so plain adds do.
@@ -894,6 +1021,20 @@ void launch_ln_bwd(const E *dy, const float *x, const float *mean, const float *
   // waves per workgroup: as many as 128 KiB of LDS holds rows of 2 d floats, and as the registers allow
   // without spilling (16 for rows of one 16-byte vector per lane, 8 up to four vectors, 4 beyond; measured
   // at d = 1024 bf16: 16 waves with spills 22 us, 8 waves 15 us, 4 waves 20 us)
+  if (nj > 2 && nj <= 16) {
+    // rows wider than two vectors per lane: several waves per row (2 up to four vectors, 4 up to eight, 8 beyond)
+    const int wpr = nj <= 4 ? 2 : nj <= 8 ? 4 : 8, slots = 8 / wpr;
+    const int grid = grid_for(T, slots, kLnBlocks);
+    float *partial = ws && ws_bytes >= uint64_t(grid) * ns * d * 4 ? ws : nullptr;
+    const size_t lds = (size_t(slots) * ns * d + 2 * 8 * 2) * 4;
+    const dim3 g(grid), b(8 * kWave);
+    if (wpr == 2) hipLaunchKernelGGL((k_layernorm_bwd_wide<E, 2>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, dres, T, d, partial);
+    else if (wpr == 4) hipLaunchKernelGGL((k_layernorm_bwd_wide<E, 4>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, dres, T, d, partial);
+    else hipLaunchKernelGGL((k_layernorm_bwd_wide<E, 8>), g, b, lds, st, dy, x, mean, rstd, gamma, res, dx, dx_e, dgamma, dbeta, dres, T, d, partial);
+    if (partial)
+      hipLaunchKernelGGL(k_ln_bwd_reduce, dim3((ns * d + 63) / 64), dim3(256), 0, st, partial, grid, d, ns, dgamma, dbeta, dres);
+    return;
+  }
   int waves = 16;
   while (waves > 1 && (uint64_t(waves) * ns * d * 4 > (128u << 10) || (nj > 1 && waves > 8) || (nj > 4 && waves > 4)))
     waves /= 2;   // also the kernels' launch bounds
@@ -918,7 +1059,7 @@ int launch_layernorm_bwd(int prec, const void *dy, const float *x, const float *
   if (T < 1 || d % 8 || d > 8192) return fail(HMY_E_INVALID, "layernorm_bwd: bad shape");
   if (dres_sum && !res) return fail(HMY_E_INVALID, "layernorm_bwd: column sums of a residual gradient that is not given");
   DISPATCH_PREC(prec, {
-    if (dres_sum && d > 8 * kWave * ElemTraits<E>::VEC) {
+    if (dres_sum && d > 16 * kWave * ElemTraits<E>::VEC) {
       // rows too wide for the register kernel: the sums get a pass of their own, before dx (which may be res) is written
       const int rc = launch_colsum(HMY_PREC_FP32, res, dres_sum, T, d, st);
       if (rc != HMY_OK) return rc;

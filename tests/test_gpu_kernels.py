@@ -49,7 +49,7 @@ def say(msg):
 
 
 @pytest.mark.parametrize("prec,pc,dt,tol", PRECS)
-@pytest.mark.parametrize("T,d", [(5, 128), (130, 1024), (67, 1600), (33, 4096)])
+@pytest.mark.parametrize("T,d", [(5, 128), (130, 1024), (67, 1600), (33, 4096), (1037, 1600), (70, 2056), (9, 8192)])
 def test_layernorm_fwd_bwd(prec, pc, dt, tol, T, d):
     say(f"layernorm {prec} T={T} d={d}")
     rng = np.random.default_rng(T * 1000 + d)
