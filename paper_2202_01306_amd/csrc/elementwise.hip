@@ -1018,9 +1018,6 @@ void launch_ln_bwd(const E *dy, const float *x, const float *mean, const float *
   constexpr int VEC = ElemTraits<E>::VEC;
   const int nj = (d + kWave * VEC - 1) / (kWave * VEC);
   const int ns = dres ? 3 : 2;   // sums per column
-  // waves per workgroup: as many as 128 KiB of LDS holds rows of 2 d floats, and as the registers allow
-  // without spilling (16 for rows of one 16-byte vector per lane, 8 up to four vectors, 4 beyond; measured
-  // at d = 1024 bf16: 16 waves with spills 22 us, 8 waves 15 us, 4 waves 20 us)
   if (nj > 2 && nj <= 16) {
     // rows wider than two vectors per lane: several waves per row (2 up to four vectors, 4 up to eight, 8 beyond)
     const int wpr = nj <= 4 ? 2 : nj <= 8 ? 4 : 8, slots = 8 / wpr;
@@ -1035,6 +1032,9 @@ void launch_ln_bwd(const E *dy, const float *x, const float *mean, const float *
       hipLaunchKernelGGL(k_ln_bwd_reduce, dim3((ns * d + 63) / 64), dim3(256), 0, st, partial, grid, d, ns, dgamma, dbeta, dres);
     return;
   }
+  // waves per workgroup: as many as 128 KiB of LDS holds rows of 2 d floats, and as the registers allow
+  // without spilling (16 for rows of one 16-byte vector per lane, 8 up to four vectors, 4 beyond; measured
+  // at d = 1024 bf16: 16 waves with spills 22 us, 8 waves 15 us, 4 waves 20 us)
   int waves = 16;
   while (waves > 1 && (uint64_t(waves) * ns * d * 4 > (128u << 10) || (nj > 1 && waves > 8) || (nj > 4 && waves > 4)))
     waves /= 2;   // also the kernels' launch bounds
