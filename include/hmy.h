@@ -389,14 +389,17 @@ int hmy_bind_state(hmy_handle *h, const hmy_host_state *state);
  * counters.  Returns with all streams idle. */
 int hmy_iteration(hmy_handle *h, const hmy_minibatch *mb, const hmy_adam *adam, hmy_stats *out);
 
-/* The Profiler of Section 4.2 for this library's kernels: runs the embedding, one block
- * and the head on `hip_device`, forward and backward as the tasks would run them, for one
- * microbatch of micro_batch sequences (pseudo-random inputs: the kernels' time does not
- * depend on the values, but all-zero operands draw less power and clock higher), `reps`
- * times each after a warm-up, once with the device to itself and once beside host-link
- * traffic on two more streams (see hmy_measured_profile), and reports the average times.
- * Allocates its own device memory (a one-block arena, two 128 MiB staging buffers) and
- * frees it; needs no host state. */
+/* The Profiler of Section 4.2 for this library's kernels: runs the embedding, a pack of up
+ * to three blocks and the head on `hip_device`, forward and backward as the tasks would run
+ * them, for one microbatch of micro_batch sequences (pseudo-random inputs: the kernels'
+ * time does not depend on the values, but all-zero operands draw less power and clock
+ * higher), `reps` times each after a warm-up, once with the device to itself and once
+ * beside host-link traffic on two more streams (see hmy_measured_profile), and reports
+ * the average times, the blocks' divided by their number (several blocks, because one
+ * block run over and over finds its weights and activations in the memory-side cache,
+ * which the blocks of a pack in an iteration do not).  Allocates its own device memory (an
+ * arena for those three packs, two 128 MiB staging buffers) and frees it; needs no host
+ * state. */
 int hmy_measure_profile(const hmy_model_spec *spec, int32_t micro_batch, int32_t hip_device,
                         int32_t reps, hmy_measured_profile *out);
 /* Parameters whose optimizer state is resident on the device (0 unless the schedule says
