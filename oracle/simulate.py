@@ -28,7 +28,11 @@ v mod S of S slots.
   stash     a forward visit sends one checkpoint per microbatch for every backward-pack
             input among its layers (swap-out stream); a backward visit that restarts
             from a checkpoint reads one per microbatch (swap-in stream).  They travel
-            while their visit computes: requested when C(v) starts, nothing waits for them.
+            while their visit computes: requested when C(v) starts.  Nothing waits for the
+            ones going out; the ones coming in are the visit's input (Section 4.3.1: the
+            backward task recomputes from the stashed pack input), so C(v) cannot end
+            before they have all arrived -- behind whatever the swap-in stream was asked
+            for earlier, such as the optimizer state of the update before.
   update    after C(v) of a backward visit (jit-update).  On the device: the optimizer
             state K(v) comes in (k_B bytes per parameter, swap-in stream, requested when
             C(v) ends, behind whatever was requested earlier); state, weights and the
@@ -180,6 +184,7 @@ def iteration_ops(spec: om.Spec, P_F, P_B, t_fwd, t_bwd, M_F: int, M_B: int, act
             ops.append(Op(f"Sout{v}", "d2h", F(len(t.stash_out_layers) * M_F * act_bytes_F) * ns_per_byte_out,
                           after_start=[f"C{v}"]))
         ops.append(Op(f"C{v}", "comp", dur, after_end=[f"W{v}"],
+                      not_before_end=[f"Sin{v}"] if t.kind == "B" and t.stash_in_layer is not None else [],
                       stretch=("d2h", beside) if beside is not None else None))
         if t.kind == "F":
             left_slot[v] = f"C{v}"

@@ -588,6 +588,23 @@ def test_simulated_iteration_with_checkpoints_and_host_update_worked_by_hand():
     assert max(e for _, e in h.values()) == 1720
 
 
+def test_simulated_visit_waits_for_its_checkpoints_worked_by_hand():
+    """The schedule of the test above with short backward visits behind a slow incoming link (1/16 ns per byte:
+    W0 = 408, W1 = 36, block W 184, W4 = 40; K1 = 72, block K 368, K4 = 80; Sin = 2*64/16 = 8; outgoing as before).
+    Backward times 30/20/20/120: C2 = C3 = 40 alone, but the checkpoints they start from queue behind the
+    optimizer state of the update before.
+    W0 0-408; C0 408-828; W1 408-444; C1 828-1068; W2 828-1012; K1 1068-1140; Out1 1068-1140;
+    C2 starts 1068, Sin2 (behind K1) 1140-1148, so C2 ends 1148, not 1108; W3 1148-1332; K2 1332-1700; Out2 1148-1700;
+    C3 starts 1332, Sin3 (behind K2) 1700-1708, so C3 ends 1708; W4 1708-1748; K3 1748-2116; Out3 1708-2116;
+    C4 1748-1808; K4 2116-2196; Out4 2116-2196."""
+    spec = _toy(2)
+    t = _sim(spec, [(0, 3)], [(0, 1), (1, 2), (2, 3), (3, 4)], [10, 100, 100, 40], [30, 20, 20, 120], n_in=Fr(1, 16))
+    assert t["K1"] == (1068, 1140) and t["Sin2"] == (1140, 1148) and t["C2"] == (1068, 1148)
+    assert t["W3"] == (1148, 1332) and t["K2"] == (1332, 1700) and t["Out2"] == (1148, 1700)
+    assert t["Sin3"] == (1700, 1708) and t["C3"] == (1332, 1708) and t["W4"] == (1708, 1748)
+    assert t["C4"] == (1748, 1808) and t["Out4"] == (2116, 2196) and max(e for _, e in t.values()) == 2196
+
+
 def test_simulated_iteration_two_slots_against_three_worked_by_hand():
     """Seven visits (P_F = [0,5), six one-layer backward packs), device->host at 1/32 ns per byte:
     W0 = 3104*4/64 = 194, C0 = 2*410 = 820, Sout0 = 4*2*64/32 = 16; visit 1: W 9, C 240, K 18, Out 144*16/32 = 72;
