@@ -431,7 +431,9 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
   for (int v = 0; v < std::min(D, n); ++v) w_ready[v] = h2d_free = h2d_free + vs[v].w;
   for (int v = 0; v < n; ++v) {
     const uint64_t comp_start = std::max(comp_free, w_ready[v]);
-    if (vs[v].sin) h2d_free = std::max(h2d_free, comp_start) + vs[v].sin;
+    // the checkpoints a backward visit starts from are its input: it cannot end before they are all in
+    uint64_t sin_end = 0;
+    if (vs[v].sin) sin_end = h2d_free = std::max(h2d_free, comp_start) + vs[v].sin;
     if (vs[v].sout) d2h_free = std::max(d2h_free, comp_start) + vs[v].sout;
     if (v + D < n) {
       uint64_t s0 = std::max(h2d_free, comp_start);
@@ -446,7 +448,7 @@ uint64_t estimate_iteration_ns(const Model &m, const std::vector<hmy_layer_profi
       const uint64_t backlog = std::min(d2h_free - comp_start, comp);
       comp += uint64_t((__uint128_t)(vs[v].comp_beside - comp) * backlog / comp);
     }
-    const uint64_t comp_end = comp_start + comp;
+    const uint64_t comp_end = std::max(comp_start + comp, sin_end);
     comp_free = comp_end;
     if (!vs[v].bwd) {
       left[v] = comp_end;
