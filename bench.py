@@ -47,10 +47,10 @@ def attention_flops(cfg, packs) -> float:
 # WRITE_SIZE by 1.0: what the same counters read for a streaming kernel of known size (k_gelu_bwd_colsum, 64 MiB in /
 # 32 MiB plus 4 MiB of atomic additions out).
 GPT2M_FWD_GEMM_TRAFFIC = [   # (what, kernel, grid threads, dispatches, FETCH_SIZE KiB as counted, WRITE_SIZE KiB)
-    ("ffn1", "k_gemm_dma256<false, false, 64, 2>", 131072, 368, 24924.5, 49864.3),
-    ("qkv", "k_gemm_dma256<false, false, 64, 2>", 98304, 368, 20820.5, 24576.0),
-    ("logits, 512-row chunk", "k_gemm_dma256<false, false, 64, 2>", 201728, 64, 60317.0, 100528.2),
-    ("out and ffn2", "k_gemm_dma<false, false, 64, 4>", 65536, 672, 37372.1, 16384.0),
+    ("ffn1", "k_gemm_dma256<false, false, 64, 2>", 131072, 384, 24924.5, 49152.0),
+    ("qkv", "k_gemm_dma256<false, false, 64, 2>", 98304, 384, 20820.5, 24576.0),
+    ("logits, 512-row chunk", "k_gemm_dma256<false, false, 64, 2>", 201728, 64, 60316.8, 100528.2),
+    ("out and ffn2", "k_gemm_dma<false, false, 64, 4>", 65536, 696, 37220.8, 16384.0),
 ]
 
 
