@@ -49,8 +49,8 @@ def attention_flops(cfg, packs) -> float:
 GPT2M_FWD_GEMM_TRAFFIC = [   # (what, kernel, grid threads, dispatches, FETCH_SIZE KiB as counted, WRITE_SIZE KiB)
     ("ffn1", "k_gemm_dma256<false, false, 64, 2>", 131072, 384, 24924.5, 49152.0),
     ("qkv", "k_gemm_dma256<false, false, 64, 2>", 98304, 384, 20820.5, 24576.0),
-    ("logits, 512-row chunk", "k_gemm_dma256<false, false, 64, 2>", 201728, 64, 60316.8, 100528.2),
-    ("out and ffn2", "k_gemm_dma<false, false, 64, 4>", 65536, 696, 37220.8, 16384.0),
+    ("logits, 512-row chunk", "k_gemm_dma256<false, false, 64, 2>", 201728, 64, 60320.8, 100528.1),
+    ("out and ffn2", "k_gemm_dma<false, false, 64, 4>", 65536, 704, 37451.9, 16384.0),
 ]
 
 
@@ -228,6 +228,8 @@ def main() -> int:
     ap.add_argument("--fwd-packs", default="", help="forward pack ends instead of the planner's, e.g. 2,6,14,25 "
                     "(the last backward pack's first layer closes the list)")
     ap.add_argument("--bwd-packs", default="", help="backward pack ends instead of the planner's, e.g. 1,3,7,26")
+    ap.add_argument("--slots", type=int, default=0, help="weight slots instead of the planner's choice")
+    ap.add_argument("--distance", type=int, default=0, help="prefetch distance instead of the planner's choice")
     ap.add_argument("--counters", action="store_true",
                     help="for runs under `rocprofv3 --pmc`, where every dispatch is serialised: ONE iteration, no warm-up, "
                          "no variants, no CPU baseline, and a line on stderr after every visit")
@@ -280,6 +282,10 @@ def main() -> int:
             setattr(sched, n_field, len(ends))
             for i, e in enumerate(ends):
                 getattr(sched, end_field)[i] = e
+    if a.slots:
+        sched.weight_slots = a.slots
+    if a.distance:
+        sched.prefetch_distance = a.distance
     sched.order = B.HMY_ORDER_MICROBATCH_MAJOR if a.order == "microbatch-major" else B.HMY_ORDER_LAYER_PACK_MAJOR
     sched.gradients = B.HMY_GRADIENTS_ON_DEVICE if a.gradients == "device" else B.HMY_GRADIENTS_EXPORTED
     sched.resident_state = B.HMY_STATE_RESIDENT_IN_SPARE_BUDGET if a.resident_state else B.HMY_STATE_SWAPPED
