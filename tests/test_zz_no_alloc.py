@@ -61,7 +61,7 @@ def test_static_workspace_matches_the_callers_workspace_on_two_calls_in_a_row(pr
     from paper_2202_01306_amd import binding as B
     _case(B, prec, pc, dt, tol, 3000, 1024, 1)   # 256 workgroups: every row of the static workspace is used
     _case(B, prec, pc, dt, tol, 37, 256, 2)      # smaller: fewer, shorter rows over the first call's leftovers
-    _case(B, prec, pc, dt, tol, 130, 4096 if prec == "bf16" else 2048, 3)   # the widest rows the kernel keeps in registers
+    _case(B, prec, pc, dt, tol, 130, 4096 if prec == "bf16" else 2048, 3)   # wide rows: several waves share a row
 
 
 def test_static_workspace_rejects_rows_beyond_its_limit():
